@@ -1,0 +1,285 @@
+"""Float64 CPU oracle for layer-wise Hessian-aware quantization of one linear layer.
+
+THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only the tests, the smoke check
+and the benchmark's cpu_baseline leg may import it.  It shares no code with the
+HIP library and must never be used as a fallback for it.
+
+What it computes (paper sections given in brackets):
+
+  * the calibration Gram / Hessian  H = 2 * X^T X  over token rows of X
+    [Sec. 2.5 "Gram matrix H_l = X_l^T X_l"; Sec. 4.2 text after Eq. (layerwise);
+     the factor 2 is the constant that makes it the Hessian of ||X(W^-W)||^2,
+     cf. Sec. 2.4 "proportional, up to a constant factor, to the local Hessian"]
+  * Tikhonov damping  lambda = eta * mean(diag H)  and a Cholesky-based factor
+    of (H + lambda I)^-1  [Sec. 4.2.1, text after Eq. (qep)]
+  * optional activation ordering: columns sorted by decreasing diag(H)
+    [Sec. 4.2, "actorder"]
+  * the column-by-column sweep: quantize one column to the per-group
+    asymmetric min-max grid, propagate its residual to the columns not yet
+    quantized  [Sec. 4.2; grid: Eq. (1) scalar quantizer, Eq. (2) min-max
+    scale / zero-point, Eq. (4) per-group layout]
+  * the layer objective tr((W-W^) H (W-W^)^T)  [Eq. (layerwise), Eq. (activation-aware)]
+
+Storage convention: W is d_out x d_in (rows = output channels), i.e. the
+transpose of the paper's N x M matrix; "column j" is input channel j and a group
+is G consecutive input channels inside one output row.
+
+Everything is float64 and unblocked: one column at a time, rank-1 feedback, no
+fusion or reordering.  numpy's matmul / Cholesky / triangular solve are used as
+library steps.
+
+Pinned by tests/test_oracle_*.py (closed forms, invariants, brute force, a
+hand-worked grid example).  Functions without an external pin are marked
+"parity unpinned" in their docstring.
+"""
+from __future__ import annotations
+
+import numpy as np
+from scipy.linalg import solve_triangular
+
+
+# --------------------------------------------------------------------------
+# Gram / Hessian
+# --------------------------------------------------------------------------
+def hessian_accumulate(X, H=None):
+    """H + 2 * X^T X in float64 (Gram matrix of Sec. 2.5 / Sec. 4.2, times 2).
+
+    X: [n_tokens, d_in] (any float dtype; widened exactly to float64).
+    H: optional running sum [d_in, d_in]; a new array is returned either way.
+    """
+    X = np.asarray(X, dtype=np.float64)
+    G = 2.0 * (X.T @ X)
+    return G if H is None else np.asarray(H, dtype=np.float64) + G
+
+
+def hessian_tile(X, idx_i, idx_k):
+    """The sub-matrix H[idx_i][:, idx_k] of 2 * X^T X over all tokens of X."""
+    X = np.asarray(X)
+    Xi = np.asarray(X[:, idx_i], dtype=np.float64)
+    Xk = np.asarray(X[:, idx_k], dtype=np.float64)
+    return 2.0 * (Xi.T @ Xk)
+
+
+# --------------------------------------------------------------------------
+# Damping, ordering, inverse factor
+# --------------------------------------------------------------------------
+def damp_hessian(H, damp):
+    """H_d = H + lambda I with lambda = damp * mean(diag H)  [Sec. 4.2.1].
+
+    Reading for a dead input channel (H_jj == 0, on which the paper is silent):
+    its diagonal entry is set to 1 before lambda is computed, which keeps H_d
+    positive definite and gives that column no feedback.
+    Returns (H_d, lambda).
+    """
+    Hd = np.array(H, dtype=np.float64, copy=True)
+    d = np.diag(Hd).copy()
+    dead = d == 0.0
+    d[dead] = 1.0
+    np.fill_diagonal(Hd, d)
+    lam = float(damp) * float(d.sum() / d.shape[0])
+    Hd[np.diag_indices_from(Hd)] += lam
+    return Hd, lam
+
+
+def act_order_perm(H):
+    """Column order by decreasing diag(H); equal keys keep the lower index first
+    [Sec. 4.2 "actorder"; the tie rule is this build's choice]."""
+    d = np.diag(np.asarray(H, dtype=np.float64))
+    return np.argsort(-d, kind="stable").astype(np.int64)
+
+
+def first_bad_pivot(A):
+    """1-based index of the first non-positive pivot met by an unpivoted
+    Cholesky of A, or 0 if A is positive definite.  Plain column algorithm."""
+    A = np.array(A, dtype=np.float64, copy=True)
+    n = A.shape[0]
+    for k in range(n):
+        p = A[k, k]
+        if not (p > 0.0):
+            return k + 1
+        r = np.sqrt(p)
+        col = A[k + 1:, k] / r
+        A[k + 1:, k + 1:] -= np.outer(col, col)
+    return 0
+
+
+def inverse_factor(Hd):
+    """Upper-triangular U with positive diagonal and U^T U = Hd^-1.
+
+    Steps: lower Cholesky L of Hd; Hd^-1 by two triangular solves against I;
+    U = (lower Cholesky of Hd^-1)^T.  Returns (U, info); info = 0 on success,
+    else the 1-based index of the first non-positive pivot (U is then None).
+    """
+    Hd = np.asarray(Hd, dtype=np.float64)
+    n = Hd.shape[0]
+    try:
+        L = np.linalg.cholesky(Hd)
+    except np.linalg.LinAlgError:
+        return None, first_bad_pivot(Hd)
+    Y = solve_triangular(L, np.eye(n), lower=True)          # L Y = I
+    Hinv = solve_triangular(L.T, Y, lower=False)            # L^T Hinv = Y
+    Hinv = 0.5 * (Hinv + Hinv.T)
+    U = np.linalg.cholesky(Hinv).T
+    return np.ascontiguousarray(U), 0
+
+
+def hessian_factor(H, damp, act_order=False):
+    """damp -> (optional) permute -> inverse factor.
+
+    Returns dict(U, perm, info, Hd, lam); Hd is the damped matrix in ORIGINAL
+    column order, U belongs to the permuted matrix Hd[perm][:, perm]."""
+    Hd, lam = damp_hessian(H, damp)
+    n = Hd.shape[0]
+    perm = act_order_perm(H) if act_order else np.arange(n, dtype=np.int64)
+    Hp = Hd[np.ix_(perm, perm)] if act_order else Hd
+    U, info = inverse_factor(Hp)
+    return {"U": U, "perm": perm, "info": info, "Hd": Hd, "lam": lam}
+
+
+# --------------------------------------------------------------------------
+# Grid (Eq. 1, 2, 4)
+# --------------------------------------------------------------------------
+def minmax_params(wmin, wmax, bits):
+    """Asymmetric min-max scale and zero-point of Eq. (2) for the unsigned
+    range 0 .. 2^b - 1.  Rounding is half-to-even.  A degenerate group
+    (wmax == wmin, on which the paper is silent) takes s = 1.
+    Returns (s, z, tz) with tz = -wmin / s the value before rounding z."""
+    qmax = float(2 ** bits - 1)
+    wmin = np.asarray(wmin, dtype=np.float64)
+    wmax = np.asarray(wmax, dtype=np.float64)
+    s = (wmax - wmin) / qmax
+    s = np.where(s == 0.0, 1.0, s)
+    tz = -wmin / s
+    z = np.clip(np.rint(tz), 0.0, qmax)
+    return s, z, tz
+
+
+def quantize_scalar(w, s, z, bits):
+    """Eq. (1): q = clamp(rne(w / s) + z, 0, 2^b - 1), w^ = s (q - z).
+    Returns (q, w^, t) with t = w / s the value before rounding."""
+    qmax = float(2 ** bits - 1)
+    t = np.asarray(w, dtype=np.float64) / s
+    q = np.clip(np.rint(t) + z, 0.0, qmax)
+    return q, s * (q - z), t
+
+
+def rtn_quantize(W, bits, group_size):
+    """Round-to-nearest of W on the per-group min-max grid (Sec. 2.4, Eq.
+    (direct weight quant) with the grid of Eq. (2), layout of Eq. (4)).
+    Written independently of the sweep (whole-array, no column loop) so that it
+    can pin the sweep's diagonal-H special case.  Returns (Q, scales, zeros, W^)."""
+    W = np.asarray(W, dtype=np.float64)
+    d_out, d_in = W.shape
+    n_g = d_in // group_size
+    Wg = W.reshape(d_out, n_g, group_size)
+    lo = Wg.min(axis=2, keepdims=True)
+    hi = Wg.max(axis=2, keepdims=True)
+    s, z, _ = minmax_params(lo, hi, bits)
+    qmax = float(2 ** bits - 1)
+    Q = np.clip(np.rint(Wg / s) + z, 0.0, qmax)
+    What = s * (Q - z)
+    return (Q.reshape(d_out, d_in).astype(np.int64), s[:, :, 0], z[:, :, 0],
+            What.reshape(d_out, d_in))
+
+
+# --------------------------------------------------------------------------
+# Column sweep (Sec. 4.2: one column at a time, residual propagated)
+# --------------------------------------------------------------------------
+def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
+                   forced_codes=None, forced_zeros=None):
+    """Greedy sequential quantization of every row of W with feedback through U.
+
+    W: [d_out, d_in] original column order.  U: upper factor of the (permuted)
+    damped inverse Hessian.  perm: column order (None = natural).  rows: optional
+    subset of output rows (rows are independent given U).
+    forced_codes: optional int array [rows, d_in] in PERMUTED column order,
+      entries >= 0 override the rounded code at that step (replay of a tie).
+    forced_zeros: optional int array [rows, n_groups], entries >= 0 override z.
+
+    Per row, for j = 0 .. d_in-1 in permuted order:
+      at a group start: (s, z) from min/max of the CURRENT values of the group
+      q_j = clamp(rne(w_j / s) + z), w^_j = s (q_j - z)
+      e_j = (w_j - w^_j) / U_jj ;  w_k -= e_j U_jk for k > j
+    loss = sum e^2, which equals tr((W - W^) H_d (W - W^)^T) because
+    U H_d U^T = I.
+
+    Returns a dict.  Q and W_hat are in ORIGINAL column order; scales / zeros are
+    indexed by group number in permuted order; E, T (w/s before rounding) and
+    Tz (-wmin/s before rounding) are in permuted order.
+    """
+    W = np.asarray(W, dtype=np.float64)
+    if rows is not None:
+        W = W[np.asarray(rows)]
+    U = np.asarray(U, dtype=np.float64)
+    d_out, d_in = W.shape
+    G = int(group_size)
+    if d_in % G != 0:
+        raise ValueError("d_in must be a multiple of group_size")
+    n_g = d_in // G
+    qmax = float(2 ** bits - 1)
+    if perm is None:
+        perm = np.arange(d_in, dtype=np.int64)
+    perm = np.asarray(perm, dtype=np.int64)
+
+    w = W[:, perm].copy()                       # working (compensated) values
+    Q = np.zeros((d_out, d_in), dtype=np.int64)
+    What = np.zeros((d_out, d_in))
+    E = np.zeros((d_out, d_in))
+    T = np.zeros((d_out, d_in))
+    scales = np.zeros((d_out, n_g))
+    zeros = np.zeros((d_out, n_g))
+    Tz = np.zeros((d_out, n_g))
+    s = z = None
+    for j in range(d_in):
+        if j % G == 0:
+            g = j // G
+            blk = w[:, j:j + G]
+            s, z, tz = minmax_params(blk.min(axis=1), blk.max(axis=1), bits)
+            if forced_zeros is not None:
+                fz = np.asarray(forced_zeros)[:, g]
+                z = np.where(fz >= 0, fz.astype(np.float64), z)
+            scales[:, g] = s
+            zeros[:, g] = z
+            Tz[:, g] = tz
+        wj = w[:, j].copy()
+        q, wh, t = quantize_scalar(wj, s, z, bits)
+        if forced_codes is not None:
+            fc = np.asarray(forced_codes)[:, j]
+            q = np.where(fc >= 0, fc.astype(np.float64), q)
+            wh = s * (q - z)
+        e = (wj - wh) / U[j, j]
+        if j + 1 < d_in:
+            w[:, j + 1:] -= e[:, None] * U[j, j + 1:][None, :]
+        Q[:, j] = q.astype(np.int64)
+        What[:, j] = wh
+        E[:, j] = e
+        T[:, j] = t
+    out_Q = np.zeros_like(Q)
+    out_What = np.zeros_like(What)
+    out_Q[:, perm] = Q
+    out_What[:, perm] = What
+    return {
+        "Q": out_Q, "W_hat": out_What, "scales": scales, "zeros": zeros,
+        "loss": float((E * E).sum()), "loss_rows": (E * E).sum(axis=1),
+        "E": E, "T": T, "Tz": Tz, "perm": perm,
+    }
+
+
+def layer_loss(W, W_hat, Hd):
+    """tr((W - W^) Hd (W - W^)^T) evaluated directly (Eq. (layerwise) with the
+    Gram matrix written out; all three arguments in the same column order)."""
+    D = np.asarray(W, dtype=np.float64) - np.asarray(W_hat, dtype=np.float64)
+    return float(((D @ np.asarray(Hd, dtype=np.float64)) * D).sum())
+
+
+def dequantize(Q, scales, zeros, group_size, perm=None):
+    """W^_ij = s_g (q_ij - z_g)  (Eq. (4)); Q in original column order, the
+    group of original column c is position_of(c) // G in the sweep order."""
+    Q = np.asarray(Q, dtype=np.float64)
+    d_out, d_in = Q.shape
+    if perm is None:
+        perm = np.arange(d_in)
+    inv = np.empty(d_in, dtype=np.int64)
+    inv[np.asarray(perm)] = np.arange(d_in)
+    g = inv // int(group_size)
+    return np.asarray(scales, dtype=np.float64)[:, g] * (Q - np.asarray(zeros, dtype=np.float64)[:, g])
