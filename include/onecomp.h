@@ -1,0 +1,148 @@
+/*
+ * onecomp.h -- C ABI of the MI355X (gfx950) layer-wise Hessian-aware quantizer.
+ *
+ * One linear layer is quantized in three calls that follow the paper's problem
+ * statement for layer-wise PTQ (Sec. 4.2):
+ *
+ *   1. onecomp_hessian_accumulate  H += 2 X^T X          (Gram matrix, Sec. 2.5 / 4.2)
+ *   2. onecomp_hessian_factor      U^T U = (H + lambda I)^-1, lambda = damp * mean(diag H)
+ *                                                         (Sec. 4.2.1, text after Eq. (qep));
+ *                                  optional activation ordering (Sec. 4.2, "actorder")
+ *   3. onecomp_quantize_layer      column-by-column sweep: each column is rounded to the
+ *                                  per-group asymmetric min-max grid (Eq. (1), (2), (4))
+ *                                  and its residual is propagated through U to the
+ *                                  columns not yet quantized (Sec. 4.2)
+ *
+ * Storage convention: W is d_out x d_in row-major (rows = output channels); this
+ * is the transpose of the paper's N x M weight matrix.  "Column j" is input
+ * channel j; a group is `group_size` consecutive input channels of one row.
+ *
+ * Common rules
+ *   - Every data pointer is caller-owned DEVICE memory on the current HIP device.
+ *     The library never allocates, frees or keeps state between calls.
+ *   - All work is enqueued asynchronously on `hip_stream` (a hipStream_t passed as
+ *     void*; NULL = the null stream).  Device scalars (`loss`, `info`) are valid
+ *     once the stream has been synchronized.
+ *   - Host-checkable problems are reported through the return code and nothing is
+ *     launched; a numerical failure (matrix not positive definite) is reported
+ *     through the device scalar `info`.
+ *   - The binary contains gfx950 code only.
+ */
+#ifndef ONECOMP_H
+#define ONECOMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ONECOMP_OK = 0,
+    ONECOMP_ERR_INVALID_ARG = 1,   /* NULL pointer, non-positive size, bad stride, bad divisibility */
+    ONECOMP_ERR_UNSUPPORTED = 2,   /* dtype / bits / group / block outside the supported set */
+    ONECOMP_ERR_NOT_POSDEF = 3,    /* reserved for callers that translate `info` */
+    ONECOMP_ERR_WORKSPACE = 4,     /* workspace NULL or smaller than the matching *_workspace_bytes() */
+    ONECOMP_ERR_HIP = 5            /* a HIP runtime call failed (launch error etc.) */
+} onecomp_status;
+
+typedef enum {
+    ONECOMP_F32 = 0,
+    ONECOMP_BF16 = 1
+} onecomp_dtype;
+
+/*
+ * H += 2 * X^T X  over the n_tokens rows of X (Gram matrix of Sec. 2.5 / Sec. 4.2; the
+ * factor 2 makes it the Hessian of ||X (W^ - W)||^2, cf. Sec. 2.4).
+ *
+ *   X        [n_tokens x d_in], row-major, row stride `ldx` elements (ldx >= d_in), dtype x_dtype.
+ *            Read only.  Must be 16-byte aligned with ldx * sizeof(elem) a multiple of 16.
+ *   H        [d_in x d_in] fp32, row-major, full symmetric storage; read-modify-write.
+ *            The caller zero-fills it before the first chunk; calls are additive, so
+ *            any split of the token axis into chunks gives the same sum up to fp32
+ *            rounding order.  The result is bit-wise symmetric and, for a fixed
+ *            chunking, bit-wise reproducible (no floating-point atomics).
+ *   d_in     must be a multiple of 16.  n_tokens == 0 is a no-op returning ONECOMP_OK.
+ * Products of bf16 inputs are exact; accumulation is fp32.  fp32 inputs are multiplied in fp32.
+ */
+onecomp_status onecomp_hessian_accumulate(const void* X, onecomp_dtype x_dtype,
+                                          int64_t n_tokens, int64_t d_in, int64_t ldx,
+                                          float* H, void* hip_stream);
+
+/*
+ * Damping, optional activation ordering, and the Cholesky-based inverse factor
+ * (Sec. 4.2.1: lambda = damp * mean(diag H), Cholesky of H + lambda I; Sec. 4.2 "actorder").
+ *
+ *   H         [d_in x d_in] fp32 symmetric, read only (only diagonal and one triangle need be valid;
+ *             the upper triangle is read).
+ *   damp      eta >= 0.  A zero diagonal entry of H (dead input channel) is replaced by 1
+ *             before lambda is computed.
+ *   act_order 0: natural column order.  non-zero: perm = indices of diag(H) in decreasing
+ *             order (equal keys: lower index first) and the matrix factored is
+ *             (H + lambda I)[perm][:, perm].
+ *   perm_out  int32[d_in]; the order used (identity when act_order == 0).  May be NULL when
+ *             act_order == 0.
+ *   U         [d_in x d_in] fp32 row-major, out: upper triangular with positive diagonal and
+ *             U^T U = (H_d)^-1 for the (permuted) damped matrix H_d; the strict lower
+ *             triangle is written as zeros.  Computed in fp64, rounded once to fp32.
+ *   info      device int32, out: 0 on success, k > 0 if the matrix is not positive definite
+ *             (k is in 1..d_in and names the pivot, counted from the END of the
+ *             permuted order, at which the factorization first met a non-positive value);
+ *             U is then unspecified but every kernel still terminates normally.
+ *   workspace device scratch of at least onecomp_factor_workspace_bytes(d_in) bytes, 256-byte aligned.
+ *   d_in      must be a multiple of 16.
+ */
+onecomp_status onecomp_hessian_factor(const float* H, int64_t d_in, float damp, int act_order,
+                                      int32_t* perm_out, float* U, int32_t* info,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The column sweep (Sec. 4.2) on the per-group asymmetric grid (Eq. (1), (2), (4)).
+ * For every output row independently, for columns j in sweep order:
+ *   at the first column of a group: s = (max - min) / (2^bits - 1) over the CURRENT
+ *     (already compensated) values of the group (s = 1 if max == min),
+ *     z = clamp(rne(-min / s), 0, 2^bits - 1)
+ *   q_j = clamp(rne(w_j / s) + z, 0, 2^bits - 1),  w^_j = s (q_j - z)
+ *   e_j = (w_j - w^_j) / U_jj,   w_k -= e_j U_jk  for all later columns k
+ * rne = round half to even.  All arithmetic is fp32.
+ *
+ *   W          [d_out x d_in] row-major (dense, stride d_in), dtype w_dtype, ORIGINAL column order. Read only.
+ *   U          [d_in x d_in] fp32, as written by onecomp_hessian_factor. Read only.
+ *   perm       NULL (natural order) or the int32[d_in] order returned by the factor call;
+ *              sweep position p handles original column perm[p].
+ *   bits       2, 3, 4 or 8.
+ *   group_size G: multiple of 16, divides d_in; groups are contiguous in SWEEP order.
+ *   block_size B: lazy-batch width; 128 (the only supported value); d_in % B == 0 and either
+ *              G divides B or B divides G.
+ *   Q_codes    uint8 [d_out x d_in], one code per byte, ORIGINAL column order.  Out.
+ *   scales     fp32 [d_out x d_in/G], indexed by group number in sweep order.  Out.
+ *   zeros      fp32 [d_out x d_in/G], integer valued.  Out.
+ *   W_hat      fp32 [d_out x d_in] = scales * (Q_codes - zeros) bit for bit, ORIGINAL column order;
+ *              may be NULL.  Out.
+ *   loss       device fp32 scalar, out: sum of e^2 over the layer, which equals
+ *              tr((W - W^) H_d (W - W^)^T) for the damped (permuted) matrix behind U (Eq. (layerwise)).
+ *              Reduced in a fixed order (bit-wise reproducible).
+ *   workspace  device scratch, >= onecomp_quantize_workspace_bytes(d_out, d_in, block_size), 256-byte aligned.
+ */
+onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                      const float* U, const int32_t* perm,
+                                      int bits, int group_size, int block_size,
+                                      uint8_t* Q_codes, float* scales, float* zeros,
+                                      float* W_hat, float* loss,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Scratch sizes for the two calls above (0 if the arguments are invalid). */
+size_t onecomp_factor_workspace_bytes(int64_t d_in);
+size_t onecomp_quantize_workspace_bytes(int64_t d_out, int64_t d_in, int block_size);
+
+/* Static, NUL-terminated description of a status code. */
+const char* onecomp_status_string(onecomp_status status);
+
+/* Library version as major * 10000 + minor * 100 + patch. */
+int onecomp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ONECOMP_H */

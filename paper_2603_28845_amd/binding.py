@@ -1,0 +1,182 @@
+"""ctypes binding of libonecomp.so: argument marshalling only.
+
+Each function has the name of the C entry point it calls (include/onecomp.h) and
+takes torch tensors that live on the GPU; torch supplies device memory and the
+current HIP stream, every step of the computation runs in the library's kernels.
+There is no CPU fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch  # imported before the library so that both share one HIP runtime
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libonecomp.so")
+
+ONECOMP_OK = 0
+ONECOMP_F32 = 0
+ONECOMP_BF16 = 1
+
+EXPORTED_SYMBOLS = (
+    "onecomp_hessian_accumulate",
+    "onecomp_hessian_factor",
+    "onecomp_quantize_layer",
+    "onecomp_factor_workspace_bytes",
+    "onecomp_quantize_workspace_bytes",
+    "onecomp_status_string",
+    "onecomp_version",
+)
+
+_lib = None
+
+
+class OnecompError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} (status {code})")
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libonecomp.so (once) and declare its prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2603_28845_amd.build` "
+            "(or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.onecomp_hessian_accumulate.argtypes = [vp, i32, i64, i64, i64, vp, vp]
+    lib.onecomp_hessian_accumulate.restype = i32
+    lib.onecomp_hessian_factor.argtypes = [vp, i64, f32, i32, vp, vp, vp, vp, sz, vp]
+    lib.onecomp_hessian_factor.restype = i32
+    lib.onecomp_quantize_layer.argtypes = [vp, i32, i64, i64, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.onecomp_quantize_layer.restype = i32
+    lib.onecomp_factor_workspace_bytes.argtypes = [i64]
+    lib.onecomp_factor_workspace_bytes.restype = sz
+    lib.onecomp_quantize_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.onecomp_quantize_workspace_bytes.restype = sz
+    lib.onecomp_status_string.argtypes = [i32]
+    lib.onecomp_status_string.restype = ctypes.c_char_p
+    lib.onecomp_version.argtypes = []
+    lib.onecomp_version.restype = i32
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load_library().onecomp_status_string(int(code)).decode()
+
+
+def onecomp_version() -> int:
+    return int(load_library().onecomp_version())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return ONECOMP_F32
+    if t.dtype == torch.bfloat16:
+        return ONECOMP_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}: float32 or bfloat16 expected")
+
+
+def _dev(t: torch.Tensor, name: str, dtype=None, contiguous=True):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if contiguous and not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def onecomp_factor_workspace_bytes(d_in: int) -> int:
+    return int(load_library().onecomp_factor_workspace_bytes(int(d_in)))
+
+
+def onecomp_quantize_workspace_bytes(d_out: int, d_in: int, block_size: int = 128) -> int:
+    return int(load_library().onecomp_quantize_workspace_bytes(int(d_out), int(d_in), int(block_size)))
+
+
+def onecomp_hessian_accumulate(X: torch.Tensor, H: torch.Tensor) -> None:
+    """H += 2 X^T X.  X: [n_tokens, d_in] fp32/bf16 (rows may be strided), H: [d_in, d_in] fp32."""
+    lib = load_library()
+    if X.dim() != 2 or H.dim() != 2 or H.shape[0] != H.shape[1] or H.shape[0] != X.shape[1]:
+        raise ValueError("shapes: X [n_tokens, d_in], H [d_in, d_in]")
+    if X.shape[0] > 0 and X.stride(1) != 1:
+        raise ValueError("X rows must be dense")
+    _dev(X, "X", contiguous=False)
+    ldx = X.stride(0) if X.shape[0] > 1 else X.shape[1]
+    rc = lib.onecomp_hessian_accumulate(_ptr(X), _dtype_code(X), X.shape[0], X.shape[1], ldx,
+                                        _dev(H, "H", torch.float32), _stream())
+    if rc != ONECOMP_OK:
+        raise OnecompError(rc, "onecomp_hessian_accumulate")
+
+
+def onecomp_hessian_factor(H: torch.Tensor, damp: float, act_order: bool = False,
+                           U: Optional[torch.Tensor] = None, perm_out: Optional[torch.Tensor] = None,
+                           info: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None
+                           ) -> Tuple[torch.Tensor, Optional[torch.Tensor], torch.Tensor]:
+    """Returns (U, perm, info) as device tensors; perm is None when act_order is False and no perm_out was given."""
+    lib = load_library()
+    d = H.shape[0]
+    if U is None:
+        U = torch.empty((d, d), dtype=torch.float32, device=H.device)
+    if info is None:
+        info = torch.zeros(1, dtype=torch.int32, device=H.device)
+    if act_order and perm_out is None:
+        perm_out = torch.empty(d, dtype=torch.int32, device=H.device)
+    need = onecomp_factor_workspace_bytes(d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=H.device)
+    rc = lib.onecomp_hessian_factor(_dev(H, "H", torch.float32), d, float(damp), int(bool(act_order)),
+                                    _ptr(perm_out), _dev(U, "U", torch.float32), _dev(info, "info", torch.int32),
+                                    _dev(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    if rc != ONECOMP_OK:
+        raise OnecompError(rc, "onecomp_hessian_factor")
+    return U, perm_out, info
+
+
+def onecomp_quantize_layer(W: torch.Tensor, U: torch.Tensor, bits: int, group_size: int,
+                           perm: Optional[torch.Tensor] = None, block_size: int = 128, want_w_hat: bool = True,
+                           workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None) -> dict:
+    """Returns dict(Q_codes uint8, scales, zeros, W_hat (or None), loss) of device tensors."""
+    lib = load_library()
+    d_out, d_in = W.shape
+    dev = W.device
+    if out is None:
+        n_g = d_in // group_size if group_size > 0 and d_in % group_size == 0 else 1
+        out = {
+            "Q_codes": torch.empty((d_out, d_in), dtype=torch.uint8, device=dev),
+            "scales": torch.empty((d_out, n_g), dtype=torch.float32, device=dev),
+            "zeros": torch.empty((d_out, n_g), dtype=torch.float32, device=dev),
+            "W_hat": torch.empty((d_out, d_in), dtype=torch.float32, device=dev) if want_w_hat else None,
+            "loss": torch.zeros(1, dtype=torch.float32, device=dev),
+        }
+    need = onecomp_quantize_workspace_bytes(d_out, d_in, block_size)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    if perm is not None:
+        _dev(perm, "perm", torch.int32)
+    rc = lib.onecomp_quantize_layer(_dev(W, "W"), _dtype_code(W), d_out, d_in, _dev(U, "U", torch.float32),
+                                    _ptr(perm), int(bits), int(group_size), int(block_size),
+                                    _dev(out["Q_codes"], "Q_codes", torch.uint8),
+                                    _dev(out["scales"], "scales", torch.float32),
+                                    _dev(out["zeros"], "zeros", torch.float32), _ptr(out["W_hat"]),
+                                    _dev(out["loss"], "loss", torch.float32),
+                                    _dev(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    if rc != ONECOMP_OK:
+        raise OnecompError(rc, "onecomp_quantize_layer")
+    return out

@@ -1,0 +1,83 @@
+// extern "C" boundary: argument checks, then dispatch to the kernel launchers.  See include/onecomp.h.
+#include "common.hpp"
+
+using namespace onecomp;
+
+namespace {
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+}  // namespace
+
+#define ONECOMP_API __attribute__((visibility("default")))
+extern "C" {
+
+ONECOMP_API onecomp_status onecomp_hessian_accumulate(const void* X, onecomp_dtype x_dtype, int64_t n_tokens, int64_t d_in,
+                                          int64_t ldx, float* H, void* hip_stream) {
+    if (x_dtype != ONECOMP_F32 && x_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
+    if (!H || d_in <= 0 || n_tokens < 0 || ldx < d_in) return ONECOMP_ERR_INVALID_ARG;
+    if (d_in % 16 != 0 || d_in > (1 << 20)) return ONECOMP_ERR_INVALID_ARG;
+    if (n_tokens == 0) return ONECOMP_OK;
+    if (!X) return ONECOMP_ERR_INVALID_ARG;
+    const size_t esz = (x_dtype == ONECOMP_BF16) ? 2 : 4;
+    if (!aligned(X, 16) || (size_t(ldx) * esz) % 16 != 0 || !aligned(H, 16)) return ONECOMP_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (x_dtype == ONECOMP_BF16) return gram_accumulate_bf16(X, n_tokens, d_in, ldx, H, s);
+    return gram_accumulate_f32(X, n_tokens, d_in, ldx, H, s);
+}
+
+ONECOMP_API size_t onecomp_factor_workspace_bytes(int64_t d_in) {
+    if (d_in <= 0 || d_in % 16 != 0 || d_in > 46336) return 0;
+    return factor_workspace_bytes(d_in);
+}
+
+ONECOMP_API onecomp_status onecomp_hessian_factor(const float* H, int64_t d_in, float damp, int act_order, int32_t* perm_out,
+                                      float* U, int32_t* info, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream) {
+    if (!H || !U || !info || d_in <= 0) return ONECOMP_ERR_INVALID_ARG;
+    if (d_in % 16 != 0 || d_in > 46336) return ONECOMP_ERR_INVALID_ARG;
+    if (!(damp >= 0.0f)) return ONECOMP_ERR_INVALID_ARG;
+    if (act_order && !perm_out) return ONECOMP_ERR_INVALID_ARG;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < factor_workspace_bytes(d_in))
+        return ONECOMP_ERR_WORKSPACE;
+    return factor_run(H, d_in, damp, act_order, perm_out, U, info, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+ONECOMP_API size_t onecomp_quantize_workspace_bytes(int64_t d_out, int64_t d_in, int block_size) {
+    if (d_out <= 0 || d_in <= 0 || block_size != 128 || d_in % 128 != 0) return 0;
+    return sweep_workspace_bytes(d_out, d_in, block_size);
+}
+
+ONECOMP_API onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                      const float* U, const int32_t* perm, int bits, int group_size, int block_size,
+                                      uint8_t* Q_codes, float* scales, float* zeros, float* W_hat, float* loss,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
+    if (!W || !U || !Q_codes || !scales || !zeros || !loss) return ONECOMP_ERR_INVALID_ARG;
+    if (d_out <= 0 || d_in <= 0 || d_out > (1 << 24) || d_in > (1 << 20)) return ONECOMP_ERR_INVALID_ARG;
+    if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return ONECOMP_ERR_UNSUPPORTED;
+    if (block_size != 128) return ONECOMP_ERR_UNSUPPORTED;
+    if (group_size <= 0 || d_in % block_size != 0 || d_in % group_size != 0) return ONECOMP_ERR_INVALID_ARG;
+    if (group_size % 16 != 0) return ONECOMP_ERR_UNSUPPORTED;
+    if (block_size % group_size != 0 && group_size % block_size != 0) return ONECOMP_ERR_INVALID_ARG;
+    if (!aligned(W, 16) || !aligned(U, 16) || !aligned(Q_codes, 4) || (W_hat && !aligned(W_hat, 16)))
+        return ONECOMP_ERR_INVALID_ARG;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < sweep_workspace_bytes(d_out, d_in, block_size))
+        return ONECOMP_ERR_WORKSPACE;
+    return sweep_run(W, w_dtype, d_out, d_in, U, perm, bits, group_size, block_size, Q_codes, scales, zeros, W_hat,
+                     loss, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+ONECOMP_API const char* onecomp_status_string(onecomp_status status) {
+    switch (status) {
+        case ONECOMP_OK: return "ok";
+        case ONECOMP_ERR_INVALID_ARG: return "invalid argument";
+        case ONECOMP_ERR_UNSUPPORTED: return "unsupported dtype, bit width, group size or block size";
+        case ONECOMP_ERR_NOT_POSDEF: return "matrix is not positive definite";
+        case ONECOMP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case ONECOMP_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+ONECOMP_API int onecomp_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,433 @@
+// Damping, activation ordering and the Cholesky-based inverse factor (Sec. 4.2.1 of the paper:
+// lambda = eta * mean(diag H), Cholesky of H + lambda I; Sec. 4.2: optional "actorder").
+//
+// Wanted: upper-triangular U, positive diagonal, U^T U = Hd^-1 for the damped (permuted) matrix Hd.
+// Route: let R be Hd with both index orders reversed, R = L L^T its lower Cholesky factor and
+// V = L^-1.  Reversing a lower-triangular matrix gives an upper-triangular one, so
+// Hd = M M^T with M = rev(L) upper, and U = M^-1 = rev(V):  U[i][k] = V[n-1-i][n-1-k].
+// One Cholesky plus one triangular inverse (2 n^3 / 3 flops), all in fp64; U is rounded once to fp32.
+//
+// gfx950 design
+//   * blocked right-looking Cholesky, block 128: diagonal block factored (and inverted) inside one
+//     workgroup's LDS; panel solve and trailing update are fp64 MFMA GEMMs (v_mfma_f64_16x16x4_f64),
+//     128 x 128 tile per workgroup, LDS double-buffered.
+//   * triangular inverse by recursive doubling over aligned block pairs: for block size s = 128 * 2^l,
+//     V[C,A] = -V[C,C] (L[C,A] V[A,A]); every level is two batched GEMMs, so the whole inverse is
+//     ~2 log2(n/128) large launches instead of n/128 skinny ones.
+//   * ordering by rank counting (stable, deterministic), no floating-point atomics anywhere.
+#include "common.hpp"
+
+namespace onecomp {
+namespace {
+
+constexpr int NB = 128;  // block size of the factorization (= GEMM tile side)
+
+// ------------------------------------------------------------------------------------------
+// small preparation kernels
+// ------------------------------------------------------------------------------------------
+// diag -> keys (original diagonal), dfix (dead channels -> 1), lambda = damp * mean(dfix).  One workgroup.
+__global__ __launch_bounds__(1024) void prep_diag_kernel(const float* __restrict__ H, int n, double damp,
+                                                        float* __restrict__ keys, double* __restrict__ dfix,
+                                                        double* __restrict__ lam, int32_t* __restrict__ info) {
+    __shared__ double part[1024];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += 1024) {
+        float h = H[int64_t(i) * n + i];
+        keys[i] = h;
+        double d = (h == 0.0f) ? 1.0 : double(h);
+        dfix[i] = d;
+        s += d;  // fixed order per thread
+    }
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 512; w > 0; w >>= 1) {
+        if (threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        *lam = damp * (part[0] / double(n));
+        *info = 0;
+    }
+}
+
+// perm: act_order ? stable descending order of keys : identity.  rank by counting.
+__global__ __launch_bounds__(256) void order_kernel(const float* __restrict__ keys, int n, int act_order,
+                                                   int32_t* __restrict__ perm, int32_t* __restrict__ perm_out) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    int pos = i;
+    if (act_order) {
+        const float ki = keys[i];
+        int rank = 0;
+        for (int k = 0; k < n; ++k) {
+            const float kk = keys[k];
+            rank += (kk > ki) || (kk == ki && k < i);
+        }
+        pos = rank;
+    }
+    perm[pos] = i;
+    if (perm_out) perm_out[pos] = i;
+}
+
+// A[r][c] = Hd[p[n-1-r]][p[n-1-c]] in fp64 (reversed, permuted, damped); upper triangle of H is read.
+__global__ __launch_bounds__(256) void build_kernel(const float* __restrict__ H, int n,
+                                                   const int32_t* __restrict__ perm,
+                                                   const double* __restrict__ dfix, const double* __restrict__ lam,
+                                                   double* __restrict__ A) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    const int r = blockIdx.y;
+    if (c >= n) return;
+    const int i = perm[n - 1 - r], k = perm[n - 1 - c];
+    double v;
+    if (i == k) v = dfix[i] + *lam;
+    else v = double(H[int64_t(min(i, k)) * n + max(i, k)]);
+    A[int64_t(r) * n + c] = v;
+}
+
+// U[i][k] = float(V[n-1-i][n-1-k]) for k >= i, 0 below the diagonal.
+__global__ __launch_bounds__(256) void output_kernel(const double* __restrict__ V, int n, float* __restrict__ U) {
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.y;
+    if (k >= n) return;
+    float u = 0.f;
+    if (k >= i) u = float(V[int64_t(n - 1 - i) * n + (n - 1 - k)]);
+    U[int64_t(i) * n + k] = u;
+}
+
+// ------------------------------------------------------------------------------------------
+// diagonal block: Cholesky in LDS, then in-place triangular inverse.  One workgroup.
+// A block (bs x bs, bs <= 128) at A + off*(n+1); L written back to A (lower part), L^-1 to V (full block,
+// zeros above the diagonal).  A non-positive pivot sets *info (first one wins) and is replaced by 1.
+// ------------------------------------------------------------------------------------------
+constexpr int DP = NB + 1;  // LDS pitch in doubles
+
+__global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A, double* __restrict__ V, int n,
+                                                        int off, int bs, int32_t* __restrict__ info) {
+    extern __shared__ double S[];  // NB x DP
+    const int tid = threadIdx.x;
+    for (int e = tid; e < NB * NB; e += 256) {
+        int r = e / NB, c = e % NB;
+        double v = (r == c) ? 1.0 : 0.0;
+        if (r < bs && c < bs) v = A[int64_t(off + r) * n + off + c];
+        S[r * DP + c] = v;
+    }
+    __syncthreads();
+    for (int j = 0; j < bs; ++j) {
+        double p = S[j * DP + j];
+        const bool bad = !(p > 0.0);
+        if (bad) p = 1.0;
+        const double rinv = 1.0 / sqrt(p);
+        __syncthreads();  // everyone has read the pivot
+        if (tid == 0) {
+            S[j * DP + j] = sqrt(p);
+            if (bad && *info == 0) *info = off + j + 1;
+        }
+        for (int i = j + 1 + tid; i < bs; i += 256) S[i * DP + j] *= rinv;
+        __syncthreads();
+        // trailing update of the lower triangle: S[i][c] -= S[i][j] S[c][j], j < c <= i < bs
+        const int rem = bs - 1 - j;
+        for (int e = tid; e < rem * rem; e += 256) {
+            int i = j + 1 + e / rem, c = j + 1 + e % rem;
+            if (c <= i) S[i * DP + c] -= S[i * DP + j] * S[c * DP + j];
+        }
+        __syncthreads();
+    }
+    for (int e = tid; e < bs * bs; e += 256) {
+        int r = e / bs, c = e % bs;
+        if (c <= r) A[int64_t(off + r) * n + off + c] = S[r * DP + c];
+    }
+    __syncthreads();
+    // in-place inverse of the lower-triangular S, last column first:
+    //   x_jj = 1 / l_jj ;  x[j+1:, j] = -(X[j+1:, j+1:] l[j+1:, j]) x_jj
+    for (int j = bs - 1; j >= 0; --j) {
+        const double djj = 1.0 / S[j * DP + j];
+        double y = 0.0;
+        const int i = j + 1 + tid;
+        if (i < bs) {
+            for (int m = j + 1; m <= i; ++m) y += S[i * DP + m] * S[m * DP + j];
+        }
+        __syncthreads();
+        if (i < bs) S[i * DP + j] = -y * djj;
+        if (tid == 0) S[j * DP + j] = djj;
+        __syncthreads();
+    }
+    for (int e = tid; e < bs * bs; e += 256) {
+        int r = e / bs, c = e % bs;
+        V[int64_t(off + r) * n + off + c] = (c <= r) ? S[r * DP + c] : 0.0;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// fp64 MFMA GEMM:  C = alpha * A * op(B) + beta * C   (batched, optional triangular structure)
+// ------------------------------------------------------------------------------------------
+constexpr int GT = 128;  // tile side
+constexpr int GK = 16;   // K per LDS stage
+constexpr int GPA = GK + 1;
+constexpr int GPB = GT + 4;
+constexpr int GSB = GT * GPA;  // >= GK * GPB
+
+enum : int { G_BTRANS = 1, G_ALOWER = 2, G_BLOWER = 4, G_CLOWER = 8 };
+
+struct GemmArgs {
+    const double* A; int64_t lda, sa;
+    const double* B; int64_t ldb, sb;
+    double* C; int64_t ldc, sc;
+    int m, n, k;   // sizes of every batch entry but the last
+    int m_last;    // rows of the last batch entry (<= m)
+    int k_last;    // inner size of the last batch entry (<= k)
+    int batch;
+    double alpha, beta;
+    int flags;
+};
+
+__global__ __launch_bounds__(256) void dgemm_kernel(GemmArgs g) {
+    __shared__ double sA[2][GT * GPA];
+    __shared__ double sB[2][GSB];
+    const int z = blockIdx.z;
+    const bool last = (z == g.batch - 1);
+    const int m = last ? g.m_last : g.m;
+    const int kdim = last ? g.k_last : g.k;
+    const int tm = blockIdx.y, tn = blockIdx.x;
+    if (tm * GT >= m) return;
+    if ((g.flags & G_CLOWER) && tn > tm) return;
+    const double* __restrict__ A = g.A + z * g.sa;
+    const double* __restrict__ B = g.B + z * g.sb;
+    double* __restrict__ C = g.C + z * g.sc;
+    const bool bt = g.flags & G_BTRANS;
+    int k_lo = 0, k_hi = kdim;
+    if (g.flags & G_BLOWER) k_lo = tn * GT;
+    if (g.flags & G_ALOWER) k_hi = min(kdim, (tm + 1) * GT);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int m0 = tm * GT, n0 = tn * GT;
+
+    // loaders: A-form tile (rows x GK, k contiguous): row = tid/2, 8 doubles at k = (tid%2)*8
+    //          NN B tile (GK x cols): krow = tid/16, 8 doubles at col (tid%16)*8
+    const int a_row = tid >> 1, a_k = (tid & 1) * 8;
+    const int b_kr = tid >> 4, b_c = (tid & 15) * 8;
+    double ra[8], rb[8];
+    auto gload = [&](int k0) {
+        {
+            const int r = m0 + a_row, kk = k0 + a_k;
+            const bool ok = (r < m) && (kk < k_hi);
+            const double2* p = reinterpret_cast<const double2*>(A + int64_t(r) * g.lda + kk);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                double2 v = ok ? p[e] : make_double2(0.0, 0.0);
+                ra[2 * e] = v.x; ra[2 * e + 1] = v.y;
+            }
+        }
+        if (bt) {
+            const int r = n0 + a_row, kk = k0 + a_k;
+            const bool ok = (r < g.n) && (kk < k_hi);
+            const double2* p = reinterpret_cast<const double2*>(B + int64_t(r) * g.ldb + kk);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                double2 v = ok ? p[e] : make_double2(0.0, 0.0);
+                rb[2 * e] = v.x; rb[2 * e + 1] = v.y;
+            }
+        } else {
+            const int kk = k0 + b_kr, c = n0 + b_c;
+            const bool ok = (kk < k_hi) && (c < g.n);
+            const double2* p = reinterpret_cast<const double2*>(B + int64_t(kk) * g.ldb + c);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                double2 v = ok ? p[e] : make_double2(0.0, 0.0);
+                rb[2 * e] = v.x; rb[2 * e + 1] = v.y;
+            }
+        }
+    };
+    auto lstore = [&](int st) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sA[st][a_row * GPA + a_k + e] = ra[e];
+        if (bt) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sB[st][a_row * GPA + a_k + e] = rb[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sB[st][b_kr * GPB + b_c + e] = rb[e];
+        }
+    };
+
+    double4v acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0;
+
+    const int l16 = lane & 15, lk = lane >> 4;
+    if (k_lo < k_hi) {
+        gload(k_lo);
+        lstore(0);
+    }
+    __syncthreads();
+    int st = 0;
+    for (int k0 = k_lo; k0 < k_hi; k0 += GK) {
+        const bool more = (k0 + GK < k_hi);
+        if (more) gload(k0 + GK);
+#pragma unroll
+        for (int k4 = 0; k4 < GK; k4 += 4) {
+            double a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = sA[st][(wr * 64 + i * 16 + l16) * GPA + k4 + lk];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                b[j] = bt ? sB[st][(wc * 64 + j * 16 + l16) * GPA + k4 + lk]
+                          : sB[st][(k4 + lk) * GPB + wc * 64 + j * 16 + l16];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) lstore(st ^ 1);
+        __syncthreads();
+        st ^= 1;
+    }
+
+    // accumulator register r of lane l: row 4 r + l / 16, column l % 16 of its 16 x 16 tile
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
+                const int col = n0 + wc * 64 + j * 16 + l16;
+                if (row < m && col < g.n) {
+                    double* p = C + int64_t(row) * g.ldc + col;
+                    double v = g.alpha * acc[i][j][r];
+                    if (g.beta != 0.0) v += g.beta * (*p);
+                    *p = v;
+                }
+            }
+}
+
+onecomp_status dgemm(const GemmArgs& g, hipStream_t stream) {
+    if (g.m <= 0 || g.n <= 0 || g.batch <= 0) return ONECOMP_OK;
+    dim3 grid(unsigned(ceil_div(g.n, GT)), unsigned(ceil_div(g.m, GT)), unsigned(g.batch));
+    hipLaunchKernelGGL(dgemm_kernel, grid, dim3(256), 0, stream, g);
+    ONECOMP_CHECK_LAUNCH();
+    return ONECOMP_OK;
+}
+
+struct Workspace {
+    double* A;      // n x n: reversed damped matrix, then L in its lower triangle
+    double* V;      // n x n: L^-1 (lower)
+    double* T;      // n x n: temporaries of the inverse
+    double* dfix;   // n
+    double* lam;    // 1
+    float* keys;    // n
+    int32_t* perm;  // n
+};
+
+Workspace carve(void* ws, int64_t n) {
+    char* p = static_cast<char*>(ws);
+    const size_t mat = align_up(size_t(n) * n * sizeof(double), 256);
+    Workspace w;
+    w.A = reinterpret_cast<double*>(p); p += mat;
+    w.V = reinterpret_cast<double*>(p); p += mat;
+    w.T = reinterpret_cast<double*>(p); p += mat;
+    w.dfix = reinterpret_cast<double*>(p); p += align_up(size_t(n) * sizeof(double), 256);
+    w.lam = reinterpret_cast<double*>(p); p += 256;
+    w.keys = reinterpret_cast<float*>(p); p += align_up(size_t(n) * sizeof(float), 256);
+    w.perm = reinterpret_cast<int32_t*>(p);
+    return w;
+}
+
+}  // namespace
+
+size_t factor_workspace_bytes(int64_t n) {
+    return 3 * align_up(size_t(n) * n * sizeof(double), 256) + align_up(size_t(n) * sizeof(double), 256) + 256 +
+           2 * align_up(size_t(n) * sizeof(float), 256);
+}
+
+onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_order, int32_t* perm_out, float* U,
+                          int32_t* info, void* workspace, hipStream_t stream) {
+    const int n = int(d_in);
+    Workspace w = carve(workspace, n);
+    onecomp_status st;
+
+    hipLaunchKernelGGL(prep_diag_kernel, dim3(1), dim3(1024), 0, stream, H, n, double(damp), w.keys, w.dfix, w.lam,
+                       info);
+    ONECOMP_CHECK_LAUNCH();
+    hipLaunchKernelGGL(order_kernel, dim3(unsigned(ceil_div(n, 256))), dim3(256), 0, stream, w.keys, n, act_order,
+                       w.perm, perm_out);
+    ONECOMP_CHECK_LAUNCH();
+    hipLaunchKernelGGL(build_kernel, dim3(unsigned(ceil_div(n, 256)), unsigned(n)), dim3(256), 0, stream, H, n,
+                       w.perm, w.dfix, w.lam, w.A);
+    ONECOMP_CHECK_LAUNCH();
+
+    static bool attr_set = false;
+    const size_t potrf_lds = size_t(NB) * DP * sizeof(double);
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&potrf_diag_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(potrf_lds)) != hipSuccess)
+            return ONECOMP_ERR_HIP;
+        attr_set = true;
+    }
+
+    // ---- blocked right-looking Cholesky of A (lower) ----
+    const int nblk = int(ceil_div(n, NB));
+    for (int kb = 0; kb < nblk; ++kb) {
+        const int off = kb * NB;
+        const int bs = min(NB, n - off);
+        hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), potrf_lds, stream, w.A, w.V, n, off, bs, info);
+        ONECOMP_CHECK_LAUNCH();
+        const int rest = n - off - bs;
+        if (rest <= 0) break;
+        // panel: A[off+bs:, off:off+bs] <- A[off+bs:, off:off+bs] * Linv_kk^T   (in place, one column tile)
+        GemmArgs p{};
+        p.A = w.A + int64_t(off + bs) * n + off; p.lda = n; p.sa = 0;
+        p.B = w.V + int64_t(off) * n + off; p.ldb = n; p.sb = 0;
+        p.C = w.A + int64_t(off + bs) * n + off; p.ldc = n; p.sc = 0;
+        p.m = rest; p.m_last = rest; p.n = bs; p.k = bs; p.k_last = bs; p.batch = 1;
+        p.alpha = 1.0; p.beta = 0.0; p.flags = G_BTRANS;
+        if ((st = dgemm(p, stream)) != ONECOMP_OK) return st;
+        // trailing: A[i][j] -= P[i] P[j]^T on the lower tiles
+        GemmArgs s{};
+        s.A = p.C; s.lda = n; s.sa = 0;
+        s.B = p.C; s.ldb = n; s.sb = 0;
+        s.C = w.A + int64_t(off + bs) * n + (off + bs); s.ldc = n; s.sc = 0;
+        s.m = rest; s.m_last = rest; s.n = rest; s.k = bs; s.k_last = bs; s.batch = 1;
+        s.alpha = -1.0; s.beta = 1.0; s.flags = G_BTRANS | G_CLOWER;
+        if ((st = dgemm(s, stream)) != ONECOMP_OK) return st;
+    }
+
+    // ---- V = L^-1 by recursive doubling over aligned block pairs ----
+    for (int64_t s = NB; s < n; s *= 2) {
+        const int64_t pairs = ceil_div(n, 2 * s);
+        // last pair may have a short or empty C range
+        int64_t m_last = n - ((pairs - 1) * 2 * s + s);
+        int64_t batch = pairs;
+        if (m_last <= 0) { batch = pairs - 1; m_last = s; }
+        if (batch <= 0) continue;
+        if (m_last > s) m_last = s;
+        const int64_t stride = 2 * s * (int64_t(n) + 1);
+        // T[C,A] = L[C,A] * V[A,A]        (V[A,A] lower triangular)
+        GemmArgs a{};
+        a.A = w.A + s * n; a.lda = n; a.sa = stride;
+        a.B = w.V; a.ldb = n; a.sb = stride;
+        a.C = w.T + s * n; a.ldc = n; a.sc = stride;
+        a.m = int(s); a.m_last = int(m_last); a.n = int(s); a.k = int(s); a.k_last = int(s); a.batch = int(batch);
+        a.alpha = 1.0; a.beta = 0.0; a.flags = G_BLOWER;
+        if ((st = dgemm(a, stream)) != ONECOMP_OK) return st;
+        // V[C,A] = -V[C,C] * T[C,A]       (V[C,C] lower triangular)
+        GemmArgs b{};
+        b.A = w.V + s * (int64_t(n) + 1); b.lda = n; b.sa = stride;
+        b.B = w.T + s * n; b.ldb = n; b.sb = stride;
+        b.C = w.V + s * n; b.ldc = n; b.sc = stride;
+        b.m = int(s); b.m_last = int(m_last); b.n = int(s); b.k = int(s); b.k_last = int(m_last); b.batch = int(batch);
+        b.alpha = -1.0; b.beta = 0.0; b.flags = G_ALOWER;
+        if ((st = dgemm(b, stream)) != ONECOMP_OK) return st;
+    }
+
+    hipLaunchKernelGGL(output_kernel, dim3(unsigned(ceil_div(n, 256)), unsigned(n)), dim3(256), 0, stream, w.V, n, U);
+    ONECOMP_CHECK_LAUNCH();
+    return ONECOMP_OK;
+}
+
+}  // namespace onecomp

@@ -1,0 +1,348 @@
+// Gram / Hessian accumulation  H += 2 X^T X  (Sec. 2.5 and Sec. 4.2 of the paper: H_l = X_l^T X_l,
+// rows of X are token activations; the factor 2 makes it the Hessian of the layer objective).
+//
+// gfx950 design
+//   * Only tiles on or above the diagonal are computed; each result is stored to H[i][k] and to
+//     its mirror H[k][i], so H stays bit-wise symmetric and one workgroup owns each tile
+//     (no floating-point atomics, reproducible).
+//   * bf16 path: square tile of 64*WT channels per workgroup, 4 waves in 2x2, each wave
+//     WT x WT tiles of v_mfma_f32_32x32x16_bf16.  X is token-major, the MFMA operands need 8
+//     consecutive TOKENS per lane: the token-major LDS tile is read with ds_read_b64_tr_b16
+//     (LDS transpose read), so no register shuffles are needed.  Double-buffered LDS, global
+//     loads of the next stage are in flight while the current one is multiplied.
+//   * The workgroup -> tile map is XCD-aware: hardware deals consecutive workgroups round-robin to
+//     the 8 XCDs, so workgroup b is given the tile with rank (b % 8) * chunk + b / 8 in an
+//     order that walks bands of 4 tile rows column by column.  The 32 workgroups that share an
+//     XCD's L2 at any time then cover a compact 4 x 8 patch of tiles (12 X panels, not 64).
+//   * fp32 path (small layers): 128-wide tiles on v_mfma_f32_32x32x2_f32, products in fp32.
+#include "common.hpp"
+
+namespace onecomp {
+namespace {
+
+constexpr int GRAM_THREADS = 256;
+constexpr int BAND = 4;  // tile rows per band in the workgroup -> tile order
+
+// rank v in the banded order -> (ti, tk), ti <= tk < n_t
+__device__ inline void tile_from_rank(int v, int n_t, int& ti, int& tk) {
+    int a = 0;
+    while (true) {
+        int rows = min(BAND, n_t - a * BAND);
+        int cols = n_t - a * BAND;
+        int cnt = rows * cols - rows * (rows - 1) / 2;
+        if (v < cnt) {
+            int tri = rows * (rows + 1) / 2;
+            if (v < tri) {
+                int c = 0;
+                while ((c + 1) * (c + 2) / 2 <= v) ++c;
+                tk = a * BAND + c;
+                ti = a * BAND + (v - c * (c + 1) / 2);
+            } else {
+                int w = v - tri;
+                tk = a * BAND + rows + w / rows;
+                ti = a * BAND + w % rows;
+            }
+            return;
+        }
+        v -= cnt;
+        ++a;
+    }
+}
+
+// -------------------------------------------------------------------------------------------
+// bf16 kernel
+// -------------------------------------------------------------------------------------------
+template <int WT>
+struct GramBf16Cfg {
+    static constexpr int TS = 64 * WT;          // tile side in channels
+    static constexpr int KT = 32;               // tokens per LDS stage
+    static constexpr int PITCH = TS + 16;       // bf16 elements; +32 B staggers 4 token rows over the banks
+    static constexpr int PANEL = KT * PITCH;    // elements per panel
+    static constexpr int CHUNKS = KT * TS / 8;  // 16-byte chunks per panel
+    static constexpr int NLOAD = CHUNKS / GRAM_THREADS;
+    static constexpr size_t LDS_BYTES = size_t(4) * PANEL * 2;  // 2 stages x (A, B)
+};
+
+template <int WT>
+__global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_kernel(const uint16_t* __restrict__ X,
+                                                                int64_t n_tokens, int d_in, int64_t ldx,
+                                                                float* __restrict__ H, int n_t,
+                                                                int n_tiles, int chunk) {
+    using C = GramBf16Cfg<WT>;
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+
+    const int v = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+    if (v >= n_tiles) return;
+    int ti, tk;
+    tile_from_rank(v, n_t, ti, tk);
+    const bool diag = (ti == tk);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int i0 = ti * C::TS, k0 = tk * C::TS;
+
+    // global -> LDS assignment
+    int ld_row[C::NLOAD], ld_col[C::NLOAD];
+#pragma unroll
+    for (int n = 0; n < C::NLOAD; ++n) {
+        int id = tid + GRAM_THREADS * n;
+        ld_row[n] = id / (C::TS / 8);
+        ld_col[n] = (id % (C::TS / 8)) * 8;
+    }
+    uint4v ra[C::NLOAD], rb[C::NLOAD];
+    auto gload = [&](int64_t t0) {
+#pragma unroll
+        for (int n = 0; n < C::NLOAD; ++n) {
+            int64_t t = t0 + ld_row[n];
+            int ca = i0 + ld_col[n], cb = k0 + ld_col[n];
+            const uint4v z = {0u, 0u, 0u, 0u};
+            ra[n] = (t < n_tokens && ca < d_in) ? *reinterpret_cast<const uint4v*>(X + t * ldx + ca) : z;
+            if (!diag) rb[n] = (t < n_tokens && cb < d_in) ? *reinterpret_cast<const uint4v*>(X + t * ldx + cb) : z;
+        }
+    };
+    auto lstore = [&](int stage) {
+        uint16_t* pa = lds + stage * 2 * C::PANEL;
+        uint16_t* pb = pa + C::PANEL;
+#pragma unroll
+        for (int n = 0; n < C::NLOAD; ++n) {
+            *reinterpret_cast<uint4v*>(pa + ld_row[n] * C::PITCH + ld_col[n]) = ra[n];
+            if (!diag) *reinterpret_cast<uint4v*>(pb + ld_row[n] * C::PITCH + ld_col[n]) = rb[n];
+        }
+    };
+
+    // LDS transpose-read addressing: inside each 16-lane group, lane 4k+c points at 4 channels of token k;
+    // the read returns, to lane i of the group, that group's channel i for tokens 0..3.
+    const int i16 = lane & 15, g16 = (lane >> 4) & 1, kb8 = lane >> 5;
+    const int frag_off = (kb8 * 8 + (i16 >> 2)) * C::PITCH + g16 * 16 + (i16 & 3) * 4;
+
+    float16v acc[WT][WT];
+#pragma unroll
+    for (int m = 0; m < WT; ++m)
+#pragma unroll
+        for (int n = 0; n < WT; ++n)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
+
+    const int64_t n_stage = (n_tokens + C::KT - 1) / C::KT;
+    gload(0);
+    lstore(0);
+    __syncthreads();
+    for (int64_t s = 0; s < n_stage; ++s) {
+        const int cur = int(s & 1);
+        if (s + 1 < n_stage) gload((s + 1) * C::KT);
+        const uint16_t* pa = lds + cur * 2 * C::PANEL;
+        const uint16_t* pb = diag ? pa : pa + C::PANEL;
+        const uint16_t* fa = pa + frag_off + wr * (32 * WT);
+        const uint16_t* fb = pb + frag_off + wc * (32 * WT);
+#pragma unroll
+        for (int kb = 0; kb < C::KT / 16; ++kb) {
+            bf16x8 a[WT], b[WT];
+#pragma unroll
+            for (int m = 0; m < WT; ++m) {
+                const uint16_t* p = fa + kb * 16 * C::PITCH + m * 32;
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)p);
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(p + 4 * C::PITCH));
+                short8v w = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                a[m] = __builtin_bit_cast(bf16x8, w);
+            }
+#pragma unroll
+            for (int n = 0; n < WT; ++n) {
+                const uint16_t* p = fb + kb * 16 * C::PITCH + n * 32;
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)p);
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(p + 4 * C::PITCH));
+                short8v w = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                b[n] = __builtin_bit_cast(bf16x8, w);
+            }
+#pragma unroll
+            for (int m = 0; m < WT; ++m)
+#pragma unroll
+                for (int n = 0; n < WT; ++n)
+                    acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[n], acc[m][n], 0, 0, 0);
+        }
+        if (s + 1 < n_stage) lstore(cur ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: H[i][k] += 2 acc, mirrored.  Accumulator register r of lane l holds
+    // row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its 32x32 tile.
+    const int lr = (lane >> 5) * 4, lc = lane & 31;
+#pragma unroll
+    for (int m = 0; m < WT; ++m) {
+#pragma unroll
+        for (int n = 0; n < WT; ++n) {
+            const int k = k0 + wc * (32 * WT) + n * 32 + lc;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ib = i0 + wr * (32 * WT) + m * 32 + q * 8 + lr;  // 4 consecutive rows ib..ib+3
+                if (k >= d_in || ib >= d_in) continue;                     // d_in % 16 == 0: the 4 rows are in or out together
+                float nv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = ib + e;
+                    float* p = H + int64_t(i) * d_in + k;
+                    nv[e] = *p + 2.0f * acc[m][n][q * 4 + e];
+                    if (!diag || i <= k) *p = nv[e];
+                }
+                if (!diag) {
+                    float4 o = make_float4(nv[0], nv[1], nv[2], nv[3]);
+                    *reinterpret_cast<float4*>(H + int64_t(k) * d_in + ib) = o;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (ib + e < k) H[int64_t(k) * d_in + ib + e] = nv[e];
+                }
+            }
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------------
+// fp32 kernel: 128 x 128 tile, 4 waves in 2x2, each 2x2 tiles of v_mfma_f32_32x32x2_f32
+// -------------------------------------------------------------------------------------------
+constexpr int F32_TS = 128, F32_KT = 16, F32_PITCH = F32_TS + 4, F32_PANEL = F32_KT * F32_PITCH;
+
+__global__ __launch_bounds__(GRAM_THREADS) void gram_f32_kernel(const float* __restrict__ X, int64_t n_tokens,
+                                                               int d_in, int64_t ldx, float* __restrict__ H,
+                                                               int n_t, int n_tiles, int chunk) {
+    __shared__ __attribute__((aligned(16))) float lds[4 * F32_PANEL];
+    const int v = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+    if (v >= n_tiles) return;
+    int ti, tk;
+    tile_from_rank(v, n_t, ti, tk);
+    const bool diag = (ti == tk);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int i0 = ti * F32_TS, k0 = tk * F32_TS;
+
+    constexpr int NLOAD = F32_KT * F32_TS / 4 / GRAM_THREADS;  // 2
+    int ld_row[NLOAD], ld_col[NLOAD];
+#pragma unroll
+    for (int n = 0; n < NLOAD; ++n) {
+        int id = tid + GRAM_THREADS * n;
+        ld_row[n] = id / (F32_TS / 4);
+        ld_col[n] = (id % (F32_TS / 4)) * 4;
+    }
+    float4v ra[NLOAD], rb[NLOAD];
+    auto gload = [&](int64_t t0) {
+#pragma unroll
+        for (int n = 0; n < NLOAD; ++n) {
+            int64_t t = t0 + ld_row[n];
+            int ca = i0 + ld_col[n], cb = k0 + ld_col[n];
+            const float4v z = {0.f, 0.f, 0.f, 0.f};
+            ra[n] = (t < n_tokens && ca < d_in) ? *reinterpret_cast<const float4v*>(X + t * ldx + ca) : z;
+            if (!diag) rb[n] = (t < n_tokens && cb < d_in) ? *reinterpret_cast<const float4v*>(X + t * ldx + cb) : z;
+        }
+    };
+    auto lstore = [&](int stage) {
+        float* pa = lds + stage * 2 * F32_PANEL;
+        float* pb = pa + F32_PANEL;
+#pragma unroll
+        for (int n = 0; n < NLOAD; ++n) {
+            *reinterpret_cast<float4v*>(pa + ld_row[n] * F32_PITCH + ld_col[n]) = ra[n];
+            if (!diag) *reinterpret_cast<float4v*>(pb + ld_row[n] * F32_PITCH + ld_col[n]) = rb[n];
+        }
+    };
+
+    float16v acc[2][2];
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
+
+    const int64_t n_stage = (n_tokens + F32_KT - 1) / F32_KT;
+    gload(0);
+    lstore(0);
+    __syncthreads();
+    const int kl = lane >> 5, cl = lane & 31;  // operand: channel = lane % 32, token = lane / 32
+    for (int64_t s = 0; s < n_stage; ++s) {
+        const int cur = int(s & 1);
+        if (s + 1 < n_stage) gload((s + 1) * F32_KT);
+        const float* pa = lds + cur * 2 * F32_PANEL;
+        const float* pb = diag ? pa : pa + F32_PANEL;
+#pragma unroll
+        for (int k2 = 0; k2 < F32_KT; k2 += 2) {
+            float a[2], b[2];
+#pragma unroll
+            for (int m = 0; m < 2; ++m) a[m] = pa[(k2 + kl) * F32_PITCH + wr * 64 + m * 32 + cl];
+#pragma unroll
+            for (int n = 0; n < 2; ++n) b[n] = pb[(k2 + kl) * F32_PITCH + wc * 64 + n * 32 + cl];
+#pragma unroll
+            for (int m = 0; m < 2; ++m)
+#pragma unroll
+                for (int n = 0; n < 2; ++n)
+                    acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[m], b[n], acc[m][n], 0, 0, 0);
+        }
+        if (s + 1 < n_stage) lstore(cur ^ 1);
+        __syncthreads();
+    }
+
+    const int lr = (lane >> 5) * 4, lc = lane & 31;
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+#pragma unroll
+        for (int n = 0; n < 2; ++n) {
+            const int k = k0 + wc * 64 + n * 32 + lc;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ib = i0 + wr * 64 + m * 32 + q * 8 + lr;
+                if (k >= d_in || ib >= d_in) continue;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = ib + e;
+                    if (diag && i > k) continue;
+                    float* p = H + int64_t(i) * d_in + k;
+                    float nv = *p + 2.0f * acc[m][n][q * 4 + e];
+                    *p = nv;
+                    if (i != k) H[int64_t(k) * d_in + i] = nv;
+                }
+            }
+        }
+    }
+}
+
+template <int WT>
+onecomp_status launch_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
+                           hipStream_t stream) {
+    using C = GramBf16Cfg<WT>;
+    const int n_t = int(ceil_div(d_in, C::TS));
+    const int n_tiles = n_t * (n_t + 1) / 2;
+    const int chunk = int(ceil_div(n_tiles, 8));
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_kernel<WT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)) != hipSuccess)
+            return ONECOMP_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(gram_bf16_kernel<WT>, dim3(chunk * 8), dim3(GRAM_THREADS), C::LDS_BYTES, stream,
+                       static_cast<const uint16_t*>(X), n_tokens, int(d_in), ldx, H, n_t, n_tiles, chunk);
+    ONECOMP_CHECK_LAUNCH();
+    return ONECOMP_OK;
+}
+
+}  // namespace
+
+onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
+                                    hipStream_t stream) {
+    // 256-wide tiles once they give every CU at least a few tiles; 128-wide below that.
+    const int64_t n256 = ceil_div(d_in, 256);
+    if (n256 * (n256 + 1) / 2 >= 512) return launch_bf16<4>(X, n_tokens, d_in, ldx, H, stream);
+    return launch_bf16<2>(X, n_tokens, d_in, ldx, H, stream);
+}
+
+onecomp_status gram_accumulate_f32(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
+                                   hipStream_t stream) {
+    const int n_t = int(ceil_div(d_in, F32_TS));
+    const int n_tiles = n_t * (n_t + 1) / 2;
+    const int chunk = int(ceil_div(n_tiles, 8));
+    hipLaunchKernelGGL(gram_f32_kernel, dim3(chunk * 8), dim3(GRAM_THREADS), 0, stream,
+                       static_cast<const float*>(X), n_tokens, int(d_in), ldx, H, n_t, n_tiles, chunk);
+    ONECOMP_CHECK_LAUNCH();
+    return ONECOMP_OK;
+}
+
+}  // namespace onecomp

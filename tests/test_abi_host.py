@@ -1,0 +1,105 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+function the header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2603_28845_amd as oc_gpu
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "onecomp.h")
+
+OK, INVALID, UNSUPPORTED, NOT_POSDEF, WORKSPACE, HIP = range(6)
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return oc_gpu.load_library()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(onecomp_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = _declared_functions()
+    assert set(names) == set(oc_gpu.EXPORTED_SYMBOLS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_status_strings(lib):
+    assert oc_gpu.onecomp_version() >= 100
+    seen = {oc_gpu.status_string(c) for c in range(6)}
+    assert len(seen) == 6 and "ok" in seen
+    assert oc_gpu.status_string(99) == "unknown status"
+
+
+def test_workspace_queries(lib):
+    assert oc_gpu.onecomp_factor_workspace_bytes(0) == 0
+    assert oc_gpu.onecomp_factor_workspace_bytes(100) == 0          # not a multiple of 16
+    assert oc_gpu.onecomp_factor_workspace_bytes(512) >= 3 * 512 * 512 * 8
+    assert oc_gpu.onecomp_quantize_workspace_bytes(256, 512, 128) >= 256 * 512 * 4
+    assert oc_gpu.onecomp_quantize_workspace_bytes(256, 512, 64) == 0
+    assert oc_gpu.onecomp_quantize_workspace_bytes(256, 500, 128) == 0
+
+
+P = ctypes.c_void_p(0x10000)   # non-null, 256-byte aligned dummy; never dereferenced on these paths
+NULL = ctypes.c_void_p(0)
+
+
+def test_accumulate_argument_checks(lib):
+    f = lib.onecomp_hessian_accumulate
+    assert f(P, 7, 10, 128, 128, P, NULL) == UNSUPPORTED
+    assert f(P, 0, 10, 128, 128, NULL, NULL) == INVALID       # H null
+    assert f(NULL, 0, 10, 128, 128, P, NULL) == INVALID       # X null with tokens
+    assert f(P, 0, 10, 120, 120, P, NULL) == INVALID          # d_in % 16
+    assert f(P, 0, 10, 128, 64, P, NULL) == INVALID           # ldx < d_in
+    assert f(P, 0, -1, 128, 128, P, NULL) == INVALID
+    assert f(ctypes.c_void_p(0x10004), 1, 10, 128, 128, P, NULL) == INVALID   # misaligned X
+    assert f(NULL, 0, 0, 128, 128, P, NULL) == OK             # zero tokens: no-op
+
+
+def test_factor_argument_checks(lib):
+    f = lib.onecomp_hessian_factor
+    big = ctypes.c_size_t(1 << 40)
+    assert f(NULL, 128, 0.01, 0, NULL, P, P, P, big, NULL) == INVALID
+    assert f(P, 128, 0.01, 0, NULL, NULL, P, P, big, NULL) == INVALID
+    assert f(P, 128, 0.01, 0, NULL, P, NULL, P, big, NULL) == INVALID
+    assert f(P, 100, 0.01, 0, NULL, P, P, P, big, NULL) == INVALID
+    assert f(P, 128, -1.0, 0, NULL, P, P, P, big, NULL) == INVALID
+    assert f(P, 128, float("nan"), 0, NULL, P, P, P, big, NULL) == INVALID
+    assert f(P, 128, 0.01, 1, NULL, P, P, P, big, NULL) == INVALID      # act_order needs perm_out
+    assert f(P, 128, 0.01, 0, NULL, P, P, NULL, big, NULL) == WORKSPACE
+    assert f(P, 128, 0.01, 0, NULL, P, P, P, ctypes.c_size_t(1024), NULL) == WORKSPACE
+    assert f(P, 128, 0.01, 0, NULL, P, P, ctypes.c_void_p(0x10010), big, NULL) == WORKSPACE
+
+
+def test_quantize_argument_checks(lib):
+    f = lib.onecomp_quantize_layer
+    big = ctypes.c_size_t(1 << 40)
+
+    def call(W=P, dt=1, d_out=64, d_in=256, U=P, perm=NULL, bits=4, G=128, B=128, Q=P, s=P, z=P, wh=P, loss=P,
+             ws=P, wsb=big):
+        return f(W, dt, d_out, d_in, U, perm, bits, G, B, Q, s, z, wh, loss, ws, wsb, NULL)
+
+    assert call(dt=3) == UNSUPPORTED
+    assert call(W=NULL) == INVALID
+    assert call(U=NULL) == INVALID
+    assert call(Q=NULL) == INVALID
+    assert call(loss=NULL) == INVALID
+    assert call(d_out=0) == INVALID
+    for b in (0, 1, 5, 6, 7, 9, 16):
+        assert call(bits=b) == UNSUPPORTED
+    assert call(B=64) == UNSUPPORTED
+    assert call(d_in=200) == INVALID            # d_in % block
+    assert call(G=96) == INVALID                # does not divide d_in
+    assert call(d_in=384, G=192) == INVALID     # divides d_in, but neither divides nor is divided by the block
+    assert call(G=8) == UNSUPPORTED             # not a multiple of 16
+    assert call(G=0) == INVALID
+    assert call(ws=NULL) == WORKSPACE
+    assert call(wsb=ctypes.c_size_t(16)) == WORKSPACE
