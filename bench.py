@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the layer-wise Hessian-aware quantization hot path on one MI355X.
+
+One "step" = the whole hot path for one linear layer on synthetic inputs already resident in HBM:
+    onecomp_hessian_accumulate (all calibration tokens) -> onecomp_hessian_factor -> onecomp_quantize_layer
+Default workload: the Llama-style down projection W 4096 x 14336 (d_in = 14336), 262144 calibration
+tokens, 4-bit, group 128, damp 0.01 (the layer the task's MFMA / HBM targets are quoted on).
+
+Prints ONE JSON line: whole-step throughput in weights/s, per-phase times, the roofline of the dominant
+kernel (Gram accumulation, MFMA bound), the sweep's HBM-roofline figure, and the float64 oracle timed on
+the host cores over a bounded sample (reported baseline, not the target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def sweep_model_bytes(d_out, d_in, B, G, w_bytes):
+    """HBM bytes of the right-looking lazy-batch schedule with an fp32 working copy (block B):
+    per block, the trailing columns are read and written once (8 B / element) and the block's rows of U are
+    read (4 B / element); plus W in, codes (1 B) and W^ (4 B) out, scales and zeros."""
+    n_b = d_in // B
+    total = 0
+    for k in range(n_b):
+        total += 8 * d_out * (d_in - (k + 1) * B) + 4 * B * (d_in - k * B)
+    total += d_out * d_in * (w_bytes + 1 + 4) + 8 * d_out * d_in // G
+    return total
+
+
+def cpu_baseline(cfg, synth, seconds_hint=20.0):
+    """Oracle (float64, numpy) timed per phase on bounded samples of the same workload and extrapolated by
+    work: Gram over n_s tokens (linear in tokens), factor at d_s = d_in / 2 (cubic), sweep of r_s rows at
+    d_s columns (linear in rows, quadratic in columns)."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import onecomp_oracle as oc
+
+    n_s = min(2048, cfg.n_tokens)
+    d_s = max(128, (cfg.d_in // 2) // cfg.group_size * cfg.group_size)
+    r_s = min(64, cfg.d_out)
+    X = synth.make_activations(cfg, "cpu", n_tokens=n_s).to(dtype=__import__("torch").float64).numpy()
+    t0 = time.perf_counter()
+    H = oc.hessian_accumulate(X)
+    t_gram = time.perf_counter() - t0
+    Hs = np.ascontiguousarray(H[:d_s, :d_s])
+    del H
+    t0 = time.perf_counter()
+    f = oc.hessian_factor(Hs, max(cfg.damp, 0.01) * 10.0, act_order=cfg.act_order)   # rank-deficient sample: heavier damping keeps it PD
+    t_factor = time.perf_counter() - t0
+    Wc = synth.scaled(cfg, d_out=r_s, d_in=d_s)
+    W = synth.make_weight(Wc, "cpu").to(dtype=__import__("torch").float64).numpy()
+    t0 = time.perf_counter()
+    oc.quantize_layer(W, f["U"], cfg.bits, cfg.group_size, perm=f["perm"])
+    t_sweep = time.perf_counter() - t0
+    est = (t_gram * cfg.n_tokens / n_s + t_factor * (cfg.d_in / d_s) ** 3 +
+           t_sweep * (cfg.d_out / r_s) * (cfg.d_in / d_s) ** 2)
+    threads = 1
+    for info in threadpool_info():
+        if info.get("user_api") == "blas":
+            threads = max(threads, int(info.get("num_threads", 1)))
+    return {
+        "value": cfg.d_out * cfg.d_in / est, "unit": "weights/s", "cores": threads, "kind": "oracle",
+        "sample": (f"extrapolated by work from: Gram over {n_s} of {cfg.n_tokens} tokens at d_in={cfg.d_in} "
+                   f"({t_gram:.2f} s), factor at d={d_s} ({t_factor:.2f} s, x(d_in/d)^3), sweep of {r_s} rows x {d_s} "
+                   f"columns ({t_sweep:.2f} s, x rows x (d_in/d)^2); estimated full step {est:.0f} s"),
+        "measured_s": {"gram": t_gram, "factor": t_factor, "sweep": t_sweep},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3b", help="synthetic layer config (see paper_2603_28845_amd/synth.py)")
+    ap.add_argument("--tokens-per-call", type=int, default=0, help="0 = all calibration tokens in one accumulate call")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2603_28845_amd as og
+    from paper_2603_28845_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    og.load_library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    d_out, d_in, T = cfg.d_out, cfg.d_in, cfg.n_tokens
+
+    W = synth.make_weight(cfg, dev)
+    X = synth.make_activations(cfg, dev)
+    H = torch.zeros((d_in, d_in), dtype=torch.float32, device=dev)
+    U = torch.empty((d_in, d_in), dtype=torch.float32, device=dev)
+    info = torch.zeros(1, dtype=torch.int32, device=dev)
+    perm = torch.empty(d_in, dtype=torch.int32, device=dev) if cfg.act_order else None
+    ws_f = torch.empty(og.onecomp_factor_workspace_bytes(d_in), dtype=torch.uint8, device=dev)
+    ws_q = torch.empty(og.onecomp_quantize_workspace_bytes(d_out, d_in, 128), dtype=torch.uint8, device=dev)
+    n_g = d_in // cfg.group_size
+    out = {
+        "Q_codes": torch.empty((d_out, d_in), dtype=torch.uint8, device=dev),
+        "scales": torch.empty((d_out, n_g), dtype=torch.float32, device=dev),
+        "zeros": torch.empty((d_out, n_g), dtype=torch.float32, device=dev),
+        "W_hat": torch.empty((d_out, d_in), dtype=torch.float32, device=dev),
+        "loss": torch.zeros(1, dtype=torch.float32, device=dev),
+    }
+    tpc = args.tokens_per_call if args.tokens_per_call > 0 else T
+    n_calls = (T + tpc - 1) // tpc
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def step(record=None):
+        e = [ev() for _ in range(4)]
+        H.zero_()
+        e[0].record()
+        for t0 in range(0, T, tpc):
+            og.onecomp_hessian_accumulate(X[t0:t0 + tpc], H)
+        e[1].record()
+        og.onecomp_hessian_factor(H, cfg.damp, cfg.act_order, U=U, perm_out=perm, info=info, workspace=ws_f)
+        e[2].record()
+        og.onecomp_quantize_layer(W, U, cfg.bits, cfg.group_size, perm=perm, workspace=ws_q, out=out)
+        e[3].record()
+        if record is not None:
+            record.append(e)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    rec = []
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step(rec)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    assert int(info.item()) == 0, "Hessian not positive definite"
+
+    acc_ms = sum(e[0].elapsed_time(e[1]) for e in rec) / len(rec)
+    fac_ms = sum(e[1].elapsed_time(e[2]) for e in rec) / len(rec)
+    swp_ms = sum(e[2].elapsed_time(e[3]) for e in rec) / len(rec)
+    ms_per_step = wall * 1e3 / args.steps
+    weights = d_out * d_in
+
+    # Gram kernel: one launch per accumulate call.  Algorithmic flops = symmetric half, T d (d + 1).
+    gram_ms = acc_ms / n_calls
+    algo_flops = float(tpc) * d_in * (d_in + 1)
+    gram_tflops = algo_flops / (gram_ms * 1e-3) / 1e12
+    roofline = {
+        "kernel": "gram_bf16_kernel" if cfg.dtype == torch.bfloat16 else "gram_f32_kernel",
+        "bound": "mfma", "achieved": gram_tflops, "peak": PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3,
+        "unit": "TFLOP/s", "frac": gram_tflops / (PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3),
+        "traffic": None,
+        "note": "algorithmic flops = T*d_in*(d_in+1) (upper triangle incl. diagonal, 2 flops per MAC); "
+                "dense-equivalent rate is 2x this",
+        "avg_launch_ms": gram_ms,
+    }
+    sweep_bytes = sweep_model_bytes(d_out, d_in, 128, cfg.group_size, 2 if cfg.dtype == torch.bfloat16 else 4)
+    sweep_gbs = sweep_bytes / (swp_ms * 1e-3) / 1e9
+    roofline_sweep = {
+        "kernel": "onecomp_quantize_layer (block_kernel + trailing_kernel launches)", "bound": "hbm",
+        "achieved": sweep_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": sweep_gbs / PEAK_HBM_GBS,
+        "traffic": None, "model_bytes": sweep_bytes,
+        "note": "modelled bytes of the right-looking B=128 schedule with fp32 working copy / whole-call time",
+    }
+
+    res = {
+        "metric": "weights_quantized_per_sec", "value": weights / (ms_per_step * 1e-3), "unit": "weights/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 inputs, f32 accumulate and sweep, f64 factor" if cfg.dtype == torch.bfloat16 else "f32 (f64 factor)",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: W {d_out}x{d_in} {str(cfg.dtype).split('.')[-1]}, {T} tokens, "
+                               f"{cfg.bits}-bit, group {cfg.group_size}, damp {cfg.damp}, act_order {cfg.act_order}, "
+                               f"block 128, {n_calls} accumulate call(s)"},
+        "phases_ms": {"hessian_accumulate": acc_ms, "hessian_factor": fac_ms, "quantize_layer": swp_ms},
+        "layer_quantize_ms": fac_ms + swp_ms,
+        "weights_per_sec_factor_plus_sweep": weights / ((fac_ms + swp_ms) * 1e-3),
+        "weights_per_sec_sweep_only": weights / (swp_ms * 1e-3),
+        "loss": float(out["loss"].item()),
+        "roofline": roofline, "roofline_sweep": roofline_sweep,
+    }
+    if not args.no_cpu_baseline:
+        del X
+        torch.cuda.empty_cache()
+        res["cpu_baseline"] = cpu_baseline(cfg, synth)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
