@@ -86,6 +86,11 @@ def main():
     ap.add_argument("--workload", default="c3b", help="synthetic layer config (see paper_2603_28845_amd/synth.py)")
     ap.add_argument("--tokens-per-call", type=int, default=0, help="0 = all calibration tokens in one accumulate call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--phase", default="all", choices=["all", "gram", "factor", "sweep"],
+                    help="profiling aid: run only one call in the timed loop (the others run once to prepare its inputs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="profiling aid: also run one plain 4 GiB device-to-device copy kernel (known HBM traffic: "
+                         "4 GiB read + 4 GiB written) so that FETCH_SIZE / WRITE_SIZE can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
@@ -127,34 +132,53 @@ def main():
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
-    def step(record=None):
+    phase = args.phase
+
+    def step(record=None, only=None):
         e = [ev() for _ in range(4)]
-        H.zero_()
+        if only in (None, "gram"):
+            H.zero_()
         e[0].record()
-        for t0 in range(0, T, tpc):
-            og.onecomp_hessian_accumulate(X[t0:t0 + tpc], H)
+        if only in (None, "gram"):
+            for t0 in range(0, T, tpc):
+                og.onecomp_hessian_accumulate(X[t0:t0 + tpc], H)
         e[1].record()
-        og.onecomp_hessian_factor(H, cfg.damp, cfg.act_order, U=U, perm_out=perm, info=info, workspace=ws_f)
+        if only in (None, "factor"):
+            og.onecomp_hessian_factor(H, cfg.damp, cfg.act_order, U=U, perm_out=perm, info=info, workspace=ws_f)
         e[2].record()
-        og.onecomp_quantize_layer(W, U, cfg.bits, cfg.group_size, perm=perm, workspace=ws_q, out=out)
+        if only in (None, "sweep"):
+            og.onecomp_quantize_layer(W, U, cfg.bits, cfg.group_size, perm=perm, workspace=ws_q, out=out)
         e[3].record()
         if record is not None:
             record.append(e)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+    if phase != "all":
+        step()          # prepares H and U for a single-phase loop
+        torch.cuda.synchronize()
+
+    only = None if phase == "all" else phase
     for _ in range(args.warmup):
-        step()
+        step(only=only)
     torch.cuda.synchronize()
     rec = []
     t_start = time.perf_counter()
     for _ in range(args.steps):
-        step(rec)
+        step(rec, only=only)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     assert int(info.item()) == 0, "Hessian not positive definite"
 
-    acc_ms = sum(e[0].elapsed_time(e[1]) for e in rec) / len(rec)
-    fac_ms = sum(e[1].elapsed_time(e[2]) for e in rec) / len(rec)
-    swp_ms = sum(e[2].elapsed_time(e[3]) for e in rec) / len(rec)
+    tiny = 1e-6   # phases skipped by --phase read as ~0; keep the ratios finite
+    acc_ms = max(tiny, sum(e[0].elapsed_time(e[1]) for e in rec) / len(rec))
+    fac_ms = max(tiny, sum(e[1].elapsed_time(e[2]) for e in rec) / len(rec))
+    swp_ms = max(tiny, sum(e[2].elapsed_time(e[3]) for e in rec) / len(rec))
     ms_per_step = wall * 1e3 / args.steps
     weights = d_out * d_in
 
@@ -188,7 +212,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: W {d_out}x{d_in} {str(cfg.dtype).split('.')[-1]}, {T} tokens, "
                                f"{cfg.bits}-bit, group {cfg.group_size}, damp {cfg.damp}, act_order {cfg.act_order}, "
-                               f"block 128, {n_calls} accumulate call(s)"},
+                               f"block 128, {n_calls} accumulate call(s)"
+                               + ("" if phase == "all" else f" [PROFILING RUN: only phase '{phase}' timed, value is not the metric]")},
         "phases_ms": {"hessian_accumulate": acc_ms, "hessian_factor": fac_ms, "quantize_layer": swp_ms},
         "layer_quantize_ms": fac_ms + swp_ms,
         "weights_per_sec_factor_plus_sweep": weights / ((fac_ms + swp_ms) * 1e-3),

@@ -95,64 +95,191 @@ __global__ __launch_bounds__(256) void output_kernel(const double* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
-// diagonal block: Cholesky in LDS, then in-place triangular inverse.  One workgroup.
+// diagonal block: Cholesky in LDS, then in-place triangular inverse.  One workgroup of 256 threads.
 // A block (bs x bs, bs <= 128) at A + off*(n+1); L written back to A (lower part), L^-1 to V (full block,
 // zeros above the diagonal).  A non-positive pivot sets *info (first one wins) and is replaced by 1.
+//
+// Both halves work on 16-wide sub-blocks so that the number of workgroup barriers is ~60 instead of one or
+// more per column: the 16 x 16 diagonal sub-block is factored by a single wave (in-order LDS traffic, no
+// workgroup barrier), rows below it are solved one thread per row in registers, the trailing part gets a
+// rank-16 update.  Square roots and reciprocals come from v_rsq_f64 plus two Newton steps.
 // ------------------------------------------------------------------------------------------
-constexpr int DP = NB + 1;  // LDS pitch in doubles
+constexpr int DP = NB + 1;   // LDS pitch in doubles
+constexpr int SBW = 16;      // sub-block width
+
+__device__ inline double rsqrt_refined(double p) {
+    double y = __builtin_amdgcn_rsq(p);
+    const double h = 0.5 * p;
+    y = y * __builtin_fma(-h * y, y, 1.5);
+    y = y * __builtin_fma(-h * y, y, 1.5);
+    return y;
+}
 
 __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A, double* __restrict__ V, int n,
                                                         int off, int bs, int32_t* __restrict__ info) {
-    extern __shared__ double S[];  // NB x DP
+    extern __shared__ double S[];          // NB x DP matrix, then NB reciprocal diagonal entries
+    double* dinv = S + NB * DP;
     const int tid = threadIdx.x;
     for (int e = tid; e < NB * NB; e += 256) {
-        int r = e / NB, c = e % NB;
-        double v = (r == c) ? 1.0 : 0.0;
+        const int r = e / NB, c = e % NB;
+        double v = (r == c) ? 1.0 : 0.0;   // identity padding for a short last block
         if (r < bs && c < bs) v = A[int64_t(off + r) * n + off + c];
         S[r * DP + c] = v;
     }
     __syncthreads();
-    for (int j = 0; j < bs; ++j) {
-        double p = S[j * DP + j];
-        const bool bad = !(p > 0.0);
-        if (bad) p = 1.0;
-        const double rinv = 1.0 / sqrt(p);
-        __syncthreads();  // everyone has read the pivot
-        if (tid == 0) {
-            S[j * DP + j] = sqrt(p);
-            if (bad && *info == 0) *info = off + j + 1;
+
+    // ---------------- Cholesky, 8 panels of 16 columns ----------------
+    for (int c0 = 0; c0 < NB; c0 += SBW) {
+        // (a1) diagonal 16 x 16 sub-block: wave 0, lane i (mod 16) = row c0 + i, row segment in registers;
+        // lanes exchange finished entries with wave shuffles, so no LDS traffic or barrier is needed inside.
+        // (Lanes 16..63 shadow lanes 0..15 so that every shuffle source is active; they store nothing.)
+        if (tid < 64) {
+            const int i = tid & 15;
+            double r[SBW];
+            double my_dinv = 1.0;
+#pragma unroll
+            for (int c = 0; c < SBW; ++c) r[c] = S[(c0 + i) * DP + c0 + c];
+#pragma unroll
+            for (int j = 0; j < SBW; ++j) {
+                double p = r[j];                       // meaningful in lane j only
+                const bool bad = !(p > 0.0);
+                if (bad) p = 1.0;
+                const double ri = rsqrt_refined(p);
+                double sq = p * ri;
+                sq = __builtin_fma(0.5 * ri, __builtin_fma(-sq, sq, p), sq);
+                const double ri_j = __shfl(ri, j, 16);
+                if (i == j) {
+                    if (bad && tid == j && *info == 0) *info = off + c0 + j + 1;
+                    r[j] = sq;
+                    my_dinv = ri;
+                }
+                const double lij = r[j] * ri_j;        // l_ij for rows below the pivot
+                if (i > j) r[j] = lij;
+#pragma unroll
+                for (int c = j + 1; c < SBW; ++c) {
+                    const double lcj = __shfl(lij, c, 16);
+                    if (i >= c) r[c] = __builtin_fma(-lij, lcj, r[c]);
+                }
+            }
+            if (tid < SBW) {
+                dinv[c0 + i] = my_dinv;
+#pragma unroll
+                for (int c = 0; c < SBW; ++c)
+                    if (c <= i) S[(c0 + i) * DP + c0 + c] = r[c];
+            }
         }
-        for (int i = j + 1 + tid; i < bs; i += 256) S[i * DP + j] *= rinv;
         __syncthreads();
-        // trailing update of the lower triangle: S[i][c] -= S[i][j] S[c][j], j < c <= i < bs
-        const int rem = bs - 1 - j;
-        for (int e = tid; e < rem * rem; e += 256) {
-            int i = j + 1 + e / rem, c = j + 1 + e % rem;
-            if (c <= i) S[i * DP + c] -= S[i * DP + j] * S[c * DP + j];
+        // (a2) rows below the sub-block: x_j = (a_ij - sum_{m<j} x_m L[j][m]) / L[j][j], one thread per row
+        {
+            const int i = c0 + SBW + tid;
+            if (i < NB) {
+                double x[SBW];
+#pragma unroll
+                for (int c = 0; c < SBW; ++c) x[c] = S[i * DP + c0 + c];
+#pragma unroll
+                for (int j = 0; j < SBW; ++j) {
+                    double acc = x[j];
+#pragma unroll
+                    for (int m = 0; m < j; ++m) acc = __builtin_fma(-x[m], S[(c0 + j) * DP + c0 + m], acc);
+                    x[j] = acc * dinv[c0 + j];
+                }
+#pragma unroll
+                for (int c = 0; c < SBW; ++c) S[i * DP + c0 + c] = x[c];
+            }
+        }
+        __syncthreads();
+        // (b) rank-16 update of the trailing lower triangle: S[i][c] -= sum_m L[i][c0+m] L[c][c0+m]
+        {
+            const int t0 = c0 + SBW;
+            for (int i = t0 + (tid >> 4); i < NB; i += 16) {
+                double li[SBW];
+#pragma unroll
+                for (int m = 0; m < SBW; ++m) li[m] = S[i * DP + c0 + m];
+                for (int c = t0 + (tid & 15); c <= i; c += 16) {
+                    double acc = S[i * DP + c];
+#pragma unroll
+                    for (int m = 0; m < SBW; ++m) acc = __builtin_fma(-li[m], S[c * DP + c0 + m], acc);
+                    S[i * DP + c] = acc;
+                }
+            }
         }
         __syncthreads();
     }
-    for (int e = tid; e < bs * bs; e += 256) {
-        int r = e / bs, c = e % bs;
+    for (int e = tid; e < bs * NB; e += 256) {
+        const int r = e / NB, c = e % NB;
         if (c <= r) A[int64_t(off + r) * n + off + c] = S[r * DP + c];
     }
     __syncthreads();
-    // in-place inverse of the lower-triangular S, last column first:
-    //   x_jj = 1 / l_jj ;  x[j+1:, j] = -(X[j+1:, j+1:] l[j+1:, j]) x_jj
-    for (int j = bs - 1; j >= 0; --j) {
-        const double djj = 1.0 / S[j * DP + j];
-        double y = 0.0;
-        const int i = j + 1 + tid;
-        if (i < bs) {
-            for (int m = j + 1; m <= i; ++m) y += S[i * DP + m] * S[m * DP + j];
+
+    // ---------------- X = L^-1 in place, 16 x 16 sub-blocks ----------------
+    // diagonal sub-blocks: thread t < 128 solves column t of its sub-block by forward substitution
+    {
+        double x[SBW];
+        const int b0 = (tid >> 4) * SBW, c = tid & 15;
+        if (tid < NB) {
+#pragma unroll
+            for (int i = 0; i < SBW; ++i) {
+                double acc = (i == c) ? 1.0 : 0.0;
+#pragma unroll
+                for (int m = 0; m < i; ++m)
+                    if (m >= c) acc = __builtin_fma(-S[(b0 + i) * DP + b0 + m], x[m], acc);
+                x[i] = (i >= c) ? acc * dinv[b0 + i] : 0.0;
+            }
         }
         __syncthreads();
-        if (i < bs) S[i * DP + j] = -y * djj;
-        if (tid == 0) S[j * DP + j] = djj;
+        if (tid < NB) {
+#pragma unroll
+            for (int i = 0; i < SBW; ++i)
+                if (i >= c) S[(b0 + i) * DP + b0 + c] = x[i];
+        }
+        __syncthreads();
+    }
+    // block rows top to bottom: X_ij = -X_ii * sum_{m=j}^{i-1} L_im X_mj  (j < i).  Row i of S still holds L_im.
+    for (int ib = 1; ib < NB / SBW; ++ib) {
+        const int i0 = ib * SBW;
+        const int n_out = SBW * i0;            // outputs of this block row: 16 rows x i0 columns
+        double t[7];                           // <= 7 outputs per thread (16 * 112 / 256)
+#pragma unroll
+        for (int q = 0; q < 7; ++q) {
+            const int e = tid + 256 * q;
+            t[q] = 0.0;
+            if (e < n_out) {
+                const int r = e / i0, c = e % i0;          // row i0 + r, column c
+                double acc = 0.0;                          // X[m][c] is zero for m < c
+                for (int m = c; m < i0; ++m) acc = __builtin_fma(S[(i0 + r) * DP + m], S[m * DP + c], acc);
+                t[q] = acc;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 7; ++q) {
+            const int e = tid + 256 * q;
+            if (e < n_out) S[(i0 + e / i0) * DP + e % i0] = t[q];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 7; ++q) {
+            const int e = tid + 256 * q;
+            t[q] = 0.0;
+            if (e < n_out) {
+                const int r = e / i0, c = e % i0;
+                double acc = 0.0;
+#pragma unroll
+                for (int m = 0; m < SBW; ++m)
+                    if (m <= r) acc = __builtin_fma(S[(i0 + r) * DP + i0 + m], S[(i0 + m) * DP + c], acc);
+                t[q] = -acc;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 7; ++q) {
+            const int e = tid + 256 * q;
+            if (e < n_out) S[(i0 + e / i0) * DP + e % i0] = t[q];
+        }
         __syncthreads();
     }
     for (int e = tid; e < bs * bs; e += 256) {
-        int r = e / bs, c = e % bs;
+        const int r = e / bs, c = e % bs;
         V[int64_t(off + r) * n + off + c] = (c <= r) ? S[r * DP + c] : 0.0;
     }
 }
@@ -180,7 +307,7 @@ struct GemmArgs {
     int flags;
 };
 
-__global__ __launch_bounds__(256) void dgemm_kernel(GemmArgs g) {
+__global__ __launch_bounds__(256, 2) void dgemm_kernel(GemmArgs g) {
     __shared__ double sA[2][GT * GPA];
     __shared__ double sB[2][GSB];
     const int z = blockIdx.z;
@@ -240,7 +367,7 @@ __global__ __launch_bounds__(256) void dgemm_kernel(GemmArgs g) {
     };
     auto lstore = [&](int st) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) sA[st][a_row * GPA + a_k + e] = ra[e];
+        for (int e = 0; e < 8; ++e) sA[st][a_row * GPA + a_k + e] = g.alpha * ra[e];   // alpha folded into A
         if (bt) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) sB[st][a_row * GPA + a_k + e] = rb[e];
@@ -250,19 +377,25 @@ __global__ __launch_bounds__(256) void dgemm_kernel(GemmArgs g) {
         }
     };
 
+    const int l16 = lane & 15, lk = lane >> 4;
+    if (k_lo < k_hi) gload(k_lo);
+    // accumulators start as beta * C (register r of lane l: row 4 r + l / 16, column l % 16 of its 16 x 16 tile),
+    // so the C tile is in flight together with the first operand tiles
     double4v acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0;
+            for (int r = 0; r < 4; ++r) {
+                const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
+                const int col = n0 + wc * 64 + j * 16 + l16;
+                double c = 0.0;
+                if (g.beta != 0.0 && row < m && col < g.n) c = g.beta * C[int64_t(row) * g.ldc + col];
+                acc[i][j][r] = c;
+            }
 
-    const int l16 = lane & 15, lk = lane >> 4;
-    if (k_lo < k_hi) {
-        gload(k_lo);
-        lstore(0);
-    }
+    if (k_lo < k_hi) lstore(0);
     __syncthreads();
     int st = 0;
     for (int k0 = k_lo; k0 < k_hi; k0 += GK) {
@@ -298,10 +431,7 @@ __global__ __launch_bounds__(256) void dgemm_kernel(GemmArgs g) {
                 const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
                 const int col = n0 + wc * 64 + j * 16 + l16;
                 if (row < m && col < g.n) {
-                    double* p = C + int64_t(row) * g.ldc + col;
-                    double v = g.alpha * acc[i][j][r];
-                    if (g.beta != 0.0) v += g.beta * (*p);
-                    *p = v;
+                    C[int64_t(row) * g.ldc + col] = acc[i][j][r];
                 }
             }
 }
@@ -362,7 +492,7 @@ onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_orde
     ONECOMP_CHECK_LAUNCH();
 
     static bool attr_set = false;
-    const size_t potrf_lds = size_t(NB) * DP * sizeof(double);
+    const size_t potrf_lds = (size_t(NB) * DP + NB) * sizeof(double);
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&potrf_diag_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, int(potrf_lds)) != hipSuccess)

@@ -56,7 +56,7 @@ template <int WT>
 struct GramBf16Cfg {
     static constexpr int TS = 64 * WT;          // tile side in channels
     static constexpr int KT = 32;               // tokens per LDS stage
-    static constexpr int PITCH = TS + 16;       // bf16 elements; +32 B staggers 4 token rows over the banks
+    static constexpr int PITCH = TS + 32;       // bf16 elements; +64 B per token row: the 4 rows x 2 lane groups of a transpose read hit 64 distinct banks
     static constexpr int PANEL = KT * PITCH;    // elements per panel
     static constexpr int CHUNKS = KT * TS / 8;  // 16-byte chunks per panel
     static constexpr int NLOAD = CHUNKS / GRAM_THREADS;
