@@ -199,6 +199,183 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_kernel(const uint16_t*
 }
 
 // -------------------------------------------------------------------------------------------
+// bf16 kernel for large d_in: 256 x 256 tile, software-pipelined
+//
+//   stage t = tokens [32 t, 32 t + 32);  LDS ring of 3 stage buffers;  one register set for global loads.
+//   iteration s:  (1) registers of stage s+1 (loaded one iteration ago) -> LDS buffer (s+1) % 3
+//                 (2) global loads of stage s+2 -> the same registers
+//                 (3) LDS -> fragments of the second half (tokens 16..31) of stage s
+//                 (4) 16 MFMAs on the first half of stage s (fragments preloaded in the previous iteration)
+//                 (5) workgroup barrier: stage s+1 is complete in LDS
+//                 (6) LDS -> fragments of the first half of stage s+1
+//                 (7) 16 MFMAs on the second half of stage s
+//   Every global load has a full iteration to land before it is needed, every LDS read half an iteration,
+//   and there is one barrier per 32 tokens, placed where 16 MFMAs are already queued behind it.
+// -------------------------------------------------------------------------------------------
+namespace pipe {
+constexpr int TS = 256, KT = 32, PITCH = TS + 32, PANEL = KT * PITCH, STAGE = 2 * PANEL, NBUF = 3;
+constexpr size_t LDS_BYTES = size_t(NBUF) * STAGE * 2;
+constexpr int NLOAD = KT * TS / 8 / GRAM_THREADS;  // 4 chunks of 16 B per thread and panel
+
+struct Frags {
+    bf16x8 a[4], b[4];
+};
+struct Staged {
+    uint4v a[NLOAD], b[NLOAD];
+};
+}  // namespace pipe
+
+__global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_pipe_kernel(const uint16_t* __restrict__ X,
+                                                                     int64_t n_tokens, int d_in, int64_t ldx,
+                                                                     float* __restrict__ H, int n_t, int n_tiles,
+                                                                     int chunk) {
+    using namespace pipe;
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+
+    const int v = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+    if (v >= n_tiles) return;
+    int ti, tk;
+    tile_from_rank(v, n_t, ti, tk);
+    const bool diag = (ti == tk);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int i0 = ti * TS, k0 = tk * TS;
+
+    // per-thread load slots.  Loads are raw buffer loads: the descriptor is rebuilt per stage with the bytes
+    // left in X as its range, so token rows past the end read as zero without any branch; channels past d_in
+    // (tiles on the ragged edge) get an offset outside the range for the same effect.
+    constexpr uint32_t OOB = 0xFFFFFFF0u;
+    uint32_t off_a[NLOAD], off_b[NLOAD];   // byte offsets from the first token row of a stage
+    int lds_w[NLOAD];
+#pragma unroll
+    for (int n = 0; n < NLOAD; ++n) {
+        const int id = tid + GRAM_THREADS * n;
+        const int row = id / (TS / 8), col = (id % (TS / 8)) * 8;
+        off_a[n] = (i0 + col < d_in) ? uint32_t((int64_t(row) * ldx + i0 + col) * 2) : OOB;
+        off_b[n] = (k0 + col < d_in) ? uint32_t((int64_t(row) * ldx + k0 + col) * 2) : OOB;
+        lds_w[n] = row * PITCH + col;
+    }
+    const int64_t n_stage = (n_tokens + KT - 1) / KT;
+
+    auto gload = [&](Staged& g, int64_t st) __attribute__((always_inline)) {
+        const int64_t t0 = st * KT;
+        const char* base = reinterpret_cast<const char*>(X) + t0 * ldx * 2;
+        const int64_t left = (n_tokens - t0) * ldx * 2;
+        const int range = left > 0x7FFFFFFF ? 0x7FFFFFFF : int(left);
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, range, 0x00020000);
+#pragma unroll
+        for (int n = 0; n < NLOAD; ++n) {
+            g.a[n] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off_a[n], 0, 0);
+            g.b[n] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off_b[n], 0, 0);
+        }
+    };
+    auto lwrite = [&](const Staged& g, int buf) __attribute__((always_inline)) {
+        uint16_t* pa = lds + buf * STAGE;
+        uint16_t* pb = pa + PANEL;
+#pragma unroll
+        for (int n = 0; n < NLOAD; ++n) {
+            *reinterpret_cast<uint4v*>(pa + lds_w[n]) = g.a[n];
+            *reinterpret_cast<uint4v*>(pb + lds_w[n]) = g.b[n];
+        }
+    };
+    // LDS transpose-read addressing (see the generic kernel)
+    const int i16 = lane & 15, g16 = (lane >> 4) & 1, kb8 = lane >> 5;
+    const int frag_off = (kb8 * 8 + (i16 >> 2)) * PITCH + g16 * 16 + (i16 & 3) * 4;
+    auto lread = [&](Frags& f, int buf, int kb) __attribute__((always_inline)) {
+        const uint16_t* pa = lds + buf * STAGE;
+        const uint16_t* pb = pa + PANEL;   // a diagonal tile simply loads its panel twice
+        const uint16_t* fa = pa + frag_off + wr * 128 + kb * 16 * PITCH;
+        const uint16_t* fb = pb + frag_off + wc * 128 + kb * 16 * PITCH;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(fa + m * 32));
+            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(fa + m * 32 + 4 * PITCH));
+            f.a[m] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(fb + n * 32));
+            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(fb + n * 32 + 4 * PITCH));
+            f.b[n] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+    };
+
+    float16v acc[4][4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
+    auto mma = [&](const Frags& f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+            for (int n = 0; n < 4; ++n)
+                acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[m], f.b[n], acc[m][n], 0, 0, 0);
+    };
+
+    Staged G;        // global-load staging registers: written to LDS one iteration after the loads were issued
+    Frags Fc, FH;    // first-half fragments (current stage, then reloaded for the next one), second-half fragments
+    // prologue: stage 0 -> LDS, stage 1 -> registers, first-half fragments of stage 0
+    gload(G, 0);
+    lwrite(G, 0);
+    if (n_stage > 1) gload(G, 1);
+    __syncthreads();
+    lread(Fc, 0, 0);
+    int buf = 0;
+#pragma unroll 1
+    for (int64_t s = 0; s < n_stage; ++s) {
+        const int nbuf = (buf + 1 == NBUF) ? 0 : buf + 1;
+        const bool has1 = (s + 1 < n_stage), has2 = (s + 2 < n_stage);
+        if (has1) lwrite(G, nbuf);        // stage s+1, loaded during the previous iteration
+        __builtin_amdgcn_sched_barrier(0);
+        if (has2) gload(G, s + 2);        // same registers, in flight until the next iteration's write
+        lread(FH, buf, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(Fc);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        if (has1) lread(Fc, nbuf, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(FH);
+        __builtin_amdgcn_sched_barrier(0);
+        buf = nbuf;
+    }
+
+    // epilogue: H[i][k] += 2 acc, mirrored (see the generic kernel for the register layout)
+    const int lr = (lane >> 5) * 4, lc = lane & 31;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+            const int k = k0 + wc * 128 + n * 32 + lc;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ib = i0 + wr * 128 + m * 32 + q * 8 + lr;
+                if (k >= d_in || ib >= d_in) continue;
+                float nv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = ib + e;
+                    float* p = H + int64_t(i) * d_in + k;
+                    nv[e] = *p + 2.0f * acc[m][n][q * 4 + e];
+                    if (!diag || i <= k) *p = nv[e];
+                }
+                if (!diag) {
+                    const float4v o = {nv[0], nv[1], nv[2], nv[3]};
+                    *reinterpret_cast<float4v*>(H + int64_t(k) * d_in + ib) = o;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (ib + e < k) H[int64_t(k) * d_in + ib + e] = nv[e];
+                }
+            }
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------------
 // fp32 kernel: 128 x 128 tile, 4 waves in 2x2, each 2x2 tiles of v_mfma_f32_32x32x2_f32
 // -------------------------------------------------------------------------------------------
 constexpr int F32_TS = 128, F32_KT = 16, F32_PITCH = F32_TS + 4, F32_PANEL = F32_KT * F32_PITCH;
@@ -324,13 +501,35 @@ onecomp_status launch_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_
     return ONECOMP_OK;
 }
 
+
+
+onecomp_status launch_bf16_pipe(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
+                                hipStream_t stream) {
+    const int n_t = int(ceil_div(d_in, pipe::TS));
+    const int n_tiles = n_t * (n_t + 1) / 2;
+    const int chunk = int(ceil_div(n_tiles, 8));
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_pipe_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(pipe::LDS_BYTES)) != hipSuccess)
+            return ONECOMP_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(gram_bf16_pipe_kernel, dim3(chunk * 8), dim3(GRAM_THREADS), pipe::LDS_BYTES, stream,
+                       static_cast<const uint16_t*>(X), n_tokens, int(d_in), ldx, H, n_t, n_tiles, chunk);
+    ONECOMP_CHECK_LAUNCH();
+    return ONECOMP_OK;
+}
+
 }  // namespace
 
 onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
                                     hipStream_t stream) {
-    // 256-wide tiles once they give every CU at least a few tiles; 128-wide below that.
+    // 256-wide pipelined tiles once they give every CU at least a few tiles (and the 32-bit per-stage byte
+    // offsets cannot overflow); 128-wide tiles below that.
     const int64_t n256 = ceil_div(d_in, 256);
-    if (n256 * (n256 + 1) / 2 >= 512) return launch_bf16<4>(X, n_tokens, d_in, ldx, H, stream);
+    if (n256 * (n256 + 1) / 2 >= 512 && ldx * 64 < (int64_t(1) << 31))
+        return launch_bf16_pipe(X, n_tokens, d_in, ldx, H, stream);
     return launch_bf16<2>(X, n_tokens, d_in, ldx, H, stream);
 }
 
