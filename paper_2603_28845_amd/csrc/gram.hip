@@ -376,6 +376,184 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_pipe_kernel(const uint
 }
 
 // -------------------------------------------------------------------------------------------
+// bf16 kernel for large d_in, direct-to-LDS variant: 256 x 256 tile, global -> LDS without passing through
+// registers (buffer_load_dwordx4 ... lds), LDS ring of 4 stages, loads issued 3 stages ahead.
+//
+//   * One wave-wide 16-byte LDS load deposits lane l at  M0 + 16 l, i.e. 1 KB contiguous = two token rows
+//     of a 256-channel panel.  Rows therefore cannot be padded against bank conflicts; instead the 16-byte
+//     chunk c of token row r is stored at chunk position  c ^ ((r & 3) << 2):  the four token rows of one
+//     transpose read then fall into four different 64-byte bank groups.  The swizzle costs nothing on the
+//     global side because every lane supplies its own global address.
+//   * The loads are inline assembly, so the compiler neither sees the LDS write (and does not serialize
+//     later LDS reads behind it) nor counts them; the kernel waits explicitly with vmcnt(8 * stages
+//     still allowed in flight) before the barrier that publishes a stage.  Out-of-range lanes (token rows
+//     past the end, channels past d_in) deposit zeros: that is the raw-buffer range check.
+//   * iteration s:  loads of stage s+3;  LDS -> second-half fragments of stage s;  16 MFMAs (first half,
+//     fragments preloaded);  wait for stage s+1 + barrier;  LDS -> first-half fragments of stage s+1;
+//     16 MFMAs (second half).
+// -------------------------------------------------------------------------------------------
+namespace dma {
+constexpr int TS = 256, KT = 32, ROWB = 512, PANELB = KT * ROWB, STAGEB = 2 * PANELB, NBUF = 4, DIST = 3;
+constexpr size_t LDS_BYTES = size_t(NBUF) * STAGEB;
+constexpr uint32_t OOB = 0xFFFFFFF0u;
+// s_waitcnt immediates that wait on vmcnt only (expcnt and lgkmcnt fields at their no-wait maximum)
+constexpr int WAIT_VM0 = 0x0F70, WAIT_VM8 = 0x0F78, WAIT_VM16 = 0x4F70;
+
+__device__ __forceinline__ void lds_load16(uint32_t lds_byte_addr, uint32_t voffset, __amdgpu_buffer_rsrc_t rsrc) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_byte_addr), "v"(voffset), "s"(rsrc) : "memory", "m0");
+}
+}  // namespace dma
+
+__global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_dma_kernel(const uint16_t* __restrict__ X,
+                                                                    int64_t n_tokens, int d_in, int64_t ldx,
+                                                                    float* __restrict__ H, int n_t, int n_tiles,
+                                                                    int chunk) {
+    using namespace dma;
+    extern __shared__ __attribute__((aligned(1024))) char ldsb[];
+
+    const int v = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+    if (v >= n_tiles) return;
+    int ti, tk;
+    tile_from_rank(v, n_t, ti, tk);
+    const bool diag = (ti == tk);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 1, wc = wave & 1;
+    const int i0 = ti * TS, k0 = tk * TS;
+    const uint32_t lds0 = uint32_t(uintptr_t((ONECOMP_LDS char*)ldsb));
+
+    // this wave's four 1 KB loads per panel: load q covers token rows 2 j and 2 j + 1, j = 4 wave + q
+    uint32_t voff_a[4], voff_b[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int row = 2 * (4 * wave + q) + (lane >> 5);
+        const int c = (lane & 31) ^ ((row & 3) << 2);       // logical chunk stored at position lane & 31
+        voff_a[q] = (i0 + c * 8 < d_in) ? uint32_t((int64_t(row) * ldx + i0 + c * 8) * 2) : OOB;
+        voff_b[q] = (k0 + c * 8 < d_in) ? uint32_t((int64_t(row) * ldx + k0 + c * 8) * 2) : OOB;
+    }
+    const int64_t n_stage = (n_tokens + KT - 1) / KT;
+    auto gload = [&](int64_t st, int buf) __attribute__((always_inline)) {
+        const int64_t t0 = st * KT;
+        const char* base = reinterpret_cast<const char*>(X) + t0 * ldx * 2;
+        const int64_t left = (n_tokens - t0) * ldx * 2;
+        const int range = left > 0x7FFFFFFF ? 0x7FFFFFFF : int(left);
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, range, 0x00020000);
+        const uint32_t dst = lds0 + buf * STAGEB + wave * 4096;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            lds_load16(dst + q * 1024, voff_a[q], rsrc);
+            lds_load16(dst + PANELB + q * 1024, voff_b[q], rsrc);
+        }
+    };
+
+    // transpose-read addressing with the chunk swizzle (see the generic kernel for the lane roles)
+    const int i16 = lane & 15, g16 = (lane >> 4) & 1, kb8 = lane >> 5;
+    const int kq = i16 >> 2;                                        // token row within its group of 4
+    const int lo = (2 * g16 + ((i16 & 3) >> 1)) * 16 + (i16 & 1) * 8;  // byte offset inside the 64-byte group
+    const int fbase_a = (kb8 * 8 + kq) * ROWB + wr * 256 + lo;
+    const int fbase_b = PANELB + (kb8 * 8 + kq) * ROWB + wc * 256 + lo;
+    int xm[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) xm[m] = (m ^ kq) << 6;
+
+    struct Frags {
+        bf16x8 a[4], b[4];
+    };
+    auto lread = [&](Frags& f, int buf, int kb) __attribute__((always_inline)) {
+        const char* pa = ldsb + buf * STAGEB + kb * 16 * ROWB + fbase_a;
+        const char* pb = ldsb + buf * STAGEB + kb * 16 * ROWB + fbase_b;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            short4v l0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pa + xm[m]));
+            short4v h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pa + xm[m] + 4 * ROWB));
+            f.a[m] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(l0, h0, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+            short4v l0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pb + xm[n]));
+            short4v h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pb + xm[n] + 4 * ROWB));
+            f.b[n] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(l0, h0, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+    };
+
+    float16v acc[4][4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
+    auto mma = [&](const Frags& f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+            for (int n = 0; n < 4; ++n)
+                acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[m], f.b[n], acc[m][n], 0, 0, 0);
+    };
+
+    Frags Fc, FH;
+    // prologue: stages 0 .. 2 in flight, stage 0 landed, first-half fragments of stage 0
+    for (int st = 0; st < DIST && st < n_stage; ++st) gload(st, st);
+    __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+    __syncthreads();
+    lread(Fc, 0, 0);
+    int buf = 0;
+#pragma unroll 1
+    for (int64_t s = 0; s < n_stage; ++s) {
+        const int nbuf = (buf + 1) & (NBUF - 1);
+        const bool has1 = (s + 1 < n_stage);
+        if (s + DIST < n_stage) gload(s + DIST, (buf + DIST) & (NBUF - 1));
+        lread(FH, buf, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(Fc);
+        __builtin_amdgcn_sched_barrier(0);
+        // stage s+1 must have landed; loads of stages s+2 and s+3 (8 per wave each) may stay in flight
+        const int64_t ahead = n_stage - 2 - s;   // stages issued beyond s+1
+        if (ahead >= 2) __builtin_amdgcn_s_waitcnt(WAIT_VM16);
+        else if (ahead == 1) __builtin_amdgcn_s_waitcnt(WAIT_VM8);
+        else __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+        __syncthreads();
+        if (has1) lread(Fc, nbuf, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(FH);
+        __builtin_amdgcn_sched_barrier(0);
+        buf = nbuf;
+    }
+
+    // epilogue: H[i][k] += 2 acc, mirrored (see the generic kernel for the register layout)
+    const int lr = (lane >> 5) * 4, lc = lane & 31;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+            const int k = k0 + wc * 128 + n * 32 + lc;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ib = i0 + wr * 128 + m * 32 + q * 8 + lr;
+                if (k >= d_in || ib >= d_in) continue;
+                float nv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = ib + e;
+                    float* p = H + int64_t(i) * d_in + k;
+                    nv[e] = *p + 2.0f * acc[m][n][q * 4 + e];
+                    if (!diag || i <= k) *p = nv[e];
+                }
+                if (!diag) {
+                    const float4v o = {nv[0], nv[1], nv[2], nv[3]};
+                    *reinterpret_cast<float4v*>(H + int64_t(k) * d_in + ib) = o;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (ib + e < k) H[int64_t(k) * d_in + ib + e] = nv[e];
+                }
+            }
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------------
 // fp32 kernel: 128 x 128 tile, 4 waves in 2x2, each 2x2 tiles of v_mfma_f32_32x32x2_f32
 // -------------------------------------------------------------------------------------------
 constexpr int F32_TS = 128, F32_KT = 16, F32_PITCH = F32_TS + 4, F32_PANEL = F32_KT * F32_PITCH;
@@ -521,6 +699,24 @@ onecomp_status launch_bf16_pipe(const void* X, int64_t n_tokens, int64_t d_in, i
     return ONECOMP_OK;
 }
 
+onecomp_status launch_bf16_dma(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
+                               hipStream_t stream) {
+    const int n_t = int(ceil_div(d_in, dma::TS));
+    const int n_tiles = n_t * (n_t + 1) / 2;
+    const int chunk = int(ceil_div(n_tiles, 8));
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_dma_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(dma::LDS_BYTES)) != hipSuccess)
+            return ONECOMP_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(gram_bf16_dma_kernel, dim3(chunk * 8), dim3(GRAM_THREADS), dma::LDS_BYTES, stream,
+                       static_cast<const uint16_t*>(X), n_tokens, int(d_in), ldx, H, n_t, n_tiles, chunk);
+    ONECOMP_CHECK_LAUNCH();
+    return ONECOMP_OK;
+}
+
 }  // namespace
 
 onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
@@ -529,7 +725,7 @@ onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_i
     // offsets cannot overflow); 128-wide tiles below that.
     const int64_t n256 = ceil_div(d_in, 256);
     if (n256 * (n256 + 1) / 2 >= 512 && ldx * 64 < (int64_t(1) << 31))
-        return launch_bf16_pipe(X, n_tokens, d_in, ldx, H, stream);
+        return launch_bf16_dma(X, n_tokens, d_in, ldx, H, stream);
     return launch_bf16<2>(X, n_tokens, d_in, ldx, H, stream);
 }
 
