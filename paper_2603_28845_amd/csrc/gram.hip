@@ -460,21 +460,24 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_dma_kernel(const uint1
     struct Frags {
         bf16x8 a[4], b[4];
     };
-    auto lread = [&](Frags& f, int buf, int kb) __attribute__((always_inline)) {
-        const char* pa = ldsb + buf * STAGEB + kb * 16 * ROWB + fbase_a;
-        const char* pb = ldsb + buf * STAGEB + kb * 16 * ROWB + fbase_b;
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            short4v l0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pa + xm[m]));
-            short4v h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pa + xm[m] + 4 * ROWB));
-            f.a[m] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(l0, h0, 0, 1, 2, 3, 4, 5, 6, 7));
-        }
-#pragma unroll
-        for (int n = 0; n < 4; ++n) {
-            short4v l0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pb + xm[n]));
-            short4v h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pb + xm[n] + 4 * ROWB));
-            f.b[n] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(l0, h0, 0, 1, 2, 3, 4, 5, 6, 7));
-        }
+    // one operand fragment = two transpose reads (tokens 0..3 and 4..7 of this lane's half of the 16-token block)
+    auto rd_a = [&](Frags& f, int m, int buf, int kb) __attribute__((always_inline)) {
+        const char* pa = ldsb + buf * STAGEB + kb * 16 * ROWB + fbase_a + xm[m];
+        short4v l0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pa));
+        short4v h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pa + 4 * ROWB));
+        f.a[m] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(l0, h0, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    auto rd_b = [&](Frags& f, int n, int buf, int kb) __attribute__((always_inline)) {
+        const char* pb = ldsb + buf * STAGEB + kb * 16 * ROWB + fbase_b + xm[n];
+        short4v l0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pb));
+        short4v h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pb + 4 * ROWB));
+        f.b[n] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(l0, h0, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // fragment number r in the order the MFMAs need them: a0 b0 b1 b2 b3 a1 a2 a3
+    auto rd = [&](Frags& f, int r, int buf, int kb) __attribute__((always_inline)) {
+        if (r == 0) rd_a(f, 0, buf, kb);
+        else if (r <= 4) rd_b(f, r - 1, buf, kb);
+        else rd_a(f, r - 4, buf, kb);
     };
 
     float16v acc[4][4];
@@ -484,40 +487,54 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_dma_kernel(const uint1
         for (int n = 0; n < 4; ++n)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
-    auto mma = [&](const Frags& f) __attribute__((always_inline)) {
-#pragma unroll
-        for (int m = 0; m < 4; ++m)
-#pragma unroll
-            for (int n = 0; n < 4; ++n)
-                acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[m], f.b[n], acc[m][n], 0, 0, 0);
-    };
 
     Frags Fc, FH;
     // prologue: stages 0 .. 2 in flight, stage 0 landed, first-half fragments of stage 0
     for (int st = 0; st < DIST && st < n_stage; ++st) gload(st, st);
     __builtin_amdgcn_s_waitcnt(WAIT_VM0);
     __syncthreads();
-    lread(Fc, 0, 0);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) rd(Fc, r, 0, 0);
     int buf = 0;
 #pragma unroll 1
     for (int64_t s = 0; s < n_stage; ++s) {
         const int nbuf = (buf + 1) & (NBUF - 1);
-        const bool has1 = (s + 1 < n_stage);
-        if (s + DIST < n_stage) gload(s + DIST, (buf + DIST) & (NBUF - 1));
-        lread(FH, buf, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(Fc);
-        __builtin_amdgcn_sched_barrier(0);
+        const bool has1 = (s + 1 < n_stage), has3 = (s + DIST < n_stage);
+        // loads of stage s+3: descriptor once, the eight 1 KB loads are spread between the MFMAs below
+        const int64_t t3 = (s + DIST) * KT;
+        const int64_t left = (n_tokens - t3) * ldx * 2;
+        const int range = left > 0x7FFFFFFF ? 0x7FFFFFFF : (left < 0 ? 0 : int(left));
+        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char*>(reinterpret_cast<const char*>(X) + (has3 ? t3 : 0) * ldx * 2), 0, has3 ? range : 0, 0x00020000);
+        const uint32_t dst = lds0 + ((buf + DIST) & (NBUF - 1)) * STAGEB + wave * 4096;
+        // An MFMA occupies the matrix pipe for 32 cycles but issues in 4: the other instructions of the
+        // iteration are placed one or two at a time behind each MFMA so that the pipe never waits for them.
+        // First half: MFMAs on the preloaded fragments Fc; second-half fragments FH and the DMA loads ride along.
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            acc[i / 4][i % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Fc.a[i / 4], Fc.b[i % 4], acc[i / 4][i % 4], 0, 0, 0);
+            if ((i & 1) == 0) {
+                rd(FH, i / 2, buf, 1);
+            } else if (has3) {
+                const int q = i / 2;    // 0..7: loads 0..3 -> panel A, 4..7 -> panel B
+                if (q < 4) lds_load16(dst + q * 1024, voff_a[q], rsrc);
+                else lds_load16(dst + PANELB + (q - 4) * 1024, voff_b[q - 4], rsrc);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
         // stage s+1 must have landed; loads of stages s+2 and s+3 (8 per wave each) may stay in flight
         const int64_t ahead = n_stage - 2 - s;   // stages issued beyond s+1
         if (ahead >= 2) __builtin_amdgcn_s_waitcnt(WAIT_VM16);
         else if (ahead == 1) __builtin_amdgcn_s_waitcnt(WAIT_VM8);
         else __builtin_amdgcn_s_waitcnt(WAIT_VM0);
         __syncthreads();
-        if (has1) lread(Fc, nbuf, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(FH);
-        __builtin_amdgcn_sched_barrier(0);
+        // second half: MFMAs on FH; first-half fragments of stage s+1 ride along
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            acc[i / 4][i % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FH.a[i / 4], FH.b[i % 4], acc[i / 4][i % 4], 0, 0, 0);
+            if ((i & 1) == 0 && has1) rd(Fc, i / 2, nbuf, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         buf = nbuf;
     }
 
