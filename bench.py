@@ -187,7 +187,8 @@ def main():
     algo_flops = float(tpc) * d_in * (d_in + 1)
     gram_tflops = algo_flops / (gram_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": "gram_bf16_kernel" if cfg.dtype == torch.bfloat16 else "gram_f32_kernel",
+        "kernel": ("gram_bf16_dma_kernel" if d_in >= 8192 else "gram_bf16_kernel<2>") if cfg.dtype == torch.bfloat16
+                  else "gram_f32_kernel",
         "bound": "mfma", "achieved": gram_tflops, "peak": PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3,
         "unit": "TFLOP/s", "frac": gram_tflops / (PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3),
         "traffic": None,
