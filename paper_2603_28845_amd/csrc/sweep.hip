@@ -4,7 +4,8 @@
 // Per output row, for sweep positions j = 0 .. d_in-1:
 //   group start:  s = (max - min) / (2^b - 1) of the current values of the group (1 if max == min),
 //                 z = clamp(rne(-min / s), 0, 2^b - 1)
-//   q = clamp(rne(w_j / s) + z, 0, 2^b - 1),  w^ = s (q - z),  e = (w_j - w^) / U_jj,
+//   q = clamp(rne(w_j / s) + z, 0, 2^b - 1),  w^ = s (q - z),  e = (w_j - w^) / U_jj
+//   (w_j / s and the division by U_jj are multiplications by correctly rounded reciprocals),
 //   w_k -= e U_jk for k > j.
 //
 // gfx950 schedule (lazy batch of B = 128 columns, right-looking):
@@ -119,10 +120,11 @@ __global__ __launch_bounds__(BLOCK_THREADS) void block_kernel(BlockArgs a) {
     const int row = min(r0 + l, a.d_out - 1);
     const bool row_ok = (r0 + l) < a.d_out;
     const float qmax = a.qmax;
-    float s = 1.f, z = 0.f, loss = 0.f;
+    float s = 1.f, rs = 1.f, z = 0.f, loss = 0.f;
     if (wave == 0 && (j0 % a.G) != 0) {  // block continues a group wider than the block
         s = a.scales[int64_t(row) * a.n_g + j0 / a.G];
         z = a.zeros[int64_t(row) * a.n_g + j0 / a.G];
+        rs = 1.0f / s;
     }
 
 #pragma unroll 1
@@ -130,61 +132,84 @@ __global__ __launch_bounds__(BLOCK_THREADS) void block_kernel(BlockArgs a) {
         if (wave == 0) {
             float w[IB];
             static_for<0, IB>([&](auto cc) { w[decltype(cc)::value] = sW[l * SP + jb + decltype(cc)::value]; });
+            // Row j of the inner block's U triangle (and 1 / U_jj) is read one step ahead of its use: the reads
+            // do not depend on the sequential chain, so their LDS latency hides behind the previous step.
+            float4v ua[IB / 4], ub[IB / 4];
+            float rdc = sRd[jb], rdn = 0.f;
+            auto load_row = [&](float4v(&dst)[IB / 4], auto jc) __attribute__((always_inline)) {
+                constexpr int j = decltype(jc)::value;
+                static_for<(j + 1) / 4, IB / 4>([&](auto gc) {
+                    constexpr int g = decltype(gc)::value;
+                    dst[g] = *reinterpret_cast<const float4v*>(sU + (jb + j) * SB + jb + 4 * g);
+                });
+            };
+            load_row(ua, std::integral_constant<int, 0>{});
             static_for<0, IB>([&](auto jc) {
                 constexpr int j = decltype(jc)::value;
-                if constexpr (j % GB == 0) {
-                    const int col = j0 + jb + j;
-                    bool fresh;
-                    float mn, mx;
-                    if constexpr (GB == 16) {
-                        fresh = true;
-                        mn = w[j]; mx = w[j];
-                        static_for<j + 1, j + 16>([&](auto cc) {
-                            mn = fminf(mn, w[decltype(cc)::value]);
-                            mx = fmaxf(mx, w[decltype(cc)::value]);
-                        });
-                    } else {
-                        fresh = (col % a.G) == 0;
-                        if (fresh) {
-                            // the group's columns inside this block are current in LDS; a group wider than
-                            // the block continues in the working copy (already updated by earlier blocks)
-                            const int in_blk = min(a.G, SB - jb);
-                            mn = mx = sW[l * SP + jb];
-                            for (int c = 1; c < in_blk; ++c) {
-                                const float v = sW[l * SP + jb + c];
-                                mn = fminf(mn, v); mx = fmaxf(mx, v);
+                auto step = [&](float4v(&cur)[IB / 4], float4v(&nxt)[IB / 4]) __attribute__((always_inline)) {
+                    if constexpr (j + 1 < IB) {
+                        load_row(nxt, std::integral_constant<int, j + 1>{});
+                        rdn = sRd[jb + j + 1];
+                    }
+                    if constexpr (j % GB == 0) {
+                        const int col = j0 + jb + j;
+                        bool fresh;
+                        float mn, mx;
+                        if constexpr (GB == 16) {
+                            fresh = true;
+                            mn = w[j]; mx = w[j];
+                            static_for<j + 1, j + 16>([&](auto cc) {
+                                mn = fminf(mn, w[decltype(cc)::value]);
+                                mx = fmaxf(mx, w[decltype(cc)::value]);
+                            });
+                        } else {
+                            fresh = (col % a.G) == 0;
+                            if (fresh) {
+                                // the group's columns inside this block are current in LDS; a group wider than
+                                // the block continues in the working copy (already updated by earlier blocks)
+                                const int in_blk = min(a.G, SB - jb);
+                                mn = mx = sW[l * SP + jb];
+                                for (int c = 1; c < in_blk; ++c) {
+                                    const float v = sW[l * SP + jb + c];
+                                    mn = fminf(mn, v); mx = fmaxf(mx, v);
+                                }
+                                const float* wr = a.Wf + int64_t(row) * d_in + j0;
+                                for (int c = SB; c < a.G; ++c) { const float v = wr[c]; mn = fminf(mn, v); mx = fmaxf(mx, v); }
                             }
-                            const float* wr = a.Wf + int64_t(row) * d_in + j0;
-                            for (int c = SB; c < a.G; ++c) { const float v = wr[c]; mn = fminf(mn, v); mx = fmaxf(mx, v); }
+                        }
+                        if (fresh) {
+                            s = (mx - mn) / qmax;
+                            if (s == 0.f) s = 1.f;
+                            rs = 1.0f / s;
+                            z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
+                            if (row_ok) {
+                                a.scales[int64_t(row) * a.n_g + col / a.G] = s;
+                                a.zeros[int64_t(row) * a.n_g + col / a.G] = z;
+                            }
                         }
                     }
-                    if (fresh) {
-                        s = (mx - mn) / qmax;
-                        if (s == 0.f) s = 1.f;
-                        z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
-                        if (row_ok) {
-                            a.scales[int64_t(row) * a.n_g + col / a.G] = s;
-                            a.zeros[int64_t(row) * a.n_g + col / a.G] = z;
-                        }
-                    }
-                }
-                const float wj = w[j];
-                const float q = fminf(fmaxf(rintf(wj / s) + z, 0.f), qmax);
-                const float wh = s * (q - z);
-                const float e = (wj - wh) * sRd[jb + j];
-                loss += e * e;
-                sE[l * SP + jb + j] = e;
-                sW[l * SP + jb + j] = wh;
-                sQ[l * QP + jb + j] = uint8_t(q);
-                // feedback inside the inner block: w_k -= e U_jk, j < k < 32 (U row read wave-uniform)
-                static_for<(j + 1) / 4, IB / 4>([&](auto c4c) {
-                    constexpr int c4 = decltype(c4c)::value * 4;
-                    const float4v u = *reinterpret_cast<const float4v*>(sU + (jb + j) * SB + jb + c4);
-                    if constexpr (c4 + 0 > j) w[c4 + 0] = __builtin_fmaf(-e, u[0], w[c4 + 0]);
-                    if constexpr (c4 + 1 > j) w[c4 + 1] = __builtin_fmaf(-e, u[1], w[c4 + 1]);
-                    if constexpr (c4 + 2 > j) w[c4 + 2] = __builtin_fmaf(-e, u[2], w[c4 + 2]);
-                    if constexpr (c4 + 3 > j) w[c4 + 3] = __builtin_fmaf(-e, u[3], w[c4 + 3]);
-                });
+                    const float wj = w[j];
+                    const float q = fminf(fmaxf(rintf(wj * rs) + z, 0.f), qmax);   // w / s as w * fl(1 / s)
+                    const float wh = s * (q - z);
+                    const float e = (wj - wh) * rdc;
+                    // feedback inside the inner block: w_k -= e U_jk, j < k < 32; the next column first, it
+                    // heads the next step's dependency chain
+                    static_for<(j + 1) / 4, IB / 4>([&](auto gc) {
+                        constexpr int g = decltype(gc)::value;
+                        constexpr int c4 = 4 * g;
+                        if constexpr (c4 + 0 > j) w[c4 + 0] = __builtin_fmaf(-e, cur[g][0], w[c4 + 0]);
+                        if constexpr (c4 + 1 > j) w[c4 + 1] = __builtin_fmaf(-e, cur[g][1], w[c4 + 1]);
+                        if constexpr (c4 + 2 > j) w[c4 + 2] = __builtin_fmaf(-e, cur[g][2], w[c4 + 2]);
+                        if constexpr (c4 + 3 > j) w[c4 + 3] = __builtin_fmaf(-e, cur[g][3], w[c4 + 3]);
+                    });
+                    loss += e * e;
+                    sE[l * SP + jb + j] = e;
+                    sW[l * SP + jb + j] = wh;
+                    sQ[l * QP + jb + j] = uint8_t(q);
+                    rdc = rdn;
+                };
+                if constexpr (j % 2 == 0) step(ua, ub);
+                else step(ub, ua);
             });
         }
         __syncthreads();
