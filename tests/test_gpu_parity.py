@@ -261,3 +261,40 @@ def test_end_to_end_c1():
     # the loss the library reports is the layer objective for the damped Hessian
     direct = oc.layer_loss(to_f64(W), to_f64(out["W_hat"]), f["Hd"])
     assert abs(loss - direct) <= 1e-3 * direct
+
+
+# ------------------------------------------------------------- full size, sampled oracle ---
+def test_full_size_down_projection_sampled():
+    """The 4096 x 14336 layer in the launch configuration bench.py times (bf16, 4-bit, group 128):
+    Gram on sampled tiles, factor against the oracle's U for the same H, sweep on sampled rows with tie
+    replay.  The calibration set is cut to 32768 tokens (still more than 2 d_in, so H has full rank as in
+    the real workload) so that the float64 oracle finishes in about half a minute."""
+    cfg = synth.scaled(synth.CONFIGS["c3b"], n_tokens=32768)
+    d_out, d_in = cfg.d_out, cfg.d_in
+    _announce(f"full size {d_out}x{d_in}: gram ({cfg.n_tokens} tokens)")
+    X = synth.make_activations(cfg, DEV)
+    W = synth.make_weight(cfg, DEV)
+    H = _gpu_gram(X)
+    Xd = to_f64(X)
+    Ho = oc.hessian_accumulate(Xd)
+    Hn = H.cpu().numpy()
+    assert np.array_equal(Hn, Hn.T)
+    assert rel_fro(Hn.astype(np.float64), Ho) <= 1e-4
+    del Xd
+    _announce("full size: oracle factor")
+    H32 = Ho.astype(np.float32)
+    del Ho
+    f = oc.hessian_factor(H32.astype(np.float64), cfg.damp)
+    assert f["info"] == 0
+    _announce("full size: GPU factor")
+    U, _, info = og.onecomp_hessian_factor(torch.from_numpy(H32).to(DEV), cfg.damp)
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0
+    err = rel_fro(U.cpu().numpy().astype(np.float64), f["U"])
+    _announce(f"   U rel. Frobenius error {err:.3e}")
+    assert err <= 1e-6
+    del U
+    _announce("full size: sweep, 48 sampled rows")
+    U32 = torch.from_numpy(f["U"].astype(np.float32)).to(DEV)
+    rows = np.sort(np.random.default_rng(7).choice(d_out, size=48, replace=False))
+    _check_sweep(W, U32, cfg.bits, cfg.group_size, rows=rows)
