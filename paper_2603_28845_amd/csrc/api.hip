@@ -52,7 +52,7 @@ ONECOMP_API onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w
                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
     if (!W || !U || !Q_codes || !scales || !zeros || !loss) return ONECOMP_ERR_INVALID_ARG;
-    if (d_out <= 0 || d_in <= 0 || d_out > (1 << 24) || d_in > (1 << 20)) return ONECOMP_ERR_INVALID_ARG;
+    if (d_out <= 0 || d_in <= 0 || d_out > (1 << 24) || d_in > 65535) return ONECOMP_ERR_INVALID_ARG;
     if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return ONECOMP_ERR_UNSUPPORTED;
     if (block_size != 128) return ONECOMP_ERR_UNSUPPORTED;
     if (group_size <= 0 || d_in % block_size != 0 || d_in % group_size != 0) return ONECOMP_ERR_INVALID_ARG;
