@@ -27,6 +27,21 @@ typedef double double4v __attribute__((ext_vector_type(4)));
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// ---- direct global -> LDS loads ---------------------------------------------------------------
+// One wave-wide 16-byte load: lane l's 16 bytes, read at buffer offset voffset, land at LDS byte address
+// lds_byte_addr + 16 l.  Lanes whose offset is outside the descriptor's range deposit zeros.  Inline assembly, so
+// the compiler neither counts the load nor orders LDS reads behind it: the caller waits with
+// __builtin_amdgcn_s_waitcnt(wait_vmcnt(n)) and a workgroup barrier before reading the data.
+__device__ __forceinline__ void lds_load16(uint32_t lds_byte_addr, uint32_t voffset, __amdgpu_buffer_rsrc_t rsrc) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_byte_addr), "v"(voffset), "s"(rsrc) : "memory", "m0");
+}
+// a buffer offset that is out of range for every descriptor used here
+constexpr uint32_t LDS_DMA_OOB = 0xFFFFFFF0u;
+// s_waitcnt immediate that waits until at most n (< 64) vector memory loads are outstanding and for nothing else
+// (expcnt and lgkmcnt fields at their no-wait maximum; vmcnt is split over bits 3:0 and 15:14)
+constexpr int wait_vmcnt(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
+
 // ---- entry points implemented in the kernel files -------------------------------------------
 onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx,
                                     float* H, hipStream_t stream);

@@ -395,14 +395,8 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_pipe_kernel(const uint
 namespace dma {
 constexpr int TS = 256, KT = 32, ROWB = 512, PANELB = KT * ROWB, STAGEB = 2 * PANELB, NBUF = 4, DIST = 3;
 constexpr size_t LDS_BYTES = size_t(NBUF) * STAGEB;
-constexpr uint32_t OOB = 0xFFFFFFF0u;
-// s_waitcnt immediates that wait on vmcnt only (expcnt and lgkmcnt fields at their no-wait maximum)
-constexpr int WAIT_VM0 = 0x0F70, WAIT_VM8 = 0x0F78, WAIT_VM16 = 0x4F70;
-
-__device__ __forceinline__ void lds_load16(uint32_t lds_byte_addr, uint32_t voffset, __amdgpu_buffer_rsrc_t rsrc) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_byte_addr), "v"(voffset), "s"(rsrc) : "memory", "m0");
-}
+constexpr uint32_t OOB = LDS_DMA_OOB;
+constexpr int WAIT_VM0 = wait_vmcnt(0), WAIT_VM8 = wait_vmcnt(8), WAIT_VM16 = wait_vmcnt(16);
 }  // namespace dma
 
 __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_dma_kernel(const uint16_t* __restrict__ X,

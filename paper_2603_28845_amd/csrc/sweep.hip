@@ -104,10 +104,10 @@ struct BlockArgs {
     float* scales;          // [d_out x n_g]
     float* zeros;
     float* W_hat;           // or nullptr
-    uint16_t* Eh;           // [d_out x SBIG] -(w - w^) * f_d split into fp16 hi + lo, columns e_col .. e_col+127 written
-    uint16_t* El;
+    uint16_t* Dh;           // [SBIG x ldD] transposed residuals -(w - w^) * f_d split into fp16 hi + lo;
+    uint16_t* Dl;           // rows e_col .. e_col+127 are written
     const Scalars* sc;
-    int e_col;
+    int e_col, ldD;
     float* rowloss;         // [d_out]
     int d_out, d_in, j0, G, n_g;
     float qmax;
@@ -270,26 +270,35 @@ __global__ __launch_bounds__(BLOCK_THREADS) void block_kernel(BlockArgs a) {
     }
     if (wave == 0 && row_ok) a.rowloss[row] += loss;
 
-    // tiles out: E (dense), W^ and codes (original column order)
+    // residual w - w^ = e U_jj, negated, scaled by a power of two and split into fp16 hi + lo
+    // (hi = rne(x), lo = rne(x - hi): 22 significant bits); saturated far above anything a sweep produces.
+    // Written transposed (column-major: the trailing GEMM wants both operands k-major), 8 rows = 16 bytes per
+    // store; rows past d_out hold copies of the last row and are never used.
+    {
+        const float f_d = a.sc->f_d;
+        for (int it = tid; it < SB * (ROWS / 8); it += BLOCK_THREADS) {
+            const int c = it / (ROWS / 8), r8 = (it % (ROWS / 8)) * 8;
+            const float ujj = sU[c * SB + c] * f_d;
+            short8v dh, dl;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float x = -sE[(r8 + e) * SP + c] * ujj;
+                x = fminf(fmaxf(x, -60000.f), 60000.f);
+                const _Float16 h = (_Float16)x;
+                const _Float16 lo = (_Float16)(x - (float)h);
+                dh[e] = __builtin_bit_cast(short, h);
+                dl[e] = __builtin_bit_cast(short, lo);
+            }
+            const int64_t off = int64_t(a.e_col + c) * a.ldD + r0 + r8;
+            *reinterpret_cast<short8v*>(a.Dh + off) = dh;
+            *reinterpret_cast<short8v*>(a.Dl + off) = dl;
+        }
+    }
+    // tiles out: W^ and codes (original column order)
     for (int it = wave; it < ROWS / 2; it += 4) {
         const int rr = it * 2 + (l >> 5), c4 = (l & 31) * 4;
         const int gr = r0 + rr;
         if (gr >= a.d_out) continue;
-        // residual w - w^ = e U_jj, negated, scaled by a power of two and split into fp16 hi + lo
-        // (hi = rne(x), lo = rne(x - hi): 22 significant bits); saturated far above anything a sweep produces
-        short4v eh, el;
-        const float f_d = a.sc->f_d;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float x = -sE[rr * SP + c4 + e] * sU[(c4 + e) * SB + c4 + e] * f_d;
-            x = fminf(fmaxf(x, -60000.f), 60000.f);
-            const _Float16 h = (_Float16)x;
-            const _Float16 lo = (_Float16)(x - (float)h);
-            eh[e] = __builtin_bit_cast(short, h);
-            el[e] = __builtin_bit_cast(short, lo);
-        }
-        *reinterpret_cast<short4v*>(a.Eh + int64_t(gr) * SBIG + a.e_col + c4) = eh;
-        *reinterpret_cast<short4v*>(a.El + int64_t(gr) * SBIG + a.e_col + c4) = el;
         if (!a.perm) {
             if (a.W_hat) {
                 float4v h;
@@ -364,77 +373,144 @@ __global__ __launch_bounds__(256) void split_kernel(const float* __restrict__ U,
 
 // ------------------------------------------------------------------------------------------
 // trailing update:  Wf[:, c0 .. c1) += f_inv * D[:, ek .. ek+K) * Un[u0 .. u0+K, c0 .. c1)
-// with D = -(w - w^) f_d and Un = U_jk / U_jj f_u as written by the block kernel and split_kernel.
+// with D = -(w - w^) f_d (stored transposed, Dt[k][row], by the block kernel) and Un = U_jk / U_jj f_u
+// (split_kernel).
 //
 // fp32 accuracy from fp16 MFMAs: both operands are split x = hi + lo (fp16 each, |lo| <= 2^-11 |hi|) and
 // three products are accumulated in fp32, hi*hi + hi*lo + lo*hi; the dropped lo*lo term and the rounding
 // of lo are ~2^-22 relative to each product, i.e. the level of fp32 rounding itself.
-// 128 x 256 tile per workgroup, 4 waves in 2 x 2 (64 x 128 each: 2 x 4 tiles of v_mfma_f32_32x32x16_f16),
-// the W tile is loaded (scaled) into the accumulators and written back once.  D is k-contiguous (plain 16-byte LDS
-// reads); U is k-major, its fragments come from LDS transpose reads.  LDS double-buffered, K step 32.
+//
+// 128 x 256 tile per workgroup, 4 waves in 2 x 2 (64 x 128 each: 2 x 4 tiles of v_mfma_f32_32x32x16_f16, three
+// products each), two workgroups per CU so that one workgroup's read and write of its W tile (the update is
+// close to the HBM / MFMA ridge: 384 flop per byte of W at K = 512) overlaps the other's inner loop.
+// Both operands are k-major, their fragments come from LDS transpose reads.  Operand tiles go global -> LDS
+// directly (lds_load16) in steps of 16 k: four panels (Dt hi, Dt lo, Un hi, Un lo) of 16 rows, 24 KB, in a
+// ring of three slots.  16-byte chunk c of panel row r sits at chunk position c ^ ((r & 3) << 2), which spreads
+// the four rows of a transpose read over four 64-byte bank groups.
+// Half-iteration h:  24 MFMAs on the fragments of k-step h (registers);  LDS -> fragments of k-step h+1;
+// loads of k-step h+3 into the slot k-step h was read from;  wait for k-step h+2 + barrier.
+// Tiles are ranked so that each XCD (blockIdx % 8) owns a contiguous run, m fastest inside bands of 8 row tiles:
+// the workgroups resident on one XCD share their Dt and Un panels through its L2.
 // ------------------------------------------------------------------------------------------
 namespace tg {
-constexpr int TM = 128, TN = 256, TK = 32;
-constexpr int PA = TK + 8;            // bf16 elements per A row in LDS (80 B: 16 rows hit 16 distinct 16-byte bank groups)
-constexpr int PB = TN + 32;           // bf16 elements per B row in LDS (+64 B, as in the Gram kernels)
-constexpr int A_ELEMS = TM * PA, B_ELEMS = TK * PB;
-constexpr int STAGE = 2 * A_ELEMS + 2 * B_ELEMS;   // hi and lo of both operands
-constexpr size_t LDS_BYTES = size_t(2) * STAGE * 2;
+constexpr int TM = 128, TN = 256, KT = 16;
+constexpr int A_ROWB = TM * 2, B_ROWB = TN * 2;                     // bytes per panel row
+constexpr int A_PANELB = KT * A_ROWB, B_PANELB = KT * B_ROWB;       // 4 KB, 8 KB
+constexpr int OFF_AH = 0, OFF_AL = A_PANELB, OFF_BH = 2 * A_PANELB, OFF_BL = 2 * A_PANELB + B_PANELB;
+constexpr int STAGEB = 2 * A_PANELB + 2 * B_PANELB;                 // 24 KB
+constexpr int NBUF = 3;
+constexpr size_t LDS_BYTES = size_t(NBUF) * STAGEB;                 // 72 KB: two workgroups per CU
+constexpr int BAND = 8;                                             // row tiles per band of the tile order
 }  // namespace tg
 
-__global__ __launch_bounds__(256) void trailing_kernel(float* __restrict__ Wf, const uint16_t* __restrict__ Eh,
-                                                       const uint16_t* __restrict__ El,
-                                                       const uint16_t* __restrict__ Uh,
-                                                       const uint16_t* __restrict__ Ul,
-                                                       const Scalars* __restrict__ sc, int d_out, int64_t d_in,
-                                                       int ek, int K, int u0, int c0, int c1) {
+struct TrailArgs {
+    float* Wf;
+    const uint16_t *Dh, *Dl;   // [SBIG x ldD] fp16 bits
+    const uint16_t *Uh, *Ul;   // [d_in x d_in] fp16 bits
+    const Scalars* sc;
+    int d_out, ldD, d_in;
+    int ek, K, u0, c0, c1;     // K % 32 == 0, c0 % 8 == 0, c1 % 8 == 0
+    int n_mt, n_nt, chunk;
+};
+
+__global__ __launch_bounds__(256, 2) void trailing_kernel(TrailArgs a) {
     using namespace tg;
-    extern __shared__ __attribute__((aligned(16))) uint16_t tl[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    extern __shared__ __attribute__((aligned(1024))) char tl[];
+
+    const int n_tiles = a.n_mt * a.n_nt;
+    const int v = (blockIdx.x & 7) * a.chunk + (blockIdx.x >> 3);
+    if (v >= n_tiles) return;
+    const int band = min(v / (BAND * a.n_nt), (a.n_mt - 1) / BAND);
+    const int rem = v - band * BAND * a.n_nt;
+    const int mb = min(BAND, a.n_mt - BAND * band);
+    const int m0 = (band * BAND + rem % mb) * TM;
+    const int n0 = a.c0 + (rem / mb) * TN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wr = wave >> 1, wc = wave & 1;
-    const int m0 = blockIdx.y * TM;
-    const int n0 = c0 + blockIdx.x * TN;
+    const int d_out = a.d_out, c1 = a.c1;
+    const int64_t d_in = a.d_in;
+    const uint32_t lds0 = uint32_t(uintptr_t((ONECOMP_LDS char*)tl));
 
-    // global -> register staging: A tile 128 rows x 32 k (4 chunks of 16 B per row), B tile 32 k x 256 n (32 chunks per row)
-    int a_row[2], a_kc[2], b_kr[4], b_nc[4];
+    // this wave's six 1 KB loads per k-step: Dt panels rows 4 wave .. 4 wave + 3 (one load each), Un panels the
+    // same rows (two loads of two rows each)
+    uint32_t voff_a, voff_b[2];
+    {
+        const int row = 4 * wave + (lane >> 4);
+        const int c = (lane & 15) ^ ((row & 3) << 2);
+        voff_a = (m0 + c * 8 < a.ldD) ? uint32_t((row * a.ldD + m0 + c * 8) * 2) : LDS_DMA_OOB;
+    }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) { const int id = tid + 256 * i; a_row[i] = id >> 2; a_kc[i] = (id & 3) * 8; }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { const int id = tid + 256 * i; b_kr[i] = id >> 5; b_nc[i] = (id & 31) * 8; }
-    uint4v rah[2], ral[2], rbh[4], rbl[4];
-    auto gload = [&](int k0) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int64_t off = int64_t(min(m0 + a_row[i], d_out - 1)) * SBIG + ek + k0 + a_kc[i];
-            rah[i] = *reinterpret_cast<const uint4v*>(Eh + off);
-            ral[i] = *reinterpret_cast<const uint4v*>(El + off);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int col = min(n0 + b_nc[i], c1 - 8);     // ragged right edge: duplicate columns, never stored
-            const int64_t off = (int64_t(u0) + k0 + b_kr[i]) * d_in + col;
-            rbh[i] = *reinterpret_cast<const uint4v*>(Uh + off);
-            rbl[i] = *reinterpret_cast<const uint4v*>(Ul + off);
-        }
+    for (int q = 0; q < 2; ++q) {
+        const int row = 4 * wave + 2 * q + (lane >> 5);
+        const int c = (lane & 31) ^ ((row & 3) << 2);
+        voff_b[q] = (n0 + c * 8 < c1) ? uint32_t((int64_t(row) * d_in + n0 + c * 8) * 2) : LDS_DMA_OOB;
+    }
+    const int n_kb = a.K / KT;
+    struct Desc {
+        __amdgpu_buffer_rsrc_t ah, al, bh, bl;
     };
-    auto lwrite = [&](int st) __attribute__((always_inline)) {
-        uint16_t* base = tl + st * STAGE;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            *reinterpret_cast<uint4v*>(base + a_row[i] * PA + a_kc[i]) = rah[i];
-            *reinterpret_cast<uint4v*>(base + A_ELEMS + a_row[i] * PA + a_kc[i]) = ral[i];
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *reinterpret_cast<uint4v*>(base + 2 * A_ELEMS + b_kr[i] * PB + b_nc[i]) = rbh[i];
-            *reinterpret_cast<uint4v*>(base + 2 * A_ELEMS + B_ELEMS + b_kr[i] * PB + b_nc[i]) = rbl[i];
-        }
+    auto make_desc = [&](int kb, bool live) __attribute__((always_inline)) {
+        Desc d;
+        if (!live) kb = 0;
+        const int64_t ea = (int64_t(a.ek) + kb * KT) * a.ldD, eb = (int64_t(a.u0) + kb * KT) * d_in;
+        const int ra = live ? KT * a.ldD * 2 : 0, rb = live ? int(KT * d_in * 2) : 0;
+        d.ah = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.Dh + ea), 0, ra, 0x00020000);
+        d.al = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.Dl + ea), 0, ra, 0x00020000);
+        d.bh = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.Uh + eb), 0, rb, 0x00020000);
+        d.bl = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.Ul + eb), 0, rb, 0x00020000);
+        return d;
+    };
+    // load number i (0..5) of a k-step into the slot at LDS byte address dst
+    auto gload1 = [&](const Desc& d, uint32_t dst, int i) __attribute__((always_inline)) {
+        if (i == 0) lds_load16(dst + OFF_AH + wave * 1024, voff_a, d.ah);
+        else if (i == 1) lds_load16(dst + OFF_AL + wave * 1024, voff_a, d.al);
+        else if (i == 2) lds_load16(dst + OFF_BH + wave * 2048, voff_b[0], d.bh);
+        else if (i == 3) lds_load16(dst + OFF_BH + wave * 2048 + 1024, voff_b[1], d.bh);
+        else if (i == 4) lds_load16(dst + OFF_BL + wave * 2048, voff_b[0], d.bl);
+        else lds_load16(dst + OFF_BL + wave * 2048 + 1024, voff_b[1], d.bl);
     };
 
-    gload(0);
-    // accumulators start as the W tile times f_d f_u (a power of two: exact), so the tile is in flight together
-    // with the first operand tiles; register r of lane l is row (r/4)*8 + (l/32)*4 + r%4, column l%32
-    const float f_all = sc->f_all, f_inv = sc->f_inv;
+    // transpose-read addressing: within 16 lanes, lane 4 k + c reads 8 bytes of panel row k at byte 8 c of a
+    // 32-byte column group; two reads (rows +0 and +4) make one MFMA operand (k = 8 (lane / 32) + 0..7)
+    const int i16 = lane & 15, g16 = (lane >> 4) & 1, kb8 = lane >> 5;
+    const int kq = i16 >> 2;
+    const int lo = (2 * g16 + ((i16 & 3) >> 1)) * 16 + (i16 & 1) * 8;
+    int fa[2], fb[4];
+#pragma unroll
+    for (int m = 0; m < 2; ++m) fa[m] = OFF_AH + (kb8 * 8 + kq) * A_ROWB + (((wr * 2 + m) ^ kq) << 6) + lo;
+#pragma unroll
+    for (int n = 0; n < 4; ++n) fb[n] = OFF_BH + (kb8 * 8 + kq) * B_ROWB + wc * 256 + ((n ^ kq) << 6) + lo;
+
+    struct Frags {
+        half8v ah[2], al[2], bh[4], bl[4];
+    };
+    auto rd2 = [&](const char* p, int rowb) __attribute__((always_inline)) {
+        short4v x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(p));
+        short4v x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(p + 4 * rowb));
+        return __builtin_bit_cast(half8v, __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // fragment r (0..11) of the slot at tl + sb, in the order the MFMAs use them
+    auto rd = [&](Frags& f, int r, int sb) __attribute__((always_inline)) {
+        const char* s = tl + sb;
+        if (r == 0) f.al[0] = rd2(s + fa[0] + A_PANELB, A_ROWB);
+        else if (r <= 4) f.bh[r - 1] = rd2(s + fb[r - 1], B_ROWB);
+        else if (r == 5) f.ah[0] = rd2(s + fa[0], A_ROWB);
+        else if (r <= 9) f.bl[r - 6] = rd2(s + fb[r - 6] + B_PANELB, B_ROWB);
+        else if (r == 10) f.al[1] = rd2(s + fa[1] + A_PANELB, A_ROWB);
+        else f.ah[1] = rd2(s + fa[1], A_ROWB);
+    };
+
+    // prologue: k-steps 0 .. 2 in flight, then the W tile (scaled by the exact power of two f_d f_u) straight into
+    // the accumulators; register r of lane l is row (r/4)*8 + (l/32)*4 + r%4, column l%32 of a 32 x 32 tile
+    for (int kb = 0; kb < NBUF; ++kb)
+        if (kb < n_kb) {
+            const Desc d = make_desc(kb, true);
+#pragma unroll
+            for (int i = 0; i < 6; ++i) gload1(d, lds0 + kb * STAGEB, i);
+        }
+    const float f_all = a.sc->f_all, f_inv = a.sc->f_inv;
     float16v acc[2][4];
     const int lr = (lane >> 5) * 4, lc = lane & 31;
 #pragma unroll
@@ -445,61 +521,82 @@ __global__ __launch_bounds__(256) void trailing_kernel(float* __restrict__ Wf, c
             for (int r = 0; r < 16; ++r) {
                 const int rr = min(m0 + wr * 64 + m * 32 + (r / 4) * 8 + lr + (r % 4), d_out - 1);
                 const int cc = min(n0 + wc * 128 + n * 32 + lc, c1 - 1);
-                acc[m][n][r] = Wf[int64_t(rr) * d_in + cc] * f_all;
+                acc[m][n][r] = a.Wf[int64_t(rr) * d_in + cc] * f_all;
             }
-    lwrite(0);
+    __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));
     __syncthreads();
+    Frags Fc, FH;
+#pragma unroll
+    for (int r = 0; r < 12; ++r) rd(Fc, r, 0);
+    __syncthreads();   // slot 0 is overwritten by the loads of the first half-iteration
 
-    const int a_off = (wr * 64 + lc) * PA + (lane >> 5) * 8;                      // + m*32*PA + kq*16
-    const int i16 = lane & 15, g16 = (lane >> 4) & 1, kb8 = lane >> 5;
-    const int b_off = (kb8 * 8 + (i16 >> 2)) * PB + g16 * 16 + (i16 & 3) * 4 + wc * 128;   // + kq*16*PB + n*32
-    const int n_st = K / TK;
-#pragma unroll 1
-    for (int st = 0; st < n_st; ++st) {
-        const int cur = st & 1;
-        if (st + 1 < n_st) gload((st + 1) * TK);
-        const uint16_t* base = tl + cur * STAGE;
+    // the 24 MFMAs of one k-step: per row tile m the products lo*hi, hi*lo, hi*hi against the four column tiles,
+    // consecutive MFMAs on different accumulators; `between(i)` is placed behind MFMA i
+    auto mma = [&](const Frags& f, auto&& between) __attribute__((always_inline)) {
 #pragma unroll
-        for (int kq = 0; kq < 2; ++kq) {
-            half8v ah[2], al[2], bh[4], bl[4];
-#pragma unroll
-            for (int m = 0; m < 2; ++m) {
-                const uint16_t* pa = base + a_off + m * 32 * PA + kq * 16;
-                ah[m] = __builtin_bit_cast(half8v, *reinterpret_cast<const uint4v*>(pa));
-                al[m] = __builtin_bit_cast(half8v, *reinterpret_cast<const uint4v*>(pa + A_ELEMS));
-            }
-#pragma unroll
-            for (int n = 0; n < 4; ++n) {
-                const uint16_t* pb = base + 2 * A_ELEMS + b_off + kq * 16 * PB + n * 32;
-                short4v h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pb));
-                short4v h1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pb + 4 * PB));
-                short4v l0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pb + B_ELEMS));
-                short4v l1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pb + B_ELEMS + 4 * PB));
-                bh[n] = __builtin_bit_cast(half8v, __builtin_shufflevector(h0, h1, 0, 1, 2, 3, 4, 5, 6, 7));
-                bl[n] = __builtin_bit_cast(half8v, __builtin_shufflevector(l0, l1, 0, 1, 2, 3, 4, 5, 6, 7));
-            }
-#pragma unroll
-            for (int m = 0; m < 2; ++m)
-#pragma unroll
-                for (int n = 0; n < 4; ++n) {
-                    acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[m], bh[n], acc[m][n], 0, 0, 0);
-                    acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[m], bl[n], acc[m][n], 0, 0, 0);
-                    acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[m], bh[n], acc[m][n], 0, 0, 0);
-                }
+        for (int i = 0; i < 24; ++i) {
+            const int m = i / 12, p = (i % 12) / 4, n = i % 4;
+            if (p == 0) acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.al[m], f.bh[n], acc[m][n], 0, 0, 0);
+            else if (p == 1) acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.ah[m], f.bl[n], acc[m][n], 0, 0, 0);
+            else acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.ah[m], f.bh[n], acc[m][n], 0, 0, 0);
+            between(i);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (st + 1 < n_st) lwrite(cur ^ 1);
-        __syncthreads();
+    };
+
+    int s0 = 0;   // slot of k-step kb
+#pragma unroll 1
+    for (int kb = 0; kb < n_kb; kb += 2) {
+        const int s1 = (s0 == NBUF - 1) ? 0 : s0 + 1, s2 = (s1 == NBUF - 1) ? 0 : s1 + 1;
+        // Loads and fragment reads past the last k-step are not branched around: the loads get an empty
+        // descriptor (they deposit zeros into a slot nobody reads again), the reads fetch stale data nobody uses.
+        {   // k-step kb from Fc; fragments of kb+1 -> FH; loads of kb+3 -> slot s0
+            const Desc d = make_desc(kb + 3, kb + 3 < n_kb);
+            const uint32_t dst = lds0 + s0 * STAGEB;
+            const int sb = s1 * STAGEB;
+            mma(Fc, [&](int i) __attribute__((always_inline)) {
+                if ((i & 1) == 0) rd(FH, i / 2, sb);
+                else if (i < 12) gload1(d, dst, i / 2);
+            });
+            __builtin_amdgcn_s_waitcnt(wait_vmcnt(6));   // k-step kb+2 has landed
+            __syncthreads();
+        }
+        {   // k-step kb+1 from FH; fragments of kb+2 -> Fc; loads of kb+4 -> slot s1
+            const Desc d = make_desc(kb + 4, kb + 4 < n_kb);
+            const uint32_t dst = lds0 + s1 * STAGEB;
+            const int sb = s2 * STAGEB;
+            mma(FH, [&](int i) __attribute__((always_inline)) {
+                if ((i & 1) == 0) rd(Fc, i / 2, sb);
+                else if (i < 12) gload1(d, dst, i / 2);
+            });
+            __builtin_amdgcn_s_waitcnt(wait_vmcnt(6));   // k-step kb+3 has landed
+            __syncthreads();
+        }
+        s0 = s2;
     }
+    __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // no LDS write may be in flight when the workgroup ends
+    // uniform branch: interior tiles store without per-element masks
+    if ((m0 + TM <= d_out) && (n0 + TN <= c1)) {
+        float* wp = a.Wf + int64_t(m0 + wr * 64 + lr) * d_in + n0 + wc * 128 + lc;
 #pragma unroll
-    for (int m = 0; m < 2; ++m)
+        for (int m = 0; m < 2; ++m)
 #pragma unroll
-        for (int n = 0; n < 4; ++n)
+            for (int n = 0; n < 4; ++n)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int rr = m0 + wr * 64 + m * 32 + (r / 4) * 8 + lr + (r % 4);
-                const int cc = n0 + wc * 128 + n * 32 + lc;
-                if (rr < d_out && cc < c1) Wf[int64_t(rr) * d_in + cc] = acc[m][n][r] * f_inv;
-            }
+                for (int r = 0; r < 16; ++r)
+                    wp[int64_t(m * 32 + (r / 4) * 8 + (r % 4)) * d_in + n * 32] = acc[m][n][r] * f_inv;
+    } else {
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+            for (int n = 0; n < 4; ++n)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int rr = m0 + wr * 64 + m * 32 + (r / 4) * 8 + lr + (r % 4);
+                    const int cc = n0 + wc * 128 + n * 32 + lc;
+                    if (rr < d_out && cc < c1) a.Wf[int64_t(rr) * d_in + cc] = acc[m][n][r] * f_inv;
+                }
+    }
 }
 
 // loss = sum of the per-row sums, fixed order.  One workgroup.
@@ -519,20 +616,23 @@ __global__ __launch_bounds__(1024) void loss_kernel(const float* __restrict__ ro
 
 struct SweepWs {
     float* Wf;        // [d_out x d_in] working copy, sweep order
-    uint16_t* Eh;     // [d_out x SBIG] scaled negated residuals of the current super-block, fp16 hi
-    uint16_t* El;     //                                                                     fp16 lo
+    uint16_t* Dh;     // [SBIG x ldD] scaled negated residuals of the current super-block, transposed, fp16 hi
+    uint16_t* Dl;     //                                                                               fp16 lo
     uint16_t* Uh;     // [d_in x d_in] scaled rows U_jk / U_jj, fp16 hi
     uint16_t* Ul;     //                                        fp16 lo
     float* rowloss;   // [d_out]
     Scalars* sc;
 };
 
+// leading dimension of the transposed residual panels: whole 64-row workgroups of the block kernel
+inline int64_t ld_d(int64_t d_out) { return ceil_div(d_out, ROWS) * ROWS; }
+
 SweepWs carve(void* ws, int64_t d_out, int64_t d_in) {
     char* p = static_cast<char*>(ws);
     SweepWs w;
     w.Wf = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * d_in * sizeof(float), 256);
-    w.Eh = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(d_out) * SBIG * 2, 256);
-    w.El = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(d_out) * SBIG * 2, 256);
+    w.Dh = reinterpret_cast<uint16_t*>(p); p += size_t(SBIG) * ld_d(d_out) * 2;
+    w.Dl = reinterpret_cast<uint16_t*>(p); p += size_t(SBIG) * ld_d(d_out) * 2;
     w.Uh = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(d_in) * d_in * 2, 256);
     w.Ul = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(d_in) * d_in * 2, 256);
     w.rowloss = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * sizeof(float), 256);
@@ -559,7 +659,7 @@ onecomp_status launch_block(const BlockArgs& a, hipStream_t stream) {
 
 size_t sweep_workspace_bytes(int64_t d_out, int64_t d_in, int block) {
     (void)block;
-    return align_up(size_t(d_out) * d_in * sizeof(float), 256) + 2 * align_up(size_t(d_out) * SBIG * 2, 256) +
+    return align_up(size_t(d_out) * d_in * sizeof(float), 256) + 2 * size_t(SBIG) * ld_d(d_out) * 2 +
            2 * align_up(size_t(d_in) * d_in * 2, 256) + align_up(size_t(d_out) * sizeof(float), 256) + 256;
 }
 
@@ -594,18 +694,23 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
             return ONECOMP_ERR_HIP;
         attr_set = true;
     }
+    TrailArgs t;
+    t.Wf = w.Wf; t.Dh = w.Dh; t.Dl = w.Dl; t.Uh = w.Uh; t.Ul = w.Ul; t.sc = w.sc;
+    t.d_out = int(d_out); t.ldD = int(ld_d(d_out)); t.d_in = int(d_in);
+    t.n_mt = int(ceil_div(d_out, tg::TM));
     auto trailing = [&](int ek, int K, int u0, int c0, int c1) -> onecomp_status {
         if (c1 <= c0) return ONECOMP_OK;
-        dim3 grid(unsigned(ceil_div(c1 - c0, tg::TN)), unsigned(ceil_div(d_out, tg::TM)));
-        hipLaunchKernelGGL(trailing_kernel, grid, dim3(256), tg::LDS_BYTES, stream, w.Wf, w.Eh, w.El, w.Uh, w.Ul, w.sc,
-                           int(d_out), d_in, ek, K, u0, c0, c1);
+        t.ek = ek; t.K = K; t.u0 = u0; t.c0 = c0; t.c1 = c1;
+        t.n_nt = int(ceil_div(c1 - c0, tg::TN));
+        t.chunk = int(ceil_div(int64_t(t.n_mt) * t.n_nt, 8));
+        hipLaunchKernelGGL(trailing_kernel, dim3(unsigned(t.chunk) * 8), dim3(256), tg::LDS_BYTES, stream, t);
         ONECOMP_CHECK_LAUNCH();
         return ONECOMP_OK;
     };
 
     BlockArgs a;
     a.Wf = w.Wf; a.U = U; a.perm = perm; a.Q = Q; a.scales = scales; a.zeros = zeros; a.W_hat = W_hat;
-    a.Eh = w.Eh; a.El = w.El; a.sc = w.sc; a.rowloss = w.rowloss;
+    a.Dh = w.Dh; a.Dl = w.Dl; a.ldD = int(ld_d(d_out)); a.sc = w.sc; a.rowloss = w.rowloss;
     a.d_out = int(d_out); a.d_in = int(d_in); a.G = group_size; a.n_g = int(d_in / group_size);
     a.qmax = float((1 << bits) - 1);
     onecomp_status st;

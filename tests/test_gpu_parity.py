@@ -297,4 +297,8 @@ def test_full_size_down_projection_sampled():
     _announce("full size: sweep, 48 sampled rows")
     U32 = torch.from_numpy(f["U"].astype(np.float32)).to(DEV)
     rows = np.sort(np.random.default_rng(7).choice(d_out, size=48, replace=False))
-    _check_sweep(W, U32, cfg.bits, cfg.group_size, rows=rows)
+    # A flip at a tie changes later codes of its row (the feedback differs by a whole grid step), so in a sample
+    # of 48 rows one flipped row alone costs a few tenths of a percent of raw agreement: the raw bar is 99 % here,
+    # the flips themselves are bounded, and agreement after replaying the flips must still be exact.
+    _, st = _check_sweep(W, U32, cfg.bits, cfg.group_size, rows=rows, min_agree=0.99)
+    assert st["tie_flips"] <= 4
