@@ -322,6 +322,365 @@ __global__ __launch_bounds__(BLOCK_THREADS) void block_kernel(BlockArgs a) {
 constexpr size_t BLOCK_LDS = (size_t(SB) * SB + SB + 2 * size_t(ROWS) * SP) * sizeof(float) + size_t(ROWS) * QP;
 
 // ------------------------------------------------------------------------------------------
+// panel kernel (group sizes up to the block width): one launch sweeps a whole super-block of up to four
+// 128-column blocks for 64 rows per workgroup.  Rows never interact, so the workgroup carries its rows through
+// the blocks without any grid-wide step in between:
+//   near update   (left-looking) before block b is swept, its columns receive the feedback of blocks 0 .. b-1 of
+//                 the super-block: W_b += D_b' Un[b', b] as split-fp16 MFMAs (see the trailing kernel) whose
+//                 operands are loaded from global memory already in MFMA fragment order, 16 bytes per lane:
+//                 the residual fragments were written by this workgroup after block b', the fragments of the
+//                 normalized U blocks by nearfrag_kernel.  Wave w owns the block's column tile w (64 x 32).
+//   sequential    four lanes per row (a quad), each holding 8 of the 32 columns of the inner block; the current
+//                 column is broadcast inside the quad by DPP, the grid arithmetic is replicated, the feedback is
+//                 8 FMAs per lane.  All four waves work (16 rows each).
+//   inner update  the inner block's 32 errors reach the remaining columns of the block through fp32 MFMAs
+//                 (v_mfma_f32_32x32x2_f32) on the tiles in LDS.
+// LDS tile sW holds current values; a finished column holds its code (as a float).
+// ------------------------------------------------------------------------------------------
+struct PanelArgs {
+    const float* Wf;            // [d_out x d_in] working copy (columns beyond the super-block are current up to the
+                                // previous super-block)
+    const float* U;
+    const int32_t* perm;
+    uint8_t* Q;
+    float* scales;
+    float* zeros;
+    float* W_hat;
+    uint16_t *Dh, *Dl;          // [SBIG x ldD] transposed residual panels for the far update
+    uint16_t *Fh, *Fl;          // [workgroup][3][8 k-steps][2 row tiles][64 lanes][8] residual fragments (own use)
+    const uint16_t *Bh, *Bl;    // [6 block pairs][8 k-steps][4 column tiles][64 lanes][8] of this super-block
+    const Scalars* sc;
+    float* rowloss;
+    int d_out, d_in, s0, nb, lgG, n_g, ldD;
+    float qmax;
+};
+
+constexpr int PANEL_LDS = (SB * SB + 2 * ROWS * SP + SB + 2 * ROWS * 8) * 4;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_quad(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+constexpr int quad_bcast(int o) { return o | (o << 2) | (o << 4) | (o << 6); }
+constexpr int QUAD_SWAP1 = 1 | (0 << 2) | (3 << 4) | (2 << 6);   // lanes 0<->1, 2<->3
+constexpr int QUAD_SWAP2 = 2 | (3 << 2) | (0 << 4) | (1 << 6);   // lanes 0<->2, 1<->3
+
+template <int GB>  // group width seen inside an inner block: 16 (G == 16) or 32 (G = 32, 64, 128)
+__global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) char psm[];
+    float* sU = reinterpret_cast<float*>(psm);   // SB x SB: U[j0 + j][j0 .. j0 + 127], filled by direct loads
+    float* sW = sU + SB * SB;                    // ROWS x SP
+    float* sE = sW + ROWS * SP;                  // ROWS x SP errors e
+    float* sRd = sE + ROWS * SP;                 // SB reciprocals of the diagonal
+    float* sS = sRd + SB;                        // ROWS x 8 scales of the block's groups
+    float* sZ = sS + ROWS * 8;                   // ROWS x 8 zero points
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r0 = blockIdx.x * ROWS;
+    const int64_t d_in = a.d_in;
+    const int G = 1 << a.lgG;
+    // sequential part: quad = row, lane in quad = slice of 8 columns
+    const int qrow = tid >> 2, sl = tid & 3;
+    const int grow = min(r0 + qrow, a.d_out - 1);
+    const bool row_ok = (r0 + qrow) < a.d_out;
+    // MFMA accumulator layout: register r of lane l = row (r/4)*8 + (l/32)*4 + r%4, column l%32
+    const int lr = (lane >> 5) * 4, lc = lane & 31;
+    const float qmax = a.qmax;
+    const float f_d = a.sc->f_d, f_all = a.sc->f_all, f_inv = a.sc->f_inv;
+    const uint32_t ldsU = uint32_t(uintptr_t((ONECOMP_LDS char*)psm));
+    float s = 1.f, rs = 1.f, z = 0.f, lossacc = 0.f;
+
+#pragma unroll 1
+    for (int b = 0; b < a.nb; ++b) {
+        const int j0 = a.s0 + b * SB;
+        __syncthreads();   // everybody is done with the previous block's tiles
+        // ---- U diagonal block -> sU, two rows (1 KB) per wave load, no registers involved
+        {
+            const float* ub = a.U + int64_t(j0) * d_in + j0;
+            __amdgpu_buffer_rsrc_t rsrc =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(ub), 0, int((int64_t(SB - 1) * d_in + SB) * 4), 0x00020000);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int row = 2 * (16 * wave + q) + (lane >> 5);
+                lds_load16(ldsU + (16 * wave + q) * 1024, uint32_t((int64_t(row) * d_in + (lane & 31) * 4) * 4), rsrc);
+            }
+        }
+        // ---- near update of this block's columns, wave = column tile
+        {
+            float16v acc[2];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int rr = min(r0 + mt * 32 + (r / 4) * 8 + lr + (r % 4), a.d_out - 1);
+                    acc[mt][r] = a.Wf[int64_t(rr) * d_in + j0 + 32 * wave + lc];
+                }
+            if (b > 0) {
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[mt][r] *= f_all;
+                // rolling window of 8 k-steps (one source block) of operand fragments
+                uint4v win[8][6];
+                const uint4v* fh = reinterpret_cast<const uint4v*>(a.Fh) + int64_t(blockIdx.x) * 3 * 8 * 2 * 64 + lane;
+                const uint4v* fl = reinterpret_cast<const uint4v*>(a.Fl) + int64_t(blockIdx.x) * 3 * 8 * 2 * 64 + lane;
+                const uint4v* bh = reinterpret_cast<const uint4v*>(a.Bh) + (b * (b - 1) / 2) * 8 * 4 * 64 + wave * 64 + lane;
+                const uint4v* bl = reinterpret_cast<const uint4v*>(a.Bl) + (b * (b - 1) / 2) * 8 * 4 * 64 + wave * 64 + lane;
+                auto issue = [&](int bp, int ks, uint4v(&d)[6]) __attribute__((always_inline)) {
+                    const int fo = (bp * 8 + ks) * 2 * 64, bo = (bp * 8 + ks) * 4 * 64;
+                    d[0] = fl[fo]; d[1] = fh[fo]; d[2] = fl[fo + 64]; d[3] = fh[fo + 64];
+                    d[4] = bh[bo]; d[5] = bl[bo];
+                };
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) issue(0, ks, win[ks]);
+#pragma unroll 1
+                for (int bp = 0; bp < b; ++bp) {
+                    const bool more = bp + 1 < b;
+#pragma unroll
+                    for (int ks = 0; ks < 8; ++ks) {
+                        const half8v al0 = __builtin_bit_cast(half8v, win[ks][0]), ah0 = __builtin_bit_cast(half8v, win[ks][1]);
+                        const half8v al1 = __builtin_bit_cast(half8v, win[ks][2]), ah1 = __builtin_bit_cast(half8v, win[ks][3]);
+                        const half8v bhv = __builtin_bit_cast(half8v, win[ks][4]), blv = __builtin_bit_cast(half8v, win[ks][5]);
+                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al0, bhv, acc[0], 0, 0, 0);
+                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al1, bhv, acc[1], 0, 0, 0);
+                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah0, blv, acc[0], 0, 0, 0);
+                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah1, blv, acc[1], 0, 0, 0);
+                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah0, bhv, acc[0], 0, 0, 0);
+                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah1, bhv, acc[1], 0, 0, 0);
+                        if (more) issue(bp + 1, ks, win[ks]);
+                    }
+                }
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[mt][r] *= f_inv;
+            }
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    sW[(mt * 32 + (r / 4) * 8 + lr + (r % 4)) * SP + 32 * wave + lc] = acc[mt][r];
+        }
+        __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // the direct loads into sU have landed
+        __syncthreads();
+        if (tid < SB) sRd[tid] = 1.0f / sU[tid * SB + tid];
+        __syncthreads();
+
+#pragma unroll 1
+        for (int jb = 0; jb < SB; jb += IB) {
+            {
+                float w[8];
+                {
+                    const float* wp = sW + qrow * SP + jb + 8 * sl;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) w[i] = wp[i];
+                }
+                // row j of the inner block's U triangle (this lane's 8 columns) and 1 / U_jj, one step ahead
+                float4v ua[2], ub[2];
+                float rdc = sRd[jb], rdn = 0.f;
+                const float* up = sU + jb * SB + jb + 8 * sl;
+                ua[0] = *reinterpret_cast<const float4v*>(up);
+                ua[1] = *reinterpret_cast<const float4v*>(up + 4);
+                static_for<0, IB>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    auto step = [&](float4v(&cur)[2], float4v(&nxt)[2]) __attribute__((always_inline)) {
+                        if constexpr (j + 1 < IB) {
+                            nxt[0] = *reinterpret_cast<const float4v*>(up + (j + 1) * SB);
+                            nxt[1] = *reinterpret_cast<const float4v*>(up + (j + 1) * SB + 4);
+                            rdn = sRd[jb + j + 1];
+                        }
+                        if constexpr (j % GB == 0) {
+                            const int col = j0 + jb + j;
+                            bool fresh;
+                            float mn, mx;
+                            if constexpr (GB == 16) {
+                                // group = the 16 columns held by lanes 2 (j / 16) and 2 (j / 16) + 1 of the quad
+                                fresh = true;
+                                mn = w[0]; mx = w[0];
+#pragma unroll
+                                for (int i = 1; i < 8; ++i) { mn = fminf(mn, w[i]); mx = fmaxf(mx, w[i]); }
+                                mn = fminf(mn, dpp_quad<QUAD_SWAP1>(mn));
+                                mx = fmaxf(mx, dpp_quad<QUAD_SWAP1>(mx));
+                                mn = dpp_quad<quad_bcast(j / 8)>(mn);
+                                mx = dpp_quad<quad_bcast(j / 8)>(mx);
+                            } else {
+                                fresh = (col & (G - 1)) == 0;
+                                if (fresh) {   // uniform: the group's G <= 128 columns are current in sW
+                                    const float* gp = sW + qrow * SP + jb + sl;
+                                    mn = gp[0]; mx = gp[0];
+                                    for (int c = 4; c < G; c += 4) { const float v = gp[c]; mn = fminf(mn, v); mx = fmaxf(mx, v); }
+                                    mn = fminf(mn, dpp_quad<QUAD_SWAP1>(mn));
+                                    mx = fmaxf(mx, dpp_quad<QUAD_SWAP1>(mx));
+                                    mn = fminf(mn, dpp_quad<QUAD_SWAP2>(mn));
+                                    mx = fmaxf(mx, dpp_quad<QUAD_SWAP2>(mx));
+                                }
+                            }
+                            if (fresh) {
+                                s = (mx - mn) / qmax;
+                                if (s == 0.f) s = 1.f;
+                                rs = 1.0f / s;
+                                z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
+                                if (sl == 0) {
+                                    const int gi = (jb + j) >> a.lgG;
+                                    sS[qrow * 8 + gi] = s;
+                                    sZ[qrow * 8 + gi] = z;
+                                    if (row_ok) {
+                                        a.scales[int64_t(grow) * a.n_g + (col >> a.lgG)] = s;
+                                        a.zeros[int64_t(grow) * a.n_g + (col >> a.lgG)] = z;
+                                    }
+                                }
+                            }
+                        }
+                        const float wj = dpp_quad<quad_bcast(j / 8)>(w[j % 8]);
+                        const float q = fminf(fmaxf(rintf(wj * rs) + z, 0.f), qmax);   // w / s as w * fl(1 / s)
+                        const float wh = s * (q - z);
+                        const float e = (wj - wh) * rdc;
+                        // feedback inside the inner block: w_k -= e U_jk.  Columns up to j are finished, updating
+                        // them is harmless; in the last slice the finished registers are skipped.
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            if (j < 24 || i > j % 8) w[i] = __builtin_fmaf(-e, cur[i / 4][i % 4], w[i]);
+                        sE[qrow * SP + jb + j] = e;
+                        sW[qrow * SP + jb + j] = q;
+                        rdc = rdn;
+                    };
+                    if constexpr (j % 2 == 0) step(ua, ub);
+                    else step(ub, ua);
+                });
+            }
+            __syncthreads();
+            // remaining columns of the block: w_c -= sum_i e_i U[jb+i][c], c >= jb + 32, on 32 x 32 tiles
+            const int cs = jb + IB;
+            if (cs < SB) {
+                const int n_tiles = 2 * ((SB - cs) / 32);
+                for (int t = wave; t < n_tiles; t += 4) {
+                    const int mt = t & 1, nt = t >> 1;
+                    float* cp = sW + (mt * 32 + lr) * SP + cs + nt * 32 + lc;
+                    float16v c;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) c[r] = cp[((r / 4) * 8 + (r % 4)) * SP];
+                    const float* ap = sE + (mt * 32 + lc) * SP + jb + (lane >> 5);
+                    const float* bp = sU + (jb + (lane >> 5)) * SB + cs + nt * 32 + lc;
+#pragma unroll
+                    for (int kk = 0; kk < IB / 2; ++kk)
+                        c = __builtin_amdgcn_mfma_f32_32x32x2f32(-ap[2 * kk], bp[2 * kk * SB], c, 0, 0, 0);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) cp[((r / 4) * 8 + (r % 4)) * SP] = c[r];
+                }
+            }
+            __syncthreads();
+        }
+
+        // ---- block done: loss, residual panels, outputs
+        {   // sum of e^2 of this row's quarter of the block, then over the quad
+            float acc = 0.f;
+            const float* ep = sE + qrow * SP + 32 * sl;
+#pragma unroll 8
+            for (int c = 0; c < 32; ++c) acc = __builtin_fmaf(ep[c], ep[c], acc);
+            acc += dpp_quad<QUAD_SWAP1>(acc);
+            acc += dpp_quad<QUAD_SWAP2>(acc);
+            lossacc += acc;
+        }
+        // residual w - w^ = e U_jj, negated, scaled by a power of two and split into fp16 hi + lo
+        // (hi = rne(x), lo = rne(x - hi): 22 significant bits); saturated far above anything a sweep produces.
+        auto split8 = [&](auto&& value, short8v& dh, short8v& dl) __attribute__((always_inline)) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float x = value(e);
+                x = fminf(fmaxf(x, -60000.f), 60000.f);
+                const _Float16 h = (_Float16)x;
+                const _Float16 lo = (_Float16)(x - (float)h);
+                dh[e] = __builtin_bit_cast(short, h);
+                dl[e] = __builtin_bit_cast(short, lo);
+            }
+        };
+        // transposed panel (k-major) for the far update; rows past d_out hold copies of the last row
+        for (int it = tid; it < SB * (ROWS / 8); it += 256) {
+            const int c = it / (ROWS / 8), r8 = (it % (ROWS / 8)) * 8;
+            const float ujj = sU[c * SB + c] * f_d;
+            short8v dh, dl;
+            split8([&](int e) { return -sE[(r8 + e) * SP + c] * ujj; }, dh, dl);
+            const int64_t off = int64_t(b * SB + c) * a.ldD + r0 + r8;
+            *reinterpret_cast<short8v*>(a.Dh + off) = dh;
+            *reinterpret_cast<short8v*>(a.Dl + off) = dl;
+        }
+        // MFMA A-operand fragments for this workgroup's own near updates: lane L of k-step ks, row tile mt holds
+        // row mt*32 + L%32, columns ks*16 + 8 (L/32) + 0..7
+        if (b + 1 < a.nb) {
+            for (int it = tid; it < 8 * 2 * 64; it += 256) {
+                const int L = it & 63, row = ((it >> 6) & 1) * 32 + (L & 31), c0 = (it >> 7) * 16 + 8 * (L >> 5);
+                short8v dh, dl;
+                split8([&](int e) { return -sE[row * SP + c0 + e] * (sU[(c0 + e) * SB + c0 + e] * f_d); }, dh, dl);
+                const int64_t off = ((int64_t(blockIdx.x) * 3 + b) * (8 * 2 * 64) + it) * 8;
+                *reinterpret_cast<short8v*>(a.Fh + off) = dh;
+                *reinterpret_cast<short8v*>(a.Fl + off) = dl;
+            }
+        }
+        // W^ = s (q - z) and codes, original column order
+        for (int it = wave; it < ROWS / 2; it += 4) {
+            const int rr = it * 2 + (lane >> 5), c4 = (lane & 31) * 4;
+            const int gr = r0 + rr;
+            if (gr >= a.d_out) continue;
+            float qv[4], hv[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int gi = (c4 + e) >> a.lgG;
+                qv[e] = sW[rr * SP + c4 + e];
+                hv[e] = sS[rr * 8 + gi] * (qv[e] - sZ[rr * 8 + gi]);
+            }
+            if (!a.perm) {
+                if (a.W_hat) {
+                    const float4v h = {hv[0], hv[1], hv[2], hv[3]};
+                    *reinterpret_cast<float4v*>(a.W_hat + int64_t(gr) * d_in + j0 + c4) = h;
+                }
+                const uint32_t pk = uint32_t(qv[0]) | (uint32_t(qv[1]) << 8) | (uint32_t(qv[2]) << 16) | (uint32_t(qv[3]) << 24);
+                *reinterpret_cast<uint32_t*>(a.Q + int64_t(gr) * d_in + j0 + c4) = pk;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int oc = a.perm[j0 + c4 + e];
+                    if (a.W_hat) a.W_hat[int64_t(gr) * d_in + oc] = hv[e];
+                    a.Q[int64_t(gr) * d_in + oc] = uint8_t(qv[e]);
+                }
+            }
+        }
+        __threadfence();   // the fragments written above are read back by other waves of this workgroup
+    }
+    if (sl == 0 && row_ok) a.rowloss[grow] += lossacc;
+}
+
+// Fragments of the normalized U blocks the panel kernel's near updates multiply with: for super-block S, block
+// pair p = b (b - 1) / 2 + b' (b' < b), k-step ks, column tile nt, lane L:
+//   Un[512 S + 128 b' + 16 ks + 8 (L/32) + e][512 S + 128 b + 32 nt + L%32] * f_u,  e = 0 .. 7,  fp16 hi and lo.
+__global__ __launch_bounds__(256) void nearfrag_kernel(const float* __restrict__ U, int n, const Scalars* __restrict__ sc,
+                                                      uint16_t* __restrict__ Bh, uint16_t* __restrict__ Bl) {
+    const int S = blockIdx.y, p = blockIdx.x;
+    const int b = (p >= 3) ? 3 : (p >= 1 ? 2 : 1), bp = p - b * (b - 1) / 2;
+    const int k00 = S * SBIG + bp * SB, n00 = S * SBIG + b * SB;
+    if (n00 >= n) return;
+    const float f_u = sc->f_u;
+    for (int it = threadIdx.x; it < 8 * 4 * 64; it += 256) {
+        const int L = it & 63, nt = (it >> 6) & 3, ks = it >> 8;
+        const int col = n00 + nt * 32 + (L & 31), k0 = k00 + ks * 16 + 8 * (L >> 5);
+        short8v h8, l8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float dj = U[int64_t(k0 + e) * n + k0 + e];
+            float x = U[int64_t(k0 + e) * n + col] / dj * f_u;
+            x = fminf(fmaxf(x, -60000.f), 60000.f);
+            const _Float16 h = (_Float16)x;
+            const _Float16 lo = (_Float16)(x - (float)h);
+            h8[e] = __builtin_bit_cast(short, h);
+            l8[e] = __builtin_bit_cast(short, lo);
+        }
+        const int64_t off = ((int64_t(S) * 6 + p) * (8 * 4 * 64) + it) * 8;
+        *reinterpret_cast<short8v*>(Bh + off) = h8;
+        *reinterpret_cast<short8v*>(Bl + off) = l8;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Operands of the trailing GEMMs (once per layer).  The feedback e_j U_jk is computed as
 // (w_j - w^_j) * (U_jk / U_jj): the residual is bounded by the weights and the normalized row by the
 // regression coefficients between input channels, so both fit fp16 after a power-of-two scaling taken
@@ -621,8 +980,13 @@ struct SweepWs {
     uint16_t* Uh;     // [d_in x d_in] scaled rows U_jk / U_jj, fp16 hi
     uint16_t* Ul;     //                                        fp16 lo
     float* rowloss;   // [d_out]
+    uint16_t *Fh, *Fl;   // panel kernel: residual fragments, [workgroups][3 x 8 x 2 x 64 x 8]
+    uint16_t *Bh, *Bl;   // panel kernel: fragments of the normalized U blocks, [super-blocks][6 x 8 x 4 x 64 x 8]
     Scalars* sc;
 };
+
+constexpr size_t F_PER_WG = size_t(3) * 8 * 2 * 64 * 8 * 2;    // bytes of Fh (or Fl) per workgroup of the panel kernel
+constexpr size_t B_PER_SB = size_t(6) * 8 * 4 * 64 * 8 * 2;    // bytes of Bh (or Bl) per super-block
 
 // leading dimension of the transposed residual panels: whole 64-row workgroups of the block kernel
 inline int64_t ld_d(int64_t d_out) { return ceil_div(d_out, ROWS) * ROWS; }
@@ -636,8 +1000,27 @@ SweepWs carve(void* ws, int64_t d_out, int64_t d_in) {
     w.Uh = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(d_in) * d_in * 2, 256);
     w.Ul = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(d_in) * d_in * 2, 256);
     w.rowloss = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * sizeof(float), 256);
+    const size_t fb = size_t(ceil_div(d_out, ROWS)) * F_PER_WG, bb = size_t(ceil_div(d_in, SBIG)) * B_PER_SB;
+    w.Fh = reinterpret_cast<uint16_t*>(p); p += fb;
+    w.Fl = reinterpret_cast<uint16_t*>(p); p += fb;
+    w.Bh = reinterpret_cast<uint16_t*>(p); p += bb;
+    w.Bl = reinterpret_cast<uint16_t*>(p); p += bb;
     w.sc = reinterpret_cast<Scalars*>(p);
     return w;
+}
+
+template <int GB>
+onecomp_status launch_panel(const PanelArgs& a, hipStream_t stream) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&panel_kernel<GB>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, PANEL_LDS) != hipSuccess)
+            return ONECOMP_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(panel_kernel<GB>, dim3(unsigned(ceil_div(a.d_out, ROWS))), dim3(256), PANEL_LDS, stream, a);
+    ONECOMP_CHECK_LAUNCH();
+    return ONECOMP_OK;
 }
 
 template <int GB>
@@ -660,7 +1043,8 @@ onecomp_status launch_block(const BlockArgs& a, hipStream_t stream) {
 size_t sweep_workspace_bytes(int64_t d_out, int64_t d_in, int block) {
     (void)block;
     return align_up(size_t(d_out) * d_in * sizeof(float), 256) + 2 * size_t(SBIG) * ld_d(d_out) * 2 +
-           2 * align_up(size_t(d_in) * d_in * 2, 256) + align_up(size_t(d_out) * sizeof(float), 256) + 256;
+           2 * align_up(size_t(d_in) * d_in * 2, 256) + align_up(size_t(d_out) * sizeof(float), 256) +
+           2 * size_t(ceil_div(d_out, ROWS)) * F_PER_WG + 2 * size_t(ceil_div(d_in, SBIG)) * B_PER_SB + 256;
 }
 
 onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* U,
@@ -708,25 +1092,58 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
         return ONECOMP_OK;
     };
 
-    BlockArgs a;
-    a.Wf = w.Wf; a.U = U; a.perm = perm; a.Q = Q; a.scales = scales; a.zeros = zeros; a.W_hat = W_hat;
-    a.Dh = w.Dh; a.Dl = w.Dl; a.ldD = int(ld_d(d_out)); a.sc = w.sc; a.rowloss = w.rowloss;
-    a.d_out = int(d_out); a.d_in = int(d_in); a.G = group_size; a.n_g = int(d_in / group_size);
-    a.qmax = float((1 << bits) - 1);
     onecomp_status st;
-    // two-level lazy batch: inside a super-block of up to 512 columns every 128-column block updates the rest
-    // of the super-block; the columns beyond it are updated once per super-block with K = its width
-    for (int s0 = 0; s0 < d_in; s0 += SBIG) {
-        const int s1 = int(d_in < int64_t(s0) + SBIG ? d_in : int64_t(s0) + SBIG);
-        for (int j0 = s0; j0 < s1; j0 += SB) {
-            a.j0 = j0;
-            a.e_col = j0 - s0;
-            if (group_size == 16) st = launch_block<16>(a, stream);
-            else st = launch_block<32>(a, stream);
+    if (group_size <= SB) {
+        // Groups no wider than a block: one panel launch sweeps a super-block (the feedback between its blocks is
+        // applied inside the kernel), then the columns beyond it are updated once with K = its width.
+        hipLaunchKernelGGL(nearfrag_kernel, dim3(6, unsigned(ceil_div(d_in, SBIG))), dim3(256), 0, stream, U, int(d_in),
+                           w.sc, w.Bh, w.Bl);
+        ONECOMP_CHECK_LAUNCH();
+        PanelArgs pa;
+        pa.Wf = w.Wf; pa.U = U; pa.perm = perm; pa.Q = Q; pa.scales = scales; pa.zeros = zeros; pa.W_hat = W_hat;
+        pa.Dh = w.Dh; pa.Dl = w.Dl; pa.Fh = w.Fh; pa.Fl = w.Fl; pa.sc = w.sc; pa.rowloss = w.rowloss;
+        pa.d_out = int(d_out); pa.d_in = int(d_in); pa.n_g = int(d_in / group_size); pa.ldD = int(ld_d(d_out));
+        pa.lgG = 0;
+        while ((1 << pa.lgG) < group_size) ++pa.lgG;
+        pa.qmax = float((1 << bits) - 1);
+        for (int s0 = 0; s0 < d_in; s0 += SBIG) {
+            const int s1 = int(d_in < int64_t(s0) + SBIG ? d_in : int64_t(s0) + SBIG);
+            pa.s0 = s0; pa.nb = (s1 - s0) / SB;
+            pa.Bh = w.Bh + size_t(s0 / SBIG) * (B_PER_SB / 2);
+            pa.Bl = w.Bl + size_t(s0 / SBIG) * (B_PER_SB / 2);
+            if (group_size == 16) st = launch_panel<16>(pa, stream);
+            else st = launch_panel<32>(pa, stream);
             if (st != ONECOMP_OK) return st;
-            if ((st = trailing(j0 - s0, SB, j0, j0 + SB, s1)) != ONECOMP_OK) return st;
+            if ((st = trailing(0, s1 - s0, s0, s1, int(d_in))) != ONECOMP_OK) return st;
         }
-        if ((st = trailing(0, s1 - s0, s0, s1, int(d_in))) != ONECOMP_OK) return st;
+    } else {
+        // Groups wider than a block: a group's parameters need the current values of all its columns when the
+        // sweep reaches its first column.  Two-level lazy batch with super-blocks that never cut a group except at
+        // its start: whole groups per super-block while they fit into 512 columns, else pieces of up to 512
+        // columns counted from the group's start.  Inside a super-block every 128-column block updates the rest
+        // of the super-block; the columns beyond it are updated once per super-block.
+        BlockArgs a;
+        a.Wf = w.Wf; a.U = U; a.perm = perm; a.Q = Q; a.scales = scales; a.zeros = zeros; a.W_hat = W_hat;
+        a.Dh = w.Dh; a.Dl = w.Dl; a.ldD = int(ld_d(d_out)); a.sc = w.sc; a.rowloss = w.rowloss;
+        a.d_out = int(d_out); a.d_in = int(d_in); a.G = group_size; a.n_g = int(d_in / group_size);
+        a.qmax = float((1 << bits) - 1);
+        const int sbw = group_size <= SBIG ? (SBIG / group_size) * group_size : SBIG;
+        for (int s0 = 0; s0 < d_in;) {
+            int s1 = s0 + sbw;
+            if (group_size > SBIG) {   // do not run past the end of the current group
+                const int g_end = (s0 / group_size + 1) * group_size;
+                if (s1 > g_end) s1 = g_end;
+            }
+            if (s1 > d_in) s1 = int(d_in);
+            for (int j0 = s0; j0 < s1; j0 += SB) {
+                a.j0 = j0;
+                a.e_col = j0 - s0;
+                if ((st = launch_block<32>(a, stream)) != ONECOMP_OK) return st;
+                if ((st = trailing(j0 - s0, SB, j0, j0 + SB, s1)) != ONECOMP_OK) return st;
+            }
+            if ((st = trailing(0, s1 - s0, s0, s1, int(d_in))) != ONECOMP_OK) return st;
+            s0 = s1;
+        }
     }
     hipLaunchKernelGGL(loss_kernel, dim3(1), dim3(1024), 0, stream, w.rowloss, int(d_out), loss);
     ONECOMP_CHECK_LAUNCH();

@@ -218,6 +218,12 @@ def test_sweep_c1():
     (3, 256, 130, 512, torch.bfloat16, False),     # group wider than the block
     (4, 384, 1, 384, torch.float32, False),        # per-channel: one group per row
     (4, 128, 300, 1024, torch.bfloat16, True),
+    (4, 384, 40, 1920, torch.float32, False),      # groups straddle 512-column boundaries
+    (3, 640, 40, 1920, torch.bfloat16, True),      # groups wider than 512 columns, not a multiple of 512
+    (4, 256, 70, 1280, torch.bfloat16, False),
+    (4, 64, 130, 1664, torch.bfloat16, True),      # several super-blocks, the last one partial (13 blocks)
+    (4, 16, 64, 640, torch.float32, False),
+    (2, 32, 100, 1152, torch.bfloat16, True),
 ])
 def test_sweep_variants(bits, G, d_out, d_in, dtype, act):
     _announce(f"sweep b{bits} g{G} {d_out}x{d_in} {dtype} act={act}")
