@@ -70,25 +70,57 @@ __global__ void init_scalars_kernel(Scalars* sc) {
 }
 
 __device__ inline void block_max_to(uint32_t* dst, float v) {
-    // wave maximum by butterfly shuffles, then one atomic per wave
+    // Atomics on one address are serialized in L2 (~10 ns each), so a launch issues few of them: wave maximum by
+    // butterfly shuffles, workgroup maximum through LDS, one atomic per workgroup of up to 4 waves.
+    __shared__ float wave_max[4];
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-    if ((threadIdx.x & 63) == 0) atomicMax(dst, __float_as_uint(v));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int nw = (blockDim.x + 63) >> 6;
+        for (int i = 1; i < nw; ++i) v = fmaxf(v, wave_max[i]);
+        atomicMax(dst, __float_as_uint(v));
+    }
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void load_kernel(const T* __restrict__ W, int64_t d_in,
+__global__ __launch_bounds__(256) void load_kernel(const T* __restrict__ W, int64_t d_out, int64_t d_in,
                                                   const int32_t* __restrict__ perm, float* __restrict__ Wf,
                                                   float* __restrict__ rowloss, Scalars* __restrict__ sc) {
-    // one workgroup per row: few atomics on the shared maximum
-    const int64_t r = blockIdx.x;
-    if (threadIdx.x == 0) rowloss[r] = 0.f;
     float m = 0.f;
-    for (int p = threadIdx.x; p < d_in; p += 256) {
-        const int c = perm ? perm[p] : p;
-        const float v = to_f32<T>(W[r * d_in + c]);
-        Wf[r * d_in + p] = v;
-        m = fmaxf(m, fabsf(v));
+    for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {   // a workgroup per row, rows strided over the grid
+    if (threadIdx.x == 0) rowloss[r] = 0.f;
+    if (perm) {
+        for (int p = threadIdx.x; p < d_in; p += 256) {
+            const float v = to_f32<T>(W[r * d_in + perm[p]]);
+            Wf[r * d_in + p] = v;
+            m = fmaxf(m, fabsf(v));
+        }
+    } else {   // rows are 16-byte aligned: d_in is a multiple of 128
+        constexpr int V = 16 / sizeof(T);
+        for (int p = threadIdx.x * V; p < d_in; p += 256 * V) {
+            const uint4v raw = *reinterpret_cast<const uint4v*>(W + r * d_in + p);
+            float v[V];
+            if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[2 * e] = __uint_as_float(raw[e] << 16);
+                    v[2 * e + 1] = __uint_as_float(raw[e] & 0xFFFF0000u);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = __uint_as_float(raw[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < V; e += 4) {
+                const float4v o = {v[e], v[e + 1], v[e + 2], v[e + 3]};
+                *reinterpret_cast<float4v*>(Wf + r * d_in + p + e) = o;
+            }
+#pragma unroll
+            for (int e = 0; e < V; ++e) m = fmaxf(m, fabsf(v[e]));
+        }
+    }
     }
     block_max_to(&sc->max_w_bits, m);
 }
@@ -416,7 +448,12 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
                     const int rr = min(r0 + mt * 32 + (r / 4) * 8 + lr + (r % 4), a.d_out - 1);
                     acc[mt][r] = a.Wf[int64_t(rr) * d_in + j0 + 32 * wave + lc];
                 }
-            if (b > 0) {
+#ifndef XEXP_NONEAR
+            if (b > 0)
+#else
+            if (b > 100)
+#endif
+            {
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -482,6 +519,9 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
                 const float* up = sU + jb * SB + jb + 8 * sl;
                 ua[0] = *reinterpret_cast<const float4v*>(up);
                 ua[1] = *reinterpret_cast<const float4v*>(up + 4);
+#ifdef XEXP_NOSEQ
+                if (a.nb > 100)
+#endif
                 static_for<0, IB>([&](auto jc) {
                     constexpr int j = decltype(jc)::value;
                     auto step = [&](float4v(&cur)[2], float4v(&nxt)[2]) __attribute__((always_inline)) {
@@ -552,7 +592,12 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
             __syncthreads();
             // remaining columns of the block: w_c -= sum_i e_i U[jb+i][c], c >= jb + 32, on 32 x 32 tiles
             const int cs = jb + IB;
-            if (cs < SB) {
+#ifdef XEXP_NOMINI
+            if (cs < SB && a.nb > 100)
+#else
+            if (cs < SB)
+#endif
+            {
                 const int n_tiles = 2 * ((SB - cs) / 32);
                 for (int t = wave; t < n_tiles; t += 4) {
                     const int mt = t & 1, nt = t >> 1;
@@ -596,6 +641,9 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
             }
         };
         // transposed panel (k-major) for the far update; rows past d_out hold copies of the last row
+#ifdef XEXP_NOEPI
+        if (a.nb > 100)
+#endif
         for (int it = tid; it < SB * (ROWS / 8); it += 256) {
             const int c = it / (ROWS / 8), r8 = (it % (ROWS / 8)) * 8;
             const float ujj = sU[c * SB + c] * f_d;
@@ -607,7 +655,12 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
         }
         // MFMA A-operand fragments for this workgroup's own near updates: lane L of k-step ks, row tile mt holds
         // row mt*32 + L%32, columns ks*16 + 8 (L/32) + 0..7
-        if (b + 1 < a.nb) {
+#ifdef XEXP_NOEPI
+        if (a.nb > 100)
+#else
+        if (b + 1 < a.nb)
+#endif
+        {
             for (int it = tid; it < 8 * 2 * 64; it += 256) {
                 const int L = it & 63, row = ((it >> 6) & 1) * 32 + (L & 31), c0 = (it >> 7) * 16 + 8 * (L >> 5);
                 short8v dh, dl;
@@ -618,6 +671,9 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
             }
         }
         // W^ = s (q - z) and codes, original column order
+#ifdef XEXP_NOEPI
+        if (a.nb > 100)
+#endif
         for (int it = wave; it < ROWS / 2; it += 4) {
             const int rr = it * 2 + (lane >> 5), c4 = (lane & 31) * 4;
             const int gr = r0 + rr;
@@ -645,7 +701,9 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
                 }
             }
         }
-        __threadfence();   // the fragments written above are read back by other waves of this workgroup
+        // the fragments written above are read back by other waves of this workgroup (same CU, same L1): a
+        // workgroup-scope release, completed by the barrier at the top of the loop
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     }
     if (sl == 0 && row_ok) a.rowloss[grow] += lossacc;
 }
@@ -687,12 +745,22 @@ __global__ __launch_bounds__(256) void nearfrag_kernel(const float* __restrict__
 // from their maxima, whereas e and U themselves span the scale of 1 / sqrt(H_jj).
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void umax_kernel(const float* __restrict__ U, int n, Scalars* __restrict__ sc) {
-    const int j = blockIdx.x;   // one workgroup per row
-    const float dj = U[int64_t(j) * n + j];
-    float m = 0.f;
-    for (int k = j + 1 + threadIdx.x; k < n; k += 256) m = fmaxf(m, fabsf(U[int64_t(j) * n + k] / dj));
-    if (!(m < 3.0e38f)) m = 3.0e38f;   // NaN / inf from a failed factorization: keep the scalars finite
-    block_max_to(&sc->max_u_bits, m);
+    // max_k |U_jk / U_jj| = max_k |U_jk| / |U_jj| exactly: rounding a quotient is monotone in the numerator
+    float mm = 0.f;
+    for (int j = blockIdx.x; j < n; j += gridDim.x) {   // a workgroup per row, rows strided over the grid
+        const float* row = U + int64_t(j) * n;
+        float m = 0.f;
+        for (int k4 = ((j + 1) & ~3) + 4 * threadIdx.x; k4 < n; k4 += 1024) {
+            const float4v v = *reinterpret_cast<const float4v*>(row + k4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (k4 + e > j) m = fmaxf(m, fabsf(v[e]));
+        }
+        m = m / fabsf(row[j]);
+        if (!(m < 3.0e38f)) m = 3.0e38f;   // NaN / inf from a failed factorization: keep the scalars finite
+        mm = fmaxf(mm, m);
+    }
+    block_max_to(&sc->max_u_bits, mm);
 }
 
 __global__ void scale_kernel(Scalars* sc) {
@@ -713,13 +781,14 @@ __global__ __launch_bounds__(256) void split_kernel(const float* __restrict__ U,
                                                    uint16_t* __restrict__ Ul) {
     const int j = blockIdx.y;
     const int k4 = (blockIdx.x * 256 + threadIdx.x) * 4;
-    if (k4 >= n) return;
+    // the trailing updates read row j only beyond its 128-column block; the rest of Uh / Ul stays unwritten
+    if (k4 >= n || k4 < (j / SB + 1) * SB) return;
     const float4v v = *reinterpret_cast<const float4v*>(U + int64_t(j) * n + k4);
     const float dj = U[int64_t(j) * n + j], f_u = sc->f_u;
     short4v h4, l4;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        float x = (k4 + e > j) ? v[e] / dj * f_u : 0.f;
+        float x = v[e] / dj * f_u;
         x = fminf(fmaxf(x, -60000.f), 60000.f);
         const _Float16 h = (_Float16)x;
         const _Float16 lo = (_Float16)(x - (float)h);
@@ -1054,15 +1123,15 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
     SweepWs w = carve(workspace, d_out, d_in);
     hipLaunchKernelGGL(init_scalars_kernel, dim3(1), dim3(1), 0, stream, w.sc);
     ONECOMP_CHECK_LAUNCH();
-    dim3 lgrid{unsigned(d_out)};
+    dim3 lgrid{unsigned(d_out < 1024 ? d_out : 1024)};
     if (w_dtype == ONECOMP_BF16)
-        hipLaunchKernelGGL(load_kernel<uint16_t>, lgrid, dim3(256), 0, stream, static_cast<const uint16_t*>(W), d_in,
-                           perm, w.Wf, w.rowloss, w.sc);
+        hipLaunchKernelGGL(load_kernel<uint16_t>, lgrid, dim3(256), 0, stream, static_cast<const uint16_t*>(W), d_out,
+                           d_in, perm, w.Wf, w.rowloss, w.sc);
     else
-        hipLaunchKernelGGL(load_kernel<float>, lgrid, dim3(256), 0, stream, static_cast<const float*>(W), d_in, perm,
-                           w.Wf, w.rowloss, w.sc);
+        hipLaunchKernelGGL(load_kernel<float>, lgrid, dim3(256), 0, stream, static_cast<const float*>(W), d_out, d_in,
+                           perm, w.Wf, w.rowloss, w.sc);
     ONECOMP_CHECK_LAUNCH();
-    hipLaunchKernelGGL(umax_kernel, dim3(unsigned(d_in)), dim3(256), 0, stream, U,
+    hipLaunchKernelGGL(umax_kernel, dim3(unsigned(d_in < 1024 ? d_in : 1024)), dim3(256), 0, stream, U,
                        int(d_in), w.sc);
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(scale_kernel, dim3(1), dim3(1), 0, stream, w.sc);
