@@ -16,6 +16,10 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 ]
+# Per-source extras.  sweep.hip: keep MFMA accumulators in the architectural VGPRs.  With the 512-register budget
+# of a one-wave-per-SIMD kernel the compiler otherwise moves them to AGPRs and then serializes the loads that
+# initialize them (one wait per load), which more than doubles the time of a trailing-update tile.
+EXTRA_FLAGS = {"sweep.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _hipcc() -> str:
@@ -33,7 +37,7 @@ def build(verbose: bool = True) -> str:
 
     def compile_one(src):
         obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *HIPCC_FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")

@@ -398,8 +398,7 @@ constexpr int QUAD_SWAP1 = 1 | (0 << 2) | (3 << 4) | (2 << 6);   // lanes 0<->1,
 constexpr int QUAD_SWAP2 = 2 | (3 << 2) | (0 << 4) | (1 << 6);   // lanes 0<->2, 1<->3
 
 template <int GB>  // group width seen inside an inner block: 16 (G == 16) or 32 (G = 32, 64, 128)
-__global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
-    extern __shared__ __attribute__((aligned(1024))) char psm[];
+__device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, char* psm) {
     float* sU = reinterpret_cast<float*>(psm);   // SB x SB: U[j0 + j][j0 .. j0 + 127], filled by direct loads
     float* sW = sU + SB * SB;                    // ROWS x SP
     float* sE = sW + ROWS * SP;                  // ROWS x SP errors e
@@ -409,7 +408,7 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int r0 = blockIdx.x * ROWS;
+    const int r0 = wg * ROWS;
     const int64_t d_in = a.d_in;
     const int G = 1 << a.lgG;
     // sequential part: quad = row, lane in quad = slice of 8 columns
@@ -448,44 +447,45 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
                     const int rr = min(r0 + mt * 32 + (r / 4) * 8 + lr + (r % 4), a.d_out - 1);
                     acc[mt][r] = a.Wf[int64_t(rr) * d_in + j0 + 32 * wave + lc];
                 }
-#ifndef XEXP_NONEAR
             if (b > 0)
-#else
-            if (b > 100)
-#endif
             {
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[mt][r] *= f_all;
-                // rolling window of 8 k-steps (one source block) of operand fragments
-                uint4v win[8][6];
-                const uint4v* fh = reinterpret_cast<const uint4v*>(a.Fh) + int64_t(blockIdx.x) * 3 * 8 * 2 * 64 + lane;
-                const uint4v* fl = reinterpret_cast<const uint4v*>(a.Fl) + int64_t(blockIdx.x) * 3 * 8 * 2 * 64 + lane;
-                const uint4v* bh = reinterpret_cast<const uint4v*>(a.Bh) + (b * (b - 1) / 2) * 8 * 4 * 64 + wave * 64 + lane;
-                const uint4v* bl = reinterpret_cast<const uint4v*>(a.Bl) + (b * (b - 1) / 2) * 8 * 4 * 64 + wave * 64 + lane;
+                // rolling window of WIN k-steps of operand fragments (a source block has 8 k-steps)
+                constexpr int WIN = 4;
+                uint4v win[WIN][6];
+                // uniform base pointers + a 32-bit lane offset: the addresses stay in scalar registers
+                const uint4v* fh = reinterpret_cast<const uint4v*>(a.Fh) + int64_t(wg) * 3 * 8 * 2 * 64;
+                const uint4v* fl = reinterpret_cast<const uint4v*>(a.Fl) + int64_t(wg) * 3 * 8 * 2 * 64;
+                const uint4v* bh = reinterpret_cast<const uint4v*>(a.Bh) + (b * (b - 1) / 2) * 8 * 4 * 64 + wave * 64;
+                const uint4v* bl = reinterpret_cast<const uint4v*>(a.Bl) + (b * (b - 1) / 2) * 8 * 4 * 64 + wave * 64;
                 auto issue = [&](int bp, int ks, uint4v(&d)[6]) __attribute__((always_inline)) {
                     const int fo = (bp * 8 + ks) * 2 * 64, bo = (bp * 8 + ks) * 4 * 64;
-                    d[0] = fl[fo]; d[1] = fh[fo]; d[2] = fl[fo + 64]; d[3] = fh[fo + 64];
-                    d[4] = bh[bo]; d[5] = bl[bo];
+                    d[0] = (fl + fo)[lane]; d[1] = (fh + fo)[lane]; d[2] = (fl + fo + 64)[lane]; d[3] = (fh + fo + 64)[lane];
+                    d[4] = (bh + bo)[lane]; d[5] = (bl + bo)[lane];
                 };
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) issue(0, ks, win[ks]);
+                for (int ks = 0; ks < WIN; ++ks) issue(0, ks, win[ks]);
 #pragma unroll 1
                 for (int bp = 0; bp < b; ++bp) {
                     const bool more = bp + 1 < b;
 #pragma unroll
                     for (int ks = 0; ks < 8; ++ks) {
-                        const half8v al0 = __builtin_bit_cast(half8v, win[ks][0]), ah0 = __builtin_bit_cast(half8v, win[ks][1]);
-                        const half8v al1 = __builtin_bit_cast(half8v, win[ks][2]), ah1 = __builtin_bit_cast(half8v, win[ks][3]);
-                        const half8v bhv = __builtin_bit_cast(half8v, win[ks][4]), blv = __builtin_bit_cast(half8v, win[ks][5]);
+                        uint4v(&cur)[6] = win[ks % WIN];
+                        const half8v al0 = __builtin_bit_cast(half8v, cur[0]), ah0 = __builtin_bit_cast(half8v, cur[1]);
+                        const half8v al1 = __builtin_bit_cast(half8v, cur[2]), ah1 = __builtin_bit_cast(half8v, cur[3]);
+                        const half8v bhv = __builtin_bit_cast(half8v, cur[4]), blv = __builtin_bit_cast(half8v, cur[5]);
                         acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al0, bhv, acc[0], 0, 0, 0);
                         acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al1, bhv, acc[1], 0, 0, 0);
                         acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah0, blv, acc[0], 0, 0, 0);
                         acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah1, blv, acc[1], 0, 0, 0);
                         acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah0, bhv, acc[0], 0, 0, 0);
                         acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah1, bhv, acc[1], 0, 0, 0);
-                        if (more) issue(bp + 1, ks, win[ks]);
+                        // refill the slot just consumed: k-step ks + WIN of this source block or of the next
+                        if (ks + WIN < 8) issue(bp, ks + WIN, cur);
+                        else if (more) issue(bp + 1, ks + WIN - 8, cur);
                     }
                 }
 #pragma unroll
@@ -519,9 +519,6 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
                 const float* up = sU + jb * SB + jb + 8 * sl;
                 ua[0] = *reinterpret_cast<const float4v*>(up);
                 ua[1] = *reinterpret_cast<const float4v*>(up + 4);
-#ifdef XEXP_NOSEQ
-                if (a.nb > 100)
-#endif
                 static_for<0, IB>([&](auto jc) {
                     constexpr int j = decltype(jc)::value;
                     auto step = [&](float4v(&cur)[2], float4v(&nxt)[2]) __attribute__((always_inline)) {
@@ -592,11 +589,7 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
             __syncthreads();
             // remaining columns of the block: w_c -= sum_i e_i U[jb+i][c], c >= jb + 32, on 32 x 32 tiles
             const int cs = jb + IB;
-#ifdef XEXP_NOMINI
-            if (cs < SB && a.nb > 100)
-#else
             if (cs < SB)
-#endif
             {
                 const int n_tiles = 2 * ((SB - cs) / 32);
                 for (int t = wave; t < n_tiles; t += 4) {
@@ -641,9 +634,6 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
             }
         };
         // transposed panel (k-major) for the far update; rows past d_out hold copies of the last row
-#ifdef XEXP_NOEPI
-        if (a.nb > 100)
-#endif
         for (int it = tid; it < SB * (ROWS / 8); it += 256) {
             const int c = it / (ROWS / 8), r8 = (it % (ROWS / 8)) * 8;
             const float ujj = sU[c * SB + c] * f_d;
@@ -655,25 +645,18 @@ __global__ __launch_bounds__(256) void panel_kernel(PanelArgs a) {
         }
         // MFMA A-operand fragments for this workgroup's own near updates: lane L of k-step ks, row tile mt holds
         // row mt*32 + L%32, columns ks*16 + 8 (L/32) + 0..7
-#ifdef XEXP_NOEPI
-        if (a.nb > 100)
-#else
         if (b + 1 < a.nb)
-#endif
         {
             for (int it = tid; it < 8 * 2 * 64; it += 256) {
                 const int L = it & 63, row = ((it >> 6) & 1) * 32 + (L & 31), c0 = (it >> 7) * 16 + 8 * (L >> 5);
                 short8v dh, dl;
                 split8([&](int e) { return -sE[row * SP + c0 + e] * (sU[(c0 + e) * SB + c0 + e] * f_d); }, dh, dl);
-                const int64_t off = ((int64_t(blockIdx.x) * 3 + b) * (8 * 2 * 64) + it) * 8;
+                const int64_t off = ((int64_t(wg) * 3 + b) * (8 * 2 * 64) + it) * 8;
                 *reinterpret_cast<short8v*>(a.Fh + off) = dh;
                 *reinterpret_cast<short8v*>(a.Fl + off) = dl;
             }
         }
         // W^ = s (q - z) and codes, original column order
-#ifdef XEXP_NOEPI
-        if (a.nb > 100)
-#endif
         for (int it = wave; it < ROWS / 2; it += 4) {
             const int rr = it * 2 + (lane >> 5), c4 = (lane & 31) * 4;
             const int gr = r0 + rr;
@@ -826,8 +809,7 @@ constexpr int A_ROWB = TM * 2, B_ROWB = TN * 2;                     // bytes per
 constexpr int A_PANELB = KT * A_ROWB, B_PANELB = KT * B_ROWB;       // 4 KB, 8 KB
 constexpr int OFF_AH = 0, OFF_AL = A_PANELB, OFF_BH = 2 * A_PANELB, OFF_BL = 2 * A_PANELB + B_PANELB;
 constexpr int STAGEB = 2 * A_PANELB + 2 * B_PANELB;                 // 24 KB
-constexpr int NBUF = 3;
-constexpr size_t LDS_BYTES = size_t(NBUF) * STAGEB;                 // 72 KB: two workgroups per CU
+constexpr size_t LDS_BYTES = size_t(3) * STAGEB;                    // 72 KB with 3 slots: two workgroups per CU
 constexpr int BAND = 8;                                             // row tiles per band of the tile order
 }  // namespace tg
 
@@ -841,12 +823,11 @@ struct TrailArgs {
     int n_mt, n_nt, chunk;
 };
 
-__global__ __launch_bounds__(256, 2) void trailing_kernel(TrailArgs a) {
+template <int NBUF>   // slots of the LDS ring
+__device__ __forceinline__ void trailing_tile(const TrailArgs& a, const int bid, char* tl) {
     using namespace tg;
-    extern __shared__ __attribute__((aligned(1024))) char tl[];
-
     const int n_tiles = a.n_mt * a.n_nt;
-    const int v = (blockIdx.x & 7) * a.chunk + (blockIdx.x >> 3);
+    const int v = (bid & 7) * a.chunk + (bid >> 3);
     if (v >= n_tiles) return;
     const int band = min(v / (BAND * a.n_nt), (a.n_mt - 1) / BAND);
     const int rem = v - band * BAND * a.n_nt;
@@ -978,26 +959,26 @@ __global__ __launch_bounds__(256, 2) void trailing_kernel(TrailArgs a) {
         const int s1 = (s0 == NBUF - 1) ? 0 : s0 + 1, s2 = (s1 == NBUF - 1) ? 0 : s1 + 1;
         // Loads and fragment reads past the last k-step are not branched around: the loads get an empty
         // descriptor (they deposit zeros into a slot nobody reads again), the reads fetch stale data nobody uses.
-        {   // k-step kb from Fc; fragments of kb+1 -> FH; loads of kb+3 -> slot s0
-            const Desc d = make_desc(kb + 3, kb + 3 < n_kb);
+        {   // k-step kb from Fc; fragments of kb+1 -> FH; loads of kb+NBUF -> slot s0
+            const Desc d = make_desc(kb + NBUF, kb + NBUF < n_kb);
             const uint32_t dst = lds0 + s0 * STAGEB;
             const int sb = s1 * STAGEB;
             mma(Fc, [&](int i) __attribute__((always_inline)) {
                 if ((i & 1) == 0) rd(FH, i / 2, sb);
                 else if (i < 12) gload1(d, dst, i / 2);
             });
-            __builtin_amdgcn_s_waitcnt(wait_vmcnt(6));   // k-step kb+2 has landed
+            __builtin_amdgcn_s_waitcnt(wait_vmcnt(6 * (NBUF - 2)));   // k-step kb+2 has landed
             __syncthreads();
         }
-        {   // k-step kb+1 from FH; fragments of kb+2 -> Fc; loads of kb+4 -> slot s1
-            const Desc d = make_desc(kb + 4, kb + 4 < n_kb);
+        {   // k-step kb+1 from FH; fragments of kb+2 -> Fc; loads of kb+1+NBUF -> slot s1
+            const Desc d = make_desc(kb + 1 + NBUF, kb + 1 + NBUF < n_kb);
             const uint32_t dst = lds0 + s1 * STAGEB;
             const int sb = s2 * STAGEB;
             mma(FH, [&](int i) __attribute__((always_inline)) {
                 if ((i & 1) == 0) rd(Fc, i / 2, sb);
                 else if (i < 12) gload1(d, dst, i / 2);
             });
-            __builtin_amdgcn_s_waitcnt(wait_vmcnt(6));   // k-step kb+3 has landed
+            __builtin_amdgcn_s_waitcnt(wait_vmcnt(6 * (NBUF - 2)));   // k-step kb+3 has landed
             __syncthreads();
         }
         s0 = s2;
@@ -1027,6 +1008,23 @@ __global__ __launch_bounds__(256, 2) void trailing_kernel(TrailArgs a) {
     }
 }
 
+__global__ __launch_bounds__(256, 2) void trailing_kernel(TrailArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) char dyn_lds[];
+    trailing_tile<3>(a, blockIdx.x, dyn_lds);
+}
+
+// One launch = the panel sweep of a super-block next to the far update of the previous super-block on the
+// columns beyond the panel's.  The panel needs only 64 rows' worth of workgroups, far fewer than there are CUs, and
+// its workgroups are the first of the grid, so they are resident from the start; the update's tiles fill the other
+// CUs, and all of them once the panel is done.  The two parts touch disjoint columns of the working copy, and the
+// panel writes the residual panels of its own super-block into the buffer the update does not read.
+template <int GB>
+__global__ __launch_bounds__(256) void panel_far_kernel(PanelArgs pa, TrailArgs ta, int n_panel) {
+    extern __shared__ __attribute__((aligned(1024))) char dyn_lds[];
+    if (int(blockIdx.x) < n_panel) panel_body<GB>(pa, blockIdx.x, dyn_lds);
+    else trailing_tile<3>(ta, blockIdx.x - n_panel, dyn_lds);
+}
+
 // loss = sum of the per-row sums, fixed order.  One workgroup.
 __global__ __launch_bounds__(1024) void loss_kernel(const float* __restrict__ rowloss, int d_out,
                                                    float* __restrict__ loss) {
@@ -1044,8 +1042,8 @@ __global__ __launch_bounds__(1024) void loss_kernel(const float* __restrict__ ro
 
 struct SweepWs {
     float* Wf;        // [d_out x d_in] working copy, sweep order
-    uint16_t* Dh;     // [SBIG x ldD] scaled negated residuals of the current super-block, transposed, fp16 hi
-    uint16_t* Dl;     //                                                                               fp16 lo
+    uint16_t* Dh;     // 2 x [SBIG x ldD] scaled negated residuals of a super-block, transposed, fp16 hi; two buffers:
+    uint16_t* Dl;     // one is read by the far update while the next super-block fills the other       fp16 lo
     uint16_t* Uh;     // [d_in x d_in] scaled rows U_jk / U_jj, fp16 hi
     uint16_t* Ul;     //                                        fp16 lo
     float* rowloss;   // [d_out]
@@ -1064,8 +1062,8 @@ SweepWs carve(void* ws, int64_t d_out, int64_t d_in) {
     char* p = static_cast<char*>(ws);
     SweepWs w;
     w.Wf = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * d_in * sizeof(float), 256);
-    w.Dh = reinterpret_cast<uint16_t*>(p); p += size_t(SBIG) * ld_d(d_out) * 2;
-    w.Dl = reinterpret_cast<uint16_t*>(p); p += size_t(SBIG) * ld_d(d_out) * 2;
+    w.Dh = reinterpret_cast<uint16_t*>(p); p += 2 * size_t(SBIG) * ld_d(d_out) * 2;
+    w.Dl = reinterpret_cast<uint16_t*>(p); p += 2 * size_t(SBIG) * ld_d(d_out) * 2;
     w.Uh = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(d_in) * d_in * 2, 256);
     w.Ul = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(d_in) * d_in * 2, 256);
     w.rowloss = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * sizeof(float), 256);
@@ -1079,15 +1077,17 @@ SweepWs carve(void* ws, int64_t d_out, int64_t d_in) {
 }
 
 template <int GB>
-onecomp_status launch_panel(const PanelArgs& a, hipStream_t stream) {
+onecomp_status launch_panel(const PanelArgs& pa, const TrailArgs& ta, int far_wgs, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&panel_kernel<GB>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&panel_far_kernel<GB>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, PANEL_LDS) != hipSuccess)
             return ONECOMP_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL(panel_kernel<GB>, dim3(unsigned(ceil_div(a.d_out, ROWS))), dim3(256), PANEL_LDS, stream, a);
+    const int n_panel = int(ceil_div(pa.d_out, ROWS));
+    hipLaunchKernelGGL(panel_far_kernel<GB>, dim3(unsigned(n_panel + far_wgs)), dim3(256), PANEL_LDS, stream, pa, ta,
+                       n_panel);
     ONECOMP_CHECK_LAUNCH();
     return ONECOMP_OK;
 }
@@ -1111,7 +1111,7 @@ onecomp_status launch_block(const BlockArgs& a, hipStream_t stream) {
 
 size_t sweep_workspace_bytes(int64_t d_out, int64_t d_in, int block) {
     (void)block;
-    return align_up(size_t(d_out) * d_in * sizeof(float), 256) + 2 * size_t(SBIG) * ld_d(d_out) * 2 +
+    return align_up(size_t(d_out) * d_in * sizeof(float), 256) + 4 * size_t(SBIG) * ld_d(d_out) * 2 +
            2 * align_up(size_t(d_in) * d_in * 2, 256) + align_up(size_t(d_out) * sizeof(float), 256) +
            2 * size_t(ceil_div(d_out, ROWS)) * F_PER_WG + 2 * size_t(ceil_div(d_in, SBIG)) * B_PER_SB + 256;
 }
@@ -1149,41 +1149,60 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
     }
     TrailArgs t;
     t.Wf = w.Wf; t.Dh = w.Dh; t.Dl = w.Dl; t.Uh = w.Uh; t.Ul = w.Ul; t.sc = w.sc;
+    t.ek = 0; t.K = 0; t.u0 = 0; t.c0 = 0; t.c1 = 0; t.n_nt = 0; t.chunk = 0;
     t.d_out = int(d_out); t.ldD = int(ld_d(d_out)); t.d_in = int(d_in);
     t.n_mt = int(ceil_div(d_out, tg::TM));
-    auto trailing = [&](int ek, int K, int u0, int c0, int c1) -> onecomp_status {
-        if (c1 <= c0) return ONECOMP_OK;
+    // fills t for Wf[:, c0 .. c1) += residual columns ek .. ek+K of buffer `buf` times rows u0 .. u0+K of Un;
+    // returns the number of workgroups (0: nothing to do)
+    const size_t d_buf = size_t(SBIG) * ld_d(d_out);
+    auto set_trailing = [&](int buf, int ek, int K, int u0, int c0, int c1) -> int {
+        if (c1 <= c0) return 0;
+        t.Dh = w.Dh + buf * d_buf; t.Dl = w.Dl + buf * d_buf;
         t.ek = ek; t.K = K; t.u0 = u0; t.c0 = c0; t.c1 = c1;
         t.n_nt = int(ceil_div(c1 - c0, tg::TN));
         t.chunk = int(ceil_div(int64_t(t.n_mt) * t.n_nt, 8));
-        hipLaunchKernelGGL(trailing_kernel, dim3(unsigned(t.chunk) * 8), dim3(256), tg::LDS_BYTES, stream, t);
+        return t.chunk * 8;
+    };
+    auto trailing = [&](int buf, int ek, int K, int u0, int c0, int c1) -> onecomp_status {
+        const int wgs = set_trailing(buf, ek, K, u0, c0, c1);
+        if (wgs == 0) return ONECOMP_OK;
+        hipLaunchKernelGGL(trailing_kernel, dim3(unsigned(wgs)), dim3(256), tg::LDS_BYTES, stream, t);
         ONECOMP_CHECK_LAUNCH();
         return ONECOMP_OK;
     };
 
     onecomp_status st;
     if (group_size <= SB) {
-        // Groups no wider than a block: one panel launch sweeps a super-block (the feedback between its blocks is
-        // applied inside the kernel), then the columns beyond it are updated once with K = its width.
+        // Groups no wider than a block: one launch sweeps a super-block of 512 columns (the feedback between its
+        // blocks is applied inside the panel kernel).  The columns beyond a super-block receive its feedback once,
+        // with K = its width: first those of the next super-block, then, in the same launch as the next panel,
+        // the rest.
         hipLaunchKernelGGL(nearfrag_kernel, dim3(6, unsigned(ceil_div(d_in, SBIG))), dim3(256), 0, stream, U, int(d_in),
                            w.sc, w.Bh, w.Bl);
         ONECOMP_CHECK_LAUNCH();
         PanelArgs pa;
         pa.Wf = w.Wf; pa.U = U; pa.perm = perm; pa.Q = Q; pa.scales = scales; pa.zeros = zeros; pa.W_hat = W_hat;
-        pa.Dh = w.Dh; pa.Dl = w.Dl; pa.Fh = w.Fh; pa.Fl = w.Fl; pa.sc = w.sc; pa.rowloss = w.rowloss;
+        pa.Fh = w.Fh; pa.Fl = w.Fl; pa.sc = w.sc; pa.rowloss = w.rowloss;
         pa.d_out = int(d_out); pa.d_in = int(d_in); pa.n_g = int(d_in / group_size); pa.ldD = int(ld_d(d_out));
         pa.lgG = 0;
         while ((1 << pa.lgG) < group_size) ++pa.lgG;
         pa.qmax = float((1 << bits) - 1);
+        int buf = 0, p0 = 0, p1 = 0;   // previous super-block: residual buffer and column range
         for (int s0 = 0; s0 < d_in; s0 += SBIG) {
             const int s1 = int(d_in < int64_t(s0) + SBIG ? d_in : int64_t(s0) + SBIG);
+            int far_wgs = 0;
+            if (s0 > 0) {
+                if ((st = trailing(buf ^ 1, 0, p1 - p0, p0, s0, s1)) != ONECOMP_OK) return st;
+                far_wgs = set_trailing(buf ^ 1, 0, p1 - p0, p0, s1, int(d_in));
+            }
             pa.s0 = s0; pa.nb = (s1 - s0) / SB;
+            pa.Dh = w.Dh + buf * d_buf; pa.Dl = w.Dl + buf * d_buf;
             pa.Bh = w.Bh + size_t(s0 / SBIG) * (B_PER_SB / 2);
             pa.Bl = w.Bl + size_t(s0 / SBIG) * (B_PER_SB / 2);
-            if (group_size == 16) st = launch_panel<16>(pa, stream);
-            else st = launch_panel<32>(pa, stream);
+            if (group_size == 16) st = launch_panel<16>(pa, t, far_wgs, stream);
+            else st = launch_panel<32>(pa, t, far_wgs, stream);
             if (st != ONECOMP_OK) return st;
-            if ((st = trailing(0, s1 - s0, s0, s1, int(d_in))) != ONECOMP_OK) return st;
+            buf ^= 1; p0 = s0; p1 = s1;
         }
     } else {
         // Groups wider than a block: a group's parameters need the current values of all its columns when the
@@ -1208,9 +1227,9 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
                 a.j0 = j0;
                 a.e_col = j0 - s0;
                 if ((st = launch_block<32>(a, stream)) != ONECOMP_OK) return st;
-                if ((st = trailing(j0 - s0, SB, j0, j0 + SB, s1)) != ONECOMP_OK) return st;
+                if ((st = trailing(0, j0 - s0, SB, j0, j0 + SB, s1)) != ONECOMP_OK) return st;
             }
-            if ((st = trailing(0, s1 - s0, s0, s1, int(d_in))) != ONECOMP_OK) return st;
+            if ((st = trailing(0, 0, s1 - s0, s0, s1, int(d_in))) != ONECOMP_OK) return st;
             s0 = s1;
         }
     }
