@@ -105,7 +105,11 @@ onecomp_status onecomp_hessian_factor(const float* H, int64_t d_in, float damp, 
  *     z = clamp(rne(-min / s), 0, 2^bits - 1)
  *   q_j = clamp(rne(w_j / s) + z, 0, 2^bits - 1),  w^_j = s (q_j - z)
  *   e_j = (w_j - w^_j) / U_jj,   w_k -= e_j U_jk  for all later columns k
- * rne = round half to even.  All arithmetic is fp32.
+ * rne = round half to even.  Arithmetic: fp32.  w_j / s and the division by U_jj are multiplications by
+ * correctly rounded reciprocals.  Feedback that crosses a 128-column block is accumulated as
+ * (w_j - w^_j) * (U_jk / U_jj) with both factors rounded to 22 significant bits (two fp16 halves after an
+ * exact power-of-two scaling taken from max |W| and max |U_jk / U_jj|) and the sum kept in fp32; a residual
+ * above 8 max|W|, which no sweep of a sane layer produces, would saturate.
  *
  *   W          [d_out x d_in] row-major (dense, stride d_in), dtype w_dtype, ORIGINAL column order. Read only.
  *   U          [d_in x d_in] fp32, as written by onecomp_hessian_factor. Read only.
@@ -123,7 +127,9 @@ onecomp_status onecomp_hessian_factor(const float* H, int64_t d_in, float damp, 
  *   loss       device fp32 scalar, out: sum of e^2 over the layer, which equals
  *              tr((W - W^) H_d (W - W^)^T) for the damped (permuted) matrix behind U (Eq. (layerwise)).
  *              Reduced in a fixed order (bit-wise reproducible).
- *   workspace  device scratch, >= onecomp_quantize_workspace_bytes(d_out, d_in, block_size), 256-byte aligned.
+ *   workspace  device scratch, >= onecomp_quantize_workspace_bytes(d_out, d_in, block_size), 256-byte aligned
+ *              (about 4 d_out d_in + 4 d_in^2 bytes: fp32 working copy of W, two fp16 halves of the scaled U).
+ *   d_in       at most 65535, d_out at most 2^24.
  */
 onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
                                       const float* U, const int32_t* perm,
