@@ -104,8 +104,17 @@ __global__ __launch_bounds__(256) void output_kernel(const double* __restrict__ 
 // workgroup barrier), rows below it are solved one thread per row in registers, the trailing part gets a
 // rank-16 update.  Square roots and reciprocals come from v_rsq_f64 plus two Newton steps.
 // ------------------------------------------------------------------------------------------
-constexpr int DP = NB + 1;   // LDS pitch in doubles
 constexpr int SBW = 16;      // sub-block width
+// LDS layout of the block: only the sub-blocks on and below the diagonal are stored, 16 x 16 each with a row
+// pitch of 17 doubles, block row after block row (36 sub-blocks, 78 KB): small enough for two workgroups per CU,
+// so the factorization can share a launch with GEMM tiles.
+constexpr int SBP = SBW + 1;
+constexpr int SBS = SBW * SBP;
+constexpr int POTRF_LDS_DOUBLES = (NB / SBW) * (NB / SBW + 1) / 2 * SBS + NB;   // + NB reciprocal diagonal entries
+__device__ __forceinline__ int tri(int r, int c) {   // element (r, c), c / 16 <= r / 16
+    const int rb = r >> 4, cb = c >> 4;
+    return ((rb * (rb + 1)) / 2 + cb) * SBS + (r & 15) * SBP + (c & 15);
+}
 
 __device__ inline double rsqrt_refined(double p) {
     double y = __builtin_amdgcn_rsq(p);
@@ -115,18 +124,22 @@ __device__ inline double rsqrt_refined(double p) {
     return y;
 }
 
-__global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A, double* __restrict__ V, int n,
-                                                        int off, int bs, int32_t* __restrict__ info) {
-    extern __shared__ double S[];          // NB x DP matrix, then NB reciprocal diagonal entries
-    double* dinv = S + NB * DP;
+// S: POTRF_LDS_DOUBLES doubles of LDS.  preloaded: the block (lower sub-blocks, identity padding beyond bs) is
+// already in S and a barrier has been passed.
+__device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __restrict__ V, int n, int off, int bs,
+                                           int32_t* __restrict__ info, double* S, bool preloaded) {
+    double* dinv = S + POTRF_LDS_DOUBLES - NB;
     const int tid = threadIdx.x;
-    for (int e = tid; e < NB * NB; e += 256) {
-        const int r = e / NB, c = e % NB;
-        double v = (r == c) ? 1.0 : 0.0;   // identity padding for a short last block
-        if (r < bs && c < bs) v = A[int64_t(off + r) * n + off + c];
-        S[r * DP + c] = v;
+    if (!preloaded) {
+        for (int e = tid; e < NB * NB; e += 256) {
+            const int r = e / NB, c = e % NB;
+            if ((c >> 4) > (r >> 4)) continue;
+            double v = (r == c) ? 1.0 : 0.0;   // identity padding for a short last block
+            if (r < bs && c < bs) v = A[int64_t(off + r) * n + off + c];
+            S[tri(r, c)] = v;
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     // ---------------- Cholesky, 8 panels of 16 columns ----------------
     for (int c0 = 0; c0 < NB; c0 += SBW) {
@@ -138,7 +151,7 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A,
             double r[SBW];
             double my_dinv = 1.0;
 #pragma unroll
-            for (int c = 0; c < SBW; ++c) r[c] = S[(c0 + i) * DP + c0 + c];
+            for (int c = 0; c < SBW; ++c) r[c] = S[tri(c0 + i, c0 + c)];
 #pragma unroll
             for (int j = 0; j < SBW; ++j) {
                 double p = r[j];                       // meaningful in lane j only
@@ -165,7 +178,7 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A,
                 dinv[c0 + i] = my_dinv;
 #pragma unroll
                 for (int c = 0; c < SBW; ++c)
-                    if (c <= i) S[(c0 + i) * DP + c0 + c] = r[c];
+                    if (c <= i) S[tri(c0 + i, c0 + c)] = r[c];
             }
         }
         __syncthreads();
@@ -175,16 +188,16 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A,
             if (i < NB) {
                 double x[SBW];
 #pragma unroll
-                for (int c = 0; c < SBW; ++c) x[c] = S[i * DP + c0 + c];
+                for (int c = 0; c < SBW; ++c) x[c] = S[tri(i, c0 + c)];
 #pragma unroll
                 for (int j = 0; j < SBW; ++j) {
                     double acc = x[j];
 #pragma unroll
-                    for (int m = 0; m < j; ++m) acc = __builtin_fma(-x[m], S[(c0 + j) * DP + c0 + m], acc);
+                    for (int m = 0; m < j; ++m) acc = __builtin_fma(-x[m], S[tri(c0 + j, c0 + m)], acc);
                     x[j] = acc * dinv[c0 + j];
                 }
 #pragma unroll
-                for (int c = 0; c < SBW; ++c) S[i * DP + c0 + c] = x[c];
+                for (int c = 0; c < SBW; ++c) S[tri(i, c0 + c)] = x[c];
             }
         }
         __syncthreads();
@@ -194,12 +207,12 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A,
             for (int i = t0 + (tid >> 4); i < NB; i += 16) {
                 double li[SBW];
 #pragma unroll
-                for (int m = 0; m < SBW; ++m) li[m] = S[i * DP + c0 + m];
+                for (int m = 0; m < SBW; ++m) li[m] = S[tri(i, c0 + m)];
                 for (int c = t0 + (tid & 15); c <= i; c += 16) {
-                    double acc = S[i * DP + c];
+                    double acc = S[tri(i, c)];
 #pragma unroll
-                    for (int m = 0; m < SBW; ++m) acc = __builtin_fma(-li[m], S[c * DP + c0 + m], acc);
-                    S[i * DP + c] = acc;
+                    for (int m = 0; m < SBW; ++m) acc = __builtin_fma(-li[m], S[tri(c, c0 + m)], acc);
+                    S[tri(i, c)] = acc;
                 }
             }
         }
@@ -207,7 +220,7 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A,
     }
     for (int e = tid; e < bs * NB; e += 256) {
         const int r = e / NB, c = e % NB;
-        if (c <= r) A[int64_t(off + r) * n + off + c] = S[r * DP + c];
+        if (c <= r) A[int64_t(off + r) * n + off + c] = S[tri(r, c)];
     }
     __syncthreads();
 
@@ -222,7 +235,7 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A,
                 double acc = (i == c) ? 1.0 : 0.0;
 #pragma unroll
                 for (int m = 0; m < i; ++m)
-                    if (m >= c) acc = __builtin_fma(-S[(b0 + i) * DP + b0 + m], x[m], acc);
+                    if (m >= c) acc = __builtin_fma(-S[tri(b0 + i, b0 + m)], x[m], acc);
                 x[i] = (i >= c) ? acc * dinv[b0 + i] : 0.0;
             }
         }
@@ -230,7 +243,7 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A,
         if (tid < NB) {
 #pragma unroll
             for (int i = 0; i < SBW; ++i)
-                if (i >= c) S[(b0 + i) * DP + b0 + c] = x[i];
+                if (i >= c) S[tri(b0 + i, b0 + c)] = x[i];
         }
         __syncthreads();
     }
@@ -246,7 +259,7 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A,
             if (e < n_out) {
                 const int r = e / i0, c = e % i0;          // row i0 + r, column c
                 double acc = 0.0;                          // X[m][c] is zero for m < c
-                for (int m = c; m < i0; ++m) acc = __builtin_fma(S[(i0 + r) * DP + m], S[m * DP + c], acc);
+                for (int m = c; m < i0; ++m) acc = __builtin_fma(S[tri(i0 + r, m)], S[tri(m, c)], acc);
                 t[q] = acc;
             }
         }
@@ -254,7 +267,7 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A,
 #pragma unroll
         for (int q = 0; q < 7; ++q) {
             const int e = tid + 256 * q;
-            if (e < n_out) S[(i0 + e / i0) * DP + e % i0] = t[q];
+            if (e < n_out) S[tri(i0 + e / i0, e % i0)] = t[q];
         }
         __syncthreads();
 #pragma unroll
@@ -266,7 +279,7 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A,
                 double acc = 0.0;
 #pragma unroll
                 for (int m = 0; m < SBW; ++m)
-                    if (m <= r) acc = __builtin_fma(S[(i0 + r) * DP + i0 + m], S[(i0 + m) * DP + c], acc);
+                    if (m <= r) acc = __builtin_fma(S[tri(i0 + r, i0 + m)], S[tri(i0 + m, c)], acc);
                 t[q] = -acc;
             }
         }
@@ -274,13 +287,13 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A,
 #pragma unroll
         for (int q = 0; q < 7; ++q) {
             const int e = tid + 256 * q;
-            if (e < n_out) S[(i0 + e / i0) * DP + e % i0] = t[q];
+            if (e < n_out) S[tri(i0 + e / i0, e % i0)] = t[q];
         }
         __syncthreads();
     }
     for (int e = tid; e < bs * bs; e += 256) {
         const int r = e / bs, c = e % bs;
-        V[int64_t(off + r) * n + off + c] = (c <= r) ? S[r * DP + c] : 0.0;
+        V[int64_t(off + r) * n + off + c] = (c <= r) ? S[tri(r, c)] : 0.0;
     }
 }
 
@@ -307,20 +320,32 @@ struct GemmArgs {
     int flags;
 };
 
-__global__ __launch_bounds__(256, 2) void dgemm_kernel(GemmArgs g) {
-    __shared__ double sA[2][GT * GPA];
-    __shared__ double sB[2][GSB];
-    const int z = blockIdx.z;
+constexpr int GEMM_LDS_DOUBLES = 2 * GT * GPA + 2 * GSB;
+constexpr int LDS_DOUBLES = GEMM_LDS_DOUBLES > POTRF_LDS_DOUBLES ? GEMM_LDS_DOUBLES : POTRF_LDS_DOUBLES;
+
+// The workgroup's LDS: one static array per kernel, shared by the GEMM tile code and the factorization code.
+__device__ __forceinline__ double* wg_lds() {
+    __shared__ double lds[LDS_DOUBLES];
+    return lds;
+}
+
+// One 128 x 128 tile (tm, tn) of batch entry z.  tri_out: the finished tile is also left in LDS (from its start,
+// over the dead operand tiles) in the layout of potrf_body (lower sub-blocks, identity beyond the matrix edge),
+// for a diagonal tile that the same workgroup factors next.
+template <bool bt>   // B is given transposed (n x k, k contiguous)
+__device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, const int tm, const int z,
+                                           const bool tri_out) {
+    double* lds = wg_lds();
+    double(*sA)[GT * GPA] = reinterpret_cast<double(*)[GT * GPA]>(lds);
+    double(*sB)[GSB] = reinterpret_cast<double(*)[GSB]>(lds + 2 * GT * GPA);
     const bool last = (z == g.batch - 1);
     const int m = last ? g.m_last : g.m;
     const int kdim = last ? g.k_last : g.k;
-    const int tm = blockIdx.y, tn = blockIdx.x;
     if (tm * GT >= m) return;
     if ((g.flags & G_CLOWER) && tn > tm) return;
     const double* __restrict__ A = g.A + z * g.sa;
     const double* __restrict__ B = g.B + z * g.sb;
     double* __restrict__ C = g.C + z * g.sc;
-    const bool bt = g.flags & G_BTRANS;
     int k_lo = 0, k_hi = kdim;
     if (g.flags & G_BLOWER) k_lo = tn * GT;
     if (g.flags & G_ALOWER) k_hi = min(kdim, (tm + 1) * GT);
@@ -382,18 +407,36 @@ __global__ __launch_bounds__(256, 2) void dgemm_kernel(GemmArgs g) {
     // accumulators start as beta * C (register r of lane l: row 4 r + l / 16, column l % 16 of its 16 x 16 tile),
     // so the C tile is in flight together with the first operand tiles
     double4v acc[4][4];
+    const bool full = (m0 + GT <= m) && (n0 + GT <= g.n);   // uniform: interior tiles need no per-element masks
+    double* __restrict__ ct = C + int64_t(m0 + wr * 64 + lk) * g.ldc + n0 + wc * 64 + l16;
+    if (g.beta == 0.0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
-                const int col = n0 + wc * 64 + j * 16 + l16;
-                double c = 0.0;
-                if (g.beta != 0.0 && row < m && col < g.n) c = g.beta * C[int64_t(row) * g.ldc + col];
-                acc[i][j][r] = c;
-            }
+                for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0;
+    } else if (full) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[i][j][r] = g.beta * ct[int64_t(i * 16 + 4 * r) * g.ldc + j * 16];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
+                    const int col = n0 + wc * 64 + j * 16 + l16;
+                    double c = 0.0;
+                    if (row < m && col < g.n) c = g.beta * C[int64_t(row) * g.ldc + col];
+                    acc[i][j][r] = c;
+                }
+    }
 
     if (k_lo < k_hi) lstore(0);
     __syncthreads();
@@ -422,24 +465,69 @@ __global__ __launch_bounds__(256, 2) void dgemm_kernel(GemmArgs g) {
     }
 
     // accumulator register r of lane l: row 4 r + l / 16, column l % 16 of its 16 x 16 tile
+    if (full) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
-                const int col = n0 + wc * 64 + j * 16 + l16;
-                if (row < m && col < g.n) {
-                    C[int64_t(row) * g.ldc + col] = acc[i][j][r];
+                for (int r = 0; r < 4; ++r) ct[int64_t(i * 16 + 4 * r) * g.ldc + j * 16] = acc[i][j][r];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
+                    const int col = n0 + wc * 64 + j * 16 + l16;
+                    if (row < m && col < g.n) C[int64_t(row) * g.ldc + col] = acc[i][j][r];
                 }
-            }
+    }
+    if (tri_out) {   // uniform; the K loop ended with a barrier, so the operand tiles are dead
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int lrow = wr * 64 + i * 16 + 4 * r + lk, lcol = wc * 64 + j * 16 + l16;
+                    if ((lcol >> 4) > (lrow >> 4)) continue;
+                    const bool inside = (m0 + lrow < m) && (n0 + lcol < g.n);
+                    lds[tri(lrow, lcol)] = inside ? acc[i][j][r] : (lrow == lcol ? 1.0 : 0.0);
+                }
+    }
+}
+
+template <bool bt>
+__global__ __launch_bounds__(256, 2) void dgemm_kernel(GemmArgs g) {
+    dgemm_tile<bt>(g, blockIdx.x, blockIdx.y, blockIdx.z, false);
+}
+
+__global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A, double* __restrict__ V, int n,
+                                                        int off, int bs, int32_t* __restrict__ info) {
+    potrf_body(A, V, n, off, bs, info, wg_lds(), false);
+}
+
+// Trailing update of one step of the blocked Cholesky together with the factorization of the next diagonal block:
+// workgroup (0, 0), the first of the grid and therefore resident from the start, computes the updated diagonal
+// tile, keeps it in LDS and factors / inverts it while the other workgroups update the rest of the trailing
+// matrix.  Takes the single-workgroup factorization off the critical path of every step whose update is longer.
+__global__ __launch_bounds__(256, 2) void syrk_potrf_kernel(GemmArgs g, double* __restrict__ A, double* __restrict__ V,
+                                                           int n, int off, int bs, int32_t* __restrict__ info) {
+    const bool first = (blockIdx.x == 0 && blockIdx.y == 0);
+    dgemm_tile<true>(g, blockIdx.x, blockIdx.y, 0, first);
+    if (first) {
+        __syncthreads();
+        potrf_body(A, V, n, off, bs, info, wg_lds(), true);
+    }
 }
 
 onecomp_status dgemm(const GemmArgs& g, hipStream_t stream) {
     if (g.m <= 0 || g.n <= 0 || g.batch <= 0) return ONECOMP_OK;
     dim3 grid(unsigned(ceil_div(g.n, GT)), unsigned(ceil_div(g.m, GT)), unsigned(g.batch));
-    hipLaunchKernelGGL(dgemm_kernel, grid, dim3(256), 0, stream, g);
+    if (g.flags & G_BTRANS) hipLaunchKernelGGL(dgemm_kernel<true>, grid, dim3(256), 0, stream, g);
+    else hipLaunchKernelGGL(dgemm_kernel<false>, grid, dim3(256), 0, stream, g);
     ONECOMP_CHECK_LAUNCH();
     return ONECOMP_OK;
 }
@@ -491,22 +579,14 @@ onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_orde
                        w.perm, w.dfix, w.lam, w.A);
     ONECOMP_CHECK_LAUNCH();
 
-    static bool attr_set = false;
-    const size_t potrf_lds = (size_t(NB) * DP + NB) * sizeof(double);
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&potrf_diag_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(potrf_lds)) != hipSuccess)
-            return ONECOMP_ERR_HIP;
-        attr_set = true;
-    }
-
     // ---- blocked right-looking Cholesky of A (lower) ----
+    // diagonal block 0 on its own; every later one inside the launch that updates the trailing matrix before it
     const int nblk = int(ceil_div(n, NB));
+    hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), 0, stream, w.A, w.V, n, 0, min(NB, n), info);
+    ONECOMP_CHECK_LAUNCH();
     for (int kb = 0; kb < nblk; ++kb) {
         const int off = kb * NB;
         const int bs = min(NB, n - off);
-        hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), potrf_lds, stream, w.A, w.V, n, off, bs, info);
-        ONECOMP_CHECK_LAUNCH();
         const int rest = n - off - bs;
         if (rest <= 0) break;
         // panel: A[off+bs:, off:off+bs] <- A[off+bs:, off:off+bs] * Linv_kk^T   (in place, one column tile)
@@ -524,7 +604,13 @@ onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_orde
         s.C = w.A + int64_t(off + bs) * n + (off + bs); s.ldc = n; s.sc = 0;
         s.m = rest; s.m_last = rest; s.n = rest; s.k = bs; s.k_last = bs; s.batch = 1;
         s.alpha = -1.0; s.beta = 1.0; s.flags = G_BTRANS | G_CLOWER;
-        if ((st = dgemm(s, stream)) != ONECOMP_OK) return st;
+        {
+            const int off1 = off + bs;
+            dim3 grid(unsigned(ceil_div(rest, GT)), unsigned(ceil_div(rest, GT)), 1);
+            hipLaunchKernelGGL(syrk_potrf_kernel, grid, dim3(256), 0, stream, s, w.A, w.V, n, off1, min(NB, n - off1),
+                               info);
+            ONECOMP_CHECK_LAUNCH();
+        }
     }
 
     // ---- V = L^-1 by recursive doubling over aligned block pairs ----
