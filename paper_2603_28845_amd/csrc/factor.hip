@@ -16,6 +16,7 @@
 //     ~2 log2(n/128) large launches instead of n/128 skinny ones.
 //   * ordering by rank counting (stable, deterministic), no floating-point atomics anywhere.
 #include "common.hpp"
+#include <type_traits>
 
 namespace onecomp {
 namespace {
@@ -95,26 +96,34 @@ __global__ __launch_bounds__(256) void output_kernel(const double* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------
-// diagonal block: Cholesky in LDS, then in-place triangular inverse.  One workgroup of 256 threads.
+// diagonal block: Cholesky in LDS, then in-place triangular inverse.  One workgroup of 256 threads (4 waves).
 // A block (bs x bs, bs <= 128) at A + off*(n+1); L written back to A (lower part), L^-1 to V (full block,
 // zeros above the diagonal).  A non-positive pivot sets *info (first one wins) and is replaced by 1.
 //
-// Both halves work on 16-wide sub-blocks so that the number of workgroup barriers is ~60 instead of one or
-// more per column: the 16 x 16 diagonal sub-block is factored by a single wave (in-order LDS traffic, no
-// workgroup barrier), rows below it are solved one thread per row in registers, the trailing part gets a
-// rank-16 update.  Square roots and reciprocals come from v_rsq_f64 plus two Newton steps.
+// The block lives in LDS as 16 x 16 sub-blocks (only those on and below the diagonal, 36 of them, row pitch 17
+// doubles, 78 KB: small enough for two workgroups per CU, so the factorization can share a launch with GEMM
+// tiles).  Everything but the 16 x 16 leaves runs on v_mfma_f64_16x16x4_f64 with sub-blocks as operands:
+//   Cholesky, block column J:  leaf factorization of (J,J) by one wave in registers (pivot and column
+//     broadcasts by DPP row_newbcast, square roots from v_rsq_f64 + two Newton steps);  T = L_JJ^-1 (one thread
+//     per column);  L_IJ = A_IJ T^T for the sub-blocks below;  A_IK -= L_IJ L_KJ^T for J < K <= I.
+//   Inverse:  leaf inverses of the 8 diagonal sub-blocks, then recursive doubling over aligned pairs of
+//     s = 16, 32, 64:  X[C,A] = -X[C,C] (L[C,A] X[A,A]), both products in place: the first by sub-block rows
+//     (a wave holds its row of L[C,A] in registers while it overwrites it), the second by sub-block columns.
+//     Every level has exactly four row / column tasks: one per wave.
+// MFMA operand layouts (lane l): A[i][k]: i = l % 16, k = l / 16;  B[k][j]: k = l / 16, j = l % 16;
+// C/D register r: row 4 r + l / 16, column l % 16.
 // ------------------------------------------------------------------------------------------
 constexpr int SBW = 16;      // sub-block width
-// LDS layout of the block: only the sub-blocks on and below the diagonal are stored, 16 x 16 each with a row
-// pitch of 17 doubles, block row after block row (36 sub-blocks, 78 KB): small enough for two workgroups per CU,
-// so the factorization can share a launch with GEMM tiles.
 constexpr int SBP = SBW + 1;
 constexpr int SBS = SBW * SBP;
-constexpr int POTRF_LDS_DOUBLES = (NB / SBW) * (NB / SBW + 1) / 2 * SBS + NB;   // + NB reciprocal diagonal entries
+constexpr int NSB = NB / SBW;
+// sub-blocks + one 16 x 16 buffer for the leaf inverse + NB reciprocal diagonal entries
+constexpr int POTRF_LDS_DOUBLES = NSB * (NSB + 1) / 2 * SBS + SBS + NB;
 __device__ __forceinline__ int tri(int r, int c) {   // element (r, c), c / 16 <= r / 16
     const int rb = r >> 4, cb = c >> 4;
     return ((rb * (rb + 1)) / 2 + cb) * SBS + (r & 15) * SBP + (c & 15);
 }
+__device__ __forceinline__ int sub(int I, int J) { return ((I * (I + 1)) / 2 + J) * SBS; }   // J <= I
 
 __device__ inline double rsqrt_refined(double p) {
     double y = __builtin_amdgcn_rsq(p);
@@ -124,12 +133,32 @@ __device__ inline double rsqrt_refined(double p) {
     return y;
 }
 
+// value of lane J of every 16-lane row, in all lanes of the row
+template <int J>
+__device__ __forceinline__ double bcast16(double v) {
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, 0x150 + J, 0xF, 0xF, true);   // row_newbcast:J
+    hi = __builtin_amdgcn_update_dpp(0, hi, 0x150 + J, 0xF, 0xF, true);
+    return __hiloint2double(hi, lo);
+}
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 // S: POTRF_LDS_DOUBLES doubles of LDS.  preloaded: the block (lower sub-blocks, identity padding beyond bs) is
 // already in S and a barrier has been passed.
 __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __restrict__ V, int n, int off, int bs,
                                            int32_t* __restrict__ info, double* S, bool preloaded) {
-    double* dinv = S + POTRF_LDS_DOUBLES - NB;
-    const int tid = threadIdx.x;
+    double* Tb = S + NSB * (NSB + 1) / 2 * SBS;   // leaf inverse of the current block column
+    double* dinv = Tb + SBS;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lk = lane >> 4;
     if (!preloaded) {
         for (int e = tid; e < NB * NB; e += 256) {
             const int r = e / NB, c = e % NB;
@@ -140,80 +169,107 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
         }
         __syncthreads();
     }
+    // operand fragments of a sub-block M (pointer to its first element), k-step q = 0..3
+    auto frag_rowk = [&](const double* M, int q) __attribute__((always_inline)) {   // M[l%16][4q + l/16]
+        return M[l16 * SBP + 4 * q + lk];
+    };
+    auto frag_krow = [&](const double* M, int q) __attribute__((always_inline)) {   // M[4q + l/16][l%16]
+        return M[(4 * q + lk) * SBP + l16];
+    };
+    auto load_c = [&](const double* M) __attribute__((always_inline)) {
+        double4v c;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) c[r] = M[(4 * r + lk) * SBP + l16];
+        return c;
+    };
+    auto store_c = [&](double* M, const double4v& c) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) M[(4 * r + lk) * SBP + l16] = c[r];
+    };
 
-    // ---------------- Cholesky, 8 panels of 16 columns ----------------
-    for (int c0 = 0; c0 < NB; c0 += SBW) {
-        // (a1) diagonal 16 x 16 sub-block: wave 0, lane i (mod 16) = row c0 + i, row segment in registers;
-        // lanes exchange finished entries with wave shuffles, so no LDS traffic or barrier is needed inside.
-        // (Lanes 16..63 shadow lanes 0..15 so that every shuffle source is active; they store nothing.)
-        if (tid < 64) {
-            const int i = tid & 15;
+    // ---------------- Cholesky, 8 block columns of 16 ----------------
+#pragma unroll 1
+    for (int J = 0; J < NSB; ++J) {
+        double* DJ = S + sub(J, J);
+        // leaf: wave 0, lane i (mod 16) = row i of the sub-block, held in registers; lanes 16..63 shadow
+        // lanes 0..15 and store nothing.
+        if (wave == 0) {
+            const int i = l16;
             double r[SBW];
             double my_dinv = 1.0;
 #pragma unroll
-            for (int c = 0; c < SBW; ++c) r[c] = S[tri(c0 + i, c0 + c)];
-#pragma unroll
-            for (int j = 0; j < SBW; ++j) {
-                double p = r[j];                       // meaningful in lane j only
+            for (int c = 0; c < SBW; ++c) r[c] = DJ[i * SBP + c];
+            static_for<0, SBW>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;
+                double p = bcast16<j>(r[j]);           // pivot, the same in every lane
                 const bool bad = !(p > 0.0);
                 if (bad) p = 1.0;
                 const double ri = rsqrt_refined(p);
                 double sq = p * ri;
                 sq = __builtin_fma(0.5 * ri, __builtin_fma(-sq, sq, p), sq);
-                const double ri_j = __shfl(ri, j, 16);
-                if (i == j) {
-                    if (bad && tid == j && *info == 0) *info = off + c0 + j + 1;
-                    r[j] = sq;
-                    my_dinv = ri;
-                }
-                const double lij = r[j] * ri_j;        // l_ij for rows below the pivot
-                if (i > j) r[j] = lij;
-#pragma unroll
-                for (int c = j + 1; c < SBW; ++c) {
-                    const double lcj = __shfl(lij, c, 16);
+                if (bad && tid == j && *info == 0) *info = off + J * SBW + j + 1;
+                const double lij = (i == j) ? sq : r[j] * ri;   // column j on and below the pivot
+                if (i >= j) r[j] = lij;
+                if (i == j) my_dinv = ri;
+                static_for<j + 1, SBW>([&](auto cc) {
+                    constexpr int c = decltype(cc)::value;
+                    const double lcj = bcast16<c>(lij);
                     if (i >= c) r[c] = __builtin_fma(-lij, lcj, r[c]);
-                }
-            }
+                });
+            });
             if (tid < SBW) {
-                dinv[c0 + i] = my_dinv;
+                dinv[J * SBW + i] = my_dinv;
 #pragma unroll
-                for (int c = 0; c < SBW; ++c)
-                    if (c <= i) S[tri(c0 + i, c0 + c)] = r[c];
+                for (int c = 0; c < SBW; ++c) DJ[i * SBP + c] = (c <= i) ? r[c] : 0.0;   // zeros above the diagonal
             }
         }
         __syncthreads();
-        // (a2) rows below the sub-block: x_j = (a_ij - sum_{m<j} x_m L[j][m]) / L[j][j], one thread per row
-        {
-            const int i = c0 + SBW + tid;
-            if (i < NB) {
-                double x[SBW];
+        // T = L_JJ^-1: thread c < 16 solves column c by forward substitution
+        if (tid < SBW) {
+            const int c = tid;
+            double x[SBW];
 #pragma unroll
-                for (int c = 0; c < SBW; ++c) x[c] = S[tri(i, c0 + c)];
+            for (int i = 0; i < SBW; ++i) {
+                double acc = (i == c) ? 1.0 : 0.0;
 #pragma unroll
-                for (int j = 0; j < SBW; ++j) {
-                    double acc = x[j];
-#pragma unroll
-                    for (int m = 0; m < j; ++m) acc = __builtin_fma(-x[m], S[tri(c0 + j, c0 + m)], acc);
-                    x[j] = acc * dinv[c0 + j];
-                }
-#pragma unroll
-                for (int c = 0; c < SBW; ++c) S[tri(i, c0 + c)] = x[c];
+                for (int m = 0; m < i; ++m)
+                    if (m >= c) acc = __builtin_fma(-DJ[i * SBP + m], x[m], acc);
+                x[i] = (i >= c) ? acc * dinv[J * SBW + i] : 0.0;
             }
+#pragma unroll
+            for (int i = 0; i < SBW; ++i) Tb[i * SBP + c] = x[i];
         }
         __syncthreads();
-        // (b) rank-16 update of the trailing lower triangle: S[i][c] -= sum_m L[i][c0+m] L[c][c0+m]
+        // L_IJ = A_IJ T^T for I > J (in place: the wave holds A_IJ's fragments before it writes)
+        for (int I = J + 1 + wave; I < NSB; I += 4) {
+            double* M = S + sub(I, J);
+            double a[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) a[q] = frag_rowk(M, q);
+            double4v c = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) c = __builtin_amdgcn_mfma_f64_16x16x4f64(a[q], frag_rowk(Tb, q), c, 0, 0, 0);
+            store_c(M, c);
+        }
+        __syncthreads();
+        // A_IK -= L_IJ L_KJ^T for J < K <= I
         {
-            const int t0 = c0 + SBW;
-            for (int i = t0 + (tid >> 4); i < NB; i += 16) {
-                double li[SBW];
+            const int nr = NSB - 1 - J;                 // sub-block rows below J
+            const int np = nr * (nr + 1) / 2;
+            for (int p = wave; p < np; p += 4) {
+                // p -> (ii, kk), kk <= ii < nr, row-major over the triangle
+                int ii = 0;
+                while ((ii + 1) * (ii + 2) / 2 <= p) ++ii;
+                const int kk = p - ii * (ii + 1) / 2;
+                const int I = J + 1 + ii, K = J + 1 + kk;
+                double* M = S + sub(I, K);
+                const double* LI = S + sub(I, J);
+                const double* LK = S + sub(K, J);
+                double4v c = load_c(M);
 #pragma unroll
-                for (int m = 0; m < SBW; ++m) li[m] = S[tri(i, c0 + m)];
-                for (int c = t0 + (tid & 15); c <= i; c += 16) {
-                    double acc = S[tri(i, c)];
-#pragma unroll
-                    for (int m = 0; m < SBW; ++m) acc = __builtin_fma(-li[m], S[tri(c, c0 + m)], acc);
-                    S[tri(i, c)] = acc;
-                }
+                for (int q = 0; q < 4; ++q)
+                    c = __builtin_amdgcn_mfma_f64_16x16x4f64(-frag_rowk(LI, q), frag_rowk(LK, q), c, 0, 0, 0);
+                store_c(M, c);
             }
         }
         __syncthreads();
@@ -222,75 +278,76 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
         const int r = e / NB, c = e % NB;
         if (c <= r) A[int64_t(off + r) * n + off + c] = S[tri(r, c)];
     }
-    __syncthreads();
 
-    // ---------------- X = L^-1 in place, 16 x 16 sub-blocks ----------------
-    // diagonal sub-blocks: thread t < 128 solves column t of its sub-block by forward substitution
+    // ---------------- X = L^-1 in place ----------------
+    // leaf inverses of the diagonal sub-blocks: thread t < 128 solves column t % 16 of sub-block t / 16
     {
         double x[SBW];
-        const int b0 = (tid >> 4) * SBW, c = tid & 15;
+        const int Jb = tid >> 4, c = tid & 15;
+        double* DJ = S + sub(Jb & 7, Jb & 7);
         if (tid < NB) {
 #pragma unroll
             for (int i = 0; i < SBW; ++i) {
                 double acc = (i == c) ? 1.0 : 0.0;
 #pragma unroll
                 for (int m = 0; m < i; ++m)
-                    if (m >= c) acc = __builtin_fma(-S[tri(b0 + i, b0 + m)], x[m], acc);
-                x[i] = (i >= c) ? acc * dinv[b0 + i] : 0.0;
+                    if (m >= c) acc = __builtin_fma(-DJ[i * SBP + m], x[m], acc);
+                x[i] = (i >= c) ? acc * dinv[Jb * SBW + i] : 0.0;
             }
         }
         __syncthreads();
         if (tid < NB) {
 #pragma unroll
-            for (int i = 0; i < SBW; ++i)
-                if (i >= c) S[tri(b0 + i, b0 + c)] = x[i];
+            for (int i = 0; i < SBW; ++i) DJ[i * SBP + c] = x[i];   // zeros above the diagonal
         }
         __syncthreads();
     }
-    // block rows top to bottom: X_ij = -X_ii * sum_{m=j}^{i-1} L_im X_mj  (j < i).  Row i of S still holds L_im.
-    for (int ib = 1; ib < NB / SBW; ++ib) {
-        const int i0 = ib * SBW;
-        const int n_out = SBW * i0;            // outputs of this block row: 16 rows x i0 columns
-        double t[7];                           // <= 7 outputs per thread (16 * 112 / 256)
+    // recursive doubling: ns = sub-blocks per side of a pair
+    static_for<0, 3>([&](auto lc) {
+        constexpr int ns = 1 << decltype(lc)::value;     // 1, 2, 4
+        const int pr = wave / ns, t = wave % ns;         // pair and row / column task of this wave
+        const int a0 = pr * 2 * ns, c0 = a0 + ns;        // first sub-block of A and of C
+        {   // T = L[C,A] X[A,A], sub-block row I = c0 + t, in place
+            const int I = c0 + t;
+            double a[ns][4];
 #pragma unroll
-        for (int q = 0; q < 7; ++q) {
-            const int e = tid + 256 * q;
-            t[q] = 0.0;
-            if (e < n_out) {
-                const int r = e / i0, c = e % i0;          // row i0 + r, column c
-                double acc = 0.0;                          // X[m][c] is zero for m < c
-                for (int m = c; m < i0; ++m) acc = __builtin_fma(S[tri(i0 + r, m)], S[tri(m, c)], acc);
-                t[q] = acc;
+            for (int kb = 0; kb < ns; ++kb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) a[kb][q] = frag_rowk(S + sub(I, a0 + kb), q);
+#pragma unroll
+            for (int jb = 0; jb < ns; ++jb) {
+                double4v c = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int kb = jb; kb < ns; ++kb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        c = __builtin_amdgcn_mfma_f64_16x16x4f64(a[kb][q], frag_krow(S + sub(a0 + kb, a0 + jb), q), c, 0,
+                                                                 0, 0);
+                store_c(S + sub(I, a0 + jb), c);
             }
         }
         __syncthreads();
+        {   // X[C,A] = -X[C,C] T, sub-block column a0 + t, in place
+            const int Jc = a0 + t;
+            double b[ns][4];
 #pragma unroll
-        for (int q = 0; q < 7; ++q) {
-            const int e = tid + 256 * q;
-            if (e < n_out) S[tri(i0 + e / i0, e % i0)] = t[q];
-        }
-        __syncthreads();
+            for (int kb = 0; kb < ns; ++kb)
 #pragma unroll
-        for (int q = 0; q < 7; ++q) {
-            const int e = tid + 256 * q;
-            t[q] = 0.0;
-            if (e < n_out) {
-                const int r = e / i0, c = e % i0;
-                double acc = 0.0;
+                for (int q = 0; q < 4; ++q) b[kb][q] = frag_krow(S + sub(c0 + kb, Jc), q);
 #pragma unroll
-                for (int m = 0; m < SBW; ++m)
-                    if (m <= r) acc = __builtin_fma(S[tri(i0 + r, i0 + m)], S[tri(i0 + m, c)], acc);
-                t[q] = -acc;
+            for (int ib = 0; ib < ns; ++ib) {
+                double4v c = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int kb = 0; kb <= ib; ++kb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        c = __builtin_amdgcn_mfma_f64_16x16x4f64(-frag_rowk(S + sub(c0 + ib, c0 + kb), q), b[kb][q], c, 0,
+                                                                 0, 0);
+                store_c(S + sub(c0 + ib, Jc), c);
             }
         }
         __syncthreads();
-#pragma unroll
-        for (int q = 0; q < 7; ++q) {
-            const int e = tid + 256 * q;
-            if (e < n_out) S[tri(i0 + e / i0, e % i0)] = t[q];
-        }
-        __syncthreads();
-    }
+    });
     for (int e = tid; e < bs * bs; e += 256) {
         const int r = e / bs, c = e % bs;
         V[int64_t(off + r) * n + off + c] = (c <= r) ? S[tri(r, c)] : 0.0;
