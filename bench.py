@@ -209,12 +209,17 @@ def main():
     gram_ms = acc_ms / n_calls
     algo_flops = float(tpc) * d_in * (d_in + 1)
     gram_tflops = algo_flops / (gram_ms * 1e-3) / 1e12
+    # counter-backed traffic of the Gram launch: known for the default workload in one call (see profiles/)
+    gram_traffic = 159.2e9 if (cfg.name == "c3b" and n_calls == 1) else None
     roofline = {
         "kernel": ("gram_bf16_dma_kernel" if d_in >= 8192 else "gram_bf16_kernel<2>") if cfg.dtype == torch.bfloat16
                   else "gram_f32_kernel",
         "bound": "mfma", "achieved": gram_tflops, "peak": PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3,
         "unit": "TFLOP/s", "frac": gram_tflops / (PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3),
-        "traffic": None,
+        "traffic": gram_traffic,
+        "traffic_note": "L2 <-> fabric bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a 4 GiB copy "
+                        "(profiles/c3b_hbm_traffic_pmc.md); measured for the default workload only, else null",
+        "algorithmic_bytes": 2.0 * tpc * d_in + 8.0 * d_in * d_in,
         "note": "algorithmic flops = T*d_in*(d_in+1) (upper triangle incl. diagonal, 2 flops per MAC); "
                 "dense-equivalent rate is 2x this",
         "avg_launch_ms": gram_ms,
@@ -226,7 +231,7 @@ def main():
     roofline_sweep = {
         "kernel": "onecomp_quantize_layer (panel_far_kernel + trailing_kernel launches)", "bound": "hbm",
         "achieved": sweep_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": sweep_gbs / PEAK_HBM_GBS,
-        "traffic": None, "model_bytes": sweep_bytes,
+        "traffic": 13.5e9 if (cfg.name == "c3b") else None, "model_bytes": sweep_bytes,
         "note": "modelled HBM bytes of the two-level schedule actually run (512-column super-blocks) / whole-call "
                 "time; the trailing updates are split-fp16 MFMA GEMMs fed from L2, so the call is not HBM bound",
         "b128_model_bytes": b128_bytes,
