@@ -50,6 +50,81 @@ __device__ inline void tile_from_rank(int v, int n_t, int& ti, int& tk) {
 }
 
 // -------------------------------------------------------------------------------------------
+// Epilogue shared by the bf16 kernels: H[i][k] += 2 acc for this wave's MT x NT tiles of 32 x 32 and the
+// mirrored entries H[k][i] (one owner per element, no atomics: bit-wise symmetric and reproducible).
+// Accumulator register r of lane l holds row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its tile; ibase / kbase are
+// the wave's first row / column.  Tiles strictly above the diagonal and inside the matrix take a path without
+// per-element masks whose loads are issued 32 at a time before the first use (left to itself the compiler
+// waits for every load separately when the accumulators live in AGPRs).
+// -------------------------------------------------------------------------------------------
+template <int MT, int NT>
+__device__ __forceinline__ void gram_store(float16v (&acc)[MT][NT], float* __restrict__ H, const int d_in,
+                                           const int ibase, const int kbase, const bool diag, const int lane) {
+    const int lr = (lane >> 5) * 4, lc = lane & 31;
+    const bool interior = !diag && (ibase + 32 * MT <= d_in) && (kbase + 32 * NT <= d_in);
+    if (interior) {
+        constexpr int NBATCH = NT < 2 ? NT : 2;   // column tiles per batch of loads
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+#pragma unroll
+            for (int n0 = 0; n0 < NT; n0 += NBATCH) {
+                float* hp = H + int64_t(ibase + m * 32 + lr) * d_in + kbase + n0 * 32 + lc;
+                float hv[NBATCH][16];
+#pragma unroll
+                for (int n = 0; n < NBATCH; ++n)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) hv[n][r] = hp[int64_t((r / 4) * 8 + (r % 4)) * d_in + n * 32];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int n = 0; n < NBATCH; ++n) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        hv[n][r] = hv[n][r] + 2.0f * acc[m][n0 + n][r];
+                        hp[int64_t((r / 4) * 8 + (r % 4)) * d_in + n * 32] = hv[n][r];
+                    }
+                    float* mp = H + int64_t(kbase + (n0 + n) * 32 + lc) * d_in + ibase + m * 32 + lr;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float4v o = {hv[n][q * 4], hv[n][q * 4 + 1], hv[n][q * 4 + 2], hv[n][q * 4 + 3]};
+                        *reinterpret_cast<float4v*>(mp + q * 8) = o;
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+            const int k = kbase + n * 32 + lc;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int ib = ibase + m * 32 + q * 8 + lr;   // 4 consecutive rows ib..ib+3
+                if (k >= d_in || ib >= d_in) continue;         // d_in % 16 == 0: the 4 rows are in or out together
+                float nv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = ib + e;
+                    float* p = H + int64_t(i) * d_in + k;
+                    nv[e] = *p + 2.0f * acc[m][n][q * 4 + e];
+                    if (!diag || i <= k) *p = nv[e];
+                }
+                if (!diag) {
+                    const float4v o = {nv[0], nv[1], nv[2], nv[3]};
+                    *reinterpret_cast<float4v*>(H + int64_t(k) * d_in + ib) = o;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (ib + e < k) H[int64_t(k) * d_in + ib + e] = nv[e];
+                }
+            }
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------------
 // bf16 kernel
 // -------------------------------------------------------------------------------------------
 template <int WT>
@@ -165,37 +240,7 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_kernel(const uint16_t*
         __syncthreads();
     }
 
-    // epilogue: H[i][k] += 2 acc, mirrored.  Accumulator register r of lane l holds
-    // row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its 32x32 tile.
-    const int lr = (lane >> 5) * 4, lc = lane & 31;
-#pragma unroll
-    for (int m = 0; m < WT; ++m) {
-#pragma unroll
-        for (int n = 0; n < WT; ++n) {
-            const int k = k0 + wc * (32 * WT) + n * 32 + lc;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int ib = i0 + wr * (32 * WT) + m * 32 + q * 8 + lr;  // 4 consecutive rows ib..ib+3
-                if (k >= d_in || ib >= d_in) continue;                     // d_in % 16 == 0: the 4 rows are in or out together
-                float nv[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = ib + e;
-                    float* p = H + int64_t(i) * d_in + k;
-                    nv[e] = *p + 2.0f * acc[m][n][q * 4 + e];
-                    if (!diag || i <= k) *p = nv[e];
-                }
-                if (!diag) {
-                    float4 o = make_float4(nv[0], nv[1], nv[2], nv[3]);
-                    *reinterpret_cast<float4*>(H + int64_t(k) * d_in + ib) = o;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (ib + e < k) H[int64_t(k) * d_in + ib + e] = nv[e];
-                }
-            }
-        }
-    }
+    gram_store<WT, WT>(acc, H, d_in, i0 + wr * (32 * WT), k0 + wc * (32 * WT), diag, lane);
 }
 
 // -------------------------------------------------------------------------------------------
@@ -343,36 +388,7 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_pipe_kernel(const uint
         buf = nbuf;
     }
 
-    // epilogue: H[i][k] += 2 acc, mirrored (see the generic kernel for the register layout)
-    const int lr = (lane >> 5) * 4, lc = lane & 31;
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-#pragma unroll
-        for (int n = 0; n < 4; ++n) {
-            const int k = k0 + wc * 128 + n * 32 + lc;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int ib = i0 + wr * 128 + m * 32 + q * 8 + lr;
-                if (k >= d_in || ib >= d_in) continue;
-                float nv[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = ib + e;
-                    float* p = H + int64_t(i) * d_in + k;
-                    nv[e] = *p + 2.0f * acc[m][n][q * 4 + e];
-                    if (!diag || i <= k) *p = nv[e];
-                }
-                if (!diag) {
-                    const float4v o = {nv[0], nv[1], nv[2], nv[3]};
-                    *reinterpret_cast<float4v*>(H + int64_t(k) * d_in + ib) = o;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (ib + e < k) H[int64_t(k) * d_in + ib + e] = nv[e];
-                }
-            }
-        }
-    }
+    gram_store<4, 4>(acc, H, d_in, i0 + wr * 128, k0 + wc * 128, diag, lane);
 }
 
 // -------------------------------------------------------------------------------------------
@@ -532,36 +548,7 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_dma_kernel(const uint1
         buf = nbuf;
     }
 
-    // epilogue: H[i][k] += 2 acc, mirrored (see the generic kernel for the register layout)
-    const int lr = (lane >> 5) * 4, lc = lane & 31;
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-#pragma unroll
-        for (int n = 0; n < 4; ++n) {
-            const int k = k0 + wc * 128 + n * 32 + lc;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int ib = i0 + wr * 128 + m * 32 + q * 8 + lr;
-                if (k >= d_in || ib >= d_in) continue;
-                float nv[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = ib + e;
-                    float* p = H + int64_t(i) * d_in + k;
-                    nv[e] = *p + 2.0f * acc[m][n][q * 4 + e];
-                    if (!diag || i <= k) *p = nv[e];
-                }
-                if (!diag) {
-                    const float4v o = {nv[0], nv[1], nv[2], nv[3]};
-                    *reinterpret_cast<float4v*>(H + int64_t(k) * d_in + ib) = o;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (ib + e < k) H[int64_t(k) * d_in + ib + e] = nv[e];
-                }
-            }
-        }
-    }
+    gram_store<4, 4>(acc, H, d_in, i0 + wr * 128, k0 + wc * 128, diag, lane);
 }
 
 // -------------------------------------------------------------------------------------------
