@@ -61,6 +61,19 @@ def sweep_model_bytes(d_out, d_in, G, w_bytes, SBW=512):
     return total
 
 
+def gram_kernel_name(d_in, bf16, n_cus=256):
+    """Name of the kernel onecomp_hessian_accumulate launches for this width (the library's own selection rule:
+    estimated rounds of 256 x 256 tiles, one per CU, against 128 x 256 tiles, two per CU)."""
+    if not bf16:
+        return "gram_f32_kernel"
+    if d_in < 1024:
+        return "gram_bf16_kernel<2>"
+    n256, n128 = -(-d_in // 256), -(-d_in // 128)
+    big = n256 * (n256 + 1) // 2
+    mid = sum(n256 - i // 2 for i in range(n128))
+    return "gram_bf16_dma_kernel" if 2.0 * -(-big // n_cus) <= 1.15 * -(-mid // n_cus) else "gram_bf16_dma128_kernel"
+
+
 def cpu_baseline(cfg, synth, seconds_hint=20.0):
     """Oracle (float64, numpy) timed per phase on bounded samples of the same workload and extrapolated by
     work: Gram over n_s tokens (linear in tokens), factor at d_s = d_in / 2 (cubic), sweep of r_s rows at
@@ -212,8 +225,7 @@ def main():
     # counter-backed traffic of the Gram launch: known for the default workload in one call (see profiles/)
     gram_traffic = 159.2e9 if (cfg.name == "c3b" and n_calls == 1) else None
     roofline = {
-        "kernel": ("gram_bf16_dma_kernel" if d_in >= 8192 else "gram_bf16_kernel<2>") if cfg.dtype == torch.bfloat16
-                  else "gram_f32_kernel",
+        "kernel": gram_kernel_name(d_in, cfg.dtype == torch.bfloat16),
         "bound": "mfma", "achieved": gram_tflops, "peak": PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3,
         "unit": "TFLOP/s", "frac": gram_tflops / (PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3),
         "traffic": gram_traffic,

@@ -244,154 +244,6 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_kernel(const uint16_t*
 }
 
 // -------------------------------------------------------------------------------------------
-// bf16 kernel for large d_in: 256 x 256 tile, software-pipelined
-//
-//   stage t = tokens [32 t, 32 t + 32);  LDS ring of 3 stage buffers;  one register set for global loads.
-//   iteration s:  (1) registers of stage s+1 (loaded one iteration ago) -> LDS buffer (s+1) % 3
-//                 (2) global loads of stage s+2 -> the same registers
-//                 (3) LDS -> fragments of the second half (tokens 16..31) of stage s
-//                 (4) 16 MFMAs on the first half of stage s (fragments preloaded in the previous iteration)
-//                 (5) workgroup barrier: stage s+1 is complete in LDS
-//                 (6) LDS -> fragments of the first half of stage s+1
-//                 (7) 16 MFMAs on the second half of stage s
-//   Every global load has a full iteration to land before it is needed, every LDS read half an iteration,
-//   and there is one barrier per 32 tokens, placed where 16 MFMAs are already queued behind it.
-// -------------------------------------------------------------------------------------------
-namespace pipe {
-constexpr int TS = 256, KT = 32, PITCH = TS + 32, PANEL = KT * PITCH, STAGE = 2 * PANEL, NBUF = 3;
-constexpr size_t LDS_BYTES = size_t(NBUF) * STAGE * 2;
-constexpr int NLOAD = KT * TS / 8 / GRAM_THREADS;  // 4 chunks of 16 B per thread and panel
-
-struct Frags {
-    bf16x8 a[4], b[4];
-};
-struct Staged {
-    uint4v a[NLOAD], b[NLOAD];
-};
-}  // namespace pipe
-
-__global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_pipe_kernel(const uint16_t* __restrict__ X,
-                                                                     int64_t n_tokens, int d_in, int64_t ldx,
-                                                                     float* __restrict__ H, int n_t, int n_tiles,
-                                                                     int chunk) {
-    using namespace pipe;
-    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-
-    const int v = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
-    if (v >= n_tiles) return;
-    int ti, tk;
-    tile_from_rank(v, n_t, ti, tk);
-    const bool diag = (ti == tk);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wr = wave >> 1, wc = wave & 1;
-    const int i0 = ti * TS, k0 = tk * TS;
-
-    // per-thread load slots.  Loads are raw buffer loads: the descriptor is rebuilt per stage with the bytes
-    // left in X as its range, so token rows past the end read as zero without any branch; channels past d_in
-    // (tiles on the ragged edge) get an offset outside the range for the same effect.
-    constexpr uint32_t OOB = 0xFFFFFFF0u;
-    uint32_t off_a[NLOAD], off_b[NLOAD];   // byte offsets from the first token row of a stage
-    int lds_w[NLOAD];
-#pragma unroll
-    for (int n = 0; n < NLOAD; ++n) {
-        const int id = tid + GRAM_THREADS * n;
-        const int row = id / (TS / 8), col = (id % (TS / 8)) * 8;
-        off_a[n] = (i0 + col < d_in) ? uint32_t((int64_t(row) * ldx + i0 + col) * 2) : OOB;
-        off_b[n] = (k0 + col < d_in) ? uint32_t((int64_t(row) * ldx + k0 + col) * 2) : OOB;
-        lds_w[n] = row * PITCH + col;
-    }
-    const int64_t n_stage = (n_tokens + KT - 1) / KT;
-
-    auto gload = [&](Staged& g, int64_t st) __attribute__((always_inline)) {
-        const int64_t t0 = st * KT;
-        const char* base = reinterpret_cast<const char*>(X) + t0 * ldx * 2;
-        const int64_t left = (n_tokens - t0) * ldx * 2;
-        const int range = left > 0x7FFFFFFF ? 0x7FFFFFFF : int(left);
-        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, range, 0x00020000);
-#pragma unroll
-        for (int n = 0; n < NLOAD; ++n) {
-            g.a[n] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off_a[n], 0, 0);
-            g.b[n] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off_b[n], 0, 0);
-        }
-    };
-    auto lwrite = [&](const Staged& g, int buf) __attribute__((always_inline)) {
-        uint16_t* pa = lds + buf * STAGE;
-        uint16_t* pb = pa + PANEL;
-#pragma unroll
-        for (int n = 0; n < NLOAD; ++n) {
-            *reinterpret_cast<uint4v*>(pa + lds_w[n]) = g.a[n];
-            *reinterpret_cast<uint4v*>(pb + lds_w[n]) = g.b[n];
-        }
-    };
-    // LDS transpose-read addressing (see the generic kernel)
-    const int i16 = lane & 15, g16 = (lane >> 4) & 1, kb8 = lane >> 5;
-    const int frag_off = (kb8 * 8 + (i16 >> 2)) * PITCH + g16 * 16 + (i16 & 3) * 4;
-    auto lread = [&](Frags& f, int buf, int kb) __attribute__((always_inline)) {
-        const uint16_t* pa = lds + buf * STAGE;
-        const uint16_t* pb = pa + PANEL;   // a diagonal tile simply loads its panel twice
-        const uint16_t* fa = pa + frag_off + wr * 128 + kb * 16 * PITCH;
-        const uint16_t* fb = pb + frag_off + wc * 128 + kb * 16 * PITCH;
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(fa + m * 32));
-            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(fa + m * 32 + 4 * PITCH));
-            f.a[m] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-        }
-#pragma unroll
-        for (int n = 0; n < 4; ++n) {
-            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(fb + n * 32));
-            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(fb + n * 32 + 4 * PITCH));
-            f.b[n] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-        }
-    };
-
-    float16v acc[4][4];
-#pragma unroll
-    for (int m = 0; m < 4; ++m)
-#pragma unroll
-        for (int n = 0; n < 4; ++n)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
-    auto mma = [&](const Frags& f) __attribute__((always_inline)) {
-#pragma unroll
-        for (int m = 0; m < 4; ++m)
-#pragma unroll
-            for (int n = 0; n < 4; ++n)
-                acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[m], f.b[n], acc[m][n], 0, 0, 0);
-    };
-
-    Staged G;        // global-load staging registers: written to LDS one iteration after the loads were issued
-    Frags Fc, FH;    // first-half fragments (current stage, then reloaded for the next one), second-half fragments
-    // prologue: stage 0 -> LDS, stage 1 -> registers, first-half fragments of stage 0
-    gload(G, 0);
-    lwrite(G, 0);
-    if (n_stage > 1) gload(G, 1);
-    __syncthreads();
-    lread(Fc, 0, 0);
-    int buf = 0;
-#pragma unroll 1
-    for (int64_t s = 0; s < n_stage; ++s) {
-        const int nbuf = (buf + 1 == NBUF) ? 0 : buf + 1;
-        const bool has1 = (s + 1 < n_stage), has2 = (s + 2 < n_stage);
-        if (has1) lwrite(G, nbuf);        // stage s+1, loaded during the previous iteration
-        __builtin_amdgcn_sched_barrier(0);
-        if (has2) gload(G, s + 2);        // same registers, in flight until the next iteration's write
-        lread(FH, buf, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(Fc);
-        __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
-        if (has1) lread(Fc, nbuf, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(FH);
-        __builtin_amdgcn_sched_barrier(0);
-        buf = nbuf;
-    }
-
-    gram_store<4, 4>(acc, H, d_in, i0 + wr * 128, k0 + wc * 128, diag, lane);
-}
-
-// -------------------------------------------------------------------------------------------
 // bf16 kernel for large d_in, direct-to-LDS variant: 256 x 256 tile, global -> LDS without passing through
 // registers (buffer_load_dwordx4 ... lds), LDS ring of 4 stages, loads issued 3 stages ahead.
 //
@@ -552,6 +404,181 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_dma_kernel(const uint1
 }
 
 // -------------------------------------------------------------------------------------------
+// bf16 kernel for mid-size d_in (too few 256 x 256 tiles to fill the CUs): 128 x 256 tile, two workgroups per CU.
+// Tile (i, k) = channel rows [128 i, +128) x channel columns [256 k, +256) is computed when it reaches above the
+// diagonal (k >= i / 2); tiles that the diagonal crosses store only their entries on or above it (and the
+// mirrors).  Same direct-to-LDS scheme and chunk swizzle as the 256 x 256 kernel, in steps of 16 tokens:
+// A panel 16 x 256 B, B panel 16 x 512 B, ring of 6 slots (72 KB).  Half-iteration h: 8 MFMAs on the fragments
+// of step h (registers); LDS -> fragments of step h+1; loads of step h+6 into the slot step h was read from;
+// wait for step h+2 + barrier.
+// -------------------------------------------------------------------------------------------
+namespace dma2 {
+constexpr int TM = 128, TN = 256, KT = 16, NBUF = 6;
+constexpr int A_ROWB = TM * 2, B_ROWB = TN * 2;
+constexpr int A_PANELB = KT * A_ROWB, B_PANELB = KT * B_ROWB, STAGEB = A_PANELB + B_PANELB;   // 4 + 8 KB
+constexpr size_t LDS_BYTES = size_t(NBUF) * STAGEB;
+constexpr int RBAND = 8;   // 128-wide tile rows per band of the tile order
+}  // namespace dma2
+
+// rank v -> tile (ti, tk): bands of RBAND tile rows, inside a band column by column, rows fastest
+__device__ inline void tile128_from_rank(int v, int n_rt, int n_ct, int& ti, int& tk) {
+    for (int a = 0;; ++a) {
+        const int r0 = a * dma2::RBAND, rows = min(dma2::RBAND, n_rt - r0);
+        for (int k = r0 / 2; k < n_ct; ++k) {
+            const int valid = min(rows, 2 * k + 2 - r0);   // rows r0 .. r0+valid-1 satisfy i / 2 <= k
+            if (v < valid) { ti = r0 + v; tk = k; return; }
+            v -= valid;
+        }
+    }
+}
+
+__global__ __launch_bounds__(GRAM_THREADS, 2) void gram_bf16_dma128_kernel(const uint16_t* __restrict__ X,
+                                                                          int64_t n_tokens, int d_in, int64_t ldx,
+                                                                          float* __restrict__ H, int n_rt, int n_ct,
+                                                                          int n_tiles, int chunk) {
+    using namespace dma2;
+    extern __shared__ __attribute__((aligned(1024))) char ldsb[];
+    const int v = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+    if (v >= n_tiles) return;
+    int ti, tk;
+    tile128_from_rank(v, n_rt, n_ct, ti, tk);
+    const int i0 = ti * TM, k0 = tk * TN;
+    const bool diag = k0 < i0 + TM;   // some entry of the tile lies on or below the diagonal
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 1, wc = wave & 1;
+    const uint32_t lds0 = uint32_t(uintptr_t((ONECOMP_LDS char*)ldsb));
+
+    // this wave's three 1 KB loads per step: token rows 4 wave .. 4 wave + 3 of the A panel (one load) and of the
+    // B panel (two loads of two rows)
+    uint32_t voff_a, voff_b[2];
+    {
+        const int row = 4 * wave + (lane >> 4);
+        const int c = (lane & 15) ^ ((row & 3) << 2);
+        voff_a = (i0 + c * 8 < d_in) ? uint32_t((int64_t(row) * ldx + i0 + c * 8) * 2) : LDS_DMA_OOB;
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int row = 4 * wave + 2 * q + (lane >> 5);
+        const int c = (lane & 31) ^ ((row & 3) << 2);
+        voff_b[q] = (k0 + c * 8 < d_in) ? uint32_t((int64_t(row) * ldx + k0 + c * 8) * 2) : LDS_DMA_OOB;
+    }
+    const int64_t n_st = (n_tokens + KT - 1) / KT;
+    const int64_t n_st2 = (n_st + 1) & ~int64_t(1);   // the loop takes two steps at a time; an extra step is all zeros
+    struct Desc {
+        __amdgpu_buffer_rsrc_t r;
+    };
+    // descriptor of step st: base = its first token row, range = what is left of X (none past the last step)
+    auto make_desc = [&](int64_t st) __attribute__((always_inline)) {
+        Desc d;
+        const int64_t t0 = st * KT;
+        const int64_t left = (n_tokens - t0) * ldx * 2;
+        const bool live = left > 0;
+        // (the 64-bit products may be computed on the vector ALU: bring the wave-uniform results back to scalar
+        // registers, where a descriptor has to live)
+        const int range = __builtin_amdgcn_readfirstlane(!live ? 0 : (left > 0x7FFFFFFF ? 0x7FFFFFFF : int(left)));
+        const int64_t boff = (live ? t0 : 0) * ldx * 2;
+        const uint32_t blo = __builtin_amdgcn_readfirstlane(uint32_t(boff));
+        const uint32_t bhi = __builtin_amdgcn_readfirstlane(uint32_t(uint64_t(boff) >> 32));
+        d.r = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char*>(reinterpret_cast<const char*>(X) + int64_t((uint64_t(bhi) << 32) | blo)), 0, range,
+            0x00020000);
+        return d;
+    };
+    auto gload1 = [&](const Desc& d, uint32_t dst, int i) __attribute__((always_inline)) {
+        if (i == 0) lds_load16(dst + wave * 1024, voff_a, d.r);
+        else if (i == 1) lds_load16(dst + A_PANELB + wave * 2048, voff_b[0], d.r);
+        else lds_load16(dst + A_PANELB + wave * 2048 + 1024, voff_b[1], d.r);
+    };
+
+    const int i16 = lane & 15, g16 = (lane >> 4) & 1, kb8 = lane >> 5;
+    const int kq = i16 >> 2;
+    const int lo = (2 * g16 + ((i16 & 3) >> 1)) * 16 + (i16 & 1) * 8;
+    int fa[2], fb[4];
+#pragma unroll
+    for (int m = 0; m < 2; ++m) fa[m] = (kb8 * 8 + kq) * A_ROWB + (((wr * 2 + m) ^ kq) << 6) + lo;
+#pragma unroll
+    for (int n = 0; n < 4; ++n) fb[n] = A_PANELB + (kb8 * 8 + kq) * B_ROWB + wc * 256 + ((n ^ kq) << 6) + lo;
+
+    struct Frags {
+        bf16x8 a[2], b[4];
+    };
+    auto rd2 = [&](const char* p, int rowb) __attribute__((always_inline)) {
+        short4v x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(p));
+        short4v x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(p + 4 * rowb));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // fragment r (0..5) of the slot at ldsb + sb, in the order the MFMAs use them: a0 b0 b1 b2 b3 a1
+    auto rd = [&](Frags& f, int r, int sb) __attribute__((always_inline)) {
+        const char* s = ldsb + sb;
+        if (r == 0) f.a[0] = rd2(s + fa[0], A_ROWB);
+        else if (r <= 4) f.b[r - 1] = rd2(s + fb[r - 1], B_ROWB);
+        else f.a[1] = rd2(s + fa[1], A_ROWB);
+    };
+
+    for (int st = 0; st < NBUF; ++st) {
+        const Desc d = make_desc(st);
+#pragma unroll
+        for (int i = 0; i < 3; ++i) gload1(d, lds0 + st * STAGEB, i);
+    }
+    float16v acc[2][4];
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
+    __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));
+    __syncthreads();
+    Frags Fc, FH;
+#pragma unroll
+    for (int r = 0; r < 6; ++r) rd(Fc, r, 0);
+    __syncthreads();   // slot 0 is overwritten by the loads of the first half-iteration
+
+    auto mma = [&](const Frags& f, auto&& between) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            acc[i / 4][i % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i / 4], f.b[i % 4], acc[i / 4][i % 4], 0, 0, 0);
+            between(i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    int s0 = 0;   // slot of step st
+#pragma unroll 1
+    for (int64_t st = 0; st < n_st2; st += 2) {
+        const int s1 = (s0 == NBUF - 1) ? 0 : s0 + 1, s2 = (s1 == NBUF - 1) ? 0 : s1 + 1;
+        // loads past the last step get an empty descriptor (zeros into a slot nobody reads again); fragment reads
+        // past it fetch stale data nobody uses
+        {
+            const Desc d = make_desc(st + NBUF);
+            const uint32_t dst = lds0 + s0 * STAGEB;
+            const int sb = s1 * STAGEB;
+            mma(Fc, [&](int i) __attribute__((always_inline)) {
+                if (i < 6) rd(FH, i, sb);
+                if (i < 3) gload1(d, dst, i);
+            });
+            __builtin_amdgcn_s_waitcnt(wait_vmcnt(3 * (NBUF - 2)));   // step st+2 has landed
+            __syncthreads();
+        }
+        {
+            const Desc d = make_desc(st + 1 + NBUF);
+            const uint32_t dst = lds0 + s1 * STAGEB;
+            const int sb = s2 * STAGEB;
+            mma(FH, [&](int i) __attribute__((always_inline)) {
+                if (i < 6) rd(Fc, i, sb);
+                if (i < 3) gload1(d, dst, i);
+            });
+            __builtin_amdgcn_s_waitcnt(wait_vmcnt(3 * (NBUF - 2)));   // step st+3 has landed
+            __syncthreads();
+        }
+        s0 = s2;
+    }
+    __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // no LDS write may be in flight when the workgroup ends
+    gram_store<2, 4>(acc, H, d_in, i0 + wr * 64, k0 + wc * 128, diag, lane);
+}
+
+// -------------------------------------------------------------------------------------------
 // fp32 kernel: 128 x 128 tile, 4 waves in 2x2, each 2x2 tiles of v_mfma_f32_32x32x2_f32
 // -------------------------------------------------------------------------------------------
 constexpr int F32_TS = 128, F32_KT = 16, F32_PITCH = F32_TS + 4, F32_PANEL = F32_KT * F32_PITCH;
@@ -679,20 +706,21 @@ onecomp_status launch_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_
 
 
 
-onecomp_status launch_bf16_pipe(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
-                                hipStream_t stream) {
-    const int n_t = int(ceil_div(d_in, pipe::TS));
-    const int n_tiles = n_t * (n_t + 1) / 2;
+onecomp_status launch_bf16_dma128(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
+                                  hipStream_t stream) {
+    const int n_rt = int(ceil_div(d_in, dma2::TM)), n_ct = int(ceil_div(d_in, dma2::TN));
+    int n_tiles = 0;
+    for (int i = 0; i < n_rt; ++i) n_tiles += n_ct - i / 2;
     const int chunk = int(ceil_div(n_tiles, 8));
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_pipe_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(pipe::LDS_BYTES)) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_dma128_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(dma2::LDS_BYTES)) != hipSuccess)
             return ONECOMP_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL(gram_bf16_pipe_kernel, dim3(chunk * 8), dim3(GRAM_THREADS), pipe::LDS_BYTES, stream,
-                       static_cast<const uint16_t*>(X), n_tokens, int(d_in), ldx, H, n_t, n_tiles, chunk);
+    hipLaunchKernelGGL(gram_bf16_dma128_kernel, dim3(chunk * 8), dim3(GRAM_THREADS), dma2::LDS_BYTES, stream,
+                       static_cast<const uint16_t*>(X), n_tokens, int(d_in), ldx, H, n_rt, n_ct, n_tiles, chunk);
     ONECOMP_CHECK_LAUNCH();
     return ONECOMP_OK;
 }
@@ -719,12 +747,26 @@ onecomp_status launch_bf16_dma(const void* X, int64_t n_tokens, int64_t d_in, in
 
 onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
                                     hipStream_t stream) {
-    // 256-wide pipelined tiles once they give every CU at least a few tiles (and the 32-bit per-stage byte
-    // offsets cannot overflow); 128-wide tiles below that.
-    const int64_t n256 = ceil_div(d_in, 256);
-    if (n256 * (n256 + 1) / 2 >= 512 && ldx * 64 < (int64_t(1) << 31))
-        return launch_bf16_dma(X, n_tokens, d_in, ldx, H, stream);
-    return launch_bf16<2>(X, n_tokens, d_in, ldx, H, stream);
+    // The direct-to-LDS kernels need 32-bit byte offsets inside a step of tokens; narrow layers take the
+    // register-staged 128 x 128 kernel.  Between the two direct-to-LDS kernels the estimated number of rounds
+    // decides: 256 x 256 tiles run one per CU and cost two units each, 128 x 256 tiles run two per CU (a CU with
+    // two of them takes twice as long) and cost one unit plus 15 % for their higher L2 traffic per flop.
+    if (ldx * 64 >= (int64_t(1) << 31) || d_in < 1024) return launch_bf16<2>(X, n_tokens, d_in, ldx, H, stream);
+    static int n_cus = 0;
+    if (n_cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+            return ONECOMP_ERR_HIP;
+        n_cus = v;
+    }
+    const int64_t n256 = ceil_div(d_in, 256), n128 = ceil_div(d_in, 128);
+    const int64_t big = n256 * (n256 + 1) / 2;
+    int64_t mid = 0;
+    for (int64_t i = 0; i < n128; ++i) mid += n256 - i / 2;
+    const double cost_big = 2.0 * double(ceil_div(big, n_cus)), cost_mid = 1.15 * double(ceil_div(mid, n_cus));
+    if (cost_big <= cost_mid) return launch_bf16_dma(X, n_tokens, d_in, ldx, H, stream);
+    return launch_bf16_dma128(X, n_tokens, d_in, ldx, H, stream);
 }
 
 onecomp_status gram_accumulate_f32(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,

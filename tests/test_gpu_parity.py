@@ -93,6 +93,8 @@ def test_gram_c1_fp32():
 @pytest.mark.parametrize("d_in,n_tok,dtype", [
     (128, 77, torch.bfloat16), (384, 1000, torch.bfloat16), (528, 333, torch.bfloat16),
     (1024, 4099, torch.bfloat16), (144, 50, torch.float32), (384, 1001, torch.float32),
+    # 128 x 256 direct-to-LDS tiles: ragged channel edge, fewer tokens than the ring holds, odd number of steps
+    (1040, 333, torch.bfloat16), (1536, 17, torch.bfloat16), (2304, 1000, torch.bfloat16), (4096, 515, torch.bfloat16),
 ])
 def test_gram_ragged_shapes(d_in, n_tok, dtype):
     _announce(f"gram d_in={d_in} n_tok={n_tok} {dtype}")
@@ -106,8 +108,8 @@ def test_gram_ragged_shapes(d_in, n_tok, dtype):
 
 
 def test_gram_big_tiles_bf16():
-    # d_in large enough for the 256-wide tile path, several stages and a ragged token tail
-    _announce("gram d_in=8192 n_tok=1055 bf16 (256-wide tiles)")
+    # d_in large enough for the direct-to-LDS tile kernels, several stages and a ragged token tail
+    _announce("gram d_in=8192 n_tok=1055 bf16 (direct-to-LDS tiles)")
     cfg = synth.scaled(synth.CONFIGS["c2"], d_out=16, d_in=8192, n_tokens=1055, seed=5)
     X = synth.make_activations(cfg, DEV)
     H = _gpu_gram(X)
