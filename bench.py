@@ -71,7 +71,8 @@ def gram_kernel_name(d_in, bf16, n_cus=256):
     n256, n128 = -(-d_in // 256), -(-d_in // 128)
     big = n256 * (n256 + 1) // 2
     mid = sum(n256 - i // 2 for i in range(n128))
-    return "gram_bf16_dma_kernel" if 2.0 * -(-big // n_cus) <= 1.15 * -(-mid // n_cus) else "gram_bf16_dma128_kernel"
+    return ("gram_bf16_ring_kernel<RingBig>" if 2.0 * -(-big // n_cus) <= 1.15 * -(-mid // n_cus)
+            else "gram_bf16_ring_kernel<RingMid>")
 
 
 def cpu_baseline(cfg, synth, seconds_hint=20.0):

@@ -5,11 +5,11 @@
 //   * Only tiles on or above the diagonal are computed; each result is stored to H[i][k] and to
 //     its mirror H[k][i], so H stays bit-wise symmetric and one workgroup owns each tile
 //     (no floating-point atomics, reproducible).
-//   * bf16 path: square tile of 64*WT channels per workgroup, 4 waves in 2x2, each wave
-//     WT x WT tiles of v_mfma_f32_32x32x16_bf16.  X is token-major, the MFMA operands need 8
-//     consecutive TOKENS per lane: the token-major LDS tile is read with ds_read_b64_tr_b16
-//     (LDS transpose read), so no register shuffles are needed.  Double-buffered LDS, global
-//     loads of the next stage are in flight while the current one is multiplied.
+//   * bf16 path: X is token-major while the MFMA operands (v_mfma_f32_32x32x16_bf16) need 8 consecutive
+//     TOKENS per lane, so the token-major LDS tile is read with ds_read_b64_tr_b16 (LDS transpose read) and no
+//     register shuffles are needed.  Wide layers: ring kernel, tiles go global -> LDS directly (256 x 256 tile,
+//     8 waves; 128 x 256 tile, two workgroups per CU, when that fills the CUs better).  Narrow layers
+//     (d_in < 1024): register-staged 128 x 128 kernel, double-buffered LDS.
 //   * The workgroup -> tile map is XCD-aware: hardware deals consecutive workgroups round-robin to
 //     the 8 XCDs, so workgroup b is given the tile with rank (b % 8) * chunk + b / 8 in an
 //     order that walks bands of 4 tile rows column by column.  The 32 workgroups that share an
@@ -244,186 +244,52 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_kernel(const uint16_t*
 }
 
 // -------------------------------------------------------------------------------------------
-// bf16 kernel for large d_in, direct-to-LDS variant: 256 x 256 tile, global -> LDS without passing through
-// registers (buffer_load_dwordx4 ... lds), LDS ring of 4 stages, loads issued 3 stages ahead.
-//
-//   * One wave-wide 16-byte LDS load deposits lane l at  M0 + 16 l, i.e. 1 KB contiguous = two token rows
-//     of a 256-channel panel.  Rows therefore cannot be padded against bank conflicts; instead the 16-byte
-//     chunk c of token row r is stored at chunk position  c ^ ((r & 3) << 2):  the four token rows of one
+// bf16 ring kernel: global -> LDS without passing through registers (buffer_load_dwordx4 ... lds), in steps of
+// 16 tokens through a ring of NBUF LDS slots.  Two shapes:
+//   RingBig  256 x 256 tile, 8 waves (2 x 4, 128 x 64 each), i.e. two waves per SIMD: one wave's waits are covered
+//            by the other's MFMAs.  Only tiles on or above the diagonal (banded, XCD-aware order of tile_from_rank).
+//   RingMid  128 x 256 tile, 4 waves (2 x 2, 64 x 128 each), two workgroups per CU: for mid-size d_in, where
+//            256 x 256 tiles are too few to fill the CUs.  Tile (i, k) = rows [128 i, +128) x columns [256 k, +256)
+//            is computed when it reaches above the diagonal (k >= i / 2).
+// Tiles that the diagonal crosses store only their entries on or above it (and the mirrors).
+//   * One wave-wide 16-byte LDS load deposits lane l at M0 + 16 l, i.e. 1 KB contiguous = two (four) token rows
+//     of a 256 (128)-channel panel.  Rows therefore cannot be padded against bank conflicts; instead the 16-byte
+//     chunk c of token row r is stored at chunk position c ^ ((r & 3) << 2): the four token rows of one
 //     transpose read then fall into four different 64-byte bank groups.  The swizzle costs nothing on the
 //     global side because every lane supplies its own global address.
-//   * The loads are inline assembly, so the compiler neither sees the LDS write (and does not serialize
-//     later LDS reads behind it) nor counts them; the kernel waits explicitly with vmcnt(8 * stages
-//     still allowed in flight) before the barrier that publishes a stage.  Out-of-range lanes (token rows
-//     past the end, channels past d_in) deposit zeros: that is the raw-buffer range check.
-//   * iteration s:  loads of stage s+3;  LDS -> second-half fragments of stage s;  16 MFMAs (first half,
-//     fragments preloaded);  wait for stage s+1 + barrier;  LDS -> first-half fragments of stage s+1;
-//     16 MFMAs (second half).
+//   * The loads are inline assembly, so the compiler neither sees the LDS write (and does not serialize later
+//     LDS reads behind it) nor counts them; the kernel waits explicitly with vmcnt(loads per step x steps still
+//     allowed in flight) before the barrier that publishes a step.  Out-of-range lanes (token rows past the end,
+//     channels past d_in) deposit zeros: that is the raw-buffer range check.
+//   * An MFMA occupies the matrix pipe for 32 cycles but issues in 4: LDS reads and loads are placed one at a
+//     time behind the MFMAs.  Half-iteration h: MT NT MFMAs on the fragments of step h (registers); LDS ->
+//     fragments of step h+1; loads of step h+NBUF into the slot step h was read from; wait for step h+2 + barrier.
 // -------------------------------------------------------------------------------------------
-namespace dma {
-constexpr int TS = 256, KT = 32, ROWB = 512, PANELB = KT * ROWB, STAGEB = 2 * PANELB, NBUF = 4, DIST = 3;
-constexpr size_t LDS_BYTES = size_t(NBUF) * STAGEB;
-constexpr uint32_t OOB = LDS_DMA_OOB;
-constexpr int WAIT_VM0 = wait_vmcnt(0), WAIT_VM8 = wait_vmcnt(8), WAIT_VM16 = wait_vmcnt(16);
-}  // namespace dma
+struct RingMid {
+    static constexpr int TM = 128, TN = 256, WM = 2, WN = 2, NBUF = 6, MIN_WAVES = 2;
+};
+struct RingBig {
+    static constexpr int TM = 256, TN = 256, WM = 2, WN = 4, NBUF = 8, MIN_WAVES = 2;
+};
+template <typename C>
+struct Ring {
+    static constexpr int KT = 16;
+    static constexpr int WAVES = C::WM * C::WN, THREADS = 64 * WAVES;
+    static constexpr int MT = C::TM / (32 * C::WM), NT = C::TN / (32 * C::WN);   // 32 x 32 tiles per wave
+    static constexpr int A_ROWB = C::TM * 2, B_ROWB = C::TN * 2;
+    static constexpr int A_PANELB = KT * A_ROWB, B_PANELB = KT * B_ROWB, STAGEB = A_PANELB + B_PANELB;
+    static constexpr int NL_A = A_PANELB / 1024, NL_B = B_PANELB / 1024;          // 1 KB wave loads per panel
+    static constexpr int LPW = (NL_A + NL_B) / WAVES;                            // loads per wave and step
+    static constexpr size_t LDS_BYTES = size_t(C::NBUF) * STAGEB;
+    static_assert((NL_A + NL_B) % WAVES == 0 && NL_A % WAVES == 0, "whole loads per wave, A loads first");
+    static_assert(MT * NT == 8 && MT + NT == 6, "schedule below is written for 8 MFMAs and 6 fragments per step");
+};
+constexpr int RBAND = 8;   // 128-wide tile rows per band of the RingMid tile order
 
-__global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_dma_kernel(const uint16_t* __restrict__ X,
-                                                                    int64_t n_tokens, int d_in, int64_t ldx,
-                                                                    float* __restrict__ H, int n_t, int n_tiles,
-                                                                    int chunk) {
-    using namespace dma;
-    extern __shared__ __attribute__((aligned(1024))) char ldsb[];
-
-    const int v = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
-    if (v >= n_tiles) return;
-    int ti, tk;
-    tile_from_rank(v, n_t, ti, tk);
-    const bool diag = (ti == tk);
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wr = wave >> 1, wc = wave & 1;
-    const int i0 = ti * TS, k0 = tk * TS;
-    const uint32_t lds0 = uint32_t(uintptr_t((ONECOMP_LDS char*)ldsb));
-
-    // this wave's four 1 KB loads per panel: load q covers token rows 2 j and 2 j + 1, j = 4 wave + q
-    uint32_t voff_a[4], voff_b[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int row = 2 * (4 * wave + q) + (lane >> 5);
-        const int c = (lane & 31) ^ ((row & 3) << 2);       // logical chunk stored at position lane & 31
-        voff_a[q] = (i0 + c * 8 < d_in) ? uint32_t((int64_t(row) * ldx + i0 + c * 8) * 2) : OOB;
-        voff_b[q] = (k0 + c * 8 < d_in) ? uint32_t((int64_t(row) * ldx + k0 + c * 8) * 2) : OOB;
-    }
-    const int64_t n_stage = (n_tokens + KT - 1) / KT;
-    auto gload = [&](int64_t st, int buf) __attribute__((always_inline)) {
-        const int64_t t0 = st * KT;
-        const char* base = reinterpret_cast<const char*>(X) + t0 * ldx * 2;
-        const int64_t left = (n_tokens - t0) * ldx * 2;
-        const int range = left > 0x7FFFFFFF ? 0x7FFFFFFF : int(left);
-        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, range, 0x00020000);
-        const uint32_t dst = lds0 + buf * STAGEB + wave * 4096;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            lds_load16(dst + q * 1024, voff_a[q], rsrc);
-            lds_load16(dst + PANELB + q * 1024, voff_b[q], rsrc);
-        }
-    };
-
-    // transpose-read addressing with the chunk swizzle (see the generic kernel for the lane roles)
-    const int i16 = lane & 15, g16 = (lane >> 4) & 1, kb8 = lane >> 5;
-    const int kq = i16 >> 2;                                        // token row within its group of 4
-    const int lo = (2 * g16 + ((i16 & 3) >> 1)) * 16 + (i16 & 1) * 8;  // byte offset inside the 64-byte group
-    const int fbase_a = (kb8 * 8 + kq) * ROWB + wr * 256 + lo;
-    const int fbase_b = PANELB + (kb8 * 8 + kq) * ROWB + wc * 256 + lo;
-    int xm[4];
-#pragma unroll
-    for (int m = 0; m < 4; ++m) xm[m] = (m ^ kq) << 6;
-
-    struct Frags {
-        bf16x8 a[4], b[4];
-    };
-    // one operand fragment = two transpose reads (tokens 0..3 and 4..7 of this lane's half of the 16-token block)
-    auto rd_a = [&](Frags& f, int m, int buf, int kb) __attribute__((always_inline)) {
-        const char* pa = ldsb + buf * STAGEB + kb * 16 * ROWB + fbase_a + xm[m];
-        short4v l0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pa));
-        short4v h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pa + 4 * ROWB));
-        f.a[m] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(l0, h0, 0, 1, 2, 3, 4, 5, 6, 7));
-    };
-    auto rd_b = [&](Frags& f, int n, int buf, int kb) __attribute__((always_inline)) {
-        const char* pb = ldsb + buf * STAGEB + kb * 16 * ROWB + fbase_b + xm[n];
-        short4v l0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pb));
-        short4v h0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(pb + 4 * ROWB));
-        f.b[n] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(l0, h0, 0, 1, 2, 3, 4, 5, 6, 7));
-    };
-    // fragment number r in the order the MFMAs need them: a0 b0 b1 b2 b3 a1 a2 a3
-    auto rd = [&](Frags& f, int r, int buf, int kb) __attribute__((always_inline)) {
-        if (r == 0) rd_a(f, 0, buf, kb);
-        else if (r <= 4) rd_b(f, r - 1, buf, kb);
-        else rd_a(f, r - 4, buf, kb);
-    };
-
-    float16v acc[4][4];
-#pragma unroll
-    for (int m = 0; m < 4; ++m)
-#pragma unroll
-        for (int n = 0; n < 4; ++n)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
-
-    Frags Fc, FH;
-    // prologue: stages 0 .. 2 in flight, stage 0 landed, first-half fragments of stage 0
-    for (int st = 0; st < DIST && st < n_stage; ++st) gload(st, st);
-    __builtin_amdgcn_s_waitcnt(WAIT_VM0);
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < 8; ++r) rd(Fc, r, 0, 0);
-    int buf = 0;
-#pragma unroll 1
-    for (int64_t s = 0; s < n_stage; ++s) {
-        const int nbuf = (buf + 1) & (NBUF - 1);
-        const bool has1 = (s + 1 < n_stage), has3 = (s + DIST < n_stage);
-        // loads of stage s+3: descriptor once, the eight 1 KB loads are spread between the MFMAs below
-        const int64_t t3 = (s + DIST) * KT;
-        const int64_t left = (n_tokens - t3) * ldx * 2;
-        const int range = left > 0x7FFFFFFF ? 0x7FFFFFFF : (left < 0 ? 0 : int(left));
-        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<char*>(reinterpret_cast<const char*>(X) + (has3 ? t3 : 0) * ldx * 2), 0, has3 ? range : 0, 0x00020000);
-        const uint32_t dst = lds0 + ((buf + DIST) & (NBUF - 1)) * STAGEB + wave * 4096;
-        // An MFMA occupies the matrix pipe for 32 cycles but issues in 4: the other instructions of the
-        // iteration are placed one or two at a time behind each MFMA so that the pipe never waits for them.
-        // First half: MFMAs on the preloaded fragments Fc; second-half fragments FH and the DMA loads ride along.
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            acc[i / 4][i % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Fc.a[i / 4], Fc.b[i % 4], acc[i / 4][i % 4], 0, 0, 0);
-            if ((i & 1) == 0) {
-                rd(FH, i / 2, buf, 1);
-            } else if (has3) {
-                const int q = i / 2;    // 0..7: loads 0..3 -> panel A, 4..7 -> panel B
-                if (q < 4) lds_load16(dst + q * 1024, voff_a[q], rsrc);
-                else lds_load16(dst + PANELB + (q - 4) * 1024, voff_b[q - 4], rsrc);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // stage s+1 must have landed; loads of stages s+2 and s+3 (8 per wave each) may stay in flight
-        const int64_t ahead = n_stage - 2 - s;   // stages issued beyond s+1
-        if (ahead >= 2) __builtin_amdgcn_s_waitcnt(WAIT_VM16);
-        else if (ahead == 1) __builtin_amdgcn_s_waitcnt(WAIT_VM8);
-        else __builtin_amdgcn_s_waitcnt(WAIT_VM0);
-        __syncthreads();
-        // second half: MFMAs on FH; first-half fragments of stage s+1 ride along
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            acc[i / 4][i % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FH.a[i / 4], FH.b[i % 4], acc[i / 4][i % 4], 0, 0, 0);
-            if ((i & 1) == 0 && has1) rd(Fc, i / 2, nbuf, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        buf = nbuf;
-    }
-
-    gram_store<4, 4>(acc, H, d_in, i0 + wr * 128, k0 + wc * 128, diag, lane);
-}
-
-// -------------------------------------------------------------------------------------------
-// bf16 kernel for mid-size d_in (too few 256 x 256 tiles to fill the CUs): 128 x 256 tile, two workgroups per CU.
-// Tile (i, k) = channel rows [128 i, +128) x channel columns [256 k, +256) is computed when it reaches above the
-// diagonal (k >= i / 2); tiles that the diagonal crosses store only their entries on or above it (and the
-// mirrors).  Same direct-to-LDS scheme and chunk swizzle as the 256 x 256 kernel, in steps of 16 tokens:
-// A panel 16 x 256 B, B panel 16 x 512 B, ring of 6 slots (72 KB).  Half-iteration h: 8 MFMAs on the fragments
-// of step h (registers); LDS -> fragments of step h+1; loads of step h+6 into the slot step h was read from;
-// wait for step h+2 + barrier.
-// -------------------------------------------------------------------------------------------
-namespace dma2 {
-constexpr int TM = 128, TN = 256, KT = 16, NBUF = 6;
-constexpr int A_ROWB = TM * 2, B_ROWB = TN * 2;
-constexpr int A_PANELB = KT * A_ROWB, B_PANELB = KT * B_ROWB, STAGEB = A_PANELB + B_PANELB;   // 4 + 8 KB
-constexpr size_t LDS_BYTES = size_t(NBUF) * STAGEB;
-constexpr int RBAND = 8;   // 128-wide tile rows per band of the tile order
-}  // namespace dma2
-
-// rank v -> tile (ti, tk): bands of RBAND tile rows, inside a band column by column, rows fastest
+// rank v -> RingMid tile (ti, tk): bands of RBAND tile rows, inside a band column by column, rows fastest
 __device__ inline void tile128_from_rank(int v, int n_rt, int n_ct, int& ti, int& tk) {
     for (int a = 0;; ++a) {
-        const int r0 = a * dma2::RBAND, rows = min(dma2::RBAND, n_rt - r0);
+        const int r0 = a * RBAND, rows = min(RBAND, n_rt - r0);
         for (int k = r0 / 2; k < n_ct; ++k) {
             const int valid = min(rows, 2 * k + 2 - r0);   // rows r0 .. r0+valid-1 satisfy i / 2 <= k
             if (v < valid) { ti = r0 + v; tk = k; return; }
@@ -432,36 +298,41 @@ __device__ inline void tile128_from_rank(int v, int n_rt, int n_ct, int& ti, int
     }
 }
 
-__global__ __launch_bounds__(GRAM_THREADS, 2) void gram_bf16_dma128_kernel(const uint16_t* __restrict__ X,
-                                                                          int64_t n_tokens, int d_in, int64_t ldx,
-                                                                          float* __restrict__ H, int n_rt, int n_ct,
-                                                                          int n_tiles, int chunk) {
-    using namespace dma2;
+template <typename C>
+__global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring_kernel(const uint16_t* __restrict__ X,
+                                                                         int64_t n_tokens, int d_in, int64_t ldx,
+                                                                         float* __restrict__ H, int n_rt, int n_ct,
+                                                                         int n_tiles, int chunk) {
+    using R = Ring<C>;
+    constexpr int KT = R::KT, NBUF = C::NBUF, MT = R::MT, NT = R::NT, LPW = R::LPW;
+    constexpr int A_ROWB = R::A_ROWB, B_ROWB = R::B_ROWB, A_PANELB = R::A_PANELB, STAGEB = R::STAGEB;
     extern __shared__ __attribute__((aligned(1024))) char ldsb[];
     const int v = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
     if (v >= n_tiles) return;
     int ti, tk;
-    tile128_from_rank(v, n_rt, n_ct, ti, tk);
-    const int i0 = ti * TM, k0 = tk * TN;
-    const bool diag = k0 < i0 + TM;   // some entry of the tile lies on or below the diagonal
+    if constexpr (C::TM == C::TN) tile_from_rank(v, n_ct, ti, tk);
+    else tile128_from_rank(v, n_rt, n_ct, ti, tk);
+    const int i0 = ti * C::TM, k0 = tk * C::TN;
+    const bool diag = k0 < i0 + C::TM;   // some entry of the tile lies on or below the diagonal
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wr = wave >> 1, wc = wave & 1;
+    const int wr = wave / C::WN, wc = wave % C::WN;
     const uint32_t lds0 = uint32_t(uintptr_t((ONECOMP_LDS char*)ldsb));
 
-    // this wave's three 1 KB loads per step: token rows 4 wave .. 4 wave + 3 of the A panel (one load) and of the
-    // B panel (two loads of two rows)
-    uint32_t voff_a, voff_b[2];
-    {
-        const int row = 4 * wave + (lane >> 4);
-        const int c = (lane & 15) ^ ((row & 3) << 2);
-        voff_a = (i0 + c * 8 < d_in) ? uint32_t((int64_t(row) * ldx + i0 + c * 8) * 2) : LDS_DMA_OOB;
-    }
+    // this wave's LPW 1 KB loads per step: load j = wave + WAVES q; j < NL_A is a load of the A panel
+    uint32_t voff[LPW], ldst[LPW];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int row = 4 * wave + 2 * q + (lane >> 5);
-        const int c = (lane & 31) ^ ((row & 3) << 2);
-        voff_b[q] = (k0 + c * 8 < d_in) ? uint32_t((int64_t(row) * ldx + k0 + c * 8) * 2) : LDS_DMA_OOB;
+    for (int q = 0; q < LPW; ++q) {
+        const int j = wave + R::WAVES * q;
+        const bool is_a = j < R::NL_A;
+        const int jj = is_a ? j : j - R::NL_A;
+        const int rowb = is_a ? A_ROWB : B_ROWB;
+        const int lpr = rowb / 16;                         // lanes (16-byte chunks) per token row
+        const int row = jj * (64 / lpr) + lane / lpr;
+        const int c = (lane % lpr) ^ ((row & 3) << 2);
+        const int col = (is_a ? i0 : k0) + c * 8;
+        voff[q] = (col < d_in) ? uint32_t((int64_t(row) * ldx + col) * 2) : LDS_DMA_OOB;
+        ldst[q] = (is_a ? 0 : A_PANELB) + jj * 1024;
     }
     const int64_t n_st = (n_tokens + KT - 1) / KT;
     const int64_t n_st2 = (n_st + 1) & ~int64_t(1);   // the loop takes two steps at a time; an extra step is all zeros
@@ -485,60 +356,55 @@ __global__ __launch_bounds__(GRAM_THREADS, 2) void gram_bf16_dma128_kernel(const
             0x00020000);
         return d;
     };
-    auto gload1 = [&](const Desc& d, uint32_t dst, int i) __attribute__((always_inline)) {
-        if (i == 0) lds_load16(dst + wave * 1024, voff_a, d.r);
-        else if (i == 1) lds_load16(dst + A_PANELB + wave * 2048, voff_b[0], d.r);
-        else lds_load16(dst + A_PANELB + wave * 2048 + 1024, voff_b[1], d.r);
-    };
 
     const int i16 = lane & 15, g16 = (lane >> 4) & 1, kb8 = lane >> 5;
     const int kq = i16 >> 2;
     const int lo = (2 * g16 + ((i16 & 3) >> 1)) * 16 + (i16 & 1) * 8;
-    int fa[2], fb[4];
+    int fa[MT], fb[NT];
 #pragma unroll
-    for (int m = 0; m < 2; ++m) fa[m] = (kb8 * 8 + kq) * A_ROWB + (((wr * 2 + m) ^ kq) << 6) + lo;
+    for (int m = 0; m < MT; ++m) fa[m] = (kb8 * 8 + kq) * A_ROWB + (((wr * MT + m) ^ kq) << 6) + lo;
 #pragma unroll
-    for (int n = 0; n < 4; ++n) fb[n] = A_PANELB + (kb8 * 8 + kq) * B_ROWB + wc * 256 + ((n ^ kq) << 6) + lo;
+    for (int n = 0; n < NT; ++n) fb[n] = A_PANELB + (kb8 * 8 + kq) * B_ROWB + (((wc * NT + n) ^ kq) << 6) + lo;
 
     struct Frags {
-        bf16x8 a[2], b[4];
+        bf16x8 a[MT], b[NT];
     };
     auto rd2 = [&](const char* p, int rowb) __attribute__((always_inline)) {
         short4v x0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(p));
         short4v x1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ONECOMP_LDS short4v*)(p + 4 * rowb));
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7));
     };
-    // fragment r (0..5) of the slot at ldsb + sb, in the order the MFMAs use them: a0 b0 b1 b2 b3 a1
+    // fragment r (0 .. MT+NT-1) of the slot at ldsb + sb: A fragments first
     auto rd = [&](Frags& f, int r, int sb) __attribute__((always_inline)) {
         const char* s = ldsb + sb;
-        if (r == 0) f.a[0] = rd2(s + fa[0], A_ROWB);
-        else if (r <= 4) f.b[r - 1] = rd2(s + fb[r - 1], B_ROWB);
-        else f.a[1] = rd2(s + fa[1], A_ROWB);
+        if (r < MT) f.a[r] = rd2(s + fa[r], A_ROWB);
+        else f.b[r - MT] = rd2(s + fb[r - MT], B_ROWB);
     };
 
     for (int st = 0; st < NBUF; ++st) {
         const Desc d = make_desc(st);
 #pragma unroll
-        for (int i = 0; i < 3; ++i) gload1(d, lds0 + st * STAGEB, i);
+        for (int q = 0; q < LPW; ++q) lds_load16(lds0 + st * STAGEB + ldst[q], voff[q], d.r);
     }
-    float16v acc[2][4];
+    float16v acc[MT][NT];
 #pragma unroll
-    for (int m = 0; m < 2; ++m)
+    for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int n = 0; n < 4; ++n)
+        for (int n = 0; n < NT; ++n)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
     __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));
     __syncthreads();
     Frags Fc, FH;
 #pragma unroll
-    for (int r = 0; r < 6; ++r) rd(Fc, r, 0);
+    for (int r = 0; r < MT + NT; ++r) rd(Fc, r, 0);
     __syncthreads();   // slot 0 is overwritten by the loads of the first half-iteration
 
     auto mma = [&](const Frags& f, auto&& between) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            acc[i / 4][i % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i / 4], f.b[i % 4], acc[i / 4][i % 4], 0, 0, 0);
+        for (int i = 0; i < MT * NT; ++i) {
+            acc[i / NT][i % NT] =
+                __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i / NT], f.b[i % NT], acc[i / NT][i % NT], 0, 0, 0);
             between(i);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -555,10 +421,10 @@ __global__ __launch_bounds__(GRAM_THREADS, 2) void gram_bf16_dma128_kernel(const
             const uint32_t dst = lds0 + s0 * STAGEB;
             const int sb = s1 * STAGEB;
             mma(Fc, [&](int i) __attribute__((always_inline)) {
-                if (i < 6) rd(FH, i, sb);
-                if (i < 3) gload1(d, dst, i);
+                if (i < MT + NT) rd(FH, i, sb);
+                if (i < LPW) lds_load16(dst + ldst[i], voff[i], d.r);
             });
-            __builtin_amdgcn_s_waitcnt(wait_vmcnt(3 * (NBUF - 2)));   // step st+2 has landed
+            __builtin_amdgcn_s_waitcnt(wait_vmcnt(LPW * (NBUF - 2)));   // step st+2 has landed
             __syncthreads();
         }
         {
@@ -566,17 +432,18 @@ __global__ __launch_bounds__(GRAM_THREADS, 2) void gram_bf16_dma128_kernel(const
             const uint32_t dst = lds0 + s1 * STAGEB;
             const int sb = s2 * STAGEB;
             mma(FH, [&](int i) __attribute__((always_inline)) {
-                if (i < 6) rd(Fc, i, sb);
-                if (i < 3) gload1(d, dst, i);
+                if (i < MT + NT) rd(Fc, i, sb);
+                if (i < LPW) lds_load16(dst + ldst[i], voff[i], d.r);
             });
-            __builtin_amdgcn_s_waitcnt(wait_vmcnt(3 * (NBUF - 2)));   // step st+3 has landed
+            __builtin_amdgcn_s_waitcnt(wait_vmcnt(LPW * (NBUF - 2)));   // step st+3 has landed
             __syncthreads();
         }
         s0 = s2;
     }
     __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // no LDS write may be in flight when the workgroup ends
-    gram_store<2, 4>(acc, H, d_in, i0 + wr * 64, k0 + wc * 128, diag, lane);
+    gram_store<MT, NT>(acc, H, d_in, i0 + wr * (32 * MT), k0 + wc * (32 * NT), diag, lane);
 }
+
 
 // -------------------------------------------------------------------------------------------
 // fp32 kernel: 128 x 128 tile, 4 waves in 2x2, each 2x2 tiles of v_mfma_f32_32x32x2_f32
@@ -706,39 +573,24 @@ onecomp_status launch_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_
 
 
 
-onecomp_status launch_bf16_dma128(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
-                                  hipStream_t stream) {
-    const int n_rt = int(ceil_div(d_in, dma2::TM)), n_ct = int(ceil_div(d_in, dma2::TN));
+template <typename C>
+onecomp_status launch_bf16_ring(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
+                                hipStream_t stream) {
+    using R = Ring<C>;
+    const int n_rt = int(ceil_div(d_in, C::TM)), n_ct = int(ceil_div(d_in, C::TN));
     int n_tiles = 0;
-    for (int i = 0; i < n_rt; ++i) n_tiles += n_ct - i / 2;
+    if (C::TM == C::TN) n_tiles = n_ct * (n_ct + 1) / 2;
+    else for (int i = 0; i < n_rt; ++i) n_tiles += n_ct - i / 2;
     const int chunk = int(ceil_div(n_tiles, 8));
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_dma128_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(dma2::LDS_BYTES)) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_ring_kernel<C>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(R::LDS_BYTES)) != hipSuccess)
             return ONECOMP_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL(gram_bf16_dma128_kernel, dim3(chunk * 8), dim3(GRAM_THREADS), dma2::LDS_BYTES, stream,
+    hipLaunchKernelGGL(gram_bf16_ring_kernel<C>, dim3(chunk * 8), dim3(R::THREADS), R::LDS_BYTES, stream,
                        static_cast<const uint16_t*>(X), n_tokens, int(d_in), ldx, H, n_rt, n_ct, n_tiles, chunk);
-    ONECOMP_CHECK_LAUNCH();
-    return ONECOMP_OK;
-}
-
-onecomp_status launch_bf16_dma(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
-                               hipStream_t stream) {
-    const int n_t = int(ceil_div(d_in, dma::TS));
-    const int n_tiles = n_t * (n_t + 1) / 2;
-    const int chunk = int(ceil_div(n_tiles, 8));
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_dma_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(dma::LDS_BYTES)) != hipSuccess)
-            return ONECOMP_ERR_HIP;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(gram_bf16_dma_kernel, dim3(chunk * 8), dim3(GRAM_THREADS), dma::LDS_BYTES, stream,
-                       static_cast<const uint16_t*>(X), n_tokens, int(d_in), ldx, H, n_t, n_tiles, chunk);
     ONECOMP_CHECK_LAUNCH();
     return ONECOMP_OK;
 }
@@ -765,8 +617,8 @@ onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_i
     int64_t mid = 0;
     for (int64_t i = 0; i < n128; ++i) mid += n256 - i / 2;
     const double cost_big = 2.0 * double(ceil_div(big, n_cus)), cost_mid = 1.15 * double(ceil_div(mid, n_cus));
-    if (cost_big <= cost_mid) return launch_bf16_dma(X, n_tokens, d_in, ldx, H, stream);
-    return launch_bf16_dma128(X, n_tokens, d_in, ldx, H, stream);
+    if (cost_big <= cost_mid) return launch_bf16_ring<RingBig>(X, n_tokens, d_in, ldx, H, stream);
+    return launch_bf16_ring<RingMid>(X, n_tokens, d_in, ldx, H, stream);
 }
 
 onecomp_status gram_accumulate_f32(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
