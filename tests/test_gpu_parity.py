@@ -125,6 +125,41 @@ def test_gram_big_tiles_bf16():
     np.testing.assert_allclose(Hn[d, d], 2.0 * (Xd * Xd).sum(0), rtol=1e-4)
 
 
+def test_gram_full_calibration_set_sampled():
+    """The Gram launch exactly as bench.py times it: 262144 tokens x 14336 channels (bf16) in ONE call.  The full
+    float64 product is out of reach of the host, so the oracle computes sampled index blocks (over all tokens)
+    and the diagonal; symmetry and additivity over calls are checked on the whole matrix."""
+    cfg = synth.CONFIGS["c3b"]
+    d_in = cfg.d_in
+    _announce(f"gram full calibration set: {cfg.n_tokens} tokens x {d_in} channels, one call")
+    X = synth.make_activations(cfg, DEV)
+    H = _gpu_gram(X)
+    assert torch.equal(H, H.T)
+    r = np.random.default_rng(11)
+    for s_i in range(4):
+        i = np.sort(r.choice(d_in, size=96, replace=False))
+        k = np.sort(r.choice(d_in, size=96, replace=False))
+        cols = np.unique(np.concatenate([i, k]))
+        Xs = to_f64(X[:, torch.from_numpy(cols).to(DEV)])          # gathered on the GPU: 262144 x <=192
+        pos = {c: n for n, c in enumerate(cols)}
+        ii = np.array([pos[c] for c in i]); kk = np.array([pos[c] for c in k])
+        ref = oc.hessian_tile(Xs, ii, kk)
+        got = H[torch.from_numpy(i).to(DEV)][:, torch.from_numpy(k).to(DEV)].cpu().numpy().astype(np.float64)
+        err = rel_fro(got, ref)
+        _announce(f"   block {s_i}: rel. Frobenius error {err:.2e}")
+        assert err <= 1e-4
+        if s_i == 0:
+            dref = 2.0 * (Xs * Xs).sum(0)
+            dgot = H[torch.from_numpy(cols).to(DEV), torch.from_numpy(cols).to(DEV)].cpu().numpy()
+            np.testing.assert_allclose(dgot, dref, rtol=1e-4)
+        del Xs
+    H4 = _gpu_gram(X, chunks=4)
+    assert torch.equal(H4, H4.T)
+    diff = (H4 - H).double().norm().item() / H.double().norm().item()
+    _announce(f"   one call vs four calls: rel. difference {diff:.2e}")
+    assert diff <= 1e-5
+
+
 def test_gram_zero_tokens_and_strided_rows():
     _announce("gram zero tokens / strided X")
     cfg = synth.scaled(synth.CONFIGS["c2"], d_out=16, d_in=256, n_tokens=300, seed=4)
