@@ -19,6 +19,8 @@ What it computes (paper sections given in brackets):
     quantized  [Sec. 4.2; grid: Eq. (1) scalar quantizer, Eq. (2) min-max
     scale / zero-point, Eq. (4) per-group layout]
   * the layer objective tr((W-W^) H (W-W^)^T)  [Eq. (layerwise), Eq. (activation-aware)]
+  * the corrected quantization target of error propagation (QEP),
+    W* = (I + alpha (H^ + lambda I)^-1 C) W  with  C = X^^T (X - X^)  [Sec. 4.2.1, Eq. (qep)]
 
 Storage convention: W is d_out x d_in (rows = output channels), i.e. the
 transpose of the paper's N x M matrix; "column j" is input channel j and a group
@@ -283,3 +285,42 @@ def dequantize(Q, scales, zeros, group_size, perm=None):
     inv[np.asarray(perm)] = np.arange(d_in)
     g = inv // int(group_size)
     return np.asarray(scales, dtype=np.float64)[:, g] * (Q - np.asarray(zeros, dtype=np.float64)[:, g])
+
+
+# --------------------------------------------------------------------------
+# Error propagation (QEP): corrected quantization target  [Sec. 4.2.1, Eq. (qep_obj), Eq. (qep)]
+# --------------------------------------------------------------------------
+def crossgram_accumulate(X_hat, X, G=None):
+    """G + 2 * X_hat^T X in float64.
+
+    X_hat: activations seen by the partly quantized model, X: full-precision activations, both
+    [n_tokens, d_in].  With H = 2 X_hat^T X_hat the error-propagation matrix of Sec. 4.2.1 is
+    C = X_hat^T (X - X_hat) = (G - H) / 2; the factor 2 is the one of hessian_accumulate.
+    """
+    X_hat = np.asarray(X_hat, dtype=np.float64)
+    X = np.asarray(X, dtype=np.float64)
+    P = 2.0 * (X_hat.T @ X)
+    return P if G is None else np.asarray(G, dtype=np.float64) + P
+
+
+def qep_target(W, G, H, damp, alpha):
+    """Corrected target of Eq. (qep) in the d_out x d_in storage convention.
+
+    Paper (W_p = W^T is d_in x d_out):  W_p* = (I + alpha (H^_p + lambda_p I)^-1 C) W_p  with
+    H^_p = X_hat^T X_hat, C = X_hat^T (X - X_hat), lambda_p = damp * mean(diag H^_p).
+    Here H = 2 H^_p and G = 2 X_hat^T X, so 2 C = G - H, lambda = damp * mean(diag H) = 2 lambda_p and
+    (H^_p + lambda_p I)^-1 C = (H + lambda I)^-1 (G - H).  Transposed:
+        W* = W + alpha * W (G - H)^T (H + lambda I)^-1.
+    The damped matrix is the one damp_hessian builds (a dead channel's diagonal entry becomes 1 first).
+    The inverse is applied with a symmetric positive definite solve (Cholesky based, as Sec. 4.2.1 says).
+    """
+    from scipy.linalg import cho_factor, cho_solve
+    W = np.asarray(W, dtype=np.float64)
+    G = np.asarray(G, dtype=np.float64)
+    H = np.asarray(H, dtype=np.float64)
+    Hd, _ = damp_hessian(H, damp)
+    C2 = G - H                                   # = 2 C
+    R = W @ C2.T                                 # d_out x d_in
+    cf = cho_factor(Hd, lower=True)
+    corr = cho_solve(cf, R.T).T                  # R Hd^-1 (Hd symmetric)
+    return W + float(alpha) * corr
