@@ -142,6 +142,46 @@ onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w_dtype, int6
 size_t onecomp_factor_workspace_bytes(int64_t d_in);
 size_t onecomp_quantize_workspace_bytes(int64_t d_out, int64_t d_in, int block_size);
 
+/*
+ * Error propagation (QEP, Sec. 4.2.1): cross-Gram of the activations X_hat that reach this layer in the partly
+ * quantized model and the activations X of the full-precision model,
+ *     G += 2 X_hat^T X        (the factor 2 of onecomp_hessian_accumulate),
+ * so that with H = 2 X_hat^T X_hat (onecomp_hessian_accumulate on X_hat) the error-propagation matrix of the
+ * paper is C = X_hat^T (X - X_hat) = (G - H) / 2.  The caller zero-fills G before the first chunk.
+ *   X_hat, X  [n_tokens x d_in] row-major, row strides ldxh / ldx elements, ONECOMP_BF16 only; read only.
+ *             bf16 products are exact in fp32; accumulation is fp32.
+ *   G         [d_in x d_in] fp32, row-major, not symmetric: G[i][k] pairs channel i of X_hat with channel k of X.
+ *   d_in      multiple of 16; a step of 16 token rows must be addressable with 32-bit byte offsets
+ *             (row stride below 2^25 elements), else ONECOMP_ERR_UNSUPPORTED.
+ */
+onecomp_status onecomp_crossgram_accumulate(const void* X_hat, const void* X, onecomp_dtype x_dtype,
+                                            int64_t n_tokens, int64_t d_in, int64_t ldxh, int64_t ldx,
+                                            float* G, void* hip_stream);
+
+/*
+ * Corrected quantization target of Eq. (qep), Sec. 4.2.1 (paper: W* = (I + alpha (H^ + lambda I)^-1 C) W for
+ * the d_in x d_out weight).  In this library's d_out x d_in storage and scaling:
+ *     W* = W + alpha W (G - H)^T (H + lambda I)^-1,   lambda = damp * mean(diag H),
+ * where the regularized inverse is taken from the factor of onecomp_hessian_factor(H, damp, ...):
+ * (H + lambda I)^-1 = P U^T U P^T with P the column order `perm` of that call.  W* is then passed to
+ * onecomp_quantize_layer (as ONECOMP_F32) together with the same U and perm.
+ *   W        [d_out x d_in] row-major, dtype w_dtype, original column order; read only.
+ *   G, H     [d_in x d_in] fp32 as accumulated by the two accumulate calls on the same tokens; read only.
+ *   U, perm  outputs of onecomp_hessian_factor for this H (perm NULL = natural order); read only.
+ *   alpha    propagation strength in [0, 1].
+ *   W_star   [d_out x d_in] fp32, original column order, out; must not alias W.
+ *   workspace device scratch, >= onecomp_qep_workspace_bytes(d_out, d_in), 256-byte aligned.
+ * Arithmetic: fp32 throughout (three GEMMs with fp32 products).  G - H cancels the leading digits of two Gram
+ * matrices, so the correction W* - W carries a relative error of about 1e-6 |X| / |X - X_hat|.
+ */
+onecomp_status onecomp_qep_target(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                  const float* G, const float* H, const float* U, const int32_t* perm,
+                                  float alpha, float* W_star,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Scratch size for onecomp_qep_target (0 if the arguments are invalid): about 4 d_in^2 + 12 d_out d_in bytes. */
+size_t onecomp_qep_workspace_bytes(int64_t d_out, int64_t d_in);
+
 /* Static, NUL-terminated description of a status code. */
 const char* onecomp_status_string(onecomp_status status);
 

@@ -8,9 +8,12 @@ from .binding import (  # noqa: F401
     LIB_PATH,
     OnecompError,
     load_library,
+    onecomp_crossgram_accumulate,
     onecomp_factor_workspace_bytes,
     onecomp_hessian_accumulate,
     onecomp_hessian_factor,
+    onecomp_qep_target,
+    onecomp_qep_workspace_bytes,
     onecomp_quantize_layer,
     onecomp_quantize_workspace_bytes,
     onecomp_version,

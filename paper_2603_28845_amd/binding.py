@@ -26,6 +26,9 @@ EXPORTED_SYMBOLS = (
     "onecomp_quantize_layer",
     "onecomp_factor_workspace_bytes",
     "onecomp_quantize_workspace_bytes",
+    "onecomp_crossgram_accumulate",
+    "onecomp_qep_target",
+    "onecomp_qep_workspace_bytes",
     "onecomp_status_string",
     "onecomp_version",
 )
@@ -60,6 +63,12 @@ def load_library() -> ctypes.CDLL:
     lib.onecomp_factor_workspace_bytes.restype = sz
     lib.onecomp_quantize_workspace_bytes.argtypes = [i64, i64, i32]
     lib.onecomp_quantize_workspace_bytes.restype = sz
+    lib.onecomp_crossgram_accumulate.argtypes = [vp, vp, i32, i64, i64, i64, i64, vp, vp]
+    lib.onecomp_crossgram_accumulate.restype = i32
+    lib.onecomp_qep_target.argtypes = [vp, i32, i64, i64, vp, vp, vp, vp, f32, vp, vp, sz, vp]
+    lib.onecomp_qep_target.restype = i32
+    lib.onecomp_qep_workspace_bytes.argtypes = [i64, i64]
+    lib.onecomp_qep_workspace_bytes.restype = sz
     lib.onecomp_status_string.argtypes = [i32]
     lib.onecomp_status_string.restype = ctypes.c_char_p
     lib.onecomp_version.argtypes = []
@@ -180,3 +189,48 @@ def onecomp_quantize_layer(W: torch.Tensor, U: torch.Tensor, bits: int, group_si
     if rc != ONECOMP_OK:
         raise OnecompError(rc, "onecomp_quantize_layer")
     return out
+
+
+def onecomp_qep_workspace_bytes(d_out: int, d_in: int) -> int:
+    return int(load_library().onecomp_qep_workspace_bytes(int(d_out), int(d_in)))
+
+
+def onecomp_crossgram_accumulate(X_hat: torch.Tensor, X: torch.Tensor, G: torch.Tensor) -> None:
+    """G += 2 X_hat^T X.  X_hat, X: [n_tokens, d_in] bf16 (rows may be strided), G: [d_in, d_in] fp32."""
+    lib = load_library()
+    if X.dim() != 2 or X_hat.shape != X.shape or G.dim() != 2 or G.shape[0] != G.shape[1] or G.shape[0] != X.shape[1]:
+        raise ValueError("shapes: X_hat, X [n_tokens, d_in], G [d_in, d_in]")
+    if X.shape[0] > 0 and (X.stride(1) != 1 or X_hat.stride(1) != 1):
+        raise ValueError("rows of X_hat and X must be dense")
+    if X_hat.dtype != X.dtype:
+        raise TypeError("X_hat and X must have the same dtype")
+    _dev(X, "X", contiguous=False)
+    _dev(X_hat, "X_hat", contiguous=False)
+    ldx = X.stride(0) if X.shape[0] > 1 else X.shape[1]
+    ldxh = X_hat.stride(0) if X_hat.shape[0] > 1 else X_hat.shape[1]
+    rc = lib.onecomp_crossgram_accumulate(_ptr(X_hat), _ptr(X), _dtype_code(X), X.shape[0], X.shape[1], ldxh, ldx,
+                                          _dev(G, "G", torch.float32), _stream())
+    if rc != ONECOMP_OK:
+        raise OnecompError(rc, "onecomp_crossgram_accumulate")
+
+
+def onecomp_qep_target(W: torch.Tensor, G: torch.Tensor, H: torch.Tensor, U: torch.Tensor, alpha: float,
+                       perm: Optional[torch.Tensor] = None, W_star: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Returns W* = W + alpha W (G - H)^T (H + lambda I)^-1 as an fp32 device tensor (U, perm from the factor call)."""
+    lib = load_library()
+    d_out, d_in = W.shape
+    if W_star is None:
+        W_star = torch.empty((d_out, d_in), dtype=torch.float32, device=W.device)
+    need = onecomp_qep_workspace_bytes(d_out, d_in)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W.device)
+    if perm is not None:
+        _dev(perm, "perm", torch.int32)
+    rc = lib.onecomp_qep_target(_dev(W, "W"), _dtype_code(W), d_out, d_in, _dev(G, "G", torch.float32),
+                                _dev(H, "H", torch.float32), _dev(U, "U", torch.float32), _ptr(perm), float(alpha),
+                                _dev(W_star, "W_star", torch.float32), _dev(workspace, "workspace", torch.uint8),
+                                workspace.numel(), _stream())
+    if rc != ONECOMP_OK:
+        raise OnecompError(rc, "onecomp_qep_target")
+    return W_star

@@ -66,6 +66,43 @@ ONECOMP_API onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w
                      loss, workspace, static_cast<hipStream_t>(hip_stream));
 }
 
+ONECOMP_API onecomp_status onecomp_crossgram_accumulate(const void* X_hat, const void* X, onecomp_dtype x_dtype,
+                                                        int64_t n_tokens, int64_t d_in, int64_t ldxh, int64_t ldx,
+                                                        float* G, void* hip_stream) {
+    if (x_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
+    if (!G || d_in <= 0 || n_tokens < 0 || ldxh < d_in || ldx < d_in) return ONECOMP_ERR_INVALID_ARG;
+    if (d_in % 16 != 0 || d_in > (1 << 20)) return ONECOMP_ERR_INVALID_ARG;
+    if (n_tokens == 0) return ONECOMP_OK;
+    if (!X_hat || !X) return ONECOMP_ERR_INVALID_ARG;
+    if (!aligned(X_hat, 16) || !aligned(X, 16) || (ldxh * 2) % 16 != 0 || (ldx * 2) % 16 != 0 || !aligned(G, 16))
+        return ONECOMP_ERR_INVALID_ARG;
+    // the kernel addresses a step of 16 token rows with 32-bit byte offsets
+    if (ldxh * 64 >= (int64_t(1) << 31) || ldx * 64 >= (int64_t(1) << 31)) return ONECOMP_ERR_UNSUPPORTED;
+    return gram_cross_accumulate_bf16(X_hat, X, n_tokens, d_in, ldxh, ldx, G, static_cast<hipStream_t>(hip_stream));
+}
+
+ONECOMP_API size_t onecomp_qep_workspace_bytes(int64_t d_out, int64_t d_in) {
+    if (d_out <= 0 || d_in <= 0 || d_in % 16 != 0 || d_in > 65535 || d_out > (1 << 24)) return 0;
+    return qep_workspace_bytes(d_out, d_in);
+}
+
+ONECOMP_API onecomp_status onecomp_qep_target(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                              const float* G, const float* H, const float* U, const int32_t* perm,
+                                              float alpha, float* W_star, void* workspace, size_t workspace_bytes,
+                                              void* hip_stream) {
+    if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
+    if (!W || !G || !H || !U || !W_star) return ONECOMP_ERR_INVALID_ARG;
+    if (d_out <= 0 || d_in <= 0 || d_in % 16 != 0 || d_in > 65535 || d_out > (1 << 24)) return ONECOMP_ERR_INVALID_ARG;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return ONECOMP_ERR_INVALID_ARG;
+    if (static_cast<const void*>(W_star) == W) return ONECOMP_ERR_INVALID_ARG;
+    if (!aligned(W, 16) || !aligned(G, 16) || !aligned(H, 16) || !aligned(U, 16) || !aligned(W_star, 16))
+        return ONECOMP_ERR_INVALID_ARG;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < qep_workspace_bytes(d_out, d_in))
+        return ONECOMP_ERR_WORKSPACE;
+    return qep_target_run(W, w_dtype, d_out, d_in, G, H, U, perm, alpha, W_star, workspace,
+                          static_cast<hipStream_t>(hip_stream));
+}
+
 ONECOMP_API const char* onecomp_status_string(onecomp_status status) {
     switch (status) {
         case ONECOMP_OK: return "ok";

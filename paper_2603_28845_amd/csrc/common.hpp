@@ -48,6 +48,9 @@ onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_i
 onecomp_status gram_accumulate_f32(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx,
                                    float* H, hipStream_t stream);
 
+onecomp_status gram_cross_accumulate_bf16(const void* Xh, const void* X, int64_t n_tokens, int64_t d_in, int64_t ldxh,
+                                          int64_t ldx, float* G, hipStream_t stream);
+
 size_t factor_workspace_bytes(int64_t d_in);
 onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_order, int32_t* perm_out,
                           float* U, int32_t* info, void* workspace, hipStream_t stream);
@@ -57,5 +60,10 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
                          const float* U, const int32_t* perm, int bits, int group_size, int block,
                          uint8_t* Q, float* scales, float* zeros, float* W_hat, float* loss,
                          void* workspace, hipStream_t stream);
+
+size_t qep_workspace_bytes(int64_t d_out, int64_t d_in);
+onecomp_status qep_target_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* G,
+                              const float* H, const float* U, const int32_t* perm, float alpha, float* W_star,
+                              void* workspace, hipStream_t stream);
 
 }  // namespace onecomp

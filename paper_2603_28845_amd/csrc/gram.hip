@@ -57,7 +57,8 @@ __device__ inline void tile_from_rank(int v, int n_t, int& ti, int& tk) {
 // per-element masks whose loads are issued 32 at a time before the first use (left to itself the compiler
 // waits for every load separately when the accumulators live in AGPRs).
 // -------------------------------------------------------------------------------------------
-template <int MT, int NT>
+// MIRROR = false: plain H[i][k] += 2 acc for every entry of the tile (cross-Gram of two different matrices).
+template <int MT, int NT, bool MIRROR = true>
 __device__ __forceinline__ void gram_store(float16v (&acc)[MT][NT], float* __restrict__ H, const int d_in,
                                            const int ibase, const int kbase, const bool diag, const int lane) {
     const int lr = (lane >> 5) * 4, lc = lane & 31;
@@ -82,11 +83,13 @@ __device__ __forceinline__ void gram_store(float16v (&acc)[MT][NT], float* __res
                         hv[n][r] = hv[n][r] + 2.0f * acc[m][n0 + n][r];
                         hp[int64_t((r / 4) * 8 + (r % 4)) * d_in + n * 32] = hv[n][r];
                     }
-                    float* mp = H + int64_t(kbase + (n0 + n) * 32 + lc) * d_in + ibase + m * 32 + lr;
+                    if constexpr (MIRROR) {
+                        float* mp = H + int64_t(kbase + (n0 + n) * 32 + lc) * d_in + ibase + m * 32 + lr;
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const float4v o = {hv[n][q * 4], hv[n][q * 4 + 1], hv[n][q * 4 + 2], hv[n][q * 4 + 3]};
-                        *reinterpret_cast<float4v*>(mp + q * 8) = o;
+                        for (int q = 0; q < 4; ++q) {
+                            const float4v o = {hv[n][q * 4], hv[n][q * 4 + 1], hv[n][q * 4 + 2], hv[n][q * 4 + 3]};
+                            *reinterpret_cast<float4v*>(mp + q * 8) = o;
+                        }
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -111,6 +114,7 @@ __device__ __forceinline__ void gram_store(float16v (&acc)[MT][NT], float* __res
                     nv[e] = *p + 2.0f * acc[m][n][q * 4 + e];
                     if (!diag || i <= k) *p = nv[e];
                 }
+                if constexpr (!MIRROR) continue;
                 if (!diag) {
                     const float4v o = {nv[0], nv[1], nv[2], nv[3]};
                     *reinterpret_cast<float4v*>(H + int64_t(k) * d_in + ib) = o;
@@ -298,11 +302,12 @@ __device__ inline void tile128_from_rank(int v, int n_rt, int n_ct, int& ti, int
     }
 }
 
-template <typename C>
-__global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring_kernel(const uint16_t* __restrict__ X,
-                                                                         int64_t n_tokens, int d_in, int64_t ldx,
-                                                                         float* __restrict__ H, int n_rt, int n_ct,
-                                                                         int n_tiles, int chunk) {
+// CROSS = false: H += 2 X^T X, tiles on or above the diagonal, mirrored.  CROSS = true: H += 2 X^T Xb for two
+// different matrices (A panels from X, B panels from Xb), every tile, no mirror.
+template <typename C, bool CROSS>
+__global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring_kernel(
+    const uint16_t* __restrict__ X, const uint16_t* __restrict__ Xb, int64_t n_tokens, int d_in, int64_t ldx,
+    int64_t ldxb, float* __restrict__ H, int n_rt, int n_ct, int n_tiles, int chunk) {
     using R = Ring<C>;
     constexpr int KT = R::KT, NBUF = C::NBUF, MT = R::MT, NT = R::NT, LPW = R::LPW;
     constexpr int A_ROWB = R::A_ROWB, B_ROWB = R::B_ROWB, A_PANELB = R::A_PANELB, STAGEB = R::STAGEB;
@@ -310,10 +315,18 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
     const int v = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
     if (v >= n_tiles) return;
     int ti, tk;
-    if constexpr (C::TM == C::TN) tile_from_rank(v, n_ct, ti, tk);
-    else tile128_from_rank(v, n_rt, n_ct, ti, tk);
+    if constexpr (CROSS) {   // all tiles: bands of 4 tile rows, column by column inside a band
+        const int band = min(v / (BAND * n_ct), (n_rt - 1) / BAND);
+        const int w = v - band * BAND * n_ct, rows = min(BAND, n_rt - band * BAND);
+        tk = w / rows;
+        ti = band * BAND + w % rows;
+    } else if constexpr (C::TM == C::TN) {
+        tile_from_rank(v, n_ct, ti, tk);
+    } else {
+        tile128_from_rank(v, n_rt, n_ct, ti, tk);
+    }
     const int i0 = ti * C::TM, k0 = tk * C::TN;
-    const bool diag = k0 < i0 + C::TM;   // some entry of the tile lies on or below the diagonal
+    const bool diag = !CROSS && k0 < i0 + C::TM;   // some entry of the tile lies on or below the diagonal
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wr = wave / C::WN, wc = wave % C::WN;
@@ -331,30 +344,40 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
         const int row = jj * (64 / lpr) + lane / lpr;
         const int c = (lane % lpr) ^ ((row & 3) << 2);
         const int col = (is_a ? i0 : k0) + c * 8;
-        voff[q] = (col < d_in) ? uint32_t((int64_t(row) * ldx + col) * 2) : LDS_DMA_OOB;
+        voff[q] = (col < d_in) ? uint32_t((int64_t(row) * (is_a ? ldx : ldxb) + col) * 2) : LDS_DMA_OOB;
         ldst[q] = (is_a ? 0 : A_PANELB) + jj * 1024;
     }
     const int64_t n_st = (n_tokens + KT - 1) / KT;
     const int64_t n_st2 = (n_st + 1) & ~int64_t(1);   // the loop takes two steps at a time; an extra step is all zeros
     struct Desc {
-        __amdgpu_buffer_rsrc_t r;
+        __amdgpu_buffer_rsrc_t a, b;   // A panels, B panels (the same matrix unless CROSS)
     };
-    // descriptor of step st: base = its first token row, range = what is left of X (none past the last step)
-    auto make_desc = [&](int64_t st) __attribute__((always_inline)) {
-        Desc d;
+    // descriptor of step st: base = its first token row, range = what is left of the matrix (none past the last
+    // step).  The 64-bit products may be computed on the vector ALU: the wave-uniform results are brought back to
+    // scalar registers, where a descriptor has to live.
+    auto make_rsrc = [&](const uint16_t* base, int64_t ld, int64_t st) __attribute__((always_inline)) {
         const int64_t t0 = st * KT;
-        const int64_t left = (n_tokens - t0) * ldx * 2;
+        const int64_t left = (n_tokens - t0) * ld * 2;
         const bool live = left > 0;
-        // (the 64-bit products may be computed on the vector ALU: bring the wave-uniform results back to scalar
-        // registers, where a descriptor has to live)
         const int range = __builtin_amdgcn_readfirstlane(!live ? 0 : (left > 0x7FFFFFFF ? 0x7FFFFFFF : int(left)));
-        const int64_t boff = (live ? t0 : 0) * ldx * 2;
+        const int64_t boff = (live ? t0 : 0) * ld * 2;
         const uint32_t blo = __builtin_amdgcn_readfirstlane(uint32_t(boff));
         const uint32_t bhi = __builtin_amdgcn_readfirstlane(uint32_t(uint64_t(boff) >> 32));
-        d.r = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<char*>(reinterpret_cast<const char*>(X) + int64_t((uint64_t(bhi) << 32) | blo)), 0, range,
+        return __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<char*>(reinterpret_cast<const char*>(base) + int64_t((uint64_t(bhi) << 32) | blo)), 0, range,
             0x00020000);
+    };
+    auto make_desc = [&](int64_t st) __attribute__((always_inline)) {
+        Desc d;
+        d.a = make_rsrc(X, ldx, st);
+        if constexpr (CROSS) d.b = make_rsrc(Xb, ldxb, st);
+        else d.b = d.a;
         return d;
+    };
+    // load q of this wave (compile-time q): A panel loads come first
+    auto gload = [&](const Desc& d, uint32_t dst, int q) __attribute__((always_inline)) {
+        if (q * R::WAVES < R::NL_A) lds_load16(dst + ldst[q], voff[q], d.a);   // wave + WAVES q < NL_A for every wave
+        else lds_load16(dst + ldst[q], voff[q], d.b);
     };
 
     const int i16 = lane & 15, g16 = (lane >> 4) & 1, kb8 = lane >> 5;
@@ -384,7 +407,7 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
     for (int st = 0; st < NBUF; ++st) {
         const Desc d = make_desc(st);
 #pragma unroll
-        for (int q = 0; q < LPW; ++q) lds_load16(lds0 + st * STAGEB + ldst[q], voff[q], d.r);
+        for (int q = 0; q < LPW; ++q) gload(d, lds0 + st * STAGEB, q);
     }
     float16v acc[MT][NT];
 #pragma unroll
@@ -422,7 +445,7 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
             const int sb = s1 * STAGEB;
             mma(Fc, [&](int i) __attribute__((always_inline)) {
                 if (i < MT + NT) rd(FH, i, sb);
-                if (i < LPW) lds_load16(dst + ldst[i], voff[i], d.r);
+                if (i < LPW) gload(d, dst, i);
             });
             __builtin_amdgcn_s_waitcnt(wait_vmcnt(LPW * (NBUF - 2)));   // step st+2 has landed
             __syncthreads();
@@ -433,7 +456,7 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
             const int sb = s2 * STAGEB;
             mma(FH, [&](int i) __attribute__((always_inline)) {
                 if (i < MT + NT) rd(Fc, i, sb);
-                if (i < LPW) lds_load16(dst + ldst[i], voff[i], d.r);
+                if (i < LPW) gload(d, dst, i);
             });
             __builtin_amdgcn_s_waitcnt(wait_vmcnt(LPW * (NBUF - 2)));   // step st+3 has landed
             __syncthreads();
@@ -441,7 +464,7 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
         s0 = s2;
     }
     __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // no LDS write may be in flight when the workgroup ends
-    gram_store<MT, NT>(acc, H, d_in, i0 + wr * (32 * MT), k0 + wc * (32 * NT), diag, lane);
+    gram_store<MT, NT, !CROSS>(acc, H, d_in, i0 + wr * (32 * MT), k0 + wc * (32 * NT), diag, lane);
 }
 
 
@@ -573,26 +596,40 @@ onecomp_status launch_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_
 
 
 
-template <typename C>
-onecomp_status launch_bf16_ring(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
-                                hipStream_t stream) {
+template <typename C, bool CROSS>
+onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens, int64_t d_in, int64_t ldx,
+                                int64_t ldxb, float* H, hipStream_t stream) {
     using R = Ring<C>;
     const int n_rt = int(ceil_div(d_in, C::TM)), n_ct = int(ceil_div(d_in, C::TN));
     int n_tiles = 0;
-    if (C::TM == C::TN) n_tiles = n_ct * (n_ct + 1) / 2;
+    if (CROSS) n_tiles = n_rt * n_ct;
+    else if (C::TM == C::TN) n_tiles = n_ct * (n_ct + 1) / 2;
     else for (int i = 0; i < n_rt; ++i) n_tiles += n_ct - i / 2;
     const int chunk = int(ceil_div(n_tiles, 8));
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_ring_kernel<C>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_ring_kernel<C, CROSS>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, int(R::LDS_BYTES)) != hipSuccess)
             return ONECOMP_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL(gram_bf16_ring_kernel<C>, dim3(chunk * 8), dim3(R::THREADS), R::LDS_BYTES, stream,
-                       static_cast<const uint16_t*>(X), n_tokens, int(d_in), ldx, H, n_rt, n_ct, n_tiles, chunk);
+    hipLaunchKernelGGL((gram_bf16_ring_kernel<C, CROSS>), dim3(chunk * 8), dim3(R::THREADS), R::LDS_BYTES, stream,
+                       static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(Xb), n_tokens, int(d_in), ldx,
+                       ldxb, H, n_rt, n_ct, n_tiles, chunk);
     ONECOMP_CHECK_LAUNCH();
     return ONECOMP_OK;
+}
+
+int device_cus() {
+    static int n_cus = 0;
+    if (n_cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+            return 0;
+        n_cus = v;
+    }
+    return n_cus;
 }
 
 }  // namespace
@@ -604,21 +641,26 @@ onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_i
     // decides: 256 x 256 tiles run one per CU and cost two units each, 128 x 256 tiles run two per CU (a CU with
     // two of them takes twice as long) and cost one unit plus 15 % for their higher L2 traffic per flop.
     if (ldx * 64 >= (int64_t(1) << 31) || d_in < 1024) return launch_bf16<2>(X, n_tokens, d_in, ldx, H, stream);
-    static int n_cus = 0;
-    if (n_cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-            return ONECOMP_ERR_HIP;
-        n_cus = v;
-    }
+    const int n_cus = device_cus();
+    if (n_cus <= 0) return ONECOMP_ERR_HIP;
     const int64_t n256 = ceil_div(d_in, 256), n128 = ceil_div(d_in, 128);
     const int64_t big = n256 * (n256 + 1) / 2;
     int64_t mid = 0;
     for (int64_t i = 0; i < n128; ++i) mid += n256 - i / 2;
     const double cost_big = 2.0 * double(ceil_div(big, n_cus)), cost_mid = 1.15 * double(ceil_div(mid, n_cus));
-    if (cost_big <= cost_mid) return launch_bf16_ring<RingBig>(X, n_tokens, d_in, ldx, H, stream);
-    return launch_bf16_ring<RingMid>(X, n_tokens, d_in, ldx, H, stream);
+    if (cost_big <= cost_mid) return launch_bf16_ring<RingBig, false>(X, X, n_tokens, d_in, ldx, ldx, H, stream);
+    return launch_bf16_ring<RingMid, false>(X, X, n_tokens, d_in, ldx, ldx, H, stream);
+}
+
+// G += 2 Xh^T X for two bf16 matrices of the same shape (every tile, no symmetry to use)
+onecomp_status gram_cross_accumulate_bf16(const void* Xh, const void* X, int64_t n_tokens, int64_t d_in, int64_t ldxh,
+                                          int64_t ldx, float* G, hipStream_t stream) {
+    const int n_cus = device_cus();
+    if (n_cus <= 0) return ONECOMP_ERR_HIP;
+    const int64_t n256 = ceil_div(d_in, 256), n128 = ceil_div(d_in, 128);
+    const double cost_big = 2.0 * double(ceil_div(n256 * n256, n_cus)), cost_mid = 1.15 * double(ceil_div(n128 * n256, n_cus));
+    if (cost_big <= cost_mid) return launch_bf16_ring<RingBig, true>(Xh, X, n_tokens, d_in, ldxh, ldx, G, stream);
+    return launch_bf16_ring<RingMid, true>(Xh, X, n_tokens, d_in, ldxh, ldx, G, stream);
 }
 
 onecomp_status gram_accumulate_f32(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,

@@ -107,3 +107,16 @@ def make_activations(cfg: LayerConfig, device="cpu", n_tokens=None) -> torch.Ten
             blk = blk * tok
         X[t0:t1] = (blk * ch[None, :]).to(cfg.dtype)
     return X
+
+
+def make_perturbed_activations(cfg: LayerConfig, X: torch.Tensor, rel_noise: float = 0.05) -> torch.Tensor:
+    """X_hat = X * (1 + rel_noise * N(0, 1)), rounded to cfg.dtype: a stand-in for the activations that reach a layer
+    once the layers before it have been quantized (same shape and outlier structure as X, a few percent off)."""
+    g = _gen(cfg.seed, 5, X.device)
+    Xh = torch.empty_like(X)
+    rows = max(1, (1 << 26) // cfg.d_in)
+    for t0 in range(0, X.shape[0], rows):
+        t1 = min(X.shape[0], t0 + rows)
+        z = torch.randn((t1 - t0, cfg.d_in), generator=g, device=X.device, dtype=torch.float32)
+        Xh[t0:t1] = (X[t0:t1].to(torch.float32) * (1.0 + rel_noise * z)).to(cfg.dtype)
+    return Xh

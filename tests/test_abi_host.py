@@ -103,3 +103,50 @@ def test_quantize_argument_checks(lib):
     assert call(G=0) == INVALID
     assert call(ws=NULL) == WORKSPACE
     assert call(wsb=ctypes.c_size_t(16)) == WORKSPACE
+    assert call(d_in=65536 + 128) == INVALID    # beyond the 16-bit column limit of the sweep
+
+
+def test_crossgram_argument_checks(lib):
+    f = lib.onecomp_crossgram_accumulate
+    f.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                  ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+    f.restype = ctypes.c_int
+    assert f(P, P, 0, 10, 128, 128, 128, P, NULL) == UNSUPPORTED       # fp32 activations
+    assert f(P, P, 1, 10, 128, 128, 128, NULL, NULL) == INVALID        # no G
+    assert f(P, P, 1, 10, 120, 120, 120, P, NULL) == INVALID           # d_in % 16
+    assert f(P, P, 1, 10, 128, 64, 128, P, NULL) == INVALID            # row stride below d_in
+    assert f(NULL, P, 1, 10, 128, 128, 128, P, NULL) == INVALID
+    assert f(P, P, 1, -1, 128, 128, 128, P, NULL) == INVALID
+    assert f(P, P, 1, 10, 128, 128, 1 << 26, P, NULL) == UNSUPPORTED   # 16 rows not addressable with 32 bits
+    assert f(NULL, NULL, 1, 0, 128, 128, 128, P, NULL) == 0            # zero tokens: nothing to do
+
+
+def test_qep_target_argument_checks(lib):
+    f = lib.onecomp_qep_target
+    f.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                  ctypes.c_void_p]
+    f.restype = ctypes.c_int
+    lib.onecomp_qep_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64]
+    lib.onecomp_qep_workspace_bytes.restype = ctypes.c_size_t
+    big = ctypes.c_size_t(1 << 40)
+    P2 = ctypes.c_void_p(0x20000)
+
+    def call(W=P, dt=1, d_out=64, d_in=256, G=P, H=P, U=P, perm=NULL, alpha=0.5, out=P2, ws=P, wsb=big):
+        return f(W, dt, d_out, d_in, G, H, U, perm, alpha, out, ws, wsb, NULL)
+
+    assert call(dt=2) == UNSUPPORTED
+    assert call(W=NULL) == INVALID
+    assert call(G=NULL) == INVALID
+    assert call(U=NULL) == INVALID
+    assert call(out=NULL) == INVALID
+    assert call(out=P) == INVALID                # W* must not alias W
+    assert call(alpha=1.5) == INVALID
+    assert call(alpha=-0.1) == INVALID
+    assert call(alpha=float("nan")) == INVALID
+    assert call(d_in=250) == INVALID
+    assert call(ws=NULL) == WORKSPACE
+    assert call(wsb=ctypes.c_size_t(1000)) == WORKSPACE
+    need = lib.onecomp_qep_workspace_bytes(64, 256)
+    assert need >= 4 * 256 * 256 + 3 * 4 * 64 * 256
+    assert lib.onecomp_qep_workspace_bytes(64, 250) == 0
