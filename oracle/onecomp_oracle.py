@@ -15,9 +15,9 @@ What it computes (paper sections given in brackets):
   * optional activation ordering: columns sorted by decreasing diag(H)
     [Sec. 4.2, "actorder"]
   * the column-by-column sweep: quantize one column to the per-group
-    asymmetric min-max grid, propagate its residual to the columns not yet
-    quantized  [Sec. 4.2; grid: Eq. (1) scalar quantizer, Eq. (2) min-max
-    scale / zero-point, Eq. (4) per-group layout]
+    asymmetric min-max grid (or the symmetric grid of Eq. (3)), propagate its
+    residual to the columns not yet quantized  [Sec. 4.2; grid: Eq. (1) scalar
+    quantizer, Eq. (2) min-max scale / zero-point, Eq. (4) per-group layout]
   * the layer objective tr((W-W^) H (W-W^)^T)  [Eq. (layerwise), Eq. (activation-aware)]
   * the corrected quantization target of error propagation (QEP),
     W* = (I + alpha (H^ + lambda I)^-1 C) W  with  C = X^^T (X - X^)  [Sec. 4.2.1, Eq. (qep)]
@@ -156,16 +156,39 @@ def minmax_params(wmin, wmax, bits):
     return s, z, tz
 
 
-def quantize_scalar(w, s, z, bits):
-    """Eq. (1): q = clamp(rne(w / s) + z, 0, 2^b - 1), w^ = s (q - z).
+def symmetric_params(wmin, wmax, bits):
+    """Symmetric scale of Eq. (3): s = max(|wmin|, |wmax|) / (2^(b-1) - 1), zero-point fixed, signed codes
+    q in {-(2^(b-1)-1), ..., 2^(b-1)-1}, w^ = s q.  Stored in the unsigned format of Eq. (4) as the code
+    u = q + (2^(b-1) - 1) with the constant zero-point z = 2^(b-1) - 1, so that w^ = s (u - z) as for the
+    asymmetric grid; the highest unsigned code 2^b - 1 is never used.  A degenerate group (all zeros, on which
+    the paper is silent) takes s = 1.  Returns (s, z, tz) with tz = z (the zero-point is not rounded)."""
+    qs = float(2 ** (bits - 1) - 1)
+    m = np.maximum(np.abs(np.asarray(wmin, dtype=np.float64)), np.abs(np.asarray(wmax, dtype=np.float64)))
+    s = m / qs
+    s = np.where(s == 0.0, 1.0, s)
+    z = np.full_like(s, qs)
+    return s, z, z.copy()
+
+
+def code_range_top(bits, grid):
+    """Highest unsigned code of the grid: 2^b - 1 (asymmetric, Eq. (1)); 2 (2^(b-1) - 1) (symmetric, Eq. (3))."""
+    if grid == "asym":
+        return float(2 ** bits - 1)
+    if grid == "sym":
+        return float(2 * (2 ** (bits - 1) - 1))
+    raise ValueError("grid must be 'asym' or 'sym'")
+
+
+def quantize_scalar(w, s, z, bits, qtop=None):
+    """Eq. (1): q = clamp(rne(w / s) + z, 0, qtop), w^ = s (q - z); qtop = 2^b - 1 unless given.
     Returns (q, w^, t) with t = w / s the value before rounding."""
-    qmax = float(2 ** bits - 1)
+    qmax = float(2 ** bits - 1) if qtop is None else float(qtop)
     t = np.asarray(w, dtype=np.float64) / s
     q = np.clip(np.rint(t) + z, 0.0, qmax)
     return q, s * (q - z), t
 
 
-def rtn_quantize(W, bits, group_size):
+def rtn_quantize(W, bits, group_size, grid="asym"):
     """Round-to-nearest of W on the per-group min-max grid (Sec. 2.4, Eq.
     (direct weight quant) with the grid of Eq. (2), layout of Eq. (4)).
     Written independently of the sweep (whole-array, no column loop) so that it
@@ -176,8 +199,8 @@ def rtn_quantize(W, bits, group_size):
     Wg = W.reshape(d_out, n_g, group_size)
     lo = Wg.min(axis=2, keepdims=True)
     hi = Wg.max(axis=2, keepdims=True)
-    s, z, _ = minmax_params(lo, hi, bits)
-    qmax = float(2 ** bits - 1)
+    s, z, _ = (minmax_params if grid == "asym" else symmetric_params)(lo, hi, bits)
+    qmax = code_range_top(bits, grid)
     Q = np.clip(np.rint(Wg / s) + z, 0.0, qmax)
     What = s * (Q - z)
     return (Q.reshape(d_out, d_in).astype(np.int64), s[:, :, 0], z[:, :, 0],
@@ -188,7 +211,7 @@ def rtn_quantize(W, bits, group_size):
 # Column sweep (Sec. 4.2: one column at a time, residual propagated)
 # --------------------------------------------------------------------------
 def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
-                   forced_codes=None, forced_zeros=None):
+                   forced_codes=None, forced_zeros=None, grid="asym"):
     """Greedy sequential quantization of every row of W with feedback through U.
 
     W: [d_out, d_in] original column order.  U: upper factor of the (permuted)
@@ -197,6 +220,7 @@ def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
     forced_codes: optional int array [rows, d_in] in PERMUTED column order,
       entries >= 0 override the rounded code at that step (replay of a tie).
     forced_zeros: optional int array [rows, n_groups], entries >= 0 override z.
+    grid: "asym" = min-max grid of Eq. (2) (default), "sym" = symmetric grid of Eq. (3).
 
     Per row, for j = 0 .. d_in-1 in permuted order:
       at a group start: (s, z) from min/max of the CURRENT values of the group
@@ -218,7 +242,8 @@ def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
     if d_in % G != 0:
         raise ValueError("d_in must be a multiple of group_size")
     n_g = d_in // G
-    qmax = float(2 ** bits - 1)
+    qtop = code_range_top(bits, grid)
+    params = minmax_params if grid == "asym" else symmetric_params
     if perm is None:
         perm = np.arange(d_in, dtype=np.int64)
     perm = np.asarray(perm, dtype=np.int64)
@@ -236,7 +261,7 @@ def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
         if j % G == 0:
             g = j // G
             blk = w[:, j:j + G]
-            s, z, tz = minmax_params(blk.min(axis=1), blk.max(axis=1), bits)
+            s, z, tz = params(blk.min(axis=1), blk.max(axis=1), bits)
             if forced_zeros is not None:
                 fz = np.asarray(forced_zeros)[:, g]
                 z = np.where(fz >= 0, fz.astype(np.float64), z)
@@ -244,7 +269,7 @@ def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
             zeros[:, g] = z
             Tz[:, g] = tz
         wj = w[:, j].copy()
-        q, wh, t = quantize_scalar(wj, s, z, bits)
+        q, wh, t = quantize_scalar(wj, s, z, bits, qtop)
         if forced_codes is not None:
             fc = np.asarray(forced_codes)[:, j]
             q = np.where(fc >= 0, fc.astype(np.float64), q)
