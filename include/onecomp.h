@@ -52,6 +52,12 @@ typedef enum {
     ONECOMP_BF16 = 1
 } onecomp_dtype;
 
+/* Grid of the column sweep: per-group asymmetric min-max grid of Eq. (2), or the symmetric grid of Eq. (3). */
+typedef enum {
+    ONECOMP_GRID_MINMAX = 0,
+    ONECOMP_GRID_SYMMETRIC = 1
+} onecomp_grid;
+
 /*
  * H += 2 * X^T X  over the n_tokens rows of X (Gram matrix of Sec. 2.5 / Sec. 4.2; the
  * factor 2 makes it the Hessian of ||X (W^ - W)||^2, cf. Sec. 2.4).
@@ -138,7 +144,24 @@ onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w_dtype, int6
                                       float* W_hat, float* loss,
                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Scratch sizes for the two calls above (0 if the arguments are invalid). */
+/*
+ * onecomp_quantize_layer with the grid chosen by the caller (onecomp_quantize_layer is this call with
+ * ONECOMP_GRID_MINMAX).  ONECOMP_GRID_SYMMETRIC is the symmetric grid of Sec. 2.2.2, Eq. (3): at the first column
+ * of a group  s = max(|min|, |max|) / (2^(bits-1) - 1)  over the current values of the group (s = 1 if all are
+ * zero), signed codes q in {-(2^(bits-1) - 1), ..., 2^(bits-1) - 1}, w^ = s q.  Outputs keep the format of the
+ * min-max grid: Q_codes holds the unsigned code q + (2^(bits-1) - 1), zeros holds the constant 2^(bits-1) - 1, so
+ * W_hat = scales * (Q_codes - zeros) bit for bit; the highest unsigned code 2^bits - 1 is never produced.
+ * Everything else (arguments, arithmetic, workspace, errors) as for onecomp_quantize_layer; an unknown grid is
+ * ONECOMP_ERR_UNSUPPORTED.
+ */
+onecomp_status onecomp_quantize_layer_grid(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                           const float* U, const int32_t* perm,
+                                           int bits, int group_size, int block_size, onecomp_grid grid,
+                                           uint8_t* Q_codes, float* scales, float* zeros,
+                                           float* W_hat, float* loss,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Scratch sizes for the factor and sweep calls above (0 if the arguments are invalid). */
 size_t onecomp_factor_workspace_bytes(int64_t d_in);
 size_t onecomp_quantize_workspace_bytes(int64_t d_out, int64_t d_in, int block_size);
 

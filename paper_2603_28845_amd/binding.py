@@ -19,11 +19,14 @@ LIB_PATH = os.path.join(_PKG_DIR, "libonecomp.so")
 ONECOMP_OK = 0
 ONECOMP_F32 = 0
 ONECOMP_BF16 = 1
+ONECOMP_GRID_MINMAX = 0
+ONECOMP_GRID_SYMMETRIC = 1
 
 EXPORTED_SYMBOLS = (
     "onecomp_hessian_accumulate",
     "onecomp_hessian_factor",
     "onecomp_quantize_layer",
+    "onecomp_quantize_layer_grid",
     "onecomp_factor_workspace_bytes",
     "onecomp_quantize_workspace_bytes",
     "onecomp_crossgram_accumulate",
@@ -59,6 +62,9 @@ def load_library() -> ctypes.CDLL:
     lib.onecomp_hessian_factor.restype = i32
     lib.onecomp_quantize_layer.argtypes = [vp, i32, i64, i64, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.onecomp_quantize_layer.restype = i32
+    lib.onecomp_quantize_layer_grid.argtypes = [vp, i32, i64, i64, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz,
+                                                vp]
+    lib.onecomp_quantize_layer_grid.restype = i32
     lib.onecomp_factor_workspace_bytes.argtypes = [i64]
     lib.onecomp_factor_workspace_bytes.restype = sz
     lib.onecomp_quantize_workspace_bytes.argtypes = [i64, i64, i32]
@@ -160,8 +166,10 @@ def onecomp_hessian_factor(H: torch.Tensor, damp: float, act_order: bool = False
 
 def onecomp_quantize_layer(W: torch.Tensor, U: torch.Tensor, bits: int, group_size: int,
                            perm: Optional[torch.Tensor] = None, block_size: int = 128, want_w_hat: bool = True,
-                           workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None) -> dict:
-    """Returns dict(Q_codes uint8, scales, zeros, W_hat (or None), loss) of device tensors."""
+                           workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None,
+                           grid: str = "minmax") -> dict:
+    """Returns dict(Q_codes uint8, scales, zeros, W_hat (or None), loss) of device tensors.
+    grid = "minmax" calls onecomp_quantize_layer, "symmetric" onecomp_quantize_layer_grid with that grid."""
     lib = load_library()
     d_out, d_in = W.shape
     dev = W.device
@@ -179,13 +187,17 @@ def onecomp_quantize_layer(W: torch.Tensor, U: torch.Tensor, bits: int, group_si
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     if perm is not None:
         _dev(perm, "perm", torch.int32)
-    rc = lib.onecomp_quantize_layer(_dev(W, "W"), _dtype_code(W), d_out, d_in, _dev(U, "U", torch.float32),
-                                    _ptr(perm), int(bits), int(group_size), int(block_size),
-                                    _dev(out["Q_codes"], "Q_codes", torch.uint8),
-                                    _dev(out["scales"], "scales", torch.float32),
-                                    _dev(out["zeros"], "zeros", torch.float32), _ptr(out["W_hat"]),
-                                    _dev(out["loss"], "loss", torch.float32),
-                                    _dev(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    head = (_dev(W, "W"), _dtype_code(W), d_out, d_in, _dev(U, "U", torch.float32), _ptr(perm), int(bits),
+            int(group_size), int(block_size))
+    tail = (_dev(out["Q_codes"], "Q_codes", torch.uint8), _dev(out["scales"], "scales", torch.float32),
+            _dev(out["zeros"], "zeros", torch.float32), _ptr(out["W_hat"]), _dev(out["loss"], "loss", torch.float32),
+            _dev(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    if grid == "minmax":
+        rc = lib.onecomp_quantize_layer(*head, *tail)
+    elif grid == "symmetric":
+        rc = lib.onecomp_quantize_layer_grid(*head, ONECOMP_GRID_SYMMETRIC, *tail)
+    else:
+        raise ValueError("grid must be 'minmax' or 'symmetric'")
     if rc != ONECOMP_OK:
         raise OnecompError(rc, "onecomp_quantize_layer")
     return out

@@ -46,11 +46,14 @@ ONECOMP_API size_t onecomp_quantize_workspace_bytes(int64_t d_out, int64_t d_in,
     return sweep_workspace_bytes(d_out, d_in, block_size);
 }
 
-ONECOMP_API onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
-                                      const float* U, const int32_t* perm, int bits, int group_size, int block_size,
-                                      uint8_t* Q_codes, float* scales, float* zeros, float* W_hat, float* loss,
-                                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+ONECOMP_API onecomp_status onecomp_quantize_layer_grid(const void* W, onecomp_dtype w_dtype, int64_t d_out,
+                                                       int64_t d_in, const float* U, const int32_t* perm, int bits,
+                                                       int group_size, int block_size, onecomp_grid grid,
+                                                       uint8_t* Q_codes, float* scales, float* zeros, float* W_hat,
+                                                       float* loss, void* workspace, size_t workspace_bytes,
+                                                       void* hip_stream) {
     if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
+    if (grid != ONECOMP_GRID_MINMAX && grid != ONECOMP_GRID_SYMMETRIC) return ONECOMP_ERR_UNSUPPORTED;
     if (!W || !U || !Q_codes || !scales || !zeros || !loss) return ONECOMP_ERR_INVALID_ARG;
     if (d_out <= 0 || d_in <= 0 || d_out > (1 << 24) || d_in > 65535) return ONECOMP_ERR_INVALID_ARG;
     if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return ONECOMP_ERR_UNSUPPORTED;
@@ -62,8 +65,17 @@ ONECOMP_API onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w
         return ONECOMP_ERR_INVALID_ARG;
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < sweep_workspace_bytes(d_out, d_in, block_size))
         return ONECOMP_ERR_WORKSPACE;
-    return sweep_run(W, w_dtype, d_out, d_in, U, perm, bits, group_size, block_size, Q_codes, scales, zeros, W_hat,
-                     loss, workspace, static_cast<hipStream_t>(hip_stream));
+    return sweep_run(W, w_dtype, d_out, d_in, U, perm, bits, group_size, block_size, int(grid), Q_codes, scales, zeros,
+                     W_hat, loss, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+ONECOMP_API onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                      const float* U, const int32_t* perm, int bits, int group_size, int block_size,
+                                      uint8_t* Q_codes, float* scales, float* zeros, float* W_hat, float* loss,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return onecomp_quantize_layer_grid(W, w_dtype, d_out, d_in, U, perm, bits, group_size, block_size,
+                                       ONECOMP_GRID_MINMAX, Q_codes, scales, zeros, W_hat, loss, workspace,
+                                       workspace_bytes, hip_stream);
 }
 
 ONECOMP_API onecomp_status onecomp_crossgram_accumulate(const void* X_hat, const void* X, onecomp_dtype x_dtype,

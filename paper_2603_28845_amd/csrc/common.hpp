@@ -57,7 +57,7 @@ onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_orde
 
 size_t sweep_workspace_bytes(int64_t d_out, int64_t d_in, int block);
 onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
-                         const float* U, const int32_t* perm, int bits, int group_size, int block,
+                         const float* U, const int32_t* perm, int bits, int group_size, int block, int grid,
                          uint8_t* Q, float* scales, float* zeros, float* W_hat, float* loss,
                          void* workspace, hipStream_t stream);
 

@@ -142,7 +142,8 @@ struct BlockArgs {
     int e_col, ldD;
     float* rowloss;         // [d_out]
     int d_out, d_in, j0, G, n_g;
-    float qmax;
+    float qmax;             // highest code of the grid
+    float qs;               // 0: min-max grid of Eq. (2); > 0: symmetric grid of Eq. (3) with zero-point qs
 };
 
 constexpr int IB = 32;          // columns swept in registers at a time
@@ -245,10 +246,16 @@ __global__ __launch_bounds__(BLOCK_THREADS) void block_kernel(BlockArgs a) {
                             }
                         }
                         if (fresh) {
-                            s = (mx - mn) / qmax;
-                            if (s == 0.f) s = 1.f;
+                            if (a.qs > 0.f) {
+                                s = fmaxf(fabsf(mn), fabsf(mx)) / a.qs;
+                                if (s == 0.f) s = 1.f;
+                                z = a.qs;
+                            } else {
+                                s = (mx - mn) / qmax;
+                                if (s == 0.f) s = 1.f;
+                                z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
+                            }
                             rs = 1.0f / s;
-                            z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
                             if (row_ok) {
                                 a.scales[int64_t(row) * a.n_g + col / a.G] = s;
                                 a.zeros[int64_t(row) * a.n_g + col / a.G] = z;
@@ -384,7 +391,8 @@ struct PanelArgs {
     const Scalars* sc;
     float* rowloss;
     int d_out, d_in, s0, nb, lgG, n_g, ldD;
-    float qmax;
+    float qmax;             // highest code of the grid
+    float qs;               // 0: min-max grid of Eq. (2); > 0: symmetric grid of Eq. (3) with zero-point qs
 };
 
 constexpr int PANEL_LDS = (SB * SB + 2 * ROWS * SP + SB + 2 * ROWS * 8) * 4;
@@ -554,10 +562,16 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                                 }
                             }
                             if (fresh) {
-                                s = (mx - mn) / qmax;
-                                if (s == 0.f) s = 1.f;
+                                if (a.qs > 0.f) {
+                                    s = fmaxf(fabsf(mn), fabsf(mx)) / a.qs;
+                                    if (s == 0.f) s = 1.f;
+                                    z = a.qs;
+                                } else {
+                                    s = (mx - mn) / qmax;
+                                    if (s == 0.f) s = 1.f;
+                                    z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
+                                }
                                 rs = 1.0f / s;
-                                z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
                                 if (sl == 0) {
                                     const int gi = (jb + j) >> a.lgG;
                                     sS[qrow * 8 + gi] = s;
@@ -1117,7 +1131,7 @@ size_t sweep_workspace_bytes(int64_t d_out, int64_t d_in, int block) {
 }
 
 onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* U,
-                         const int32_t* perm, int bits, int group_size, int block, uint8_t* Q, float* scales,
+                         const int32_t* perm, int bits, int group_size, int block, int grid, uint8_t* Q, float* scales,
                          float* zeros, float* W_hat, float* loss, void* workspace, hipStream_t stream) {
     (void)block;
     SweepWs w = carve(workspace, d_out, d_in);
@@ -1186,7 +1200,8 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
         pa.d_out = int(d_out); pa.d_in = int(d_in); pa.n_g = int(d_in / group_size); pa.ldD = int(ld_d(d_out));
         pa.lgG = 0;
         while ((1 << pa.lgG) < group_size) ++pa.lgG;
-        pa.qmax = float((1 << bits) - 1);
+        pa.qs = grid == ONECOMP_GRID_SYMMETRIC ? float((1 << (bits - 1)) - 1) : 0.f;
+        pa.qmax = grid == ONECOMP_GRID_SYMMETRIC ? 2.f * pa.qs : float((1 << bits) - 1);
         int buf = 0, p0 = 0, p1 = 0;   // previous super-block: residual buffer and column range
         for (int s0 = 0; s0 < d_in; s0 += SBIG) {
             const int s1 = int(d_in < int64_t(s0) + SBIG ? d_in : int64_t(s0) + SBIG);
@@ -1214,7 +1229,8 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
         a.Wf = w.Wf; a.U = U; a.perm = perm; a.Q = Q; a.scales = scales; a.zeros = zeros; a.W_hat = W_hat;
         a.Dh = w.Dh; a.Dl = w.Dl; a.ldD = int(ld_d(d_out)); a.sc = w.sc; a.rowloss = w.rowloss;
         a.d_out = int(d_out); a.d_in = int(d_in); a.G = group_size; a.n_g = int(d_in / group_size);
-        a.qmax = float((1 << bits) - 1);
+        a.qs = grid == ONECOMP_GRID_SYMMETRIC ? float((1 << (bits - 1)) - 1) : 0.f;
+        a.qmax = grid == ONECOMP_GRID_SYMMETRIC ? 2.f * a.qs : float((1 << bits) - 1);
         const int sbw = group_size <= SBIG ? (SBIG / group_size) * group_size : SBIG;
         for (int s0 = 0; s0 < d_in;) {
             int s1 = s0 + sbw;

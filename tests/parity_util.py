@@ -19,7 +19,7 @@ def _near_tie(t: np.ndarray) -> np.ndarray:
     return np.abs((t - np.floor(t)) - 0.5) < TIE_TOL
 
 
-def compare_codes(gpu_Q, gpu_zeros, W, U, bits, G, perm=None, rows=None, max_rounds=64):
+def compare_codes(gpu_Q, gpu_zeros, W, U, bits, G, perm=None, rows=None, max_rounds=64, grid="asym"):
     """GPU codes / zero-points against the oracle with tie replay.
 
     gpu_Q: [n_rows, d_in] codes in ORIGINAL column order, gpu_zeros: [n_rows, n_g].
@@ -39,7 +39,7 @@ def compare_codes(gpu_Q, gpu_zeros, W, U, bits, G, perm=None, rows=None, max_rou
     n_rows, n_g = gz.shape
     fc = -np.ones((n_rows, d_in), dtype=np.int64)
     fz = -np.ones((n_rows, n_g), dtype=np.int64)
-    out = oc.quantize_layer(W, U, bits, G, perm=perm, rows=rows)
+    out = oc.quantize_layer(W, U, bits, G, perm=perm, rows=rows, grid=grid)
     oq = out["Q"][:, perm].copy()
     raw_agree = float((oq == gq).mean())
     res = {k: np.array(v, copy=True) if isinstance(v, np.ndarray) else v for k, v in out.items()}
@@ -74,7 +74,7 @@ def compare_codes(gpu_Q, gpu_zeros, W, U, bits, G, perm=None, rows=None, max_rou
             break
         redo = np.array(redo)
         sub = oc.quantize_layer(W, U, bits, G, perm=perm, rows=rows[redo],
-                                forced_codes=fc[redo], forced_zeros=fz[redo])
+                                forced_codes=fc[redo], forced_zeros=fz[redo], grid=grid)
         for k in ("Q", "W_hat", "scales", "zeros", "E", "T", "Tz", "loss_rows"):
             res[k][redo] = sub[k]
         active = redo

@@ -150,3 +150,16 @@ def test_qep_target_argument_checks(lib):
     need = lib.onecomp_qep_workspace_bytes(64, 256)
     assert need >= 4 * 256 * 256 + 3 * 4 * 64 * 256
     assert lib.onecomp_qep_workspace_bytes(64, 250) == 0
+
+
+def test_quantize_grid_argument_checks(lib):
+    f = lib.onecomp_quantize_layer_grid
+    f.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                  ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    f.restype = ctypes.c_int
+    big = ctypes.c_size_t(1 << 40)
+    assert f(P, 1, 64, 256, P, NULL, 4, 128, 128, 2, P, P, P, P, P, P, big, NULL) == UNSUPPORTED    # unknown grid
+    assert f(P, 1, 64, 256, P, NULL, 4, 128, 128, -1, P, P, P, P, P, P, big, NULL) == UNSUPPORTED
+    assert f(NULL, 1, 64, 256, P, NULL, 4, 128, 128, 1, P, P, P, P, P, P, big, NULL) == INVALID
+    assert f(P, 1, 64, 256, P, NULL, 4, 128, 128, 1, P, P, P, P, P, NULL, big, NULL) == WORKSPACE

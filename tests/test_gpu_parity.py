@@ -40,9 +40,9 @@ def _gpu_gram(X, chunks=1):
     return H
 
 
-def _check_sweep(W, U32, bits, G, perm=None, rows=None, min_agree=0.999):
+def _check_sweep(W, U32, bits, G, perm=None, rows=None, min_agree=0.999, grid="minmax"):
     """W: torch tensor on GPU (original order), U32: torch fp32 on GPU."""
-    out = og.onecomp_quantize_layer(W, U32, bits, G, perm=perm)
+    out = og.onecomp_quantize_layer(W, U32, bits, G, perm=perm, grid=grid)
     torch.cuda.synchronize()
     Q = out["Q_codes"].cpu().numpy()
     S = out["scales"].cpu().numpy()
@@ -59,7 +59,10 @@ def _check_sweep(W, U32, bits, G, perm=None, rows=None, min_agree=0.999):
     g = inv // G
     deq = (S[:, g] * (Q.astype(np.float32) - Z[:, g])).astype(np.float32)
     assert np.array_equal(deq, WH)
-    st = compare_codes(Q[sel], Z[sel], to_f64(W), to_f64(U32), bits, G, perm=p, rows=sel)
+    st = compare_codes(Q[sel], Z[sel], to_f64(W), to_f64(U32), bits, G, perm=p, rows=sel,
+                       grid="sym" if grid == "symmetric" else "asym")
+    if grid == "symmetric":
+        assert np.all(Z == 2 ** (bits - 1) - 1) and Q.max() <= 2 ** bits - 2
     _announce(f"   raw agreement {st['raw_agree']:.6f}, tie flips {st['tie_flips']}, real {len(st['real_mismatches'])}")
     assert st["real_mismatches"] == []
     assert st["final_agree"] == 1.0
@@ -266,6 +269,29 @@ def test_sweep_variants(bits, G, d_out, d_in, dtype, act):
     _announce(f"sweep b{bits} g{G} {d_out}x{d_in} {dtype} act={act}")
     W, U32, perm = _layer(d_out, d_in, 2 * d_in + 13, seed=20 + bits + G, dtype=dtype, act=act)
     _check_sweep(W, U32, bits, G, perm=perm)
+
+
+@pytest.mark.parametrize("bits,G,d_out,d_in,dtype,act", [
+    (4, 128, 100, 1024, torch.bfloat16, False),
+    (3, 64, 33, 640, torch.float32, True),
+    (2, 16, 64, 256, torch.bfloat16, False),
+    (8, 32, 7, 384, torch.float32, False),
+    (4, 1280, 40, 1280, torch.bfloat16, False),    # per-channel, symmetric: the setting of the paper's Tables
+    (3, 256, 70, 1024, torch.bfloat16, True),
+])
+def test_sweep_symmetric_grid(bits, G, d_out, d_in, dtype, act):
+    _announce(f"sweep symmetric grid b{bits} g{G} {d_out}x{d_in} {dtype} act={act}")
+    W, U32, perm = _layer(d_out, d_in, 2 * d_in + 13, seed=60 + bits + G % 7, dtype=dtype, act=act)
+    _check_sweep(W, U32, bits, G, perm=perm, grid="symmetric")
+
+
+def test_sweep_symmetric_all_zero_group():
+    _announce("sweep symmetric grid, all-zero group")
+    W, U32, _ = _layer(8, 256, 700, seed=33)
+    W = W.clone()
+    W[0, :] = 0.0             # every group of this row is zero from the start: s = 1, codes at the zero-point
+    out, _ = _check_sweep(W, U32, 4, 64, grid="symmetric")
+    assert torch.all(out["W_hat"][0] == 0) and torch.all(out["Q_codes"][0] == 7) and torch.all(out["scales"][0] == 1)
 
 
 def test_sweep_degenerate_and_one_signed_groups():
