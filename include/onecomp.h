@@ -205,6 +205,28 @@ onecomp_status onecomp_qep_target(const void* W, onecomp_dtype w_dtype, int64_t 
 /* Scratch size for onecomp_qep_target (0 if the arguments are invalid): about 4 d_in^2 + 12 d_out d_in bytes. */
 size_t onecomp_qep_workspace_bytes(int64_t d_out, int64_t d_in);
 
+/*
+ * Activation-aware sensitivity of the layer under one candidate configuration (bit-width allocation, Sec. 4.1:
+ * err(l, c) ~ 1/2 tr(B dW A dW^T) with only the diagonals of A and B, dW = W^ - W from a fast round-to-nearest
+ * proxy).  In this library's d_out x d_in storage:
+ *     err = 1/2 sum_r sum_c b_r a_c (W^_rc - W_rc)^2,
+ * where W^ rounds every group of group_size consecutive input channels of a row to its own grid (min-max grid of
+ * Eq. (2) or symmetric grid of Eq. (3), no error feedback).  With a = b = 1 this is half the squared Frobenius
+ * norm of the perturbation.
+ *   W        [d_out x d_in] row-major, dtype w_dtype; read only.
+ *   a_diag   fp32 [d_in]: diagonal of the input Gram matrix A (e.g. diag H of onecomp_hessian_accumulate, which
+ *            carries that call's factor 2); read only.
+ *   b_diag   fp32 [d_out]: diagonal of the output curvature B, or NULL for all ones; read only.
+ *   bits, group_size, grid: the candidate; group_size a multiple of 16 that divides d_in (no block restriction).
+ *   err      device fp32 scalar, out.  fp32 arithmetic, partial sums combined in a fixed order (reproducible).
+ *   workspace device scratch, >= onecomp_sensitivity_workspace_bytes(), 256-byte aligned.
+ */
+onecomp_status onecomp_rtn_sensitivity(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                       const float* a_diag, const float* b_diag,
+                                       int bits, int group_size, onecomp_grid grid, float* err,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t onecomp_sensitivity_workspace_bytes(void);
+
 /* Static, NUL-terminated description of a status code. */
 const char* onecomp_status_string(onecomp_status status);
 

@@ -349,3 +349,18 @@ def qep_target(W, G, H, damp, alpha):
     cf = cho_factor(Hd, lower=True)
     corr = cho_solve(cf, R.T).T                  # R Hd^-1 (Hd symmetric)
     return W + float(alpha) * corr
+
+
+# --------------------------------------------------------------------------
+# Sensitivity proxy for bit-width allocation  [Sec. 4.1, "AutoBit"]
+# --------------------------------------------------------------------------
+def rtn_sensitivity(W, a_diag, b_diag, bits, group_size, grid="asym"):
+    """err = 1/2 tr(B dW A dW^T) with diagonal A (input channels) and B (output rows) and dW = W^ - W from the
+    round-to-nearest proxy (rtn_quantize), written for the d_out x d_in storage:
+    1/2 sum_r sum_c b_r a_c dW_rc^2.  b_diag None = ones."""
+    W = np.asarray(W, dtype=np.float64)
+    _, _, _, What = rtn_quantize(W, bits, group_size, grid=grid)
+    D = What - W
+    a = np.asarray(a_diag, dtype=np.float64)
+    b = np.ones(W.shape[0]) if b_diag is None else np.asarray(b_diag, dtype=np.float64)
+    return 0.5 * float((b[:, None] * D * D * a[None, :]).sum())

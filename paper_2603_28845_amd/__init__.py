@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     onecomp_qep_workspace_bytes,
     onecomp_quantize_layer,
     onecomp_quantize_workspace_bytes,
+    onecomp_rtn_sensitivity,
     onecomp_version,
     status_string,
 )

@@ -32,6 +32,8 @@ EXPORTED_SYMBOLS = (
     "onecomp_crossgram_accumulate",
     "onecomp_qep_target",
     "onecomp_qep_workspace_bytes",
+    "onecomp_rtn_sensitivity",
+    "onecomp_sensitivity_workspace_bytes",
     "onecomp_status_string",
     "onecomp_version",
 )
@@ -75,6 +77,10 @@ def load_library() -> ctypes.CDLL:
     lib.onecomp_qep_target.restype = i32
     lib.onecomp_qep_workspace_bytes.argtypes = [i64, i64]
     lib.onecomp_qep_workspace_bytes.restype = sz
+    lib.onecomp_rtn_sensitivity.argtypes = [vp, i32, i64, i64, vp, vp, i32, i32, i32, vp, vp, sz, vp]
+    lib.onecomp_rtn_sensitivity.restype = i32
+    lib.onecomp_sensitivity_workspace_bytes.argtypes = []
+    lib.onecomp_sensitivity_workspace_bytes.restype = sz
     lib.onecomp_status_string.argtypes = [i32]
     lib.onecomp_status_string.restype = ctypes.c_char_p
     lib.onecomp_version.argtypes = []
@@ -246,3 +252,26 @@ def onecomp_qep_target(W: torch.Tensor, G: torch.Tensor, H: torch.Tensor, U: tor
     if rc != ONECOMP_OK:
         raise OnecompError(rc, "onecomp_qep_target")
     return W_star
+
+
+def onecomp_rtn_sensitivity(W: torch.Tensor, a_diag: torch.Tensor, bits: int, group_size: int,
+                            b_diag: Optional[torch.Tensor] = None, grid: str = "minmax",
+                            err: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """err = 1/2 sum_r sum_c b_r a_c (RTN(W) - W)_rc^2 as a device fp32 scalar tensor."""
+    lib = load_library()
+    d_out, d_in = W.shape
+    if err is None:
+        err = torch.zeros(1, dtype=torch.float32, device=W.device)
+    if workspace is None:
+        workspace = torch.empty(max(int(lib.onecomp_sensitivity_workspace_bytes()), 256), dtype=torch.uint8,
+                                device=W.device)
+    if grid not in ("minmax", "symmetric"):
+        raise ValueError("grid must be 'minmax' or 'symmetric'")
+    rc = lib.onecomp_rtn_sensitivity(_dev(W, "W"), _dtype_code(W), d_out, d_in, _dev(a_diag, "a_diag", torch.float32),
+                                     _ptr(b_diag), int(bits), int(group_size),
+                                     ONECOMP_GRID_SYMMETRIC if grid == "symmetric" else ONECOMP_GRID_MINMAX,
+                                     _dev(err, "err", torch.float32), _dev(workspace, "workspace", torch.uint8),
+                                     workspace.numel(), _stream())
+    if rc != ONECOMP_OK:
+        raise OnecompError(rc, "onecomp_rtn_sensitivity")
+    return err

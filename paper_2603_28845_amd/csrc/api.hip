@@ -115,6 +115,25 @@ ONECOMP_API onecomp_status onecomp_qep_target(const void* W, onecomp_dtype w_dty
                           static_cast<hipStream_t>(hip_stream));
 }
 
+ONECOMP_API size_t onecomp_sensitivity_workspace_bytes(void) { return sensitivity_workspace_bytes(); }
+
+ONECOMP_API onecomp_status onecomp_rtn_sensitivity(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                                   const float* a_diag, const float* b_diag, int bits, int group_size,
+                                                   onecomp_grid grid, float* err, void* workspace,
+                                                   size_t workspace_bytes, void* hip_stream) {
+    if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
+    if (grid != ONECOMP_GRID_MINMAX && grid != ONECOMP_GRID_SYMMETRIC) return ONECOMP_ERR_UNSUPPORTED;
+    if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return ONECOMP_ERR_UNSUPPORTED;
+    if (!W || !a_diag || !err) return ONECOMP_ERR_INVALID_ARG;
+    if (d_out <= 0 || d_in <= 0 || d_out > (1 << 24) || d_in > (1 << 24)) return ONECOMP_ERR_INVALID_ARG;
+    if (group_size <= 0 || d_in % group_size != 0) return ONECOMP_ERR_INVALID_ARG;
+    if (group_size % 16 != 0) return ONECOMP_ERR_UNSUPPORTED;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < sensitivity_workspace_bytes())
+        return ONECOMP_ERR_WORKSPACE;
+    return sensitivity_run(W, w_dtype, d_out, d_in, a_diag, b_diag, bits, group_size, int(grid), err, workspace,
+                           static_cast<hipStream_t>(hip_stream));
+}
+
 ONECOMP_API const char* onecomp_status_string(onecomp_status status) {
     switch (status) {
         case ONECOMP_OK: return "ok";

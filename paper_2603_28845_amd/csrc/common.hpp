@@ -66,4 +66,9 @@ onecomp_status qep_target_run(const void* W, onecomp_dtype w_dtype, int64_t d_ou
                               const float* H, const float* U, const int32_t* perm, float alpha, float* W_star,
                               void* workspace, hipStream_t stream);
 
+size_t sensitivity_workspace_bytes();
+onecomp_status sensitivity_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* a_diag,
+                               const float* b_diag, int bits, int group_size, int grid, float* err, void* workspace,
+                               hipStream_t stream);
+
 }  // namespace onecomp

@@ -163,3 +163,28 @@ def test_quantize_grid_argument_checks(lib):
     assert f(P, 1, 64, 256, P, NULL, 4, 128, 128, -1, P, P, P, P, P, P, big, NULL) == UNSUPPORTED
     assert f(NULL, 1, 64, 256, P, NULL, 4, 128, 128, 1, P, P, P, P, P, P, big, NULL) == INVALID
     assert f(P, 1, 64, 256, P, NULL, 4, 128, 128, 1, P, P, P, P, P, NULL, big, NULL) == WORKSPACE
+
+
+def test_sensitivity_argument_checks(lib):
+    f = lib.onecomp_rtn_sensitivity
+    f.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                  ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                  ctypes.c_void_p]
+    f.restype = ctypes.c_int
+    lib.onecomp_sensitivity_workspace_bytes.restype = ctypes.c_size_t
+    big = ctypes.c_size_t(1 << 30)
+
+    def call(W=P, dt=1, d_out=64, d_in=256, a=P, b=NULL, bits=4, G=128, grid=0, err=P, ws=P, wsb=big):
+        return f(W, dt, d_out, d_in, a, b, bits, G, grid, err, ws, wsb, NULL)
+
+    assert call(dt=5) == UNSUPPORTED
+    assert call(grid=3) == UNSUPPORTED
+    assert call(bits=5) == UNSUPPORTED
+    assert call(G=24) == INVALID           # does not divide d_in
+    assert call(G=8) == UNSUPPORTED        # not a multiple of 16
+    assert call(W=NULL) == INVALID
+    assert call(a=NULL) == INVALID
+    assert call(err=NULL) == INVALID
+    assert call(ws=NULL) == WORKSPACE
+    assert call(wsb=ctypes.c_size_t(8)) == WORKSPACE
+    assert lib.onecomp_sensitivity_workspace_bytes() >= 4

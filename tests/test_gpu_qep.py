@@ -135,3 +135,31 @@ def test_qep_reduces_the_output_error_of_the_quantized_layer():
     err_unq = torch.linalg.norm(Xhd @ Wd.T - target).item()
     _announce(f"   output error: unquantized W on X_hat {err_unq:.4g}, quantized W {err_base:.4g}, quantized W* {err_qep:.4g}")
     assert err_qep < err_base
+
+
+@pytest.mark.parametrize("bits,G,d_out,d_in,dtype,grid", [
+    (4, 128, 300, 1024, torch.bfloat16, "minmax"),
+    (3, 64, 33, 640, torch.float32, "symmetric"),
+    (2, 16, 64, 256, torch.bfloat16, "minmax"),
+    (8, 32, 7, 384, torch.float32, "minmax"),
+    (4, 1280, 40, 1280, torch.bfloat16, "symmetric"),     # per-channel
+    (4, 128, 4096, 4096, torch.bfloat16, "minmax"),       # a full-size attention projection
+])
+def test_rtn_sensitivity(bits, G, d_out, d_in, dtype, grid):
+    """Bit-allocation proxy 1/2 sum b_r a_c dW_rc^2 (Sec. 4.1).  Bar: relative error <= 1e-3 against the float64
+    oracle, the bar of the sweep's loss (fp32 grid parameters; an isolated rounding tie moves one element by a
+    grid step)."""
+    _announce(f"RTN sensitivity b{bits} g{G} {d_out}x{d_in} {dtype} {grid}")
+    cfg = synth.scaled(synth.CONFIGS["c2"], d_out=d_out, d_in=d_in, n_tokens=16, seed=70 + bits, dtype=dtype)
+    W = synth.make_weight(cfg, DEV)
+    gen = torch.Generator(device=DEV).manual_seed(5)
+    a = (0.5 + 3.0 * torch.rand(d_in, generator=gen, device=DEV)).to(torch.float32)
+    b = (0.5 + torch.rand(d_out, generator=gen, device=DEV)).to(torch.float32)
+    og_grid = "sym" if grid == "symmetric" else "asym"
+    for bd in (None, b):
+        e = og.onecomp_rtn_sensitivity(W, a, bits, G, b_diag=bd, grid=grid)
+        e2 = og.onecomp_rtn_sensitivity(W, a, bits, G, b_diag=bd, grid=grid)
+        torch.cuda.synchronize()
+        ref = oc.rtn_sensitivity(to_f64(W), to_f64(a), None if bd is None else to_f64(bd), bits, G, grid=og_grid)
+        assert abs(float(e.item()) - ref) <= 1e-3 * ref
+        assert torch.equal(e, e2)        # reproducible bit for bit
