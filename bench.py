@@ -150,6 +150,16 @@ def bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out):
         step(rec)
     torch.cuda.synchronize()
     assert int(info.item()) == 0
+    # the bit-allocation proxy on the same layer (one candidate = the configured bits / group): memory bound
+    a_diag = torch.diagonal(H).contiguous()
+    e_s = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    og.onecomp_rtn_sensitivity(W, a_diag, cfg.bits, cfg.group_size)
+    e_s[0].record()
+    for _ in range(10):
+        sens = og.onecomp_rtn_sensitivity(W, a_diag, cfg.bits, cfg.group_size)
+    e_s[1].record()
+    torch.cuda.synchronize()
+    sens_ms = e_s[0].elapsed_time(e_s[1]) / 10
     names = ["hessian_accumulate", "crossgram_accumulate", "hessian_factor", "qep_target", "quantize_layer"]
     ph = {n: sum(e[i].elapsed_time(e[i + 1]) for e in rec) / len(rec) for i, n in enumerate(names)}
     total = sum(ph.values())
@@ -158,6 +168,9 @@ def bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out):
         "crossgram_tflops": 2.0 * cfg.n_tokens * d_in * d_in / (ph["crossgram_accumulate"] * 1e-3) / 1e12,
         "qep_target_tflops_fp32": 4.0 * d_out * d_in * d_in / (ph["qep_target"] * 1e-3) / 1e12,
         "loss": float(out["loss"].item()),
+        "rtn_sensitivity": {"ms": sens_ms, "value": float(sens.item()),
+                            "gbs": W.numel() * W.element_size() / (sens_ms * 1e-3) / 1e9,
+                            "note": "one candidate configuration; W read once from HBM (second pass from cache)"},
         "note": "X_hat = X * (1 + 0.05 N(0,1)); alpha = 1; cross-Gram flops 2 T d_in^2 (no symmetry to use); target flops "
                 "4 d_out d_in^2 (one full and two triangular products)",
     }

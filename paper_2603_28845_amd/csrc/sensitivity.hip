@@ -6,19 +6,36 @@
 // every group of G consecutive input channels of a row to its own grid (Eq. (1), (2) or (3), (4)), no feedback.
 //
 // gfx950: memory bound (W is read once from HBM, a second time from cache).  A team of TS <= 64 lanes of one
-// wave owns a group at a time: strided pass for min / max (shuffle reduction inside the team), second pass to
-// round and accumulate.  Per-workgroup partial sums are combined in a fixed order: bit-wise reproducible.
+// wave owns a group at a time, 16 bytes per lane and load: pass for min / max (shuffle reduction inside the team),
+// second pass to round and accumulate.  Per-workgroup partial sums are combined in a fixed order: bit-wise reproducible.
 #include "common.hpp"
 
 namespace onecomp {
 namespace {
 
+// V consecutive elements (16 bytes) as floats
 template <typename T>
-__device__ inline float ld_f32(const T* p);
+struct Vec;
 template <>
-__device__ inline float ld_f32<float>(const float* p) { return *p; }
+struct Vec<float> {
+    static constexpr int V = 4;
+    static __device__ inline void load(const float* p, float (&v)[4]) {
+        const float4v x = *reinterpret_cast<const float4v*>(p);
+        v[0] = x[0]; v[1] = x[1]; v[2] = x[2]; v[3] = x[3];
+    }
+};
 template <>
-__device__ inline float ld_f32<uint16_t>(const uint16_t* p) { return __uint_as_float(uint32_t(*p) << 16); }
+struct Vec<uint16_t> {
+    static constexpr int V = 8;
+    static __device__ inline void load(const uint16_t* p, float (&v)[8]) {
+        const uint4v x = *reinterpret_cast<const uint4v*>(p);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[2 * e] = __uint_as_float(x[e] << 16);
+            v[2 * e + 1] = __uint_as_float(x[e] & 0xFFFF0000u);
+        }
+    }
+};
 
 struct SensArgs {
     const void* W;
@@ -32,10 +49,11 @@ struct SensArgs {
 
 template <typename T>
 __global__ __launch_bounds__(256) void sens_kernel(SensArgs g) {
-    __shared__ float team_sum[32];
+    constexpr int V = Vec<T>::V;
+    __shared__ float team_sum[128];
     const T* W = static_cast<const T*>(g.W);
     const int tid = threadIdx.x;
-    const int ts = g.ts;                         // lanes per team, a power of two in 8 .. 64
+    const int ts = g.ts;                         // lanes per team, a power of two in 2 .. 64; a lane takes V elements
     const int team = tid / ts, tl = tid % ts, teams = 256 / ts;
     float acc = 0.f;
     for (int64_t gi = int64_t(blockIdx.x) * teams + team; gi < g.n_groups; gi += int64_t(gridDim.x) * teams) {
@@ -43,9 +61,11 @@ __global__ __launch_bounds__(256) void sens_kernel(SensArgs g) {
         const int c0 = int(gi % g.n_g) * g.G;
         const T* wp = W + row * g.d_in + c0;
         float mn = 3.0e38f, mx = -3.0e38f;
-        for (int c = tl; c < g.G; c += ts) {
-            const float v = ld_f32<T>(wp + c);
-            mn = fminf(mn, v); mx = fmaxf(mx, v);
+        for (int c = tl * V; c < g.G; c += ts * V) {
+            float v[V];
+            Vec<T>::load(wp + c, v);
+#pragma unroll
+            for (int e = 0; e < V; ++e) { mn = fminf(mn, v[e]); mx = fmaxf(mx, v[e]); }
         }
         for (int off = ts >> 1; off > 0; off >>= 1) {
             mn = fminf(mn, __shfl_xor(mn, off, 64));
@@ -64,11 +84,20 @@ __global__ __launch_bounds__(256) void sens_kernel(SensArgs g) {
         const float rs = 1.0f / s;
         const float br = g.b ? g.b[row] : 1.0f;
         float part = 0.f;
-        for (int c = tl; c < g.G; c += ts) {
-            const float v = ld_f32<T>(wp + c);
-            const float q = fminf(fmaxf(rintf(v * rs) + z, 0.f), g.qmax);
-            const float d = v - s * (q - z);
-            part = __builtin_fmaf(g.a[c0 + c] * d, d, part);
+        for (int c = tl * V; c < g.G; c += ts * V) {     // second pass: the group is in cache
+            float v[V], av[V];
+            Vec<T>::load(wp + c, v);
+#pragma unroll
+            for (int e = 0; e < V; e += 4) {
+                const float4v x = *reinterpret_cast<const float4v*>(g.a + c0 + c + e);
+                av[e] = x[0]; av[e + 1] = x[1]; av[e + 2] = x[2]; av[e + 3] = x[3];
+            }
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const float q = fminf(fmaxf(rintf(v[e] * rs) + z, 0.f), g.qmax);
+                const float d = v[e] - s * (q - z);
+                part = __builtin_fmaf(av[e] * d, d, part);
+            }
         }
         acc = __builtin_fmaf(br, part, acc);
     }
@@ -109,8 +138,9 @@ onecomp_status sensitivity_run(const void* W, onecomp_dtype w_dtype, int64_t d_o
     g.W = W; g.a = a_diag; g.b = b_diag; g.partial = static_cast<float*>(workspace);
     g.d_in = int(d_in); g.G = group_size; g.n_g = int(d_in / group_size);
     g.n_groups = d_out * int64_t(g.n_g);
-    int ts = 8;
-    while (ts < 64 && ts * 2 <= group_size / 2) ts *= 2;      // at least two elements per lane
+    const int vec = w_dtype == ONECOMP_BF16 ? 8 : 4;          // elements per 16-byte lane load
+    int ts = 2;
+    while (ts < 64 && ts * 2 * vec <= group_size) ts *= 2;    // one pass over the group if it fits 64 lanes
     g.ts = ts;
     g.qs = grid == ONECOMP_GRID_SYMMETRIC ? float((1 << (bits - 1)) - 1) : 0.f;
     g.qmax = grid == ONECOMP_GRID_SYMMETRIC ? 2.f * g.qs : float((1 << bits) - 1);
