@@ -83,7 +83,7 @@ def cpu_baseline(cfg, synth, seconds_hint=20.0):
     from threadpoolctl import threadpool_info
     from oracle import onecomp_oracle as oc
 
-    n_s = min(8192, cfg.n_tokens)
+    n_s = min(16384, cfg.n_tokens)
     d_s = max(128, (cfg.d_in // 2) // cfg.group_size * cfg.group_size)
     r_s = min(256, cfg.d_out)
     X = synth.make_activations(cfg, "cpu", n_tokens=n_s).to(dtype=__import__("torch").float64).numpy()
