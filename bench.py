@@ -190,6 +190,10 @@ def main():
                     help="also time the layer with error propagation (Sec. 4.2.1): Gram of the perturbed activations, "
                          "cross-Gram, factor, corrected target, sweep of the corrected target; reported under 'qep', "
                          "the headline value is unchanged")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="context only: also time the vendor library's dense bf16 GEMM X^T X (torch.matmul, full d_in x "
+                         "d_in output, no symmetry, no accumulate into fp32 H) on the same activations; reported under "
+                         "'vendor_gemm_context', the headline value is unchanged")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="profiling aid: also run one plain 4 GiB device-to-device copy kernel (known HBM traffic: "
                          "4 GiB read + 4 GiB written) so that FETCH_SIZE / WRITE_SIZE can be scaled")
@@ -336,6 +340,22 @@ def main():
         "loss": float(out["loss"].item()),
         "roofline": roofline, "roofline_sweep": roofline_sweep,
     }
+    if args.vendor_gemm and cfg.dtype == torch.bfloat16:
+        e = [ev() for _ in range(2)]
+        torch.matmul(X.t(), X)
+        e[0].record()
+        for _ in range(3):
+            G = torch.matmul(X.t(), X)
+        e[1].record()
+        torch.cuda.synchronize()
+        v_ms = e[0].elapsed_time(e[1]) / 3
+        del G
+        res["vendor_gemm_context"] = {
+            "op": "torch.matmul(X.t(), X), bf16 in and out, all d_in x d_in entries", "ms": v_ms,
+            "dense_tflops": 2.0 * T * d_in * d_in / (v_ms * 1e-3) / 1e12,
+            "frac_of_bf16_peak": 2.0 * T * d_in * d_in / (v_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "gram_kernel_ms_for_the_same_tokens": acc_ms,
+        }
     if args.qep:
         res["qep"] = bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out)
     if not args.no_cpu_baseline:
