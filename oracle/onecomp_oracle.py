@@ -19,6 +19,10 @@ What it computes (paper sections given in brackets):
     residual to the columns not yet quantized  [Sec. 4.2; grid: Eq. (1) scalar
     quantizer, Eq. (2) min-max scale / zero-point, Eq. (4) per-group layout]
   * the layer objective tr((W-W^) H (W-W^)^T)  [Eq. (layerwise), Eq. (activation-aware)]
+  * the same sweep without the off-diagonal part of the inverse factor (direct_factor, block_feedback_factor,
+    quantize_layer_direct): with R = U^-1, R R^T = H + lambda I, the propagated errors are e = (w - w^) R, so a
+    blocked sweep can run on one Cholesky factor of the damped matrix itself and the inverses of its diagonal
+    blocks  [a restatement of Sec. 4.2, derived in quantize_layer_direct]
   * the corrected quantization target of error propagation (QEP),
     W* = (I + alpha (H^ + lambda I)^-1 C) W  with  C = X^^T (X - X^)  [Sec. 4.2.1, Eq. (qep)]
 
@@ -136,6 +140,34 @@ def hessian_factor(H, damp, act_order=False):
     Hp = Hd[np.ix_(perm, perm)] if act_order else Hd
     U, info = inverse_factor(Hp)
     return {"U": U, "perm": perm, "info": info, "Hd": Hd, "lam": lam}
+
+
+def direct_factor(Hd):
+    """Upper-triangular R with positive diagonal and R R^T = Hd, so that R = U^-1 for the inverse factor U of
+    Sec. 4.2.1 (U^T U = Hd^-1  <=>  Hd = U^-1 U^-T).  One Cholesky of the index-reversed matrix:
+    J Hd J = L L^T  =>  Hd = (J L J)(J L J)^T  with J L J upper.  Returns (R, info) like inverse_factor."""
+    Hd = np.asarray(Hd, dtype=np.float64)
+    try:
+        L = np.linalg.cholesky(Hd[::-1, ::-1])
+    except np.linalg.LinAlgError:
+        return None, first_bad_pivot(Hd[::-1, ::-1])
+    return np.ascontiguousarray(L[::-1, ::-1]), 0
+
+
+def block_feedback_factor(U, R, block):
+    """The matrix F from which a blocked sweep can run without the off-diagonal part of U (quantize_layer_direct):
+    F = U on the block x block diagonal blocks;  F_jk = -U_jj R_jk / R_kk  where j and k lie in different blocks
+    (k > j);  0 below the diagonal.  Only the diagonal blocks of U enter, and those are the inverses of the
+    diagonal blocks of R."""
+    U = np.asarray(U, dtype=np.float64)
+    R = np.asarray(R, dtype=np.float64)
+    n = R.shape[0]
+    d = np.diag(R)
+    F = -np.triu(R, 1) / d[None, :] * np.diag(U)[:, None]
+    for b0 in range(0, n, block):
+        b1 = min(n, b0 + block)
+        F[b0:b1, b0:b1] = np.triu(U[b0:b1, b0:b1])
+    return np.triu(F)
 
 
 # --------------------------------------------------------------------------
@@ -297,6 +329,68 @@ def layer_loss(W, W_hat, Hd):
     Gram matrix written out; all three arguments in the same column order)."""
     D = np.asarray(W, dtype=np.float64) - np.asarray(W_hat, dtype=np.float64)
     return float(((D @ np.asarray(Hd, dtype=np.float64)) * D).sum())
+
+
+def quantize_layer_direct(W, R, bits, group_size, block, perm=None, grid="asym"):
+    """The sweep of Sec. 4.2 arranged so that only ONE Cholesky factor of the damped matrix is needed.
+
+    For one row let w be the original weights, w^ the quantized ones, e the propagated errors of
+    quantize_layer and R = U^-1 (upper, R R^T = Hd, direct_factor).  Column j receives sum_{i<j} e_i U_ij and
+    its own step removes e_j U_jj, hence  w - w^ = e U  and  e = (w - w^) R.
+    Split the columns into those already finished (A) and the rest (B).  The inverse of a block-triangular
+    matrix gives U_AB = -U_AA R_AB U_BB, so the compensated values of the unfinished columns are
+        w_B - e_A U_AB = w_B + (w_A - w^_A) R_AA U_AA R_AB U_BB = w_B + (w_A - w^_A) R_AB U_BB ,
+    and because U_BB is upper triangular its leading block x block part, the inverse of the diagonal block of R,
+    is all that the next `block` columns need.  Per block of columns b:
+        c    = sum over finished columns i of (w_i - w^_i) R_ib          (deviations from the ORIGINAL weights)
+        w'_b = w_b + c (R_bb)^-1                                         (state the paper's sweep has on entering b)
+        then the paper's steps inside the block with U_bb = (R_bb)^-1.
+    Same greedy rule, same grid, same outputs as quantize_layer in exact arithmetic as long as no group
+    straddles a block.  Returns dict(Q, W_hat, scales, zeros, loss), Q and W_hat in original column order.
+    Pinned against quantize_layer in tests/test_oracle_direct.py."""
+    W = np.asarray(W, dtype=np.float64)
+    R = np.asarray(R, dtype=np.float64)
+    d_out, d_in = W.shape
+    G, B = int(group_size), int(block)
+    if B % G != 0 or d_in % B != 0:
+        raise ValueError("groups must not straddle blocks")
+    n_g = d_in // G
+    qtop = code_range_top(bits, grid)
+    params = minmax_params if grid == "asym" else symmetric_params
+    if perm is None:
+        perm = np.arange(d_in, dtype=np.int64)
+    perm = np.asarray(perm, dtype=np.int64)
+    w0 = W[:, perm]
+    dev = np.zeros((d_out, d_in))                # w - w^ of the finished columns
+    Q = np.zeros((d_out, d_in), dtype=np.int64)
+    What = np.zeros((d_out, d_in))
+    scales = np.zeros((d_out, n_g))
+    zeros = np.zeros((d_out, n_g))
+    loss = 0.0
+    for b0 in range(0, d_in, B):
+        Ubb = solve_triangular(R[b0:b0 + B, b0:b0 + B], np.eye(B), lower=False)
+        c = dev[:, :b0] @ R[:b0, b0:b0 + B]
+        w = w0[:, b0:b0 + B] + c @ Ubb
+        s = z = None
+        for j in range(B):
+            if j % G == 0:
+                blk = w[:, j:j + G]
+                s, z, _ = params(blk.min(axis=1), blk.max(axis=1), bits)
+                scales[:, (b0 + j) // G] = s
+                zeros[:, (b0 + j) // G] = z
+            q, wh, _ = quantize_scalar(w[:, j], s, z, bits, qtop)
+            e = (w[:, j] - wh) / Ubb[j, j]
+            if j + 1 < B:
+                w[:, j + 1:] -= e[:, None] * Ubb[j, j + 1:][None, :]
+            loss += float((e * e).sum())
+            Q[:, b0 + j] = q.astype(np.int64)
+            What[:, b0 + j] = wh
+        dev[:, b0:b0 + B] = w0[:, b0:b0 + B] - What[:, b0:b0 + B]
+    out_Q = np.zeros_like(Q)
+    out_What = np.zeros_like(What)
+    out_Q[:, perm] = Q
+    out_What[:, perm] = What
+    return {"Q": out_Q, "W_hat": out_What, "scales": scales, "zeros": zeros, "loss": loss}
 
 
 def dequantize(Q, scales, zeros, group_size, perm=None):
