@@ -190,6 +190,10 @@ def main():
                     help="also time the layer with error propagation (Sec. 4.2.1): Gram of the perturbed activations, "
                          "cross-Gram, factor, corrected target, sweep of the corrected target; reported under 'qep', "
                          "the headline value is unchanged")
+    ap.add_argument("--factor-form", default="inverse", choices=["inverse", "block"],
+                    help="inverse: the factor call returns U with U^T U = (H + lambda I)^-1 (Sec. 4.2.1) and the sweep "
+                         "propagates through it; block: one Cholesky only, the sweep runs on the block form (same codes "
+                         "up to ties; groups up to 128 columns)")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="context only: also time the vendor library's dense bf16 GEMM X^T X (torch.matmul, full d_in x "
                          "d_in output, no symmetry, no accumulate into fp32 H) on the same activations; reported under "
@@ -250,10 +254,12 @@ def main():
                 og.onecomp_hessian_accumulate(X[t0:t0 + tpc], H)
         e[1].record()
         if only in (None, "factor"):
-            og.onecomp_hessian_factor(H, cfg.damp, cfg.act_order, U=U, perm_out=perm, info=info, workspace=ws_f)
+            og.onecomp_hessian_factor(H, cfg.damp, cfg.act_order, U=U, perm_out=perm, info=info, workspace=ws_f,
+                                      form=args.factor_form)
         e[2].record()
         if only in (None, "sweep"):
-            og.onecomp_quantize_layer(W, U, cfg.bits, cfg.group_size, perm=perm, workspace=ws_q, out=out)
+            og.onecomp_quantize_layer(W, U, cfg.bits, cfg.group_size, perm=perm, workspace=ws_q, out=out,
+                                      form=args.factor_form)
         e[3].record()
         if record is not None:
             record.append(e)
@@ -331,7 +337,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: W {d_out}x{d_in} {str(cfg.dtype).split('.')[-1]}, {T} tokens, "
                                f"{cfg.bits}-bit, group {cfg.group_size}, damp {cfg.damp}, act_order {cfg.act_order}, "
-                               f"block 128, {n_calls} accumulate call(s)"
+                               f"block 128, {n_calls} accumulate call(s), factor form {args.factor_form}"
                                + ("" if phase == "all" else f" [PROFILING RUN: only phase '{phase}' timed, value is not the metric]")},
         "phases_ms": {"hessian_accumulate": acc_ms, "hessian_factor": fac_ms, "quantize_layer": swp_ms},
         "layer_quantize_ms": fac_ms + swp_ms,

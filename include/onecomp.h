@@ -58,6 +58,20 @@ typedef enum {
     ONECOMP_GRID_SYMMETRIC = 1
 } onecomp_grid;
 
+/* What the factor call hands to the sweep.
+ *   ONECOMP_FACTOR_INVERSE  the inverse factor U of Sec. 4.2.1, U^T U = (H + lambda I)^-1 (one Cholesky plus one
+ *                           triangular inverse, 2 d_in^3 / 3 flops).
+ *   ONECOMP_FACTOR_BLOCK    one Cholesky only (d_in^3 / 3 flops).  With R = U^-1 (upper, R R^T = H + lambda I) the
+ *                           matrix written is F = U on the 128 x 128 diagonal blocks and
+ *                           F_jk = -U_jj R_jk / R_kk where j and k lie in different blocks.  The sweep's errors
+ *                           satisfy e = (w - w^) R (w the original weights), so the compensated values on entering a
+ *                           block are  w_b + c (R_bb)^-1  with  c = sum over finished columns i of (w_i - w^_i) R_ib:
+ *                           the same codes, scales, zeros and loss as with U, up to rounding. */
+typedef enum {
+    ONECOMP_FACTOR_INVERSE = 0,
+    ONECOMP_FACTOR_BLOCK = 1
+} onecomp_factor_form;
+
 /*
  * H += 2 * X^T X  over the n_tokens rows of X (Gram matrix of Sec. 2.5 / Sec. 4.2; the
  * factor 2 makes it the Hessian of ||X (W^ - W)||^2, cf. Sec. 2.4).
@@ -102,6 +116,17 @@ onecomp_status onecomp_hessian_accumulate(const void* X, onecomp_dtype x_dtype,
 onecomp_status onecomp_hessian_factor(const float* H, int64_t d_in, float damp, int act_order,
                                       int32_t* perm_out, float* U, int32_t* info,
                                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * onecomp_hessian_factor with the form of the result chosen by the caller (onecomp_hessian_factor is this call
+ * with ONECOMP_FACTOR_INVERSE).  ONECOMP_FACTOR_BLOCK writes the matrix F described at onecomp_factor_form into
+ * `F_out` (same shape and layout as U, strict lower triangle zero); it needs d_in % 128 == 0 and is meant for
+ * onecomp_quantize_layer_form only (onecomp_qep_target needs the inverse form).  Same workspace, same `info`.
+ * An unknown form, or a d_in the form does not support, is ONECOMP_ERR_UNSUPPORTED.
+ */
+onecomp_status onecomp_hessian_factor_form(const float* H, int64_t d_in, float damp, int act_order,
+                                           onecomp_factor_form form, int32_t* perm_out, float* F_out, int32_t* info,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * The column sweep (Sec. 4.2) on the per-group asymmetric grid (Eq. (1), (2), (4)).
@@ -156,6 +181,24 @@ onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w_dtype, int6
  */
 onecomp_status onecomp_quantize_layer_grid(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
                                            const float* U, const int32_t* perm,
+                                           int bits, int group_size, int block_size, onecomp_grid grid,
+                                           uint8_t* Q_codes, float* scales, float* zeros,
+                                           float* W_hat, float* loss,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * onecomp_quantize_layer_grid for a factor in either form (onecomp_quantize_layer_grid is this call with
+ * ONECOMP_FACTOR_INVERSE).  With ONECOMP_FACTOR_BLOCK, `F` is the output of onecomp_hessian_factor_form in that
+ * form: inside a 128-column block the steps are those of onecomp_quantize_layer (F holds U there); between blocks
+ * the workspace accumulates c_k = sum_i (w_i - w^_i) R_ik / R_kk over the finished columns i of earlier blocks
+ * (deviations from the ORIGINAL weights; 22-bit operands, fp32 sum, as described at onecomp_quantize_layer) and a
+ * block starts from  w_b + c (U_bb rows divided by their diagonal)  in fp32.  Outputs and their meaning are
+ * unchanged; results agree with the inverse form up to rounding.  ONECOMP_FACTOR_BLOCK needs group_size <= 128
+ * (wider groups take their grid from columns of later blocks, whose compensated values this form does not hold):
+ * otherwise ONECOMP_ERR_UNSUPPORTED.
+ */
+onecomp_status onecomp_quantize_layer_form(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                           const float* F, onecomp_factor_form form, const int32_t* perm,
                                            int bits, int group_size, int block_size, onecomp_grid grid,
                                            uint8_t* Q_codes, float* scales, float* zeros,
                                            float* W_hat, float* loss,

@@ -21,12 +21,16 @@ ONECOMP_F32 = 0
 ONECOMP_BF16 = 1
 ONECOMP_GRID_MINMAX = 0
 ONECOMP_GRID_SYMMETRIC = 1
+ONECOMP_FACTOR_INVERSE = 0
+ONECOMP_FACTOR_BLOCK = 1
 
 EXPORTED_SYMBOLS = (
     "onecomp_hessian_accumulate",
     "onecomp_hessian_factor",
     "onecomp_quantize_layer",
     "onecomp_quantize_layer_grid",
+    "onecomp_hessian_factor_form",
+    "onecomp_quantize_layer_form",
     "onecomp_factor_workspace_bytes",
     "onecomp_quantize_workspace_bytes",
     "onecomp_crossgram_accumulate",
@@ -62,6 +66,11 @@ def load_library() -> ctypes.CDLL:
     lib.onecomp_hessian_accumulate.restype = i32
     lib.onecomp_hessian_factor.argtypes = [vp, i64, f32, i32, vp, vp, vp, vp, sz, vp]
     lib.onecomp_hessian_factor.restype = i32
+    lib.onecomp_hessian_factor_form.argtypes = [vp, i64, f32, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.onecomp_hessian_factor_form.restype = i32
+    lib.onecomp_quantize_layer_form.argtypes = [vp, i32, i64, i64, vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp,
+                                                vp, sz, vp]
+    lib.onecomp_quantize_layer_form.restype = i32
     lib.onecomp_quantize_layer.argtypes = [vp, i32, i64, i64, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.onecomp_quantize_layer.restype = i32
     lib.onecomp_quantize_layer_grid.argtypes = [vp, i32, i64, i64, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz,
@@ -148,9 +157,11 @@ def onecomp_hessian_accumulate(X: torch.Tensor, H: torch.Tensor) -> None:
 
 def onecomp_hessian_factor(H: torch.Tensor, damp: float, act_order: bool = False,
                            U: Optional[torch.Tensor] = None, perm_out: Optional[torch.Tensor] = None,
-                           info: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None
-                           ) -> Tuple[torch.Tensor, Optional[torch.Tensor], torch.Tensor]:
-    """Returns (U, perm, info) as device tensors; perm is None when act_order is False and no perm_out was given."""
+                           info: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                           form: str = "inverse") -> Tuple[torch.Tensor, Optional[torch.Tensor], torch.Tensor]:
+    """Returns (U, perm, info) as device tensors; perm is None when act_order is False and no perm_out was given.
+    form = "inverse" calls onecomp_hessian_factor, "block" onecomp_hessian_factor_form with ONECOMP_FACTOR_BLOCK
+    (the matrix returned is then meant for onecomp_quantize_layer(..., form="block") only)."""
     lib = load_library()
     d = H.shape[0]
     if U is None:
@@ -162,9 +173,15 @@ def onecomp_hessian_factor(H: torch.Tensor, damp: float, act_order: bool = False
     need = onecomp_factor_workspace_bytes(d)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=H.device)
-    rc = lib.onecomp_hessian_factor(_dev(H, "H", torch.float32), d, float(damp), int(bool(act_order)),
-                                    _ptr(perm_out), _dev(U, "U", torch.float32), _dev(info, "info", torch.int32),
-                                    _dev(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    tail = (_ptr(perm_out), _dev(U, "U", torch.float32), _dev(info, "info", torch.int32),
+            _dev(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    if form == "inverse":
+        rc = lib.onecomp_hessian_factor(_dev(H, "H", torch.float32), d, float(damp), int(bool(act_order)), *tail)
+    elif form == "block":
+        rc = lib.onecomp_hessian_factor_form(_dev(H, "H", torch.float32), d, float(damp), int(bool(act_order)),
+                                             ONECOMP_FACTOR_BLOCK, *tail)
+    else:
+        raise ValueError("form must be 'inverse' or 'block'")
     if rc != ONECOMP_OK:
         raise OnecompError(rc, "onecomp_hessian_factor")
     return U, perm_out, info
@@ -173,9 +190,10 @@ def onecomp_hessian_factor(H: torch.Tensor, damp: float, act_order: bool = False
 def onecomp_quantize_layer(W: torch.Tensor, U: torch.Tensor, bits: int, group_size: int,
                            perm: Optional[torch.Tensor] = None, block_size: int = 128, want_w_hat: bool = True,
                            workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None,
-                           grid: str = "minmax") -> dict:
+                           grid: str = "minmax", form: str = "inverse") -> dict:
     """Returns dict(Q_codes uint8, scales, zeros, W_hat (or None), loss) of device tensors.
-    grid = "minmax" calls onecomp_quantize_layer, "symmetric" onecomp_quantize_layer_grid with that grid."""
+    grid = "minmax" calls onecomp_quantize_layer, "symmetric" onecomp_quantize_layer_grid with that grid;
+    form = "block" (U from onecomp_hessian_factor(..., form="block")) calls onecomp_quantize_layer_form."""
     lib = load_library()
     d_out, d_in = W.shape
     dev = W.device
@@ -198,12 +216,18 @@ def onecomp_quantize_layer(W: torch.Tensor, U: torch.Tensor, bits: int, group_si
     tail = (_dev(out["Q_codes"], "Q_codes", torch.uint8), _dev(out["scales"], "scales", torch.float32),
             _dev(out["zeros"], "zeros", torch.float32), _ptr(out["W_hat"]), _dev(out["loss"], "loss", torch.float32),
             _dev(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
-    if grid == "minmax":
-        rc = lib.onecomp_quantize_layer(*head, *tail)
-    elif grid == "symmetric":
-        rc = lib.onecomp_quantize_layer_grid(*head, ONECOMP_GRID_SYMMETRIC, *tail)
-    else:
+    if grid not in ("minmax", "symmetric"):
         raise ValueError("grid must be 'minmax' or 'symmetric'")
+    if form == "block":
+        rc = lib.onecomp_quantize_layer_form(*head[:5], ONECOMP_FACTOR_BLOCK, *head[5:],
+                                             ONECOMP_GRID_SYMMETRIC if grid == "symmetric" else ONECOMP_GRID_MINMAX,
+                                             *tail)
+    elif form != "inverse":
+        raise ValueError("form must be 'inverse' or 'block'")
+    elif grid == "minmax":
+        rc = lib.onecomp_quantize_layer(*head, *tail)
+    else:
+        rc = lib.onecomp_quantize_layer_grid(*head, ONECOMP_GRID_SYMMETRIC, *tail)
     if rc != ONECOMP_OK:
         raise OnecompError(rc, "onecomp_quantize_layer")
     return out

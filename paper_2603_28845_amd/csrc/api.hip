@@ -29,21 +29,58 @@ ONECOMP_API size_t onecomp_factor_workspace_bytes(int64_t d_in) {
     return factor_workspace_bytes(d_in);
 }
 
-ONECOMP_API onecomp_status onecomp_hessian_factor(const float* H, int64_t d_in, float damp, int act_order, int32_t* perm_out,
-                                      float* U, int32_t* info, void* workspace, size_t workspace_bytes,
-                                      void* hip_stream) {
-    if (!H || !U || !info || d_in <= 0) return ONECOMP_ERR_INVALID_ARG;
+ONECOMP_API onecomp_status onecomp_hessian_factor_form(const float* H, int64_t d_in, float damp, int act_order,
+                                                       onecomp_factor_form form, int32_t* perm_out, float* F_out,
+                                                       int32_t* info, void* workspace, size_t workspace_bytes,
+                                                       void* hip_stream) {
+    if (form != ONECOMP_FACTOR_INVERSE && form != ONECOMP_FACTOR_BLOCK) return ONECOMP_ERR_UNSUPPORTED;
+    if (!H || !F_out || !info || d_in <= 0) return ONECOMP_ERR_INVALID_ARG;
     if (d_in % 16 != 0 || d_in > 46336) return ONECOMP_ERR_INVALID_ARG;
+    if (form == ONECOMP_FACTOR_BLOCK && d_in % 128 != 0) return ONECOMP_ERR_UNSUPPORTED;
     if (!(damp >= 0.0f)) return ONECOMP_ERR_INVALID_ARG;
     if (act_order && !perm_out) return ONECOMP_ERR_INVALID_ARG;
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < factor_workspace_bytes(d_in))
         return ONECOMP_ERR_WORKSPACE;
-    return factor_run(H, d_in, damp, act_order, perm_out, U, info, workspace, static_cast<hipStream_t>(hip_stream));
+    return factor_run(H, d_in, damp, act_order, int(form), perm_out, F_out, info, workspace,
+                      static_cast<hipStream_t>(hip_stream));
+}
+
+ONECOMP_API onecomp_status onecomp_hessian_factor(const float* H, int64_t d_in, float damp, int act_order, int32_t* perm_out,
+                                      float* U, int32_t* info, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream) {
+    return onecomp_hessian_factor_form(H, d_in, damp, act_order, ONECOMP_FACTOR_INVERSE, perm_out, U, info, workspace,
+                                       workspace_bytes, hip_stream);
 }
 
 ONECOMP_API size_t onecomp_quantize_workspace_bytes(int64_t d_out, int64_t d_in, int block_size) {
     if (d_out <= 0 || d_in <= 0 || block_size != 128 || d_in % 128 != 0) return 0;
     return sweep_workspace_bytes(d_out, d_in, block_size);
+}
+
+ONECOMP_API onecomp_status onecomp_quantize_layer_form(const void* W, onecomp_dtype w_dtype, int64_t d_out,
+                                                       int64_t d_in, const float* F, onecomp_factor_form form,
+                                                       const int32_t* perm, int bits, int group_size, int block_size,
+                                                       onecomp_grid grid, uint8_t* Q_codes, float* scales,
+                                                       float* zeros, float* W_hat, float* loss, void* workspace,
+                                                       size_t workspace_bytes, void* hip_stream) {
+    const float* U = F;
+    if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
+    if (grid != ONECOMP_GRID_MINMAX && grid != ONECOMP_GRID_SYMMETRIC) return ONECOMP_ERR_UNSUPPORTED;
+    if (form != ONECOMP_FACTOR_INVERSE && form != ONECOMP_FACTOR_BLOCK) return ONECOMP_ERR_UNSUPPORTED;
+    if (!W || !U || !Q_codes || !scales || !zeros || !loss) return ONECOMP_ERR_INVALID_ARG;
+    if (d_out <= 0 || d_in <= 0 || d_out > (1 << 24) || d_in > 65535) return ONECOMP_ERR_INVALID_ARG;
+    if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return ONECOMP_ERR_UNSUPPORTED;
+    if (block_size != 128) return ONECOMP_ERR_UNSUPPORTED;
+    if (group_size <= 0 || d_in % block_size != 0 || d_in % group_size != 0) return ONECOMP_ERR_INVALID_ARG;
+    if (group_size % 16 != 0) return ONECOMP_ERR_UNSUPPORTED;
+    if (block_size % group_size != 0 && group_size % block_size != 0) return ONECOMP_ERR_INVALID_ARG;
+    if (form == ONECOMP_FACTOR_BLOCK && group_size > block_size) return ONECOMP_ERR_UNSUPPORTED;
+    if (!aligned(W, 16) || !aligned(U, 16) || !aligned(Q_codes, 4) || (W_hat && !aligned(W_hat, 16)))
+        return ONECOMP_ERR_INVALID_ARG;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < sweep_workspace_bytes(d_out, d_in, block_size))
+        return ONECOMP_ERR_WORKSPACE;
+    return sweep_run(W, w_dtype, d_out, d_in, U, int(form), perm, bits, group_size, block_size, int(grid), Q_codes,
+                     scales, zeros, W_hat, loss, workspace, static_cast<hipStream_t>(hip_stream));
 }
 
 ONECOMP_API onecomp_status onecomp_quantize_layer_grid(const void* W, onecomp_dtype w_dtype, int64_t d_out,
@@ -52,21 +89,9 @@ ONECOMP_API onecomp_status onecomp_quantize_layer_grid(const void* W, onecomp_dt
                                                        uint8_t* Q_codes, float* scales, float* zeros, float* W_hat,
                                                        float* loss, void* workspace, size_t workspace_bytes,
                                                        void* hip_stream) {
-    if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
-    if (grid != ONECOMP_GRID_MINMAX && grid != ONECOMP_GRID_SYMMETRIC) return ONECOMP_ERR_UNSUPPORTED;
-    if (!W || !U || !Q_codes || !scales || !zeros || !loss) return ONECOMP_ERR_INVALID_ARG;
-    if (d_out <= 0 || d_in <= 0 || d_out > (1 << 24) || d_in > 65535) return ONECOMP_ERR_INVALID_ARG;
-    if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return ONECOMP_ERR_UNSUPPORTED;
-    if (block_size != 128) return ONECOMP_ERR_UNSUPPORTED;
-    if (group_size <= 0 || d_in % block_size != 0 || d_in % group_size != 0) return ONECOMP_ERR_INVALID_ARG;
-    if (group_size % 16 != 0) return ONECOMP_ERR_UNSUPPORTED;
-    if (block_size % group_size != 0 && group_size % block_size != 0) return ONECOMP_ERR_INVALID_ARG;
-    if (!aligned(W, 16) || !aligned(U, 16) || !aligned(Q_codes, 4) || (W_hat && !aligned(W_hat, 16)))
-        return ONECOMP_ERR_INVALID_ARG;
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < sweep_workspace_bytes(d_out, d_in, block_size))
-        return ONECOMP_ERR_WORKSPACE;
-    return sweep_run(W, w_dtype, d_out, d_in, U, perm, bits, group_size, block_size, int(grid), Q_codes, scales, zeros,
-                     W_hat, loss, workspace, static_cast<hipStream_t>(hip_stream));
+    return onecomp_quantize_layer_form(W, w_dtype, d_out, d_in, U, ONECOMP_FACTOR_INVERSE, perm, bits, group_size,
+                                       block_size, grid, Q_codes, scales, zeros, W_hat, loss, workspace, workspace_bytes,
+                                       hip_stream);
 }
 
 ONECOMP_API onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,

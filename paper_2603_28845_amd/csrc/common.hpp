@@ -52,12 +52,12 @@ onecomp_status gram_cross_accumulate_bf16(const void* Xh, const void* X, int64_t
                                           int64_t ldx, float* G, hipStream_t stream);
 
 size_t factor_workspace_bytes(int64_t d_in);
-onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_order, int32_t* perm_out,
+onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_order, int form, int32_t* perm_out,
                           float* U, int32_t* info, void* workspace, hipStream_t stream);
 
 size_t sweep_workspace_bytes(int64_t d_out, int64_t d_in, int block);
 onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
-                         const float* U, const int32_t* perm, int bits, int group_size, int block, int grid,
+                         const float* U, int form, const int32_t* perm, int bits, int group_size, int block, int grid,
                          uint8_t* Q, float* scales, float* zeros, float* W_hat, float* loss,
                          void* workspace, hipStream_t stream);
 

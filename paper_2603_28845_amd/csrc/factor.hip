@@ -95,6 +95,30 @@ __global__ __launch_bounds__(256) void output_kernel(const double* __restrict__ 
     U[int64_t(i) * n + k] = u;
 }
 
+// Block form (no triangular inverse of the whole factor).  With R = U^-1, i.e. R[i][k] = L[n-1-i][n-1-k] and
+// Hd = R R^T:  F = U on the NB x NB diagonal blocks (the index-reversed inverses of the diagonal blocks of L, which
+// the factorization leaves in V);  F[i][k] = -U_ii R_ik / R_kk where i and k lie in different blocks.
+// rdiag[r] = 1 / L[r][r] = V[r][r].
+__global__ __launch_bounds__(256) void rdiag_kernel(const double* __restrict__ V, int n, double* __restrict__ rdiag) {
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r < n) rdiag[r] = V[int64_t(r) * n + r];
+}
+
+__global__ __launch_bounds__(256) void output_block_kernel(const double* __restrict__ L, const double* __restrict__ V,
+                                                          const double* __restrict__ rdiag, int n,
+                                                          float* __restrict__ F) {
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.y;
+    if (k >= n) return;
+    float f = 0.f;
+    if (k >= i) {
+        const int ri = n - 1 - i, rk = n - 1 - k;   // ri >= rk
+        if (ri / NB == rk / NB) f = float(V[int64_t(ri) * n + rk]);
+        else f = float(-(rdiag[ri] * rdiag[rk]) * L[int64_t(ri) * n + rk]);
+    }
+    F[int64_t(i) * n + k] = f;
+}
+
 // ------------------------------------------------------------------------------------------
 // diagonal block: Cholesky in LDS, then in-place triangular inverse.  One workgroup of 256 threads (4 waves).
 // A block (bs x bs, bs <= 128) at A + off*(n+1); L written back to A (lower part), L^-1 to V (full block,
@@ -620,8 +644,8 @@ size_t factor_workspace_bytes(int64_t n) {
            2 * align_up(size_t(n) * sizeof(float), 256);
 }
 
-onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_order, int32_t* perm_out, float* U,
-                          int32_t* info, void* workspace, hipStream_t stream) {
+onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_order, int form, int32_t* perm_out,
+                          float* U, int32_t* info, void* workspace, hipStream_t stream) {
     const int n = int(d_in);
     Workspace w = carve(workspace, n);
     onecomp_status st;
@@ -668,6 +692,15 @@ onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_orde
                                info);
             ONECOMP_CHECK_LAUNCH();
         }
+    }
+
+    if (form == ONECOMP_FACTOR_BLOCK) {   // diagonal blocks of L^-1 are in V already; the rest comes from L itself
+        hipLaunchKernelGGL(rdiag_kernel, dim3(unsigned(ceil_div(n, 256))), dim3(256), 0, stream, w.V, n, w.dfix);
+        ONECOMP_CHECK_LAUNCH();
+        hipLaunchKernelGGL(output_block_kernel, dim3(unsigned(ceil_div(n, 256)), unsigned(n)), dim3(256), 0, stream, w.A,
+                           w.V, w.dfix, n, U);
+        ONECOMP_CHECK_LAUNCH();
+        return ONECOMP_OK;
     }
 
     // ---- V = L^-1 by recursive doubling over aligned block pairs ----

@@ -87,14 +87,16 @@ __device__ inline void block_max_to(uint32_t* dst, float v) {
 template <typename T>
 __global__ __launch_bounds__(256) void load_kernel(const T* __restrict__ W, int64_t d_out, int64_t d_in,
                                                   const int32_t* __restrict__ perm, float* __restrict__ Wf,
-                                                  float* __restrict__ rowloss, Scalars* __restrict__ sc) {
+                                                  float* __restrict__ rowloss, Scalars* __restrict__ sc,
+                                                  const int zero_fill) {
+    // zero_fill: the working copy starts as zeros (it then holds only the feedback, the weights are read from W)
     float m = 0.f;
     for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {   // a workgroup per row, rows strided over the grid
     if (threadIdx.x == 0) rowloss[r] = 0.f;
     if (perm) {
         for (int p = threadIdx.x; p < d_in; p += 256) {
             const float v = to_f32<T>(W[r * d_in + perm[p]]);
-            Wf[r * d_in + p] = v;
+            Wf[r * d_in + p] = zero_fill ? 0.f : v;
             m = fmaxf(m, fabsf(v));
         }
     } else {   // rows are 16-byte aligned: d_in is a multiple of 128
@@ -114,7 +116,8 @@ __global__ __launch_bounds__(256) void load_kernel(const T* __restrict__ W, int6
             }
 #pragma unroll
             for (int e = 0; e < V; e += 4) {
-                const float4v o = {v[e], v[e + 1], v[e + 2], v[e + 3]};
+                float4v o = {v[e], v[e + 1], v[e + 2], v[e + 3]};
+                if (zero_fill) o = float4v{0.f, 0.f, 0.f, 0.f};
                 *reinterpret_cast<float4v*>(Wf + r * d_in + p + e) = o;
             }
 #pragma unroll
@@ -378,7 +381,9 @@ constexpr size_t BLOCK_LDS = (size_t(SB) * SB + SB + 2 * size_t(ROWS) * SP) * si
 // ------------------------------------------------------------------------------------------
 struct PanelArgs {
     const float* Wf;            // [d_out x d_in] working copy (columns beyond the super-block are current up to the
-                                // previous super-block)
+                                // previous super-block); block form: only the accumulated feedback c
+    const void* W0;             // block form: the layer's weights as passed in (original column order)
+    int w0_bf16;
     const float* U;
     const int32_t* perm;
     uint8_t* Q;
@@ -405,7 +410,21 @@ constexpr int quad_bcast(int o) { return o | (o << 2) | (o << 4) | (o << 6); }
 constexpr int QUAD_SWAP1 = 1 | (0 << 2) | (3 << 4) | (2 << 6);   // lanes 0<->1, 2<->3
 constexpr int QUAD_SWAP2 = 2 | (3 << 2) | (0 << 4) | (1 << 6);   // lanes 0<->2, 1<->3
 
-template <int GB>  // group width seen inside an inner block: 16 (G == 16) or 32 (G = 32, 64, 128)
+// weight of sweep position p in row `row`, from the caller's matrix
+__device__ __forceinline__ float w0_at(const PanelArgs& a, const int64_t row, const int p) {
+    const int64_t idx = row * a.d_in + (a.perm ? a.perm[p] : p);
+    return a.w0_bf16 ? __uint_as_float(uint32_t(static_cast<const uint16_t*>(a.W0)[idx]) << 16)
+                     : static_cast<const float*>(a.W0)[idx];
+}
+
+// DIRECT (block form of the factor): a.U holds U only on its 128 x 128 diagonal blocks and -U_jj R_jk / R_kk
+// elsewhere (R = U^-1).  The working copy then accumulates c_k = sum_i (w_i - w^_i) R_ik / R_kk over the finished
+// columns i of earlier blocks, where w are the ORIGINAL weights; a block starts from
+//   w_b + c Un_bb ,   Un_bb = rows of U_bb divided by their diagonal entries,
+// which is the state the sweep with the full U has on entering the block (e = (w - w^) R and
+// U_AB = -U_AA R_AB U_BB for finished columns A, remaining columns B).  Inside the block nothing changes; what the
+// block passes on is w - w^ measured from the original weights instead of the compensated ones.
+template <int GB, bool DIRECT>  // GB: group width seen inside an inner block: 16 (G == 16) or 32 (G = 32, 64, 128)
 __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, char* psm) {
     float* sU = reinterpret_cast<float*>(psm);   // SB x SB: U[j0 + j][j0 .. j0 + 127], filled by direct loads
     float* sW = sU + SB * SB;                    // ROWS x SP
@@ -501,16 +520,53 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[mt][r] *= f_inv;
             }
+            if constexpr (!DIRECT) {
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+                for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    sW[(mt * 32 + (r / 4) * 8 + lr + (r % 4)) * SP + 32 * wave + lc] = acc[mt][r];
+                    for (int r = 0; r < 16; ++r)
+                        sW[(mt * 32 + (r / 4) * 8 + lr + (r % 4)) * SP + 32 * wave + lc] = acc[mt][r];
+            }
+            __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // the direct loads into sU have landed
+            __syncthreads();
+            if (tid < SB) sRd[tid] = 1.0f / sU[tid * SB + tid];
+            __syncthreads();
+            if constexpr (DIRECT) {
+                // c_k / U_kk -> sE (free until the sweep writes its errors), as the A operand of c Un_bb = (c / diag) U_bb
+                if (j0 > 0) {
+                    const float rd = sRd[32 * wave + lc];
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            sE[(mt * 32 + (r / 4) * 8 + lr + (r % 4)) * SP + 32 * wave + lc] = acc[mt][r] * rd;
+                    __syncthreads();
+                }
+                // eight 32 x 32 tiles of w_b + (c / diag) U_bb; column tile nt needs k < 32 (nt + 1) (U_bb is upper
+                // triangular), so wave w takes (row tile 0, column tile w) and (1, 3 - w): 80 MFMAs each
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    const int nt = mt == 0 ? wave : 3 - wave;
+                    float16v c;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int rr = min(r0 + mt * 32 + (r / 4) * 8 + lr + (r % 4), a.d_out - 1);
+                        c[r] = w0_at(a, rr, j0 + nt * 32 + lc);
+                    }
+                    if (j0 > 0) {
+                        const float* ap = sE + (mt * 32 + lc) * SP + (lane >> 5);
+                        const float* bp = sU + (lane >> 5) * SB + nt * 32 + lc;
+                        const int n_k = 16 * (nt + 1);
+#pragma unroll 4
+                        for (int kk = 0; kk < n_k; ++kk)
+                            c = __builtin_amdgcn_mfma_f32_32x32x2f32(ap[2 * kk], bp[2 * kk * SB], c, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sW[(mt * 32 + (r / 4) * 8 + lr + (r % 4)) * SP + nt * 32 + lc] = c[r];
+                }
+                __syncthreads();
+            }
         }
-        __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // the direct loads into sU have landed
-        __syncthreads();
-        if (tid < SB) sRd[tid] = 1.0f / sU[tid * SB + tid];
-        __syncthreads();
 
 #pragma unroll 1
         for (int jb = 0; jb < SB; jb += IB) {
@@ -647,12 +703,27 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                 dl[e] = __builtin_bit_cast(short, lo);
             }
         };
+        float* sO = sU;   // DIRECT: w - w^ against the original weights, ROWS x SP (the U block is no longer needed)
+        if constexpr (DIRECT) {
+            for (int it = wave; it < ROWS / 2; it += 4) {
+                const int rr = it * 2 + (lane >> 5), c4 = (lane & 31) * 4;
+                const int gr = min(r0 + rr, a.d_out - 1);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int gi = (c4 + e) >> a.lgG;
+                    const float wh = sS[rr * 8 + gi] * (sW[rr * SP + c4 + e] - sZ[rr * 8 + gi]);
+                    sO[rr * SP + c4 + e] = w0_at(a, gr, j0 + c4 + e) - wh;
+                }
+            }
+            __syncthreads();
+        }
         // transposed panel (k-major) for the far update; rows past d_out hold copies of the last row
         for (int it = tid; it < SB * (ROWS / 8); it += 256) {
             const int c = it / (ROWS / 8), r8 = (it % (ROWS / 8)) * 8;
-            const float ujj = sU[c * SB + c] * f_d;
+            const float ujj = DIRECT ? 0.f : sU[c * SB + c] * f_d;
             short8v dh, dl;
-            split8([&](int e) { return -sE[(r8 + e) * SP + c] * ujj; }, dh, dl);
+            if constexpr (DIRECT) split8([&](int e) { return -sO[(r8 + e) * SP + c] * f_d; }, dh, dl);
+            else split8([&](int e) { return -sE[(r8 + e) * SP + c] * ujj; }, dh, dl);
             const int64_t off = int64_t(b * SB + c) * a.ldD + r0 + r8;
             *reinterpret_cast<short8v*>(a.Dh + off) = dh;
             *reinterpret_cast<short8v*>(a.Dl + off) = dl;
@@ -664,7 +735,8 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
             for (int it = tid; it < 8 * 2 * 64; it += 256) {
                 const int L = it & 63, row = ((it >> 6) & 1) * 32 + (L & 31), c0 = (it >> 7) * 16 + 8 * (L >> 5);
                 short8v dh, dl;
-                split8([&](int e) { return -sE[row * SP + c0 + e] * (sU[(c0 + e) * SB + c0 + e] * f_d); }, dh, dl);
+                if constexpr (DIRECT) split8([&](int e) { return -sO[row * SP + c0 + e] * f_d; }, dh, dl);
+                else split8([&](int e) { return -sE[row * SP + c0 + e] * (sU[(c0 + e) * SB + c0 + e] * f_d); }, dh, dl);
                 const int64_t off = ((int64_t(wg) * 3 + b) * (8 * 2 * 64) + it) * 8;
                 *reinterpret_cast<short8v*>(a.Fh + off) = dh;
                 *reinterpret_cast<short8v*>(a.Fl + off) = dl;
@@ -1032,10 +1104,10 @@ __global__ __launch_bounds__(256, 2) void trailing_kernel(TrailArgs a) {
 // its workgroups are the first of the grid, so they are resident from the start; the update's tiles fill the other
 // CUs, and all of them once the panel is done.  The two parts touch disjoint columns of the working copy, and the
 // panel writes the residual panels of its own super-block into the buffer the update does not read.
-template <int GB>
+template <int GB, bool DIRECT>
 __global__ __launch_bounds__(256) void panel_far_kernel(PanelArgs pa, TrailArgs ta, int n_panel) {
     extern __shared__ __attribute__((aligned(1024))) char dyn_lds[];
-    if (int(blockIdx.x) < n_panel) panel_body<GB>(pa, blockIdx.x, dyn_lds);
+    if (int(blockIdx.x) < n_panel) panel_body<GB, DIRECT>(pa, blockIdx.x, dyn_lds);
     else trailing_tile<3>(ta, blockIdx.x - n_panel, dyn_lds);
 }
 
@@ -1090,18 +1162,18 @@ SweepWs carve(void* ws, int64_t d_out, int64_t d_in) {
     return w;
 }
 
-template <int GB>
+template <int GB, bool DIRECT>
 onecomp_status launch_panel(const PanelArgs& pa, const TrailArgs& ta, int far_wgs, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&panel_far_kernel<GB>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&panel_far_kernel<GB, DIRECT>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, PANEL_LDS) != hipSuccess)
             return ONECOMP_ERR_HIP;
         attr_set = true;
     }
     const int n_panel = int(ceil_div(pa.d_out, ROWS));
-    hipLaunchKernelGGL(panel_far_kernel<GB>, dim3(unsigned(n_panel + far_wgs)), dim3(256), PANEL_LDS, stream, pa, ta,
-                       n_panel);
+    hipLaunchKernelGGL((panel_far_kernel<GB, DIRECT>), dim3(unsigned(n_panel + far_wgs)), dim3(256), PANEL_LDS, stream,
+                       pa, ta, n_panel);
     ONECOMP_CHECK_LAUNCH();
     return ONECOMP_OK;
 }
@@ -1131,19 +1203,21 @@ size_t sweep_workspace_bytes(int64_t d_out, int64_t d_in, int block) {
 }
 
 onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* U,
-                         const int32_t* perm, int bits, int group_size, int block, int grid, uint8_t* Q, float* scales,
-                         float* zeros, float* W_hat, float* loss, void* workspace, hipStream_t stream) {
+                         int form, const int32_t* perm, int bits, int group_size, int block, int grid, uint8_t* Q,
+                         float* scales, float* zeros, float* W_hat, float* loss, void* workspace, hipStream_t stream) {
     (void)block;
+    const bool direct = form == ONECOMP_FACTOR_BLOCK;   // block form of the factor: see panel_body
+    if (direct && group_size > SB) return ONECOMP_ERR_UNSUPPORTED;
     SweepWs w = carve(workspace, d_out, d_in);
     hipLaunchKernelGGL(init_scalars_kernel, dim3(1), dim3(1), 0, stream, w.sc);
     ONECOMP_CHECK_LAUNCH();
     dim3 lgrid{unsigned(d_out < 1024 ? d_out : 1024)};
     if (w_dtype == ONECOMP_BF16)
         hipLaunchKernelGGL(load_kernel<uint16_t>, lgrid, dim3(256), 0, stream, static_cast<const uint16_t*>(W), d_out,
-                           d_in, perm, w.Wf, w.rowloss, w.sc);
+                           d_in, perm, w.Wf, w.rowloss, w.sc, int(direct));
     else
         hipLaunchKernelGGL(load_kernel<float>, lgrid, dim3(256), 0, stream, static_cast<const float*>(W), d_out, d_in,
-                           perm, w.Wf, w.rowloss, w.sc);
+                           perm, w.Wf, w.rowloss, w.sc, int(direct));
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(umax_kernel, dim3(unsigned(d_in < 1024 ? d_in : 1024)), dim3(256), 0, stream, U,
                        int(d_in), w.sc);
@@ -1195,7 +1269,7 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
                            w.sc, w.Bh, w.Bl);
         ONECOMP_CHECK_LAUNCH();
         PanelArgs pa;
-        pa.Wf = w.Wf; pa.U = U; pa.perm = perm; pa.Q = Q; pa.scales = scales; pa.zeros = zeros; pa.W_hat = W_hat;
+        pa.Wf = w.Wf; pa.W0 = W; pa.w0_bf16 = w_dtype == ONECOMP_BF16; pa.U = U; pa.perm = perm; pa.Q = Q; pa.scales = scales; pa.zeros = zeros; pa.W_hat = W_hat;
         pa.Fh = w.Fh; pa.Fl = w.Fl; pa.sc = w.sc; pa.rowloss = w.rowloss;
         pa.d_out = int(d_out); pa.d_in = int(d_in); pa.n_g = int(d_in / group_size); pa.ldD = int(ld_d(d_out));
         pa.lgG = 0;
@@ -1214,8 +1288,8 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
             pa.Dh = w.Dh + buf * d_buf; pa.Dl = w.Dl + buf * d_buf;
             pa.Bh = w.Bh + size_t(s0 / SBIG) * (B_PER_SB / 2);
             pa.Bl = w.Bl + size_t(s0 / SBIG) * (B_PER_SB / 2);
-            if (group_size == 16) st = launch_panel<16>(pa, t, far_wgs, stream);
-            else st = launch_panel<32>(pa, t, far_wgs, stream);
+            if (group_size == 16) st = direct ? launch_panel<16, true>(pa, t, far_wgs, stream) : launch_panel<16, false>(pa, t, far_wgs, stream);
+            else st = direct ? launch_panel<32, true>(pa, t, far_wgs, stream) : launch_panel<32, false>(pa, t, far_wgs, stream);
             if (st != ONECOMP_OK) return st;
             buf ^= 1; p0 = s0; p1 = s1;
         }

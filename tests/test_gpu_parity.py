@@ -40,9 +40,13 @@ def _gpu_gram(X, chunks=1):
     return H
 
 
-def _check_sweep(W, U32, bits, G, perm=None, rows=None, min_agree=0.999, grid="minmax"):
-    """W: torch tensor on GPU (original order), U32: torch fp32 on GPU."""
-    out = og.onecomp_quantize_layer(W, U32, bits, G, perm=perm, grid=grid)
+def _check_sweep(W, U32, bits, G, perm=None, rows=None, min_agree=0.999, grid="minmax", F32=None):
+    """W: torch tensor on GPU (original order), U32: torch fp32 on GPU: the inverse factor the oracle sweeps with.
+    F32: block form of the same factor; when given, the GPU sweeps with it instead of U32."""
+    if F32 is None:
+        out = og.onecomp_quantize_layer(W, U32, bits, G, perm=perm, grid=grid)
+    else:
+        out = og.onecomp_quantize_layer(W, F32, bits, G, perm=perm, grid=grid, form="block")
     torch.cuda.synchronize()
     Q = out["Q_codes"].cpu().numpy()
     S = out["scales"].cpu().numpy()
@@ -221,6 +225,51 @@ def test_factor_dead_channel_and_not_posdef():
     assert oc.hessian_factor(-np.eye(256), 0.0)["info"] > 0
 
 
+def _oracle_block_factor(f):
+    """Block form (128-column blocks) of the oracle's factor f = oc.hessian_factor(...), in float64."""
+    p = f["perm"]
+    R, info = oc.direct_factor(f["Hd"][np.ix_(p, p)])
+    assert info == 0
+    return oc.block_feedback_factor(f["U"], R, 128)
+
+
+@pytest.mark.parametrize("d_in,act", [(128, False), (384, True), (1024, False), (1152, True), (2048, False)])
+def test_block_factor_against_oracle(d_in, act):
+    _announce(f"factor, block form, d_in={d_in} act_order={act}")
+    H32 = _oracle_H32(d_in, 3 * d_in + 7, seed=13)
+    f = oc.hessian_factor(H32.astype(np.float64), 0.01, act_order=act)
+    Fo = _oracle_block_factor(f)
+    F, perm, info = og.onecomp_hessian_factor(torch.from_numpy(H32).to(DEV), 0.01, act_order=act, form="block")
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0
+    Fn = F.cpu().numpy().astype(np.float64)
+    if act:
+        np.testing.assert_array_equal(perm.cpu().numpy(), f["perm"])
+    assert np.all(np.tril(Fn, -1) == 0.0) and np.all(np.diag(Fn) > 0.0)
+    assert rel_fro(Fn, Fo) <= 1e-6
+    # the diagonal blocks are those of the inverse factor, bit for bit what the inverse form returns
+    U, _, _ = og.onecomp_hessian_factor(torch.from_numpy(H32).to(DEV), 0.01, act_order=act)
+    torch.cuda.synchronize()
+    for b0 in range(0, d_in, 128):
+        assert torch.equal(F[b0:b0 + 128, b0:b0 + 128], U[b0:b0 + 128, b0:b0 + 128])
+    # outside them the largest entry-wise deviation stays at fp32 rounding of the entry
+    off = np.abs(Fn - Fo)
+    assert off.max() <= 2e-7 * np.abs(Fo).max()
+
+
+def test_block_form_argument_checks():
+    _announce("block form: rejected arguments")
+    H = torch.eye(144, dtype=torch.float32, device=DEV)
+    with pytest.raises(og.OnecompError) as ei:
+        og.onecomp_hessian_factor(H, 0.01, form="block")          # d_in not a multiple of 128
+    assert ei.value.code == 2
+    W = torch.zeros((4, 512), dtype=torch.float32, device=DEV)
+    F = torch.eye(512, dtype=torch.float32, device=DEV)
+    with pytest.raises(og.OnecompError) as ei:
+        og.onecomp_quantize_layer(W, F, 4, 256, form="block")     # group wider than a block
+    assert ei.value.code == 2
+
+
 # ----------------------------------------------------------------------------------- sweep ---
 def _layer(d_out, d_in, n_tok, seed, dtype=torch.float32, act=False):
     cfg = synth.scaled(synth.CONFIGS["c2"], d_out=d_out, d_in=d_in, n_tokens=n_tok, seed=seed, dtype=dtype,
@@ -269,6 +318,58 @@ def test_sweep_variants(bits, G, d_out, d_in, dtype, act):
     _announce(f"sweep b{bits} g{G} {d_out}x{d_in} {dtype} act={act}")
     W, U32, perm = _layer(d_out, d_in, 2 * d_in + 13, seed=20 + bits + G, dtype=dtype, act=act)
     _check_sweep(W, U32, bits, G, perm=perm)
+
+
+def _layer_block(d_out, d_in, n_tok, seed, dtype=torch.float32, act=False):
+    """As _layer, plus the block form of the factor (from the oracle, rounded to fp32)."""
+    cfg = synth.scaled(synth.CONFIGS["c2"], d_out=d_out, d_in=d_in, n_tokens=n_tok, seed=seed, dtype=dtype,
+                       n_outlier=max(1, d_in // 100))
+    W = synth.make_weight(cfg, DEV)
+    X = synth.make_activations(cfg, "cpu")
+    f = oc.hessian_factor(oc.hessian_accumulate(to_f64(X)), 0.01, act_order=act)
+    U32 = torch.from_numpy(f["U"].astype(np.float32)).to(DEV)
+    F32 = torch.from_numpy(_oracle_block_factor(f).astype(np.float32)).to(DEV)
+    perm = torch.from_numpy(f["perm"].astype(np.int32)).to(DEV) if act else None
+    return W, U32, F32, perm
+
+
+@pytest.mark.parametrize("bits,G,d_out,d_in,dtype,act,grid", [
+    (4, 128, 256, 512, torch.float32, False, "minmax"),
+    (4, 128, 300, 1024, torch.bfloat16, True, "minmax"),
+    (3, 64, 7, 256, torch.float32, True, "minmax"),
+    (2, 64, 100, 384, torch.bfloat16, True, "minmax"),
+    (4, 16, 33, 256, torch.bfloat16, False, "minmax"),
+    (4, 32, 65, 128, torch.float32, True, "minmax"),              # a single block: nothing crosses a block
+    (4, 64, 130, 1664, torch.bfloat16, True, "minmax"),           # several super-blocks, the last one partial
+    (8, 128, 64, 640, torch.float32, False, "minmax"),
+    (2, 32, 100, 1152, torch.bfloat16, True, "minmax"),
+    (4, 128, 100, 1024, torch.bfloat16, False, "symmetric"),
+    (3, 64, 33, 640, torch.float32, True, "symmetric"),
+])
+def test_sweep_block_form(bits, G, d_out, d_in, dtype, act, grid):
+    """The sweep fed with the block form of the factor against the oracle's sweep with the inverse factor."""
+    _announce(f"sweep, block form, b{bits} g{G} {d_out}x{d_in} {dtype} act={act} {grid}")
+    W, U32, F32, perm = _layer_block(d_out, d_in, 2 * d_in + 13, seed=80 + bits + G % 5, dtype=dtype, act=act)
+    out, _ = _check_sweep(W, U32, bits, G, perm=perm, grid=grid, F32=F32)
+    out2 = og.onecomp_quantize_layer(W, F32, bits, G, perm=perm, grid=grid, form="block")
+    torch.cuda.synchronize()
+    for k in ("Q_codes", "scales", "zeros", "W_hat", "loss"):
+        assert torch.equal(out[k], out2[k])
+
+
+def test_end_to_end_block_form():
+    """Gram, factor in block form and sweep on the GPU against the oracle's path with the inverse factor."""
+    cfg = synth.scaled(synth.CONFIGS["c2"], d_out=200, d_in=1536, n_tokens=4096, seed=5)
+    _announce("end to end, block form, 200x1536 bf16 b4 g128")
+    W = synth.make_weight(cfg, DEV)
+    X = synth.make_activations(cfg, DEV)
+    H = _gpu_gram(X)
+    F, _, info = og.onecomp_hessian_factor(H, cfg.damp, form="block")
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0
+    f = oc.hessian_factor(H.cpu().numpy().astype(np.float64), cfg.damp)
+    U32 = torch.from_numpy(f["U"].astype(np.float32)).to(DEV)
+    _check_sweep(W, U32, cfg.bits, cfg.group_size, F32=F)
 
 
 @pytest.mark.parametrize("bits,G,d_out,d_in,dtype,act", [
@@ -370,4 +471,18 @@ def test_full_size_down_projection_sampled():
     # of 48 rows one flipped row alone costs a few tenths of a percent of raw agreement: the raw bar is 99 % here,
     # the flips themselves are bounded, and agreement after replaying the flips must still be exact.
     _, st = _check_sweep(W, U32, cfg.bits, cfg.group_size, rows=rows, min_agree=0.99)
+    assert st["tie_flips"] <= 4
+    del U32
+    _announce("full size: factor in block form")
+    F, _, info = og.onecomp_hessian_factor(torch.from_numpy(H32).to(DEV), cfg.damp, form="block")
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0
+    Fo = _oracle_block_factor(f)
+    err = rel_fro(F.cpu().numpy().astype(np.float64), Fo)
+    _announce(f"   F rel. Frobenius error {err:.3e}")
+    assert err <= 1e-6
+    del Fo
+    _announce("full size: sweep with the block form, same rows")
+    U32 = torch.from_numpy(f["U"].astype(np.float32)).to(DEV)
+    _, st = _check_sweep(W, U32, cfg.bits, cfg.group_size, rows=rows, min_agree=0.99, F32=F)
     assert st["tie_flips"] <= 4
