@@ -244,7 +244,8 @@ def main():
 
     phase = args.phase
 
-    def step(record=None, only=None):
+    def step(record=None, only=None, form=None):
+        form = form or args.factor_form
         e = [ev() for _ in range(4)]
         if only in (None, "gram"):
             H.zero_()
@@ -255,11 +256,11 @@ def main():
         e[1].record()
         if only in (None, "factor"):
             og.onecomp_hessian_factor(H, cfg.damp, cfg.act_order, U=U, perm_out=perm, info=info, workspace=ws_f,
-                                      form=args.factor_form)
+                                      form=form)
         e[2].record()
         if only in (None, "sweep"):
             og.onecomp_quantize_layer(W, U, cfg.bits, cfg.group_size, perm=perm, workspace=ws_q, out=out,
-                                      form=args.factor_form)
+                                      form=form)
         e[3].record()
         if record is not None:
             record.append(e)
@@ -286,6 +287,30 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
     assert int(info.item()) == 0, "Hessian not positive definite"
+    loss_main = float(out["loss"].item())
+
+    # the same step with the factor in block form (one Cholesky, no triangular inverse), reported next to the headline
+    alt = None
+    if phase == "all" and args.factor_form == "inverse" and cfg.group_size <= 128 and d_in % 128 == 0:
+        for _ in range(args.warmup):
+            step(form="block")
+        torch.cuda.synchronize()
+        rec_b = []
+        t_b = time.perf_counter()
+        for _ in range(args.steps):
+            step(rec_b, form="block")
+        torch.cuda.synchronize()
+        wall_b = time.perf_counter() - t_b
+        ms_b = wall_b * 1e3 / args.steps
+        alt = {
+            "what": "same step through onecomp_hessian_factor_form / onecomp_quantize_layer_form with "
+                    "ONECOMP_FACTOR_BLOCK: one Cholesky instead of Cholesky + triangular inverse; same codes up to ties",
+            "ms_per_step": ms_b, "value": d_out * d_in / (ms_b * 1e-3),
+            "phases_ms": {"hessian_accumulate": sum(e[0].elapsed_time(e[1]) for e in rec_b) / len(rec_b),
+                          "hessian_factor": sum(e[1].elapsed_time(e[2]) for e in rec_b) / len(rec_b),
+                          "quantize_layer": sum(e[2].elapsed_time(e[3]) for e in rec_b) / len(rec_b)},
+            "loss": float(out["loss"].item()),
+        }
 
     tiny = 1e-6   # phases skipped by --phase read as ~0; keep the ratios finite
     acc_ms = max(tiny, sum(e[0].elapsed_time(e[1]) for e in rec) / len(rec))
@@ -343,9 +368,11 @@ def main():
         "layer_quantize_ms": fac_ms + swp_ms,
         "weights_per_sec_factor_plus_sweep": weights / ((fac_ms + swp_ms) * 1e-3),
         "weights_per_sec_sweep_only": weights / (swp_ms * 1e-3),
-        "loss": float(out["loss"].item()),
+        "loss": loss_main,
         "roofline": roofline, "roofline_sweep": roofline_sweep,
     }
+    if alt is not None:
+        res["block_form"] = alt
     if args.vendor_gemm and cfg.dtype == torch.bfloat16:
         e = [ev() for _ in range(2)]
         torch.matmul(X.t(), X)

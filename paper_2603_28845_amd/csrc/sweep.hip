@@ -410,13 +410,6 @@ constexpr int quad_bcast(int o) { return o | (o << 2) | (o << 4) | (o << 6); }
 constexpr int QUAD_SWAP1 = 1 | (0 << 2) | (3 << 4) | (2 << 6);   // lanes 0<->1, 2<->3
 constexpr int QUAD_SWAP2 = 2 | (3 << 2) | (0 << 4) | (1 << 6);   // lanes 0<->2, 1<->3
 
-// weight of sweep position p in row `row`, from the caller's matrix
-__device__ __forceinline__ float w0_at(const PanelArgs& a, const int64_t row, const int p) {
-    const int64_t idx = row * a.d_in + (a.perm ? a.perm[p] : p);
-    return a.w0_bf16 ? __uint_as_float(uint32_t(static_cast<const uint16_t*>(a.W0)[idx]) << 16)
-                     : static_cast<const float*>(a.W0)[idx];
-}
-
 // DIRECT (block form of the factor): a.U holds U only on its 128 x 128 diagonal blocks and -U_jj R_jk / R_kk
 // elsewhere (R = U^-1).  The working copy then accumulates c_k = sum_i (w_i - w^_i) R_ik / R_kk over the finished
 // columns i of earlier blocks, where w are the ORIGINAL weights; a block starts from
@@ -462,6 +455,36 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
             for (int q = 0; q < 16; ++q) {
                 const int row = 2 * (16 * wave + q) + (lane >> 5);
                 lds_load16(ldsU + (16 * wave + q) * 1024, uint32_t((int64_t(row) * d_in + (lane & 31) * 4) * 4), rsrc);
+            }
+        }
+        // DIRECT: the original weights of this wave's two 32 x 32 tiles (row tile 0, column tile wave) and
+        // (1, 3 - wave), in accumulator layout; requested here so that they arrive behind the near update, kept in
+        // registers until the block is done
+        float16v w0r[2];
+        if constexpr (DIRECT) {
+            // a lane's column is the same for all 16 rows of a tile: one look-up of the column order per tile, then
+            // 32 independent loads in straight-line code (one uniform branch on the element type around them)
+            int64_t off[2][16];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                const int p = j0 + (mt == 0 ? wave : 3 - wave) * 32 + lc;
+                const int oc = a.perm ? a.perm[p] : p;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    off[mt][r] = int64_t(min(r0 + mt * 32 + (r / 4) * 8 + lr + (r % 4), a.d_out - 1)) * d_in + oc;
+            }
+            if (a.w0_bf16) {
+                const uint16_t* wp = static_cast<const uint16_t*>(a.W0);
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) w0r[mt][r] = __uint_as_float(uint32_t(wp[off[mt][r]]) << 16);
+            } else {
+                const float* wp = static_cast<const float*>(a.W0);
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) w0r[mt][r] = wp[off[mt][r]];
             }
         }
         // ---- near update of this block's columns, wave = column tile
@@ -543,26 +566,36 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                     __syncthreads();
                 }
                 // eight 32 x 32 tiles of w_b + (c / diag) U_bb; column tile nt needs k < 32 (nt + 1) (U_bb is upper
-                // triangular), so wave w takes (row tile 0, column tile w) and (1, 3 - w): 80 MFMAs each
+                // triangular), so wave w takes (row tile 0, column tile w) and (1, 3 - w): five chunks of 32 k, 16
+                // MFMAs each.  A chunk's 32 operand values are read before its first MFMA, and the two tiles'
+                // chunks alternate so that one tile's LDS reads fall behind the other's MFMAs.
+                float16v c0 = w0r[0], c1 = w0r[1];
+                if (j0 > 0) {
+                    const int nt0 = wave, nt1 = 3 - wave;
+                    const float* ap0 = sE + lc * SP + (lane >> 5);
+                    const float* ap1 = sE + (32 + lc) * SP + (lane >> 5);
+                    const float* bp0 = sU + (lane >> 5) * SB + nt0 * 32 + lc;
+                    const float* bp1 = sU + (lane >> 5) * SB + nt1 * 32 + lc;
+                    auto chunk = [&](float16v& c, const float* ap, const float* bp, const int ch) __attribute__((always_inline)) {
+                        float av[16], bv[16];
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt) {
-                    const int nt = mt == 0 ? wave : 3 - wave;
-                    float16v c;
+                        for (int kk = 0; kk < 16; ++kk) {
+                            av[kk] = ap[32 * ch + 2 * kk];
+                            bv[kk] = bp[(32 * ch + 2 * kk) * SB];
+                        }
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int rr = min(r0 + mt * 32 + (r / 4) * 8 + lr + (r % 4), a.d_out - 1);
-                        c[r] = w0_at(a, rr, j0 + nt * 32 + lc);
+                        for (int kk = 0; kk < 16; ++kk) c = __builtin_amdgcn_mfma_f32_32x32x2f32(av[kk], bv[kk], c, 0, 0, 0);
+                    };
+#pragma unroll 1
+                    for (int ch = 0; ch < 4; ++ch) {
+                        if (ch <= nt0) chunk(c0, ap0, bp0, ch);
+                        if (ch <= nt1) chunk(c1, ap1, bp1, ch);
                     }
-                    if (j0 > 0) {
-                        const float* ap = sE + (mt * 32 + lc) * SP + (lane >> 5);
-                        const float* bp = sU + (lane >> 5) * SB + nt * 32 + lc;
-                        const int n_k = 16 * (nt + 1);
-#pragma unroll 4
-                        for (int kk = 0; kk < n_k; ++kk)
-                            c = __builtin_amdgcn_mfma_f32_32x32x2f32(ap[2 * kk], bp[2 * kk * SB], c, 0, 0, 0);
-                    }
+                }
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) sW[(mt * 32 + (r / 4) * 8 + lr + (r % 4)) * SP + nt * 32 + lc] = c[r];
+                for (int r = 0; r < 16; ++r) {
+                    sW[((r / 4) * 8 + lr + (r % 4)) * SP + wave * 32 + lc] = c0[r];
+                    sW[(32 + (r / 4) * 8 + lr + (r % 4)) * SP + (3 - wave) * 32 + lc] = c1[r];
                 }
                 __syncthreads();
             }
@@ -705,14 +738,14 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
         };
         float* sO = sU;   // DIRECT: w - w^ against the original weights, ROWS x SP (the U block is no longer needed)
         if constexpr (DIRECT) {
-            for (int it = wave; it < ROWS / 2; it += 4) {
-                const int rr = it * 2 + (lane >> 5), c4 = (lane & 31) * 4;
-                const int gr = min(r0 + rr, a.d_out - 1);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int gi = (c4 + e) >> a.lgG;
-                    const float wh = sS[rr * 8 + gi] * (sW[rr * SP + c4 + e] - sZ[rr * 8 + gi]);
-                    sO[rr * SP + c4 + e] = w0_at(a, gr, j0 + c4 + e) - wh;
+            for (int mt = 0; mt < 2; ++mt) {
+                const int col = (mt == 0 ? wave : 3 - wave) * 32 + lc, gi = col >> a.lgG;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int rr = mt * 32 + (r / 4) * 8 + lr + (r % 4);
+                    const float wh = sS[rr * 8 + gi] * (sW[rr * SP + col] - sZ[rr * 8 + gi]);
+                    sO[rr * SP + col] = w0r[mt][r] - wh;
                 }
             }
             __syncthreads();

@@ -165,6 +165,46 @@ def test_quantize_grid_argument_checks(lib):
     assert f(P, 1, 64, 256, P, NULL, 4, 128, 128, 1, P, P, P, P, P, NULL, big, NULL) == WORKSPACE
 
 
+def test_factor_form_argument_checks(lib):
+    f = lib.onecomp_hessian_factor_form
+    big = ctypes.c_size_t(1 << 40)
+    BLOCK = 1
+    assert f(P, 256, 0.01, 0, 2, NULL, P, P, P, big, NULL) == UNSUPPORTED       # unknown form
+    assert f(P, 256, 0.01, 0, -1, NULL, P, P, P, big, NULL) == UNSUPPORTED
+    assert f(P, 144, 0.01, 0, BLOCK, NULL, P, P, P, big, NULL) == UNSUPPORTED   # block form needs d_in % 128 == 0
+    assert f(P, 100, 0.01, 0, BLOCK, NULL, P, P, P, big, NULL) == INVALID       # d_in % 16 comes first
+    assert f(NULL, 256, 0.01, 0, BLOCK, NULL, P, P, P, big, NULL) == INVALID
+    assert f(P, 256, 0.01, 0, BLOCK, NULL, NULL, P, P, big, NULL) == INVALID
+    assert f(P, 256, 0.01, 1, BLOCK, NULL, P, P, P, big, NULL) == INVALID       # act_order needs perm_out
+    assert f(P, 256, -1.0, 0, BLOCK, NULL, P, P, P, big, NULL) == INVALID
+    assert f(P, 256, 0.01, 0, BLOCK, NULL, P, P, NULL, big, NULL) == WORKSPACE
+    assert f(P, 256, 0.01, 0, BLOCK, NULL, P, P, P, ctypes.c_size_t(1024), NULL) == WORKSPACE
+
+
+def test_quantize_form_argument_checks(lib):
+    f = lib.onecomp_quantize_layer_form
+    big = ctypes.c_size_t(1 << 40)
+    BLOCK = 1
+
+    def call(W=P, dt=1, d_out=64, d_in=256, F=P, form=BLOCK, perm=NULL, bits=4, G=128, B=128, grid=0, Q=P, s=P, z=P,
+             wh=P, loss=P, ws=P, wsb=big):
+        return f(W, dt, d_out, d_in, F, form, perm, bits, G, B, grid, Q, s, z, wh, loss, ws, wsb, NULL)
+
+    assert call(form=2) == UNSUPPORTED
+    assert call(form=-1) == UNSUPPORTED
+    assert call(G=256) == UNSUPPORTED            # block form: groups no wider than a block
+    assert call(d_in=384, G=384) == UNSUPPORTED
+    assert call(grid=2) == UNSUPPORTED
+    assert call(dt=3) == UNSUPPORTED
+    assert call(bits=5) == UNSUPPORTED
+    assert call(W=NULL) == INVALID
+    assert call(F=NULL) == INVALID
+    assert call(d_in=200) == INVALID
+    assert call(G=96) == INVALID
+    assert call(ws=NULL) == WORKSPACE
+    assert call(wsb=ctypes.c_size_t(16)) == WORKSPACE
+
+
 def test_sensitivity_argument_checks(lib):
     f = lib.onecomp_rtn_sensitivity
     f.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
