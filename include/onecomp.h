@@ -13,6 +13,11 @@
  *                                  and its residual is propagated through U to the
  *                                  columns not yet quantized (Sec. 4.2)
  *
+ * Variants: onecomp_quantize_layer_grid (symmetric grid of Eq. (3)); onecomp_hessian_factor_form and
+ * onecomp_quantize_layer_form (the same sweep on one Cholesky factor, without the triangular inverse);
+ * onecomp_crossgram_accumulate and onecomp_qep_target (error propagation, Sec. 4.2.1);
+ * onecomp_rtn_sensitivity (error metric of the bit allocation, Sec. 4.1).
+ *
  * Storage convention: W is d_out x d_in row-major (rows = output channels); this
  * is the transpose of the paper's N x M weight matrix.  "Column j" is input
  * channel j; a group is `group_size` consecutive input channels of one row.
@@ -159,7 +164,8 @@ onecomp_status onecomp_hessian_factor_form(const float* H, int64_t d_in, float d
  *              tr((W - W^) H_d (W - W^)^T) for the damped (permuted) matrix behind U (Eq. (layerwise)).
  *              Reduced in a fixed order (bit-wise reproducible).
  *   workspace  device scratch, >= onecomp_quantize_workspace_bytes(d_out, d_in, block_size), 256-byte aligned
- *              (about 4 d_out d_in + 4 d_in^2 bytes: fp32 working copy of W, two fp16 halves of the scaled U).
+ *              (about 9 d_out d_in + 4 d_in^2 bytes: two fp32 copies of W, codes staged in sweep order, two fp16
+ *              halves of the scaled U).
  *   d_in       at most 65535, d_out at most 2^24.
  */
 onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,

@@ -88,8 +88,9 @@ template <typename T>
 __global__ __launch_bounds__(256) void load_kernel(const T* __restrict__ W, int64_t d_out, int64_t d_in,
                                                   const int32_t* __restrict__ perm, float* __restrict__ Wf,
                                                   float* __restrict__ rowloss, Scalars* __restrict__ sc,
-                                                  const int zero_fill) {
-    // zero_fill: the working copy starts as zeros (it then holds only the feedback, the weights are read from W)
+                                                  const int zero_fill, float* __restrict__ W0p) {
+    // zero_fill: the working copy starts as zeros (it then holds only the feedback, the weights are read from W, or,
+    // under a column order, from the gathered copy W0p written here)
     float m = 0.f;
     for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {   // a workgroup per row, rows strided over the grid
     if (threadIdx.x == 0) rowloss[r] = 0.f;
@@ -97,6 +98,7 @@ __global__ __launch_bounds__(256) void load_kernel(const T* __restrict__ W, int6
         for (int p = threadIdx.x; p < d_in; p += 256) {
             const float v = to_f32<T>(W[r * d_in + perm[p]]);
             Wf[r * d_in + p] = zero_fill ? 0.f : v;
+            if (W0p) W0p[r * d_in + p] = v;
             m = fmaxf(m, fabsf(v));
         }
     } else {   // rows are 16-byte aligned: d_in is a multiple of 128
@@ -134,8 +136,7 @@ __global__ __launch_bounds__(256) void load_kernel(const T* __restrict__ W, int6
 struct BlockArgs {
     float* Wf;              // [d_out x d_in] working copy, sweep order
     const float* U;         // [d_in x d_in]
-    const int32_t* perm;    // or nullptr
-    uint8_t* Q;             // [d_out x d_in] original order
+    uint8_t* Q;             // [d_out x d_in] sweep order (the caller's array, or the staging copy under a column order)
     float* scales;          // [d_out x n_g]
     float* zeros;
     float* W_hat;           // or nullptr
@@ -336,28 +337,20 @@ __global__ __launch_bounds__(BLOCK_THREADS) void block_kernel(BlockArgs a) {
             *reinterpret_cast<short8v*>(a.Dl + off) = dl;
         }
     }
-    // tiles out: W^ and codes (original column order)
+    // tiles out: W^ and codes, in sweep order (with a column order the caller's arrays are filled by
+    // unpermute_kernel from the staged codes)
     for (int it = wave; it < ROWS / 2; it += 4) {
         const int rr = it * 2 + (l >> 5), c4 = (l & 31) * 4;
         const int gr = r0 + rr;
         if (gr >= a.d_out) continue;
-        if (!a.perm) {
-            if (a.W_hat) {
-                float4v h;
-                h[0] = sW[rr * SP + c4 + 0]; h[1] = sW[rr * SP + c4 + 1];
-                h[2] = sW[rr * SP + c4 + 2]; h[3] = sW[rr * SP + c4 + 3];
-                *reinterpret_cast<float4v*>(a.W_hat + int64_t(gr) * d_in + j0 + c4) = h;
-            }
-            *reinterpret_cast<uint32_t*>(a.Q + int64_t(gr) * d_in + j0 + c4) =
-                *reinterpret_cast<const uint32_t*>(sQ + rr * QP + c4);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int oc = a.perm[j0 + c4 + e];
-                if (a.W_hat) a.W_hat[int64_t(gr) * d_in + oc] = sW[rr * SP + c4 + e];
-                a.Q[int64_t(gr) * d_in + oc] = sQ[rr * QP + c4 + e];
-            }
+        if (a.W_hat) {
+            float4v h;
+            h[0] = sW[rr * SP + c4 + 0]; h[1] = sW[rr * SP + c4 + 1];
+            h[2] = sW[rr * SP + c4 + 2]; h[3] = sW[rr * SP + c4 + 3];
+            *reinterpret_cast<float4v*>(a.W_hat + int64_t(gr) * d_in + j0 + c4) = h;
         }
+        *reinterpret_cast<uint32_t*>(a.Q + int64_t(gr) * d_in + j0 + c4) =
+            *reinterpret_cast<const uint32_t*>(sQ + rr * QP + c4);
     }
 }
 
@@ -382,14 +375,14 @@ constexpr size_t BLOCK_LDS = (size_t(SB) * SB + SB + 2 * size_t(ROWS) * SP) * si
 struct PanelArgs {
     const float* Wf;            // [d_out x d_in] working copy (columns beyond the super-block are current up to the
                                 // previous super-block); block form: only the accumulated feedback c
-    const void* W0;             // block form: the layer's weights as passed in (original column order)
+    const void* W0;             // block form: the layer's weights in sweep order (the caller's matrix, or the gathered
+                                // fp32 copy under a column order)
     int w0_bf16;
     const float* U;
-    const int32_t* perm;
-    uint8_t* Q;
+    uint8_t* Q;                 // sweep order (the caller's array, or the staging copy under a column order)
     float* scales;
     float* zeros;
-    float* W_hat;
+    float* W_hat;               // sweep order, or nullptr
     uint16_t *Dh, *Dl;          // [SBIG x ldD] transposed residual panels for the far update
     uint16_t *Fh, *Fl;          // [workgroup][3][8 k-steps][2 row tiles][64 lanes][8] residual fragments (own use)
     const uint16_t *Bh, *Bl;    // [6 block pairs][8 k-steps][4 column tiles][64 lanes][8] of this super-block
@@ -462,13 +455,12 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
         // registers until the block is done
         float16v w0r[2];
         if constexpr (DIRECT) {
-            // a lane's column is the same for all 16 rows of a tile: one look-up of the column order per tile, then
             // 32 independent loads in straight-line code (one uniform branch on the element type around them)
             int64_t off[2][16];
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
                 const int p = j0 + (mt == 0 ? wave : 3 - wave) * 32 + lc;
-                const int oc = a.perm ? a.perm[p] : p;
+                const int oc = p;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     off[mt][r] = int64_t(min(r0 + mt * 32 + (r / 4) * 8 + lr + (r % 4), a.d_out - 1)) * d_in + oc;
@@ -775,7 +767,7 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                 *reinterpret_cast<short8v*>(a.Fl + off) = dl;
             }
         }
-        // W^ = s (q - z) and codes, original column order
+        // W^ = s (q - z) and codes, in sweep order (see unpermute_kernel)
         for (int it = wave; it < ROWS / 2; it += 4) {
             const int rr = it * 2 + (lane >> 5), c4 = (lane & 31) * 4;
             const int gr = r0 + rr;
@@ -787,21 +779,12 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                 qv[e] = sW[rr * SP + c4 + e];
                 hv[e] = sS[rr * 8 + gi] * (qv[e] - sZ[rr * 8 + gi]);
             }
-            if (!a.perm) {
-                if (a.W_hat) {
-                    const float4v h = {hv[0], hv[1], hv[2], hv[3]};
-                    *reinterpret_cast<float4v*>(a.W_hat + int64_t(gr) * d_in + j0 + c4) = h;
-                }
-                const uint32_t pk = uint32_t(qv[0]) | (uint32_t(qv[1]) << 8) | (uint32_t(qv[2]) << 16) | (uint32_t(qv[3]) << 24);
-                *reinterpret_cast<uint32_t*>(a.Q + int64_t(gr) * d_in + j0 + c4) = pk;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int oc = a.perm[j0 + c4 + e];
-                    if (a.W_hat) a.W_hat[int64_t(gr) * d_in + oc] = hv[e];
-                    a.Q[int64_t(gr) * d_in + oc] = uint8_t(qv[e]);
-                }
+            if (a.W_hat) {
+                const float4v h = {hv[0], hv[1], hv[2], hv[3]};
+                *reinterpret_cast<float4v*>(a.W_hat + int64_t(gr) * d_in + j0 + c4) = h;
             }
+            const uint32_t pk = uint32_t(qv[0]) | (uint32_t(qv[1]) << 8) | (uint32_t(qv[2]) << 16) | (uint32_t(qv[3]) << 24);
+            *reinterpret_cast<uint32_t*>(a.Q + int64_t(gr) * d_in + j0 + c4) = pk;
         }
         // the fragments written above are read back by other waves of this workgroup (same CU, same L1): a
         // workgroup-scope release, completed by the barrier at the top of the loop
@@ -1144,6 +1127,37 @@ __global__ __launch_bounds__(256) void panel_far_kernel(PanelArgs pa, TrailArgs 
     else trailing_tile<3>(ta, blockIdx.x - n_panel, dyn_lds);
 }
 
+// Column order (activation ordering): the sweep stages its codes in sweep order (coalesced rows); the caller's
+// arrays are then written in ORIGINAL column order, coalesced, gathering from the staged row (a row is a few KB and
+// stays in cache).  W^ is recomputed as s (q - z), the same fp32 operations the sweep used.
+__global__ __launch_bounds__(256) void inv_perm_kernel(const int32_t* __restrict__ perm, int n, int32_t* __restrict__ inv) {
+    const int p = blockIdx.x * 256 + threadIdx.x;
+    if (p < n) inv[perm[p]] = p;
+}
+
+__global__ __launch_bounds__(256) void unpermute_kernel(const uint8_t* __restrict__ Qs, const float* __restrict__ scales,
+                                                       const float* __restrict__ zeros, const int32_t* __restrict__ inv,
+                                                       int d_out, int d_in, int G, int n_g, uint8_t* __restrict__ Q,
+                                                       float* __restrict__ W_hat) {
+    for (int64_t r = blockIdx.y; r < d_out; r += gridDim.y) {
+        const int oc = (blockIdx.x * 256 + threadIdx.x) * 4;   // d_in % 128 == 0: whole groups of 4 columns
+        if (oc >= d_in) continue;
+        const int4 pv = *reinterpret_cast<const int4*>(inv + oc);
+        const int ps[4] = {pv.x, pv.y, pv.z, pv.w};
+        uint32_t pk = 0;
+        float4v h;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t q = Qs[r * d_in + ps[e]];
+            const int g = ps[e] / G;
+            h[e] = scales[r * n_g + g] * (float(q) - zeros[r * n_g + g]);
+            pk |= q << (8 * e);
+        }
+        *reinterpret_cast<uint32_t*>(Q + r * d_in + oc) = pk;
+        if (W_hat) *reinterpret_cast<float4v*>(W_hat + r * d_in + oc) = h;
+    }
+}
+
 // loss = sum of the per-row sums, fixed order.  One workgroup.
 __global__ __launch_bounds__(1024) void loss_kernel(const float* __restrict__ rowloss, int d_out,
                                                    float* __restrict__ loss) {
@@ -1169,6 +1183,9 @@ struct SweepWs {
     uint16_t *Fh, *Fl;   // panel kernel: residual fragments, [workgroups][3 x 8 x 2 x 64 x 8]
     uint16_t *Bh, *Bl;   // panel kernel: fragments of the normalized U blocks, [super-blocks][6 x 8 x 4 x 64 x 8]
     Scalars* sc;
+    uint8_t* Qs;         // [d_out x d_in] codes in sweep order (used under a column order)
+    int32_t* inv;        // [d_in] inverse of the column order
+    float* W0p;          // [d_out x d_in] the weights gathered into sweep order (block form under a column order)
 };
 
 constexpr size_t F_PER_WG = size_t(3) * 8 * 2 * 64 * 8 * 2;    // bytes of Fh (or Fl) per workgroup of the panel kernel
@@ -1191,7 +1208,10 @@ SweepWs carve(void* ws, int64_t d_out, int64_t d_in) {
     w.Fl = reinterpret_cast<uint16_t*>(p); p += fb;
     w.Bh = reinterpret_cast<uint16_t*>(p); p += bb;
     w.Bl = reinterpret_cast<uint16_t*>(p); p += bb;
-    w.sc = reinterpret_cast<Scalars*>(p);
+    w.sc = reinterpret_cast<Scalars*>(p); p += 256;
+    w.Qs = reinterpret_cast<uint8_t*>(p); p += align_up(size_t(d_out) * d_in, 256);
+    w.inv = reinterpret_cast<int32_t*>(p); p += align_up(size_t(d_in) * sizeof(int32_t), 256);
+    w.W0p = reinterpret_cast<float*>(p);
     return w;
 }
 
@@ -1232,7 +1252,9 @@ size_t sweep_workspace_bytes(int64_t d_out, int64_t d_in, int block) {
     (void)block;
     return align_up(size_t(d_out) * d_in * sizeof(float), 256) + 4 * size_t(SBIG) * ld_d(d_out) * 2 +
            2 * align_up(size_t(d_in) * d_in * 2, 256) + align_up(size_t(d_out) * sizeof(float), 256) +
-           2 * size_t(ceil_div(d_out, ROWS)) * F_PER_WG + 2 * size_t(ceil_div(d_in, SBIG)) * B_PER_SB + 256;
+           2 * size_t(ceil_div(d_out, ROWS)) * F_PER_WG + 2 * size_t(ceil_div(d_in, SBIG)) * B_PER_SB + 256 +
+           align_up(size_t(d_out) * d_in, 256) + align_up(size_t(d_in) * sizeof(int32_t), 256) +
+           align_up(size_t(d_out) * d_in * sizeof(float), 256);
 }
 
 onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* U,
@@ -1247,10 +1269,10 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
     dim3 lgrid{unsigned(d_out < 1024 ? d_out : 1024)};
     if (w_dtype == ONECOMP_BF16)
         hipLaunchKernelGGL(load_kernel<uint16_t>, lgrid, dim3(256), 0, stream, static_cast<const uint16_t*>(W), d_out,
-                           d_in, perm, w.Wf, w.rowloss, w.sc, int(direct));
+                           d_in, perm, w.Wf, w.rowloss, w.sc, int(direct), (direct && perm) ? w.W0p : nullptr);
     else
         hipLaunchKernelGGL(load_kernel<float>, lgrid, dim3(256), 0, stream, static_cast<const float*>(W), d_out, d_in,
-                           perm, w.Wf, w.rowloss, w.sc, int(direct));
+                           perm, w.Wf, w.rowloss, w.sc, int(direct), (direct && perm) ? w.W0p : nullptr);
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(umax_kernel, dim3(unsigned(d_in < 1024 ? d_in : 1024)), dim3(256), 0, stream, U,
                        int(d_in), w.sc);
@@ -1302,7 +1324,11 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
                            w.sc, w.Bh, w.Bl);
         ONECOMP_CHECK_LAUNCH();
         PanelArgs pa;
-        pa.Wf = w.Wf; pa.W0 = W; pa.w0_bf16 = w_dtype == ONECOMP_BF16; pa.U = U; pa.perm = perm; pa.Q = Q; pa.scales = scales; pa.zeros = zeros; pa.W_hat = W_hat;
+        pa.Wf = w.Wf; pa.U = U;
+        // block form: where the panel finds the original weights; under a column order, the gathered fp32 copy
+        pa.W0 = (direct && perm) ? static_cast<const void*>(w.W0p) : W;
+        pa.w0_bf16 = !(direct && perm) && w_dtype == ONECOMP_BF16;
+        pa.Q = perm ? w.Qs : Q; pa.scales = scales; pa.zeros = zeros; pa.W_hat = perm ? nullptr : W_hat;
         pa.Fh = w.Fh; pa.Fl = w.Fl; pa.sc = w.sc; pa.rowloss = w.rowloss;
         pa.d_out = int(d_out); pa.d_in = int(d_in); pa.n_g = int(d_in / group_size); pa.ldD = int(ld_d(d_out));
         pa.lgG = 0;
@@ -1333,7 +1359,7 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
         // columns counted from the group's start.  Inside a super-block every 128-column block updates the rest
         // of the super-block; the columns beyond it are updated once per super-block.
         BlockArgs a;
-        a.Wf = w.Wf; a.U = U; a.perm = perm; a.Q = Q; a.scales = scales; a.zeros = zeros; a.W_hat = W_hat;
+        a.Wf = w.Wf; a.U = U; a.Q = perm ? w.Qs : Q; a.scales = scales; a.zeros = zeros; a.W_hat = perm ? nullptr : W_hat;
         a.Dh = w.Dh; a.Dl = w.Dl; a.ldD = int(ld_d(d_out)); a.sc = w.sc; a.rowloss = w.rowloss;
         a.d_out = int(d_out); a.d_in = int(d_in); a.G = group_size; a.n_g = int(d_in / group_size);
         a.qs = grid == ONECOMP_GRID_SYMMETRIC ? float((1 << (bits - 1)) - 1) : 0.f;
@@ -1355,6 +1381,15 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
             if ((st = trailing(0, 0, s1 - s0, s0, s1, int(d_in))) != ONECOMP_OK) return st;
             s0 = s1;
         }
+    }
+    if (perm) {
+        hipLaunchKernelGGL(inv_perm_kernel, dim3(unsigned(ceil_div(d_in, 256))), dim3(256), 0, stream, perm, int(d_in),
+                           w.inv);
+        ONECOMP_CHECK_LAUNCH();
+        hipLaunchKernelGGL(unpermute_kernel, dim3(unsigned(ceil_div(d_in, 1024)), unsigned(d_out < 4096 ? d_out : 4096)),
+                           dim3(256), 0, stream, w.Qs, scales, zeros, w.inv, int(d_out), int(d_in), group_size,
+                           int(d_in / group_size), Q, W_hat);
+        ONECOMP_CHECK_LAUNCH();
     }
     hipLaunchKernelGGL(loss_kernel, dim3(1), dim3(1024), 0, stream, w.rowloss, int(d_out), loss);
     ONECOMP_CHECK_LAUNCH();
