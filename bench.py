@@ -194,6 +194,9 @@ def main():
                     help="inverse: the factor call returns U with U^T U = (H + lambda I)^-1 (Sec. 4.2.1) and the sweep "
                          "propagates through it; block: one Cholesky only, the sweep runs on the block form (same codes "
                          "up to ties; groups up to 128 columns)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (accumulate, factor, quantize) in a HIP graph after the warm-up and time "
+                         "replays of it; per-phase times are then not available (reported as the eager warm-up's)")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="context only: also time the vendor library's dense bf16 GEMM X^T X (torch.matmul, full d_in x "
                          "d_in output, no symmetry, no accumulate into fp32 H) on the same activations; reported under "
@@ -246,7 +249,12 @@ def main():
 
     def step(record=None, only=None, form=None):
         form = form or args.factor_form
-        e = [ev() for _ in range(4)]
+
+        class _NoEvent:
+            def record(self):
+                pass
+        # events only when the caller wants the phase times (none are recorded into a graph capture)
+        e = [ev() for _ in range(4)] if record is not None else [_NoEvent()] * 4
         if only in (None, "gram"):
             H.zero_()
         e[0].record()
@@ -281,11 +289,33 @@ def main():
         step(only=only)
     torch.cuda.synchronize()
     rec = []
-    t_start = time.perf_counter()
-    for _ in range(args.steps):
+    if args.graph:
+        # the library neither allocates nor synchronizes, so a step can be captured as it is; the eager pass
+        # before it supplies the per-phase times
         step(rec, only=only)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t_start
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step(only=only)                      # warm-up on the capture stream
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                step(only=only)
+        torch.cuda.current_stream().wait_stream(side)
+        g.replay()
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t_start
+    else:
+        t_start = time.perf_counter()
+        for _ in range(args.steps):
+            step(rec, only=only)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t_start
     assert int(info.item()) == 0, "Hessian not positive definite"
     loss_main = float(out["loss"].item())
 
@@ -363,6 +393,7 @@ def main():
         "config": {"workload": f"{cfg.name}: W {d_out}x{d_in} {str(cfg.dtype).split('.')[-1]}, {T} tokens, "
                                f"{cfg.bits}-bit, group {cfg.group_size}, damp {cfg.damp}, act_order {cfg.act_order}, "
                                f"block 128, {n_calls} accumulate call(s), factor form {args.factor_form}"
+                               + (", HIP graph replay" if args.graph else "")
                                + ("" if phase == "all" else f" [PROFILING RUN: only phase '{phase}' timed, value is not the metric]")},
         "phases_ms": {"hessian_accumulate": acc_ms, "hessian_factor": fac_ms, "quantize_layer": swp_ms},
         "layer_quantize_ms": fac_ms + swp_ms,

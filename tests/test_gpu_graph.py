@@ -1,0 +1,72 @@
+"""The library allocates nothing, synchronizes nothing and clears its scratch with kernels, so a caller may record
+a whole layer step into a HIP graph.  Each replay is checked against the eager result, with eager work and
+synchronizations between the replays."""
+import pytest
+import torch
+
+import paper_2603_28845_amd as og
+from paper_2603_28845_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.mark.parametrize("form,act", [("inverse", False), ("block", True)])
+def test_layer_step_in_a_hip_graph(form, act):
+    print(f"[case] graph capture of a layer step, factor form {form}, act_order {act}", flush=True)
+    cfg = synth.scaled(synth.CONFIGS["c2"], d_out=130, d_in=640, n_tokens=2100, seed=3)
+    W = synth.make_weight(cfg, DEV)
+    X = synth.make_activations(cfg, DEV)
+    d = cfg.d_in
+    H = torch.zeros((d, d), dtype=torch.float32, device=DEV)
+    U = torch.empty((d, d), dtype=torch.float32, device=DEV)
+    info = torch.zeros(1, dtype=torch.int32, device=DEV)
+    perm = torch.empty(d, dtype=torch.int32, device=DEV)
+    ws_f = torch.empty(og.onecomp_factor_workspace_bytes(d), dtype=torch.uint8, device=DEV)
+    ws_q = torch.empty(og.onecomp_quantize_workspace_bytes(cfg.d_out, d), dtype=torch.uint8, device=DEV)
+
+    def new_out():
+        return {
+            "Q_codes": torch.empty((cfg.d_out, d), dtype=torch.uint8, device=DEV),
+            "scales": torch.empty((cfg.d_out, d // cfg.group_size), dtype=torch.float32, device=DEV),
+            "zeros": torch.empty((cfg.d_out, d // cfg.group_size), dtype=torch.float32, device=DEV),
+            "W_hat": torch.empty((cfg.d_out, d), dtype=torch.float32, device=DEV),
+            "loss": torch.zeros(1, dtype=torch.float32, device=DEV),
+        }
+
+    def step(out):
+        H.zero_()                     # a fill kernel, not a memset node
+        og.onecomp_hessian_accumulate(X[:1000], H)
+        og.onecomp_hessian_accumulate(X[1000:], H)
+        og.onecomp_hessian_factor(H, cfg.damp, act, U=U, perm_out=perm, info=info, workspace=ws_f, form=form)
+        og.onecomp_quantize_layer(W, U, cfg.bits, cfg.group_size, perm=perm if act else None, workspace=ws_q,
+                                  out=out, form=form)
+
+    ref = new_out()
+    step(ref)
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0
+    H_ref = H.clone()
+
+    out = new_out()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step(out)
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            step(out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+
+    for rep in range(3):
+        for t in out.values():        # eager work between replays: wipe what the replay must rewrite
+            t.zero_()
+        H.fill_(7.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(H, H_ref), f"replay {rep}: H"
+        for k in ref:
+            assert torch.equal(out[k], ref[k]), f"replay {rep}: {k}"
