@@ -434,14 +434,15 @@ def test_end_to_end_c1():
 
 
 # ------------------------------------------------------------- full size, sampled oracle ---
-def test_full_size_down_projection_sampled():
-    """The 4096 x 14336 layer in the launch configuration bench.py times (bf16, 4-bit, group 128):
-    Gram on sampled tiles, factor against the oracle's U for the same H, sweep on sampled rows with tie
-    replay.  The calibration set is cut to 32768 tokens (still more than 2 d_in, so H has full rank as in
-    the real workload) so that the float64 oracle finishes in about half a minute."""
-    cfg = synth.scaled(synth.CONFIGS["c3b"], n_tokens=32768)
+def _full_size_sampled(name, n_rows, act):
+    """One full-size layer of the benchmark configurations (bf16, d_in 14336): Gram against the oracle, both forms
+    of the factor against the oracle's for the same H, sweep on sampled rows with tie replay, both forms.  The
+    calibration set is cut to 32768 tokens (still more than 2 d_in, so H has full rank as in the real workload)
+    so that the float64 oracle finishes in about half a minute."""
+    cfg = synth.scaled(synth.CONFIGS[name], n_tokens=32768)
     d_out, d_in = cfg.d_out, cfg.d_in
-    _announce(f"full size {d_out}x{d_in}: gram ({cfg.n_tokens} tokens)")
+    assert cfg.act_order == act
+    _announce(f"full size {name} {d_out}x{d_in} b{cfg.bits} g{cfg.group_size} act={act}: gram ({cfg.n_tokens} tokens)")
     X = synth.make_activations(cfg, DEV)
     W = synth.make_weight(cfg, DEV)
     H = _gpu_gram(X)
@@ -450,31 +451,33 @@ def test_full_size_down_projection_sampled():
     Hn = H.cpu().numpy()
     assert np.array_equal(Hn, Hn.T)
     assert rel_fro(Hn.astype(np.float64), Ho) <= 1e-4
-    del Xd
+    del Xd, X
     _announce("full size: oracle factor")
     H32 = Ho.astype(np.float32)
     del Ho
-    f = oc.hessian_factor(H32.astype(np.float64), cfg.damp)
+    f = oc.hessian_factor(H32.astype(np.float64), cfg.damp, act_order=act)
     assert f["info"] == 0
     _announce("full size: GPU factor")
-    U, _, info = og.onecomp_hessian_factor(torch.from_numpy(H32).to(DEV), cfg.damp)
+    U, perm, info = og.onecomp_hessian_factor(torch.from_numpy(H32).to(DEV), cfg.damp, act_order=act)
     torch.cuda.synchronize()
     assert int(info.item()) == 0
+    if act:
+        np.testing.assert_array_equal(perm.cpu().numpy(), f["perm"])
     err = rel_fro(U.cpu().numpy().astype(np.float64), f["U"])
     _announce(f"   U rel. Frobenius error {err:.3e}")
     assert err <= 1e-6
     del U
-    _announce("full size: sweep, 48 sampled rows")
+    _announce(f"full size: sweep, {n_rows} sampled rows")
     U32 = torch.from_numpy(f["U"].astype(np.float32)).to(DEV)
-    rows = np.sort(np.random.default_rng(7).choice(d_out, size=48, replace=False))
+    rows = np.sort(np.random.default_rng(7).choice(d_out, size=n_rows, replace=False))
     # A flip at a tie changes later codes of its row (the feedback differs by a whole grid step), so in a sample
-    # of 48 rows one flipped row alone costs a few tenths of a percent of raw agreement: the raw bar is 99 % here,
-    # the flips themselves are bounded, and agreement after replaying the flips must still be exact.
-    _, st = _check_sweep(W, U32, cfg.bits, cfg.group_size, rows=rows, min_agree=0.99)
+    # of a few dozen rows one flipped row alone costs a few tenths of a percent of raw agreement: the raw bar is
+    # 99 % here, the flips themselves are bounded, and agreement after replaying the flips must still be exact.
+    _, st = _check_sweep(W, U32, cfg.bits, cfg.group_size, perm=perm if act else None, rows=rows, min_agree=0.99)
     assert st["tie_flips"] <= 4
     del U32
     _announce("full size: factor in block form")
-    F, _, info = og.onecomp_hessian_factor(torch.from_numpy(H32).to(DEV), cfg.damp, form="block")
+    F, _, info = og.onecomp_hessian_factor(torch.from_numpy(H32).to(DEV), cfg.damp, act_order=act, form="block")
     torch.cuda.synchronize()
     assert int(info.item()) == 0
     Fo = _oracle_block_factor(f)
@@ -484,5 +487,16 @@ def test_full_size_down_projection_sampled():
     del Fo
     _announce("full size: sweep with the block form, same rows")
     U32 = torch.from_numpy(f["U"].astype(np.float32)).to(DEV)
-    _, st = _check_sweep(W, U32, cfg.bits, cfg.group_size, rows=rows, min_agree=0.99, F32=F)
+    _, st = _check_sweep(W, U32, cfg.bits, cfg.group_size, perm=perm if act else None, rows=rows, min_agree=0.99,
+                         F32=F)
     assert st["tie_flips"] <= 4
+
+
+def test_full_size_down_projection_sampled():
+    """The 4096 x 14336 layer in the launch configuration bench.py times (4-bit, group 128, natural order)."""
+    _full_size_sampled("c3b", 48, act=False)
+
+
+def test_full_size_act_order_3bit_sampled():
+    """The same layer at 3 bits, group 64, with activation ordering."""
+    _full_size_sampled("c4_3bit", 32, act=True)
