@@ -247,6 +247,76 @@ __global__ __launch_bounds__(GRAM_THREADS) void gram_bf16_kernel(const uint16_t*
     gram_store<WT, WT>(acc, H, d_in, i0 + wr * (32 * WT), k0 + wc * (32 * WT), diag, lane);
 }
 
+// Epilogue of a tile whose tokens are split between two workgroups (see gram_bf16_ring_kernel): the tile lies
+// strictly above the diagonal and inside the matrix.  The workgroup with the first half of the tokens adds its sum
+// to H[i][k] and leaves the mirror alone; the one with the second half overwrites the mirror entries H[k][i] with
+// its sum.  gram_merge_kernel then sets both to H[i][k] + H[k][i]: one fixed order of additions, bit-wise symmetric.
+template <int MT, int NT>
+__device__ __forceinline__ void gram_store_half(float16v (&acc)[MT][NT], float* __restrict__ H, const int d_in,
+                                                const int ibase, const int kbase, const int half, const int lane) {
+    const int lr = (lane >> 5) * 4, lc = lane & 31;
+    if (half == 0) {
+        constexpr int NBATCH = NT < 2 ? NT : 2;
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+#pragma unroll
+            for (int n0 = 0; n0 < NT; n0 += NBATCH) {
+                float* hp = H + int64_t(ibase + m * 32 + lr) * d_in + kbase + n0 * 32 + lc;
+                float hv[NBATCH][16];
+#pragma unroll
+                for (int n = 0; n < NBATCH; ++n)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) hv[n][r] = hp[int64_t((r / 4) * 8 + (r % 4)) * d_in + n * 32];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int n = 0; n < NBATCH; ++n)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        hp[int64_t((r / 4) * 8 + (r % 4)) * d_in + n * 32] = hv[n][r] + 2.0f * acc[m][n0 + n][r];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int n = 0; n < NT; ++n) {
+                float* mp = H + int64_t(kbase + n * 32 + lc) * d_in + ibase + m * 32 + lr;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4v o = {2.0f * acc[m][n][q * 4], 2.0f * acc[m][n][q * 4 + 1], 2.0f * acc[m][n][q * 4 + 2],
+                                       2.0f * acc[m][n][q * 4 + 3]};
+                    *reinterpret_cast<float4v*>(mp + q * 8) = o;
+                }
+            }
+    }
+}
+
+// H[i][k] = H[k][i] = H[i][k] + H[k][i] on the 256 x 256 tiles with ranks split0 .. split0 + n_split - 1 of the
+// first band (tile rows 0 .. 3, columns from 4 on: rank split0 + m is tile (m % 4, 4 + m / 4) when split0 is the
+// size of the band's triangle).  One workgroup of 32 x 8 threads per 32 x 32 block, through LDS so that both
+// matrices are read and written along rows.
+__global__ __launch_bounds__(256) void gram_merge_kernel(float* __restrict__ H, int d_in, int n_split) {
+    __shared__ float sa[32][33], sb[32][33];
+    const int m = blockIdx.y;
+    if (m >= n_split) return;
+    const int ti = m % BAND, tk = BAND + m / BAND;
+    const int bi = blockIdx.x / 8, bk = blockIdx.x % 8;            // 8 x 8 blocks of 32 x 32 per tile
+    const int i0 = ti * 256 + bi * 32, k0 = tk * 256 + bk * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+    for (int y = ty; y < 32; y += 8) {
+        sa[y][tx] = H[int64_t(i0 + y) * d_in + k0 + tx];
+        sb[y][tx] = H[int64_t(k0 + y) * d_in + i0 + tx];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int y = ty; y < 32; y += 8) {
+        H[int64_t(i0 + y) * d_in + k0 + tx] = sa[y][tx] + sb[tx][y];
+        H[int64_t(k0 + y) * d_in + i0 + tx] = sa[tx][y] + sb[y][tx];
+    }
+}
+
 // -------------------------------------------------------------------------------------------
 // bf16 ring kernel: global -> LDS without passing through registers (buffer_load_dwordx4 ... lds), in steps of
 // 16 tokens through a ring of NBUF LDS slots.  Two shapes:
@@ -307,13 +377,36 @@ __device__ inline void tile128_from_rank(int v, int n_rt, int n_ct, int& ti, int
 template <typename C, bool CROSS>
 __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring_kernel(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ Xb, int64_t n_tokens, int d_in, int64_t ldx,
-    int64_t ldxb, float* __restrict__ H, int n_rt, int n_ct, int n_tiles, int chunk) {
+    int64_t ldxb, float* __restrict__ H, int n_rt, int n_ct, int n_tiles, int chunk, int split0, int n_split) {
     using R = Ring<C>;
     constexpr int KT = R::KT, NBUF = C::NBUF, MT = R::MT, NT = R::NT, LPW = R::LPW;
     constexpr int A_ROWB = R::A_ROWB, B_ROWB = R::B_ROWB, A_PANELB = R::A_PANELB, STAGEB = R::STAGEB;
     extern __shared__ __attribute__((aligned(1024))) char ldsb[];
-    const int v = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
-    if (v >= n_tiles) return;
+    // Workgroups 0 .. 8 chunk - 1 take whole tiles: the ranks outside [split0, split0 + n_split), `chunk` of them
+    // per XCD.  The workgroups after them take the n_split tiles of that range by halves of the token axis, so that
+    // what would be a short last round of whole tiles costs half a round (n_split = 0: no such tiles).
+    int v, half = -1;
+    if (int(blockIdx.x) < 8 * chunk) {
+        v = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+        if (v >= n_tiles - n_split) return;
+        if (v >= split0) v += n_split;
+    } else {
+        const int b = blockIdx.x - 8 * chunk, per_xcd = (n_split + 7) >> 3;
+        const int m = (b & 7) * per_xcd + (b >> 4);
+        if (m >= n_split) return;
+        v = split0 + m;
+        half = (b >> 3) & 1;
+    }
+    if (half >= 0) {   // this workgroup's half of the tokens: whole steps of KT, the first half takes the odd one
+        const int64_t t_split = ((n_tokens + KT - 1) / KT + 1) / 2 * KT;
+        if (half == 1) {
+            X += t_split * ldx;
+            Xb += t_split * ldxb;
+            n_tokens -= t_split;
+        } else {
+            n_tokens = t_split;
+        }
+    }
     int ti, tk;
     if constexpr (CROSS) {   // all tiles: bands of 4 tile rows, column by column inside a band
         const int band = min(v / (BAND * n_ct), (n_rt - 1) / BAND);
@@ -464,7 +557,8 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
         s0 = s2;
     }
     __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // no LDS write may be in flight when the workgroup ends
-    gram_store<MT, NT, !CROSS>(acc, H, d_in, i0 + wr * (32 * MT), k0 + wc * (32 * NT), diag, lane);
+    if (half >= 0) gram_store_half<MT, NT>(acc, H, d_in, i0 + wr * (32 * MT), k0 + wc * (32 * NT), half, lane);
+    else gram_store<MT, NT, !CROSS>(acc, H, d_in, i0 + wr * (32 * MT), k0 + wc * (32 * NT), diag, lane);
 }
 
 
@@ -596,30 +690,6 @@ onecomp_status launch_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_
 
 
 
-template <typename C, bool CROSS>
-onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens, int64_t d_in, int64_t ldx,
-                                int64_t ldxb, float* H, hipStream_t stream) {
-    using R = Ring<C>;
-    const int n_rt = int(ceil_div(d_in, C::TM)), n_ct = int(ceil_div(d_in, C::TN));
-    int n_tiles = 0;
-    if (CROSS) n_tiles = n_rt * n_ct;
-    else if (C::TM == C::TN) n_tiles = n_ct * (n_ct + 1) / 2;
-    else for (int i = 0; i < n_rt; ++i) n_tiles += n_ct - i / 2;
-    const int chunk = int(ceil_div(n_tiles, 8));
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_ring_kernel<C, CROSS>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(R::LDS_BYTES)) != hipSuccess)
-            return ONECOMP_ERR_HIP;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL((gram_bf16_ring_kernel<C, CROSS>), dim3(chunk * 8), dim3(R::THREADS), R::LDS_BYTES, stream,
-                       static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(Xb), n_tokens, int(d_in), ldx,
-                       ldxb, H, n_rt, n_ct, n_tiles, chunk);
-    ONECOMP_CHECK_LAUNCH();
-    return ONECOMP_OK;
-}
-
 int device_cus() {
     static int n_cus = 0;
     if (n_cus == 0) {
@@ -630,6 +700,55 @@ int device_cus() {
         n_cus = v;
     }
     return n_cus;
+}
+
+// Number of 256 x 256 tiles of the symmetric Gram computed by halves of the token axis (0: none), see
+// launch_bf16_ring.
+int split_tiles(int64_t n_tiles, int64_t n_ct, int64_t d_in, int64_t n_tokens, int n_cus) {
+    const int64_t r = n_tiles % n_cus;
+    if (r > 0 && r <= n_cus / 2 && n_tokens >= 1024 && n_ct >= BAND + ceil_div(r, BAND) &&
+        (BAND + ceil_div(r, BAND)) * 256 <= d_in)
+        return int(r);
+    return 0;
+}
+
+template <typename C, bool CROSS>
+onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens, int64_t d_in, int64_t ldx,
+                                int64_t ldxb, float* H, hipStream_t stream) {
+    using R = Ring<C>;
+    const int n_rt = int(ceil_div(d_in, C::TM)), n_ct = int(ceil_div(d_in, C::TN));
+    int n_tiles = 0;
+    if (CROSS) n_tiles = n_rt * n_ct;
+    else if (C::TM == C::TN) n_tiles = n_ct * (n_ct + 1) / 2;
+    else for (int i = 0; i < n_rt; ++i) n_tiles += n_ct - i / 2;
+    // A short last round: when the tiles left over after whole rounds of one tile per CU fill at most half of the
+    // CUs, that many tiles (taken from the rectangular part of the first band: strictly above the diagonal, inside
+    // the matrix) are computed by two workgroups each, one per half of the tokens, dispatched last.
+    int n_split = 0, split0 = 0;
+    if (!CROSS && C::TM == 256 && C::TN == 256) {
+        const int n_cus = device_cus();
+        if (n_cus <= 0) return ONECOMP_ERR_HIP;
+        n_split = split_tiles(n_tiles, n_ct, d_in, n_tokens, n_cus);
+        split0 = BAND * (BAND + 1) / 2;
+    }
+    const int chunk = int(ceil_div(n_tiles - n_split, 8));
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_ring_kernel<C, CROSS>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, int(R::LDS_BYTES)) != hipSuccess)
+            return ONECOMP_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gram_bf16_ring_kernel<C, CROSS>), dim3(chunk * 8 + 16 * int(ceil_div(n_split, 8))),
+                       dim3(R::THREADS), R::LDS_BYTES, stream, static_cast<const uint16_t*>(X),
+                       static_cast<const uint16_t*>(Xb), n_tokens, int(d_in), ldx, ldxb, H, n_rt, n_ct, n_tiles, chunk,
+                       split0, n_split);
+    ONECOMP_CHECK_LAUNCH();
+    if (n_split > 0) {
+        hipLaunchKernelGGL(gram_merge_kernel, dim3(64, unsigned(n_split)), dim3(256), 0, stream, H, int(d_in), n_split);
+        ONECOMP_CHECK_LAUNCH();
+    }
+    return ONECOMP_OK;
 }
 
 }  // namespace
@@ -647,7 +766,10 @@ onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_i
     const int64_t big = n256 * (n256 + 1) / 2;
     int64_t mid = 0;
     for (int64_t i = 0; i < n128; ++i) mid += n256 - i / 2;
-    const double cost_big = 2.0 * double(ceil_div(big, n_cus)), cost_mid = 1.15 * double(ceil_div(mid, n_cus));
+    // a last round of 256 x 256 tiles that is computed by halves of the token axis costs half a round
+    const double rounds_big = split_tiles(big, n256, d_in, n_tokens, n_cus) > 0 ? double(big / n_cus) + 0.5
+                                                                                : double(ceil_div(big, n_cus));
+    const double cost_big = 2.0 * rounds_big, cost_mid = 1.15 * double(ceil_div(mid, n_cus));
     if (cost_big <= cost_mid) return launch_bf16_ring<RingBig, false>(X, X, n_tokens, d_in, ldx, ldx, H, stream);
     return launch_bf16_ring<RingMid, false>(X, X, n_tokens, d_in, ldx, ldx, H, stream);
 }

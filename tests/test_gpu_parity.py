@@ -130,6 +130,14 @@ def test_gram_big_tiles_bf16():
         assert rel_fro(Hn[np.ix_(i, k)].astype(np.float64), oc.hessian_tile(Xd, i, k)) <= 1e-4
     d = np.arange(8192)
     np.testing.assert_allclose(Hn[d, d], 2.0 * (Xd * Xd).sum(0), rtol=1e-4)
+    # the tiles whose tokens two workgroups share (rows 0 .. 1023, columns from 1024 on): every entry and its mirror
+    i = np.arange(0, 1024)
+    k = np.arange(1024, 2560)
+    assert rel_fro(Hn[np.ix_(i, k)].astype(np.float64), oc.hessian_tile(Xd, i, k)) <= 1e-4
+    # additivity over calls on the same path (second call adds onto a non-zero H)
+    H2 = _gpu_gram(torch.cat([X, X]), chunks=2)
+    assert torch.equal(H2, H2.T)
+    assert rel_fro(H2.cpu().numpy().astype(np.float64), 2.0 * Hn.astype(np.float64)) <= 1e-6
 
 
 def test_gram_full_calibration_set_sampled():
@@ -160,6 +168,15 @@ def test_gram_full_calibration_set_sampled():
             dgot = H[torch.from_numpy(cols).to(DEV), torch.from_numpy(cols).to(DEV)].cpu().numpy()
             np.testing.assert_allclose(dgot, dref, rtol=1e-4)
         del Xs
+    # a block inside the tiles that two workgroups compute by halves of the tokens (tile row 0, tile column 4)
+    i = np.arange(40, 136); k = np.arange(1100, 1196)
+    cols = np.concatenate([i, k])
+    Xs = to_f64(X[:, torch.from_numpy(cols).to(DEV)])
+    ref = oc.hessian_tile(Xs, np.arange(96), np.arange(96, 192))
+    err = rel_fro(H[40:136, 1100:1196].cpu().numpy().astype(np.float64), ref)
+    _announce(f"   block in a token-split tile: rel. Frobenius error {err:.2e}")
+    assert err <= 1e-4
+    del Xs
     H4 = _gpu_gram(X, chunks=4)
     assert torch.equal(H4, H4.T)
     diff = (H4 - H).double().norm().item() / H.double().norm().item()
