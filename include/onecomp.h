@@ -24,7 +24,7 @@
  *
  * Common rules
  *   - Every data pointer is caller-owned DEVICE memory on the current HIP device.
- *     The library never allocates, frees or keeps state between calls.
+ *     The library never allocates or frees, and keeps no state between calls beyond cached device properties.
  *   - All work is enqueued asynchronously on `hip_stream` (a hipStream_t passed as
  *     void*; NULL = the null stream).  Device scalars (`loss`, `info`) are valid
  *     once the stream has been synchronized.

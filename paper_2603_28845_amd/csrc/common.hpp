@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <atomic>
 #include "../../include/onecomp.h"
 
 namespace onecomp {
@@ -23,6 +24,19 @@ typedef double double4v __attribute__((ext_vector_type(4)));
     do {                                                         \
         if (hipGetLastError() != hipSuccess) return ONECOMP_ERR_HIP; \
     } while (0)
+
+// Raises a kernel's limit of dynamic LDS once per device (the attribute belongs to the device's copy of the code).
+// `done` is that kernel's bit mask of devices already prepared; the only host-side state the library keeps is such
+// caches of device properties, safe to use from several host threads and with several devices.
+static inline onecomp_status allow_dynamic_lds(const void* fn, int bytes, std::atomic<uint64_t>& done) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return ONECOMP_ERR_HIP;
+    const uint64_t bit = uint64_t(1) << (dev & 63);
+    if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return ONECOMP_OK;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return ONECOMP_ERR_HIP;
+    if (dev < 64) done.fetch_or(bit, std::memory_order_release);
+    return ONECOMP_OK;
+}
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -675,13 +675,9 @@ onecomp_status launch_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_
     const int n_t = int(ceil_div(d_in, C::TS));
     const int n_tiles = n_t * (n_t + 1) / 2;
     const int chunk = int(ceil_div(n_tiles, 8));
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_kernel<WT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(C::LDS_BYTES)) != hipSuccess)
-            return ONECOMP_ERR_HIP;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(&gram_bf16_kernel<WT>), int(C::LDS_BYTES), lds_ok) != ONECOMP_OK)
+        return ONECOMP_ERR_HIP;
     hipLaunchKernelGGL(gram_bf16_kernel<WT>, dim3(chunk * 8), dim3(GRAM_THREADS), C::LDS_BYTES, stream,
                        static_cast<const uint16_t*>(X), n_tokens, int(d_in), ldx, H, n_t, n_tiles, chunk);
     ONECOMP_CHECK_LAUNCH();
@@ -690,16 +686,15 @@ onecomp_status launch_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_
 
 
 
+// compute units of the current device (0 on failure); looked up once per device
 int device_cus() {
-    static int n_cus = 0;
-    if (n_cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-            return 0;
-        n_cus = v;
-    }
-    return n_cus;
+    static std::atomic<int> cus[64];
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (dev >= 0 && dev < 64 && (v = cus[dev].load(std::memory_order_relaxed)) > 0) return v;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 0;
+    if (dev >= 0 && dev < 64) cus[dev].store(v, std::memory_order_relaxed);
+    return v;
 }
 
 // Number of 256 x 256 tiles of the symmetric Gram computed by halves of the token axis (0: none), see
@@ -732,13 +727,10 @@ onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens,
         split0 = BAND * (BAND + 1) / 2;
     }
     const int chunk = int(ceil_div(n_tiles - n_split, 8));
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gram_bf16_ring_kernel<C, CROSS>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(R::LDS_BYTES)) != hipSuccess)
-            return ONECOMP_ERR_HIP;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(&gram_bf16_ring_kernel<C, CROSS>), int(R::LDS_BYTES),
+                          lds_ok) != ONECOMP_OK)
+        return ONECOMP_ERR_HIP;
     hipLaunchKernelGGL((gram_bf16_ring_kernel<C, CROSS>), dim3(chunk * 8 + 16 * int(ceil_div(n_split, 8))),
                        dim3(R::THREADS), R::LDS_BYTES, stream, static_cast<const uint16_t*>(X),
                        static_cast<const uint16_t*>(Xb), n_tokens, int(d_in), ldx, ldxb, H, n_rt, n_ct, n_tiles, chunk,

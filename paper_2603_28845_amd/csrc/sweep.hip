@@ -1217,13 +1217,9 @@ SweepWs carve(void* ws, int64_t d_out, int64_t d_in) {
 
 template <int GB, bool DIRECT>
 onecomp_status launch_panel(const PanelArgs& pa, const TrailArgs& ta, int far_wgs, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&panel_far_kernel<GB, DIRECT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, PANEL_LDS) != hipSuccess)
-            return ONECOMP_ERR_HIP;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(&panel_far_kernel<GB, DIRECT>), PANEL_LDS, lds_ok) != ONECOMP_OK)
+        return ONECOMP_ERR_HIP;
     const int n_panel = int(ceil_div(pa.d_out, ROWS));
     hipLaunchKernelGGL((panel_far_kernel<GB, DIRECT>), dim3(unsigned(n_panel + far_wgs)), dim3(256), PANEL_LDS, stream,
                        pa, ta, n_panel);
@@ -1233,13 +1229,9 @@ onecomp_status launch_panel(const PanelArgs& pa, const TrailArgs& ta, int far_wg
 
 template <int GB>
 onecomp_status launch_block(const BlockArgs& a, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&block_kernel<GB>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(BLOCK_LDS)) != hipSuccess)
-            return ONECOMP_ERR_HIP;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(&block_kernel<GB>), int(BLOCK_LDS), lds_ok) != ONECOMP_OK)
+        return ONECOMP_ERR_HIP;
     hipLaunchKernelGGL(block_kernel<GB>, dim3(unsigned(ceil_div(a.d_out, ROWS))), dim3(BLOCK_THREADS), BLOCK_LDS, stream,
                        a);
     ONECOMP_CHECK_LAUNCH();
@@ -1283,13 +1275,9 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
                        int(d_in), w.sc, w.Uh, w.Ul);
     ONECOMP_CHECK_LAUNCH();
 
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&trailing_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, int(tg::LDS_BYTES)) != hipSuccess)
-            return ONECOMP_ERR_HIP;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(&trailing_kernel), int(tg::LDS_BYTES), lds_ok) != ONECOMP_OK)
+        return ONECOMP_ERR_HIP;
     TrailArgs t;
     t.Wf = w.Wf; t.Dh = w.Dh; t.Dl = w.Dl; t.Uh = w.Uh; t.Ul = w.Ul; t.sc = w.sc;
     t.ek = 0; t.K = 0; t.u0 = 0; t.c0 = 0; t.c1 = 0; t.n_nt = 0; t.chunk = 0;
@@ -1347,8 +1335,10 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
             pa.Dh = w.Dh + buf * d_buf; pa.Dl = w.Dl + buf * d_buf;
             pa.Bh = w.Bh + size_t(s0 / SBIG) * (B_PER_SB / 2);
             pa.Bl = w.Bl + size_t(s0 / SBIG) * (B_PER_SB / 2);
-            if (group_size == 16) st = direct ? launch_panel<16, true>(pa, t, far_wgs, stream) : launch_panel<16, false>(pa, t, far_wgs, stream);
-            else st = direct ? launch_panel<32, true>(pa, t, far_wgs, stream) : launch_panel<32, false>(pa, t, far_wgs, stream);
+            if (group_size == 16 && direct) st = launch_panel<16, true>(pa, t, far_wgs, stream);
+            else if (group_size == 16) st = launch_panel<16, false>(pa, t, far_wgs, stream);
+            else if (direct) st = launch_panel<32, true>(pa, t, far_wgs, stream);
+            else st = launch_panel<32, false>(pa, t, far_wgs, stream);
             if (st != ONECOMP_OK) return st;
             buf ^= 1; p0 = s0; p1 = s1;
         }
