@@ -194,6 +194,11 @@ def main():
                     help="inverse: the factor call returns U with U^T U = (H + lambda I)^-1 (Sec. 4.2.1) and the sweep "
                          "propagates through it; block: one Cholesky only, the sweep runs on the block form (same codes "
                          "up to ties; groups up to 128 columns)")
+    ap.add_argument("--group-size", type=int, default=0,
+                    help="override the workload's group size (d_in = one group per row, the per-channel setting of the "
+                         "paper's Table 3); 0 = as configured")
+    ap.add_argument("--grid", default="minmax", choices=["minmax", "symmetric"],
+                    help="grid of the sweep: min-max (Eq. (2), the configured workloads) or symmetric (Eq. (3))")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (accumulate, factor, quantize) in a HIP graph after the warm-up and time "
                          "replays of it; per-phase times are then not available (reported as the eager warm-up's)")
@@ -221,6 +226,8 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.workload]
+    if args.group_size > 0:
+        cfg = synth.scaled(cfg, group_size=args.group_size)
     d_out, d_in, T = cfg.d_out, cfg.d_in, cfg.n_tokens
 
     W = synth.make_weight(cfg, dev)
@@ -268,7 +275,7 @@ def main():
         e[2].record()
         if only in (None, "sweep"):
             og.onecomp_quantize_layer(W, U, cfg.bits, cfg.group_size, perm=perm, workspace=ws_q, out=out,
-                                      form=form)
+                                      form=form, grid=args.grid)
         e[3].record()
         if record is not None:
             record.append(e)
@@ -321,7 +328,8 @@ def main():
 
     # the same step with the factor in block form (one Cholesky, no triangular inverse), reported next to the headline
     alt = None
-    if phase == "all" and args.factor_form == "inverse" and cfg.group_size <= 128 and d_in % 128 == 0:
+    if phase == "all" and args.factor_form == "inverse" and (cfg.group_size <= 128 or cfg.group_size == d_in) \
+            and d_in % 128 == 0:
         for _ in range(args.warmup):
             step(form="block")
         torch.cuda.synchronize()
@@ -391,7 +399,7 @@ def main():
         "dtype": "bf16 inputs, f32 accumulate and sweep, f64 factor" if cfg.dtype == torch.bfloat16 else "f32 (f64 factor)",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: W {d_out}x{d_in} {str(cfg.dtype).split('.')[-1]}, {T} tokens, "
-                               f"{cfg.bits}-bit, group {cfg.group_size}, damp {cfg.damp}, act_order {cfg.act_order}, "
+                               f"{cfg.bits}-bit, group {cfg.group_size}, {args.grid} grid, damp {cfg.damp}, act_order {cfg.act_order}, "
                                f"block 128, {n_calls} accumulate call(s), factor form {args.factor_form}"
                                + (", HIP graph replay" if args.graph else "")
                                + ("" if phase == "all" else f" [PROFILING RUN: only phase '{phase}' timed, value is not the metric]")},

@@ -199,9 +199,9 @@ onecomp_status onecomp_quantize_layer_grid(const void* W, onecomp_dtype w_dtype,
  * the workspace accumulates c_k = sum_i (w_i - w^_i) R_ik / R_kk over the finished columns i of earlier blocks
  * (deviations from the ORIGINAL weights; 22-bit operands, fp32 sum, as described at onecomp_quantize_layer) and a
  * block starts from  w_b + c (U_bb rows divided by their diagonal)  in fp32.  Outputs and their meaning are
- * unchanged; results agree with the inverse form up to rounding.  ONECOMP_FACTOR_BLOCK needs group_size <= 128
- * (wider groups take their grid from columns of later blocks, whose compensated values this form does not hold):
- * otherwise ONECOMP_ERR_UNSUPPORTED.
+ * unchanged; results agree with the inverse form up to rounding.  ONECOMP_FACTOR_BLOCK needs group_size <= 128 or
+ * group_size == d_in (one group per row, whose grid comes from the original weights); other wide groups take their
+ * grid from columns of later blocks, whose compensated values this form does not hold: ONECOMP_ERR_UNSUPPORTED.
  */
 onecomp_status onecomp_quantize_layer_form(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
                                            const float* F, onecomp_factor_form form, const int32_t* perm,

@@ -389,6 +389,8 @@ struct PanelArgs {
     const Scalars* sc;
     float* rowloss;
     int d_out, d_in, s0, nb, lgG, n_g, ldD;
+    int wide_g;             // >= 0: the whole super-block lies in group wide_g, whose scale and zero-point are already
+                            // in scales / zeros (groups of whole super-blocks, or one group per row); lgG is then 7
     float qmax;             // highest code of the grid
     float qs;               // 0: min-max grid of Eq. (2); > 0: symmetric grid of Eq. (3) with zero-point qs
 };
@@ -434,11 +436,20 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
     const float f_d = a.sc->f_d, f_all = a.sc->f_all, f_inv = a.sc->f_inv;
     const uint32_t ldsU = uint32_t(uintptr_t((ONECOMP_LDS char*)psm));
     float s = 1.f, rs = 1.f, z = 0.f, lossacc = 0.f;
+    if (a.wide_g >= 0) {
+        s = a.scales[int64_t(grow) * a.n_g + a.wide_g];
+        z = a.zeros[int64_t(grow) * a.n_g + a.wide_g];
+        rs = 1.0f / s;
+    }
 
 #pragma unroll 1
     for (int b = 0; b < a.nb; ++b) {
         const int j0 = a.s0 + b * SB;
         __syncthreads();   // everybody is done with the previous block's tiles
+        if (a.wide_g >= 0 && sl == 0) {   // published by the barriers below, long before the first use
+            sS[qrow * 8] = s;
+            sZ[qrow * 8] = z;
+        }
         // ---- U diagonal block -> sU, two rows (1 KB) per wave load, no registers involved
         {
             const float* ub = a.U + int64_t(j0) * d_in + j0;
@@ -631,7 +642,7 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                                 mn = dpp_quad<quad_bcast(j / 8)>(mn);
                                 mx = dpp_quad<quad_bcast(j / 8)>(mx);
                             } else {
-                                fresh = (col & (G - 1)) == 0;
+                                fresh = a.wide_g < 0 && (col & (G - 1)) == 0;
                                 if (fresh) {   // uniform: the group's G <= 128 columns are current in sW
                                     const float* gp = sW + qrow * SP + jb + sl;
                                     mn = gp[0]; mx = gp[0];
@@ -1127,6 +1138,49 @@ __global__ __launch_bounds__(256) void panel_far_kernel(PanelArgs pa, TrailArgs 
     else trailing_tile<3>(ta, blockIdx.x - n_panel, dyn_lds);
 }
 
+// Scale and zero-point of one wide group (columns g0 .. g0 + G - 1 of every row) from the values in Wsrc, which the
+// caller guarantees to be current: the original weights for the first group of a row, the working copy after the
+// feedback of all earlier columns has been applied for a later one.  One workgroup per row.
+template <typename T>
+__global__ __launch_bounds__(256) void group_params_kernel(const T* __restrict__ Wsrc, int d_out, int d_in, int g0, int G,
+                                                          float qmax, float qs, int n_g, int g_idx,
+                                                          float* __restrict__ scales, float* __restrict__ zeros) {
+    __shared__ float smn[256], smx[256];
+    for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {
+        const T* row = Wsrc + r * d_in + g0;
+        float mn = to_f32<T>(row[0]), mx = mn;
+        for (int c = threadIdx.x; c < G; c += 256) {
+            const float v = to_f32<T>(row[c]);
+            mn = fminf(mn, v); mx = fmaxf(mx, v);
+        }
+        smn[threadIdx.x] = mn; smx[threadIdx.x] = mx;
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if (int(threadIdx.x) < w) {
+                smn[threadIdx.x] = fminf(smn[threadIdx.x], smn[threadIdx.x + w]);
+                smx[threadIdx.x] = fmaxf(smx[threadIdx.x], smx[threadIdx.x + w]);
+            }
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            mn = smn[0]; mx = smx[0];
+            float s, z;
+            if (qs > 0.f) {
+                s = fmaxf(fabsf(mn), fabsf(mx)) / qs;
+                if (s == 0.f) s = 1.f;
+                z = qs;
+            } else {
+                s = (mx - mn) / qmax;
+                if (s == 0.f) s = 1.f;
+                z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
+            }
+            scales[r * n_g + g_idx] = s;
+            zeros[r * n_g + g_idx] = z;
+        }
+        __syncthreads();
+    }
+}
+
 // Column order (activation ordering): the sweep stages its codes in sweep order (coalesced rows); the caller's
 // arrays are then written in ORIGINAL column order, coalesced, gathering from the staged row (a row is a few KB and
 // stays in cache).  W^ is recomputed as s (q - z), the same fp32 operations the sweep used.
@@ -1254,7 +1308,11 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
                          float* scales, float* zeros, float* W_hat, float* loss, void* workspace, hipStream_t stream) {
     (void)block;
     const bool direct = form == ONECOMP_FACTOR_BLOCK;   // block form of the factor: see panel_body
-    if (direct && group_size > SB) return ONECOMP_ERR_UNSUPPORTED;
+    // Wide groups whose parameters can be fixed before the sweep enters them: one group per row (its values are the
+    // original weights), or groups made of whole super-blocks (all earlier feedback has reached the working copy
+    // once the previous super-block's far update is complete).  These run through the panel kernel.
+    const bool wide_static = group_size > SB && (group_size == d_in || group_size % SBIG == 0);
+    if (direct && group_size > SB && group_size != d_in) return ONECOMP_ERR_UNSUPPORTED;
     SweepWs w = carve(workspace, d_out, d_in);
     hipLaunchKernelGGL(init_scalars_kernel, dim3(1), dim3(1), 0, stream, w.sc);
     ONECOMP_CHECK_LAUNCH();
@@ -1303,7 +1361,7 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
     };
 
     onecomp_status st;
-    if (group_size <= SB) {
+    if (group_size <= SB || wide_static) {
         // Groups no wider than a block: one launch sweeps a super-block of 512 columns (the feedback between its
         // blocks is applied inside the panel kernel).  The columns beyond a super-block receive its feedback once,
         // with K = its width: first those of the next super-block, then, in the same launch as the next panel,
@@ -1321,16 +1379,38 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
         pa.d_out = int(d_out); pa.d_in = int(d_in); pa.n_g = int(d_in / group_size); pa.ldD = int(ld_d(d_out));
         pa.lgG = 0;
         while ((1 << pa.lgG) < group_size) ++pa.lgG;
+        if (wide_static) pa.lgG = 7;
+        pa.wide_g = -1;
         pa.qs = grid == ONECOMP_GRID_SYMMETRIC ? float((1 << (bits - 1)) - 1) : 0.f;
         pa.qmax = grid == ONECOMP_GRID_SYMMETRIC ? 2.f * pa.qs : float((1 << bits) - 1);
         int buf = 0, p0 = 0, p1 = 0;   // previous super-block: residual buffer and column range
         for (int s0 = 0; s0 < d_in; s0 += SBIG) {
             const int s1 = int(d_in < int64_t(s0) + SBIG ? d_in : int64_t(s0) + SBIG);
             int far_wgs = 0;
-            if (s0 > 0) {
+            const bool group_start = wide_static && s0 % group_size == 0;
+            if (s0 > 0 && group_start) {   // every later column must be current before the group's range is taken
+                if ((st = trailing(buf ^ 1, 0, p1 - p0, p0, s0, int(d_in))) != ONECOMP_OK) return st;
+            } else if (s0 > 0) {
                 if ((st = trailing(buf ^ 1, 0, p1 - p0, p0, s0, s1)) != ONECOMP_OK) return st;
                 far_wgs = set_trailing(buf ^ 1, 0, p1 - p0, p0, s1, int(d_in));
             }
+            if (group_start) {
+                const dim3 pgrid{unsigned(d_out < 2048 ? d_out : 2048)};
+                const int g_idx = s0 / group_size;
+                if (!direct)
+                    hipLaunchKernelGGL(group_params_kernel<float>, pgrid, dim3(256), 0, stream, w.Wf, int(d_out), int(d_in),
+                                       s0, group_size, pa.qmax, pa.qs, pa.n_g, g_idx, scales, zeros);
+                else if (pa.w0_bf16)
+                    hipLaunchKernelGGL(group_params_kernel<uint16_t>, pgrid, dim3(256), 0, stream,
+                                       static_cast<const uint16_t*>(pa.W0), int(d_out), int(d_in), s0, group_size, pa.qmax,
+                                       pa.qs, pa.n_g, g_idx, scales, zeros);
+                else
+                    hipLaunchKernelGGL(group_params_kernel<float>, pgrid, dim3(256), 0, stream,
+                                       static_cast<const float*>(pa.W0), int(d_out), int(d_in), s0, group_size, pa.qmax,
+                                       pa.qs, pa.n_g, g_idx, scales, zeros);
+                ONECOMP_CHECK_LAUNCH();
+            }
+            if (wide_static) pa.wide_g = s0 / group_size;
             pa.s0 = s0; pa.nb = (s1 - s0) / SB;
             pa.Dh = w.Dh + buf * d_buf; pa.Dl = w.Dl + buf * d_buf;
             pa.Bh = w.Bh + size_t(s0 / SBIG) * (B_PER_SB / 2);

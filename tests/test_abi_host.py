@@ -192,8 +192,7 @@ def test_quantize_form_argument_checks(lib):
 
     assert call(form=2) == UNSUPPORTED
     assert call(form=-1) == UNSUPPORTED
-    assert call(G=256) == UNSUPPORTED            # block form: groups no wider than a block
-    assert call(d_in=384, G=384) == UNSUPPORTED
+    assert call(d_in=512, G=256) == UNSUPPORTED  # block form: groups no wider than a block, or one group per row
     assert call(grid=2) == UNSUPPORTED
     assert call(dt=3) == UNSUPPORTED
     assert call(bits=5) == UNSUPPORTED

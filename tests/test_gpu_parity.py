@@ -70,7 +70,12 @@ def _check_sweep(W, U32, bits, G, perm=None, rows=None, min_agree=0.999, grid="m
     _announce(f"   raw agreement {st['raw_agree']:.6f}, tie flips {st['tie_flips']}, real {len(st['real_mismatches'])}")
     assert st["real_mismatches"] == []
     assert st["final_agree"] == 1.0
-    assert st["raw_agree"] >= min_agree
+    # Raw agreement: 99.9 % of the entries.  A flip at a tie can change every later code of its row, so on a layer
+    # of few rows one legitimate flip alone may cost more than 0.1 %: there the bar is what the counted flips can
+    # account for (at most one row's worth of entries each), with the number of flips itself bounded.
+    n_cmp = len(sel)
+    assert st["raw_agree"] >= min(min_agree, 1.0 - st["tie_flips"] / n_cmp)
+    assert st["tie_flips"] <= max(2, n_cmp // 50)
     orc = st["oracle"]
     np.testing.assert_allclose(S[sel], orc["scales"], rtol=1e-5)
     np.testing.assert_array_equal(Z[sel], orc["zeros"])
@@ -283,7 +288,7 @@ def test_block_form_argument_checks():
     W = torch.zeros((4, 512), dtype=torch.float32, device=DEV)
     F = torch.eye(512, dtype=torch.float32, device=DEV)
     with pytest.raises(og.OnecompError) as ei:
-        og.onecomp_quantize_layer(W, F, 4, 256, form="block")     # group wider than a block
+        og.onecomp_quantize_layer(W, F, 4, 256, form="block")     # group wider than a block, not the whole row
     assert ei.value.code == 2
 
 
@@ -330,6 +335,9 @@ def test_sweep_c1():
     (4, 64, 130, 1664, torch.bfloat16, True),      # several super-blocks, the last one partial (13 blocks)
     (4, 16, 64, 640, torch.float32, False),
     (2, 32, 100, 1152, torch.bfloat16, True),
+    (4, 512, 96, 1536, torch.bfloat16, False),     # groups of one super-block each: parameters fixed at the group start
+    (3, 1024, 33, 2048, torch.float32, True),      # groups of two super-blocks
+    (4, 1664, 130, 1664, torch.bfloat16, False),   # one group per row, last super-block partial
 ])
 def test_sweep_variants(bits, G, d_out, d_in, dtype, act):
     _announce(f"sweep b{bits} g{G} {d_out}x{d_in} {dtype} act={act}")
@@ -362,6 +370,8 @@ def _layer_block(d_out, d_in, n_tok, seed, dtype=torch.float32, act=False):
     (2, 32, 100, 1152, torch.bfloat16, True, "minmax"),
     (4, 128, 100, 1024, torch.bfloat16, False, "symmetric"),
     (3, 64, 33, 640, torch.float32, True, "symmetric"),
+    (4, 1280, 40, 1280, torch.bfloat16, False, "symmetric"),      # one group per row (the setting of the paper's Tables)
+    (3, 1152, 65, 1152, torch.float32, True, "minmax"),
 ])
 def test_sweep_block_form(bits, G, d_out, d_in, dtype, act, grid):
     """The sweep fed with the block form of the factor against the oracle's sweep with the inverse factor."""
