@@ -8,18 +8,18 @@
 //   (w_j / s and the division by U_jj are multiplications by correctly rounded reciprocals),
 //   w_k -= e U_jk for k > j.
 //
-// gfx950 schedule (lazy batch of B = 128 columns inside super-blocks of 512, right-looking):
-//   block kernel    one LANE per output row: the row's 128 current values live in registers, the 128
-//                   dependent column steps are fully unrolled, so there is no cross-lane traffic at all in
-//                   the sequential part; group min / max are in-register reductions.  The 128 x 128
-//                   diagonal block of U sits in LDS and is read with wave-uniform (broadcast) addresses.
-//                   Tiles of W / E / W^ / codes move between HBM and registers through LDS so that every
-//                   global access is a coalesced row segment.
-//   trailing kernel W[:, cols] -= E U[rows, cols] as a split-fp16 MFMA GEMM (three v_mfma_f32_32x32x16_f16 products
-//                   per term, fp32 accuracy), 128 x 256 tile per workgroup, the W tile is loaded straight into
-//                   the accumulators.  Two levels: after each 128-column block only the rest of its 512-column
-//                   super-block is updated (K = 128); the columns beyond are updated once per super-block
-//                   (K = 512), which cuts the read-modify-write traffic on W four-fold.
+// gfx950 schedule (lazy batch of B = 128 columns inside super-blocks of up to 512 columns):
+//   panel kernel    64 rows per workgroup carried through the blocks of a super-block: the feedback between the
+//                   super-block's blocks is applied inside the kernel (split-fp16 MFMAs on operands stored in
+//                   fragment order), the sequential part runs four lanes per row with DPP broadcasts, the rest of
+//                   a block is updated with fp32 MFMAs on tiles in LDS.  See panel_body.
+//   far update      W[:, cols] += D Un[rows, cols] for the columns beyond a super-block, once per super-block
+//                   (K = its width), as a split-fp16 MFMA GEMM (three v_mfma_f32_32x32x16_f16 products per term,
+//                   fp32 accuracy), 128 x 256 tile per workgroup, the W tile loaded straight into the accumulators;
+//                   the part beyond the next super-block shares a launch with the next panel.  See trailing_tile.
+//   Groups wider than a block are runs of whole super-blocks (width 512, 384, 256 or 128, whichever divides the
+//   group; one group per row: 512): their scale and zero-point are fixed by group_params_kernel when the sweep
+//   reaches them, after the far update has brought every later column up to date.
 //   The loss is the sum of e^2 (equal to tr((W-W^) Hd (W-W^)^T) because U Hd U^T = I), kept per row and
 //   reduced in a fixed order.
 #include "common.hpp"
@@ -40,7 +40,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 constexpr int SB = 128;        // lazy-batch block
 constexpr int SBIG = 512;      // super-block: columns beyond it are updated once per 512 columns
-constexpr int ROWS = 64;       // rows per workgroup of the block kernel (one wave)
+constexpr int ROWS = 64;       // rows per workgroup of the panel kernel
 constexpr int SP = SB + 1;     // LDS pitch (floats) of row tiles: lane l reading column c hits bank (l + c) % 32
 
 // ------------------------------------------------------------------------------------------
@@ -130,234 +130,10 @@ __global__ __launch_bounds__(256) void load_kernel(const T* __restrict__ W, int6
     block_max_to(&sc->max_w_bits, m);
 }
 
-// ------------------------------------------------------------------------------------------
-// block kernel
-// ------------------------------------------------------------------------------------------
-struct BlockArgs {
-    float* Wf;              // [d_out x d_in] working copy, sweep order
-    const float* U;         // [d_in x d_in]
-    uint8_t* Q;             // [d_out x d_in] sweep order (the caller's array, or the staging copy under a column order)
-    float* scales;          // [d_out x n_g]
-    float* zeros;
-    float* W_hat;           // or nullptr
-    uint16_t* Dh;           // [SBIG x ldD] transposed residuals -(w - w^) * f_d split into fp16 hi + lo;
-    uint16_t* Dl;           // rows e_col .. e_col+127 are written
-    const Scalars* sc;
-    int e_col, ldD;
-    float* rowloss;         // [d_out]
-    int d_out, d_in, j0, G, n_g;
-    float qmax;             // highest code of the grid
-    float qs;               // 0: min-max grid of Eq. (2); > 0: symmetric grid of Eq. (3) with zero-point qs
-};
-
 constexpr int IB = 32;          // columns swept in registers at a time
-constexpr int QP = SB + 4;      // byte pitch of the code tile
-constexpr int BLOCK_THREADS = 256;
-
-// One workgroup = 64 rows x 128 columns.  The block is swept in 4 inner blocks of 32 columns:
-//   wave 0, one lane per row, runs the 32 dependent column steps of the inner block in registers;
-//   then all 4 waves apply the inner block's 32 errors to the block's remaining columns (kept in LDS),
-//   each wave taking every fourth group of 4 columns, lane = row.
-template <int GB>  // group width seen inside an inner block: 16 (G == 16) or 32 (G >= 32)
-__global__ __launch_bounds__(BLOCK_THREADS) void block_kernel(BlockArgs a) {
-    extern __shared__ __attribute__((aligned(16))) float smem[];
-    float* sU = smem;                      // SB x SB, row j holds U[j0+j][j0 .. j0+127]
-    float* sRd = sU + SB * SB;             // SB reciprocals of the diagonal
-    float* sW = sRd + SB;                  // ROWS x SP : current values; a finished column holds its W^
-    float* sE = sW + ROWS * SP;            // ROWS x SP : errors e
-    uint8_t* sQ = reinterpret_cast<uint8_t*>(sE + ROWS * SP);  // ROWS x QP bytes
-
-    const int tid = threadIdx.x, l = tid & 63, wave = tid >> 6;
-    const int r0 = blockIdx.x * ROWS;
-    const int j0 = a.j0;
-    const int64_t d_in = a.d_in;
-
-    // U block (coalesced rows) and reciprocal diagonal
-    for (int e = tid; e < SB * SB / 4; e += BLOCK_THREADS) {
-        const int rr = e / (SB / 4), c4 = (e % (SB / 4)) * 4;
-        *reinterpret_cast<float4v*>(sU + rr * SB + c4) =
-            *reinterpret_cast<const float4v*>(a.U + (int64_t(j0) + rr) * d_in + j0 + c4);
-    }
-    if (tid < SB) sRd[tid] = 1.0f / a.U[(int64_t(j0) + tid) * d_in + j0 + tid];
-    // W tile: every wave instruction covers 2 rows x 512 B
-    for (int it = wave; it < ROWS / 2; it += 4) {
-        const int rr = it * 2 + (l >> 5), c4 = (l & 31) * 4;
-        const int gr = min(r0 + rr, a.d_out - 1);
-        const float4v v = *reinterpret_cast<const float4v*>(a.Wf + int64_t(gr) * d_in + j0 + c4);
-        sW[rr * SP + c4 + 0] = v[0]; sW[rr * SP + c4 + 1] = v[1];
-        sW[rr * SP + c4 + 2] = v[2]; sW[rr * SP + c4 + 3] = v[3];
-    }
-    __syncthreads();
-
-    const int row = min(r0 + l, a.d_out - 1);
-    const bool row_ok = (r0 + l) < a.d_out;
-    const float qmax = a.qmax;
-    float s = 1.f, rs = 1.f, z = 0.f, loss = 0.f;
-    if (wave == 0 && (j0 % a.G) != 0) {  // block continues a group wider than the block
-        s = a.scales[int64_t(row) * a.n_g + j0 / a.G];
-        z = a.zeros[int64_t(row) * a.n_g + j0 / a.G];
-        rs = 1.0f / s;
-    }
-
-#pragma unroll 1
-    for (int jb = 0; jb < SB; jb += IB) {
-        if (wave == 0) {
-            float w[IB];
-            static_for<0, IB>([&](auto cc) { w[decltype(cc)::value] = sW[l * SP + jb + decltype(cc)::value]; });
-            // Row j of the inner block's U triangle (and 1 / U_jj) is read one step ahead of its use: the reads
-            // do not depend on the sequential chain, so their LDS latency hides behind the previous step.
-            float4v ua[IB / 4], ub[IB / 4];
-            float rdc = sRd[jb], rdn = 0.f;
-            auto load_row = [&](float4v(&dst)[IB / 4], auto jc) __attribute__((always_inline)) {
-                constexpr int j = decltype(jc)::value;
-                static_for<(j + 1) / 4, IB / 4>([&](auto gc) {
-                    constexpr int g = decltype(gc)::value;
-                    dst[g] = *reinterpret_cast<const float4v*>(sU + (jb + j) * SB + jb + 4 * g);
-                });
-            };
-            load_row(ua, std::integral_constant<int, 0>{});
-            static_for<0, IB>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                auto step = [&](float4v(&cur)[IB / 4], float4v(&nxt)[IB / 4]) __attribute__((always_inline)) {
-                    if constexpr (j + 1 < IB) {
-                        load_row(nxt, std::integral_constant<int, j + 1>{});
-                        rdn = sRd[jb + j + 1];
-                    }
-                    if constexpr (j % GB == 0) {
-                        const int col = j0 + jb + j;
-                        bool fresh;
-                        float mn, mx;
-                        if constexpr (GB == 16) {
-                            fresh = true;
-                            mn = w[j]; mx = w[j];
-                            static_for<j + 1, j + 16>([&](auto cc) {
-                                mn = fminf(mn, w[decltype(cc)::value]);
-                                mx = fmaxf(mx, w[decltype(cc)::value]);
-                            });
-                        } else {
-                            fresh = (col % a.G) == 0;
-                            if (fresh) {
-                                // the group's columns inside this block are current in LDS; a group wider than
-                                // the block continues in the working copy (already updated by earlier blocks)
-                                const int in_blk = min(a.G, SB - jb);
-                                mn = mx = sW[l * SP + jb];
-                                for (int c = 1; c < in_blk; ++c) {
-                                    const float v = sW[l * SP + jb + c];
-                                    mn = fminf(mn, v); mx = fmaxf(mx, v);
-                                }
-                                const float* wr = a.Wf + int64_t(row) * d_in + j0;
-                                for (int c = SB; c < a.G; ++c) { const float v = wr[c]; mn = fminf(mn, v); mx = fmaxf(mx, v); }
-                            }
-                        }
-                        if (fresh) {
-                            if (a.qs > 0.f) {
-                                s = fmaxf(fabsf(mn), fabsf(mx)) / a.qs;
-                                if (s == 0.f) s = 1.f;
-                                z = a.qs;
-                            } else {
-                                s = (mx - mn) / qmax;
-                                if (s == 0.f) s = 1.f;
-                                z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
-                            }
-                            rs = 1.0f / s;
-                            if (row_ok) {
-                                a.scales[int64_t(row) * a.n_g + col / a.G] = s;
-                                a.zeros[int64_t(row) * a.n_g + col / a.G] = z;
-                            }
-                        }
-                    }
-                    const float wj = w[j];
-                    const float q = fminf(fmaxf(rintf(wj * rs) + z, 0.f), qmax);   // w / s as w * fl(1 / s)
-                    const float wh = s * (q - z);
-                    const float e = (wj - wh) * rdc;
-                    // feedback inside the inner block: w_k -= e U_jk, j < k < 32; the next column first, it
-                    // heads the next step's dependency chain
-                    static_for<(j + 1) / 4, IB / 4>([&](auto gc) {
-                        constexpr int g = decltype(gc)::value;
-                        constexpr int c4 = 4 * g;
-                        if constexpr (c4 + 0 > j) w[c4 + 0] = __builtin_fmaf(-e, cur[g][0], w[c4 + 0]);
-                        if constexpr (c4 + 1 > j) w[c4 + 1] = __builtin_fmaf(-e, cur[g][1], w[c4 + 1]);
-                        if constexpr (c4 + 2 > j) w[c4 + 2] = __builtin_fmaf(-e, cur[g][2], w[c4 + 2]);
-                        if constexpr (c4 + 3 > j) w[c4 + 3] = __builtin_fmaf(-e, cur[g][3], w[c4 + 3]);
-                    });
-                    loss += e * e;
-                    sE[l * SP + jb + j] = e;
-                    sW[l * SP + jb + j] = wh;
-                    sQ[l * QP + jb + j] = uint8_t(q);
-                    rdc = rdn;
-                };
-                if constexpr (j % 2 == 0) step(ua, ub);
-                else step(ub, ua);
-            });
-        }
-        __syncthreads();
-        // remaining columns of the block: w_c -= sum_i e_i U[jb+i][c], c >= jb + 32
-        const int cs = jb + IB;
-        if (cs < SB) {
-            float ev[IB];
-            static_for<0, IB>([&](auto ic) { ev[decltype(ic)::value] = sE[l * SP + jb + decltype(ic)::value]; });
-            for (int c = cs + 4 * wave; c < SB; c += 16) {
-                float a0 = sW[l * SP + c + 0], a1 = sW[l * SP + c + 1], a2 = sW[l * SP + c + 2], a3 = sW[l * SP + c + 3];
-                static_for<0, IB>([&](auto ic) {
-                    constexpr int i = decltype(ic)::value;
-                    const float4v u = *reinterpret_cast<const float4v*>(sU + (jb + i) * SB + c);
-                    a0 = __builtin_fmaf(-ev[i], u[0], a0);
-                    a1 = __builtin_fmaf(-ev[i], u[1], a1);
-                    a2 = __builtin_fmaf(-ev[i], u[2], a2);
-                    a3 = __builtin_fmaf(-ev[i], u[3], a3);
-                });
-                sW[l * SP + c + 0] = a0; sW[l * SP + c + 1] = a1; sW[l * SP + c + 2] = a2; sW[l * SP + c + 3] = a3;
-            }
-        }
-        __syncthreads();
-    }
-    if (wave == 0 && row_ok) a.rowloss[row] += loss;
-
-    // residual w - w^ = e U_jj, negated, scaled by a power of two and split into fp16 hi + lo
-    // (hi = rne(x), lo = rne(x - hi): 22 significant bits); saturated far above anything a sweep produces.
-    // Written transposed (column-major: the trailing GEMM wants both operands k-major), 8 rows = 16 bytes per
-    // store; rows past d_out hold copies of the last row and are never used.
-    {
-        const float f_d = a.sc->f_d;
-        for (int it = tid; it < SB * (ROWS / 8); it += BLOCK_THREADS) {
-            const int c = it / (ROWS / 8), r8 = (it % (ROWS / 8)) * 8;
-            const float ujj = sU[c * SB + c] * f_d;
-            short8v dh, dl;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float x = -sE[(r8 + e) * SP + c] * ujj;
-                x = fminf(fmaxf(x, -60000.f), 60000.f);
-                const _Float16 h = (_Float16)x;
-                const _Float16 lo = (_Float16)(x - (float)h);
-                dh[e] = __builtin_bit_cast(short, h);
-                dl[e] = __builtin_bit_cast(short, lo);
-            }
-            const int64_t off = int64_t(a.e_col + c) * a.ldD + r0 + r8;
-            *reinterpret_cast<short8v*>(a.Dh + off) = dh;
-            *reinterpret_cast<short8v*>(a.Dl + off) = dl;
-        }
-    }
-    // tiles out: W^ and codes, in sweep order (with a column order the caller's arrays are filled by
-    // unpermute_kernel from the staged codes)
-    for (int it = wave; it < ROWS / 2; it += 4) {
-        const int rr = it * 2 + (l >> 5), c4 = (l & 31) * 4;
-        const int gr = r0 + rr;
-        if (gr >= a.d_out) continue;
-        if (a.W_hat) {
-            float4v h;
-            h[0] = sW[rr * SP + c4 + 0]; h[1] = sW[rr * SP + c4 + 1];
-            h[2] = sW[rr * SP + c4 + 2]; h[3] = sW[rr * SP + c4 + 3];
-            *reinterpret_cast<float4v*>(a.W_hat + int64_t(gr) * d_in + j0 + c4) = h;
-        }
-        *reinterpret_cast<uint32_t*>(a.Q + int64_t(gr) * d_in + j0 + c4) =
-            *reinterpret_cast<const uint32_t*>(sQ + rr * QP + c4);
-    }
-}
-
-constexpr size_t BLOCK_LDS = (size_t(SB) * SB + SB + 2 * size_t(ROWS) * SP) * sizeof(float) + size_t(ROWS) * QP;
 
 // ------------------------------------------------------------------------------------------
-// panel kernel (group sizes up to the block width): one launch sweeps a whole super-block of up to four
+// panel kernel: one launch sweeps a whole super-block of up to four
 // 128-column blocks for 64 rows per workgroup.  Rows never interact, so the workgroup carries its rows through
 // the blocks without any grid-wide step in between:
 //   near update   (left-looking) before block b is swept, its columns receive the feedback of blocks 0 .. b-1 of
@@ -804,14 +580,15 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
     if (sl == 0 && row_ok) a.rowloss[grow] += lossacc;
 }
 
-// Fragments of the normalized U blocks the panel kernel's near updates multiply with: for super-block S, block
-// pair p = b (b - 1) / 2 + b' (b' < b), k-step ks, column tile nt, lane L:
-//   Un[512 S + 128 b' + 16 ks + 8 (L/32) + e][512 S + 128 b + 32 nt + L%32] * f_u,  e = 0 .. 7,  fp16 hi and lo.
+// Fragments of the normalized U blocks the panel kernel's near updates multiply with: for super-block S (sbw
+// columns wide, gridDim.x = its number of block pairs), block pair p = b (b - 1) / 2 + b' (b' < b), k-step ks,
+// column tile nt, lane L:
+//   Un[sbw S + 128 b' + 16 ks + 8 (L/32) + e][sbw S + 128 b + 32 nt + L%32] * f_u,  e = 0 .. 7,  fp16 hi and lo.
 __global__ __launch_bounds__(256) void nearfrag_kernel(const float* __restrict__ U, int n, const Scalars* __restrict__ sc,
-                                                      uint16_t* __restrict__ Bh, uint16_t* __restrict__ Bl) {
+                                                      uint16_t* __restrict__ Bh, uint16_t* __restrict__ Bl, int sbw) {
     const int S = blockIdx.y, p = blockIdx.x;
     const int b = (p >= 3) ? 3 : (p >= 1 ? 2 : 1), bp = p - b * (b - 1) / 2;
-    const int k00 = S * SBIG + bp * SB, n00 = S * SBIG + b * SB;
+    const int k00 = S * sbw + bp * SB, n00 = S * sbw + b * SB;
     if (n00 >= n) return;
     const float f_u = sc->f_u;
     for (int it = threadIdx.x; it < 8 * 4 * 64; it += 256) {
@@ -828,7 +605,7 @@ __global__ __launch_bounds__(256) void nearfrag_kernel(const float* __restrict__
             h8[e] = __builtin_bit_cast(short, h);
             l8[e] = __builtin_bit_cast(short, lo);
         }
-        const int64_t off = ((int64_t(S) * 6 + p) * (8 * 4 * 64) + it) * 8;
+        const int64_t off = ((int64_t(S) * gridDim.x + p) * (8 * 4 * 64) + it) * 8;
         *reinterpret_cast<short8v*>(Bh + off) = h8;
         *reinterpret_cast<short8v*>(Bl + off) = l8;
     }
@@ -897,7 +674,7 @@ __global__ __launch_bounds__(256) void split_kernel(const float* __restrict__ U,
 
 // ------------------------------------------------------------------------------------------
 // trailing update:  Wf[:, c0 .. c1) += f_inv * D[:, ek .. ek+K) * Un[u0 .. u0+K, c0 .. c1)
-// with D = -(w - w^) f_d (stored transposed, Dt[k][row], by the block kernel) and Un = U_jk / U_jj f_u
+// with D = -(w - w^) f_d (stored transposed, Dt[k][row], by the panel kernel) and Un = U_jk / U_jj f_u
 // (split_kernel).
 //
 // fp32 accuracy from fp16 MFMAs: both operands are split x = hi + lo (fp16 each, |lo| <= 2^-11 |hi|) and
@@ -1245,7 +1022,7 @@ struct SweepWs {
 constexpr size_t F_PER_WG = size_t(3) * 8 * 2 * 64 * 8 * 2;    // bytes of Fh (or Fl) per workgroup of the panel kernel
 constexpr size_t B_PER_SB = size_t(6) * 8 * 4 * 64 * 8 * 2;    // bytes of Bh (or Bl) per super-block
 
-// leading dimension of the transposed residual panels: whole 64-row workgroups of the block kernel
+// leading dimension of the transposed residual panels: whole 64-row workgroups of the panel kernel
 inline int64_t ld_d(int64_t d_out) { return ceil_div(d_out, ROWS) * ROWS; }
 
 SweepWs carve(void* ws, int64_t d_out, int64_t d_in) {
@@ -1281,17 +1058,6 @@ onecomp_status launch_panel(const PanelArgs& pa, const TrailArgs& ta, int far_wg
     return ONECOMP_OK;
 }
 
-template <int GB>
-onecomp_status launch_block(const BlockArgs& a, hipStream_t stream) {
-    static std::atomic<uint64_t> lds_ok{0};
-    if (allow_dynamic_lds(reinterpret_cast<const void*>(&block_kernel<GB>), int(BLOCK_LDS), lds_ok) != ONECOMP_OK)
-        return ONECOMP_ERR_HIP;
-    hipLaunchKernelGGL(block_kernel<GB>, dim3(unsigned(ceil_div(a.d_out, ROWS))), dim3(BLOCK_THREADS), BLOCK_LDS, stream,
-                       a);
-    ONECOMP_CHECK_LAUNCH();
-    return ONECOMP_OK;
-}
-
 }  // namespace
 
 size_t sweep_workspace_bytes(int64_t d_out, int64_t d_in, int block) {
@@ -1311,7 +1077,14 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
     // Wide groups whose parameters can be fixed before the sweep enters them: one group per row (its values are the
     // original weights), or groups made of whole super-blocks (all earlier feedback has reached the working copy
     // once the previous super-block's far update is complete).  These run through the panel kernel.
-    const bool wide_static = group_size > SB && (group_size == d_in || group_size % SBIG == 0);
+    const bool wide_static = group_size > SB;
+    // super-block width: 512 columns, or for wide groups the largest of 512 / 384 / 256 / 128 that divides the group,
+    // so that a group is a run of whole super-blocks
+    int sbw = SBIG;
+    if (wide_static && group_size != d_in)
+        for (int c = SBIG; c >= SB; c -= SB)
+            if (group_size % c == 0) { sbw = c; break; }
+    const int sb_pairs = (sbw / SB) * (sbw / SB - 1) / 2;   // block pairs (b' < b) inside a super-block
     if (direct && group_size > SB && group_size != d_in) return ONECOMP_ERR_UNSUPPORTED;
     SweepWs w = carve(workspace, d_out, d_in);
     hipLaunchKernelGGL(init_scalars_kernel, dim3(1), dim3(1), 0, stream, w.sc);
@@ -1361,14 +1134,16 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
     };
 
     onecomp_status st;
-    if (group_size <= SB || wide_static) {
+    {
         // Groups no wider than a block: one launch sweeps a super-block of 512 columns (the feedback between its
         // blocks is applied inside the panel kernel).  The columns beyond a super-block receive its feedback once,
         // with K = its width: first those of the next super-block, then, in the same launch as the next panel,
         // the rest.
-        hipLaunchKernelGGL(nearfrag_kernel, dim3(6, unsigned(ceil_div(d_in, SBIG))), dim3(256), 0, stream, U, int(d_in),
-                           w.sc, w.Bh, w.Bl);
-        ONECOMP_CHECK_LAUNCH();
+        if (sb_pairs > 0) {
+            hipLaunchKernelGGL(nearfrag_kernel, dim3(unsigned(sb_pairs), unsigned(ceil_div(d_in, sbw))), dim3(256), 0,
+                               stream, U, int(d_in), w.sc, w.Bh, w.Bl, sbw);
+            ONECOMP_CHECK_LAUNCH();
+        }
         PanelArgs pa;
         pa.Wf = w.Wf; pa.U = U;
         // block form: where the panel finds the original weights; under a column order, the gathered fp32 copy
@@ -1384,8 +1159,8 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
         pa.qs = grid == ONECOMP_GRID_SYMMETRIC ? float((1 << (bits - 1)) - 1) : 0.f;
         pa.qmax = grid == ONECOMP_GRID_SYMMETRIC ? 2.f * pa.qs : float((1 << bits) - 1);
         int buf = 0, p0 = 0, p1 = 0;   // previous super-block: residual buffer and column range
-        for (int s0 = 0; s0 < d_in; s0 += SBIG) {
-            const int s1 = int(d_in < int64_t(s0) + SBIG ? d_in : int64_t(s0) + SBIG);
+        for (int s0 = 0; s0 < d_in; s0 += sbw) {
+            const int s1 = int(d_in < int64_t(s0) + sbw ? d_in : int64_t(s0) + sbw);
             int far_wgs = 0;
             const bool group_start = wide_static && s0 % group_size == 0;
             if (s0 > 0 && group_start) {   // every later column must be current before the group's range is taken
@@ -1413,43 +1188,14 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
             if (wide_static) pa.wide_g = s0 / group_size;
             pa.s0 = s0; pa.nb = (s1 - s0) / SB;
             pa.Dh = w.Dh + buf * d_buf; pa.Dl = w.Dl + buf * d_buf;
-            pa.Bh = w.Bh + size_t(s0 / SBIG) * (B_PER_SB / 2);
-            pa.Bl = w.Bl + size_t(s0 / SBIG) * (B_PER_SB / 2);
+            pa.Bh = w.Bh + size_t(s0 / sbw) * sb_pairs * (8 * 4 * 64 * 8);
+            pa.Bl = w.Bl + size_t(s0 / sbw) * sb_pairs * (8 * 4 * 64 * 8);
             if (group_size == 16 && direct) st = launch_panel<16, true>(pa, t, far_wgs, stream);
             else if (group_size == 16) st = launch_panel<16, false>(pa, t, far_wgs, stream);
             else if (direct) st = launch_panel<32, true>(pa, t, far_wgs, stream);
             else st = launch_panel<32, false>(pa, t, far_wgs, stream);
             if (st != ONECOMP_OK) return st;
             buf ^= 1; p0 = s0; p1 = s1;
-        }
-    } else {
-        // Groups wider than a block: a group's parameters need the current values of all its columns when the
-        // sweep reaches its first column.  Two-level lazy batch with super-blocks that never cut a group except at
-        // its start: whole groups per super-block while they fit into 512 columns, else pieces of up to 512
-        // columns counted from the group's start.  Inside a super-block every 128-column block updates the rest
-        // of the super-block; the columns beyond it are updated once per super-block.
-        BlockArgs a;
-        a.Wf = w.Wf; a.U = U; a.Q = perm ? w.Qs : Q; a.scales = scales; a.zeros = zeros; a.W_hat = perm ? nullptr : W_hat;
-        a.Dh = w.Dh; a.Dl = w.Dl; a.ldD = int(ld_d(d_out)); a.sc = w.sc; a.rowloss = w.rowloss;
-        a.d_out = int(d_out); a.d_in = int(d_in); a.G = group_size; a.n_g = int(d_in / group_size);
-        a.qs = grid == ONECOMP_GRID_SYMMETRIC ? float((1 << (bits - 1)) - 1) : 0.f;
-        a.qmax = grid == ONECOMP_GRID_SYMMETRIC ? 2.f * a.qs : float((1 << bits) - 1);
-        const int sbw = group_size <= SBIG ? (SBIG / group_size) * group_size : SBIG;
-        for (int s0 = 0; s0 < d_in;) {
-            int s1 = s0 + sbw;
-            if (group_size > SBIG) {   // do not run past the end of the current group
-                const int g_end = (s0 / group_size + 1) * group_size;
-                if (s1 > g_end) s1 = g_end;
-            }
-            if (s1 > d_in) s1 = int(d_in);
-            for (int j0 = s0; j0 < s1; j0 += SB) {
-                a.j0 = j0;
-                a.e_col = j0 - s0;
-                if ((st = launch_block<32>(a, stream)) != ONECOMP_OK) return st;
-                if ((st = trailing(0, j0 - s0, SB, j0, j0 + SB, s1)) != ONECOMP_OK) return st;
-            }
-            if ((st = trailing(0, 0, s1 - s0, s0, s1, int(d_in))) != ONECOMP_OK) return st;
-            s0 = s1;
         }
     }
     if (perm) {
