@@ -61,18 +61,14 @@ def sweep_model_bytes(d_out, d_in, G, w_bytes, SBW=512):
     return total
 
 
-def gram_kernel_name(d_in, bf16, n_cus=256):
-    """Name of the kernel onecomp_hessian_accumulate launches for this width (the library's own selection rule:
-    estimated rounds of 256 x 256 tiles, one per CU, against 128 x 256 tiles, two per CU)."""
+def gram_kernel_name(d_in, bf16):
+    """Kernel onecomp_hessian_accumulate launches for this width; the ring kernel's tile shape (256 x 256 or 128 x 256)
+    and how it cuts tiles along the token axis are the library's own choice (estimated rounds over the CUs)."""
     if not bf16:
         return "gram_f32_kernel"
     if d_in < 1024:
         return "gram_bf16_kernel<2>"
-    n256, n128 = -(-d_in // 256), -(-d_in // 128)
-    big = n256 * (n256 + 1) // 2
-    mid = sum(n256 - i // 2 for i in range(n128))
-    return ("gram_bf16_ring_kernel<RingBig>" if 2.0 * -(-big // n_cus) <= 1.15 * -(-mid // n_cus)
-            else "gram_bf16_ring_kernel<RingMid>")
+    return "gram_bf16_ring_kernel"
 
 
 def cpu_baseline(cfg, synth, seconds_hint=20.0):
@@ -236,6 +232,8 @@ def main():
     U = torch.empty((d_in, d_in), dtype=torch.float32, device=dev)
     info = torch.zeros(1, dtype=torch.int32, device=dev)
     perm = torch.empty(d_in, dtype=torch.int32, device=dev) if cfg.act_order else None
+    ws_a_bytes = og.onecomp_accumulate_workspace_bytes(cfg.dtype, d_in)
+    ws_a = torch.empty(ws_a_bytes, dtype=torch.uint8, device=dev) if ws_a_bytes > 0 else None
     ws_f = torch.empty(og.onecomp_factor_workspace_bytes(d_in), dtype=torch.uint8, device=dev)
     ws_q = torch.empty(og.onecomp_quantize_workspace_bytes(d_out, d_in, 128), dtype=torch.uint8, device=dev)
     n_g = d_in // cfg.group_size
@@ -267,7 +265,7 @@ def main():
         e[0].record()
         if only in (None, "gram"):
             for t0 in range(0, T, tpc):
-                og.onecomp_hessian_accumulate(X[t0:t0 + tpc], H)
+                og.onecomp_hessian_accumulate(X[t0:t0 + tpc], H, workspace=ws_a)
         e[1].record()
         if only in (None, "factor"):
             og.onecomp_hessian_factor(H, cfg.damp, cfg.act_order, U=U, perm_out=perm, info=info, workspace=ws_f,
@@ -400,7 +398,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: W {d_out}x{d_in} {str(cfg.dtype).split('.')[-1]}, {T} tokens, "
                                f"{cfg.bits}-bit, group {cfg.group_size}, {args.grid} grid, damp {cfg.damp}, act_order {cfg.act_order}, "
-                               f"block 128, {n_calls} accumulate call(s), factor form {args.factor_form}"
+                               f"block 128, {n_calls} accumulate call(s) with a {ws_a_bytes >> 20} MiB workspace, "
+                               f"factor form {args.factor_form}"
                                + (", HIP graph replay" if args.graph else "")
                                + ("" if phase == "all" else f" [PROFILING RUN: only phase '{phase}' timed, value is not the metric]")},
         "phases_ms": {"hessian_accumulate": acc_ms, "hessian_factor": fac_ms, "quantize_layer": swp_ms},

@@ -30,6 +30,8 @@ EXPORTED_SYMBOLS = (
     "onecomp_quantize_layer",
     "onecomp_quantize_layer_grid",
     "onecomp_hessian_factor_form",
+    "onecomp_hessian_accumulate_ws",
+    "onecomp_accumulate_workspace_bytes",
     "onecomp_quantize_layer_form",
     "onecomp_factor_workspace_bytes",
     "onecomp_quantize_workspace_bytes",
@@ -66,6 +68,10 @@ def load_library() -> ctypes.CDLL:
     lib.onecomp_hessian_accumulate.restype = i32
     lib.onecomp_hessian_factor.argtypes = [vp, i64, f32, i32, vp, vp, vp, vp, sz, vp]
     lib.onecomp_hessian_factor.restype = i32
+    lib.onecomp_hessian_accumulate_ws.argtypes = [vp, i32, i64, i64, i64, vp, vp, sz, vp]
+    lib.onecomp_hessian_accumulate_ws.restype = i32
+    lib.onecomp_accumulate_workspace_bytes.argtypes = [i32, i64]
+    lib.onecomp_accumulate_workspace_bytes.restype = sz
     lib.onecomp_hessian_factor_form.argtypes = [vp, i64, f32, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.onecomp_hessian_factor_form.restype = i32
     lib.onecomp_quantize_layer_form.argtypes = [vp, i32, i64, i64, vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp,
@@ -140,8 +146,14 @@ def onecomp_quantize_workspace_bytes(d_out: int, d_in: int, block_size: int = 12
     return int(load_library().onecomp_quantize_workspace_bytes(int(d_out), int(d_in), int(block_size)))
 
 
-def onecomp_hessian_accumulate(X: torch.Tensor, H: torch.Tensor) -> None:
-    """H += 2 X^T X.  X: [n_tokens, d_in] fp32/bf16 (rows may be strided), H: [d_in, d_in] fp32."""
+def onecomp_accumulate_workspace_bytes(dtype: torch.dtype, d_in: int) -> int:
+    code = ONECOMP_BF16 if dtype == torch.bfloat16 else ONECOMP_F32
+    return int(load_library().onecomp_accumulate_workspace_bytes(code, int(d_in)))
+
+
+def onecomp_hessian_accumulate(X: torch.Tensor, H: torch.Tensor, workspace: Optional[torch.Tensor] = None) -> None:
+    """H += 2 X^T X.  X: [n_tokens, d_in] fp32/bf16 (rows may be strided), H: [d_in, d_in] fp32.
+    workspace (uint8 device tensor, see onecomp_accumulate_workspace_bytes) selects onecomp_hessian_accumulate_ws."""
     lib = load_library()
     if X.dim() != 2 or H.dim() != 2 or H.shape[0] != H.shape[1] or H.shape[0] != X.shape[1]:
         raise ValueError("shapes: X [n_tokens, d_in], H [d_in, d_in]")
@@ -149,8 +161,13 @@ def onecomp_hessian_accumulate(X: torch.Tensor, H: torch.Tensor) -> None:
         raise ValueError("X rows must be dense")
     _dev(X, "X", contiguous=False)
     ldx = X.stride(0) if X.shape[0] > 1 else X.shape[1]
-    rc = lib.onecomp_hessian_accumulate(_ptr(X), _dtype_code(X), X.shape[0], X.shape[1], ldx,
-                                        _dev(H, "H", torch.float32), _stream())
+    if workspace is None:
+        rc = lib.onecomp_hessian_accumulate(_ptr(X), _dtype_code(X), X.shape[0], X.shape[1], ldx,
+                                            _dev(H, "H", torch.float32), _stream())
+    else:
+        rc = lib.onecomp_hessian_accumulate_ws(_ptr(X), _dtype_code(X), X.shape[0], X.shape[1], ldx,
+                                               _dev(H, "H", torch.float32), _dev(workspace, "workspace", torch.uint8),
+                                               workspace.numel(), _stream())
     if rc != ONECOMP_OK:
         raise OnecompError(rc, "onecomp_hessian_accumulate")
 

@@ -10,18 +10,31 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 #define ONECOMP_API __attribute__((visibility("default")))
 extern "C" {
 
-ONECOMP_API onecomp_status onecomp_hessian_accumulate(const void* X, onecomp_dtype x_dtype, int64_t n_tokens, int64_t d_in,
-                                          int64_t ldx, float* H, void* hip_stream) {
+ONECOMP_API size_t onecomp_accumulate_workspace_bytes(onecomp_dtype x_dtype, int64_t d_in) {
+    if (x_dtype != ONECOMP_BF16 || d_in <= 0 || d_in % 16 != 0 || d_in > (1 << 20)) return 0;
+    return gram_workspace_bytes(d_in);
+}
+
+ONECOMP_API onecomp_status onecomp_hessian_accumulate_ws(const void* X, onecomp_dtype x_dtype, int64_t n_tokens,
+                                                         int64_t d_in, int64_t ldx, float* H, void* workspace,
+                                                         size_t workspace_bytes, void* hip_stream) {
     if (x_dtype != ONECOMP_F32 && x_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
     if (!H || d_in <= 0 || n_tokens < 0 || ldx < d_in) return ONECOMP_ERR_INVALID_ARG;
     if (d_in % 16 != 0 || d_in > (1 << 20)) return ONECOMP_ERR_INVALID_ARG;
+    if (workspace && !aligned(workspace, 256)) return ONECOMP_ERR_WORKSPACE;
     if (n_tokens == 0) return ONECOMP_OK;
     if (!X) return ONECOMP_ERR_INVALID_ARG;
     const size_t esz = (x_dtype == ONECOMP_BF16) ? 2 : 4;
     if (!aligned(X, 16) || (size_t(ldx) * esz) % 16 != 0 || !aligned(H, 16)) return ONECOMP_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    if (x_dtype == ONECOMP_BF16) return gram_accumulate_bf16(X, n_tokens, d_in, ldx, H, s);
+    if (x_dtype == ONECOMP_BF16)
+        return gram_accumulate_bf16(X, n_tokens, d_in, ldx, H, workspace, workspace ? workspace_bytes : 0, s);
     return gram_accumulate_f32(X, n_tokens, d_in, ldx, H, s);
+}
+
+ONECOMP_API onecomp_status onecomp_hessian_accumulate(const void* X, onecomp_dtype x_dtype, int64_t n_tokens, int64_t d_in,
+                                          int64_t ldx, float* H, void* hip_stream) {
+    return onecomp_hessian_accumulate_ws(X, x_dtype, n_tokens, d_in, ldx, H, nullptr, 0, hip_stream);
 }
 
 ONECOMP_API size_t onecomp_factor_workspace_bytes(int64_t d_in) {

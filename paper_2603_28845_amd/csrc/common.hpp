@@ -57,8 +57,9 @@ constexpr uint32_t LDS_DMA_OOB = 0xFFFFFFF0u;
 constexpr int wait_vmcnt(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
 // ---- entry points implemented in the kernel files -------------------------------------------
+size_t gram_workspace_bytes(int64_t d_in);
 onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx,
-                                    float* H, hipStream_t stream);
+                                    float* H, void* ws, size_t ws_bytes, hipStream_t stream);
 onecomp_status gram_accumulate_f32(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx,
                                    float* H, hipStream_t stream);
 

@@ -377,35 +377,37 @@ __device__ inline void tile128_from_rank(int v, int n_rt, int n_ct, int& ti, int
 template <typename C, bool CROSS>
 __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring_kernel(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ Xb, int64_t n_tokens, int d_in, int64_t ldx,
-    int64_t ldxb, float* __restrict__ H, int n_rt, int n_ct, int n_tiles, int chunk, int split0, int n_split) {
+    int64_t ldxb, float* __restrict__ H, int n_rt, int n_ct, int n_tiles, int chunk, int split0, int n_split,
+    int n_piece, float* __restrict__ ws) {
     using R = Ring<C>;
     constexpr int KT = R::KT, NBUF = C::NBUF, MT = R::MT, NT = R::NT, LPW = R::LPW;
     constexpr int A_ROWB = R::A_ROWB, B_ROWB = R::B_ROWB, A_PANELB = R::A_PANELB, STAGEB = R::STAGEB;
     extern __shared__ __attribute__((aligned(1024))) char ldsb[];
     // Workgroups 0 .. 8 chunk - 1 take whole tiles: the ranks outside [split0, split0 + n_split), `chunk` of them
-    // per XCD.  The workgroups after them take the n_split tiles of that range by halves of the token axis, so that
-    // what would be a short last round of whole tiles costs half a round (n_split = 0: no such tiles).
-    int v, half = -1;
+    // per XCD.  The workgroups after them take the n_split tiles of that range in n_piece pieces of the token axis
+    // each, so that a short last round of whole tiles (or a matrix of fewer tiles than CUs) still fills the chip
+    // (n_split = 0: no such tiles).  Without a workspace n_piece is 2 and the mirror positions hold the second
+    // partial sum (gram_store_half); with one, every piece stores its sum there and gram_reduce_kernel adds them.
+    int v, piece = -1, m_split = 0;
     if (int(blockIdx.x) < 8 * chunk) {
         v = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
         if (v >= n_tiles - n_split) return;
         if (v >= split0) v += n_split;
     } else {
-        const int b = blockIdx.x - 8 * chunk, per_xcd = (n_split + 7) >> 3;
-        const int m = (b & 7) * per_xcd + (b >> 4);
-        if (m >= n_split) return;
-        v = split0 + m;
-        half = (b >> 3) & 1;
+        // on an XCD the pieces run tile after tile for one range of tokens, then for the next: workgroups that are
+        // resident together then read the same tokens and share their column panels through the L2
+        const int b = blockIdx.x - 8 * chunk, per_xcd = (n_split + 7) >> 3, j = b >> 3;
+        m_split = (b & 7) * per_xcd + j % per_xcd;
+        if (m_split >= n_split) return;
+        v = split0 + m_split;
+        piece = j / per_xcd;
     }
-    if (half >= 0) {   // this workgroup's half of the tokens: whole steps of KT, the first half takes the odd one
-        const int64_t t_split = ((n_tokens + KT - 1) / KT + 1) / 2 * KT;
-        if (half == 1) {
-            X += t_split * ldx;
-            Xb += t_split * ldxb;
-            n_tokens -= t_split;
-        } else {
-            n_tokens = t_split;
-        }
+    if (piece >= 0) {   // this workgroup's share of the tokens: whole steps of KT
+        const int64_t n_st_all = (n_tokens + KT - 1) / KT;
+        const int64_t t_piece = (n_st_all + n_piece - 1) / n_piece * KT, t_begin = piece * t_piece;
+        X += t_begin * ldx;
+        Xb += t_begin * ldxb;
+        n_tokens = n_tokens - t_begin < t_piece ? n_tokens - t_begin : t_piece;   // <= 0: nothing left, the sum is 0
     }
     int ti, tk;
     if constexpr (CROSS) {   // all tiles: bands of 4 tile rows, column by column inside a band
@@ -557,8 +559,53 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
         s0 = s2;
     }
     __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // no LDS write may be in flight when the workgroup ends
-    if (half >= 0) gram_store_half<MT, NT>(acc, H, d_in, i0 + wr * (32 * MT), k0 + wc * (32 * NT), half, lane);
-    else gram_store<MT, NT, !CROSS>(acc, H, d_in, i0 + wr * (32 * MT), k0 + wc * (32 * NT), diag, lane);
+    if (piece >= 0 && ws) {   // partial sum of the tile, in accumulator order: consecutive lanes, consecutive addresses
+        float* slot = ws + (int64_t(m_split) * n_piece + piece) * (C::TM * C::TN) + wave * (MT * NT * 16 * 64) + lane;
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int n = 0; n < NT; ++n)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) slot[((m * NT + n) * 16 + r) * 64] = acc[m][n][r];
+    } else if (piece >= 0) {
+        gram_store_half<MT, NT>(acc, H, d_in, i0 + wr * (32 * MT), k0 + wc * (32 * NT), piece, lane);
+    } else {
+        gram_store<MT, NT, !CROSS>(acc, H, d_in, i0 + wr * (32 * MT), k0 + wc * (32 * NT), diag, lane);
+    }
+}
+
+// Sum of the n_piece partial sums of each split tile (fixed order), then the usual epilogue: H += 2 sum, mirrored.
+// One workgroup of the main kernel's shape per tile.
+template <typename C>
+__global__ __launch_bounds__(Ring<C>::THREADS) void gram_reduce_kernel(const float* __restrict__ ws, float* __restrict__ H,
+                                                                      int d_in, int n_ct, int split0, int n_split,
+                                                                      int n_piece) {
+    using R = Ring<C>;
+    constexpr int MT = R::MT, NT = R::NT;
+    const int m_split = blockIdx.x;
+    if (m_split >= n_split) return;
+    int ti, tk;
+    tile_from_rank(split0 + m_split, n_ct, ti, tk);
+    const int i0 = ti * C::TM, k0 = tk * C::TN;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wr = wave / C::WN, wc = wave % C::WN;
+    float16v acc[MT][NT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
+    for (int p = 0; p < n_piece; ++p) {
+        const float* slot = ws + (int64_t(m_split) * n_piece + p) * (C::TM * C::TN) + wave * (MT * NT * 16 * 64) + lane;
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int n = 0; n < NT; ++n)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[m][n][r] += slot[((m * NT + n) * 16 + r) * 64];
+    }
+    gram_store<MT, NT, true>(acc, H, d_in, i0 + wr * (32 * MT), k0 + wc * (32 * NT), k0 < i0 + C::TM, lane);
 }
 
 
@@ -697,46 +744,82 @@ int device_cus() {
     return v;
 }
 
-// Number of 256 x 256 tiles of the symmetric Gram computed by halves of the token axis (0: none), see
-// launch_bf16_ring.
-int split_tiles(int64_t n_tiles, int64_t n_ct, int64_t d_in, int64_t n_tokens, int n_cus) {
+// Which 256 x 256 tiles of the symmetric Gram are computed in pieces of the token axis, and the estimated
+// duration of the launch in units of one whole tile on one CU.
+constexpr size_t GRAM_SLOT_BYTES = size_t(256) * 256 * sizeof(float);   // one partial sum of a 256 x 256 tile
+struct SplitPlan {
+    int split0 = 0, n_split = 0, n_piece = 1;
+    bool use_ws = false;
+    double rounds = 0.0;
+};
+
+// Without a workspace only two pieces per tile are possible (the second partial sum is parked in the tile's mirror
+// position), for tiles strictly above the diagonal and inside the matrix: the short last round is taken from the
+// rectangular part of the first band.  With a workspace any tile can be cut into 2, 4 or 8 pieces: either the
+// tiles left over after whole rounds, or all of them when there are fewer than two rounds.  A piece costs its share
+// of the tile plus about 3 % of a tile for filling the pipeline and storing the partial sum, and it must keep at
+// least 2048 tokens.
+// ws_slots: how many 256 x 256 partial sums the workspace holds (0: none).
+SplitPlan plan_split(int64_t n_tiles, int64_t n_ct, int64_t d_in, int64_t n_tokens, int n_cus, int64_t ws_slots) {
+    SplitPlan best;
+    best.rounds = double(ceil_div(n_tiles, n_cus));
     const int64_t r = n_tiles % n_cus;
     if (r > 0 && r <= n_cus / 2 && n_tokens >= 1024 && n_ct >= BAND + ceil_div(r, BAND) &&
-        (BAND + ceil_div(r, BAND)) * 256 <= d_in)
-        return int(r);
-    return 0;
+        (BAND + ceil_div(r, BAND)) * 256 <= d_in) {
+        best.split0 = BAND * (BAND + 1) / 2;
+        best.n_split = int(r);
+        best.n_piece = 2;
+        best.rounds = double(n_tiles / n_cus) + 0.5 * 1.06;
+    }
+    for (int pc = 2; pc <= 8; pc *= 2) {
+        if (n_tokens / pc < 2048) break;
+        const double piece_cost = 1.0 / pc + 0.03;
+        if (r > 0 && n_tiles > n_cus && r * pc <= ws_slots) {   // the leftover tiles, from the end of the rank order
+            const double rounds = double(n_tiles / n_cus) + double(ceil_div(r * pc, n_cus)) * piece_cost;
+            if (rounds < best.rounds) best = SplitPlan{int(n_tiles - r), int(r), pc, true, rounds};
+        }
+        if (n_tiles < 2 * n_cus && n_tiles * pc <= ws_slots) {   // every tile
+            const double rounds = double(ceil_div(n_tiles * pc, n_cus)) * piece_cost;
+            if (rounds < best.rounds) best = SplitPlan{0, int(n_tiles), pc, true, rounds};
+        }
+    }
+    return best;
 }
 
 template <typename C, bool CROSS>
 onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens, int64_t d_in, int64_t ldx,
-                                int64_t ldxb, float* H, hipStream_t stream) {
+                                int64_t ldxb, float* H, float* ws, size_t ws_bytes, hipStream_t stream) {
     using R = Ring<C>;
     const int n_rt = int(ceil_div(d_in, C::TM)), n_ct = int(ceil_div(d_in, C::TN));
     int n_tiles = 0;
     if (CROSS) n_tiles = n_rt * n_ct;
     else if (C::TM == C::TN) n_tiles = n_ct * (n_ct + 1) / 2;
     else for (int i = 0; i < n_rt; ++i) n_tiles += n_ct - i / 2;
-    // A short last round: when the tiles left over after whole rounds of one tile per CU fill at most half of the
-    // CUs, that many tiles (taken from the rectangular part of the first band: strictly above the diagonal, inside
-    // the matrix) are computed by two workgroups each, one per half of the tokens, dispatched last.
-    int n_split = 0, split0 = 0;
+    // tiles computed in pieces of the token axis, dispatched after the whole tiles (see plan_split)
+    SplitPlan sp;
     if (!CROSS && C::TM == 256 && C::TN == 256) {
         const int n_cus = device_cus();
         if (n_cus <= 0) return ONECOMP_ERR_HIP;
-        n_split = split_tiles(n_tiles, n_ct, d_in, n_tokens, n_cus);
-        split0 = BAND * (BAND + 1) / 2;
+        sp = plan_split(n_tiles, n_ct, d_in, n_tokens, n_cus, ws ? int64_t(ws_bytes / GRAM_SLOT_BYTES) : 0);
     }
+    const int n_split = sp.n_split, split0 = sp.split0;
     const int chunk = int(ceil_div(n_tiles - n_split, 8));
     static std::atomic<uint64_t> lds_ok{0};
     if (allow_dynamic_lds(reinterpret_cast<const void*>(&gram_bf16_ring_kernel<C, CROSS>), int(R::LDS_BYTES),
                           lds_ok) != ONECOMP_OK)
         return ONECOMP_ERR_HIP;
-    hipLaunchKernelGGL((gram_bf16_ring_kernel<C, CROSS>), dim3(chunk * 8 + 16 * int(ceil_div(n_split, 8))),
-                       dim3(R::THREADS), R::LDS_BYTES, stream, static_cast<const uint16_t*>(X),
-                       static_cast<const uint16_t*>(Xb), n_tokens, int(d_in), ldx, ldxb, H, n_rt, n_ct, n_tiles, chunk,
-                       split0, n_split);
+    hipLaunchKernelGGL((gram_bf16_ring_kernel<C, CROSS>),
+                       dim3(chunk * 8 + 8 * sp.n_piece * int(ceil_div(n_split, 8))), dim3(R::THREADS), R::LDS_BYTES,
+                       stream, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(Xb), n_tokens, int(d_in),
+                       ldx, ldxb, H, n_rt, n_ct, n_tiles, chunk, split0, n_split, sp.n_piece, sp.use_ws ? ws : nullptr);
     ONECOMP_CHECK_LAUNCH();
-    if (n_split > 0) {
+    if (n_split > 0 && sp.use_ws) {
+        if constexpr (!CROSS && C::TM == 256 && C::TN == 256) {
+            hipLaunchKernelGGL(gram_reduce_kernel<C>, dim3(unsigned(n_split)), dim3(R::THREADS), 0, stream, ws, H,
+                               int(d_in), n_ct, split0, n_split, sp.n_piece);
+            ONECOMP_CHECK_LAUNCH();
+        }
+    } else if (n_split > 0) {
         hipLaunchKernelGGL(gram_merge_kernel, dim3(64, unsigned(n_split)), dim3(256), 0, stream, H, int(d_in), n_split);
         ONECOMP_CHECK_LAUNCH();
     }
@@ -745,8 +828,19 @@ onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens,
 
 }  // namespace
 
-onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,
-                                    hipStream_t stream) {
+// bytes of workspace that let gram_accumulate_bf16 cut tiles into pieces (0: this width never does)
+size_t gram_workspace_bytes(int64_t d_in) {
+    if (d_in < 1024) return 0;
+    const int n_cus = device_cus();
+    if (n_cus <= 0) return 0;
+    const int64_t n256 = ceil_div(d_in, 256), big = n256 * (n256 + 1) / 2;
+    const SplitPlan sp = plan_split(big, n256, d_in, int64_t(1) << 40, n_cus, int64_t(1) << 40);
+    return sp.use_ws ? size_t(sp.n_split) * sp.n_piece * GRAM_SLOT_BYTES : 0;
+}
+
+onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H, void* wsv,
+                                    size_t ws_bytes, hipStream_t stream) {
+    float* ws = static_cast<float*>(wsv);
     // The direct-to-LDS kernels need 32-bit byte offsets inside a step of tokens; narrow layers take the
     // register-staged 128 x 128 kernel.  Between the two direct-to-LDS kernels the estimated number of rounds
     // decides: 256 x 256 tiles run one per CU and cost two units each, 128 x 256 tiles run two per CU (a CU with
@@ -758,12 +852,12 @@ onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_i
     const int64_t big = n256 * (n256 + 1) / 2;
     int64_t mid = 0;
     for (int64_t i = 0; i < n128; ++i) mid += n256 - i / 2;
-    // a last round of 256 x 256 tiles that is computed by halves of the token axis costs half a round
-    const double rounds_big = split_tiles(big, n256, d_in, n_tokens, n_cus) > 0 ? double(big / n_cus) + 0.5
-                                                                                : double(ceil_div(big, n_cus));
+    const double rounds_big =
+        plan_split(big, n256, d_in, n_tokens, n_cus, ws ? int64_t(ws_bytes / GRAM_SLOT_BYTES) : 0).rounds;
     const double cost_big = 2.0 * rounds_big, cost_mid = 1.15 * double(ceil_div(mid, n_cus));
-    if (cost_big <= cost_mid) return launch_bf16_ring<RingBig, false>(X, X, n_tokens, d_in, ldx, ldx, H, stream);
-    return launch_bf16_ring<RingMid, false>(X, X, n_tokens, d_in, ldx, ldx, H, stream);
+    if (cost_big <= cost_mid)
+        return launch_bf16_ring<RingBig, false>(X, X, n_tokens, d_in, ldx, ldx, H, ws, ws_bytes, stream);
+    return launch_bf16_ring<RingMid, false>(X, X, n_tokens, d_in, ldx, ldx, H, nullptr, 0, stream);
 }
 
 // G += 2 Xh^T X for two bf16 matrices of the same shape (every tile, no symmetry to use)
@@ -773,8 +867,9 @@ onecomp_status gram_cross_accumulate_bf16(const void* Xh, const void* X, int64_t
     if (n_cus <= 0) return ONECOMP_ERR_HIP;
     const int64_t n256 = ceil_div(d_in, 256), n128 = ceil_div(d_in, 128);
     const double cost_big = 2.0 * double(ceil_div(n256 * n256, n_cus)), cost_mid = 1.15 * double(ceil_div(n128 * n256, n_cus));
-    if (cost_big <= cost_mid) return launch_bf16_ring<RingBig, true>(Xh, X, n_tokens, d_in, ldxh, ldx, G, stream);
-    return launch_bf16_ring<RingMid, true>(Xh, X, n_tokens, d_in, ldxh, ldx, G, stream);
+    if (cost_big <= cost_mid)
+        return launch_bf16_ring<RingBig, true>(Xh, X, n_tokens, d_in, ldxh, ldx, G, nullptr, 0, stream);
+    return launch_bf16_ring<RingMid, true>(Xh, X, n_tokens, d_in, ldxh, ldx, G, nullptr, 0, stream);
 }
 
 onecomp_status gram_accumulate_f32(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H,

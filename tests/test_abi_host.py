@@ -64,6 +64,22 @@ def test_accumulate_argument_checks(lib):
     assert f(NULL, 0, 0, 128, 128, P, NULL) == OK             # zero tokens: no-op
 
 
+def test_accumulate_ws_argument_checks(lib):
+    f = lib.onecomp_hessian_accumulate_ws
+    big = ctypes.c_size_t(1 << 30)
+    assert f(P, 7, 10, 128, 128, P, P, big, NULL) == UNSUPPORTED
+    assert f(P, 1, 10, 128, 128, NULL, P, big, NULL) == INVALID                 # H null
+    assert f(NULL, 1, 10, 128, 128, P, P, big, NULL) == INVALID                 # X null with tokens
+    assert f(P, 1, 10, 120, 120, P, P, big, NULL) == INVALID                    # d_in % 16
+    assert f(P, 1, 10, 128, 64, P, P, big, NULL) == INVALID                     # ldx < d_in
+    assert f(P, 1, 10, 128, 128, P, ctypes.c_void_p(0x10010), big, NULL) == WORKSPACE   # misaligned workspace
+    assert f(P, 1, 0, 128, 128, P, P, big, NULL) == OK                          # no tokens: nothing to do
+    assert f(P, 1, 0, 128, 128, P, NULL, ctypes.c_size_t(0), NULL) == OK
+    g = lib.onecomp_accumulate_workspace_bytes
+    assert g(0, 4096) == 0          # fp32 inputs never use one
+    assert g(1, 0) == 0 and g(1, 100) == 0
+
+
 def test_factor_argument_checks(lib):
     f = lib.onecomp_hessian_factor
     big = ctypes.c_size_t(1 << 40)

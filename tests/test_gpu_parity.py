@@ -27,15 +27,15 @@ def _announce(msg):
     print(f"[case] {msg}", flush=True)
 
 
-def _gpu_gram(X, chunks=1):
+def _gpu_gram(X, chunks=1, ws=None):
     d = X.shape[1]
     H = torch.zeros((d, d), dtype=torch.float32, device=DEV)
     n = X.shape[0]
     step = (n + chunks - 1) // chunks if n else 0
     if n == 0:
-        og.onecomp_hessian_accumulate(X, H)
+        og.onecomp_hessian_accumulate(X, H, workspace=ws)
     for t0 in range(0, n, max(step, 1)):
-        og.onecomp_hessian_accumulate(X[t0:t0 + step], H)
+        og.onecomp_hessian_accumulate(X[t0:t0 + step], H, workspace=ws)
     torch.cuda.synchronize()
     return H
 
@@ -145,6 +145,46 @@ def test_gram_big_tiles_bf16():
     assert rel_fro(H2.cpu().numpy().astype(np.float64), 2.0 * Hn.astype(np.float64)) <= 1e-6
 
 
+@pytest.mark.parametrize("d_in,n_tok,ws_frac", [
+    (4096, 17001, 1.0),     # fewer tiles than CUs: every tile (the diagonal ones too) in 8 pieces of the token axis
+    (4096, 9000, 1.0),      # fewer tokens: 4 pieces
+    (8192, 9001, 1.0),      # two whole rounds plus 16 tiles: those 16 in 4 pieces
+    (4096, 17001, 0.3),     # a workspace too small for 8 pieces per tile: fewer pieces
+    (4096, 17001, 0.0005),  # a workspace too small for anything: as without one
+])
+def test_gram_with_workspace(d_in, n_tok, ws_frac):
+    """onecomp_hessian_accumulate_ws: partial sums of token pieces parked in a workspace and added in a fixed order."""
+    _announce(f"gram with workspace d_in={d_in} n_tok={n_tok} workspace fraction {ws_frac}")
+    need = og.onecomp_accumulate_workspace_bytes(torch.bfloat16, d_in)
+    assert need > 0 and need % (256 * 256 * 4) == 0
+    ws = torch.empty(max(256, int(need * ws_frac) // 256 * 256), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)          # the contents on entry must not matter (0xFFFFFFFF is a NaN)
+    cfg = synth.scaled(synth.CONFIGS["c2"], d_out=16, d_in=d_in, n_tokens=n_tok, seed=9)
+    X = synth.make_activations(cfg, DEV)
+    H = _gpu_gram(X, ws=ws)
+    assert torch.equal(H, H.T)
+    H_again = _gpu_gram(X, ws=ws)
+    assert torch.equal(H, H_again)                      # reproducible bit for bit
+    Hn = H.cpu().numpy()
+    Xd = to_f64(X)
+    r = np.random.default_rng(1)
+    for _ in range(4):
+        i = np.sort(r.choice(d_in, size=200, replace=False))
+        k = np.sort(r.choice(d_in, size=200, replace=False))
+        assert rel_fro(Hn[np.ix_(i, k)].astype(np.float64), oc.hessian_tile(Xd, i, k)) <= 1e-4
+    i = np.arange(0, 300)                               # a diagonal tile and its neighbour, every entry
+    assert rel_fro(Hn[np.ix_(i, i)].astype(np.float64), oc.hessian_tile(Xd, i, i)) <= 1e-4
+    d = np.arange(d_in)
+    np.testing.assert_allclose(Hn[d, d], 2.0 * (Xd * Xd).sum(0), rtol=1e-4)
+    # same sums as the call without a workspace, up to fp32 rounding order
+    H0 = _gpu_gram(X)
+    assert rel_fro(Hn.astype(np.float64), H0.cpu().numpy().astype(np.float64)) <= 1e-6
+    # additive on a non-zero H
+    H2 = _gpu_gram(torch.cat([X, X]), chunks=2, ws=ws)
+    assert torch.equal(H2, H2.T)
+    assert rel_fro(H2.cpu().numpy().astype(np.float64), 2.0 * Hn.astype(np.float64)) <= 1e-6
+
+
 def test_gram_full_calibration_set_sampled():
     """The Gram launch exactly as bench.py times it: 262144 tokens x 14336 channels (bf16) in ONE call.  The full
     float64 product is out of reach of the host, so the oracle computes sampled index blocks (over all tokens)
@@ -187,6 +227,13 @@ def test_gram_full_calibration_set_sampled():
     diff = (H4 - H).double().norm().item() / H.double().norm().item()
     _announce(f"   one call vs four calls: rel. difference {diff:.2e}")
     assert diff <= 1e-5
+    del H4
+    ws = torch.empty(og.onecomp_accumulate_workspace_bytes(torch.bfloat16, d_in), dtype=torch.uint8, device=DEV)
+    Hw = _gpu_gram(X, ws=ws)
+    assert torch.equal(Hw, Hw.T)
+    diff = (Hw - H).double().norm().item() / H.double().norm().item()
+    _announce(f"   with workspace ({ws.numel() >> 20} MiB) vs without: rel. difference {diff:.2e}")
+    assert diff <= 1e-6
 
 
 def test_gram_zero_tokens_and_strided_rows():
