@@ -70,14 +70,16 @@ __global__ __launch_bounds__(256) void order_kernel(const float* __restrict__ ke
     if (perm_out) perm_out[pos] = i;
 }
 
-// A[r][c] = Hd[p[n-1-r]][p[n-1-c]] in fp64 (reversed, permuted, damped); upper triangle of H is read.
+// A[r][c] = Hd[p[n-1-r]][p[n-1-c]] in fp64 (reversed, permuted, damped); upper triangle of H is read.  Only the
+// 128 x 128 blocks on and below the diagonal are written: the factorization never reads the others, and in natural
+// order those are the ones whose source rows are read along the row.
 __global__ __launch_bounds__(256) void build_kernel(const float* __restrict__ H, int n,
                                                    const int32_t* __restrict__ perm,
                                                    const double* __restrict__ dfix, const double* __restrict__ lam,
                                                    double* __restrict__ A) {
     const int c = blockIdx.x * 256 + threadIdx.x;
     const int r = blockIdx.y;
-    if (c >= n) return;
+    if (c >= n || c / NB > r / NB) return;
     const int i = perm[n - 1 - r], k = perm[n - 1 - c];
     double v;
     if (i == k) v = dfix[i] + *lam;
