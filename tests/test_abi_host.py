@@ -243,3 +243,29 @@ def test_sensitivity_argument_checks(lib):
     assert call(ws=NULL) == WORKSPACE
     assert call(wsb=ctypes.c_size_t(8)) == WORKSPACE
     assert lib.onecomp_sensitivity_workspace_bytes() >= 4
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    """No CPU fallback: with the shared library missing, the first use of the binding raises and names the build step."""
+    from paper_2603_28845_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libonecomp.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.load_library()
+    with pytest.raises(RuntimeError, match="missing"):
+        binding.onecomp_factor_workspace_bytes(512)
+
+
+def test_product_never_imports_the_oracle():
+    """The oracle is test infrastructure: nothing in the package or its C sources refers to it."""
+    pkg = os.path.join(ROOT, "paper_2603_28845_amd")
+    for base, _, files in os.walk(pkg):
+        if "_build" in base or "__pycache__" in base:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(base, f), errors="ignore").read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), os.path.join(base, f)
+                assert "oracle/" not in text and "onecomp_oracle" not in text, os.path.join(base, f)
+    text = open(HEADER).read()
+    assert "oracle" not in text.lower()
