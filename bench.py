@@ -360,7 +360,7 @@ def main():
     algo_flops = float(tpc) * d_in * (d_in + 1)
     gram_tflops = algo_flops / (gram_ms * 1e-3) / 1e12
     # counter-backed traffic of the Gram launch: known for the default workload in one call (see profiles/)
-    gram_traffic = 163.0e9 if (cfg.name == "c3b" and n_calls == 1) else None
+    gram_traffic = 175.0e9 if (cfg.name == "c3b" and n_calls == 1) else None
     roofline = {
         "kernel": gram_kernel_name(d_in, cfg.dtype == torch.bfloat16),
         "bound": "mfma", "achieved": gram_tflops, "peak": PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3,
