@@ -606,6 +606,64 @@ __global__ __launch_bounds__(256, 2) void syrk_potrf_kernel(GemmArgs g, double* 
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Panel solve of the blocked Cholesky:  P <- P Linv^T  for the m x 128 panel below a 128 x 128 diagonal block whose
+// inverse Linv (lower triangular, zeros above the diagonal) is known.  A 128 x 128 GEMM tile per workgroup would
+// occupy only m / 128 of the CUs for about 23 us (fp64 MFMA bound), on the critical path of every block step; here
+// a workgroup takes 32 rows and only the non-zero half of Linv:  wave w computes the 16-column tiles 7 - w and w
+// (k < 16 (c + 1) for tile c: 9 units of 16 k per wave).  The rows go through LDS (read once, written in place);
+// the Linv operands, shared by all workgroups and resident in L2, are read from global memory straight in MFMA
+// operand order.  Layouts as in potrf_body: A[i][k]: i = l % 16, k = l / 16; B[k][j]: k = l / 16, j = l % 16;
+// D register r: row 4 r + l / 16, column l % 16.
+// ------------------------------------------------------------------------------------------
+constexpr int TR = 32;          // rows per workgroup
+constexpr int TRP = NB + 1;     // LDS pitch in doubles
+
+__global__ __launch_bounds__(256) void trsm_kernel(double* __restrict__ P, int64_t ldp, int m,
+                                                  const double* __restrict__ Linv, int64_t ldl) {
+    __shared__ double sA[TR * TRP];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m0 = blockIdx.x * TR;
+    {
+        const int r = tid >> 3, c0 = (tid & 7) * 16;
+        const bool ok = m0 + r < m;
+        const double2* src = reinterpret_cast<const double2*>(P + int64_t(ok ? m0 + r : 0) * ldp + c0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const double2 v = ok ? src[e] : make_double2(0.0, 0.0);
+            sA[r * TRP + c0 + 2 * e] = v.x;
+            sA[r * TRP + c0 + 2 * e + 1] = v.y;
+        }
+    }
+    __syncthreads();
+    const int li = lane & 15, lk = lane >> 4;
+#pragma unroll 1
+    for (int pass = 0; pass < 2; ++pass) {
+        const int c = pass == 0 ? NB / 16 - 1 - wave : wave;   // column tile
+        const int nk = 4 * (c + 1);                             // MFMA steps of 4 k
+        const double* bp = Linv + int64_t(c * 16 + li) * ldl + lk;
+        double bv[32];
+#pragma unroll
+        for (int ks = 0; ks < 32; ++ks) bv[ks] = ks < nk ? bp[4 * ks] : 0.0;
+        const double* ap0 = sA + li * TRP + lk;
+        const double* ap1 = sA + (16 + li) * TRP + lk;
+        double4v acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int ks = 0; ks < 32; ++ks) {
+            if (ks < nk) {   // uniform per wave
+                acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(ap0[4 * ks], bv[ks], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(ap1[4 * ks], bv[ks], acc1, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row0 = m0 + 4 * r + lk, row1 = row0 + 16;
+            if (row0 < m) P[int64_t(row0) * ldp + c * 16 + li] = acc0[r];
+            if (row1 < m) P[int64_t(row1) * ldp + c * 16 + li] = acc1[r];
+        }
+    }
+}
+
 onecomp_status dgemm(const GemmArgs& g, hipStream_t stream) {
     if (g.m <= 0 || g.n <= 0 || g.batch <= 0) return ONECOMP_OK;
     dim3 grid(unsigned(ceil_div(g.n, GT)), unsigned(ceil_div(g.m, GT)), unsigned(g.batch));
@@ -672,14 +730,13 @@ onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_orde
         const int bs = min(NB, n - off);
         const int rest = n - off - bs;
         if (rest <= 0) break;
-        // panel: A[off+bs:, off:off+bs] <- A[off+bs:, off:off+bs] * Linv_kk^T   (in place, one column tile)
+        // panel: A[off+bs:, off:off+bs] <- A[off+bs:, off:off+bs] * Linv_kk^T   (in place; bs = NB: only the last
+        // block can be shorter and it has no panel below it)
         GemmArgs p{};
-        p.A = w.A + int64_t(off + bs) * n + off; p.lda = n; p.sa = 0;
-        p.B = w.V + int64_t(off) * n + off; p.ldb = n; p.sb = 0;
-        p.C = w.A + int64_t(off + bs) * n + off; p.ldc = n; p.sc = 0;
-        p.m = rest; p.m_last = rest; p.n = bs; p.k = bs; p.k_last = bs; p.batch = 1;
-        p.alpha = 1.0; p.beta = 0.0; p.flags = G_BTRANS;
-        if ((st = dgemm(p, stream)) != ONECOMP_OK) return st;
+        p.C = w.A + int64_t(off + bs) * n + off;
+        hipLaunchKernelGGL(trsm_kernel, dim3(unsigned(ceil_div(rest, TR))), dim3(256), 0, stream, p.C, int64_t(n), rest,
+                           w.V + int64_t(off) * n + off, int64_t(n));
+        ONECOMP_CHECK_LAUNCH();
         // trailing: A[i][j] -= P[i] P[j]^T on the lower tiles
         GemmArgs s{};
         s.A = p.C; s.lda = n; s.sa = 0;
