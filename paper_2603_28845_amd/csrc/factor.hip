@@ -176,6 +176,25 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
+// Inverse of a 16 x 16 lower-triangular block, one row per lane of a 16-lane row, all in registers: lane i holds row
+// i of L in r[] and 1 / L_ii in rdi, and returns row i of L^-1 in x[].  Row m of the inverse is final once rows
+// 0 .. m-1 have been eliminated from it; it is then scaled in lane m and broadcast (DPP row_newbcast) to the lanes
+// below.  136 broadcast + FMA pairs, no memory traffic.
+__device__ __forceinline__ void tri_inverse16(const double (&r)[SBW], const double rdi, const int i, double (&x)[SBW]) {
+#pragma unroll
+    for (int c = 0; c < SBW; ++c) x[c] = (c == i) ? 1.0 : 0.0;
+    static_for<0, SBW>([&](auto mc) {
+        constexpr int m = decltype(mc)::value;
+        static_for<0, m + 1>([&](auto cc) {
+            constexpr int c = decltype(cc)::value;
+            if (i == m) x[c] *= rdi;
+            const double xm = bcast16<m>(x[c]);
+            if (i > m) x[c] = __builtin_fma(-r[m], xm, x[c]);
+        });
+        __builtin_amdgcn_sched_barrier(0);   // keeps the scheduler from issuing later rows' broadcasts early (registers)
+    });
+}
+
 // S: POTRF_LDS_DOUBLES doubles of LDS.  preloaded: the block (lower sub-blocks, identity padding beyond bs) is
 // already in S and a barrier has been passed.
 __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __restrict__ V, int n, int off, int bs,
@@ -243,27 +262,17 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
                     if (i >= c) r[c] = __builtin_fma(-lij, lcj, r[c]);
                 });
             });
+            // T = L_JJ^-1 from the rows still in registers
+            double x[SBW];
+            tri_inverse16(r, my_dinv, i, x);
             if (tid < SBW) {
                 dinv[J * SBW + i] = my_dinv;
 #pragma unroll
-                for (int c = 0; c < SBW; ++c) DJ[i * SBP + c] = (c <= i) ? r[c] : 0.0;   // zeros above the diagonal
+                for (int c = 0; c < SBW; ++c) {
+                    DJ[i * SBP + c] = (c <= i) ? r[c] : 0.0;   // zeros above the diagonal
+                    Tb[i * SBP + c] = x[c];
+                }
             }
-        }
-        __syncthreads();
-        // T = L_JJ^-1: thread c < 16 solves column c by forward substitution
-        if (tid < SBW) {
-            const int c = tid;
-            double x[SBW];
-#pragma unroll
-            for (int i = 0; i < SBW; ++i) {
-                double acc = (i == c) ? 1.0 : 0.0;
-#pragma unroll
-                for (int m = 0; m < i; ++m)
-                    if (m >= c) acc = __builtin_fma(-DJ[i * SBP + m], x[m], acc);
-                x[i] = (i >= c) ? acc * dinv[J * SBW + i] : 0.0;
-            }
-#pragma unroll
-            for (int i = 0; i < SBW; ++i) Tb[i * SBP + c] = x[i];
         }
         __syncthreads();
         // L_IJ = A_IJ T^T for I > J (in place: the wave holds A_IJ's fragments before it writes)
@@ -307,24 +316,17 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
 
     // ---------------- X = L^-1 in place ----------------
     // leaf inverses of the diagonal sub-blocks: thread t < 128 solves column t % 16 of sub-block t / 16
+    // (one sub-block per 16-lane row of waves 0 and 1, in registers; every lane reads its own row and writes it back)
     {
-        double x[SBW];
-        const int Jb = tid >> 4, c = tid & 15;
-        double* DJ = S + sub(Jb & 7, Jb & 7);
-        if (tid < NB) {
+        const int Jb = (tid >> 4) & 7, i = tid & 15;
+        double* DJ = S + sub(Jb, Jb);
+        if (wave < 2) {
+            double r[SBW], x[SBW];
 #pragma unroll
-            for (int i = 0; i < SBW; ++i) {
-                double acc = (i == c) ? 1.0 : 0.0;
+            for (int c = 0; c < SBW; ++c) r[c] = DJ[i * SBP + c];
+            tri_inverse16(r, dinv[Jb * SBW + i], i, x);
 #pragma unroll
-                for (int m = 0; m < i; ++m)
-                    if (m >= c) acc = __builtin_fma(-DJ[i * SBP + m], x[m], acc);
-                x[i] = (i >= c) ? acc * dinv[Jb * SBW + i] : 0.0;
-            }
-        }
-        __syncthreads();
-        if (tid < NB) {
-#pragma unroll
-            for (int i = 0; i < SBW; ++i) DJ[i * SBP + c] = x[i];   // zeros above the diagonal
+            for (int c = 0; c < SBW; ++c) DJ[i * SBP + c] = x[c];   // zeros above the diagonal
         }
         __syncthreads();
     }
