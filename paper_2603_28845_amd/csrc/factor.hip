@@ -176,20 +176,22 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
-// Inverse of a 16 x 16 lower-triangular block, one row per lane of a 16-lane row, all in registers: lane i holds row
-// i of L in r[] and 1 / L_ii in rdi, and returns row i of L^-1 in x[].  Row m of the inverse is final once rows
-// 0 .. m-1 have been eliminated from it; it is then scaled in lane m and broadcast (DPP row_newbcast) to the lanes
-// below.  136 broadcast + FMA pairs, no memory traffic.
-__device__ __forceinline__ void tri_inverse16(const double (&r)[SBW], const double rdi, const int i, double (&x)[SBW]) {
+// Inverse of a 16 x 16 lower-triangular block by one wave, all in registers.  Every 16-lane row of the wave holds
+// the block (lane i of each row: row i of L in r[], 1 / L_ii in rdi); row q of lanes computes the columns
+// c = 4 k + q of L^-1, so lane (q, i) returns X[i][4 k + q] in x[k], k = 0 .. 3.  Row m of the inverse is final
+// once rows 0 .. m-1 have been eliminated from it; it is then scaled in lane m and broadcast inside each 16-lane
+// row (DPP row_newbcast) to the lanes below.  40 broadcast + FMA pairs, no memory traffic.
+__device__ __forceinline__ void tri_inverse16(const double (&r)[SBW], const double rdi, const int i, const int q,
+                                              double (&x)[4]) {
 #pragma unroll
-    for (int c = 0; c < SBW; ++c) x[c] = (c == i) ? 1.0 : 0.0;
+    for (int k = 0; k < 4; ++k) x[k] = (4 * k + q == i) ? 1.0 : 0.0;
     static_for<0, SBW>([&](auto mc) {
         constexpr int m = decltype(mc)::value;
-        static_for<0, m + 1>([&](auto cc) {
-            constexpr int c = decltype(cc)::value;
-            if (i == m) x[c] *= rdi;
-            const double xm = bcast16<m>(x[c]);
-            if (i > m) x[c] = __builtin_fma(-r[m], xm, x[c]);
+        static_for<0, m / 4 + 1>([&](auto kc) {   // columns beyond m are still zero in row m: harmless
+            constexpr int k = decltype(kc)::value;
+            if (i == m) x[k] *= rdi;
+            const double xm = bcast16<m>(x[k]);
+            if (i > m) x[k] = __builtin_fma(-r[m], xm, x[k]);
         });
         __builtin_amdgcn_sched_barrier(0);   // keeps the scheduler from issuing later rows' broadcasts early (registers)
     });
@@ -262,16 +264,15 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
                     if (i >= c) r[c] = __builtin_fma(-lij, lcj, r[c]);
                 });
             });
-            // T = L_JJ^-1 from the rows still in registers
-            double x[SBW];
-            tri_inverse16(r, my_dinv, i, x);
+            // T = L_JJ^-1 from the rows still in registers (all four 16-lane rows hold them)
+            double x[4];
+            tri_inverse16(r, my_dinv, i, lk, x);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) Tb[i * SBP + 4 * k + lk] = x[k];
             if (tid < SBW) {
                 dinv[J * SBW + i] = my_dinv;
 #pragma unroll
-                for (int c = 0; c < SBW; ++c) {
-                    DJ[i * SBP + c] = (c <= i) ? r[c] : 0.0;   // zeros above the diagonal
-                    Tb[i * SBP + c] = x[c];
-                }
+                for (int c = 0; c < SBW; ++c) DJ[i * SBP + c] = (c <= i) ? r[c] : 0.0;   // zeros above the diagonal
             }
         }
         __syncthreads();
@@ -309,27 +310,31 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
         }
         __syncthreads();
     }
-    for (int e = tid; e < bs * NB; e += 256) {
+    // rows of L back to the matrix: 8 LDS reads in flight per thread before the stores that need them
+#pragma unroll 8
+    for (int e = tid; e < NB * NB; e += 256) {
         const int r = e / NB, c = e % NB;
-        if (c <= r) A[int64_t(off + r) * n + off + c] = S[tri(r, c)];
+        const double v = S[tri(r, min(c, r))];
+        if (c <= r && r < bs) A[int64_t(off + r) * n + off + c] = v;
     }
 
     // ---------------- X = L^-1 in place ----------------
     // leaf inverses of the diagonal sub-blocks: thread t < 128 solves column t % 16 of sub-block t / 16
-    // (one sub-block per 16-lane row of waves 0 and 1, in registers; every lane reads its own row and writes it back)
-    {
-        const int Jb = (tid >> 4) & 7, i = tid & 15;
+    // (two sub-blocks per wave, in registers: every lane reads row l % 16 and writes back its four columns)
+    __syncthreads();   // the write-out above has read every sub-block
+#pragma unroll 1
+    for (int h = 0; h < 2; ++h) {
+        const int Jb = 2 * wave + h, i = l16;
         double* DJ = S + sub(Jb, Jb);
-        if (wave < 2) {
-            double r[SBW], x[SBW];
+        double r[SBW], x[4];
 #pragma unroll
-            for (int c = 0; c < SBW; ++c) r[c] = DJ[i * SBP + c];
-            tri_inverse16(r, dinv[Jb * SBW + i], i, x);
+        for (int c = 0; c < SBW; ++c) r[c] = DJ[i * SBP + c];
+        tri_inverse16(r, dinv[Jb * SBW + i], i, lk, x);
+        // all lanes of the wave have read the sub-block before any of them overwrites it (one wave: program order)
 #pragma unroll
-            for (int c = 0; c < SBW; ++c) DJ[i * SBP + c] = x[c];   // zeros above the diagonal
-        }
-        __syncthreads();
+        for (int k = 0; k < 4; ++k) DJ[i * SBP + 4 * k + lk] = x[k];   // zeros above the diagonal
     }
+    __syncthreads();
     // recursive doubling: ns = sub-blocks per side of a pair
     static_for<0, 3>([&](auto lc) {
         constexpr int ns = 1 << decltype(lc)::value;     // 1, 2, 4
@@ -376,9 +381,11 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
         }
         __syncthreads();
     });
-    for (int e = tid; e < bs * bs; e += 256) {
-        const int r = e / bs, c = e % bs;
-        V[int64_t(off + r) * n + off + c] = (c <= r) ? S[tri(r, c)] : 0.0;
+#pragma unroll 8
+    for (int e = tid; e < NB * NB; e += 256) {
+        const int r = e / NB, c = e % NB;
+        const double v = S[tri(r, min(c, r))];
+        if (r < bs && c < bs) V[int64_t(off + r) * n + off + c] = (c <= r) ? v : 0.0;
     }
 }
 
