@@ -123,8 +123,8 @@ __global__ __launch_bounds__(256) void output_block_kernel(const double* __restr
 
 // ------------------------------------------------------------------------------------------
 // diagonal block: Cholesky in LDS, then in-place triangular inverse.  One workgroup of 256 threads (4 waves).
-// A block (bs x bs, bs <= 128) at A + off*(n+1); L written back to A (lower part), L^-1 to V (full block,
-// zeros above the diagonal).  A non-positive pivot sets *info (first one wins) and is replaced by 1.
+// A block (bs x bs, bs <= 128) at A + off*(n+1); L^-1 is written to V (full block, zeros above the diagonal); the
+// factor L_kk of the block itself stays in LDS (nothing downstream reads it).  A non-positive pivot sets *info (first one wins) and is replaced by 1.
 //
 // The block lives in LDS as 16 x 16 sub-blocks (only those on and below the diagonal, 36 of them, row pitch 17
 // doubles, 78 KB: small enough for two workgroups per CU, so the factorization can share a launch with GEMM
@@ -151,10 +151,12 @@ __device__ __forceinline__ int tri(int r, int c) {   // element (r, c), c / 16 <
 }
 __device__ __forceinline__ int sub(int I, int J) { return ((I * (I + 1)) / 2 + J) * SBS; }   // J <= I
 
+// 1 / sqrt(p): v_rsq_f64 is good to 5e-8 relative (measured over 120 binades), one Newton step brings it to 4e-15.
+// That is what scales a column of the factor; the diagonal entry itself gets a further correction step where it is
+// computed.  The step sits on the dependency chain of every pivot, so there is exactly one.
 __device__ inline double rsqrt_refined(double p) {
     double y = __builtin_amdgcn_rsq(p);
     const double h = 0.5 * p;
-    y = y * __builtin_fma(-h * y, y, 1.5);
     y = y * __builtin_fma(-h * y, y, 1.5);
     return y;
 }
@@ -310,13 +312,10 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
         }
         __syncthreads();
     }
-    // rows of L back to the matrix: 8 LDS reads in flight per thread before the stores that need them
-#pragma unroll 8
-    for (int e = tid; e < NB * NB; e += 256) {
-        const int r = e / NB, c = e % NB;
-        const double v = S[tri(r, min(c, r))];
-        if (c <= r && r < bs) A[int64_t(off + r) * n + off + c] = v;
-    }
+    // L_kk itself is not written back to A: nothing reads the diagonal blocks of L afterwards (the panel solve, the
+    // triangular inverse and the block-form output take L_kk^-1 from V; the trailing updates and the off-diagonal
+    // blocks of the inverse and of the block form read only blocks below the block diagonal).
+    (void)A;
 
     // ---------------- X = L^-1 in place ----------------
     // leaf inverses of the diagonal sub-blocks: thread t < 128 solves column t % 16 of sub-block t / 16
@@ -381,11 +380,20 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
         }
         __syncthreads();
     });
-#pragma unroll 8
-    for (int e = tid; e < NB * NB; e += 256) {
-        const int r = e / NB, c = e % NB;
-        const double v = S[tri(r, min(c, r))];
-        if (r < bs && c < bs) V[int64_t(off + r) * n + off + c] = (c <= r) ? v : 0.0;
+    // L_kk^-1 to V (zeros above the diagonal): 8 LDS reads per thread in flight before the stores that need them
+#pragma unroll 1
+    for (int e0 = tid; e0 < NB * NB; e0 += 256 * 8) {
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int e = e0 + 256 * u, r = e / NB, c = e % NB;
+            v[u] = S[tri(r, min(c, r))];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int e = e0 + 256 * u, r = e / NB, c = e % NB;
+            if (r < bs && c < bs) V[int64_t(off + r) * n + off + c] = (c <= r) ? v[u] : 0.0;
+        }
     }
 }
 
