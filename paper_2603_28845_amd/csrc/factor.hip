@@ -179,24 +179,34 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 // Inverse of a 16 x 16 lower-triangular block by one wave, all in registers.  Every 16-lane row of the wave holds
-// the block (lane i of each row: row i of L in r[], 1 / L_ii in rdi); row q of lanes computes the columns
-// c = 4 k + q of L^-1, so lane (q, i) returns X[i][4 k + q] in x[k], k = 0 .. 3.  Row m of the inverse is final
-// once rows 0 .. m-1 have been eliminated from it; it is then scaled in lane m and broadcast inside each 16-lane
-// row (DPP row_newbcast) to the lanes below.  40 broadcast + FMA pairs, no memory traffic.
+// the block (lane i of each row: row i of L in r[], entries above the diagonal arbitrary, 1 / L_ii in rdi); row q
+// of lanes computes the columns c = 4 k + q of L^-1, so lane (q, i) returns X[i][4 k + q] in x[k], k = 0 .. 3.
+// With L = Lh D (Lh = columns of L divided by their diagonal entries, unit diagonal) L^-1 = D^-1 Lh^-1: the rows of
+// Z = Lh^-1 follow without divisions, z_m = e_m - sum_{k<m} Lh[m][k] z_k, row m being final once rows 0 .. m-1 have
+// been eliminated from it and then broadcast inside each 16-lane row (DPP row_newbcast) to the lanes below; the
+// scaling by 1 / L_ii at the end is local to the lane.  Entries of Lh on and above the diagonal are set to zero
+// beforehand, so the elimination needs no per-step predicates: 40 broadcast + FMA pairs, no memory traffic.
 __device__ __forceinline__ void tri_inverse16(const double (&r)[SBW], const double rdi, const int i, const int q,
                                               double (&x)[4]) {
+    double lh[SBW];
+    static_for<0, SBW>([&](auto mc) {
+        constexpr int m = decltype(mc)::value;
+        const double rdm = bcast16<m>(rdi);
+        lh[m] = (i > m) ? r[m] * rdm : 0.0;
+    });
 #pragma unroll
     for (int k = 0; k < 4; ++k) x[k] = (4 * k + q == i) ? 1.0 : 0.0;
-    static_for<0, SBW>([&](auto mc) {
+    static_for<0, SBW - 1>([&](auto mc) {
         constexpr int m = decltype(mc)::value;
         static_for<0, m / 4 + 1>([&](auto kc) {   // columns beyond m are still zero in row m: harmless
             constexpr int k = decltype(kc)::value;
-            if (i == m) x[k] *= rdi;
-            const double xm = bcast16<m>(x[k]);
-            if (i > m) x[k] = __builtin_fma(-r[m], xm, x[k]);
+            const double zm = bcast16<m>(x[k]);
+            x[k] = __builtin_fma(-lh[m], zm, x[k]);
         });
         __builtin_amdgcn_sched_barrier(0);   // keeps the scheduler from issuing later rows' broadcasts early (registers)
     });
+#pragma unroll
+    for (int k = 0; k < 4; ++k) x[k] *= rdi;
 }
 
 // S: POTRF_LDS_DOUBLES doubles of LDS.  preloaded: the block (lower sub-blocks, identity padding beyond bs) is
@@ -244,8 +254,12 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
         // lanes 0..15 and store nothing.
         if (wave == 0) {
             const int i = l16;
+            // Entries above the diagonal (c > i) are carried along unmasked: they never reach a valid entry (a
+            // broadcast of column j takes lane c >= j) and are zeroed when the sub-block is stored.  The first bad
+            // pivot is remembered in a register, so the 16 steps form one straight-line block.
             double r[SBW];
             double my_dinv = 1.0;
+            int bad_at = -1;
 #pragma unroll
             for (int c = 0; c < SBW; ++c) r[c] = DJ[i * SBP + c];
             static_for<0, SBW>([&](auto jc) {
@@ -253,19 +267,20 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
                 double p = bcast16<j>(r[j]);           // pivot, the same in every lane
                 const bool bad = !(p > 0.0);
                 if (bad) p = 1.0;
+                bad_at = (bad && bad_at < 0) ? j : bad_at;
                 const double ri = rsqrt_refined(p);
                 double sq = p * ri;
                 sq = __builtin_fma(0.5 * ri, __builtin_fma(-sq, sq, p), sq);
-                if (bad && tid == j && *info == 0) *info = off + J * SBW + j + 1;
                 const double lij = (i == j) ? sq : r[j] * ri;   // column j on and below the pivot
-                if (i >= j) r[j] = lij;
+                r[j] = lij;
                 if (i == j) my_dinv = ri;
                 static_for<j + 1, SBW>([&](auto cc) {
                     constexpr int c = decltype(cc)::value;
                     const double lcj = bcast16<c>(lij);
-                    if (i >= c) r[c] = __builtin_fma(-lij, lcj, r[c]);
+                    r[c] = __builtin_fma(-lij, lcj, r[c]);
                 });
             });
+            if (bad_at >= 0 && tid == 0 && *info == 0) *info = off + J * SBW + bad_at + 1;
             // T = L_JJ^-1 from the rows still in registers (all four 16-lane rows hold them)
             double x[4];
             tri_inverse16(r, my_dinv, i, lk, x);
