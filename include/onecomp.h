@@ -99,9 +99,9 @@ onecomp_status onecomp_hessian_accumulate(const void* X, onecomp_dtype x_dtype,
  * onecomp_hessian_accumulate with an optional scratch buffer (onecomp_hessian_accumulate is this call with
  * workspace = NULL).  The kernel computes H in 256 x 256 tiles, one per compute unit at a time; when the number of
  * tiles does not fill the last round of compute units (or there are fewer tiles than units), a workspace lets it
- * cut tiles into 2, 4 or 8 pieces along the token axis, park the partial sums there and add them in a fixed order:
+ * cut tiles into 2 to 16 pieces along the token axis, park the partial sums there and add them in a fixed order:
  * same result up to fp32 rounding order, still bit-wise symmetric and reproducible, and faster for such widths
- * (d_in 4096, 262144 tokens: 6.0 -> 5.3 ms; d_in 8192, 131072 tokens: 9.1 -> 8.3 ms).  Without a workspace only
+ * (d_in 4096, 262144 tokens: 6.0 -> 4.5 ms; d_in 8192, 131072 tokens: 9.1 -> 8.0 ms).  Without a workspace only
  * the mirror positions of H can hold a second partial sum, which covers a short last round of wide matrices.
  *   workspace        device scratch or NULL, 256-byte aligned; any size is accepted, the kernel uses what fits
  *                    (onecomp_accumulate_workspace_bytes(x_dtype, d_in) is what it can use at most; 0 for fp32

@@ -755,10 +755,10 @@ struct SplitPlan {
 
 // Without a workspace only two pieces per tile are possible (the second partial sum is parked in the tile's mirror
 // position), for tiles strictly above the diagonal and inside the matrix: the short last round is taken from the
-// rectangular part of the first band.  With a workspace any tile can be cut into 2, 4 or 8 pieces: either the
-// tiles left over after whole rounds, or all of them when there are fewer than two rounds.  A piece costs its share
-// of the tile plus about 3 % of a tile for filling the pipeline and storing the partial sum, and it must keep at
-// least 2048 tokens.
+// rectangular part of the first band.  With a workspace any tile can be cut into 2 .. 16 pieces: either the tiles
+// left over after whole rounds, or all of them when there are fewer than two rounds.  A piece costs its share of
+// the tile plus about half a percent of a tile for filling the pipeline and storing the partial sum, and it must
+// keep at least 2048 tokens.
 // ws_slots: how many 256 x 256 partial sums the workspace holds (0: none).
 SplitPlan plan_split(int64_t n_tiles, int64_t n_ct, int64_t d_in, int64_t n_tokens, int n_cus, int64_t ws_slots) {
     SplitPlan best;
@@ -771,9 +771,9 @@ SplitPlan plan_split(int64_t n_tiles, int64_t n_ct, int64_t d_in, int64_t n_toke
         best.n_piece = 2;
         best.rounds = double(n_tiles / n_cus) + 0.5 * 1.06;
     }
-    for (int pc = 2; pc <= 8; pc *= 2) {
+    for (int pc = 2; pc <= 16; ++pc) {
         if (n_tokens / pc < 2048) break;
-        const double piece_cost = 1.0 / pc + 0.03;
+        const double piece_cost = 1.0 / pc + 0.005;
         if (r > 0 && n_tiles > n_cus && r * pc <= ws_slots) {   // the leftover tiles, from the end of the rank order
             const double rounds = double(n_tiles / n_cus) + double(ceil_div(r * pc, n_cus)) * piece_cost;
             if (rounds < best.rounds) best = SplitPlan{int(n_tiles - r), int(r), pc, true, rounds};

@@ -176,13 +176,13 @@ def test_gram_with_workspace(d_in, n_tok, ws_frac):
     assert rel_fro(Hn[np.ix_(i, i)].astype(np.float64), oc.hessian_tile(Xd, i, i)) <= 1e-4
     d = np.arange(d_in)
     np.testing.assert_allclose(Hn[d, d], 2.0 * (Xd * Xd).sum(0), rtol=1e-4)
-    # same sums as the call without a workspace, up to fp32 rounding order
+    # same sums as the call without a workspace, up to fp32 rounding order (each is ~3e-6 from the float64 result)
     H0 = _gpu_gram(X)
-    assert rel_fro(Hn.astype(np.float64), H0.cpu().numpy().astype(np.float64)) <= 1e-6
+    assert rel_fro(Hn.astype(np.float64), H0.cpu().numpy().astype(np.float64)) <= 5e-6
     # additive on a non-zero H
     H2 = _gpu_gram(torch.cat([X, X]), chunks=2, ws=ws)
     assert torch.equal(H2, H2.T)
-    assert rel_fro(H2.cpu().numpy().astype(np.float64), 2.0 * Hn.astype(np.float64)) <= 1e-6
+    assert rel_fro(H2.cpu().numpy().astype(np.float64), 2.0 * Hn.astype(np.float64)) <= 5e-6
 
 
 def test_gram_full_calibration_set_sampled():
@@ -233,7 +233,7 @@ def test_gram_full_calibration_set_sampled():
     assert torch.equal(Hw, Hw.T)
     diff = (Hw - H).double().norm().item() / H.double().norm().item()
     _announce(f"   with workspace ({ws.numel() >> 20} MiB) vs without: rel. difference {diff:.2e}")
-    assert diff <= 1e-6
+    assert diff <= 5e-6
 
 
 def test_gram_zero_tokens_and_strided_rows():
