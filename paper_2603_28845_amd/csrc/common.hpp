@@ -38,6 +38,17 @@ static inline onecomp_status allow_dynamic_lds(const void* fn, int bytes, std::a
     return ONECOMP_OK;
 }
 
+// compute units of the current device (0 on failure); looked up once per device
+static inline int device_cus() {
+    static std::atomic<int> cus[64];
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (dev >= 0 && dev < 64 && (v = cus[dev].load(std::memory_order_relaxed)) > 0) return v;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 0;
+    if (dev >= 0 && dev < 64) cus[dev].store(v, std::memory_order_relaxed);
+    return v;
+}
+
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -733,17 +733,6 @@ onecomp_status launch_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_
 
 
 
-// compute units of the current device (0 on failure); looked up once per device
-int device_cus() {
-    static std::atomic<int> cus[64];
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
-    if (dev >= 0 && dev < 64 && (v = cus[dev].load(std::memory_order_relaxed)) > 0) return v;
-    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 0;
-    if (dev >= 0 && dev < 64) cus[dev].store(v, std::memory_order_relaxed);
-    return v;
-}
-
 // Which 256 x 256 tiles of the symmetric Gram are computed in pieces of the token axis, and the estimated
 // duration of the launch in units of one whole tile on one CU.
 constexpr size_t GRAM_SLOT_BYTES = size_t(256) * 256 * sizeof(float);   // one partial sum of a 256 x 256 tile
