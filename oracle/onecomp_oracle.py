@@ -23,6 +23,8 @@ What it computes (paper sections given in brackets):
     quantize_layer_direct): with R = U^-1, R R^T = H + lambda I, the propagated errors are e = (w - w^) R, so a
     blocked sweep can run on one Cholesky factor of the damped matrix itself and the inverses of its diagonal
     blocks  [a restatement of Sec. 4.2, derived in quantize_layer_direct]
+  * the scale search of the sweep ("mse": per group, candidate ranges shrunk from the observed one, the smallest
+    squared reconstruction error wins)  [Sec. 4.2; the candidate set is this build's reading, see mse_search]
   * the corrected quantization target of error propagation (QEP),
     W* = (I + alpha (H^ + lambda I)^-1 C) W  with  C = X^^T (X - X^)  [Sec. 4.2.1, Eq. (qep)]
 
@@ -211,6 +213,39 @@ def code_range_top(bits, grid):
     raise ValueError("grid must be 'asym' or 'sym'")
 
 
+MSE_CANDIDATES = 80     # candidate ranges of the scale search: the min-max range shrunk by p_i = 1 - i / 100,
+MSE_STEP = 0.01         # i = 0 .. 79 (down to 21 % of the range); the paper names the search but gives no set
+
+
+def mse_search(vals, bits, grid="asym", n_cand=MSE_CANDIDATES, step=MSE_STEP):
+    """Scale search per group [Sec. 4.2: "MSE-based grid tuning (mse), which searches over candidate scales to
+    minimize the mean squared reconstruction error per-group"; the candidate set is this build's reading].
+
+    vals: [rows, G] current values of one group per row.  Candidate i shrinks both ends of the observed range by
+    p_i = 1 - i * step and takes (s, z) from it by the rule of the grid (Eq. (2), or Eq. (3) for "sym"); its error
+    is sum_k (w_k - w^_k)^2 with w^ from Eq. (1) on that grid.  The smallest error wins, the lower index on a tie;
+    candidate 0 is the plain min-max rule.  Returns dict(s, z, tz, cand [rows], err [rows, n_cand],
+    s_all [rows, n_cand])."""
+    vals = np.asarray(vals, dtype=np.float64)
+    lo = vals.min(axis=1)
+    hi = vals.max(axis=1)
+    params = minmax_params if grid == "asym" else symmetric_params
+    qtop = code_range_top(bits, grid)
+    errs, ss, zs, tzs = [], [], [], []
+    for i in range(n_cand):
+        p = 1.0 - i * step
+        s_i, z_i, tz_i = params(p * lo, p * hi, bits)
+        q, wh, _ = quantize_scalar(vals, s_i[:, None], z_i[:, None], bits, qtop)
+        errs.append(((vals - wh) ** 2).sum(axis=1))
+        ss.append(s_i); zs.append(z_i); tzs.append(tz_i)
+    err = np.stack(errs, axis=1)
+    cand = np.argmin(err, axis=1)          # first minimum
+    r = np.arange(vals.shape[0])
+    s_all = np.stack(ss, axis=1)
+    return {"s": s_all[r, cand], "z": np.stack(zs, axis=1)[r, cand], "tz": np.stack(tzs, axis=1)[r, cand],
+            "cand": cand, "err": err, "s_all": s_all, "z_all": np.stack(zs, axis=1), "tz_all": np.stack(tzs, axis=1)}
+
+
 def quantize_scalar(w, s, z, bits, qtop=None):
     """Eq. (1): q = clamp(rne(w / s) + z, 0, qtop), w^ = s (q - z); qtop = 2^b - 1 unless given.
     Returns (q, w^, t) with t = w / s the value before rounding."""
@@ -220,11 +255,12 @@ def quantize_scalar(w, s, z, bits, qtop=None):
     return q, s * (q - z), t
 
 
-def rtn_quantize(W, bits, group_size, grid="asym"):
+def rtn_quantize(W, bits, group_size, grid="asym", scale_search=None):
     """Round-to-nearest of W on the per-group min-max grid (Sec. 2.4, Eq.
     (direct weight quant) with the grid of Eq. (2), layout of Eq. (4)).
     Written independently of the sweep (whole-array, no column loop) so that it
-    can pin the sweep's diagonal-H special case.  Returns (Q, scales, zeros, W^)."""
+    can pin the sweep's diagonal-H special case.  scale_search="mse": the grid of every group comes from
+    mse_search instead of the plain range.  Returns (Q, scales, zeros, W^)."""
     W = np.asarray(W, dtype=np.float64)
     d_out, d_in = W.shape
     n_g = d_in // group_size
@@ -232,6 +268,13 @@ def rtn_quantize(W, bits, group_size, grid="asym"):
     lo = Wg.min(axis=2, keepdims=True)
     hi = Wg.max(axis=2, keepdims=True)
     s, z, _ = (minmax_params if grid == "asym" else symmetric_params)(lo, hi, bits)
+    if scale_search == "mse":
+        for g in range(n_g):
+            m = mse_search(Wg[:, g, :], bits, grid)
+            s[:, g, 0] = m["s"]
+            z[:, g, 0] = m["z"]
+    elif scale_search is not None:
+        raise ValueError("scale_search must be None or 'mse'")
     qmax = code_range_top(bits, grid)
     Q = np.clip(np.rint(Wg / s) + z, 0.0, qmax)
     What = s * (Q - z)
@@ -243,7 +286,7 @@ def rtn_quantize(W, bits, group_size, grid="asym"):
 # Column sweep (Sec. 4.2: one column at a time, residual propagated)
 # --------------------------------------------------------------------------
 def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
-                   forced_codes=None, forced_zeros=None, grid="asym"):
+                   forced_codes=None, forced_zeros=None, grid="asym", scale_search=None, forced_cand=None):
     """Greedy sequential quantization of every row of W with feedback through U.
 
     W: [d_out, d_in] original column order.  U: upper factor of the (permuted)
@@ -253,6 +296,9 @@ def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
       entries >= 0 override the rounded code at that step (replay of a tie).
     forced_zeros: optional int array [rows, n_groups], entries >= 0 override z.
     grid: "asym" = min-max grid of Eq. (2) (default), "sym" = symmetric grid of Eq. (3).
+    scale_search: None = the grid of a group comes from the plain range of its current values; "mse" = from
+      mse_search over those values.  forced_cand: optional int array [rows, n_groups], entries >= 0 override the
+      candidate the search picks (replay of a near-tie between candidates).
 
     Per row, for j = 0 .. d_in-1 in permuted order:
       at a group start: (s, z) from min/max of the CURRENT values of the group
@@ -288,12 +334,29 @@ def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
     scales = np.zeros((d_out, n_g))
     zeros = np.zeros((d_out, n_g))
     Tz = np.zeros((d_out, n_g))
+    n_c = MSE_CANDIDATES if scale_search == "mse" else 0
+    Cand = np.zeros((d_out, n_g), dtype=np.int64)
+    Ecand = np.zeros((d_out, n_g, n_c))
+    Scand = np.zeros((d_out, n_g, n_c))
     s = z = None
     for j in range(d_in):
         if j % G == 0:
             g = j // G
             blk = w[:, j:j + G]
             s, z, tz = params(blk.min(axis=1), blk.max(axis=1), bits)
+            if scale_search == "mse":
+                m = mse_search(blk, bits, grid)
+                c = m["cand"]
+                if forced_cand is not None:
+                    fcd = np.asarray(forced_cand)[:, g]
+                    c = np.where(fcd >= 0, fcd, c)
+                rr = np.arange(d_out)
+                s, z, tz = m["s_all"][rr, c], m["z_all"][rr, c], m["tz_all"][rr, c]
+                Cand[:, g] = c
+                Ecand[:, g, :] = m["err"]
+                Scand[:, g, :] = m["s_all"]
+            elif scale_search is not None:
+                raise ValueError("scale_search must be None or 'mse'")
             if forced_zeros is not None:
                 fz = np.asarray(forced_zeros)[:, g]
                 z = np.where(fz >= 0, fz.astype(np.float64), z)
@@ -320,7 +383,7 @@ def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
     return {
         "Q": out_Q, "W_hat": out_What, "scales": scales, "zeros": zeros,
         "loss": float((E * E).sum()), "loss_rows": (E * E).sum(axis=1),
-        "E": E, "T": T, "Tz": Tz, "perm": perm,
+        "E": E, "T": T, "Tz": Tz, "perm": perm, "cand": Cand, "Ecand": Ecand, "Scand": Scand,
     }
 
 
