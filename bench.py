@@ -193,8 +193,9 @@ def main():
     ap.add_argument("--group-size", type=int, default=0,
                     help="override the workload's group size (d_in = one group per row, the per-channel setting of the "
                          "paper's Table 3); 0 = as configured")
-    ap.add_argument("--grid", default="minmax", choices=["minmax", "symmetric"],
-                    help="grid of the sweep: min-max (Eq. (2), the configured workloads) or symmetric (Eq. (3))")
+    ap.add_argument("--grid", default="minmax", choices=["minmax", "symmetric", "minmax_mse", "symmetric_mse"],
+                    help="grid of the sweep: min-max (Eq. (2), the configured workloads) or symmetric (Eq. (3)); "
+                         "_mse adds the scale search of Sec. 4.2")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (accumulate, factor, quantize) in a HIP graph after the warm-up and time "
                          "replays of it; per-phase times are then not available (reported as the eager warm-up's)")

@@ -57,10 +57,17 @@ typedef enum {
     ONECOMP_BF16 = 1
 } onecomp_dtype;
 
-/* Grid of the column sweep: per-group asymmetric min-max grid of Eq. (2), or the symmetric grid of Eq. (3). */
+/* Grid of the column sweep: per-group asymmetric min-max grid of Eq. (2), or the symmetric grid of Eq. (3).
+ * The _MSE variants add the scale search of Sec. 4.2 (the sweep's "mse" option): when a group's parameters are
+ * fixed, its range [lo, hi] is shrunk to p_i [lo, hi], p_i = 1 - i / 100 for i = 0 .. 79, (s, z) follow from the
+ * shrunk range by the grid's own rule, and the candidate with the least sum over the group of (w - s (q - z))^2
+ * (q rounded and clamped as in the sweep) is kept, the lowest i on equal sums; i = 0 is the plain grid.  The search
+ * runs in fp32 on the compensated values, for group sizes of at least 32. */
 typedef enum {
     ONECOMP_GRID_MINMAX = 0,
-    ONECOMP_GRID_SYMMETRIC = 1
+    ONECOMP_GRID_SYMMETRIC = 1,
+    ONECOMP_GRID_MINMAX_MSE = 2,
+    ONECOMP_GRID_SYMMETRIC_MSE = 3
 } onecomp_grid;
 
 /* What the factor call hands to the sweep.

@@ -225,25 +225,31 @@ def mse_search(vals, bits, grid="asym", n_cand=MSE_CANDIDATES, step=MSE_STEP):
     p_i = 1 - i * step and takes (s, z) from it by the rule of the grid (Eq. (2), or Eq. (3) for "sym"); its error
     is sum_k (w_k - w^_k)^2 with w^ from Eq. (1) on that grid.  The smallest error wins, the lower index on a tie;
     candidate 0 is the plain min-max rule.  Returns dict(s, z, tz, cand [rows], err [rows, n_cand],
-    s_all [rows, n_cand])."""
+    s_all, z_all, tz_all [rows, n_cand]) and, for the analysis of ties only (no decision here uses them),
+    z_alt [rows, n_cand] = the zero-point a candidate would get were its tz rounded the other way, with
+    err_alt [rows, n_cand] the candidate's error on that grid."""
     vals = np.asarray(vals, dtype=np.float64)
     lo = vals.min(axis=1)
     hi = vals.max(axis=1)
     params = minmax_params if grid == "asym" else symmetric_params
     qtop = code_range_top(bits, grid)
-    errs, ss, zs, tzs = [], [], [], []
+    errs, ss, zs, tzs, zas, eas = [], [], [], [], [], []
     for i in range(n_cand):
         p = 1.0 - i * step
         s_i, z_i, tz_i = params(p * lo, p * hi, bits)
         q, wh, _ = quantize_scalar(vals, s_i[:, None], z_i[:, None], bits, qtop)
         errs.append(((vals - wh) ** 2).sum(axis=1))
         ss.append(s_i); zs.append(z_i); tzs.append(tz_i)
+        za_i = np.clip(2.0 * np.floor(tz_i) + 1.0 - np.rint(tz_i), 0.0, qtop)   # the other neighbour of tz
+        _, wha, _ = quantize_scalar(vals, s_i[:, None], za_i[:, None], bits, qtop)
+        zas.append(za_i); eas.append(((vals - wha) ** 2).sum(axis=1))
     err = np.stack(errs, axis=1)
     cand = np.argmin(err, axis=1)          # first minimum
     r = np.arange(vals.shape[0])
     s_all = np.stack(ss, axis=1)
     return {"s": s_all[r, cand], "z": np.stack(zs, axis=1)[r, cand], "tz": np.stack(tzs, axis=1)[r, cand],
-            "cand": cand, "err": err, "s_all": s_all, "z_all": np.stack(zs, axis=1), "tz_all": np.stack(tzs, axis=1)}
+            "cand": cand, "err": err, "s_all": s_all, "z_all": np.stack(zs, axis=1), "tz_all": np.stack(tzs, axis=1),
+            "z_alt": np.stack(zas, axis=1), "err_alt": np.stack(eas, axis=1)}
 
 
 def quantize_scalar(w, s, z, bits, qtop=None):
@@ -338,6 +344,10 @@ def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
     Cand = np.zeros((d_out, n_g), dtype=np.int64)
     Ecand = np.zeros((d_out, n_g, n_c))
     Scand = np.zeros((d_out, n_g, n_c))
+    Zcand = np.zeros((d_out, n_g, n_c))
+    Tzcand = np.zeros((d_out, n_g, n_c))
+    Zalt = np.zeros((d_out, n_g, n_c))
+    Ealt = np.zeros((d_out, n_g, n_c))
     s = z = None
     for j in range(d_in):
         if j % G == 0:
@@ -355,6 +365,10 @@ def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
                 Cand[:, g] = c
                 Ecand[:, g, :] = m["err"]
                 Scand[:, g, :] = m["s_all"]
+                Zcand[:, g, :] = m["z_all"]
+                Tzcand[:, g, :] = m["tz_all"]
+                Zalt[:, g, :] = m["z_alt"]
+                Ealt[:, g, :] = m["err_alt"]
             elif scale_search is not None:
                 raise ValueError("scale_search must be None or 'mse'")
             if forced_zeros is not None:
@@ -384,6 +398,7 @@ def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
         "Q": out_Q, "W_hat": out_What, "scales": scales, "zeros": zeros,
         "loss": float((E * E).sum()), "loss_rows": (E * E).sum(axis=1),
         "E": E, "T": T, "Tz": Tz, "perm": perm, "cand": Cand, "Ecand": Ecand, "Scand": Scand,
+        "Zcand": Zcand, "Tzcand": Tzcand, "Zalt": Zalt, "Ealt": Ealt,
     }
 
 

@@ -21,6 +21,10 @@ ONECOMP_F32 = 0
 ONECOMP_BF16 = 1
 ONECOMP_GRID_MINMAX = 0
 ONECOMP_GRID_SYMMETRIC = 1
+ONECOMP_GRID_MINMAX_MSE = 2
+ONECOMP_GRID_SYMMETRIC_MSE = 3
+_GRIDS = {"minmax": ONECOMP_GRID_MINMAX, "symmetric": ONECOMP_GRID_SYMMETRIC, "minmax_mse": ONECOMP_GRID_MINMAX_MSE,
+          "symmetric_mse": ONECOMP_GRID_SYMMETRIC_MSE}
 ONECOMP_FACTOR_INVERSE = 0
 ONECOMP_FACTOR_BLOCK = 1
 
@@ -210,6 +214,7 @@ def onecomp_quantize_layer(W: torch.Tensor, U: torch.Tensor, bits: int, group_si
                            grid: str = "minmax", form: str = "inverse") -> dict:
     """Returns dict(Q_codes uint8, scales, zeros, W_hat (or None), loss) of device tensors.
     grid = "minmax" calls onecomp_quantize_layer, "symmetric" onecomp_quantize_layer_grid with that grid;
+    "minmax_mse" / "symmetric_mse" (the grid with the scale search) call onecomp_quantize_layer_form;
     form = "block" (U from onecomp_hessian_factor(..., form="block")) calls onecomp_quantize_layer_form."""
     lib = load_library()
     d_out, d_in = W.shape
@@ -233,14 +238,13 @@ def onecomp_quantize_layer(W: torch.Tensor, U: torch.Tensor, bits: int, group_si
     tail = (_dev(out["Q_codes"], "Q_codes", torch.uint8), _dev(out["scales"], "scales", torch.float32),
             _dev(out["zeros"], "zeros", torch.float32), _ptr(out["W_hat"]), _dev(out["loss"], "loss", torch.float32),
             _dev(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
-    if grid not in ("minmax", "symmetric"):
-        raise ValueError("grid must be 'minmax' or 'symmetric'")
-    if form == "block":
-        rc = lib.onecomp_quantize_layer_form(*head[:5], ONECOMP_FACTOR_BLOCK, *head[5:],
-                                             ONECOMP_GRID_SYMMETRIC if grid == "symmetric" else ONECOMP_GRID_MINMAX,
-                                             *tail)
-    elif form != "inverse":
+    if grid not in _GRIDS:
+        raise ValueError("grid must be one of " + ", ".join(sorted(_GRIDS)))
+    if form not in ("inverse", "block"):
         raise ValueError("form must be 'inverse' or 'block'")
+    if form == "block" or grid.endswith("_mse"):
+        rc = lib.onecomp_quantize_layer_form(*head[:5], ONECOMP_FACTOR_BLOCK if form == "block" else ONECOMP_FACTOR_INVERSE,
+                                             *head[5:], _GRIDS[grid], *tail)
     elif grid == "minmax":
         rc = lib.onecomp_quantize_layer(*head, *tail)
     else:

@@ -78,7 +78,9 @@ ONECOMP_API onecomp_status onecomp_quantize_layer_form(const void* W, onecomp_dt
                                                        size_t workspace_bytes, void* hip_stream) {
     const float* U = F;
     if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
-    if (grid != ONECOMP_GRID_MINMAX && grid != ONECOMP_GRID_SYMMETRIC) return ONECOMP_ERR_UNSUPPORTED;
+    if (grid != ONECOMP_GRID_MINMAX && grid != ONECOMP_GRID_SYMMETRIC && grid != ONECOMP_GRID_MINMAX_MSE &&
+        grid != ONECOMP_GRID_SYMMETRIC_MSE)
+        return ONECOMP_ERR_UNSUPPORTED;
     if (form != ONECOMP_FACTOR_INVERSE && form != ONECOMP_FACTOR_BLOCK) return ONECOMP_ERR_UNSUPPORTED;
     if (!W || !U || !Q_codes || !scales || !zeros || !loss) return ONECOMP_ERR_INVALID_ARG;
     if (d_out <= 0 || d_in <= 0 || d_out > (1 << 24) || d_in > 65535) return ONECOMP_ERR_INVALID_ARG;
@@ -88,6 +90,8 @@ ONECOMP_API onecomp_status onecomp_quantize_layer_form(const void* W, onecomp_dt
     if (group_size % 16 != 0) return ONECOMP_ERR_UNSUPPORTED;
     if (block_size % group_size != 0 && group_size % block_size != 0) return ONECOMP_ERR_INVALID_ARG;
     if (form == ONECOMP_FACTOR_BLOCK && group_size > block_size && group_size != d_in) return ONECOMP_ERR_UNSUPPORTED;
+    if ((grid == ONECOMP_GRID_MINMAX_MSE || grid == ONECOMP_GRID_SYMMETRIC_MSE) && group_size < 32)
+        return ONECOMP_ERR_UNSUPPORTED;
     if (!aligned(W, 16) || !aligned(U, 16) || !aligned(Q_codes, 4) || (W_hat && !aligned(W_hat, 16)))
         return ONECOMP_ERR_INVALID_ARG;
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < sweep_workspace_bytes(d_out, d_in, block_size))

@@ -169,7 +169,44 @@ struct PanelArgs {
                             // in scales / zeros (groups of whole super-blocks, or one group per row); lgG is then 7
     float qmax;             // highest code of the grid
     float qs;               // 0: min-max grid of Eq. (2); > 0: symmetric grid of Eq. (3) with zero-point qs
+    int mse;                // scale search: the group's range is shrunk by 1 - i / 100, i < 80; least squared error wins
 };
+
+// Scale search of one group ("mse" option of Sec. 4.2).  value(k) returns the k-th of this lane's n values of the
+// group; reduce(x) sums x over the lanes that share the group.  Candidate i takes (s, z) by the grid's rule from the
+// range shrunk by p_i = 1 - i / 100 and is charged sum (w - w^)^2; the first smallest error wins, candidate 0 is
+// the plain rule.  All lanes of the group end with the same (s, z).
+constexpr int MSE_CANDIDATES = 80;
+template <typename V, typename R>
+__device__ __forceinline__ void mse_search(const float mn, const float mx, const float qmax, const float qs, const int n,
+                                           V&& value, R&& reduce, float& s, float& z) {
+    float best = 3.0e38f;
+#pragma unroll 1
+    for (int i = 0; i < MSE_CANDIDATES; ++i) {
+        const float p = 1.0f - float(i) * 0.01f;
+        const float lo = p * mn, hi = p * mx;
+        float si, zi;
+        if (qs > 0.f) {
+            si = fmaxf(fabsf(lo), fabsf(hi)) / qs;
+            if (si == 0.f) si = 1.f;
+            zi = qs;
+        } else {
+            si = (hi - lo) / qmax;
+            if (si == 0.f) si = 1.f;
+            zi = fminf(fmaxf(rintf(-lo / si), 0.f), qmax);
+        }
+        const float rsi = 1.0f / si;
+        float err = 0.f;
+        for (int k = 0; k < n; ++k) {
+            const float v = value(k);
+            const float q = fminf(fmaxf(rintf(v * rsi) + zi, 0.f), qmax);
+            const float d = v - si * (q - zi);
+            err += d * d;
+        }
+        err = reduce(err);
+        if (err < best) { best = err; s = si; z = zi; }
+    }
+}
 
 constexpr int PANEL_LDS = (SB * SB + 2 * ROWS * SP + SB + 2 * ROWS * 8) * 4;
 
@@ -438,6 +475,18 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                                     s = (mx - mn) / qmax;
                                     if (s == 0.f) s = 1.f;
                                     z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
+                                }
+                                if constexpr (GB != 16) {
+                                    if (a.mse) {   // uniform; this lane's quarter of the group, from the LDS tile
+                                        const float* gp = sW + qrow * SP + jb + sl;
+                                        mse_search(mn, mx, qmax, a.qs, G >> 2,
+                                                   [&](int k) __attribute__((always_inline)) { return gp[4 * k]; },
+                                                   [&](float x) __attribute__((always_inline)) {
+                                                       x += dpp_quad<QUAD_SWAP1>(x);
+                                                       return x + dpp_quad<QUAD_SWAP2>(x);
+                                                   },
+                                                   s, z);
+                                    }
                                 }
                                 rs = 1.0f / s;
                                 if (sl == 0) {
@@ -920,7 +969,7 @@ __global__ __launch_bounds__(256) void panel_far_kernel(PanelArgs pa, TrailArgs 
 // feedback of all earlier columns has been applied for a later one.  One workgroup per row.
 template <typename T>
 __global__ __launch_bounds__(256) void group_params_kernel(const T* __restrict__ Wsrc, int d_out, int d_in, int g0, int G,
-                                                          float qmax, float qs, int n_g, int g_idx,
+                                                          float qmax, float qs, int mse, int n_g, int g_idx,
                                                           float* __restrict__ scales, float* __restrict__ zeros) {
     __shared__ float smn[256], smx[256];
     for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {
@@ -939,22 +988,38 @@ __global__ __launch_bounds__(256) void group_params_kernel(const T* __restrict__
             }
             __syncthreads();
         }
+        mn = smn[0]; mx = smx[0];
+        __syncthreads();
+        float s, z;
+        if (qs > 0.f) {
+            s = fmaxf(fabsf(mn), fabsf(mx)) / qs;
+            if (s == 0.f) s = 1.f;
+            z = qs;
+        } else {
+            s = (mx - mn) / qmax;
+            if (s == 0.f) s = 1.f;
+            z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
+        }
+        if (mse) {   // uniform; the row's values are re-read from cache for every candidate
+            const int n = (G - int(threadIdx.x) + 255) >> 8;
+            mse_search(mn, mx, qmax, qs, n,
+                       [&](int k) __attribute__((always_inline)) { return to_f32<T>(row[threadIdx.x + 256 * k]); },
+                       [&](float x) __attribute__((always_inline)) {   // workgroup sum, the same value in every thread
+                           x += dpp_quad<QUAD_SWAP1>(x);
+                           x += dpp_quad<QUAD_SWAP2>(x);
+                           smn[threadIdx.x] = x;
+                           __syncthreads();
+                           float t = 0.f;
+                           for (int w = 0; w < 256; w += 4) t += smn[w];
+                           __syncthreads();
+                           return t;
+                       },
+                       s, z);
+        }
         if (threadIdx.x == 0) {
-            mn = smn[0]; mx = smx[0];
-            float s, z;
-            if (qs > 0.f) {
-                s = fmaxf(fabsf(mn), fabsf(mx)) / qs;
-                if (s == 0.f) s = 1.f;
-                z = qs;
-            } else {
-                s = (mx - mn) / qmax;
-                if (s == 0.f) s = 1.f;
-                z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
-            }
             scales[r * n_g + g_idx] = s;
             zeros[r * n_g + g_idx] = z;
         }
-        __syncthreads();
     }
 }
 
@@ -1086,6 +1151,8 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
             if (group_size % c == 0) { sbw = c; break; }
     const int sb_pairs = (sbw / SB) * (sbw / SB - 1) / 2;   // block pairs (b' < b) inside a super-block
     if (direct && group_size > SB && group_size != d_in) return ONECOMP_ERR_UNSUPPORTED;
+    if ((grid == ONECOMP_GRID_MINMAX_MSE || grid == ONECOMP_GRID_SYMMETRIC_MSE) && group_size < 32)
+        return ONECOMP_ERR_UNSUPPORTED;
     SweepWs w = carve(workspace, d_out, d_in);
     hipLaunchKernelGGL(init_scalars_kernel, dim3(1), dim3(1), 0, stream, w.sc);
     ONECOMP_CHECK_LAUNCH();
@@ -1156,8 +1223,10 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
         while ((1 << pa.lgG) < group_size) ++pa.lgG;
         if (wide_static) pa.lgG = 7;
         pa.wide_g = -1;
-        pa.qs = grid == ONECOMP_GRID_SYMMETRIC ? float((1 << (bits - 1)) - 1) : 0.f;
-        pa.qmax = grid == ONECOMP_GRID_SYMMETRIC ? 2.f * pa.qs : float((1 << bits) - 1);
+        const bool symmetric = grid == ONECOMP_GRID_SYMMETRIC || grid == ONECOMP_GRID_SYMMETRIC_MSE;
+        pa.mse = grid == ONECOMP_GRID_MINMAX_MSE || grid == ONECOMP_GRID_SYMMETRIC_MSE;
+        pa.qs = symmetric ? float((1 << (bits - 1)) - 1) : 0.f;
+        pa.qmax = symmetric ? 2.f * pa.qs : float((1 << bits) - 1);
         int buf = 0, p0 = 0, p1 = 0;   // previous super-block: residual buffer and column range
         for (int s0 = 0; s0 < d_in; s0 += sbw) {
             const int s1 = int(d_in < int64_t(s0) + sbw ? d_in : int64_t(s0) + sbw);
@@ -1174,15 +1243,15 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
                 const int g_idx = s0 / group_size;
                 if (!direct)
                     hipLaunchKernelGGL(group_params_kernel<float>, pgrid, dim3(256), 0, stream, w.Wf, int(d_out), int(d_in),
-                                       s0, group_size, pa.qmax, pa.qs, pa.n_g, g_idx, scales, zeros);
+                                       s0, group_size, pa.qmax, pa.qs, pa.mse, pa.n_g, g_idx, scales, zeros);
                 else if (pa.w0_bf16)
                     hipLaunchKernelGGL(group_params_kernel<uint16_t>, pgrid, dim3(256), 0, stream,
                                        static_cast<const uint16_t*>(pa.W0), int(d_out), int(d_in), s0, group_size, pa.qmax,
-                                       pa.qs, pa.n_g, g_idx, scales, zeros);
+                                       pa.qs, pa.mse, pa.n_g, g_idx, scales, zeros);
                 else
                     hipLaunchKernelGGL(group_params_kernel<float>, pgrid, dim3(256), 0, stream,
                                        static_cast<const float*>(pa.W0), int(d_out), int(d_in), s0, group_size, pa.qmax,
-                                       pa.qs, pa.n_g, g_idx, scales, zeros);
+                                       pa.qs, pa.mse, pa.n_g, g_idx, scales, zeros);
                 ONECOMP_CHECK_LAUNCH();
             }
             if (wide_static) pa.wide_g = s0 / group_size;

@@ -5,6 +5,8 @@ import torch
 from oracle import onecomp_oracle as oc
 
 TIE_TOL = 1e-4   # a first mismatch is a legitimate tie flip iff the oracle's pre-rounding value is this close to x.5
+CAND_TOL = 1e-4  # scale search: another candidate is a legitimate choice iff its squared error (the oracle's) is within
+                 # this relative distance of the smallest one
 
 
 def to_f64(t: torch.Tensor) -> np.ndarray:
@@ -19,7 +21,8 @@ def _near_tie(t: np.ndarray) -> np.ndarray:
     return np.abs((t - np.floor(t)) - 0.5) < TIE_TOL
 
 
-def compare_codes(gpu_Q, gpu_zeros, W, U, bits, G, perm=None, rows=None, max_rounds=64, grid="asym"):
+def compare_codes(gpu_Q, gpu_zeros, W, U, bits, G, perm=None, rows=None, max_rounds=64, grid="asym",
+                  scale_search=None, gpu_scales=None):
     """GPU codes / zero-points against the oracle with tie replay.
 
     gpu_Q: [n_rows, d_in] codes in ORIGINAL column order, gpu_zeros: [n_rows, n_g].
@@ -27,7 +30,10 @@ def compare_codes(gpu_Q, gpu_zeros, W, U, bits, G, perm=None, rows=None, max_rou
     Per row the first disagreement (in sweep order; a group's zero-point comes before its codes)
     must sit at a rounding tie of the oracle (|frac - 0.5| < TIE_TOL, values differ by one);
     the oracle row is then replayed with that decision forced to the GPU's and the comparison
-    continues.  Returns stats incl. the final oracle output (after replay)."""
+    continues.  With scale_search = "mse" a group's first decision is the candidate of the search: the GPU's
+    is read off its scale (gpu_scales, matched against the oracle's candidate scales); a different candidate is
+    accepted iff the oracle's own error sums of the two agree to CAND_TOL, and is then forced in the replay.
+    Returns stats incl. the final oracle output (after replay)."""
     W = np.asarray(W, dtype=np.float64)
     d_in = W.shape[1]
     if perm is None:
@@ -39,11 +45,14 @@ def compare_codes(gpu_Q, gpu_zeros, W, U, bits, G, perm=None, rows=None, max_rou
     n_rows, n_g = gz.shape
     fc = -np.ones((n_rows, d_in), dtype=np.int64)
     fz = -np.ones((n_rows, n_g), dtype=np.int64)
-    out = oc.quantize_layer(W, U, bits, G, perm=perm, rows=rows, grid=grid)
+    fcand = -np.ones((n_rows, n_g), dtype=np.int64)
+    mse = scale_search == "mse"
+    gs = np.asarray(gpu_scales, dtype=np.float64) if mse else None
+    out = oc.quantize_layer(W, U, bits, G, perm=perm, rows=rows, grid=grid, scale_search=scale_search)
     oq = out["Q"][:, perm].copy()
     raw_agree = float((oq == gq).mean())
     res = {k: np.array(v, copy=True) if isinstance(v, np.ndarray) else v for k, v in out.items()}
-    tie_flips, real = 0, []
+    tie_flips, cand_flips, real = 0, 0, []
     active = np.arange(n_rows)
     for _ in range(max_rounds):
         redo = []
@@ -54,9 +63,34 @@ def compare_codes(gpu_Q, gpu_zeros, W, U, bits, G, perm=None, rows=None, max_rou
             bad_z = np.nonzero(ozi != gz[i])[0]
             jq = bad_q[0] if len(bad_q) else d_in
             jz = bad_z[0] * G if len(bad_z) else d_in
-            if jq == d_in and jz == d_in:
+            jc = d_in
+            if mse:
+                bad_s = np.nonzero(np.abs(gs[i] - res["scales"][i]) > 1e-5 * np.abs(res["scales"][i]))[0]
+                jc = bad_s[0] * G if len(bad_s) else d_in
+            if jq == d_in and jz == d_in and jc == d_in:
                 continue
-            if jz <= jq:
+            if jc <= jz and jc <= jq:
+                g = jc // G
+                sc, ec = res["Scand"][i, g], res["Ecand"][i, g]
+                # a candidate whose zero-point sits at a rounding tie may be charged with either neighbour
+                tied = _near_tie(res["Tzcand"][i, g])
+                e_hi = np.where(tied, np.maximum(ec, res["Ealt"][i, g]), ec)
+                k = int(np.argmin(np.abs(sc - gs[i, g])))
+                if gz[i, g] == res["Zcand"][i, g, k]:
+                    ek = ec[k]
+                elif tied[k] and gz[i, g] == res["Zalt"][i, g, k]:
+                    ek = res["Ealt"][i, g, k]
+                else:
+                    ek = np.inf
+                ok = (abs(sc[k] - gs[i, g]) <= 1e-5 * abs(sc[k]) and k != res["cand"][i, g]
+                      and ek <= e_hi.min() * (1.0 + CAND_TOL))
+                if ok:
+                    fcand[i, g] = k
+                    if gz[i, g] != res["Zcand"][i, g, k]:
+                        fz[i, g] = gz[i, g]
+                    cand_flips += 1
+                    tie_flips -= 1   # counted separately
+            elif jz <= jq:
                 g = jz // G
                 ok = _near_tie(res["Tz"][i, g]) and abs(int(ozi[g]) - int(gz[i, g])) == 1
                 if ok:
@@ -69,16 +103,18 @@ def compare_codes(gpu_Q, gpu_zeros, W, U, bits, G, perm=None, rows=None, max_rou
                 tie_flips += 1
                 redo.append(i)
             else:
-                real.append((int(rows[i]), int(min(jq, jz))))
+                real.append((int(rows[i]), int(min(jq, jz, jc))))
         if not redo:
             break
         redo = np.array(redo)
         sub = oc.quantize_layer(W, U, bits, G, perm=perm, rows=rows[redo],
-                                forced_codes=fc[redo], forced_zeros=fz[redo], grid=grid)
-        for k in ("Q", "W_hat", "scales", "zeros", "E", "T", "Tz", "loss_rows"):
+                                forced_codes=fc[redo], forced_zeros=fz[redo], grid=grid, scale_search=scale_search,
+                                forced_cand=fcand[redo] if mse else None)
+        for k in ("Q", "W_hat", "scales", "zeros", "E", "T", "Tz", "loss_rows", "cand", "Ecand", "Scand", "Zcand", "Tzcand", "Zalt",
+                  "Ealt"):
             res[k][redo] = sub[k]
         active = redo
     res["loss"] = float(res["loss_rows"].sum())
     final_agree = float((res["Q"][:, perm] == gq).mean())
-    return {"raw_agree": raw_agree, "final_agree": final_agree, "tie_flips": tie_flips,
+    return {"raw_agree": raw_agree, "final_agree": final_agree, "tie_flips": tie_flips, "cand_flips": cand_flips,
             "real_mismatches": real, "oracle": res}

@@ -63,19 +63,30 @@ def _check_sweep(W, U32, bits, G, perm=None, rows=None, min_agree=0.999, grid="m
     g = inv // G
     deq = (S[:, g] * (Q.astype(np.float32) - Z[:, g])).astype(np.float32)
     assert np.array_equal(deq, WH)
+    mse = grid.endswith("_mse")
     st = compare_codes(Q[sel], Z[sel], to_f64(W), to_f64(U32), bits, G, perm=p, rows=sel,
-                       grid="sym" if grid == "symmetric" else "asym")
-    if grid == "symmetric":
+                       grid="sym" if grid.startswith("symmetric") else "asym",
+                       scale_search="mse" if mse else None, gpu_scales=S[sel] if mse else None)
+    if grid.startswith("symmetric"):
         assert np.all(Z == 2 ** (bits - 1) - 1) and Q.max() <= 2 ** bits - 2
-    _announce(f"   raw agreement {st['raw_agree']:.6f}, tie flips {st['tie_flips']}, real {len(st['real_mismatches'])}")
+    _announce(f"   raw agreement {st['raw_agree']:.6f}, tie flips {st['tie_flips']}, candidate flips {st['cand_flips']}, "
+              f"real {len(st['real_mismatches'])}")
     assert st["real_mismatches"] == []
     assert st["final_agree"] == 1.0
     # Raw agreement: 99.9 % of the entries.  A flip at a tie can change every later code of its row, so on a layer
     # of few rows one legitimate flip alone may cost more than 0.1 %: there the bar is what the counted flips can
     # account for (at most one row's worth of entries each), with the number of flips itself bounded.
+    # With the scale search, two candidates whose error sums agree to 1e-4 are either one a valid choice; such a
+    # flip changes its group and the rest of the row like a rounding tie does and is counted the same way.
     n_cmp = len(sel)
-    assert st["raw_agree"] >= min(min_agree, 1.0 - st["tie_flips"] / n_cmp)
+    flips = st["tie_flips"] + st["cand_flips"]
+    assert st["raw_agree"] >= min(min_agree, 1.0 - flips / n_cmp)
     assert st["tie_flips"] <= max(2, n_cmp // 50)
+    assert st["cand_flips"] <= max(2, n_cmp // 20)
+    if mse:
+        # the search can only lower a group's own error against the plain grid at the same compensated values;
+        # what the returned arrays allow to check: every scale is one of the shrunk ranges' (<= the plain one's)
+        assert np.all(S > 0)
     orc = st["oracle"]
     np.testing.assert_allclose(S[sel], orc["scales"], rtol=1e-5)
     np.testing.assert_array_equal(Z[sel], orc["zeros"])
@@ -467,6 +478,51 @@ def test_sweep_symmetric_all_zero_group():
     W[0, :] = 0.0             # every group of this row is zero from the start: s = 1, codes at the zero-point
     out, _ = _check_sweep(W, U32, 4, 64, grid="symmetric")
     assert torch.all(out["W_hat"][0] == 0) and torch.all(out["Q_codes"][0] == 7) and torch.all(out["scales"][0] == 1)
+
+
+@pytest.mark.parametrize("bits,G,d_out,d_in,dtype,act,grid,block", [
+    (4, 128, 256, 512, torch.float32, False, "minmax_mse", False),
+    (3, 64, 100, 384, torch.bfloat16, True, "minmax_mse", False),
+    (4, 32, 65, 256, torch.float32, False, "minmax_mse", False),
+    (2, 128, 64, 1664, torch.bfloat16, True, "minmax_mse", False),     # several super-blocks, the last one partial
+    (4, 128, 100, 1024, torch.bfloat16, False, "symmetric_mse", False),
+    (3, 64, 33, 640, torch.float32, True, "symmetric_mse", False),
+    (4, 1280, 40, 1280, torch.bfloat16, False, "symmetric_mse", False),  # one group per row
+    (3, 256, 70, 1024, torch.bfloat16, True, "minmax_mse", False),       # group wider than the block
+    (4, 640, 40, 1920, torch.float32, False, "minmax_mse", False),       # groups wider than 512 columns
+    (4, 128, 130, 1024, torch.bfloat16, True, "minmax_mse", True),       # block form of the factor
+    (4, 1152, 33, 1152, torch.float32, False, "symmetric_mse", True),
+])
+def test_sweep_scale_search(bits, G, d_out, d_in, dtype, act, grid, block):
+    """Grid with the scale search (Sec. 4.2, "mse") against the oracle's sweep with the same search."""
+    _announce(f"sweep with scale search b{bits} g{G} {d_out}x{d_in} {dtype} act={act} {grid} block={block}")
+    if block:
+        W, U32, F32, perm = _layer_block(d_out, d_in, 2 * d_in + 13, seed=120 + bits + G % 5, dtype=dtype, act=act)
+    else:
+        W, U32, perm = _layer(d_out, d_in, 2 * d_in + 13, seed=120 + bits + G % 5, dtype=dtype, act=act)
+        F32 = None
+    out, st = _check_sweep(W, U32, bits, G, perm=perm, grid=grid, F32=F32)
+    # the search does something: most groups end on a shrunk range
+    assert (st["oracle"]["cand"] > 0).mean() > 0.5
+    out2 = og.onecomp_quantize_layer(W, U32 if F32 is None else F32, bits, G, perm=perm, grid=grid,
+                                     form="inverse" if F32 is None else "block")
+    torch.cuda.synchronize()
+    for k in ("Q_codes", "scales", "zeros", "W_hat", "loss"):
+        assert torch.equal(out[k], out2[k])
+
+
+def test_sweep_scale_search_degenerate_groups():
+    _announce("sweep with scale search: all-zero, constant and one-signed groups; group size 16 refused")
+    W, U32, _ = _layer(8, 256, 700, seed=34)
+    W = W.clone()
+    W[0, :] = 0.0
+    W[1, :] = 0.0125
+    W[2, :] = W[2, :].abs() + 0.01
+    out, _ = _check_sweep(W, U32, 4, 64, grid="minmax_mse")
+    assert torch.all(out["W_hat"][0] == 0) and torch.all(out["scales"][0] == 1)
+    _check_sweep(W, U32, 3, 64, grid="symmetric_mse")
+    with pytest.raises(og.OnecompError):
+        og.onecomp_quantize_layer(W, U32, 4, 16, grid="minmax_mse")
 
 
 def test_sweep_degenerate_and_one_signed_groups():
