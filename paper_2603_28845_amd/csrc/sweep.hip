@@ -172,14 +172,19 @@ struct PanelArgs {
     int mse;                // scale search: the group's range is shrunk by 1 - i / 100, i < 80; least squared error wins
 };
 
-// Scale search of one group ("mse" option of Sec. 4.2).  value(k) returns the k-th of this lane's n values of the
-// group; reduce(x) sums x over the lanes that share the group.  Candidate i takes (s, z) by the grid's rule from the
-// range shrunk by p_i = 1 - i / 100 and is charged sum (w - w^)^2; the first smallest error wins, candidate 0 is
-// the plain rule.  All lanes of the group end with the same (s, z).
+// Scale search of one group ("mse" option of Sec. 4.2).  partial(s, z, 1 / s) returns the sum of (w - w^)^2 over
+// this lane's values of the group on the grid (s, z) (mse_term per value); reduce(x) sums x over the lanes that share
+// the group.  Candidate i takes (s, z) by the grid's rule from the range shrunk by p_i = 1 - i / 100; the first
+// smallest error wins, candidate 0 is the plain rule.  All lanes of the group end with the same (s, z).
 constexpr int MSE_CANDIDATES = 80;
-template <typename V, typename R>
-__device__ __forceinline__ void mse_search(const float mn, const float mx, const float qmax, const float qs, const int n,
-                                           V&& value, R&& reduce, float& s, float& z) {
+__device__ __forceinline__ float mse_term(float v, float si, float zi, float rsi, float qmax) {
+    const float q = fminf(fmaxf(rintf(v * rsi) + zi, 0.f), qmax);
+    const float d = v - si * (q - zi);
+    return d * d;
+}
+template <typename P, typename R>
+__device__ __forceinline__ void mse_search(const float mn, const float mx, const float qmax, const float qs,
+                                           P&& partial, R&& reduce, float& s, float& z) {
     float best = 3.0e38f;
 #pragma unroll 1
     for (int i = 0; i < MSE_CANDIDATES; ++i) {
@@ -195,15 +200,7 @@ __device__ __forceinline__ void mse_search(const float mn, const float mx, const
             if (si == 0.f) si = 1.f;
             zi = fminf(fmaxf(rintf(-lo / si), 0.f), qmax);
         }
-        const float rsi = 1.0f / si;
-        float err = 0.f;
-        for (int k = 0; k < n; ++k) {
-            const float v = value(k);
-            const float q = fminf(fmaxf(rintf(v * rsi) + zi, 0.f), qmax);
-            const float d = v - si * (q - zi);
-            err += d * d;
-        }
-        err = reduce(err);
+        const float err = reduce(partial(si, zi, 1.0f / si));
         if (err < best) { best = err; s = si; z = zi; }
     }
 }
@@ -477,10 +474,36 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                                     z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
                                 }
                                 if constexpr (GB != 16) {
-                                    if (a.mse) {   // uniform; this lane's quarter of the group, from the LDS tile
+                                    if (a.mse) {   // uniform; this lane's quarter of the group, held in registers
                                         const float* gp = sW + qrow * SP + jb + sl;
-                                        mse_search(mn, mx, qmax, a.qs, G >> 2,
-                                                   [&](int k) __attribute__((always_inline)) { return gp[4 * k]; },
+                                        float gv[32];
+#pragma unroll
+                                        for (int k = 0; k < 32; ++k) gv[k] = gp[(4 * k) & (G - 1)];
+                                        const int n8 = G >> 5;   // batches of 8 values: 1, 2 or 4
+                                        mse_search(mn, mx, qmax, a.qs,
+                                                   [&](float si, float zi, float rsi) __attribute__((always_inline)) {
+                                                       float e0 = 0.f, e1 = 0.f;
+#pragma unroll
+                                                       for (int k = 0; k < 8; k += 2) {
+                                                           e0 += mse_term(gv[k], si, zi, rsi, qmax);
+                                                           e1 += mse_term(gv[k + 1], si, zi, rsi, qmax);
+                                                       }
+                                                       if (n8 > 1) {
+#pragma unroll
+                                                           for (int k = 8; k < 16; k += 2) {
+                                                               e0 += mse_term(gv[k], si, zi, rsi, qmax);
+                                                               e1 += mse_term(gv[k + 1], si, zi, rsi, qmax);
+                                                           }
+                                                       }
+                                                       if (n8 > 2) {
+#pragma unroll
+                                                           for (int k = 16; k < 32; k += 2) {
+                                                               e0 += mse_term(gv[k], si, zi, rsi, qmax);
+                                                               e1 += mse_term(gv[k + 1], si, zi, rsi, qmax);
+                                                           }
+                                                       }
+                                                       return e0 + e1;
+                                                   },
                                                    [&](float x) __attribute__((always_inline)) {
                                                        x += dpp_quad<QUAD_SWAP1>(x);
                                                        return x + dpp_quad<QUAD_SWAP2>(x);
@@ -1001,9 +1024,12 @@ __global__ __launch_bounds__(256) void group_params_kernel(const T* __restrict__
             z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
         }
         if (mse) {   // uniform; the row's values are re-read from cache for every candidate
-            const int n = (G - int(threadIdx.x) + 255) >> 8;
-            mse_search(mn, mx, qmax, qs, n,
-                       [&](int k) __attribute__((always_inline)) { return to_f32<T>(row[threadIdx.x + 256 * k]); },
+            mse_search(mn, mx, qmax, qs,
+                       [&](float si, float zi, float rsi) __attribute__((always_inline)) {
+                           float e = 0.f;
+                           for (int c = threadIdx.x; c < G; c += 256) e += mse_term(to_f32<T>(row[c]), si, zi, rsi, qmax);
+                           return e;
+                       },
                        [&](float x) __attribute__((always_inline)) {   // workgroup sum, the same value in every thread
                            x += dpp_quad<QUAD_SWAP1>(x);
                            x += dpp_quad<QUAD_SWAP2>(x);

@@ -564,7 +564,7 @@ def test_end_to_end_c1():
 
 
 # ------------------------------------------------------------- full size, sampled oracle ---
-def _full_size_sampled(name, n_rows, act):
+def _full_size_sampled(name, n_rows, act, search=False):
     """One full-size layer of the benchmark configurations (bf16, d_in 14336): Gram against the oracle, both forms
     of the factor against the oracle's for the same H, sweep on sampled rows with tie replay, both forms.  The
     calibration set is cut to 32768 tokens (still more than 2 d_in, so H has full rank as in the real workload)
@@ -605,6 +605,11 @@ def _full_size_sampled(name, n_rows, act):
     # 99 % here, the flips themselves are bounded, and agreement after replaying the flips must still be exact.
     _, st = _check_sweep(W, U32, cfg.bits, cfg.group_size, perm=perm if act else None, rows=rows, min_agree=0.99)
     assert st["tie_flips"] <= 4
+    if search:
+        _announce("full size: sweep with the scale search, same rows")
+        _, st = _check_sweep(W, U32, cfg.bits, cfg.group_size, perm=perm if act else None, rows=rows, min_agree=0.99,
+                             grid="minmax_mse")
+        assert st["tie_flips"] <= 4
     del U32
     _announce("full size: factor in block form")
     F, _, info = og.onecomp_hessian_factor(torch.from_numpy(H32).to(DEV), cfg.damp, act_order=act, form="block")
@@ -624,7 +629,7 @@ def _full_size_sampled(name, n_rows, act):
 
 def test_full_size_down_projection_sampled():
     """The 4096 x 14336 layer in the launch configuration bench.py times (4-bit, group 128, natural order)."""
-    _full_size_sampled("c3b", 48, act=False)
+    _full_size_sampled("c3b", 48, act=False, search=True)
 
 
 def test_full_size_act_order_3bit_sampled():
