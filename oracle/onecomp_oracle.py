@@ -25,6 +25,8 @@ What it computes (paper sections given in brackets):
     blocks  [a restatement of Sec. 4.2, derived in quantize_layer_direct]
   * the scale search of the sweep ("mse": per group, candidate ranges shrunk from the observed one, the smallest
     squared reconstruction error wins)  [Sec. 4.2; the candidate set is this build's reading, see mse_search]
+  * JointQ's local search over codes with the group scale refit in the same move (jointq_refine)
+    [Sec. 4.2.2, Eq. (jointq); order of moves and stopping are this build's reading, see the function]
   * the corrected quantization target of error propagation (QEP),
     W* = (I + alpha (H^ + lambda I)^-1 C) W  with  C = X^^T (X - X^)  [Sec. 4.2.1, Eq. (qep)]
 
@@ -521,6 +523,121 @@ def qep_target(W, G, H, damp, alpha):
     cf = cho_factor(Hd, lower=True)
     corr = cho_solve(cf, R.T).T                  # R Hd^-1 (Hd symmetric)
     return W + float(alpha) * corr
+
+
+# --------------------------------------------------------------------------
+# JointQ: local search over integer codes with the group scale refit in the same move  [Sec. 4.2.2, Eq. (jointq)]
+# --------------------------------------------------------------------------
+def row_objective(W, W_hat, A):
+    """Per row (w - w^) A (w - w^)^T: the objective of Eq. (jointq) for one output row when A = X^T X up to the
+    constant factor this build carries in H (Eq. (jointq_reg): A = H + lam I, the augmented input matrix)."""
+    D = np.asarray(W, dtype=np.float64) - np.asarray(W_hat, dtype=np.float64)
+    return ((D @ np.asarray(A, dtype=np.float64)) * D).sum(axis=1)
+
+
+def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=1, max_scans=4, rows=None,
+                  forced=None, tie_tol=0.0, g_tol=0.0):
+    """Local search of Sec. 4.2.2 on a solution in the per-group format of Eq. (4), rows independent.
+
+    What the paper fixes: one move changes one integer code by a small amount inside the codebook, the scale of
+    that code's group is refit in the same step to the codes, a move is kept iff the objective of Eq. (jointq)
+    falls, and the search stops when no move improves; a GPTQ result may serve as the start.  What it leaves open
+    and this build reads as follows: the change is +-1; zero-points stay as given; the groups of a row are visited
+    in order, n_pass times; inside a visit the columns of the group are scanned in order, for each column +1 is
+    tried before -1 and the first improving one is taken at once (at most one per column and scan); the visit ends
+    with the first scan that takes no move, or after max_scans scans; on entering a visit the group's scale is
+    first refit to its current codes; a group whose codes all equal its zero-point is left alone.
+
+    One visit, one row, group t with codes q, u = q - z, residual r = w - w^ over the whole row:
+        p = (A r)_t + s_old A_tt u     (= (A r0)_t with r0 the residual with group t taken out; fixed in the visit)
+        b = u.p,  c = u.A_tt u,        best scale s* = b / c,  objective = r0 A r0^T - b^2 / c .
+    Move u' = u + d e_j:  b' = b + d p_j,  c' = c + 2 d a_j + A_jj  with a = A_tt u.  With g = p_j - s* a_j (the
+    gradient at the refit scale) and D = c A_jj - a_j^2:
+        N = c' (b'^2 / c' - b^2 / c) = 2 d b g + g^2 + 2 s* g a_j - s*^2 D ,
+    and the move is taken iff N > 0 and c' > 0 (the objective then falls by N / c').
+
+    W [d_out, d_in]; A symmetric [d_in, d_in]; Q codes, scales / zeros [d_out, n_g] as the sweep returns them
+    (natural column order).  forced: {(row, pass, t, scan, j, d): bool} overrides single decisions (rows numbered
+    within the subset); with tie_tol > 0 every decision with |N| <= tie_tol * M + 2 |b| g_tol (|r| |A|)_j, M the sum
+    of the absolute values of the terms N is built from, is listed in "ties".
+    Returns dict(Q, scales, W_hat, f0, f1 (row objective before / after), moves [rows], ties [list per row])."""
+    W = np.asarray(W, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    sel = np.arange(W.shape[0]) if rows is None else np.asarray(rows)
+    W = W[sel]
+    Q = np.array(np.asarray(Q)[sel], dtype=np.float64, copy=True)
+    S = np.array(np.asarray(scales)[sel], dtype=np.float64, copy=True)
+    Z = np.asarray(zeros, dtype=np.float64)[sel]
+    n, d_in = W.shape
+    G = int(group_size)
+    n_g = d_in // G
+    qtop = code_range_top(bits, grid)
+    forced = forced or {}
+    ties = [[] for _ in range(n)]
+    moves = np.zeros(n, dtype=np.int64)
+
+    def dequant():
+        return np.repeat(S, G, axis=1) * (Q - np.repeat(Z, G, axis=1))
+
+    f0 = row_objective(W, dequant(), A)
+    absA = np.abs(A) if g_tol > 0.0 else None
+    for ps in range(int(n_pass)):
+        for t in range(n_g):
+            cs = slice(t * G, (t + 1) * G)
+            r = W - dequant()
+            g = r @ A[:, cs]
+            gabs = np.abs(r) @ absA[:, cs] if g_tol > 0.0 else np.zeros_like(g)
+            Att = A[cs, cs]
+            u = Q[:, cs] - Z[:, t][:, None]
+            a = u @ Att
+            s_old = S[:, t].copy()
+            p = g + s_old[:, None] * a
+            b = (u * p).sum(axis=1)
+            c = (u * a).sum(axis=1)
+            live = c > 0.0
+            active = live.copy()
+            for scan in range(int(max_scans)):
+                took = np.zeros(n, dtype=bool)
+                for j in range(G):
+                    done = np.zeros(n, dtype=bool)
+                    for d in (1.0, -1.0):
+                        qn = Q[:, t * G + j] + d
+                        ok = active & ~done & (qn >= 0.0) & (qn <= qtop)
+                        if not ok.any():
+                            continue
+                        aj, pj, Ajj = a[:, j], p[:, j], Att[j, j]
+                        cc = np.where(live, c, 1.0)
+                        ss = b / cc
+                        gs = pj - ss * aj
+                        N = 2.0 * d * b * gs + gs * gs + 2.0 * ss * gs * aj - ss * ss * (cc * Ajj - aj * aj)
+                        cn = c + 2.0 * d * aj + Ajj
+                        acc = ok & (N > 0.0) & (cn > 0.0)
+                        if tie_tol > 0.0 or g_tol > 0.0:
+                            M = (2.0 * np.abs(b) * (np.abs(pj) + np.abs(ss * aj)) + gs * gs + 2.0 * np.abs(ss * gs * aj)
+                                 + ss * ss * (cc * Ajj + aj * aj))
+                            near = ok & (np.abs(N) <= tie_tol * M + 2.0 * np.abs(b) * g_tol * gabs[:, j])
+                            for i in np.nonzero(near)[0]:
+                                ties[i].append((ps, t, scan, j, int(d)))
+                        for i in np.nonzero(ok)[0] if forced else ():
+                            key = (int(i), ps, t, scan, j, int(d))
+                            if key in forced:
+                                acc[i] = bool(forced[key]) and cn[i] > 0.0
+                        if acc.any():
+                            Q[acc, t * G + j] += d
+                            u[acc, j] += d
+                            b = np.where(acc, b + d * pj, b)
+                            c = np.where(acc, cn, c)
+                            a[acc] += d * Att[j][None, :]
+                            done |= acc
+                            took |= acc
+                            moves += acc
+                active &= took
+                if not active.any():
+                    break
+            S[:, t] = np.where(live, b / np.where(live, c, 1.0), s_old)
+    What = dequant()
+    return {"Q": Q.astype(np.int64), "scales": S, "W_hat": What, "f0": f0, "f1": row_objective(W, What, A),
+            "moves": moves, "ties": ties}
 
 
 # --------------------------------------------------------------------------
