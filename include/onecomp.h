@@ -301,6 +301,42 @@ onecomp_status onecomp_rtn_sensitivity(const void* W, onecomp_dtype w_dtype, int
                                        void* workspace, size_t workspace_bytes, void* hip_stream);
 size_t onecomp_sensitivity_workspace_bytes(void);
 
+/*
+ * JointQ refinement of a quantized layer (Sec. 4.2.2, Eq. (jointq); with lam > 0 Eq. (jointq_reg)): local search over
+ * the integer codes, the scale of the touched group refit in the same move, started from a solution in the format
+ * onecomp_quantize_layer returns (natural column order, perm == NULL).  Per output row the objective is
+ * f = (w - w^) (H + lam I) (w - w^)^T, w^ = s_g (q - z_g).
+ *
+ * Moves, order and stopping (the paper fixes only "one code changes a little, the group's scale is refit in the same
+ * step, the move is kept iff the objective falls"): codes change by +-1 inside 0 .. 2^bits - 1 (0 .. 2 (2^(bits-1) - 1)
+ * for the symmetric grids); zero-points stay; the groups are visited in order, n_pass times; on entering a visit the
+ * group's scale is refit to its codes (s = u.p / u.A_tt u with u = q - z, p the gradient of the row's residual with
+ * the group taken out); the group's columns are then scanned in order, +1 is tried before -1, the first of the two
+ * that lowers f is taken at once; a visit ends with the first scan that takes nothing, or after max_scans scans.  A
+ * group whose codes all equal its zero-point is left alone.
+ *
+ *   W         device, d_out x d_in, row-major, fp32 or bf16: the weights the objective measures against.
+ *   H         device fp32, d_in x d_in, symmetric (as onecomp_hessian_accumulate leaves it), read only.
+ *   lam       >= 0, added to the diagonal of H (in the paper's terms 2 n lambda, since H = 2 X^T X).
+ *   group_size  multiple of 16, at most 128, divides d_in.
+ *   Q_codes, scales  device, in and out (d_out x d_in uint8, d_out x d_in/group_size fp32).
+ *   zeros     device fp32, d_out x d_in/group_size, read only.
+ *   W_hat     device fp32 d_out x d_in or NULL, out: s (q - z) of the result.
+ *   objective device fp32[2], out: sum over rows of f before and after.
+ *   n_moves   device int32, out: number of moves taken.
+ *   workspace device scratch, >= onecomp_jointq_workspace_bytes() (about 8 d_out d_in bytes), 256-byte aligned.
+ * Arithmetic: fp32 throughout (fp32 MFMA for the gradient R (H + lam I) and its rank-group_size updates).  A decision
+ * whose gain is within rounding of zero may fall either way; results are reproducible run to run.
+ * Errors: INVALID_ARG (null pointer, bad size, lam < 0, n_pass < 0, max_scans < 1), UNSUPPORTED (dtype, bits, grid,
+ * group_size > 128 or not a multiple of 16), WORKSPACE.
+ */
+onecomp_status onecomp_jointq_refine(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                     const float* H, float lam, int bits, int group_size, onecomp_grid grid,
+                                     int n_pass, int max_scans, uint8_t* Q_codes, float* scales, const float* zeros,
+                                     float* W_hat, float* objective, int32_t* n_moves,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t onecomp_jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size);
+
 /* Static, NUL-terminated description of a status code. */
 const char* onecomp_status_string(onecomp_status status);
 

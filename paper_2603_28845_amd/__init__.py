@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     onecomp_factor_workspace_bytes,
     onecomp_hessian_accumulate,
     onecomp_hessian_factor,
+    onecomp_jointq_refine,
+    onecomp_jointq_workspace_bytes,
     onecomp_qep_target,
     onecomp_qep_workspace_bytes,
     onecomp_quantize_layer,

@@ -44,6 +44,8 @@ EXPORTED_SYMBOLS = (
     "onecomp_qep_workspace_bytes",
     "onecomp_rtn_sensitivity",
     "onecomp_sensitivity_workspace_bytes",
+    "onecomp_jointq_refine",
+    "onecomp_jointq_workspace_bytes",
     "onecomp_status_string",
     "onecomp_version",
 )
@@ -100,6 +102,11 @@ def load_library() -> ctypes.CDLL:
     lib.onecomp_rtn_sensitivity.restype = i32
     lib.onecomp_sensitivity_workspace_bytes.argtypes = []
     lib.onecomp_sensitivity_workspace_bytes.restype = sz
+    lib.onecomp_jointq_refine.argtypes = [vp, i32, i64, i64, vp, f32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp,
+                                          sz, vp]
+    lib.onecomp_jointq_refine.restype = i32
+    lib.onecomp_jointq_workspace_bytes.argtypes = [i64, i64, i32]
+    lib.onecomp_jointq_workspace_bytes.restype = sz
     lib.onecomp_status_string.argtypes = [i32]
     lib.onecomp_status_string.restype = ctypes.c_char_p
     lib.onecomp_version.argtypes = []
@@ -320,3 +327,35 @@ def onecomp_rtn_sensitivity(W: torch.Tensor, a_diag: torch.Tensor, bits: int, gr
     if rc != ONECOMP_OK:
         raise OnecompError(rc, "onecomp_rtn_sensitivity")
     return err
+
+
+def onecomp_jointq_workspace_bytes(d_out: int, d_in: int, group_size: int) -> int:
+    return int(load_library().onecomp_jointq_workspace_bytes(int(d_out), int(d_in), int(group_size)))
+
+
+def onecomp_jointq_refine(W: torch.Tensor, H: torch.Tensor, Q_codes: torch.Tensor, scales: torch.Tensor,
+                          zeros: torch.Tensor, bits: int, group_size: int, grid: str = "minmax", lam: float = 0.0,
+                          n_pass: int = 1, max_scans: int = 4, want_w_hat: bool = True,
+                          workspace: Optional[torch.Tensor] = None) -> dict:
+    """Refines Q_codes and scales IN PLACE; returns dict(Q_codes, scales, W_hat (or None), objective [2] = row
+    objective summed over the layer before and after, n_moves) of device tensors."""
+    lib = load_library()
+    d_out, d_in = W.shape
+    dev = W.device
+    if grid not in _GRIDS:
+        raise ValueError("grid must be one of " + ", ".join(sorted(_GRIDS)))
+    if workspace is None:
+        workspace = torch.empty(max(onecomp_jointq_workspace_bytes(d_out, d_in, group_size), 256), dtype=torch.uint8,
+                                device=dev)
+    W_hat = torch.empty((d_out, d_in), dtype=torch.float32, device=dev) if want_w_hat else None
+    objective = torch.zeros(2, dtype=torch.float32, device=dev)
+    n_moves = torch.zeros(1, dtype=torch.int32, device=dev)
+    rc = lib.onecomp_jointq_refine(_dev(W, "W"), _dtype_code(W), d_out, d_in, _dev(H, "H", torch.float32), float(lam),
+                                   int(bits), int(group_size), _GRIDS[grid], int(n_pass), int(max_scans),
+                                   _dev(Q_codes, "Q_codes", torch.uint8), _dev(scales, "scales", torch.float32),
+                                   _dev(zeros, "zeros", torch.float32), _ptr(W_hat),
+                                   _dev(objective, "objective", torch.float32), _dev(n_moves, "n_moves", torch.int32),
+                                   _dev(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    if rc != ONECOMP_OK:
+        raise OnecompError(rc, "onecomp_jointq_refine")
+    return {"Q_codes": Q_codes, "scales": scales, "W_hat": W_hat, "objective": objective, "n_moves": n_moves}

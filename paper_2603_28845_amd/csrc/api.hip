@@ -157,6 +157,35 @@ ONECOMP_API onecomp_status onecomp_qep_target(const void* W, onecomp_dtype w_dty
                           static_cast<hipStream_t>(hip_stream));
 }
 
+ONECOMP_API size_t onecomp_jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size) {
+    if (d_out <= 0 || d_in <= 0 || group_size <= 0 || group_size > 128 || group_size % 16 != 0 || d_in % group_size != 0)
+        return 0;
+    return jointq_workspace_bytes(d_out, d_in, group_size);
+}
+
+ONECOMP_API onecomp_status onecomp_jointq_refine(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                                 const float* H, float lam, int bits, int group_size,
+                                                 onecomp_grid grid, int n_pass, int max_scans, uint8_t* Q_codes,
+                                                 float* scales, const float* zeros, float* W_hat, float* objective,
+                                                 int32_t* n_moves, void* workspace, size_t workspace_bytes,
+                                                 void* hip_stream) {
+    if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
+    if (grid != ONECOMP_GRID_MINMAX && grid != ONECOMP_GRID_SYMMETRIC && grid != ONECOMP_GRID_MINMAX_MSE &&
+        grid != ONECOMP_GRID_SYMMETRIC_MSE)
+        return ONECOMP_ERR_UNSUPPORTED;
+    if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return ONECOMP_ERR_UNSUPPORTED;
+    if (!W || !H || !Q_codes || !scales || !zeros || !objective || !n_moves) return ONECOMP_ERR_INVALID_ARG;
+    if (d_out <= 0 || d_in <= 0 || d_out > (1 << 24) || d_in > (1 << 20)) return ONECOMP_ERR_INVALID_ARG;
+    if (!(lam >= 0.0f) || n_pass < 0 || max_scans < 1) return ONECOMP_ERR_INVALID_ARG;
+    if (group_size <= 0 || d_in % 16 != 0 || d_in % group_size != 0) return ONECOMP_ERR_INVALID_ARG;
+    if (group_size % 16 != 0 || group_size > 128) return ONECOMP_ERR_UNSUPPORTED;
+    if (!aligned(W, 16) || !aligned(H, 16) || (W_hat && !aligned(W_hat, 16))) return ONECOMP_ERR_INVALID_ARG;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < jointq_workspace_bytes(d_out, d_in, group_size))
+        return ONECOMP_ERR_WORKSPACE;
+    return jointq_run(W, w_dtype, d_out, d_in, H, lam, bits, group_size, int(grid), n_pass, max_scans, Q_codes, scales,
+                      zeros, W_hat, objective, n_moves, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
 ONECOMP_API size_t onecomp_sensitivity_workspace_bytes(void) { return sensitivity_workspace_bytes(); }
 
 ONECOMP_API onecomp_status onecomp_rtn_sensitivity(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,

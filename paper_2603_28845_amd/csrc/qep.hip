@@ -10,6 +10,7 @@
 // 4 waves in 2 x 2 (64 x 64 each), operands staged through registers into double-buffered LDS, K step 16.
 // The triangular structure of U halves the second and third product (k ranges cut per column tile).
 #include "common.hpp"
+#include "sgemm.hpp"
 
 namespace onecomp {
 namespace {
@@ -19,22 +20,6 @@ constexpr int SK = 16;     // K per LDS stage
 constexpr int SPA = SK + 1;      // pitch of a k-contiguous tile (rows x SK)
 constexpr int SPB = ST + 4;      // pitch of a k-major tile (SK x cols)
 constexpr int SSB = ST * SPA;    // >= SK * SPB
-
-enum : int { S_BTRANS = 1, S_BUPPER_T = 2, S_BUPPER = 4 };
-
-struct SgemmArgs {
-    const float* A; int64_t lda;     // m x k, k contiguous
-    const float* B; int64_t ldb;     // S_BTRANS: n x k (k contiguous), else k x n
-    float* C; int64_t ldc;           // m x n out (plain store), or nullptr when the fused epilogue is used
-    int m, n, k;
-    int flags;                       // S_BUPPER_T: B given transposed is upper triangular as n x k (zero for k < n)
-                                     // S_BUPPER:   B (k x n) is upper triangular (zero for k > n)
-    // fused epilogue (C == nullptr): out[r][colmap ? colmap[c] : c] = base[r][c] + alpha * acc
-    const float* base; int64_t ldbase;
-    const int32_t* colmap;
-    float* out; int64_t ldout;
-    float alpha;
-};
 
 template <bool bt>
 __global__ __launch_bounds__(256, 2) void sgemm_kernel(SgemmArgs g) {
@@ -147,6 +132,8 @@ __global__ __launch_bounds__(256, 2) void sgemm_kernel(SgemmArgs g) {
             }
 }
 
+}  // namespace
+
 onecomp_status sgemm(const SgemmArgs& g, hipStream_t stream) {
     if (g.m <= 0 || g.n <= 0) return ONECOMP_OK;
     dim3 grid(unsigned(ceil_div(g.n, ST)), unsigned(ceil_div(g.m, ST)));
@@ -155,6 +142,8 @@ onecomp_status sgemm(const SgemmArgs& g, hipStream_t stream) {
     ONECOMP_CHECK_LAUNCH();
     return ONECOMP_OK;
 }
+
+namespace {
 
 // Cp[a][b] = G[p(a)][p(b)] - H[p(a)][p(b)]   (p = perm, or the identity)
 __global__ __launch_bounds__(256) void cp_kernel(const float* __restrict__ G, const float* __restrict__ H, int n,

@@ -118,3 +118,72 @@ def compare_codes(gpu_Q, gpu_zeros, W, U, bits, G, perm=None, rows=None, max_rou
     final_agree = float((res["Q"][:, perm] == gq).mean())
     return {"raw_agree": raw_agree, "final_agree": final_agree, "tie_flips": tie_flips, "cand_flips": cand_flips,
             "real_mismatches": real, "oracle": res}
+
+
+JQ_TIE_TOL = 1e-4   # JointQ: a decision is a legitimate toss-up iff |N| is within this fraction of the terms it sums
+JQ_G_TOL = 2e-6     # ... plus this fraction of sum |r_k| |A_kj|, the rounding of the fp32 gradient kept on the GPU
+
+
+def _jq_prefix(o, i, gq, gs, G, n_g):
+    """Number of leading groups (visit order of one pass) in which oracle row i equals the GPU row."""
+    for t in range(n_g):
+        same = (np.array_equal(o["Q"][i, t * G:(t + 1) * G], gq[t * G:(t + 1) * G])
+                and abs(o["scales"][i, t] - gs[t]) <= 1e-4 * abs(o["scales"][i, t]))
+        if not same:
+            return t
+    return n_g
+
+
+def compare_jointq(gpu_Q, gpu_S, W, A, Q0, S0, Z, bits, G, grid="asym", n_pass=1, max_scans=4, rows=None,
+                   max_flips=6, max_tries=16):
+    """GPU result of onecomp_jointq_refine against the oracle's local search from the same start.
+
+    A row must equal the oracle's exactly in its codes (scales to 1e-4), or become equal once decisions the oracle
+    itself lists as toss-ups (JQ_TIE_TOL, JQ_G_TOL) are forced the other way: per mismatching row the oracle is
+    rerun with one listed decision forced at a time, a flip is kept when the rows then agree over more leading
+    groups (for several passes: when they agree entirely), up to max_flips flips.
+    Returns dict(clean_rows, flipped_rows, flips, real_mismatches, oracle)."""
+    W = np.asarray(W, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    rows = np.arange(W.shape[0]) if rows is None else np.asarray(rows)
+    gq = np.asarray(gpu_Q, dtype=np.int64)
+    gs = np.asarray(gpu_S, dtype=np.float64)
+    n_g = W.shape[1] // G
+    kw = dict(bits=bits, group_size=G, grid=grid, n_pass=n_pass, max_scans=max_scans, tie_tol=JQ_TIE_TOL,
+              g_tol=JQ_G_TOL)
+    o = oc.jointq_refine(W, A, Q0, S0, Z, rows=rows, **kw)
+    res = {k: (np.array(v, copy=True) if isinstance(v, np.ndarray) else v) for k, v in o.items()}
+    clean, flipped, flips, real = 0, 0, 0, []
+    for i in range(len(rows)):
+        if _jq_prefix(o, i, gq[i], gs[i], G, n_g) == n_g:
+            clean += 1
+            continue
+        forced, cur, ok = {}, None, False
+        cur = oc.jointq_refine(W, A, Q0, S0, Z, rows=rows[i:i + 1], **kw)
+        for _ in range(max_flips):
+            pre = _jq_prefix(cur, 0, gq[i], gs[i], G, n_g)
+            if pre == n_g:
+                ok = True
+                break
+            cands = [k for k in cur["ties"][0] if (0,) + k not in forced and (n_pass > 1 or k[1] == pre)]
+            best = None
+            for k in cands[:max_tries]:
+                for val in (True, False):
+                    f2 = dict(forced)
+                    f2[(0,) + k] = val
+                    trial = oc.jointq_refine(W, A, Q0, S0, Z, rows=rows[i:i + 1], forced=f2, **kw)
+                    pre2 = _jq_prefix(trial, 0, gq[i], gs[i], G, n_g)
+                    if pre2 > pre and (best is None or pre2 > best[0]):
+                        best = (pre2, f2, trial)
+            if best is None:
+                break
+            _, forced, cur = best
+            flips += 1
+        ok = ok or _jq_prefix(cur, 0, gq[i], gs[i], G, n_g) == n_g
+        if ok:
+            flipped += 1
+            for k in ("Q", "scales", "W_hat", "f0", "f1", "moves"):
+                res[k][i] = cur[k][0]
+        else:
+            real.append(int(rows[i]))
+    return {"clean_rows": clean, "flipped_rows": flipped, "flips": flips, "real_mismatches": real, "oracle": res}
