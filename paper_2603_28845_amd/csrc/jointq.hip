@@ -17,8 +17,8 @@
 // (A r)_t, so the whole layer moves through the groups together:
 //   * Gm = R A (d_out x d_in, fp32) is built once (fp32 MFMA GEMM) and kept current;
 //   * visit kernel: one wave per row, the group's columns spread over the lanes (two per lane at G = 128), A_tt in
-//     LDS (shared by the rows of a workgroup); the decisions of a row are sequential and wave-uniform, an accepted
-//     move updates a with one LDS row;
+//     LDS (shared by the 16 rows of a workgroup); the lanes evaluate their columns' moves together, a ballot picks
+//     the first improving one in scan order, a taken move updates a with one LDS row;
 //   * after the visit the change of the residual of the group, dR (d_out x G), is fed back by one rank-G update
 //     Gm += dR A[t, :] (fp32 MFMA GEMM), which is where the flops are (2 d_out d_in^2 per pass).
 #include "common.hpp"
@@ -27,7 +27,7 @@
 namespace onecomp {
 namespace {
 
-constexpr int JQ_ROWS = 4;   // rows (waves) per workgroup of the visit kernel
+constexpr int JQ_ROWS = 16;   // rows (waves) per workgroup of the visit kernel
 
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll
@@ -112,15 +112,21 @@ struct VisitArgs {
     int32_t* moves;
 };
 
-// NC = columns per lane (1: G <= 64, 2: G <= 128)
+// NC = columns per lane (1: G <= 64, 2: G <= 128).  The scan "columns in order, first improving move wins" is run as:
+// every lane evaluates the gain of its own columns under the current state, a ballot finds the first improving
+// column behind the last one taken, that move is applied, and the evaluation is repeated.  The columns between two
+// taken moves are rejected under the same state the sequential scan would see, so the sequence of moves is the same,
+// at one wave-wide evaluation per taken move instead of one per column.
 template <int NC>
 __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     extern __shared__ float sA[];   // G x G: A_tt + lam I
     const int G = v.G;
     const int c0 = v.t * G;
-    for (int e = threadIdx.x; e < G * G; e += 64 * JQ_ROWS) {
+    for (int e = threadIdx.x * 4; e < G * G; e += 64 * JQ_ROWS * 4) {
         const int k = e / G, c = e - k * G;
-        sA[e] = v.A[int64_t(c0 + k) * v.d_in + c0 + c] + (k == c ? v.lam : 0.f);
+        float4v x = *reinterpret_cast<const float4v*>(v.A + int64_t(c0 + k) * v.d_in + c0 + c);
+        if (k >= c && k < c + 4) x[k - c] += v.lam;
+        *reinterpret_cast<float4v*>(sA + e) = x;
     }
     __syncthreads();
     const int lane = threadIdx.x & 63;
@@ -129,7 +135,7 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
 
     const float z = v.zeros[int64_t(row) * v.n_g + v.t];
     const float s_old = v.scales[int64_t(row) * v.n_g + v.t];
-    float u[NC], u0[NC], a[NC], p[NC], q[NC];
+    float u[NC], u0[NC], a[NC], p[NC], q[NC], ad[NC];
     bool has[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
@@ -140,6 +146,7 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         u[c] = q[c] - z;
         u0[c] = u[c];
         a[c] = 0.f;
+        ad[c] = has[c] ? sA[col * G + col] : 1.f;
         // (A r)_t + lam r_t + s_old (A_tt + lam I) u  =  Gm + lam w + s_old A_tt u; the lam u part comes with a below
         p[c] = has[c] ? v.Gm[i] + v.lam * (load_w(v.W, v.w_bf16, i) - s_old * u[c]) : 0.f;
     }
@@ -168,38 +175,56 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     int n_moves = 0;
     if (live) {
         float ss = b / cc;
-        for (int scan = 0; scan < v.max_scans; ++scan) {
-            bool took = false;
+        int scan = 0, j0 = -1;   // j0: the column of the last move taken in this scan
+        bool took = false;
+        for (;;) {
+            bool imp[NC];
+            float dd[NC];
 #pragma unroll
-            for (int cu = 0; cu < NC; ++cu) {
-                const int jn = G - 64 * cu < 64 ? G - 64 * cu : 64;
-                for (int jl = 0; jl < jn; ++jl) {
-                    const int j = 64 * cu + jl;
-                    const float aj = readlane_f(a[cu], jl);
-                    const float pj = readlane_f(p[cu], jl);
-                    const float qj = readlane_f(q[cu], jl);
-                    const float Ajj = sA[j * G + j];
-                    const float gs = pj - ss * aj;
-                    const float base = gs * gs + 2.0f * ss * gs * aj - ss * ss * (cc * Ajj - aj * aj);
-                    const float t1 = 2.0f * b * gs;
-                    float d = 0.f;
-                    if (qj + 1.0f <= v.qtop && base + t1 > 0.f && cc + 2.0f * aj + Ajj > 0.f) d = 1.0f;
-                    else if (qj - 1.0f >= 0.f && base - t1 > 0.f && cc - 2.0f * aj + Ajj > 0.f) d = -1.0f;
-                    if (d != 0.f) {   // wave-uniform
-                        b += d * pj;
-                        cc += 2.0f * d * aj + Ajj;
-                        ss = b / cc;
-                        if (lane == jl) { u[cu] += d; q[cu] += d; }
-                        const float* rowj = sA + j * G + lane;
-#pragma unroll
-                        for (int c = 0; c < NC; ++c)
-                            if (has[c]) a[c] += d * rowj[64 * c];
-                        took = true;
-                        ++n_moves;
-                    }
-                }
+            for (int c = 0; c < NC; ++c) {
+                const float gs = p[c] - ss * a[c];
+                const float base = gs * gs + 2.0f * ss * gs * a[c] - ss * ss * (cc * ad[c] - a[c] * a[c]);
+                const float t1 = 2.0f * b * gs;
+                const bool up = q[c] + 1.0f <= v.qtop && base + t1 > 0.f && cc + 2.0f * a[c] + ad[c] > 0.f;
+                const bool dn = q[c] - 1.0f >= 0.f && base - t1 > 0.f && cc - 2.0f * a[c] + ad[c] > 0.f;
+                imp[c] = has[c] && (up || dn);
+                dd[c] = up ? 1.0f : -1.0f;
             }
-            if (!took) break;
+            int j = -1;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                if (j >= 0) continue;
+                uint64_t m = __ballot(imp[c]);
+                const int lo = j0 - 64 * c;          // columns up to lo (local numbering) are behind
+                if (lo >= 63) m = 0;
+                else if (lo >= 0) m &= ~((uint64_t(2) << lo) - 1);
+                if (m) j = 64 * c + __builtin_ctzll(m);
+            }
+            if (j < 0) {   // the scan is over
+                if (!took || ++scan >= v.max_scans) break;
+                took = false;
+                j0 = -1;
+                continue;
+            }
+            float d, pj, aj, adj;
+            if (NC == 1 || j < 64) {
+                d = readlane_f(dd[0], j); pj = readlane_f(p[0], j); aj = readlane_f(a[0], j); adj = readlane_f(ad[0], j);
+                if (lane == j) { u[0] += d; q[0] += d; }
+            } else {
+                d = readlane_f(dd[NC - 1], j - 64); pj = readlane_f(p[NC - 1], j - 64);
+                aj = readlane_f(a[NC - 1], j - 64); adj = readlane_f(ad[NC - 1], j - 64);
+                if (lane == j - 64) { u[NC - 1] += d; q[NC - 1] += d; }
+            }
+            b += d * pj;
+            cc += 2.0f * d * aj + adj;
+            ss = b / cc;
+            const float* rowj = sA + j * G + lane;
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                if (has[c]) a[c] += d * rowj[64 * c];
+            took = true;
+            j0 = j;
+            ++n_moves;
         }
     }
     const float s_new = live ? b / cc : s_old;

@@ -116,3 +116,48 @@ def test_jointq_degenerate_rows_and_zero_passes():
     assert float(o0["objective"][0]) == float(o0["objective"][1])
     with pytest.raises(og.OnecompError):
         og.onecomp_jointq_refine(W, torch.from_numpy(H32).to(DEV), Q, S[:, :1].contiguous(), Z[:, :1].contiguous(), 4, 256)
+
+
+def test_jointq_full_size_sampled():
+    """The 4096 x 14336 layer of the benchmark (bf16, 4-bit, group 128): the whole layer is refined on the GPU, a
+    sample of rows is compared with the oracle.  The sampled rows start from the oracle's own sweep, the other rows
+    from the GPU's (rows are independent); H is the oracle's Gram matrix of 32768 tokens rounded to fp32."""
+    cfg = synth.scaled(synth.CONFIGS["c3b"], n_tokens=32768)
+    d_out, d_in, G, bits = cfg.d_out, cfg.d_in, cfg.group_size, cfg.bits
+    _announce(f"jointq full size {d_out}x{d_in} b{bits} g{G}: oracle Gram and factor")
+    W = synth.make_weight(cfg, DEV)
+    X = synth.make_activations(cfg, DEV)
+    H32 = oc.hessian_accumulate(to_f64(X)).astype(np.float32)
+    del X
+    A = H32.astype(np.float64)
+    f = oc.hessian_factor(A, cfg.damp)
+    rows = np.sort(np.random.default_rng(11).choice(d_out, size=12, replace=False))
+    Wd = to_f64(W)
+    _announce("jointq full size: oracle sweep of the sampled rows, GPU sweep of the layer")
+    o0 = oc.quantize_layer(Wd, f["U"], bits, G, rows=rows)
+    H = torch.from_numpy(H32).to(DEV)
+    U32 = torch.from_numpy(f["U"].astype(np.float32)).to(DEV)
+    del f
+    g0 = og.onecomp_quantize_layer(W, U32, bits, G, want_w_hat=False)
+    del U32
+    Q, S, Z = g0["Q_codes"], g0["scales"], g0["zeros"]
+    ridx = torch.from_numpy(rows).to(DEV)
+    Q[ridx] = torch.from_numpy(o0["Q"].astype(np.uint8)).to(DEV)
+    S[ridx] = torch.from_numpy(o0["scales"].astype(np.float32)).to(DEV)
+    Z[ridx] = torch.from_numpy(o0["zeros"].astype(np.float32)).to(DEV)
+    _announce("jointq full size: GPU refinement, one pass")
+    out = og.onecomp_jointq_refine(W, H, Q, S, Z, bits, G, n_pass=1, max_scans=4, want_w_hat=False)
+    torch.cuda.synchronize()
+    obj = out["objective"].cpu().numpy()
+    _announce(f"   objective {obj[0]:.4e} -> {obj[1]:.4e}, moves {int(out['n_moves'].item())}")
+    assert obj[1] < 0.8 * obj[0]
+    gq = out["Q_codes"][ridx].cpu().numpy()
+    gs = out["scales"][ridx].cpu().numpy()
+    _announce("jointq full size: oracle refinement of the sampled rows")
+    S0f = o0["scales"].astype(np.float32).astype(np.float64)
+    st = compare_jointq(gq, gs, Wd[rows], A, o0["Q"], S0f, o0["zeros"], bits, G, n_pass=1, max_scans=4)
+    _announce(f"   clean rows {st['clean_rows']}/{len(rows)}, rows equal after {st['flips']} forced toss-ups: "
+              f"{st['flipped_rows']}, real mismatches {len(st['real_mismatches'])}")
+    assert st["real_mismatches"] == []
+    assert np.array_equal(st["oracle"]["Q"], gq)
+    np.testing.assert_allclose(gs, st["oracle"]["scales"], rtol=1e-4)
