@@ -111,6 +111,39 @@ def cpu_baseline(cfg, synth, seconds_hint=20.0):
     }
 
 
+def bench_jointq(args, cfg, og, W, H, out):
+    """JointQ refinement (Sec. 4.2.2) of the sweep's result: args.jointq passes over the groups, four scans per
+    visit, on the H of the timed steps.  The refinement works on copies; two timed calls after one warm-up."""
+    import torch
+    d_out, d_in, G = cfg.d_out, cfg.d_in, cfg.group_size
+    base_grid = "symmetric" if args.grid.startswith("symmetric") else "minmax"
+    ws = torch.empty(og.onecomp_jointq_workspace_bytes(d_out, d_in, G), dtype=torch.uint8, device=W.device)
+    ms = []
+    for it in range(3):
+        Q, S = out["Q_codes"].clone(), out["scales"].clone()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        e[0].record()
+        r = og.onecomp_jointq_refine(W, H, Q, S, out["zeros"], cfg.bits, G, grid=base_grid, n_pass=args.jointq,
+                                     max_scans=4, workspace=ws, want_w_hat=False)
+        e[1].record()
+        torch.cuda.synchronize()
+        if it > 0:
+            ms.append(e[0].elapsed_time(e[1]))
+    t = sum(ms) / len(ms)
+    obj = r["objective"].tolist()
+    flops = 2.0 * d_out * d_in * d_in * (1 + args.jointq)
+    return {
+        "what": f"onecomp_jointq_refine on the sweep's codes and scales: {args.jointq} pass(es) over the groups, up to 4 "
+                "scans per visit, lam 0",
+        "ms": t, "weights_per_sec": d_out * d_in / (t * 1e-3),
+        "objective_before": obj[0], "objective_after": obj[1], "moves": int(r["n_moves"].item()),
+        "roofline": {"kernel": "sgemm_kernel (gradient R H once, then one rank-group update per visit) + jq_visit_kernel",
+                     "bound": "mfma", "achieved": flops / (t * 1e-3) / 1e12, "peak": 157.3, "unit": "TFLOP/s",
+                     "frac": flops / (t * 1e-3) / 1e12 / 157.3,
+                     "note": "fp32 MFMA flops 2 d_out d_in^2 (1 + passes) over the whole call, visit kernels included"},
+    }
+
+
 def bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out):
     """The layer with error propagation: X_hat = X perturbed by 5 % stands in for the activations of the partly
     quantized model.  One step = H from X_hat, G from (X_hat, X), factor, corrected target W*, sweep of W*."""
@@ -182,6 +215,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--phase", default="all", choices=["all", "gram", "factor", "sweep"],
                     help="profiling aid: run only one call in the timed loop (the others run once to prepare its inputs)")
+    ap.add_argument("--jointq", type=int, default=1,
+                    help="passes of the JointQ refinement (Sec. 4.2.2) timed on the result of the last step and "
+                         "reported under 'jointq' (0 = skip; skipped for activation ordering and groups wider than "
+                         "128); the headline value is unchanged")
     ap.add_argument("--qep", action="store_true",
                     help="also time the layer with error propagation (Sec. 4.2.1): Gram of the perturbed activations, "
                          "cross-Gram, factor, corrected target, sweep of the corrected target; reported under 'qep', "
@@ -428,6 +465,8 @@ def main():
             "frac_of_bf16_peak": 2.0 * T * d_in * d_in / (v_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "gram_kernel_ms_for_the_same_tokens": acc_ms,
         }
+    if args.jointq > 0 and phase == "all" and not cfg.act_order and cfg.group_size <= 128:
+        res["jointq"] = bench_jointq(args, cfg, og, W, H, out)
     if args.qep:
         res["qep"] = bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out)
     if not args.no_cpu_baseline:

@@ -19,14 +19,19 @@
 //   * visit kernel: one wave per row, the group's columns spread over the lanes (two per lane at G = 128), A_tt in
 //     LDS (shared by the 16 rows of a workgroup); the lanes evaluate their columns' moves together, a ballot picks
 //     the first improving one in scan order, a taken move updates a with one LDS row;
-//   * after the visit the change of the residual of the group, dR (d_out x G), is fed back by one rank-G update
-//     Gm += dR A[t, :] (fp32 MFMA GEMM), which is where the flops are (2 d_out d_in^2 per pass).
+//   * the change of the residual, dR = r_new - r_old on the group's columns, is fed back as Gm += dR A[t, :] (fp32
+//     MFMA GEMM, 2 d_out d_in^2 flops per pass: where the time goes).  Only the columns of the groups visited next
+//     need it at once: groups are bundled into super-blocks of up to 512 columns; after a visit the update goes to
+//     the super-block's own columns (k = G, n <= 512), and once the super-block is done all other columns receive
+//     its groups' updates in one product with k <= 512, so Gm is read and written d_in / 512 times per pass
+//     instead of d_in / G times.
 #include "common.hpp"
 #include "sgemm.hpp"
 
 namespace onecomp {
 namespace {
 
+constexpr int JQ_SBW = 512;   // columns of a super-block (at most)
 constexpr int JQ_ROWS = 16;   // rows (waves) per workgroup of the visit kernel
 
 __device__ __forceinline__ float wave_sum(float x) {
@@ -107,7 +112,8 @@ struct VisitArgs {
     const float* A; float lam;
     float qtop;
     uint8_t* Q; float* scales; const float* zeros;
-    const float* Gm; float* dR;
+    const float* Gm;
+    float* dR; int ldr;        // the group's dR: row r at dR + r * ldr
     int max_scans;
     int32_t* moves;
 };
@@ -234,7 +240,7 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         const int col = lane + 64 * c;
         const int64_t i = int64_t(row) * v.d_in + c0 + col;
         v.Q[i] = uint8_t(q[c]);
-        v.dR[int64_t(row) * G + col] = s_old * u0[c] - s_new * u[c];   // change of the residual w - w^
+        v.dR[int64_t(row) * v.ldr + col] = s_old * u0[c] - s_new * u[c];   // change of the residual w - w^
     }
     if (lane == 0) {
         v.scales[int64_t(row) * v.n_g + v.t] = s_new;
@@ -245,7 +251,7 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
 struct JqWs {
     float* R;      // d_out x d_in: residual at the start (operand of the first GEMM)
     float* Gm;     // d_out x d_in: R A, kept current
-    float* dR;     // d_out x G
+    float* dR;     // d_out x JQ_SBW: dR of the groups of the current super-block side by side
     float* rowf;   // d_out
 };
 
@@ -254,7 +260,7 @@ JqWs carve(void* ws, int64_t d_out, int64_t d_in, int G) {
     JqWs w;
     w.R = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * d_in * 4, 256);
     w.Gm = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * d_in * 4, 256);
-    w.dR = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * G * 4, 256);
+    w.dR = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * JQ_SBW * 4, 256);
     w.rowf = reinterpret_cast<float*>(p);
     return w;
 }
@@ -262,7 +268,8 @@ JqWs carve(void* ws, int64_t d_out, int64_t d_in, int G) {
 }  // namespace
 
 size_t jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size) {
-    return 2 * align_up(size_t(d_out) * d_in * 4, 256) + align_up(size_t(d_out) * group_size * 4, 256) +
+    (void)group_size;
+    return 2 * align_up(size_t(d_out) * d_in * 4, 256) + align_up(size_t(d_out) * JQ_SBW * 4, 256) +
            align_up(size_t(d_out) * 4, 256);
 }
 
@@ -308,18 +315,34 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
     v.A = A; v.lam = lam; v.qtop = qtop; v.Q = Q; v.scales = scales; v.zeros = zeros; v.Gm = w.Gm; v.dR = w.dR;
     v.max_scans = max_scans; v.moves = n_moves;
     const dim3 vgrid{unsigned(ceil_div(d_out, JQ_ROWS))};
+    const int sbg = JQ_SBW / G > 0 ? JQ_SBW / G : 1;   // groups per super-block
+    v.ldr = sbg * G;
     SgemmArgs up{};
-    up.A = w.dR; up.lda = G; up.ldb = d_in; up.C = nullptr; up.ldc = 0;
-    up.m = int(d_out); up.n = int(d_in); up.k = G; up.flags = 0;
-    up.base = w.Gm; up.ldbase = d_in; up.colmap = nullptr; up.out = w.Gm; up.ldout = d_in; up.alpha = 1.0f;
+    up.lda = v.ldr; up.ldb = d_in; up.C = nullptr; up.ldc = 0;
+    up.m = int(d_out); up.flags = 0;
+    up.ldbase = d_in; up.colmap = nullptr; up.ldout = d_in; up.alpha = 1.0f;
+    // Gm[:, c_lo .. c_hi) += dR[:, k_lo .. k_hi) A[t0 G + k_lo .. t0 G + k_hi, c_lo .. c_hi)
+    auto update = [&](int t0, int k_lo, int k_hi, int c_lo, int c_hi) -> onecomp_status {
+        if (c_hi <= c_lo || k_hi <= k_lo) return ONECOMP_OK;
+        up.A = w.dR + k_lo; up.k = k_hi - k_lo;
+        up.B = A + (int64_t(t0) * G + k_lo) * d_in + c_lo;
+        up.n = c_hi - c_lo;
+        up.base = w.Gm + c_lo; up.out = w.Gm + c_lo;
+        return sgemm(up, stream);
+    };
     for (int ps = 0; ps < n_pass; ++ps)
-        for (int t = 0; t < n_g; ++t) {
-            v.t = t;
-            if (G <= 64) hipLaunchKernelGGL(jq_visit_kernel<1>, vgrid, dim3(64 * JQ_ROWS), lds_bytes, stream, v);
-            else hipLaunchKernelGGL(jq_visit_kernel<2>, vgrid, dim3(64 * JQ_ROWS), lds_bytes, stream, v);
-            ONECOMP_CHECK_LAUNCH();
-            up.B = A + int64_t(t) * G * d_in;
-            if ((st = sgemm(up, stream)) != ONECOMP_OK) return st;
+        for (int t0 = 0; t0 < n_g; t0 += sbg) {
+            const int t1 = t0 + sbg < n_g ? t0 + sbg : n_g;
+            for (int t = t0; t < t1; ++t) {
+                v.t = t;
+                v.dR = w.dR + (t - t0) * G;
+                if (G <= 64) hipLaunchKernelGGL(jq_visit_kernel<1>, vgrid, dim3(64 * JQ_ROWS), lds_bytes, stream, v);
+                else hipLaunchKernelGGL(jq_visit_kernel<2>, vgrid, dim3(64 * JQ_ROWS), lds_bytes, stream, v);
+                ONECOMP_CHECK_LAUNCH();
+                if ((st = update(t0, (t - t0) * G, (t - t0 + 1) * G, t0 * G, t1 * G)) != ONECOMP_OK) return st;
+            }
+            if ((st = update(t0, 0, (t1 - t0) * G, 0, t0 * G)) != ONECOMP_OK) return st;
+            if ((st = update(t0, 0, (t1 - t0) * G, t1 * G, int(d_in))) != ONECOMP_OK) return st;
         }
     hipLaunchKernelGGL(jq_objective_kernel, rgrid, dim3(256), 0, stream, W, bf16, int(d_out), int(d_in), Q, scales, zeros,
                        G, n_g, w.Gm, lam, w.rowf, W_hat);

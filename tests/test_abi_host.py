@@ -273,3 +273,33 @@ def test_product_never_imports_the_oracle():
                 assert "oracle/" not in text and "onecomp_oracle" not in text, os.path.join(base, f)
     text = open(HEADER).read()
     assert "oracle" not in text.lower()
+
+
+def test_jointq_argument_checks(lib):
+    f = lib.onecomp_jointq_refine
+    big = ctypes.c_size_t(1 << 40)
+
+    def call(W=P, dt=1, d_out=64, d_in=256, H=P, lam=0.0, bits=4, G=128, grid=0, n_pass=1, scans=4, Q=P, s=P, z=P,
+             wh=NULL, obj=P, mv=P, ws=P, wsb=big):
+        return f(W, dt, d_out, d_in, H, lam, bits, G, grid, n_pass, scans, Q, s, z, wh, obj, mv, ws, wsb, NULL)
+
+    assert call(dt=3) == UNSUPPORTED
+    assert call(grid=7) == UNSUPPORTED
+    assert call(bits=5) == UNSUPPORTED
+    assert call(G=256, d_in=512) == UNSUPPORTED      # groups wider than 128
+    assert call(G=24, d_in=240) == UNSUPPORTED       # not a multiple of 16
+    assert call(W=NULL) == INVALID
+    assert call(H=NULL) == INVALID
+    assert call(Q=NULL) == INVALID
+    assert call(obj=NULL) == INVALID
+    assert call(mv=NULL) == INVALID
+    assert call(lam=-1.0) == INVALID
+    assert call(lam=float("nan")) == INVALID
+    assert call(n_pass=-1) == INVALID
+    assert call(scans=0) == INVALID
+    assert call(G=96) == INVALID                     # does not divide d_in
+    assert call(ws=NULL) == WORKSPACE
+    assert call(wsb=ctypes.c_size_t(1024)) == WORKSPACE
+    g = lib.onecomp_jointq_workspace_bytes
+    assert g(64, 256, 128) >= 2 * 64 * 256 * 4
+    assert g(64, 256, 256) == 0 and g(0, 256, 128) == 0 and g(64, 250, 50) == 0
