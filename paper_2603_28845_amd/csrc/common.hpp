@@ -67,6 +67,28 @@ constexpr uint32_t LDS_DMA_OOB = 0xFFFFFFF0u;
 // (expcnt and lgkmcnt fields at their no-wait maximum; vmcnt is split over bits 3:0 and 15:14)
 constexpr int wait_vmcnt(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
+// Device scalars of a split-fp16 product: maxima (as the bit patterns of non-negative floats, which order like
+// unsigned integers, so an integer atomic max is exact and order independent) and the power-of-two scales derived
+// from them.
+struct Scalars {
+    uint32_t max_w_bits;   // max |left operand| (the sweep: max |W|)
+    uint32_t max_u_bits;   // max |right operand| (the sweep: max |U_jk / U_jj| over the strict upper triangle)
+    float f_d;             // the left operand is stored as fp16 hi + lo of  x * f_d
+    float f_u;             // the right operand as fp16 hi + lo of  y * f_u
+    float f_all;           // f_d * f_u
+    float f_inv;           // 1 / (f_d * f_u)
+};
+
+// C[:, c0 .. c1) += f_inv * D^T B over k = 0 .. K-1 with fp32 accuracy from fp16 MFMAs (operands split hi + lo, three
+// products): C fp32 d_out x d_in row-major; D k-major, row ek + k holds the d_out left-operand values of k
+// (hi in Dh, lo in Dl, row length ldD = split_update_ld(d_out), the padding may hold anything finite);
+// B row-major with d_in columns, row u0 + k (hi in Bh, lo in Bl); sc->f_all and sc->f_inv are read on the device.
+// K % 32 == 0, c0 % 8 == 0, c1 % 8 == 0.
+onecomp_status split_update(float* C, int64_t d_out, int64_t d_in, const uint16_t* Dh, const uint16_t* Dl, int64_t ldD,
+                            const uint16_t* Bh, const uint16_t* Bl, const Scalars* sc, int ek, int K, int u0, int c0,
+                            int c1, hipStream_t stream);
+int64_t split_update_ld(int64_t d_out);
+
 // ---- entry points implemented in the kernel files -------------------------------------------
 size_t gram_workspace_bytes(int64_t d_in);
 onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx,

@@ -15,18 +15,22 @@
 //
 // gfx950 mapping.  The rows are independent and a visit only needs the row's gradient restricted to the group,
 // (A r)_t, so the whole layer moves through the groups together:
-//   * Gm = R A (d_out x d_in, fp32) is built once (fp32 MFMA GEMM) and kept current;
+//   * the gradient Gm = R A (d_out x d_in, fp32) is built once and kept current, stored column-normalized,
+//     Gm~_j = Gm_j / d_j with d_j = sqrt(A_jj);
 //   * visit kernel: one wave per row, the group's columns spread over the lanes (two per lane at G = 128), A_tt in
 //     LDS (shared by the 16 rows of a workgroup); the lanes evaluate their columns' moves together, a ballot picks
 //     the first improving one in scan order, a taken move updates a with one LDS row;
-//   * the change of the residual, dR = r_new - r_old on the group's columns, is fed back as Gm += dR A[t, :] (fp32
-//     MFMA GEMM, 2 d_out d_in^2 flops per pass: where the time goes).  Only the columns of the groups visited next
-//     need it at once: groups are bundled into super-blocks of up to 512 columns; after a visit the update goes to
-//     the super-block's own columns (k = G, n <= 512), and once the super-block is done all other columns receive
-//     its groups' updates in one product with k <= 512, so Gm is read and written d_in / 512 times per pass
-//     instead of d_in / G times.
+//   * the change of the residual, dR = r_new - r_old on the group's columns, is fed back as Gm += dR A[t, :]
+//     (2 d_out d_in^2 flops per pass: where the time goes).  Only the columns of the groups visited next need it at
+//     once: groups are bundled into super-blocks of up to 512 columns; after a visit the update goes to the
+//     super-block's own columns (k = G), and once the super-block is done all other columns receive its groups'
+//     updates in one product with k <= 512, so Gm is read and written d_in / 512 times per pass.
+//   * the products run on the fp16 MFMAs with fp32 accuracy, the split_update of the sweep (operands hi + lo, three
+//     products).  fp16 has no range to spare, and A's diagonal spans decades on activations with outlier channels,
+//     so A is used as the correlation matrix A~_kj = A_kj / (d_k d_j) (entries within [-1, 1], scaled by 2^14) and
+//     the left operands as (R d) resp. (dR d) scaled by a power of two taken from their own maximum on the device:
+//     Gm~ += (dR d) A~.  Each operand keeps 22 significant bits relative to itself.
 #include "common.hpp"
-#include "sgemm.hpp"
 
 namespace onecomp {
 namespace {
@@ -49,24 +53,133 @@ __device__ __forceinline__ float load_w(const void* W, int bf16, int64_t i) {
     return static_cast<const float*>(W)[i];
 }
 
-// R = W - s (q - z) over the whole layer
+constexpr float JQ_FU = 16384.f;   // scale of A~ (|A~| <= 1) in fp16
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+    return x;
+}
+
+// workgroup maximum of non-negative values into *dst (bit patterns order like the values); one atomic per workgroup
+__device__ __forceinline__ void block_max_bits(uint32_t* dst, float v, uint32_t* s_max) {
+    if (threadIdx.x == 0) *s_max = 0u;
+    __syncthreads();
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) atomicMax(s_max, __float_as_uint(v));
+    __syncthreads();
+    if (threadIdx.x == 0 && *s_max != 0u) atomicMax(dst, *s_max);
+}
+
+__global__ void jq_scalars_init_kernel(Scalars* sc, int n) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+        sc[i].max_w_bits = 0u; sc[i].max_u_bits = 0u;
+        sc[i].f_d = 1.f; sc[i].f_u = JQ_FU; sc[i].f_all = JQ_FU; sc[i].f_inv = 1.f / JQ_FU;
+    }
+}
+
+// d_j = sqrt(A_jj + lam); 1 for a dead channel without regularizer (its row and column of A are zero)
+__global__ __launch_bounds__(256) void jq_diag_kernel(const float* __restrict__ A, int n, float lam, float* __restrict__ d) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    const float x = A[int64_t(j) * n + j] + lam;
+    d[j] = x > 0.f ? sqrtf(x) : 1.f;
+}
+
+// A~ = (A + lam I)_kj / (d_k d_j) * 2^14 as fp16 hi + lo; rows n .. n_rows-1 (padding of the k range) are zero
+__global__ __launch_bounds__(256) void jq_asplit_kernel(const float* __restrict__ A, int n, int n_rows, float lam,
+                                                        const float* __restrict__ d, uint16_t* __restrict__ Bh,
+                                                        uint16_t* __restrict__ Bl) {
+    const int k = blockIdx.y;
+    const int j4 = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (j4 >= n) return;
+    short4v h4 = {0, 0, 0, 0}, l4 = {0, 0, 0, 0};
+    if (k < n) {
+        const float4v v = *reinterpret_cast<const float4v*>(A + int64_t(k) * n + j4);
+        const float rk = 1.0f / d[k];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float x = (v[e] + (j4 + e == k ? lam : 0.f)) * rk / d[j4 + e] * JQ_FU;
+            x = fminf(fmaxf(x, -60000.f), 60000.f);
+            const _Float16 h = (_Float16)x;
+            const _Float16 lo = (_Float16)(x - (float)h);
+            h4[e] = __builtin_bit_cast(short, h);
+            l4[e] = __builtin_bit_cast(short, lo);
+        }
+    }
+    *reinterpret_cast<short4v*>(Bh + int64_t(k) * n + j4) = h4;
+    *reinterpret_cast<short4v*>(Bl + int64_t(k) * n + j4) = l4;
+}
+
+// R = W - s (q - z) over the whole layer; max |R d| into sc->max_w_bits
 __global__ __launch_bounds__(256) void jq_residual_kernel(const void* __restrict__ W, int bf16, int d_out, int d_in,
                                                           const uint8_t* __restrict__ Q, const float* __restrict__ scales,
                                                           const float* __restrict__ zeros, int G, int n_g,
-                                                          float* __restrict__ R) {
+                                                          const float* __restrict__ d, float* __restrict__ R,
+                                                          Scalars* sc) {
+    __shared__ uint32_t s_max;
+    float mx = 0.f;
     for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x)
         for (int c = threadIdx.x; c < d_in; c += 256) {
             const int64_t i = r * d_in + c;
             const int g = c / G;
-            R[i] = load_w(W, bf16, i) - scales[r * n_g + g] * (float(Q[i]) - zeros[r * n_g + g]);
+            const float x = load_w(W, bf16, i) - scales[r * n_g + g] * (float(Q[i]) - zeros[r * n_g + g]);
+            R[i] = x;
+            mx = fmaxf(mx, fabsf(x) * d[c]);
         }
+    block_max_bits(&sc->max_w_bits, mx, &s_max);
 }
 
-// rowf[r] = sum_j r_j (Gm_rj + lam r_j) with r recomputed from the codes; optional W^ output
+// Left operand of a split product: Dt[k][row] = src[row][k] * d[k] * f_d as fp16 hi + lo for k < k_count, zero for
+// k_count <= k < k_pad and for the padding rows up to ldD.  f_d = 2^(13 - exponent of the maximum in sc), so that
+// the largest value lands in [2^12, 2^13); thread 0 of the grid leaves f_d, f_all, f_inv in sc for the product and
+// clears the maximum of `other` (the slot the next producer accumulates into).  64 x 64 tiles through LDS.
+__global__ __launch_bounds__(256) void jq_dsplit_kernel(const float* __restrict__ src, int64_t ld_src, int d_out,
+                                                        int k_count, int k_pad, const float* __restrict__ d,
+                                                        Scalars* sc, Scalars* other, uint16_t* __restrict__ Dh,
+                                                        uint16_t* __restrict__ Dl, int64_t ldD) {
+    __shared__ float tile[64][65];
+    const float mx = __uint_as_float(sc->max_w_bits);
+    int e = 0;
+    if (mx > 0.f) (void)frexpf(mx, &e);
+    const int sd = max(-60, min(60, 13 - e));
+    const float f_d = ldexpf(1.f, sd);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        sc->f_d = f_d; sc->f_u = JQ_FU;
+        sc->f_all = ldexpf(1.f, sd + 14);
+        sc->f_inv = ldexpf(1.f, -(sd + 14));
+        if (other) other->max_w_bits = 0u;
+    }
+    const int k0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int rr = ty; rr < 64; rr += 4) {
+        const int r = r0 + rr, k = k0 + tx;
+        tile[rr][tx] = (r < d_out && k < k_count) ? src[int64_t(r) * ld_src + k] * d[k] * f_d : 0.f;
+    }
+    __syncthreads();
+    for (int kk = ty; kk < 64; kk += 4) {
+        const int k = k0 + kk, r = r0 + tx;
+        if (k >= k_pad || r >= ldD) continue;
+        float x = tile[tx][kk];
+        x = fminf(fmaxf(x, -60000.f), 60000.f);
+        const _Float16 h = (_Float16)x;
+        const _Float16 lo = (_Float16)(x - (float)h);
+        Dh[int64_t(k) * ldD + r] = __builtin_bit_cast(uint16_t, h);
+        Dl[int64_t(k) * ldD + r] = __builtin_bit_cast(uint16_t, lo);
+    }
+}
+
+__global__ __launch_bounds__(256) void jq_fill0_kernel(float* __restrict__ p, int64_t n4) {
+    const float4v z = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < n4; i += int64_t(gridDim.x) * 256)
+        reinterpret_cast<float4v*>(p)[i] = z;
+}
+
+// rowf[r] = sum_j r_j Gm~_rj d_j with r recomputed from the codes; optional W^ output
 __global__ __launch_bounds__(256) void jq_objective_kernel(const void* __restrict__ W, int bf16, int d_out, int d_in,
                                                            const uint8_t* __restrict__ Q, const float* __restrict__ scales,
                                                            const float* __restrict__ zeros, int G, int n_g,
-                                                           const float* __restrict__ Gm, float lam,
+                                                           const float* __restrict__ Gm, const float* __restrict__ d,
                                                            float* __restrict__ rowf, float* __restrict__ W_hat) {
     __shared__ float red[256];
     for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {
@@ -76,7 +189,7 @@ __global__ __launch_bounds__(256) void jq_objective_kernel(const void* __restric
             const int g = c / G;
             const float wh = scales[r * n_g + g] * (float(Q[i]) - zeros[r * n_g + g]);
             const float rr = load_w(W, bf16, i) - wh;
-            acc += rr * (Gm[i] + lam * rr);
+            acc += rr * Gm[i] * d[c];
             if (W_hat) W_hat[i] = wh;
         }
         red[threadIdx.x] = acc;
@@ -112,8 +225,11 @@ struct VisitArgs {
     const float* A; float lam;
     float qtop;
     uint8_t* Q; float* scales; const float* zeros;
-    const float* Gm;
+    const float* Gm;           // column-normalized gradient of the whole objective (lam included)
+    const float* d;            // d_j = sqrt(A_jj + lam)
     float* dR; int ldr;        // the group's dR: row r at dR + r * ldr
+    Scalars* sc_near;          // max |dR d| of this visit
+    Scalars* sc_far;           // max |dR d| of the super-block
     int max_scans;
     int32_t* moves;
 };
@@ -126,6 +242,7 @@ struct VisitArgs {
 template <int NC>
 __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     extern __shared__ float sA[];   // G x G: A_tt + lam I
+    __shared__ uint32_t s_max;
     const int G = v.G;
     const int c0 = v.t * G;
     for (int e = threadIdx.x * 4; e < G * G; e += 64 * JQ_ROWS * 4) {
@@ -137,11 +254,11 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     __syncthreads();
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * JQ_ROWS + (threadIdx.x >> 6);
-    if (row >= v.d_out) return;
-
+    float dr_max = 0.f;
+    if (row < v.d_out) {
     const float z = v.zeros[int64_t(row) * v.n_g + v.t];
     const float s_old = v.scales[int64_t(row) * v.n_g + v.t];
-    float u[NC], u0[NC], a[NC], p[NC], q[NC], ad[NC];
+    float u[NC], u0[NC], a[NC], p[NC], q[NC], ad[NC], dj[NC];
     bool has[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
@@ -153,8 +270,8 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         u0[c] = u[c];
         a[c] = 0.f;
         ad[c] = has[c] ? sA[col * G + col] : 1.f;
-        // (A r)_t + lam r_t + s_old (A_tt + lam I) u  =  Gm + lam w + s_old A_tt u; the lam u part comes with a below
-        p[c] = has[c] ? v.Gm[i] + v.lam * (load_w(v.W, v.w_bf16, i) - s_old * u[c]) : 0.f;
+        dj[c] = has[c] ? v.d[c0 + col] : 0.f;
+        p[c] = has[c] ? v.Gm[i] * dj[c] : 0.f;   // ((A + lam I) r)_t; s_old (A_tt + lam I) u is added below
     }
     // a = (A_tt + lam I) u
 #pragma unroll
@@ -240,28 +357,55 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         const int col = lane + 64 * c;
         const int64_t i = int64_t(row) * v.d_in + c0 + col;
         v.Q[i] = uint8_t(q[c]);
-        v.dR[int64_t(row) * v.ldr + col] = s_old * u0[c] - s_new * u[c];   // change of the residual w - w^
+        const float dr = s_old * u0[c] - s_new * u[c];   // change of the residual w - w^
+        v.dR[int64_t(row) * v.ldr + col] = dr;
+        dr_max = fmaxf(dr_max, fabsf(dr) * dj[c]);
     }
     if (lane == 0) {
         v.scales[int64_t(row) * v.n_g + v.t] = s_new;
         if (n_moves > 0) atomicAdd(v.moves, n_moves);
     }
+    }
+    if (threadIdx.x == 0) s_max = 0u;
+    __syncthreads();
+    dr_max = wave_max(dr_max);
+    if (lane == 0) atomicMax(&s_max, __float_as_uint(dr_max));
+    __syncthreads();
+    if (threadIdx.x == 0 && s_max != 0u) {
+        atomicMax(&v.sc_near->max_w_bits, s_max);
+        atomicMax(&v.sc_far->max_w_bits, s_max);
+    }
 }
 
+constexpr int JQ_NEAR0 = 608;   // first row of the staging area of the per-visit left operand (the far one uses 0 ..)
+
 struct JqWs {
-    float* R;      // d_out x d_in: residual at the start (operand of the first GEMM)
-    float* Gm;     // d_out x d_in: R A, kept current
-    float* dR;     // d_out x JQ_SBW: dR of the groups of the current super-block side by side
-    float* rowf;   // d_out
+    float* Gm;        // d_out x d_in: column-normalized gradient, kept current
+    float* R;         // d_out x d_in: residual at the start (left operand of the first product)
+    uint16_t *Bh, *Bl;   // (d_in + 32) x d_in: A~ hi / lo, zero rows behind the matrix
+    uint16_t *Dh, *Dl;   // rows_d x ldD: left operands, k-major
+    float* dR;        // d_out x JQ_SBW: dR of the groups of the current super-block side by side
+    float* d;         // d_in
+    float* rowf;      // d_out
+    Scalars* sc;      // [0] first product, [1], [2] visits (alternating), [3], [4] super-blocks (alternating)
 };
 
-JqWs carve(void* ws, int64_t d_out, int64_t d_in, int G) {
+int64_t rows_d(int64_t d_in) { return d_in + 32 > JQ_NEAR0 + 160 ? d_in + 32 : JQ_NEAR0 + 160; }
+
+JqWs carve(void* ws, int64_t d_out, int64_t d_in) {
     char* p = static_cast<char*>(ws);
+    const int64_t ldD = split_update_ld(d_out);
     JqWs w;
-    w.R = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * d_in * 4, 256);
     w.Gm = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * d_in * 4, 256);
+    w.R = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * d_in * 4, 256);
+    w.Bh = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(d_in + 32) * d_in * 2, 256);
+    w.Bl = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(d_in + 32) * d_in * 2, 256);
+    w.Dh = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(rows_d(d_in)) * ldD * 2, 256);
+    w.Dl = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(rows_d(d_in)) * ldD * 2, 256);
     w.dR = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * JQ_SBW * 4, 256);
-    w.rowf = reinterpret_cast<float*>(p);
+    w.d = reinterpret_cast<float*>(p); p += align_up(size_t(d_in) * 4, 256);
+    w.rowf = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * 4, 256);
+    w.sc = reinterpret_cast<Scalars*>(p);
     return w;
 }
 
@@ -269,8 +413,10 @@ JqWs carve(void* ws, int64_t d_out, int64_t d_in, int G) {
 
 size_t jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size) {
     (void)group_size;
-    return 2 * align_up(size_t(d_out) * d_in * 4, 256) + align_up(size_t(d_out) * JQ_SBW * 4, 256) +
-           align_up(size_t(d_out) * 4, 256);
+    const int64_t ldD = split_update_ld(d_out);
+    return 2 * align_up(size_t(d_out) * d_in * 4, 256) + 2 * align_up(size_t(d_in + 32) * d_in * 2, 256) +
+           2 * align_up(size_t(rows_d(d_in)) * ldD * 2, 256) + align_up(size_t(d_out) * JQ_SBW * 4, 256) +
+           align_up(size_t(d_in) * 4, 256) + align_up(size_t(d_out) * 4, 256) + 256;
 }
 
 onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* A, float lam,
@@ -282,21 +428,45 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
     const bool symmetric = grid == ONECOMP_GRID_SYMMETRIC || grid == ONECOMP_GRID_SYMMETRIC_MSE;
     const float qtop = symmetric ? float(2 * ((1 << (bits - 1)) - 1)) : float((1 << bits) - 1);
     const int bf16 = w_dtype == ONECOMP_BF16;
-    JqWs w = carve(workspace, d_out, d_in, G);
+    JqWs w = carve(workspace, d_out, d_in);
+    const int64_t ldD = split_update_ld(d_out);
     const dim3 rgrid{unsigned(d_out < 4096 ? d_out : 4096)};
+    auto pad32 = [](int k) { return (k + 31) / 32 * 32; };
+    onecomp_status st;
 
     hipLaunchKernelGGL(jq_zero_kernel, dim3(1), dim3(1), 0, stream, n_moves);
     ONECOMP_CHECK_LAUNCH();
-    hipLaunchKernelGGL(jq_residual_kernel, rgrid, dim3(256), 0, stream, W, bf16, int(d_out), int(d_in), Q, scales, zeros,
-                       G, n_g, w.R);
+    hipLaunchKernelGGL(jq_scalars_init_kernel, dim3(1), dim3(64), 0, stream, w.sc, 5);
     ONECOMP_CHECK_LAUNCH();
-    SgemmArgs g{};
-    g.A = w.R; g.lda = d_in; g.B = A; g.ldb = d_in; g.C = w.Gm; g.ldc = d_in;
-    g.m = int(d_out); g.n = int(d_in); g.k = int(d_in); g.flags = 0;
-    onecomp_status st = sgemm(g, stream);
-    if (st != ONECOMP_OK) return st;
+    hipLaunchKernelGGL(jq_diag_kernel, dim3(unsigned(ceil_div(d_in, 256))), dim3(256), 0, stream, A, int(d_in), lam, w.d);
+    ONECOMP_CHECK_LAUNCH();
+    hipLaunchKernelGGL(jq_asplit_kernel, dim3(unsigned(ceil_div(d_in, 1024)), unsigned(d_in + 32)), dim3(256), 0, stream,
+                       A, int(d_in), int(d_in + 32), lam, w.d, w.Bh, w.Bl);
+    ONECOMP_CHECK_LAUNCH();
+    hipLaunchKernelGGL(jq_residual_kernel, rgrid, dim3(256), 0, stream, W, bf16, int(d_out), int(d_in), Q, scales, zeros,
+                       G, n_g, w.d, w.R, w.sc);
+    ONECOMP_CHECK_LAUNCH();
+    // left operand rows [row0, row0 + pad32(k_count)) of the D buffers from src[:, 0 .. k_count), columns c_first ..
+    auto dsplit = [&](const float* src, int64_t ld_src, int k_count, int c_first, int row0, Scalars* sc,
+                      Scalars* other) -> onecomp_status {
+        const int k_pad = pad32(k_count);
+        hipLaunchKernelGGL(jq_dsplit_kernel, dim3(unsigned(ceil_div(k_pad, 64)), unsigned(ceil_div(ldD, 64))), dim3(256), 0,
+                           stream, src, ld_src, int(d_out), k_count, k_pad, w.d + c_first, sc, other,
+                           w.Dh + int64_t(row0) * ldD, w.Dl + int64_t(row0) * ldD, ldD);
+        ONECOMP_CHECK_LAUNCH();
+        return ONECOMP_OK;
+    };
+    // Gm~[:, c_lo .. c_hi) += (rows row0 .. of D)^T A~[u0 .. u0 + pad32(k_count), c_lo .. c_hi)
+    auto update = [&](int row0, int k_count, int u0, int c_lo, int c_hi, const Scalars* sc) -> onecomp_status {
+        return split_update(w.Gm, d_out, d_in, w.Dh, w.Dl, ldD, w.Bh, w.Bl, sc, row0, pad32(k_count), u0, c_lo, c_hi,
+                            stream);
+    };
+    if ((st = dsplit(w.R, d_in, int(d_in), 0, 0, w.sc, nullptr)) != ONECOMP_OK) return st;
+    hipLaunchKernelGGL(jq_fill0_kernel, dim3(2048), dim3(256), 0, stream, w.Gm, d_out * d_in / 4);
+    ONECOMP_CHECK_LAUNCH();
+    if ((st = update(0, int(d_in), 0, 0, int(d_in), w.sc)) != ONECOMP_OK) return st;
     hipLaunchKernelGGL(jq_objective_kernel, rgrid, dim3(256), 0, stream, W, bf16, int(d_out), int(d_in), Q, scales, zeros,
-                       G, n_g, w.Gm, lam, w.rowf, static_cast<float*>(nullptr));
+                       G, n_g, w.Gm, w.d, w.rowf, static_cast<float*>(nullptr));
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(jq_total_kernel, dim3(1), dim3(1024), 0, stream, w.rowf, int(d_out), objective);
     ONECOMP_CHECK_LAUNCH();
@@ -312,40 +482,37 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
     }
     VisitArgs v;
     v.W = W; v.w_bf16 = bf16; v.d_out = int(d_out); v.d_in = int(d_in); v.G = G; v.n_g = n_g; v.t = 0;
-    v.A = A; v.lam = lam; v.qtop = qtop; v.Q = Q; v.scales = scales; v.zeros = zeros; v.Gm = w.Gm; v.dR = w.dR;
-    v.max_scans = max_scans; v.moves = n_moves;
+    v.A = A; v.lam = lam; v.qtop = qtop; v.Q = Q; v.scales = scales; v.zeros = zeros; v.Gm = w.Gm; v.d = w.d;
+    v.dR = w.dR; v.max_scans = max_scans; v.moves = n_moves;
     const dim3 vgrid{unsigned(ceil_div(d_out, JQ_ROWS))};
     const int sbg = JQ_SBW / G > 0 ? JQ_SBW / G : 1;   // groups per super-block
     v.ldr = sbg * G;
-    SgemmArgs up{};
-    up.lda = v.ldr; up.ldb = d_in; up.C = nullptr; up.ldc = 0;
-    up.m = int(d_out); up.flags = 0;
-    up.ldbase = d_in; up.colmap = nullptr; up.ldout = d_in; up.alpha = 1.0f;
-    // Gm[:, c_lo .. c_hi) += dR[:, k_lo .. k_hi) A[t0 G + k_lo .. t0 G + k_hi, c_lo .. c_hi)
-    auto update = [&](int t0, int k_lo, int k_hi, int c_lo, int c_hi) -> onecomp_status {
-        if (c_hi <= c_lo || k_hi <= k_lo) return ONECOMP_OK;
-        up.A = w.dR + k_lo; up.k = k_hi - k_lo;
-        up.B = A + (int64_t(t0) * G + k_lo) * d_in + c_lo;
-        up.n = c_hi - c_lo;
-        up.base = w.Gm + c_lo; up.out = w.Gm + c_lo;
-        return sgemm(up, stream);
-    };
+    int n_visit = 0, n_sb = 0;
     for (int ps = 0; ps < n_pass; ++ps)
-        for (int t0 = 0; t0 < n_g; t0 += sbg) {
+        for (int t0 = 0; t0 < n_g; t0 += sbg, ++n_sb) {
             const int t1 = t0 + sbg < n_g ? t0 + sbg : n_g;
-            for (int t = t0; t < t1; ++t) {
+            Scalars* sc_far = w.sc + 3 + (n_sb & 1);
+            for (int t = t0; t < t1; ++t, ++n_visit) {
+                Scalars* sc_near = w.sc + 1 + (n_visit & 1);
                 v.t = t;
                 v.dR = w.dR + (t - t0) * G;
+                v.sc_near = sc_near; v.sc_far = sc_far;
                 if (G <= 64) hipLaunchKernelGGL(jq_visit_kernel<1>, vgrid, dim3(64 * JQ_ROWS), lds_bytes, stream, v);
                 else hipLaunchKernelGGL(jq_visit_kernel<2>, vgrid, dim3(64 * JQ_ROWS), lds_bytes, stream, v);
                 ONECOMP_CHECK_LAUNCH();
-                if ((st = update(t0, (t - t0) * G, (t - t0 + 1) * G, t0 * G, t1 * G)) != ONECOMP_OK) return st;
+                // the super-block's own columns at once
+                if ((st = dsplit(v.dR, v.ldr, G, t * G, JQ_NEAR0, sc_near, w.sc + 1 + ((n_visit + 1) & 1))) != ONECOMP_OK)
+                    return st;
+                if ((st = update(JQ_NEAR0, G, t * G, t0 * G, t1 * G, sc_near)) != ONECOMP_OK) return st;
             }
-            if ((st = update(t0, 0, (t1 - t0) * G, 0, t0 * G)) != ONECOMP_OK) return st;
-            if ((st = update(t0, 0, (t1 - t0) * G, t1 * G, int(d_in))) != ONECOMP_OK) return st;
+            // all other columns once per super-block
+            if ((st = dsplit(w.dR, v.ldr, (t1 - t0) * G, t0 * G, 0, sc_far, w.sc + 3 + ((n_sb + 1) & 1))) != ONECOMP_OK)
+                return st;
+            if ((st = update(0, (t1 - t0) * G, t0 * G, 0, t0 * G, sc_far)) != ONECOMP_OK) return st;
+            if ((st = update(0, (t1 - t0) * G, t0 * G, t1 * G, int(d_in), sc_far)) != ONECOMP_OK) return st;
         }
     hipLaunchKernelGGL(jq_objective_kernel, rgrid, dim3(256), 0, stream, W, bf16, int(d_out), int(d_in), Q, scales, zeros,
-                       G, n_g, w.Gm, lam, w.rowf, W_hat);
+                       G, n_g, w.Gm, w.d, w.rowf, W_hat);
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(jq_total_kernel, dim3(1), dim3(1024), 0, stream, w.rowf, int(d_out), objective + 1);
     ONECOMP_CHECK_LAUNCH();

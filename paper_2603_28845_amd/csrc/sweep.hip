@@ -53,17 +53,6 @@ __device__ inline float to_f32<float>(float v) { return v; }
 template <>
 __device__ inline float to_f32<uint16_t>(uint16_t v) { return __uint_as_float(uint32_t(v) << 16); }
 
-// Device scalars of one sweep: maxima (as the bit patterns of non-negative floats, which order like unsigned
-// integers, so an integer atomic max is exact and order independent) and the power-of-two scales derived from them.
-struct Scalars {
-    uint32_t max_w_bits;   // max |W|
-    uint32_t max_u_bits;   // max |U_jk / U_jj| over the strict upper triangle
-    float f_d;             // residuals are stored as fp16 of  -(w - w^) * f_d
-    float f_u;             // rows of U are stored as fp16 of  U_jk / U_jj * f_u
-    float f_all;           // f_d * f_u
-    float f_inv;           // 1 / (f_d * f_u)
-};
-
 __global__ void init_scalars_kernel(Scalars* sc) {
     sc->max_w_bits = 0u;
     sc->max_u_bits = 0u;
@@ -1159,6 +1148,29 @@ size_t sweep_workspace_bytes(int64_t d_out, int64_t d_in, int block) {
            align_up(size_t(d_out) * d_in, 256) + align_up(size_t(d_in) * sizeof(int32_t), 256) +
            align_up(size_t(d_out) * d_in * sizeof(float), 256);
 }
+
+// C[:, c0 .. c1) += f_inv * (D[ek .. ek + K, :])^T * B[u0 .. u0 + K, c0 .. c1): the split-fp16 product of the sweep's
+// trailing update, for other callers (see the declaration).
+onecomp_status split_update(float* C, int64_t d_out, int64_t d_in, const uint16_t* Dh, const uint16_t* Dl, int64_t ldD,
+                            const uint16_t* Bh, const uint16_t* Bl, const Scalars* sc, int ek, int K, int u0, int c0,
+                            int c1, hipStream_t stream) {
+    if (c1 <= c0 || K <= 0) return ONECOMP_OK;
+    static std::atomic<uint64_t> lds_ok{0};
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(&trailing_kernel), int(tg::LDS_BYTES), lds_ok) != ONECOMP_OK)
+        return ONECOMP_ERR_HIP;
+    TrailArgs t;
+    t.Wf = C; t.Dh = Dh; t.Dl = Dl; t.Uh = Bh; t.Ul = Bl; t.sc = sc;
+    t.d_out = int(d_out); t.ldD = int(ldD); t.d_in = int(d_in);
+    t.ek = ek; t.K = K; t.u0 = u0; t.c0 = c0; t.c1 = c1;
+    t.n_mt = int(ceil_div(d_out, tg::TM));
+    t.n_nt = int(ceil_div(c1 - c0, tg::TN));
+    t.chunk = int(ceil_div(int64_t(t.n_mt) * t.n_nt, 8));
+    hipLaunchKernelGGL(trailing_kernel, dim3(unsigned(t.chunk * 8)), dim3(256), tg::LDS_BYTES, stream, t);
+    ONECOMP_CHECK_LAUNCH();
+    return ONECOMP_OK;
+}
+
+int64_t split_update_ld(int64_t d_out) { return ld_d(d_out); }
 
 onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* U,
                          int form, const int32_t* perm, int bits, int group_size, int block, int grid, uint8_t* Q,
