@@ -324,9 +324,12 @@ size_t onecomp_sensitivity_workspace_bytes(void);
  *   W_hat     device fp32 d_out x d_in or NULL, out: s (q - z) of the result.
  *   objective device fp32[2], out: sum over rows of f before and after.
  *   n_moves   device int32, out: number of moves taken.
- *   workspace device scratch, >= onecomp_jointq_workspace_bytes() (about 8 d_out d_in bytes), 256-byte aligned.
- * Arithmetic: fp32 throughout (fp32 MFMA for the gradient R (H + lam I) and its rank-group_size updates).  A decision
- * whose gain is within rounding of zero may fall either way; results are reproducible run to run.
+ *   workspace device scratch, >= onecomp_jointq_workspace_bytes() (about 9 d_out d_in + 4 d_in^2 bytes), 256-byte
+ *             aligned.
+ * Arithmetic: fp32; the gradient R (H + lam I) and its rank-group_size updates are fp16 MFMA products of operands
+ * split into hi + lo halves (22 significant bits each, H taken as the correlation matrix H_kj / sqrt(H_kk H_jj)),
+ * accumulated in fp32.  A decision whose gain is within rounding of zero may fall either way; results are
+ * reproducible run to run.
  * Errors: INVALID_ARG (null pointer, bad size, lam < 0, n_pass < 0, max_scans < 1), UNSUPPORTED (dtype, bits, grid,
  * group_size > 128 or not a multiple of 16), WORKSPACE.
  */

@@ -11,7 +11,8 @@
 // One visit of group t for one row (u = q - z, a = A_tt u, p = (A r)_t + s_old a, b = u.p, c = u.a, s* = b / c):
 // the move u + d e_j changes b^2 / c by N / c' with
 //     g = p_j - s* a_j,   N = 2 d b g + g^2 + 2 s* g a_j - s*^2 (c A_jj - a_j^2),   c' = c + 2 d a_j + A_jj,
-// and is taken iff N > 0 and c' > 0.
+// and is taken iff N > 0 and c' > 0.  (The last three terms of N equal p_j^2 - s*^2 c A_jj, which is how the kernel
+// forms them; what matters for fp32 is that the small g is computed first and multiplied by the large b.)
 //
 // gfx950 mapping.  The rows are independent and a visit only needs the row's gradient restricted to the group,
 // (A r)_t, so the whole layer moves through the groups together:
@@ -297,38 +298,47 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     const bool live = cc > 0.f;
     int n_moves = 0;
     if (live) {
-        float ss = b / cc;
+        // b / cc to within rounding, in fewer dependent steps than the correctly rounded division
+        auto ratio = [](float x, float y) __attribute__((always_inline)) {
+            float r = __builtin_amdgcn_rcpf(y);
+            r = fmaf(fmaf(-y, r, 1.0f), r, r);
+            return x * r;
+        };
+        float ss = ratio(b, cc);
         int scan = 0, j0 = -1;   // j0: the column of the last move taken in this scan
         bool took = false;
         for (;;) {
-            bool imp[NC];
+            // N = 2 d b g + (p^2 - s*^2 c A_jj): the bracket is the expanded form's g^2 + 2 s* g a - s*^2 (c A_jj - a^2)
+            const float twob = 2.0f * b, bss = b * ss;
+            uint64_t m[NC];
             float dd[NC];
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
-                const float gs = p[c] - ss * a[c];
-                const float base = gs * gs + 2.0f * ss * gs * a[c] - ss * ss * (cc * ad[c] - a[c] * a[c]);
-                const float t1 = 2.0f * b * gs;
-                const bool up = q[c] + 1.0f <= v.qtop && base + t1 > 0.f && cc + 2.0f * a[c] + ad[c] > 0.f;
-                const bool dn = q[c] - 1.0f >= 0.f && base - t1 > 0.f && cc - 2.0f * a[c] + ad[c] > 0.f;
-                imp[c] = has[c] && (up || dn);
+                const float gs = fmaf(-ss, a[c], p[c]);
+                const float base = fmaf(p[c], p[c], -bss * ad[c]);
+                const float t1 = twob * gs;
+                const float cad = cc + ad[c], a2 = 2.0f * a[c];
+                const bool up = q[c] + 1.0f <= v.qtop && base + t1 > 0.f && cad + a2 > 0.f;
+                const bool dn = q[c] - 1.0f >= 0.f && base - t1 > 0.f && cad - a2 > 0.f;
                 dd[c] = up ? 1.0f : -1.0f;
+                m[c] = __ballot(has[c] && (up || dn));
+                const int lo = j0 - 64 * c;          // columns up to lo (local numbering) are behind
+                if (lo >= 63) m[c] = 0;
+                else if (lo >= 0) m[c] &= ~((uint64_t(2) << lo) - 1);
             }
             int j = -1;
-#pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                if (j >= 0) continue;
-                uint64_t m = __ballot(imp[c]);
-                const int lo = j0 - 64 * c;          // columns up to lo (local numbering) are behind
-                if (lo >= 63) m = 0;
-                else if (lo >= 0) m &= ~((uint64_t(2) << lo) - 1);
-                if (m) j = 64 * c + __builtin_ctzll(m);
-            }
+            if (m[0]) j = __builtin_ctzll(m[0]);
+            else if (NC > 1 && m[NC - 1]) j = 64 + __builtin_ctzll(m[NC - 1]);
             if (j < 0) {   // the scan is over
                 if (!took || ++scan >= v.max_scans) break;
                 took = false;
                 j0 = -1;
                 continue;
             }
+            const float* rowj = sA + j * G + lane;
+            float arow[NC];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) arow[c] = has[c] ? rowj[64 * c] : 0.f;
             float d, pj, aj, adj;
             if (NC == 1 || j < 64) {
                 d = readlane_f(dd[0], j); pj = readlane_f(p[0], j); aj = readlane_f(a[0], j); adj = readlane_f(ad[0], j);
@@ -338,13 +348,11 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
                 aj = readlane_f(a[NC - 1], j - 64); adj = readlane_f(ad[NC - 1], j - 64);
                 if (lane == j - 64) { u[NC - 1] += d; q[NC - 1] += d; }
             }
-            b += d * pj;
-            cc += 2.0f * d * aj + adj;
-            ss = b / cc;
-            const float* rowj = sA + j * G + lane;
+            b = fmaf(d, pj, b);
+            cc += fmaf(2.0f * d, aj, adj);
+            ss = ratio(b, cc);
 #pragma unroll
-            for (int c = 0; c < NC; ++c)
-                if (has[c]) a[c] += d * rowj[64 * c];
+            for (int c = 0; c < NC; ++c) a[c] = fmaf(d, arow[c], a[c]);
             took = true;
             j0 = j;
             ++n_moves;
