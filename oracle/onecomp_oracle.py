@@ -536,7 +536,7 @@ def row_objective(W, W_hat, A):
 
 
 def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=1, max_scans=4, rows=None,
-                  forced=None, tie_tol=0.0, g_tol=0.0):
+                  forced=None, tie_tol=0.0, g_tol=0.0, a_tol=0.0):
     """Local search of Sec. 4.2.2 on a solution in the per-group format of Eq. (4), rows independent.
 
     What the paper fixes: one move changes one integer code by a small amount inside the codebook, the scale of
@@ -558,8 +558,10 @@ def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=
 
     W [d_out, d_in]; A symmetric [d_in, d_in]; Q codes, scales / zeros [d_out, n_g] as the sweep returns them
     (natural column order).  forced: {(row, pass, t, scan, j, d): bool} overrides single decisions (rows numbered
-    within the subset); with tie_tol > 0 every decision with |N| <= tie_tol * M + 2 |b| g_tol (|r| |A|)_j, M the sum
-    of the absolute values of the terms N is built from, is listed in "ties".
+    within the subset); with tie_tol > 0 every decision with
+    |N| <= tie_tol * M + 2 |b| (g_tol (|r| |A|)_j + a_tol |s*| (|u| |A_tt|)_j), M the sum of the absolute values of
+    the terms N is built from, is listed in "ties" (g_tol, a_tol: the rounding of a gradient and of a = A_tt u that
+    are carried along rather than recomputed).
     Returns dict(Q, scales, W_hat, f0, f1 (row objective before / after), moves [rows], ties [list per row])."""
     W = np.asarray(W, dtype=np.float64)
     A = np.asarray(A, dtype=np.float64)
@@ -598,6 +600,7 @@ def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=
             active = live.copy()
             for scan in range(int(max_scans)):
                 took = np.zeros(n, dtype=bool)
+                aabs = np.abs(u) @ np.abs(Att) if a_tol > 0.0 else None
                 for j in range(G):
                     done = np.zeros(n, dtype=bool)
                     for d in (1.0, -1.0):
@@ -612,10 +615,13 @@ def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=
                         N = 2.0 * d * b * gs + gs * gs + 2.0 * ss * gs * aj - ss * ss * (cc * Ajj - aj * aj)
                         cn = c + 2.0 * d * aj + Ajj
                         acc = ok & (N > 0.0) & (cn > 0.0)
-                        if tie_tol > 0.0 or g_tol > 0.0:
+                        if tie_tol > 0.0 or g_tol > 0.0 or a_tol > 0.0:
                             M = (2.0 * np.abs(b) * (np.abs(pj) + np.abs(ss * aj)) + gs * gs + 2.0 * np.abs(ss * gs * aj)
                                  + ss * ss * (cc * Ajj + aj * aj))
-                            near = ok & (np.abs(N) <= tie_tol * M + 2.0 * np.abs(b) * g_tol * gabs[:, j])
+                            slack = g_tol * gabs[:, j]
+                            if a_tol > 0.0:
+                                slack = slack + a_tol * np.abs(ss) * aabs[:, j]
+                            near = ok & (np.abs(N) <= tie_tol * M + 2.0 * np.abs(b) * slack)
                             for i in np.nonzero(near)[0]:
                                 ties[i].append((ps, t, scan, j, int(d)))
                         for i in np.nonzero(ok)[0] if forced else ():

@@ -158,8 +158,8 @@ ONECOMP_API onecomp_status onecomp_qep_target(const void* W, onecomp_dtype w_dty
 }
 
 ONECOMP_API size_t onecomp_jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size) {
-    if (d_out <= 0 || d_in <= 0 || group_size <= 0 || group_size > 128 || group_size % 16 != 0 || d_in % group_size != 0)
-        return 0;
+    if (d_out <= 0 || d_in <= 0 || group_size <= 0 || group_size % 16 != 0 || d_in % group_size != 0) return 0;
+    if (group_size > 128 && group_size % 128 != 0) return 0;
     return jointq_workspace_bytes(d_out, d_in, group_size);
 }
 
@@ -178,7 +178,7 @@ ONECOMP_API onecomp_status onecomp_jointq_refine(const void* W, onecomp_dtype w_
     if (d_out <= 0 || d_in <= 0 || d_out > (1 << 24) || d_in > (1 << 20)) return ONECOMP_ERR_INVALID_ARG;
     if (!(lam >= 0.0f) || n_pass < 0 || max_scans < 1) return ONECOMP_ERR_INVALID_ARG;
     if (group_size <= 0 || d_in % 16 != 0 || d_in % group_size != 0) return ONECOMP_ERR_INVALID_ARG;
-    if (group_size % 16 != 0 || group_size > 128) return ONECOMP_ERR_UNSUPPORTED;
+    if (group_size % 16 != 0 || (group_size > 128 && group_size % 128 != 0)) return ONECOMP_ERR_UNSUPPORTED;
     if (!aligned(W, 16) || !aligned(H, 16) || (W_hat && !aligned(W_hat, 16))) return ONECOMP_ERR_INVALID_ARG;
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < jointq_workspace_bytes(d_out, d_in, group_size))
         return ONECOMP_ERR_WORKSPACE;

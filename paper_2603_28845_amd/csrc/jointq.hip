@@ -231,6 +231,12 @@ struct VisitArgs {
     float* dR; int ldr;        // the group's dR: row r at dR + r * ldr
     Scalars* sc_near;          // max |dR d| of this visit
     Scalars* sc_far;           // max |dR d| of the super-block
+    // groups wider than a block (WIDE): the launch covers the block of v.G = 128 columns starting at col0
+    int col0;                  // first column of the block (groups up to 128 columns: t * G)
+    const float* Am;           // column-normalized a = (A_gg + lam I) u of the group, kept current
+    const float* P;            // p of the group's columns, fixed during the visit
+    float* bc;                 // per row b, c of the visited group
+    int32_t* flags;            // per row: [0] still scanning this visit, [1] took a move in this scan
     int max_scans;
     int32_t* moves;
 };
@@ -240,12 +246,17 @@ struct VisitArgs {
 // column behind the last one taken, that move is applied, and the evaluation is repeated.  The columns between two
 // taken moves are rejected under the same state the sequential scan would see, so the sequence of moves is the same,
 // at one wave-wide evaluation per taken move instead of one per column.
-template <int NC>
+//
+// WIDE (groups of several 128-column blocks): one launch is one block's share of one scan of the visit.  b and c
+// live in memory across the launches, a = (A_gg + lam I) u comes from Am (updated between the launches with the
+// same split products as the gradient, for every column of the group), p from P; the launch scans its columns once,
+// writes the code changes dU = u_new - u_old (the update's left operand) and marks the row when it took a move.
+template <int NC, bool WIDE>
 __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     extern __shared__ float sA[];   // G x G: A_tt + lam I
     __shared__ uint32_t s_max;
     const int G = v.G;
-    const int c0 = v.t * G;
+    const int c0 = v.col0;
     for (int e = threadIdx.x * 4; e < G * G; e += 64 * JQ_ROWS * 4) {
         const int k = e / G, c = e - k * G;
         float4v x = *reinterpret_cast<const float4v*>(v.A + int64_t(c0 + k) * v.d_in + c0 + c);
@@ -256,7 +267,14 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * JQ_ROWS + (threadIdx.x >> 6);
     float dr_max = 0.f;
-    if (row < v.d_out) {
+    bool run = row < v.d_out;
+    if (WIDE && run && v.flags[2 * row] == 0) {   // the row's visit is over: no change from this block
+        run = false;
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+            if (lane + 64 * c < G) v.dR[int64_t(row) * v.ldr + lane + 64 * c] = 0.f;
+    }
+    if (run) {
     const float z = v.zeros[int64_t(row) * v.n_g + v.t];
     const float s_old = v.scales[int64_t(row) * v.n_g + v.t];
     float u[NC], u0[NC], a[NC], p[NC], q[NC], ad[NC], dj[NC];
@@ -272,11 +290,16 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         a[c] = 0.f;
         ad[c] = has[c] ? sA[col * G + col] : 1.f;
         dj[c] = has[c] ? v.d[c0 + col] : 0.f;
-        p[c] = has[c] ? v.Gm[i] * dj[c] : 0.f;   // ((A + lam I) r)_t; s_old (A_tt + lam I) u is added below
+        if (WIDE) {
+            p[c] = has[c] ? v.P[i] : 0.f;
+            a[c] = has[c] ? v.Am[i] * dj[c] : 0.f;
+        } else {
+            p[c] = has[c] ? v.Gm[i] * dj[c] : 0.f;   // ((A + lam I) r)_t; s_old (A_tt + lam I) u is added below
+        }
     }
     // a = (A_tt + lam I) u
 #pragma unroll
-    for (int cu = 0; cu < NC; ++cu) {
+    for (int cu = 0; cu < (WIDE ? 0 : NC); ++cu) {
         const int kn = G - 64 * cu < 64 ? G - 64 * cu : 64;
         for (int k = 0; k < kn; ++k) {
             const float uk = readlane_f(u[cu], k);
@@ -287,14 +310,19 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         }
     }
     float b = 0.f, cc = 0.f;
+    if (WIDE) {
+        b = v.bc[2 * row];
+        cc = v.bc[2 * row + 1];
+    } else {
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-        p[c] += s_old * a[c];
-        b += u[c] * p[c];
-        cc += u[c] * a[c];
+        for (int c = 0; c < NC; ++c) {
+            p[c] += s_old * a[c];
+            b += u[c] * p[c];
+            cc += u[c] * a[c];
+        }
+        b = wave_sum(b);
+        cc = wave_sum(cc);
     }
-    b = wave_sum(b);
-    cc = wave_sum(cc);
     const bool live = cc > 0.f;
     int n_moves = 0;
     if (live) {
@@ -330,7 +358,7 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
             if (m[0]) j = __builtin_ctzll(m[0]);
             else if (NC > 1 && m[NC - 1]) j = 64 + __builtin_ctzll(m[NC - 1]);
             if (j < 0) {   // the scan is over
-                if (!took || ++scan >= v.max_scans) break;
+                if (WIDE || !took || ++scan >= v.max_scans) break;
                 took = false;
                 j0 = -1;
                 continue;
@@ -365,12 +393,19 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         const int col = lane + 64 * c;
         const int64_t i = int64_t(row) * v.d_in + c0 + col;
         v.Q[i] = uint8_t(q[c]);
-        const float dr = s_old * u0[c] - s_new * u[c];   // change of the residual w - w^
+        // groups up to a block: change of the residual w - w^;  wider: change of the codes
+        const float dr = WIDE ? u[c] - u0[c] : s_old * u0[c] - s_new * u[c];
         v.dR[int64_t(row) * v.ldr + col] = dr;
         dr_max = fmaxf(dr_max, fabsf(dr) * dj[c]);
     }
     if (lane == 0) {
-        v.scales[int64_t(row) * v.n_g + v.t] = s_new;
+        if (WIDE) {
+            v.bc[2 * row] = b;
+            v.bc[2 * row + 1] = cc;
+            if (n_moves > 0) v.flags[2 * row + 1] = 1;
+        } else {
+            v.scales[int64_t(row) * v.n_g + v.t] = s_new;
+        }
         if (n_moves > 0) atomicAdd(v.moves, n_moves);
     }
     }
@@ -385,6 +420,94 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     }
 }
 
+// ---- groups wider than a block -----------------------------------------------------------------------------------
+// start of a visit: U[row][c] = q - z over the group's columns (left operand of a = (A_gg + lam I) u); max |u d|
+__global__ __launch_bounds__(256) void jq_wide_begin_kernel(int d_out, int d_in, const uint8_t* __restrict__ Q,
+                                                            const float* __restrict__ zeros, int n_g, int g, int G,
+                                                            const float* __restrict__ d, float* __restrict__ U,
+                                                            Scalars* sc) {
+    __shared__ uint32_t s_max;
+    float mx = 0.f;
+    const int g0 = g * G;
+    for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {
+        const float z = zeros[r * n_g + g];
+        for (int c = threadIdx.x; c < G; c += 256) {
+            const int64_t i = r * d_in + g0 + c;
+            const float u = float(Q[i]) - z;
+            U[i] = u;
+            mx = fmaxf(mx, fabsf(u) * d[g0 + c]);
+        }
+    }
+    block_max_bits(&sc->max_w_bits, mx, &s_max);
+}
+
+// P = ((A + lam I) r)_g + s_old a,  b = u.P,  c = u.a  with a = Am d (one workgroup per row at a time)
+__global__ __launch_bounds__(256) void jq_wide_p_kernel(int d_out, int d_in, const float* __restrict__ scales, int n_g,
+                                                        int g, int G, const float* __restrict__ d,
+                                                        const float* __restrict__ U, const float* __restrict__ Gm,
+                                                        const float* __restrict__ Am, float* __restrict__ P,
+                                                        float* __restrict__ bc, int32_t* __restrict__ flags) {
+    __shared__ float rb[256], rc[256];
+    const int g0 = g * G;
+    for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {
+        const float s_old = scales[r * n_g + g];
+        float b = 0.f, c = 0.f;
+        for (int k = threadIdx.x; k < G; k += 256) {
+            const int64_t i = r * d_in + g0 + k;
+            const float dj = d[g0 + k], a = Am[i] * dj, u = U[i];
+            const float p = Gm[i] * dj + s_old * a;
+            P[i] = p;
+            b += u * p;
+            c += u * a;
+        }
+        rb[threadIdx.x] = b; rc[threadIdx.x] = c;
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if (int(threadIdx.x) < w) { rb[threadIdx.x] += rb[threadIdx.x + w]; rc[threadIdx.x] += rc[threadIdx.x + w]; }
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            bc[2 * r] = rb[0]; bc[2 * r + 1] = rc[0];
+            flags[2 * r] = rc[0] > 0.f ? 1 : 0;
+            flags[2 * r + 1] = 0;
+        }
+        __syncthreads();
+    }
+}
+
+// end of a scan: a row whose scan took nothing has finished its visit
+__global__ __launch_bounds__(256) void jq_scan_end_kernel(int d_out, int32_t* __restrict__ flags) {
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= d_out) return;
+    if (flags[2 * r + 1] == 0) flags[2 * r] = 0;
+    flags[2 * r + 1] = 0;
+}
+
+// end of a visit: s = b / c; U <- change of the residual s_old u_old - s_new u_new; max |dR d|
+__global__ __launch_bounds__(256) void jq_wide_end_kernel(int d_out, int d_in, const uint8_t* __restrict__ Q,
+                                                          float* __restrict__ scales, const float* __restrict__ zeros,
+                                                          int n_g, int g, int G, const float* __restrict__ d,
+                                                          const float* __restrict__ bc, float* __restrict__ U,
+                                                          Scalars* sc) {
+    __shared__ uint32_t s_max;
+    float mx = 0.f;
+    const int g0 = g * G;
+    for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {
+        const float z = zeros[r * n_g + g], s_old = scales[r * n_g + g];
+        const float b = bc[2 * r], c = bc[2 * r + 1];
+        const float s_new = c > 0.f ? b / c : s_old;
+        for (int k = threadIdx.x; k < G; k += 256) {
+            const int64_t i = r * d_in + g0 + k;
+            const float dr = s_old * U[i] - s_new * (float(Q[i]) - z);
+            U[i] = dr;
+            mx = fmaxf(mx, fabsf(dr) * d[g0 + k]);
+        }
+        __syncthreads();   // every thread has read the old scale
+        if (threadIdx.x == 0) scales[r * n_g + g] = s_new;
+    }
+    block_max_bits(&sc->max_w_bits, mx, &s_max);
+}
+
 constexpr int JQ_NEAR0 = 608;   // first row of the staging area of the per-visit left operand (the far one uses 0 ..)
 
 struct JqWs {
@@ -395,12 +518,18 @@ struct JqWs {
     float* dR;        // d_out x JQ_SBW: dR of the groups of the current super-block side by side
     float* d;         // d_in
     float* rowf;      // d_out
-    Scalars* sc;      // [0] first product, [1], [2] visits (alternating), [3], [4] super-blocks (alternating)
+    Scalars* sc;      // [0] first product, [1], [2] visits (alternating), [3], [4] super-blocks (alternating),
+                      // [5] start, [6] end of a wide group's visit
+    // groups wider than a block only
+    float* Am;        // d_out x d_in: column-normalized a of the visited group
+    float* P;         // d_out x d_in: p of the visited group
+    float* bc;        // d_out x 2
+    int32_t* flags;   // d_out x 2
 };
 
 int64_t rows_d(int64_t d_in) { return d_in + 32 > JQ_NEAR0 + 160 ? d_in + 32 : JQ_NEAR0 + 160; }
 
-JqWs carve(void* ws, int64_t d_out, int64_t d_in) {
+JqWs carve(void* ws, int64_t d_out, int64_t d_in, bool wide) {
     char* p = static_cast<char*>(ws);
     const int64_t ldD = split_update_ld(d_out);
     JqWs w;
@@ -413,18 +542,26 @@ JqWs carve(void* ws, int64_t d_out, int64_t d_in) {
     w.dR = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * JQ_SBW * 4, 256);
     w.d = reinterpret_cast<float*>(p); p += align_up(size_t(d_in) * 4, 256);
     w.rowf = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * 4, 256);
-    w.sc = reinterpret_cast<Scalars*>(p);
+    w.sc = reinterpret_cast<Scalars*>(p); p += 256;
+    w.Am = w.P = w.bc = nullptr; w.flags = nullptr;
+    if (wide) {
+        w.Am = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * d_in * 4, 256);
+        w.P = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * d_in * 4, 256);
+        w.bc = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * 8, 256);
+        w.flags = reinterpret_cast<int32_t*>(p);
+    }
     return w;
 }
 
 }  // namespace
 
 size_t jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size) {
-    (void)group_size;
     const int64_t ldD = split_update_ld(d_out);
+    const size_t wide = group_size > 128 ? 2 * align_up(size_t(d_out) * d_in * 4, 256) + 2 * align_up(size_t(d_out) * 8, 256)
+                                         : 0;
     return 2 * align_up(size_t(d_out) * d_in * 4, 256) + 2 * align_up(size_t(d_in + 32) * d_in * 2, 256) +
            2 * align_up(size_t(rows_d(d_in)) * ldD * 2, 256) + align_up(size_t(d_out) * JQ_SBW * 4, 256) +
-           align_up(size_t(d_in) * 4, 256) + align_up(size_t(d_out) * 4, 256) + 256;
+           align_up(size_t(d_in) * 4, 256) + align_up(size_t(d_out) * 4, 256) + 256 + wide;
 }
 
 onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* A, float lam,
@@ -436,7 +573,8 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
     const bool symmetric = grid == ONECOMP_GRID_SYMMETRIC || grid == ONECOMP_GRID_SYMMETRIC_MSE;
     const float qtop = symmetric ? float(2 * ((1 << (bits - 1)) - 1)) : float((1 << bits) - 1);
     const int bf16 = w_dtype == ONECOMP_BF16;
-    JqWs w = carve(workspace, d_out, d_in);
+    const bool wide = G > 128;
+    JqWs w = carve(workspace, d_out, d_in, wide);
     const int64_t ldD = split_update_ld(d_out);
     const dim3 rgrid{unsigned(d_out < 4096 ? d_out : 4096)};
     auto pad32 = [](int k) { return (k + 31) / 32 * 32; };
@@ -444,7 +582,7 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
 
     hipLaunchKernelGGL(jq_zero_kernel, dim3(1), dim3(1), 0, stream, n_moves);
     ONECOMP_CHECK_LAUNCH();
-    hipLaunchKernelGGL(jq_scalars_init_kernel, dim3(1), dim3(64), 0, stream, w.sc, 5);
+    hipLaunchKernelGGL(jq_scalars_init_kernel, dim3(1), dim3(64), 0, stream, w.sc, 7);
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(jq_diag_kernel, dim3(unsigned(ceil_div(d_in, 256))), dim3(256), 0, stream, A, int(d_in), lam, w.d);
     ONECOMP_CHECK_LAUNCH();
@@ -465,9 +603,12 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
         return ONECOMP_OK;
     };
     // Gm~[:, c_lo .. c_hi) += (rows row0 .. of D)^T A~[u0 .. u0 + pad32(k_count), c_lo .. c_hi)
+    auto update_to = [&](float* C, int row0, int k_count, int u0, int c_lo, int c_hi,
+                         const Scalars* sc) -> onecomp_status {
+        return split_update(C, d_out, d_in, w.Dh, w.Dl, ldD, w.Bh, w.Bl, sc, row0, pad32(k_count), u0, c_lo, c_hi, stream);
+    };
     auto update = [&](int row0, int k_count, int u0, int c_lo, int c_hi, const Scalars* sc) -> onecomp_status {
-        return split_update(w.Gm, d_out, d_in, w.Dh, w.Dl, ldD, w.Bh, w.Bl, sc, row0, pad32(k_count), u0, c_lo, c_hi,
-                            stream);
+        return update_to(w.Gm, row0, k_count, u0, c_lo, c_hi, sc);
     };
     if ((st = dsplit(w.R, d_in, int(d_in), 0, 0, w.sc, nullptr)) != ONECOMP_OK) return st;
     hipLaunchKernelGGL(jq_fill0_kernel, dim3(2048), dim3(256), 0, stream, w.Gm, d_out * d_in / 4);
@@ -479,46 +620,109 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
     hipLaunchKernelGGL(jq_total_kernel, dim3(1), dim3(1024), 0, stream, w.rowf, int(d_out), objective);
     ONECOMP_CHECK_LAUNCH();
 
-    static std::atomic<uint64_t> lds1{0}, lds2{0};
-    const int lds_bytes = G * G * 4;
-    if (G <= 64) {
-        if (allow_dynamic_lds(reinterpret_cast<const void*>(&jq_visit_kernel<1>), 64 * 64 * 4, lds1) != ONECOMP_OK)
+    static std::atomic<uint64_t> lds1{0}, lds2{0}, lds3{0};
+    const int GB = wide ? 128 : G;   // columns of one launch of the visit kernel
+    const int lds_bytes = GB * GB * 4;
+    if (wide) {
+        if (allow_dynamic_lds(reinterpret_cast<const void*>(&jq_visit_kernel<2, true>), 128 * 128 * 4, lds3) != ONECOMP_OK)
+            return ONECOMP_ERR_HIP;
+    } else if (G <= 64) {
+        if (allow_dynamic_lds(reinterpret_cast<const void*>(&jq_visit_kernel<1, false>), 64 * 64 * 4, lds1) != ONECOMP_OK)
             return ONECOMP_ERR_HIP;
     } else {
-        if (allow_dynamic_lds(reinterpret_cast<const void*>(&jq_visit_kernel<2>), 128 * 128 * 4, lds2) != ONECOMP_OK)
+        if (allow_dynamic_lds(reinterpret_cast<const void*>(&jq_visit_kernel<2, false>), 128 * 128 * 4, lds2) != ONECOMP_OK)
             return ONECOMP_ERR_HIP;
     }
     VisitArgs v;
-    v.W = W; v.w_bf16 = bf16; v.d_out = int(d_out); v.d_in = int(d_in); v.G = G; v.n_g = n_g; v.t = 0;
+    v.W = W; v.w_bf16 = bf16; v.d_out = int(d_out); v.d_in = int(d_in); v.G = GB; v.n_g = n_g; v.t = 0;
     v.A = A; v.lam = lam; v.qtop = qtop; v.Q = Q; v.scales = scales; v.zeros = zeros; v.Gm = w.Gm; v.d = w.d;
     v.dR = w.dR; v.max_scans = max_scans; v.moves = n_moves;
+    v.col0 = 0; v.Am = w.Am; v.P = w.P; v.bc = w.bc; v.flags = w.flags;
     const dim3 vgrid{unsigned(ceil_div(d_out, JQ_ROWS))};
-    const int sbg = JQ_SBW / G > 0 ? JQ_SBW / G : 1;   // groups per super-block
-    v.ldr = sbg * G;
+    const int sbg = JQ_SBW / GB > 0 ? JQ_SBW / GB : 1;   // launches of the visit kernel per super-block
+    v.ldr = sbg * GB;
     int n_visit = 0, n_sb = 0;
-    for (int ps = 0; ps < n_pass; ++ps)
-        for (int t0 = 0; t0 < n_g; t0 += sbg, ++n_sb) {
-            const int t1 = t0 + sbg < n_g ? t0 + sbg : n_g;
-            Scalars* sc_far = w.sc + 3 + (n_sb & 1);
-            for (int t = t0; t < t1; ++t, ++n_visit) {
-                Scalars* sc_near = w.sc + 1 + (n_visit & 1);
-                v.t = t;
-                v.dR = w.dR + (t - t0) * G;
-                v.sc_near = sc_near; v.sc_far = sc_far;
-                if (G <= 64) hipLaunchKernelGGL(jq_visit_kernel<1>, vgrid, dim3(64 * JQ_ROWS), lds_bytes, stream, v);
-                else hipLaunchKernelGGL(jq_visit_kernel<2>, vgrid, dim3(64 * JQ_ROWS), lds_bytes, stream, v);
-                ONECOMP_CHECK_LAUNCH();
-                // the super-block's own columns at once
-                if ((st = dsplit(v.dR, v.ldr, G, t * G, JQ_NEAR0, sc_near, w.sc + 1 + ((n_visit + 1) & 1))) != ONECOMP_OK)
+    if (!wide) {
+        for (int ps = 0; ps < n_pass; ++ps)
+            for (int t0 = 0; t0 < n_g; t0 += sbg, ++n_sb) {
+                const int t1 = t0 + sbg < n_g ? t0 + sbg : n_g;
+                Scalars* sc_far = w.sc + 3 + (n_sb & 1);
+                for (int t = t0; t < t1; ++t, ++n_visit) {
+                    Scalars* sc_near = w.sc + 1 + (n_visit & 1);
+                    v.t = t;
+                    v.col0 = t * G;
+                    v.dR = w.dR + (t - t0) * G;
+                    v.sc_near = sc_near; v.sc_far = sc_far;
+                    if (G <= 64)
+                        hipLaunchKernelGGL((jq_visit_kernel<1, false>), vgrid, dim3(64 * JQ_ROWS), lds_bytes, stream, v);
+                    else
+                        hipLaunchKernelGGL((jq_visit_kernel<2, false>), vgrid, dim3(64 * JQ_ROWS), lds_bytes, stream, v);
+                    ONECOMP_CHECK_LAUNCH();
+                    // the super-block's own columns at once
+                    if ((st = dsplit(v.dR, v.ldr, G, t * G, JQ_NEAR0, sc_near, w.sc + 1 + ((n_visit + 1) & 1))) != ONECOMP_OK)
+                        return st;
+                    if ((st = update(JQ_NEAR0, G, t * G, t0 * G, t1 * G, sc_near)) != ONECOMP_OK) return st;
+                }
+                // all other columns once per super-block
+                if ((st = dsplit(w.dR, v.ldr, (t1 - t0) * G, t0 * G, 0, sc_far, w.sc + 3 + ((n_sb + 1) & 1))) != ONECOMP_OK)
                     return st;
-                if ((st = update(JQ_NEAR0, G, t * G, t0 * G, t1 * G, sc_near)) != ONECOMP_OK) return st;
+                if ((st = update(0, (t1 - t0) * G, t0 * G, 0, t0 * G, sc_far)) != ONECOMP_OK) return st;
+                if ((st = update(0, (t1 - t0) * G, t0 * G, t1 * G, int(d_in), sc_far)) != ONECOMP_OK) return st;
             }
-            // all other columns once per super-block
-            if ((st = dsplit(w.dR, v.ldr, (t1 - t0) * G, t0 * G, 0, sc_far, w.sc + 3 + ((n_sb + 1) & 1))) != ONECOMP_OK)
-                return st;
-            if ((st = update(0, (t1 - t0) * G, t0 * G, 0, t0 * G, sc_far)) != ONECOMP_OK) return st;
-            if ((st = update(0, (t1 - t0) * G, t0 * G, t1 * G, int(d_in), sc_far)) != ONECOMP_OK) return st;
-        }
+    } else {
+        // A group spans n_b blocks of 128 columns.  Visit of group g: a = (A_gg + lam I) u for the whole group by one
+        // product (Am), p, b, c from it; then up to max_scans scans, each one launch per block in column order with
+        // Am brought up to date between the launches (the super-block's columns at once, the group's other columns
+        // once per super-block); at the end the scale, and the gradient of all columns from the group's dR.
+        const int n_b = G / 128;
+        const dim3 fgrid{2048};
+        for (int ps = 0; ps < n_pass; ++ps)
+            for (int g = 0; g < n_g; ++g) {
+                const int g0 = g * G;
+                v.t = g;
+                hipLaunchKernelGGL(jq_wide_begin_kernel, rgrid, dim3(256), 0, stream, int(d_out), int(d_in), Q, zeros, n_g, g,
+                                   G, w.d, w.R, w.sc + 5);
+                ONECOMP_CHECK_LAUNCH();
+                if ((st = dsplit(w.R + g0, d_in, G, g0, 0, w.sc + 5, w.sc + 6)) != ONECOMP_OK) return st;
+                hipLaunchKernelGGL(jq_fill0_kernel, fgrid, dim3(256), 0, stream, w.Am, d_out * d_in / 4);
+                ONECOMP_CHECK_LAUNCH();
+                if ((st = update_to(w.Am, 0, G, g0, g0, g0 + G, w.sc + 5)) != ONECOMP_OK) return st;
+                hipLaunchKernelGGL(jq_wide_p_kernel, rgrid, dim3(256), 0, stream, int(d_out), int(d_in), scales, n_g, g, G,
+                                   w.d, w.R, w.Gm, w.Am, w.P, w.bc, w.flags);
+                ONECOMP_CHECK_LAUNCH();
+                for (int scan = 0; scan < max_scans; ++scan) {
+                    for (int i0 = 0; i0 < n_b; i0 += sbg, ++n_sb) {
+                        const int i1 = i0 + sbg < n_b ? i0 + sbg : n_b;
+                        const int sb0 = g0 + i0 * 128, sb1 = g0 + i1 * 128;
+                        Scalars* sc_far = w.sc + 3 + (n_sb & 1);
+                        for (int i = i0; i < i1; ++i, ++n_visit) {
+                            Scalars* sc_near = w.sc + 1 + (n_visit & 1);
+                            v.col0 = g0 + i * 128;
+                            v.dR = w.dR + (i - i0) * 128;
+                            v.sc_near = sc_near; v.sc_far = sc_far;
+                            hipLaunchKernelGGL((jq_visit_kernel<2, true>), vgrid, dim3(64 * JQ_ROWS), lds_bytes, stream, v);
+                            ONECOMP_CHECK_LAUNCH();
+                            if ((st = dsplit(v.dR, v.ldr, 128, v.col0, JQ_NEAR0, sc_near,
+                                             w.sc + 1 + ((n_visit + 1) & 1))) != ONECOMP_OK)
+                                return st;
+                            if ((st = update_to(w.Am, JQ_NEAR0, 128, v.col0, sb0, sb1, sc_near)) != ONECOMP_OK) return st;
+                        }
+                        if ((st = dsplit(w.dR, v.ldr, sb1 - sb0, sb0, 0, sc_far, w.sc + 3 + ((n_sb + 1) & 1))) != ONECOMP_OK)
+                            return st;
+                        if ((st = update_to(w.Am, 0, sb1 - sb0, sb0, g0, sb0, sc_far)) != ONECOMP_OK) return st;
+                        if ((st = update_to(w.Am, 0, sb1 - sb0, sb0, sb1, g0 + G, sc_far)) != ONECOMP_OK) return st;
+                    }
+                    hipLaunchKernelGGL(jq_scan_end_kernel, dim3(unsigned(ceil_div(d_out, 256))), dim3(256), 0, stream,
+                                       int(d_out), w.flags);
+                    ONECOMP_CHECK_LAUNCH();
+                }
+                hipLaunchKernelGGL(jq_wide_end_kernel, rgrid, dim3(256), 0, stream, int(d_out), int(d_in), Q, scales, zeros,
+                                   n_g, g, G, w.d, w.bc, w.R, w.sc + 6);
+                ONECOMP_CHECK_LAUNCH();
+                if ((st = dsplit(w.R + g0, d_in, G, g0, 0, w.sc + 6, w.sc + 5)) != ONECOMP_OK) return st;
+                if ((st = update(0, G, g0, 0, int(d_in), w.sc + 6)) != ONECOMP_OK) return st;
+            }
+    }
     hipLaunchKernelGGL(jq_objective_kernel, rgrid, dim3(256), 0, stream, W, bf16, int(d_out), int(d_in), Q, scales, zeros,
                        G, n_g, w.Gm, w.d, w.rowf, W_hat);
     ONECOMP_CHECK_LAUNCH();

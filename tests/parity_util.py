@@ -122,6 +122,7 @@ def compare_codes(gpu_Q, gpu_zeros, W, U, bits, G, perm=None, rows=None, max_rou
 
 JQ_TIE_TOL = 1e-4   # JointQ: a decision is a legitimate toss-up iff |N| is within this fraction of the terms it sums
 JQ_G_TOL = 2e-6     # ... plus this fraction of sum |r_k| |A_kj|, the rounding of the fp32 gradient kept on the GPU
+JQ_A_TOL = 2e-6     # ... and, for groups wider than a block, of s* sum |u_k| |A_kj|: there a = A_gg u is carried along too
 
 
 def _jq_prefix(o, i, gq, gs, G, n_g):
@@ -135,7 +136,7 @@ def _jq_prefix(o, i, gq, gs, G, n_g):
 
 
 def compare_jointq(gpu_Q, gpu_S, W, A, Q0, S0, Z, bits, G, grid="asym", n_pass=1, max_scans=4, rows=None,
-                   max_flips=6, max_tries=16):
+                   max_flips=6, max_tries=16, wide=False):
     """GPU result of onecomp_jointq_refine against the oracle's local search from the same start.
 
     A row must equal the oracle's exactly in its codes (scales to 1e-4), or become equal once decisions the oracle
@@ -150,7 +151,7 @@ def compare_jointq(gpu_Q, gpu_S, W, A, Q0, S0, Z, bits, G, grid="asym", n_pass=1
     gs = np.asarray(gpu_S, dtype=np.float64)
     n_g = W.shape[1] // G
     kw = dict(bits=bits, group_size=G, grid=grid, n_pass=n_pass, max_scans=max_scans, tie_tol=JQ_TIE_TOL,
-              g_tol=JQ_G_TOL)
+              g_tol=JQ_G_TOL, a_tol=JQ_A_TOL if wide else 0.0)
     o = oc.jointq_refine(W, A, Q0, S0, Z, rows=rows, **kw)
     res = {k: (np.array(v, copy=True) if isinstance(v, np.ndarray) else v) for k, v in o.items()}
     clean, flipped, flips, real = 0, 0, 0, []

@@ -286,7 +286,7 @@ def test_jointq_argument_checks(lib):
     assert call(dt=3) == UNSUPPORTED
     assert call(grid=7) == UNSUPPORTED
     assert call(bits=5) == UNSUPPORTED
-    assert call(G=256, d_in=512) == UNSUPPORTED      # groups wider than 128
+    assert call(G=192, d_in=384) == UNSUPPORTED      # wider than 128 and not a multiple of 128
     assert call(G=24, d_in=240) == UNSUPPORTED       # not a multiple of 16
     assert call(W=NULL) == INVALID
     assert call(H=NULL) == INVALID
@@ -302,4 +302,5 @@ def test_jointq_argument_checks(lib):
     assert call(wsb=ctypes.c_size_t(1024)) == WORKSPACE
     g = lib.onecomp_jointq_workspace_bytes
     assert g(64, 256, 128) >= 2 * 64 * 256 * 4
-    assert g(64, 256, 256) == 0 and g(0, 256, 128) == 0 and g(64, 250, 50) == 0
+    assert g(64, 384, 192) == 0 and g(0, 256, 128) == 0 and g(64, 250, 50) == 0
+    assert g(64, 256, 256) > g(64, 256, 128)         # wider groups carry two more matrices

@@ -52,7 +52,8 @@ def _run(W, Wd, H32, Q0, S0, Z0, bits, G, grid="asym", lam=0.0, n_pass=1, max_sc
     assert gq.max() <= qtop
     deq = (np.repeat(gs, G, axis=1) * (gq.astype(np.float32) - np.repeat(Z0.astype(np.float32), G, axis=1)))
     assert np.array_equal(deq.astype(np.float32), wh)
-    st = compare_jointq(gq, gs, Wd, A, Q0, S0f, Z0, bits, G, grid=grid, n_pass=n_pass, max_scans=max_scans)
+    st = compare_jointq(gq, gs, Wd, A, Q0, S0f, Z0, bits, G, grid=grid, n_pass=n_pass, max_scans=max_scans,
+                        wide=G > 128)
     _announce(f"   clean rows {st['clean_rows']}/{d_out}, rows equal after {st['flips']} forced toss-ups: "
               f"{st['flipped_rows']}, real mismatches {len(st['real_mismatches'])}, moves {int(out['n_moves'].item())}")
     assert st["real_mismatches"] == []
@@ -98,6 +99,19 @@ def test_jointq_matches_oracle(bits, G, d_out, d_in, dtype, grid, start, n_pass,
         assert torch.equal(out[k], out2[k])
 
 
+@pytest.mark.parametrize("bits,G,d_out,d_in,dtype,grid,start,n_pass,scans,lam", [
+    (4, 256, 40, 512, torch.float32, "asym", "rtn", 1, 3, 0.0),        # two blocks per group
+    (3, 640, 33, 1280, torch.bfloat16, "asym", "gptq", 1, 4, 0.0),     # a group straddles a 512-column super-block
+    (4, 1024, 24, 1024, torch.bfloat16, "sym", "gptq", 1, 4, 0.0),     # one group per row, symmetric: the paper's setting
+    (3, 384, 20, 768, torch.float32, "asym", "rtn", 2, 2, 10.0),       # two passes, regularizer
+])
+def test_jointq_wide_groups(bits, G, d_out, d_in, dtype, grid, start, n_pass, scans, lam):
+    """Groups of several 128-column blocks: b, c and a = A_gg u are carried from launch to launch."""
+    _announce(f"jointq wide b{bits} g{G} {d_out}x{d_in} {dtype} {grid} start={start} passes={n_pass} scans={scans} lam={lam}")
+    W, Wd, H32, Q0, S0, Z0 = _start(d_out, d_in, bits, G, seed=300 + bits + G % 7, dtype=dtype, grid=grid, start=start)
+    _run(W, Wd, H32, Q0, S0, Z0, bits, G, grid=grid, lam=lam, n_pass=n_pass, max_scans=scans)
+
+
 def test_jointq_degenerate_rows_and_zero_passes():
     _announce("jointq: all-zero group, codes at the zero-point; n_pass = 0 returns the start")
     W, Wd, H32, Q0, S0, Z0 = _start(8, 256, 4, 64, seed=77)
@@ -114,8 +128,9 @@ def test_jointq_degenerate_rows_and_zero_passes():
     torch.cuda.synchronize()
     assert np.array_equal(o0["Q_codes"].cpu().numpy(), Q0) and int(o0["n_moves"].item()) == 0
     assert float(o0["objective"][0]) == float(o0["objective"][1])
-    with pytest.raises(og.OnecompError):
-        og.onecomp_jointq_refine(W, torch.from_numpy(H32).to(DEV), Q, S[:, :1].contiguous(), Z[:, :1].contiguous(), 4, 256)
+    with pytest.raises(og.OnecompError):     # wider than a block and not a multiple of 128
+        og.onecomp_jointq_refine(W[:, :192].contiguous(), torch.from_numpy(H32[:192, :192].copy()).to(DEV),
+                                 Q[:, :192].contiguous(), S[:, :1].contiguous(), Z[:, :1].contiguous(), 4, 192)
 
 
 def test_jointq_full_size_sampled():
