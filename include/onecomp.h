@@ -318,20 +318,20 @@ size_t onecomp_sensitivity_workspace_bytes(void);
  *   W         device, d_out x d_in, row-major, fp32 or bf16: the weights the objective measures against.
  *   H         device fp32, d_in x d_in, symmetric (as onecomp_hessian_accumulate leaves it), read only.
  *   lam       >= 0, added to the diagonal of H (in the paper's terms 2 n lambda, since H = 2 X^T X).
- *   group_size  multiple of 16, at most 128, divides d_in.
+ *   group_size  divides d_in; a multiple of 16 up to 128, or a multiple of 128 (up to d_in: one group per row).
  *   Q_codes, scales  device, in and out (d_out x d_in uint8, d_out x d_in/group_size fp32).
  *   zeros     device fp32, d_out x d_in/group_size, read only.
  *   W_hat     device fp32 d_out x d_in or NULL, out: s (q - z) of the result.
  *   objective device fp32[2], out: sum over rows of f before and after.
  *   n_moves   device int32, out: number of moves taken.
- *   workspace device scratch, >= onecomp_jointq_workspace_bytes() (about 9 d_out d_in + 4 d_in^2 bytes), 256-byte
- *             aligned.
+ *   workspace device scratch, >= onecomp_jointq_workspace_bytes() (about 9 d_out d_in + 4 d_in^2 bytes, 17 d_out d_in
+ *             + 4 d_in^2 for groups wider than 128), 256-byte aligned.
  * Arithmetic: fp32; the gradient R (H + lam I) and its rank-group_size updates are fp16 MFMA products of operands
  * split into hi + lo halves (22 significant bits each, H taken as the correlation matrix H_kj / sqrt(H_kk H_jj)),
  * accumulated in fp32.  A decision whose gain is within rounding of zero may fall either way; results are
  * reproducible run to run.
  * Errors: INVALID_ARG (null pointer, bad size, lam < 0, n_pass < 0, max_scans < 1), UNSUPPORTED (dtype, bits, grid,
- * group_size > 128 or not a multiple of 16), WORKSPACE.
+ * group_size not a multiple of 16, or above 128 and not a multiple of 128), WORKSPACE.
  */
 onecomp_status onecomp_jointq_refine(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
                                      const float* H, float lam, int bits, int group_size, onecomp_grid grid,

@@ -560,8 +560,8 @@ def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=
     (natural column order).  forced: {(row, pass, t, scan, j, d): bool} overrides single decisions (rows numbered
     within the subset); with tie_tol > 0 every decision with
     |N| <= tie_tol * M + 2 |b| (g_tol (|r| |A|)_j + a_tol |s*| (|u| |A_tt|)_j), M the sum of the absolute values of
-    the terms N is built from, is listed in "ties" (g_tol, a_tol: the rounding of a gradient and of a = A_tt u that
-    are carried along rather than recomputed).
+    the terms N is built from, is listed in "ties" as (pass, t, scan, j, d, taken) (g_tol, a_tol: the rounding of a
+    gradient and of a = A_tt u that are carried along rather than recomputed).
     Returns dict(Q, scales, W_hat, f0, f1 (row objective before / after), moves [rows], ties [list per row])."""
     W = np.asarray(W, dtype=np.float64)
     A = np.asarray(A, dtype=np.float64)
@@ -623,7 +623,7 @@ def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=
                                 slack = slack + a_tol * np.abs(ss) * aabs[:, j]
                             near = ok & (np.abs(N) <= tie_tol * M + 2.0 * np.abs(b) * slack)
                             for i in np.nonzero(near)[0]:
-                                ties[i].append((ps, t, scan, j, int(d)))
+                                ties[i].append((ps, t, scan, j, int(d), bool(acc[i])))
                         for i in np.nonzero(ok)[0] if forced else ():
                             key = (int(i), ps, t, scan, j, int(d))
                             if key in forced:

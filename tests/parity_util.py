@@ -135,47 +135,78 @@ def _jq_prefix(o, i, gq, gs, G, n_g):
     return n_g
 
 
+def _jq_first_column(o, i, gq):
+    bad = np.nonzero(o["Q"][i] != gq)[0]
+    return int(bad[0]) if len(bad) else -1
+
+
 def compare_jointq(gpu_Q, gpu_S, W, A, Q0, S0, Z, bits, G, grid="asym", n_pass=1, max_scans=4, rows=None,
-                   max_flips=6, max_tries=16, wide=False):
+                   max_flips=6, max_tries=24, wide=False):
     """GPU result of onecomp_jointq_refine against the oracle's local search from the same start.
 
     A row must equal the oracle's exactly in its codes (scales to 1e-4), or become equal once decisions the oracle
-    itself lists as toss-ups (JQ_TIE_TOL, JQ_G_TOL) are forced the other way: per mismatching row the oracle is
-    rerun with one listed decision forced at a time, a flip is kept when the rows then agree over more leading
-    groups (for several passes: when they agree entirely), up to max_flips flips.
+    itself lists as toss-ups (JQ_TIE_TOL, JQ_G_TOL, JQ_A_TOL) are forced the other way.
+    One pass of one scan: every column is decided once, so the GPU's decisions can be read off its codes; the
+    first column that differs names the decision, which must be a listed toss-up and is then forced to the GPU's
+    (the replay of the sweep's protocol).  Otherwise the decisions are not observable: the oracle is rerun with one
+    listed toss-up flipped at a time, and a flip is kept when the rows then agree over more leading groups or, with
+    that unchanged, in more codes; up to max_flips flips.
     Returns dict(clean_rows, flipped_rows, flips, real_mismatches, oracle)."""
     W = np.asarray(W, dtype=np.float64)
     A = np.asarray(A, dtype=np.float64)
     rows = np.arange(W.shape[0]) if rows is None else np.asarray(rows)
     gq = np.asarray(gpu_Q, dtype=np.int64)
     gs = np.asarray(gpu_S, dtype=np.float64)
+    Q0 = np.asarray(Q0)
     n_g = W.shape[1] // G
     kw = dict(bits=bits, group_size=G, grid=grid, n_pass=n_pass, max_scans=max_scans, tie_tol=JQ_TIE_TOL,
               g_tol=JQ_G_TOL, a_tol=JQ_A_TOL if wide else 0.0)
     o = oc.jointq_refine(W, A, Q0, S0, Z, rows=rows, **kw)
     res = {k: (np.array(v, copy=True) if isinstance(v, np.ndarray) else v) for k, v in o.items()}
     clean, flipped, flips, real = 0, 0, 0, []
+    single = n_pass == 1 and max_scans == 1
+
+    def run1(i, forced):
+        return oc.jointq_refine(W, A, Q0, S0, Z, rows=rows[i:i + 1], forced=forced, **kw)
+
     for i in range(len(rows)):
         if _jq_prefix(o, i, gq[i], gs[i], G, n_g) == n_g:
             clean += 1
             continue
-        forced, cur, ok = {}, None, False
-        cur = oc.jointq_refine(W, A, Q0, S0, Z, rows=rows[i:i + 1], **kw)
-        for _ in range(max_flips):
+        forced, ok = {}, False
+        cur = run1(i, forced)
+        for _ in range(max_flips if not single else 4 * max_flips):
             pre = _jq_prefix(cur, 0, gq[i], gs[i], G, n_g)
             if pre == n_g:
                 ok = True
                 break
-            cands = [k for k in cur["ties"][0] if (0,) + k not in forced and (n_pass > 1 or k[1] == pre)]
+            listed = {k[:5]: k[5] for k in cur["ties"][0]}
+            if single:
+                j = _jq_first_column(cur, 0, gq[i])
+                if j < 0:
+                    break                        # codes equal, a scale differs: not a toss-up
+                t, jl = j // G, j % G
+                want = int(gq[i, j] - Q0[rows[i], j])          # the GPU's decision at this column
+                f2 = dict(forced)
+                for d in (1, -1):
+                    key = (0, t, 0, jl, d)
+                    if key in listed and listed[key] != (want == d):
+                        f2[(0,) + key] = (want == d)
+                if f2 == forced:
+                    break                        # the differing decision is not a listed toss-up
+                forced, cur = f2, run1(i, f2)
+                flips += 1
+                continue
+            ham = int((cur["Q"][0] != gq[i]).sum())
+            cands = [k for k in listed if (0,) + k not in forced and (n_pass > 1 or k[1] == pre)]
             best = None
             for k in cands[:max_tries]:
-                for val in (True, False):
-                    f2 = dict(forced)
-                    f2[(0,) + k] = val
-                    trial = oc.jointq_refine(W, A, Q0, S0, Z, rows=rows[i:i + 1], forced=f2, **kw)
-                    pre2 = _jq_prefix(trial, 0, gq[i], gs[i], G, n_g)
-                    if pre2 > pre and (best is None or pre2 > best[0]):
-                        best = (pre2, f2, trial)
+                f2 = dict(forced)
+                f2[(0,) + k] = not listed[k]
+                trial = run1(i, f2)
+                score = (_jq_prefix(trial, 0, gq[i], gs[i], G, n_g), -int((trial["Q"][0] != gq[i]).sum()))
+                if score > (pre, -ham) and (best is None or score > best[0]):
+                    best = (score, f2, trial)
             if best is None:
                 break
             _, forced, cur = best

@@ -82,6 +82,7 @@ def _run(W, Wd, H32, Q0, S0, Z0, bits, G, grid="asym", lam=0.0, n_pass=1, max_sc
     (4, 128, 48, 512, torch.bfloat16, "asym", "gptq", 2, 3, 0.0),     # two passes over the groups
     (3, 64, 32, 256, torch.float32, "asym", "rtn", 1, 4, 25.0),       # proximity regularizer (Eq. (jointq_reg))
     (4, 48, 16, 192, torch.float32, "asym", "rtn", 1, 4, 0.0),        # group size not a power of two
+    (3, 128, 64, 768, torch.bfloat16, "asym", "rtn", 1, 1, 0.0),      # one scan: decisions replayed exactly
 ])
 def test_jointq_matches_oracle(bits, G, d_out, d_in, dtype, grid, start, n_pass, scans, lam):
     _announce(f"jointq b{bits} g{G} {d_out}x{d_in} {dtype} {grid} start={start} passes={n_pass} scans={scans} lam={lam}")
@@ -104,6 +105,7 @@ def test_jointq_matches_oracle(bits, G, d_out, d_in, dtype, grid, start, n_pass,
     (3, 640, 33, 1280, torch.bfloat16, "asym", "gptq", 1, 4, 0.0),     # a group straddles a 512-column super-block
     (4, 1024, 24, 1024, torch.bfloat16, "sym", "gptq", 1, 4, 0.0),     # one group per row, symmetric: the paper's setting
     (3, 384, 20, 768, torch.float32, "asym", "rtn", 2, 2, 10.0),       # two passes, regularizer
+    (4, 1024, 40, 1024, torch.bfloat16, "asym", "rtn", 1, 1, 0.0),     # one scan: decisions replayed exactly
 ])
 def test_jointq_wide_groups(bits, G, d_out, d_in, dtype, grid, start, n_pass, scans, lam):
     """Groups of several 128-column blocks: b, c and a = A_gg u are carried from launch to launch."""
@@ -134,45 +136,50 @@ def test_jointq_degenerate_rows_and_zero_passes():
 
 
 def test_jointq_full_size_sampled():
-    """The 4096 x 14336 layer of the benchmark (bf16, 4-bit, group 128): the whole layer is refined on the GPU, a
-    sample of rows is compared with the oracle.  The sampled rows start from the oracle's own sweep, the other rows
+    """The 4096 x 14336 layer of the benchmark (bf16, 4-bit): the whole layer is refined on the GPU, a sample of rows
+    is compared with the oracle, for group 128 on the min-max grid and for one group per row on the symmetric grid
+    (the setting of the paper's JointQ table).  The sampled rows start from the oracle's own sweep, the other rows
     from the GPU's (rows are independent); H is the oracle's Gram matrix of 32768 tokens rounded to fp32."""
     cfg = synth.scaled(synth.CONFIGS["c3b"], n_tokens=32768)
-    d_out, d_in, G, bits = cfg.d_out, cfg.d_in, cfg.group_size, cfg.bits
-    _announce(f"jointq full size {d_out}x{d_in} b{bits} g{G}: oracle Gram and factor")
+    d_out, d_in, bits = cfg.d_out, cfg.d_in, cfg.bits
+    _announce(f"jointq full size {d_out}x{d_in} b{bits}: oracle Gram and factor")
     W = synth.make_weight(cfg, DEV)
     X = synth.make_activations(cfg, DEV)
     H32 = oc.hessian_accumulate(to_f64(X)).astype(np.float32)
     del X
     A = H32.astype(np.float64)
     f = oc.hessian_factor(A, cfg.damp)
-    rows = np.sort(np.random.default_rng(11).choice(d_out, size=12, replace=False))
     Wd = to_f64(W)
-    _announce("jointq full size: oracle sweep of the sampled rows, GPU sweep of the layer")
-    o0 = oc.quantize_layer(Wd, f["U"], bits, G, rows=rows)
     H = torch.from_numpy(H32).to(DEV)
     U32 = torch.from_numpy(f["U"].astype(np.float32)).to(DEV)
-    del f
-    g0 = og.onecomp_quantize_layer(W, U32, bits, G, want_w_hat=False)
-    del U32
-    Q, S, Z = g0["Q_codes"], g0["scales"], g0["zeros"]
-    ridx = torch.from_numpy(rows).to(DEV)
-    Q[ridx] = torch.from_numpy(o0["Q"].astype(np.uint8)).to(DEV)
-    S[ridx] = torch.from_numpy(o0["scales"].astype(np.float32)).to(DEV)
-    Z[ridx] = torch.from_numpy(o0["zeros"].astype(np.float32)).to(DEV)
-    _announce("jointq full size: GPU refinement, one pass")
-    out = og.onecomp_jointq_refine(W, H, Q, S, Z, bits, G, n_pass=1, max_scans=4, want_w_hat=False)
-    torch.cuda.synchronize()
-    obj = out["objective"].cpu().numpy()
-    _announce(f"   objective {obj[0]:.4e} -> {obj[1]:.4e}, moves {int(out['n_moves'].item())}")
-    assert obj[1] < 0.8 * obj[0]
-    gq = out["Q_codes"][ridx].cpu().numpy()
-    gs = out["scales"][ridx].cpu().numpy()
-    _announce("jointq full size: oracle refinement of the sampled rows")
-    S0f = o0["scales"].astype(np.float32).astype(np.float64)
-    st = compare_jointq(gq, gs, Wd[rows], A, o0["Q"], S0f, o0["zeros"], bits, G, n_pass=1, max_scans=4)
-    _announce(f"   clean rows {st['clean_rows']}/{len(rows)}, rows equal after {st['flips']} forced toss-ups: "
-              f"{st['flipped_rows']}, real mismatches {len(st['real_mismatches'])}")
-    assert st["real_mismatches"] == []
-    assert np.array_equal(st["oracle"]["Q"], gq)
-    np.testing.assert_allclose(gs, st["oracle"]["scales"], rtol=1e-4)
+    # one group per row: a single scan, so that every decision can be read off the codes and replayed exactly
+    for G, grid, n_rows, scans in ((cfg.group_size, "asym", 12, 4), (d_in, "sym", 6, 1)):
+        ggrid = "symmetric" if grid == "sym" else "minmax"
+        rows = np.sort(np.random.default_rng(11).choice(d_out, size=n_rows, replace=False))
+        _announce(f"jointq full size g{G} {grid}: oracle sweep of {n_rows} sampled rows, GPU sweep of the layer")
+        o0 = oc.quantize_layer(Wd, f["U"], bits, G, rows=rows, grid=grid)
+        g0 = og.onecomp_quantize_layer(W, U32, bits, G, want_w_hat=False, grid=ggrid)
+        Q, S, Z = g0["Q_codes"], g0["scales"], g0["zeros"]
+        ridx = torch.from_numpy(rows).to(DEV)
+        Q[ridx] = torch.from_numpy(o0["Q"].astype(np.uint8)).to(DEV)
+        S[ridx] = torch.from_numpy(o0["scales"].astype(np.float32)).to(DEV)
+        Z[ridx] = torch.from_numpy(o0["zeros"].astype(np.float32)).to(DEV)
+        _announce("jointq full size: GPU refinement, one pass")
+        out = og.onecomp_jointq_refine(W, H, Q, S, Z, bits, G, grid=ggrid, n_pass=1, max_scans=scans, want_w_hat=False)
+        torch.cuda.synchronize()
+        obj = out["objective"].cpu().numpy()
+        _announce(f"   objective {obj[0]:.4e} -> {obj[1]:.4e}, moves {int(out['n_moves'].item())}")
+        assert obj[1] < 0.9 * obj[0]
+        gq = out["Q_codes"][ridx].cpu().numpy()
+        gs = out["scales"][ridx].cpu().numpy()
+        del out, g0, Q, S, Z
+        torch.cuda.empty_cache()
+        _announce("jointq full size: oracle refinement of the sampled rows")
+        S0f = o0["scales"].astype(np.float32).astype(np.float64)
+        st = compare_jointq(gq, gs, Wd[rows], A, o0["Q"], S0f, o0["zeros"], bits, G, grid=grid, n_pass=1,
+                            max_scans=scans, wide=G > 128)
+        _announce(f"   clean rows {st['clean_rows']}/{len(rows)}, rows equal after {st['flips']} forced toss-ups: "
+                  f"{st['flipped_rows']}, real mismatches {len(st['real_mismatches'])}")
+        assert st["real_mismatches"] == []
+        assert np.array_equal(st["oracle"]["Q"], gq)
+        np.testing.assert_allclose(gs, st["oracle"]["scales"], rtol=1e-4)

@@ -163,7 +163,9 @@ def test_symmetric_grid_zero_group_rows_subset_and_forced_decisions():
     assert np.array_equal(sub["Q"], o["Q"][[4, 1]]) and np.array_equal(sub["scales"], o["scales"][[4, 1]])
     # flipping a recorded near-tie changes that decision and nothing before it
     row = next(i for i in range(6) if o["ties"][i])
-    key = o["ties"][row][0]
+    key, taken = o["ties"][row][0][:5], o["ties"][row][0][5]
     f = oc.jointq_refine(W, H, Q, s, z, 3, 16, grid="sym", n_pass=2, rows=[row], forced={(0,) + key: True})
     g = oc.jointq_refine(W, H, Q, s, z, 3, 16, grid="sym", n_pass=2, rows=[row], forced={(0,) + key: False})
     assert not (np.array_equal(f["Q"], g["Q"]) and np.array_equal(f["scales"], g["scales"]))
+    same = f if taken else g                      # forcing a decision the way it fell changes nothing
+    assert np.array_equal(same["Q"][0], o["Q"][row]) and np.allclose(same["scales"][0], o["scales"][row], rtol=1e-12)
