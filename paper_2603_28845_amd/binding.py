@@ -336,9 +336,10 @@ def onecomp_jointq_workspace_bytes(d_out: int, d_in: int, group_size: int) -> in
 def onecomp_jointq_refine(W: torch.Tensor, H: torch.Tensor, Q_codes: torch.Tensor, scales: torch.Tensor,
                           zeros: torch.Tensor, bits: int, group_size: int, grid: str = "minmax", lam: float = 0.0,
                           n_pass: int = 1, max_scans: int = 4, want_w_hat: bool = True,
-                          workspace: Optional[torch.Tensor] = None) -> dict:
+                          workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None) -> dict:
     """Refines Q_codes and scales IN PLACE; returns dict(Q_codes, scales, W_hat (or None), objective [2] = row
-    objective summed over the layer before and after, n_moves) of device tensors."""
+    objective summed over the layer before and after, n_moves) of device tensors.  out: optional dict with
+    preallocated "W_hat" (or None), "objective" (fp32[2]) and "n_moves" (int32[1])."""
     lib = load_library()
     d_out, d_in = W.shape
     dev = W.device
@@ -347,9 +348,12 @@ def onecomp_jointq_refine(W: torch.Tensor, H: torch.Tensor, Q_codes: torch.Tenso
     if workspace is None:
         workspace = torch.empty(max(onecomp_jointq_workspace_bytes(d_out, d_in, group_size), 256), dtype=torch.uint8,
                                 device=dev)
-    W_hat = torch.empty((d_out, d_in), dtype=torch.float32, device=dev) if want_w_hat else None
-    objective = torch.zeros(2, dtype=torch.float32, device=dev)
-    n_moves = torch.zeros(1, dtype=torch.int32, device=dev)
+    if out is not None:
+        W_hat, objective, n_moves = out.get("W_hat"), out["objective"], out["n_moves"]
+    else:
+        W_hat = torch.empty((d_out, d_in), dtype=torch.float32, device=dev) if want_w_hat else None
+        objective = torch.zeros(2, dtype=torch.float32, device=dev)
+        n_moves = torch.zeros(1, dtype=torch.int32, device=dev)
     rc = lib.onecomp_jointq_refine(_dev(W, "W"), _dtype_code(W), d_out, d_in, _dev(H, "H", torch.float32), float(lam),
                                    int(bits), int(group_size), _GRIDS[grid], int(n_pass), int(max_scans),
                                    _dev(Q_codes, "Q_codes", torch.uint8), _dev(scales, "scales", torch.float32),
