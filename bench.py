@@ -111,7 +111,7 @@ def cpu_baseline(cfg, synth, seconds_hint=20.0):
     }
 
 
-def bench_jointq(args, cfg, og, W, H, out):
+def bench_jointq(args, cfg, og, W, H, out, perm):
     """JointQ refinement (Sec. 4.2.2) of the sweep's result: args.jointq passes over the groups, four scans per
     visit, on the H of the timed steps.  The refinement works on copies; two timed calls after one warm-up."""
     import torch
@@ -124,7 +124,7 @@ def bench_jointq(args, cfg, og, W, H, out):
         e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
         e[0].record()
         r = og.onecomp_jointq_refine(W, H, Q, S, out["zeros"], cfg.bits, G, grid=base_grid, n_pass=args.jointq,
-                                     max_scans=4, workspace=ws, want_w_hat=False)
+                                     max_scans=4, workspace=ws, want_w_hat=False, perm=perm)
         e[1].record()
         torch.cuda.synchronize()
         if it > 0:
@@ -226,8 +226,7 @@ def main():
                     help="profiling aid: run only one call in the timed loop (the others run once to prepare its inputs)")
     ap.add_argument("--jointq", type=int, default=1,
                     help="passes of the JointQ refinement (Sec. 4.2.2) timed on the result of the last step and "
-                         "reported under 'jointq' (0 = skip; skipped for activation ordering); the headline value is "
-                         "unchanged")
+                         "reported under 'jointq' (0 = skip); the headline value is unchanged")
     ap.add_argument("--qep", action="store_true",
                     help="also time the layer with error propagation (Sec. 4.2.1): Gram of the perturbed activations, "
                          "cross-Gram, factor, corrected target, sweep of the corrected target; reported under 'qep', "
@@ -474,8 +473,8 @@ def main():
             "frac_of_bf16_peak": 2.0 * T * d_in * d_in / (v_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "gram_kernel_ms_for_the_same_tokens": acc_ms,
         }
-    if args.jointq > 0 and phase == "all" and not cfg.act_order and (cfg.group_size <= 128 or cfg.group_size % 128 == 0):
-        res["jointq"] = bench_jointq(args, cfg, og, W, H, out)
+    if args.jointq > 0 and phase == "all" and (cfg.group_size <= 128 or cfg.group_size % 128 == 0):
+        res["jointq"] = bench_jointq(args, cfg, og, W, H, out, perm if cfg.act_order else None)
     if args.qep:
         res["qep"] = bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out)
     if not args.no_cpu_baseline:

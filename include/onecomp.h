@@ -304,7 +304,7 @@ size_t onecomp_sensitivity_workspace_bytes(void);
 /*
  * JointQ refinement of a quantized layer (Sec. 4.2.2, Eq. (jointq); with lam > 0 Eq. (jointq_reg)): local search over
  * the integer codes, the scale of the touched group refit in the same move, started from a solution in the format
- * onecomp_quantize_layer returns (natural column order, perm == NULL).  Per output row the objective is
+ * onecomp_quantize_layer returns.  Per output row the objective is
  * f = (w - w^) (H + lam I) (w - w^)^T, w^ = s_g (q - z_g).
  *
  * Moves, order and stopping (the paper fixes only "one code changes a little, the group's scale is refit in the same
@@ -317,6 +317,10 @@ size_t onecomp_sensitivity_workspace_bytes(void);
  *
  *   W         device, d_out x d_in, row-major, fp32 or bf16: the weights the objective measures against.
  *   H         device fp32, d_in x d_in, symmetric (as onecomp_hessian_accumulate leaves it), read only.
+ *   perm      device int32[d_in] or NULL: the column order the start was quantized in (perm_out of
+ *             onecomp_hessian_factor).  As in onecomp_quantize_layer, groups are group_size consecutive columns of
+ *             that order, scales / zeros are indexed by group in that order, W, H, Q_codes and W_hat stay in the
+ *             original column order; "in order" below means that order.
  *   lam       >= 0, added to the diagonal of H (in the paper's terms 2 n lambda, since H = 2 X^T X).
  *   group_size  divides d_in; a multiple of 16 up to 128, or a multiple of 128 (up to d_in: one group per row).
  *   Q_codes, scales  device, in and out (d_out x d_in uint8, d_out x d_in/group_size fp32).
@@ -334,7 +338,8 @@ size_t onecomp_sensitivity_workspace_bytes(void);
  * group_size not a multiple of 16, or above 128 and not a multiple of 128), WORKSPACE.
  */
 onecomp_status onecomp_jointq_refine(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
-                                     const float* H, float lam, int bits, int group_size, onecomp_grid grid,
+                                     const float* H, const int32_t* perm, float lam, int bits, int group_size,
+                                     onecomp_grid grid,
                                      int n_pass, int max_scans, uint8_t* Q_codes, float* scales, const float* zeros,
                                      float* W_hat, float* objective, int32_t* n_moves,
                                      void* workspace, size_t workspace_bytes, void* hip_stream);

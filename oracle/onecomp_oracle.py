@@ -536,7 +536,7 @@ def row_objective(W, W_hat, A):
 
 
 def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=1, max_scans=4, rows=None,
-                  forced=None, tie_tol=0.0, g_tol=0.0, a_tol=0.0):
+                  forced=None, tie_tol=0.0, g_tol=0.0, a_tol=0.0, perm=None):
     """Local search of Sec. 4.2.2 on a solution in the per-group format of Eq. (4), rows independent.
 
     What the paper fixes: one move changes one integer code by a small amount inside the codebook, the scale of
@@ -556,8 +556,9 @@ def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=
         N = c' (b'^2 / c' - b^2 / c) = 2 d b g + g^2 + 2 s* g a_j - s*^2 D ,
     and the move is taken iff N > 0 and c' > 0 (the objective then falls by N / c').
 
-    W [d_out, d_in]; A symmetric [d_in, d_in]; Q codes, scales / zeros [d_out, n_g] as the sweep returns them
-    (natural column order).  forced: {(row, pass, t, scan, j, d): bool} overrides single decisions (rows numbered
+    W [d_out, d_in]; A symmetric [d_in, d_in]; Q codes, scales / zeros [d_out, n_g] as the sweep returns them.
+    perm: the column order of the sweep that produced the start (None = natural): groups, "in order" and the
+    column index j of a decision refer to that order, W, A, Q and W_hat are given and returned in the original one.  forced: {(row, pass, t, scan, j, d): bool} overrides single decisions (rows numbered
     within the subset); with tie_tol > 0 every decision with
     |N| <= tie_tol * M + 2 |b| (g_tol (|r| |A|)_j + a_tol |s*| (|u| |A_tt|)_j), M the sum of the absolute values of
     the terms N is built from, is listed in "ties" as (pass, t, scan, j, d, taken) (g_tol, a_tol: the rounding of a
@@ -568,6 +569,9 @@ def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=
     sel = np.arange(W.shape[0]) if rows is None else np.asarray(rows)
     W = W[sel]
     Q = np.array(np.asarray(Q)[sel], dtype=np.float64, copy=True)
+    if perm is not None:
+        perm = np.asarray(perm, dtype=np.int64)
+        W, Q, A = W[:, perm], Q[:, perm], A[np.ix_(perm, perm)]
     S = np.array(np.asarray(scales)[sel], dtype=np.float64, copy=True)
     Z = np.asarray(zeros, dtype=np.float64)[sel]
     n, d_in = W.shape
@@ -642,8 +646,12 @@ def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=
                     break
             S[:, t] = np.where(live, b / np.where(live, c, 1.0), s_old)
     What = dequant()
-    return {"Q": Q.astype(np.int64), "scales": S, "W_hat": What, "f0": f0, "f1": row_objective(W, What, A),
-            "moves": moves, "ties": ties}
+    f1 = row_objective(W, What, A)
+    if perm is not None:
+        Qo, Wo = np.empty_like(Q), np.empty_like(What)
+        Qo[:, perm], Wo[:, perm] = Q, What
+        Q, What = Qo, Wo
+    return {"Q": Q.astype(np.int64), "scales": S, "W_hat": What, "f0": f0, "f1": f1, "moves": moves, "ties": ties}
 
 
 # --------------------------------------------------------------------------

@@ -102,8 +102,8 @@ def load_library() -> ctypes.CDLL:
     lib.onecomp_rtn_sensitivity.restype = i32
     lib.onecomp_sensitivity_workspace_bytes.argtypes = []
     lib.onecomp_sensitivity_workspace_bytes.restype = sz
-    lib.onecomp_jointq_refine.argtypes = [vp, i32, i64, i64, vp, f32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp,
-                                          sz, vp]
+    lib.onecomp_jointq_refine.argtypes = [vp, i32, i64, i64, vp, vp, f32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
+                                          vp, sz, vp]
     lib.onecomp_jointq_refine.restype = i32
     lib.onecomp_jointq_workspace_bytes.argtypes = [i64, i64, i32]
     lib.onecomp_jointq_workspace_bytes.restype = sz
@@ -336,7 +336,8 @@ def onecomp_jointq_workspace_bytes(d_out: int, d_in: int, group_size: int) -> in
 def onecomp_jointq_refine(W: torch.Tensor, H: torch.Tensor, Q_codes: torch.Tensor, scales: torch.Tensor,
                           zeros: torch.Tensor, bits: int, group_size: int, grid: str = "minmax", lam: float = 0.0,
                           n_pass: int = 1, max_scans: int = 4, want_w_hat: bool = True,
-                          workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None) -> dict:
+                          workspace: Optional[torch.Tensor] = None, out: Optional[dict] = None,
+                          perm: Optional[torch.Tensor] = None) -> dict:
     """Refines Q_codes and scales IN PLACE; returns dict(Q_codes, scales, W_hat (or None), objective [2] = row
     objective summed over the layer before and after, n_moves) of device tensors.  out: optional dict with
     preallocated "W_hat" (or None), "objective" (fp32[2]) and "n_moves" (int32[1])."""
@@ -354,7 +355,10 @@ def onecomp_jointq_refine(W: torch.Tensor, H: torch.Tensor, Q_codes: torch.Tenso
         W_hat = torch.empty((d_out, d_in), dtype=torch.float32, device=dev) if want_w_hat else None
         objective = torch.zeros(2, dtype=torch.float32, device=dev)
         n_moves = torch.zeros(1, dtype=torch.int32, device=dev)
-    rc = lib.onecomp_jointq_refine(_dev(W, "W"), _dtype_code(W), d_out, d_in, _dev(H, "H", torch.float32), float(lam),
+    if perm is not None:
+        _dev(perm, "perm", torch.int32)
+    rc = lib.onecomp_jointq_refine(_dev(W, "W"), _dtype_code(W), d_out, d_in, _dev(H, "H", torch.float32), _ptr(perm),
+                                   float(lam),
                                    int(bits), int(group_size), _GRIDS[grid], int(n_pass), int(max_scans),
                                    _dev(Q_codes, "Q_codes", torch.uint8), _dev(scales, "scales", torch.float32),
                                    _dev(zeros, "zeros", torch.float32), _ptr(W_hat),

@@ -164,7 +164,8 @@ ONECOMP_API size_t onecomp_jointq_workspace_bytes(int64_t d_out, int64_t d_in, i
 }
 
 ONECOMP_API onecomp_status onecomp_jointq_refine(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
-                                                 const float* H, float lam, int bits, int group_size,
+                                                 const float* H, const int32_t* perm, float lam, int bits,
+                                                 int group_size,
                                                  onecomp_grid grid, int n_pass, int max_scans, uint8_t* Q_codes,
                                                  float* scales, const float* zeros, float* W_hat, float* objective,
                                                  int32_t* n_moves, void* workspace, size_t workspace_bytes,
@@ -182,7 +183,7 @@ ONECOMP_API onecomp_status onecomp_jointq_refine(const void* W, onecomp_dtype w_
     if (!aligned(W, 16) || !aligned(H, 16) || (W_hat && !aligned(W_hat, 16))) return ONECOMP_ERR_INVALID_ARG;
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < jointq_workspace_bytes(d_out, d_in, group_size))
         return ONECOMP_ERR_WORKSPACE;
-    return jointq_run(W, w_dtype, d_out, d_in, H, lam, bits, group_size, int(grid), n_pass, max_scans, Q_codes, scales,
+    return jointq_run(W, w_dtype, d_out, d_in, H, perm, lam, bits, group_size, int(grid), n_pass, max_scans, Q_codes, scales,
                       zeros, W_hat, objective, n_moves, workspace, static_cast<hipStream_t>(hip_stream));
 }
 

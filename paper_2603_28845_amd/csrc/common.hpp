@@ -120,8 +120,8 @@ onecomp_status sensitivity_run(const void* W, onecomp_dtype w_dtype, int64_t d_o
                                hipStream_t stream);
 
 size_t jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size);
-onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* A, float lam,
-                          int bits, int group_size, int grid, int n_pass, int max_scans, uint8_t* Q, float* scales,
+onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* A,
+                          const int32_t* perm, float lam, int bits, int group_size, int grid, int n_pass, int max_scans, uint8_t* Q, float* scales,
                           const float* zeros, float* W_hat, float* objective, int32_t* n_moves, void* workspace,
                           hipStream_t stream);
 

@@ -49,6 +49,9 @@ __device__ __forceinline__ float readlane_f(float x, int l) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
 }
 
+// original column of sweep position c (perm == nullptr: natural order)
+__device__ __forceinline__ int pcol(const int32_t* perm, int c) { return perm ? perm[c] : c; }
+
 __device__ __forceinline__ float load_w(const void* W, int bf16, int64_t i) {
     if (bf16) return __uint_as_float(uint32_t(static_cast<const uint16_t*>(W)[i]) << 16);
     return static_cast<const float*>(W)[i];
@@ -80,15 +83,18 @@ __global__ void jq_scalars_init_kernel(Scalars* sc, int n) {
 }
 
 // d_j = sqrt(A_jj + lam); 1 for a dead channel without regularizer (its row and column of A are zero)
-__global__ __launch_bounds__(256) void jq_diag_kernel(const float* __restrict__ A, int n, float lam, float* __restrict__ d) {
+__global__ __launch_bounds__(256) void jq_diag_kernel(const float* __restrict__ A, int n, float lam,
+                                                      const int32_t* __restrict__ perm, float* __restrict__ d) {
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= n) return;
-    const float x = A[int64_t(j) * n + j] + lam;
+    const int oj = pcol(perm, j);
+    const float x = A[int64_t(oj) * n + oj] + lam;
     d[j] = x > 0.f ? sqrtf(x) : 1.f;
 }
 
 // A~ = (A + lam I)_kj / (d_k d_j) * 2^14 as fp16 hi + lo; rows n .. n_rows-1 (padding of the k range) are zero
 __global__ __launch_bounds__(256) void jq_asplit_kernel(const float* __restrict__ A, int n, int n_rows, float lam,
+                                                        const int32_t* __restrict__ perm,
                                                         const float* __restrict__ d, uint16_t* __restrict__ Bh,
                                                         uint16_t* __restrict__ Bl) {
     const int k = blockIdx.y;
@@ -96,7 +102,14 @@ __global__ __launch_bounds__(256) void jq_asplit_kernel(const float* __restrict_
     if (j4 >= n) return;
     short4v h4 = {0, 0, 0, 0}, l4 = {0, 0, 0, 0};
     if (k < n) {
-        const float4v v = *reinterpret_cast<const float4v*>(A + int64_t(k) * n + j4);
+        float4v v;
+        if (perm) {
+            const float* rowp = A + int64_t(perm[k]) * n;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = rowp[perm[j4 + e]];
+        } else {
+            v = *reinterpret_cast<const float4v*>(A + int64_t(k) * n + j4);
+        }
         const float rk = 1.0f / d[k];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -116,16 +129,17 @@ __global__ __launch_bounds__(256) void jq_asplit_kernel(const float* __restrict_
 __global__ __launch_bounds__(256) void jq_residual_kernel(const void* __restrict__ W, int bf16, int d_out, int d_in,
                                                           const uint8_t* __restrict__ Q, const float* __restrict__ scales,
                                                           const float* __restrict__ zeros, int G, int n_g,
+                                                          const int32_t* __restrict__ perm,
                                                           const float* __restrict__ d, float* __restrict__ R,
                                                           Scalars* sc) {
     __shared__ uint32_t s_max;
     float mx = 0.f;
     for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x)
         for (int c = threadIdx.x; c < d_in; c += 256) {
-            const int64_t i = r * d_in + c;
+            const int64_t i = r * d_in + pcol(perm, c);
             const int g = c / G;
             const float x = load_w(W, bf16, i) - scales[r * n_g + g] * (float(Q[i]) - zeros[r * n_g + g]);
-            R[i] = x;
+            R[r * d_in + c] = x;
             mx = fmaxf(mx, fabsf(x) * d[c]);
         }
     block_max_bits(&sc->max_w_bits, mx, &s_max);
@@ -180,18 +194,19 @@ __global__ __launch_bounds__(256) void jq_fill0_kernel(float* __restrict__ p, in
 __global__ __launch_bounds__(256) void jq_objective_kernel(const void* __restrict__ W, int bf16, int d_out, int d_in,
                                                            const uint8_t* __restrict__ Q, const float* __restrict__ scales,
                                                            const float* __restrict__ zeros, int G, int n_g,
+                                                           const int32_t* __restrict__ perm,
                                                            const float* __restrict__ Gm, const float* __restrict__ d,
                                                            float* __restrict__ rowf, float* __restrict__ W_hat) {
     __shared__ float red[256];
     for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {
         float acc = 0.f;
         for (int c = threadIdx.x; c < d_in; c += 256) {
-            const int64_t i = r * d_in + c;
+            const int64_t i = r * d_in + pcol(perm, c);
             const int g = c / G;
             const float wh = scales[r * n_g + g] * (float(Q[i]) - zeros[r * n_g + g]);
             const float rr = load_w(W, bf16, i) - wh;
-            acc += rr * Gm[i] * d[c];
-            if (W_hat) W_hat[i] = wh;
+            acc += rr * Gm[r * d_in + c] * d[c];
+            if (W_hat) W_hat[i] = wh;   // i: the caller's column order
         }
         red[threadIdx.x] = acc;
         __syncthreads();
@@ -224,6 +239,7 @@ struct VisitArgs {
     const void* W; int w_bf16;
     int d_out, d_in, G, n_g, t;
     const float* A; float lam;
+    const int32_t* perm;       // sweep position -> original column of A, W and Q (nullptr: natural order)
     float qtop;
     uint8_t* Q; float* scales; const float* zeros;
     const float* Gm;           // column-normalized gradient of the whole objective (lam included)
@@ -259,7 +275,14 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     const int c0 = v.col0;
     for (int e = threadIdx.x * 4; e < G * G; e += 64 * JQ_ROWS * 4) {
         const int k = e / G, c = e - k * G;
-        float4v x = *reinterpret_cast<const float4v*>(v.A + int64_t(c0 + k) * v.d_in + c0 + c);
+        float4v x;
+        if (v.perm) {
+            const float* rowp = v.A + int64_t(v.perm[c0 + k]) * v.d_in;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[i] = rowp[v.perm[c0 + c + i]];
+        } else {
+            x = *reinterpret_cast<const float4v*>(v.A + int64_t(c0 + k) * v.d_in + c0 + c);
+        }
         if (k >= c && k < c + 4) x[k - c] += v.lam;
         *reinterpret_cast<float4v*>(sA + e) = x;
     }
@@ -283,8 +306,9 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     for (int c = 0; c < NC; ++c) {
         const int col = lane + 64 * c;
         has[c] = col < G;
-        const int64_t i = int64_t(row) * v.d_in + c0 + (has[c] ? col : 0);
-        q[c] = has[c] ? float(v.Q[i]) : z;
+        const int64_t i = int64_t(row) * v.d_in + c0 + (has[c] ? col : 0);     // sweep order: Gm, Am, P
+        const int64_t iq = int64_t(row) * v.d_in + pcol(v.perm, c0 + (has[c] ? col : 0));   // caller's order: Q
+        q[c] = has[c] ? float(v.Q[iq]) : z;
         u[c] = q[c] - z;
         u0[c] = u[c];
         a[c] = 0.f;
@@ -391,8 +415,7 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     for (int c = 0; c < NC; ++c) {
         if (!has[c]) continue;
         const int col = lane + 64 * c;
-        const int64_t i = int64_t(row) * v.d_in + c0 + col;
-        v.Q[i] = uint8_t(q[c]);
+        v.Q[int64_t(row) * v.d_in + pcol(v.perm, c0 + col)] = uint8_t(q[c]);
         // groups up to a block: change of the residual w - w^;  wider: change of the codes
         const float dr = WIDE ? u[c] - u0[c] : s_old * u0[c] - s_new * u[c];
         v.dR[int64_t(row) * v.ldr + col] = dr;
@@ -424,6 +447,7 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
 // start of a visit: U[row][c] = q - z over the group's columns (left operand of a = (A_gg + lam I) u); max |u d|
 __global__ __launch_bounds__(256) void jq_wide_begin_kernel(int d_out, int d_in, const uint8_t* __restrict__ Q,
                                                             const float* __restrict__ zeros, int n_g, int g, int G,
+                                                            const int32_t* __restrict__ perm,
                                                             const float* __restrict__ d, float* __restrict__ U,
                                                             Scalars* sc) {
     __shared__ uint32_t s_max;
@@ -433,7 +457,7 @@ __global__ __launch_bounds__(256) void jq_wide_begin_kernel(int d_out, int d_in,
         const float z = zeros[r * n_g + g];
         for (int c = threadIdx.x; c < G; c += 256) {
             const int64_t i = r * d_in + g0 + c;
-            const float u = float(Q[i]) - z;
+            const float u = float(Q[r * d_in + pcol(perm, g0 + c)]) - z;
             U[i] = u;
             mx = fmaxf(mx, fabsf(u) * d[g0 + c]);
         }
@@ -486,7 +510,8 @@ __global__ __launch_bounds__(256) void jq_scan_end_kernel(int d_out, int32_t* __
 // end of a visit: s = b / c; U <- change of the residual s_old u_old - s_new u_new; max |dR d|
 __global__ __launch_bounds__(256) void jq_wide_end_kernel(int d_out, int d_in, const uint8_t* __restrict__ Q,
                                                           float* __restrict__ scales, const float* __restrict__ zeros,
-                                                          int n_g, int g, int G, const float* __restrict__ d,
+                                                          int n_g, int g, int G, const int32_t* __restrict__ perm,
+                                                          const float* __restrict__ d,
                                                           const float* __restrict__ bc, float* __restrict__ U,
                                                           Scalars* sc) {
     __shared__ uint32_t s_max;
@@ -498,7 +523,7 @@ __global__ __launch_bounds__(256) void jq_wide_end_kernel(int d_out, int d_in, c
         const float s_new = c > 0.f ? b / c : s_old;
         for (int k = threadIdx.x; k < G; k += 256) {
             const int64_t i = r * d_in + g0 + k;
-            const float dr = s_old * U[i] - s_new * (float(Q[i]) - z);
+            const float dr = s_old * U[i] - s_new * (float(Q[r * d_in + pcol(perm, g0 + k)]) - z);
             U[i] = dr;
             mx = fmaxf(mx, fabsf(dr) * d[g0 + k]);
         }
@@ -564,8 +589,8 @@ size_t jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size) {
            align_up(size_t(d_in) * 4, 256) + align_up(size_t(d_out) * 4, 256) + 256 + wide;
 }
 
-onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* A, float lam,
-                          int bits, int group_size, int grid, int n_pass, int max_scans, uint8_t* Q, float* scales,
+onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* A,
+                          const int32_t* perm, float lam, int bits, int group_size, int grid, int n_pass, int max_scans, uint8_t* Q, float* scales,
                           const float* zeros, float* W_hat, float* objective, int32_t* n_moves, void* workspace,
                           hipStream_t stream) {
     const int G = group_size;
@@ -584,13 +609,14 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(jq_scalars_init_kernel, dim3(1), dim3(64), 0, stream, w.sc, 7);
     ONECOMP_CHECK_LAUNCH();
-    hipLaunchKernelGGL(jq_diag_kernel, dim3(unsigned(ceil_div(d_in, 256))), dim3(256), 0, stream, A, int(d_in), lam, w.d);
+    hipLaunchKernelGGL(jq_diag_kernel, dim3(unsigned(ceil_div(d_in, 256))), dim3(256), 0, stream, A, int(d_in), lam, perm,
+                       w.d);
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(jq_asplit_kernel, dim3(unsigned(ceil_div(d_in, 1024)), unsigned(d_in + 32)), dim3(256), 0, stream,
-                       A, int(d_in), int(d_in + 32), lam, w.d, w.Bh, w.Bl);
+                       A, int(d_in), int(d_in + 32), lam, perm, w.d, w.Bh, w.Bl);
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(jq_residual_kernel, rgrid, dim3(256), 0, stream, W, bf16, int(d_out), int(d_in), Q, scales, zeros,
-                       G, n_g, w.d, w.R, w.sc);
+                       G, n_g, perm, w.d, w.R, w.sc);
     ONECOMP_CHECK_LAUNCH();
     // left operand rows [row0, row0 + pad32(k_count)) of the D buffers from src[:, 0 .. k_count), columns c_first ..
     auto dsplit = [&](const float* src, int64_t ld_src, int k_count, int c_first, int row0, Scalars* sc,
@@ -615,7 +641,7 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
     ONECOMP_CHECK_LAUNCH();
     if ((st = update(0, int(d_in), 0, 0, int(d_in), w.sc)) != ONECOMP_OK) return st;
     hipLaunchKernelGGL(jq_objective_kernel, rgrid, dim3(256), 0, stream, W, bf16, int(d_out), int(d_in), Q, scales, zeros,
-                       G, n_g, w.Gm, w.d, w.rowf, static_cast<float*>(nullptr));
+                       G, n_g, perm, w.Gm, w.d, w.rowf, static_cast<float*>(nullptr));
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(jq_total_kernel, dim3(1), dim3(1024), 0, stream, w.rowf, int(d_out), objective);
     ONECOMP_CHECK_LAUNCH();
@@ -635,7 +661,7 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
     }
     VisitArgs v;
     v.W = W; v.w_bf16 = bf16; v.d_out = int(d_out); v.d_in = int(d_in); v.G = GB; v.n_g = n_g; v.t = 0;
-    v.A = A; v.lam = lam; v.qtop = qtop; v.Q = Q; v.scales = scales; v.zeros = zeros; v.Gm = w.Gm; v.d = w.d;
+    v.A = A; v.lam = lam; v.perm = perm; v.qtop = qtop; v.Q = Q; v.scales = scales; v.zeros = zeros; v.Gm = w.Gm; v.d = w.d;
     v.dR = w.dR; v.max_scans = max_scans; v.moves = n_moves;
     v.col0 = 0; v.Am = w.Am; v.P = w.P; v.bc = w.bc; v.flags = w.flags;
     const dim3 vgrid{unsigned(ceil_div(d_out, JQ_ROWS))};
@@ -681,7 +707,7 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
                 const int g0 = g * G;
                 v.t = g;
                 hipLaunchKernelGGL(jq_wide_begin_kernel, rgrid, dim3(256), 0, stream, int(d_out), int(d_in), Q, zeros, n_g, g,
-                                   G, w.d, w.R, w.sc + 5);
+                                   G, perm, w.d, w.R, w.sc + 5);
                 ONECOMP_CHECK_LAUNCH();
                 if ((st = dsplit(w.R + g0, d_in, G, g0, 0, w.sc + 5, w.sc + 6)) != ONECOMP_OK) return st;
                 hipLaunchKernelGGL(jq_fill0_kernel, fgrid, dim3(256), 0, stream, w.Am, d_out * d_in / 4);
@@ -717,14 +743,14 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
                     ONECOMP_CHECK_LAUNCH();
                 }
                 hipLaunchKernelGGL(jq_wide_end_kernel, rgrid, dim3(256), 0, stream, int(d_out), int(d_in), Q, scales, zeros,
-                                   n_g, g, G, w.d, w.bc, w.R, w.sc + 6);
+                                   n_g, g, G, perm, w.d, w.bc, w.R, w.sc + 6);
                 ONECOMP_CHECK_LAUNCH();
                 if ((st = dsplit(w.R + g0, d_in, G, g0, 0, w.sc + 6, w.sc + 5)) != ONECOMP_OK) return st;
                 if ((st = update(0, G, g0, 0, int(d_in), w.sc + 6)) != ONECOMP_OK) return st;
             }
     }
     hipLaunchKernelGGL(jq_objective_kernel, rgrid, dim3(256), 0, stream, W, bf16, int(d_out), int(d_in), Q, scales, zeros,
-                       G, n_g, w.Gm, w.d, w.rowf, W_hat);
+                       G, n_g, perm, w.Gm, w.d, w.rowf, W_hat);
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(jq_total_kernel, dim3(1), dim3(1024), 0, stream, w.rowf, int(d_out), objective + 1);
     ONECOMP_CHECK_LAUNCH();

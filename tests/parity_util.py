@@ -125,23 +125,27 @@ JQ_G_TOL = 2e-6     # ... plus this fraction of sum |r_k| |A_kj|, the rounding o
 JQ_A_TOL = 2e-6     # ... and, for groups wider than a block, of s* sum |u_k| |A_kj|: there a = A_gg u is carried along too
 
 
-def _jq_prefix(o, i, gq, gs, G, n_g):
-    """Number of leading groups (visit order of one pass) in which oracle row i equals the GPU row."""
+def _jq_prefix(o, i, gq, gs, G, n_g, pv=None):
+    """Number of leading groups (visit order of one pass) in which oracle row i equals the GPU row; pv maps sweep
+    positions to columns."""
+    oq = o["Q"][i] if pv is None else o["Q"][i][pv]
+    gq = gq if pv is None else gq[pv]
     for t in range(n_g):
-        same = (np.array_equal(o["Q"][i, t * G:(t + 1) * G], gq[t * G:(t + 1) * G])
+        same = (np.array_equal(oq[t * G:(t + 1) * G], gq[t * G:(t + 1) * G])
                 and abs(o["scales"][i, t] - gs[t]) <= 1e-4 * abs(o["scales"][i, t]))
         if not same:
             return t
     return n_g
 
 
-def _jq_first_column(o, i, gq):
-    bad = np.nonzero(o["Q"][i] != gq)[0]
+def _jq_first_column(o, i, gq, pv):
+    """First sweep position at which the codes differ, or -1."""
+    bad = np.nonzero(o["Q"][i][pv] != gq[pv])[0]
     return int(bad[0]) if len(bad) else -1
 
 
 def compare_jointq(gpu_Q, gpu_S, W, A, Q0, S0, Z, bits, G, grid="asym", n_pass=1, max_scans=4, rows=None,
-                   max_flips=6, max_tries=24, wide=False):
+                   max_flips=6, max_tries=24, wide=False, perm=None):
     """GPU result of onecomp_jointq_refine against the oracle's local search from the same start.
 
     A row must equal the oracle's exactly in its codes (scales to 1e-4), or become equal once decisions the oracle
@@ -160,7 +164,8 @@ def compare_jointq(gpu_Q, gpu_S, W, A, Q0, S0, Z, bits, G, grid="asym", n_pass=1
     Q0 = np.asarray(Q0)
     n_g = W.shape[1] // G
     kw = dict(bits=bits, group_size=G, grid=grid, n_pass=n_pass, max_scans=max_scans, tie_tol=JQ_TIE_TOL,
-              g_tol=JQ_G_TOL, a_tol=JQ_A_TOL if wide else 0.0)
+              g_tol=JQ_G_TOL, a_tol=JQ_A_TOL if wide else 0.0, perm=perm)
+    pv = np.arange(W.shape[1]) if perm is None else np.asarray(perm, dtype=np.int64)   # sweep position -> column
     o = oc.jointq_refine(W, A, Q0, S0, Z, rows=rows, **kw)
     res = {k: (np.array(v, copy=True) if isinstance(v, np.ndarray) else v) for k, v in o.items()}
     clean, flipped, flips, real = 0, 0, 0, []
@@ -170,23 +175,23 @@ def compare_jointq(gpu_Q, gpu_S, W, A, Q0, S0, Z, bits, G, grid="asym", n_pass=1
         return oc.jointq_refine(W, A, Q0, S0, Z, rows=rows[i:i + 1], forced=forced, **kw)
 
     for i in range(len(rows)):
-        if _jq_prefix(o, i, gq[i], gs[i], G, n_g) == n_g:
+        if _jq_prefix(o, i, gq[i], gs[i], G, n_g, pv) == n_g:
             clean += 1
             continue
         forced, ok = {}, False
         cur = run1(i, forced)
         for _ in range(max_flips if not single else 4 * max_flips):
-            pre = _jq_prefix(cur, 0, gq[i], gs[i], G, n_g)
+            pre = _jq_prefix(cur, 0, gq[i], gs[i], G, n_g, pv)
             if pre == n_g:
                 ok = True
                 break
             listed = {k[:5]: k[5] for k in cur["ties"][0]}
             if single:
-                j = _jq_first_column(cur, 0, gq[i])
+                j = _jq_first_column(cur, 0, gq[i], pv)
                 if j < 0:
                     break                        # codes equal, a scale differs: not a toss-up
                 t, jl = j // G, j % G
-                want = int(gq[i, j] - Q0[rows[i], j])          # the GPU's decision at this column
+                want = int(gq[i, pv[j]] - Q0[rows[i], pv[j]])   # the GPU's decision at this sweep position
                 f2 = dict(forced)
                 for d in (1, -1):
                     key = (0, t, 0, jl, d)
@@ -204,14 +209,14 @@ def compare_jointq(gpu_Q, gpu_S, W, A, Q0, S0, Z, bits, G, grid="asym", n_pass=1
                 f2 = dict(forced)
                 f2[(0,) + k] = not listed[k]
                 trial = run1(i, f2)
-                score = (_jq_prefix(trial, 0, gq[i], gs[i], G, n_g), -int((trial["Q"][0] != gq[i]).sum()))
+                score = (_jq_prefix(trial, 0, gq[i], gs[i], G, n_g, pv), -int((trial["Q"][0] != gq[i]).sum()))
                 if score > (pre, -ham) and (best is None or score > best[0]):
                     best = (score, f2, trial)
             if best is None:
                 break
             _, forced, cur = best
             flips += 1
-        ok = ok or _jq_prefix(cur, 0, gq[i], gs[i], G, n_g) == n_g
+        ok = ok or _jq_prefix(cur, 0, gq[i], gs[i], G, n_g, pv) == n_g
         if ok:
             flipped += 1
             for k in ("Q", "scales", "W_hat", "f0", "f1", "moves"):

@@ -281,7 +281,7 @@ def test_jointq_argument_checks(lib):
 
     def call(W=P, dt=1, d_out=64, d_in=256, H=P, lam=0.0, bits=4, G=128, grid=0, n_pass=1, scans=4, Q=P, s=P, z=P,
              wh=NULL, obj=P, mv=P, ws=P, wsb=big):
-        return f(W, dt, d_out, d_in, H, lam, bits, G, grid, n_pass, scans, Q, s, z, wh, obj, mv, ws, wsb, NULL)
+        return f(W, dt, d_out, d_in, H, NULL, lam, bits, G, grid, n_pass, scans, Q, s, z, wh, obj, mv, ws, wsb, NULL)
 
     assert call(dt=3) == UNSUPPORTED
     assert call(grid=7) == UNSUPPORTED

@@ -16,8 +16,9 @@ def _announce(msg):
     print(f"[case] {msg}", flush=True)
 
 
-def _start(d_out, d_in, bits, G, seed, dtype=torch.float32, grid="asym", start="rtn"):
-    """Synthetic layer, its Gram matrix (fp32 values, shared by both sides) and a start from the oracle."""
+def _start(d_out, d_in, bits, G, seed, dtype=torch.float32, grid="asym", start="rtn", act=False):
+    """Synthetic layer, its Gram matrix (fp32 values, shared by both sides) and a start from the oracle (act: the
+    sweep with activation ordering; the column order is returned as the last element)."""
     cfg = synth.scaled(synth.CONFIGS["c2"], d_out=d_out, d_in=d_in, n_tokens=2 * d_in + 13, seed=seed, dtype=dtype,
                        n_outlier=max(1, d_in // 100))
     W = synth.make_weight(cfg, DEV)
@@ -27,19 +28,22 @@ def _start(d_out, d_in, bits, G, seed, dtype=torch.float32, grid="asym", start="
     if start == "rtn":
         Q0, S0, Z0, _ = oc.rtn_quantize(Wd, bits, G, grid)
     else:
-        f = oc.hessian_factor(H32.astype(np.float64), 0.01)
-        out = oc.quantize_layer(Wd, f["U"], bits, G, grid=grid)
+        f = oc.hessian_factor(H32.astype(np.float64), 0.01, act_order=act)
+        out = oc.quantize_layer(Wd, f["U"], bits, G, grid=grid, perm=f["perm"] if act else None)
         Q0, S0, Z0 = out["Q"], out["scales"], out["zeros"]
+        if act:
+            return W, Wd, H32, Q0, S0, Z0, f["perm"]
     return W, Wd, H32, Q0, S0, Z0
 
 
-def _run(W, Wd, H32, Q0, S0, Z0, bits, G, grid="asym", lam=0.0, n_pass=1, max_scans=4, max_bad_rows=None):
+def _run(W, Wd, H32, Q0, S0, Z0, bits, G, grid="asym", lam=0.0, n_pass=1, max_scans=4, max_bad_rows=None, perm=None):
     Q = torch.from_numpy(Q0.astype(np.uint8)).to(DEV)
     S = torch.from_numpy(S0.astype(np.float32)).to(DEV)
     Z = torch.from_numpy(Z0.astype(np.float32)).to(DEV)
     H = torch.from_numpy(H32).to(DEV)
+    pt = None if perm is None else torch.from_numpy(perm.astype(np.int32)).to(DEV)
     out = og.onecomp_jointq_refine(W, H, Q, S, Z, bits, G, grid="symmetric" if grid == "sym" else "minmax", lam=lam,
-                                   n_pass=n_pass, max_scans=max_scans)
+                                   n_pass=n_pass, max_scans=max_scans, perm=pt)
     torch.cuda.synchronize()
     gq = out["Q_codes"].cpu().numpy()
     gs = out["scales"].cpu().numpy()
@@ -50,10 +54,11 @@ def _run(W, Wd, H32, Q0, S0, Z0, bits, G, grid="asym", lam=0.0, n_pass=1, max_sc
     S0f = S0.astype(np.float32).astype(np.float64)      # the start as the GPU received it
     qtop = oc.code_range_top(bits, grid)
     assert gq.max() <= qtop
-    deq = (np.repeat(gs, G, axis=1) * (gq.astype(np.float32) - np.repeat(Z0.astype(np.float32), G, axis=1)))
+    grp = (np.arange(d_in) if perm is None else np.argsort(perm)) // G       # group of every original column
+    deq = gs[:, grp] * (gq.astype(np.float32) - Z0.astype(np.float32)[:, grp])
     assert np.array_equal(deq.astype(np.float32), wh)
     st = compare_jointq(gq, gs, Wd, A, Q0, S0f, Z0, bits, G, grid=grid, n_pass=n_pass, max_scans=max_scans,
-                        wide=G > 128)
+                        wide=G > 128, perm=perm)
     _announce(f"   clean rows {st['clean_rows']}/{d_out}, rows equal after {st['flips']} forced toss-ups: "
               f"{st['flipped_rows']}, real mismatches {len(st['real_mismatches'])}, moves {int(out['n_moves'].item())}")
     assert st["real_mismatches"] == []
@@ -112,6 +117,22 @@ def test_jointq_wide_groups(bits, G, d_out, d_in, dtype, grid, start, n_pass, sc
     _announce(f"jointq wide b{bits} g{G} {d_out}x{d_in} {dtype} {grid} start={start} passes={n_pass} scans={scans} lam={lam}")
     W, Wd, H32, Q0, S0, Z0 = _start(d_out, d_in, bits, G, seed=300 + bits + G % 7, dtype=dtype, grid=grid, start=start)
     _run(W, Wd, H32, Q0, S0, Z0, bits, G, grid=grid, lam=lam, n_pass=n_pass, max_scans=scans)
+
+
+@pytest.mark.parametrize("bits,G,d_out,d_in,dtype,grid,n_pass,scans", [
+    (4, 128, 48, 512, torch.bfloat16, "asym", 1, 4),
+    (3, 64, 33, 384, torch.float32, "sym", 2, 2),
+    (4, 256, 24, 768, torch.bfloat16, "asym", 1, 3),       # wide groups in sweep order
+    (3, 32, 40, 256, torch.float32, "asym", 1, 1),         # one scan: decisions replayed exactly
+])
+def test_jointq_after_activation_ordering(bits, G, d_out, d_in, dtype, grid, n_pass, scans):
+    """Start from the sweep with activation ordering: groups, scan order, scales and zeros follow the sweep's column
+    order, W, H and the codes stay in the original one."""
+    _announce(f"jointq act-order b{bits} g{G} {d_out}x{d_in} {dtype} {grid} passes={n_pass} scans={scans}")
+    W, Wd, H32, Q0, S0, Z0, perm = _start(d_out, d_in, bits, G, seed=400 + bits + G % 11, dtype=dtype, grid=grid,
+                                          start="gptq", act=True)
+    assert not np.array_equal(perm, np.arange(d_in))
+    _run(W, Wd, H32, Q0, S0, Z0, bits, G, grid=grid, n_pass=n_pass, max_scans=scans, perm=perm)
 
 
 def test_jointq_degenerate_rows_and_zero_passes():
