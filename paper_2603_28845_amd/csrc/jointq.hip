@@ -92,8 +92,9 @@ __global__ __launch_bounds__(256) void jq_diag_kernel(const float* __restrict__ 
     d[j] = x > 0.f ? sqrtf(x) : 1.f;
 }
 
-// A~ = (A + lam I)_kj / (d_k d_j) * 2^14 as fp16 hi + lo; rows n .. n_rows-1 (padding of the k range) are zero
-__global__ __launch_bounds__(256) void jq_asplit_kernel(const float* __restrict__ A, int n, int n_rows, float lam,
+// A~ = (A + lam I)_kj / (d_k d_j) * 2^14 as fp16 hi + lo; the rows of the grid behind row n - 1 (padding of the k
+// range) are zero
+__global__ __launch_bounds__(256) void jq_asplit_kernel(const float* __restrict__ A, int n, float lam,
                                                         const int32_t* __restrict__ perm,
                                                         const float* __restrict__ d, uint16_t* __restrict__ Bh,
                                                         uint16_t* __restrict__ Bl) {
@@ -236,7 +237,6 @@ __global__ __launch_bounds__(1024) void jq_total_kernel(const float* __restrict_
 __global__ void jq_zero_kernel(int32_t* p) { p[0] = 0; }
 
 struct VisitArgs {
-    const void* W; int w_bf16;
     int d_out, d_in, G, n_g, t;
     const float* A; float lam;
     const int32_t* perm;       // sweep position -> original column of A, W and Q (nullptr: natural order)
@@ -613,7 +613,7 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
                        w.d);
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(jq_asplit_kernel, dim3(unsigned(ceil_div(d_in, 1024)), unsigned(d_in + 32)), dim3(256), 0, stream,
-                       A, int(d_in), int(d_in + 32), lam, perm, w.d, w.Bh, w.Bl);
+                       A, int(d_in), lam, perm, w.d, w.Bh, w.Bl);
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(jq_residual_kernel, rgrid, dim3(256), 0, stream, W, bf16, int(d_out), int(d_in), Q, scales, zeros,
                        G, n_g, perm, w.d, w.R, w.sc);
@@ -660,7 +660,7 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
             return ONECOMP_ERR_HIP;
     }
     VisitArgs v;
-    v.W = W; v.w_bf16 = bf16; v.d_out = int(d_out); v.d_in = int(d_in); v.G = GB; v.n_g = n_g; v.t = 0;
+    v.d_out = int(d_out); v.d_in = int(d_in); v.G = GB; v.n_g = n_g; v.t = 0;
     v.A = A; v.lam = lam; v.perm = perm; v.qtop = qtop; v.Q = Q; v.scales = scales; v.zeros = zeros; v.Gm = w.Gm; v.d = w.d;
     v.dR = w.dR; v.max_scans = max_scans; v.moves = n_moves;
     v.col0 = 0; v.Am = w.Am; v.P = w.P; v.bc = w.bc; v.flags = w.flags;
