@@ -161,14 +161,17 @@ struct PanelArgs {
     int mse;                // scale search: the group's range is shrunk by 1 - i / 100, i < 80; least squared error wins
 };
 
-// Scale search of one group ("mse" option of Sec. 4.2).  partial(s, z, 1 / s) returns the sum of (w - w^)^2 over
+// Scale search of one group ("mse" option of Sec. 4.2).  partial(z, 1 / s) returns the sum of ((w - w^) / s)^2 over
 // this lane's values of the group on the grid (s, z) (mse_term per value); reduce(x) sums x over the lanes that share
 // the group.  Candidate i takes (s, z) by the grid's rule from the range shrunk by p_i = 1 - i / 100; the first
 // smallest error wins, candidate 0 is the plain rule.  All lanes of the group end with the same (s, z).
 constexpr int MSE_CANDIDATES = 80;
-__device__ __forceinline__ float mse_term(float v, float si, float zi, float rsi, float qmax) {
-    const float q = fminf(fmaxf(rintf(v * rsi) + zi, 0.f), qmax);
-    const float d = v - si * (q - zi);
+// one value's squared error in units of the scale: t = v / s + z, ((t - clamp(rne(t), 0, qmax)))^2; the caller
+// multiplies the sum by s^2.  (rne(v / s) + z and rne(v / s + z) agree except at exact ties, where both choices give
+// the same error.)
+__device__ __forceinline__ float mse_term(float v, float zi, float rsi, float qmax) {
+    const float t = fmaf(v, rsi, zi);
+    const float d = t - __builtin_amdgcn_fmed3f(rintf(t), 0.f, qmax);
     return d * d;
 }
 template <typename P, typename R>
@@ -189,7 +192,7 @@ __device__ __forceinline__ void mse_search(const float mn, const float mx, const
             if (si == 0.f) si = 1.f;
             zi = fminf(fmaxf(rintf(-lo / si), 0.f), qmax);
         }
-        const float err = reduce(partial(si, zi, 1.0f / si));
+        const float err = si * si * reduce(partial(zi, 1.0f / si));
         if (err < best) { best = err; s = si; z = zi; }
     }
 }
@@ -470,25 +473,25 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                                         for (int k = 0; k < 32; ++k) gv[k] = gp[(4 * k) & (G - 1)];
                                         const int n8 = G >> 5;   // batches of 8 values: 1, 2 or 4
                                         mse_search(mn, mx, qmax, a.qs,
-                                                   [&](float si, float zi, float rsi) __attribute__((always_inline)) {
+                                                   [&](float zi, float rsi) __attribute__((always_inline)) {
                                                        float e0 = 0.f, e1 = 0.f;
 #pragma unroll
                                                        for (int k = 0; k < 8; k += 2) {
-                                                           e0 += mse_term(gv[k], si, zi, rsi, qmax);
-                                                           e1 += mse_term(gv[k + 1], si, zi, rsi, qmax);
+                                                           e0 += mse_term(gv[k], zi, rsi, qmax);
+                                                           e1 += mse_term(gv[k + 1], zi, rsi, qmax);
                                                        }
                                                        if (n8 > 1) {
 #pragma unroll
                                                            for (int k = 8; k < 16; k += 2) {
-                                                               e0 += mse_term(gv[k], si, zi, rsi, qmax);
-                                                               e1 += mse_term(gv[k + 1], si, zi, rsi, qmax);
+                                                               e0 += mse_term(gv[k], zi, rsi, qmax);
+                                                               e1 += mse_term(gv[k + 1], zi, rsi, qmax);
                                                            }
                                                        }
                                                        if (n8 > 2) {
 #pragma unroll
                                                            for (int k = 16; k < 32; k += 2) {
-                                                               e0 += mse_term(gv[k], si, zi, rsi, qmax);
-                                                               e1 += mse_term(gv[k + 1], si, zi, rsi, qmax);
+                                                               e0 += mse_term(gv[k], zi, rsi, qmax);
+                                                               e1 += mse_term(gv[k + 1], zi, rsi, qmax);
                                                            }
                                                        }
                                                        return e0 + e1;
@@ -1014,9 +1017,9 @@ __global__ __launch_bounds__(256) void group_params_kernel(const T* __restrict__
         }
         if (mse) {   // uniform; the row's values are re-read from cache for every candidate
             mse_search(mn, mx, qmax, qs,
-                       [&](float si, float zi, float rsi) __attribute__((always_inline)) {
+                       [&](float zi, float rsi) __attribute__((always_inline)) {
                            float e = 0.f;
-                           for (int c = threadIdx.x; c < G; c += 256) e += mse_term(to_f32<T>(row[c]), si, zi, rsi, qmax);
+                           for (int c = threadIdx.x; c < G; c += 256) e += mse_term(to_f32<T>(row[c]), zi, rsi, qmax);
                            return e;
                        },
                        [&](float x) __attribute__((always_inline)) {   // workgroup sum, the same value in every thread
