@@ -88,6 +88,13 @@ onecomp_status split_update(float* C, int64_t d_out, int64_t d_in, const uint16_
                             const uint16_t* Bh, const uint16_t* Bl, const Scalars* sc, int ek, int K, int u0, int c0,
                             int c1, hipStream_t stream);
 int64_t split_update_ld(int64_t d_out);
+// Left operand of split_update from a row-major fp32 matrix: rows [0, k_count rounded up to 32) of Dh / Dl receive
+// (src[:, k] d[k] f_d)^T as fp16 hi + lo (d == nullptr: 1; zero behind k_count), with f_d the power of two that puts
+// the maximum found in sc->max_w_bits (left there by the producer of src: max |src d|) into [2^12, 2^13).  Expects
+// sc->f_u (power of two, the right operand's scale); leaves f_d, f_all, f_inv in sc; clears other->max_w_bits if
+// other is given.
+onecomp_status split_left_operand(const float* src, int64_t ld_src, int64_t d_out, int k_count, const float* d,
+                                  Scalars* sc, Scalars* other, uint16_t* Dh, uint16_t* Dl, hipStream_t stream);
 
 // ---- entry points implemented in the kernel files -------------------------------------------
 size_t gram_workspace_bytes(int64_t d_in);

@@ -146,10 +146,11 @@ __global__ __launch_bounds__(256) void jq_residual_kernel(const void* __restrict
     block_max_bits(&sc->max_w_bits, mx, &s_max);
 }
 
-// Left operand of a split product: Dt[k][row] = src[row][k] * d[k] * f_d as fp16 hi + lo for k < k_count, zero for
-// k_count <= k < k_pad and for the padding rows up to ldD.  f_d = 2^(13 - exponent of the maximum in sc), so that
-// the largest value lands in [2^12, 2^13); thread 0 of the grid leaves f_d, f_all, f_inv in sc for the product and
-// clears the maximum of `other` (the slot the next producer accumulates into).  64 x 64 tiles through LDS.
+// Left operand of a split product: Dt[k][row] = src[row][k] * d[k] * f_d (d == nullptr: 1) as fp16 hi + lo for
+// k < k_count, zero for k_count <= k < k_pad and for the padding rows up to ldD.  f_d = 2^(13 - exponent of the
+// maximum in sc), so that the largest value lands in [2^12, 2^13); thread 0 of the grid leaves f_d, f_all = f_d f_u
+// and f_inv in sc for the product (f_u, a power of two, is already there) and clears the maximum of `other` (the
+// slot the next producer accumulates into).  64 x 64 tiles through LDS.
 __global__ __launch_bounds__(256) void jq_dsplit_kernel(const float* __restrict__ src, int64_t ld_src, int d_out,
                                                         int k_count, int k_pad, const float* __restrict__ d,
                                                         Scalars* sc, Scalars* other, uint16_t* __restrict__ Dh,
@@ -161,16 +162,17 @@ __global__ __launch_bounds__(256) void jq_dsplit_kernel(const float* __restrict_
     const int sd = max(-60, min(60, 13 - e));
     const float f_d = ldexpf(1.f, sd);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-        sc->f_d = f_d; sc->f_u = JQ_FU;
-        sc->f_all = ldexpf(1.f, sd + 14);
-        sc->f_inv = ldexpf(1.f, -(sd + 14));
+        const float f_u = sc->f_u;
+        sc->f_d = f_d;
+        sc->f_all = f_d * f_u;
+        sc->f_inv = 1.0f / (f_d * f_u);
         if (other) other->max_w_bits = 0u;
     }
     const int k0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     for (int rr = ty; rr < 64; rr += 4) {
         const int r = r0 + rr, k = k0 + tx;
-        tile[rr][tx] = (r < d_out && k < k_count) ? src[int64_t(r) * ld_src + k] * d[k] * f_d : 0.f;
+        tile[rr][tx] = (r < d_out && k < k_count) ? src[int64_t(r) * ld_src + k] * (d ? d[k] : 1.0f) * f_d : 0.f;
     }
     __syncthreads();
     for (int kk = ty; kk < 64; kk += 4) {
@@ -579,6 +581,16 @@ JqWs carve(void* ws, int64_t d_out, int64_t d_in, bool wide) {
 }
 
 }  // namespace
+
+onecomp_status split_left_operand(const float* src, int64_t ld_src, int64_t d_out, int k_count, const float* d,
+                                  Scalars* sc, Scalars* other, uint16_t* Dh, uint16_t* Dl, hipStream_t stream) {
+    const int64_t ldD = split_update_ld(d_out);
+    const int k_pad = (k_count + 31) / 32 * 32;
+    hipLaunchKernelGGL(jq_dsplit_kernel, dim3(unsigned(ceil_div(k_pad, 64)), unsigned(ceil_div(ldD, 64))), dim3(256), 0,
+                       stream, src, ld_src, int(d_out), k_count, k_pad, d, sc, other, Dh, Dl, ldD);
+    ONECOMP_CHECK_LAUNCH();
+    return ONECOMP_OK;
+}
 
 size_t jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size) {
     const int64_t ldD = split_update_ld(d_out);
