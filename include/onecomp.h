@@ -268,15 +268,17 @@ onecomp_status onecomp_crossgram_accumulate(const void* X_hat, const void* X, on
  *   alpha    propagation strength in [0, 1].
  *   W_star   [d_out x d_in] fp32, original column order, out; must not alias W.
  *   workspace device scratch, >= onecomp_qep_workspace_bytes(d_out, d_in), 256-byte aligned.
- * Arithmetic: fp32 throughout (three GEMMs with fp32 products).  G - H cancels the leading digits of two Gram
- * matrices, so the correction W* - W carries a relative error of about 1e-6 |X| / |X - X_hat|.
+ * Arithmetic: three products accumulated in fp32 from operands split into fp16 hi + lo halves (22 significant bits
+ * each; every factor in the scaling of the correlation matrix, H_kj / sqrt(H_kk H_jj), so that fp16's range
+ * suffices).  G - H cancels the leading digits of two Gram matrices, so the correction W* - W carries a relative
+ * error of about 1e-6 |X| / |X - X_hat|.
  */
 onecomp_status onecomp_qep_target(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
                                   const float* G, const float* H, const float* U, const int32_t* perm,
                                   float alpha, float* W_star,
                                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Scratch size for onecomp_qep_target (0 if the arguments are invalid): about 4 d_in^2 + 12 d_out d_in bytes. */
+/* Scratch size for onecomp_qep_target (0 if the arguments are invalid): about 8 d_in^2 + 16 d_out d_in bytes. */
 size_t onecomp_qep_workspace_bytes(int64_t d_out, int64_t d_in);
 
 /*

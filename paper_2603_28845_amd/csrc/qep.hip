@@ -5,144 +5,11 @@
 //     W*_p = W_p + alpha ((W_p Cp^T) U^T) U,     Cp = (G - H)[perm][:, perm],  W_p = W[:, perm],
 // and W* is W*_p with its columns put back into the original order.
 //
-// gfx950: three fp32 GEMMs on v_mfma_f32_32x32x2_f32 (fp32 products and sums: the correction is a difference of
-// nearly equal Gram matrices times an inverse, bf16 operands would lose it).  128 x 128 tile per workgroup,
-// 4 waves in 2 x 2 (64 x 64 each), operands staged through registers into double-buffered LDS, K step 16.
-// The triangular structure of U halves the second and third product (k ranges cut per column tile).
+// gfx950: the three products run on the fp16 MFMAs with fp32 accuracy (operands split hi + lo, three products each,
+// fp32 accumulation: split_update); see qep_target_run for the scaling that makes fp16's range suffice.
 #include "common.hpp"
-#include "sgemm.hpp"
 
 namespace onecomp {
-namespace {
-
-constexpr int ST = 128;    // tile side
-constexpr int SK = 16;     // K per LDS stage
-constexpr int SPA = SK + 1;      // pitch of a k-contiguous tile (rows x SK)
-constexpr int SPB = ST + 4;      // pitch of a k-major tile (SK x cols)
-constexpr int SSB = ST * SPA;    // >= SK * SPB
-
-template <bool bt>
-__global__ __launch_bounds__(256, 2) void sgemm_kernel(SgemmArgs g) {
-    __shared__ float sA[2][ST * SPA];
-    __shared__ float sB[2][SSB];
-    const int tm = blockIdx.y, tn = blockIdx.x;
-    const int m0 = tm * ST, n0 = tn * ST;
-    int k_lo = 0, k_hi = g.k;
-    if (g.flags & S_BUPPER_T) k_lo = n0;                       // B^T[n][k] = 0 for k < n
-    if (g.flags & S_BUPPER) k_hi = min(g.k, n0 + ST);          // B[k][n] = 0 for k > n
-    k_lo = (k_lo / SK) * SK;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wr = wave >> 1, wc = wave & 1;
-    // loaders: k-contiguous tile (rows x SK): row = tid / 2, 8 floats at k = (tid % 2) * 8
-    //          k-major B tile (SK x cols): krow = tid / 16, 8 floats at col (tid % 16) * 8
-    const int a_row = tid >> 1, a_k = (tid & 1) * 8;
-    const int b_kr = tid >> 4, b_c = (tid & 15) * 8;
-    float4v ra[2], rb[2];
-    const float4v zero = {0.f, 0.f, 0.f, 0.f};
-    auto gload = [&](int k0) __attribute__((always_inline)) {
-        {
-            const int r = m0 + a_row, kk = k0 + a_k;
-            const bool ok = (r < g.m) && (kk < k_hi);
-            const float4v* p = reinterpret_cast<const float4v*>(g.A + int64_t(r) * g.lda + kk);
-            ra[0] = ok ? p[0] : zero;
-            ra[1] = ok ? p[1] : zero;
-        }
-        if (bt) {
-            const int r = n0 + a_row, kk = k0 + a_k;
-            const bool ok = (r < g.n) && (kk < k_hi);
-            const float4v* p = reinterpret_cast<const float4v*>(g.B + int64_t(r) * g.ldb + kk);
-            rb[0] = ok ? p[0] : zero;
-            rb[1] = ok ? p[1] : zero;
-        } else {
-            const int kk = k0 + b_kr, c = n0 + b_c;
-            const bool ok = (kk < k_hi) && (c < g.n);
-            const float4v* p = reinterpret_cast<const float4v*>(g.B + int64_t(kk) * g.ldb + c);
-            rb[0] = ok ? p[0] : zero;
-            rb[1] = ok ? p[1] : zero;
-        }
-    };
-    auto lstore = [&](int st) __attribute__((always_inline)) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sA[st][a_row * SPA + a_k + e] = ra[e / 4][e % 4];
-        if (bt) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) sB[st][a_row * SPA + a_k + e] = rb[e / 4][e % 4];
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) sB[st][b_kr * SPB + b_c + e] = rb[e / 4][e % 4];
-        }
-    };
-
-    float16v acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    // MFMA operand layouts (lane l): A[i][k]: i = l % 32, k = l / 32;  B[k][j]: k = l / 32, j = l % 32
-    const int l32 = lane & 31, lk = lane >> 5;
-    if (k_lo < k_hi) {
-        gload(k_lo);
-        lstore(0);
-    }
-    __syncthreads();
-    int st = 0;
-    for (int k0 = k_lo; k0 < k_hi; k0 += SK) {
-        const bool more = (k0 + SK < k_hi);
-        if (more) gload(k0 + SK);
-#pragma unroll
-        for (int k2 = 0; k2 < SK; k2 += 2) {
-            float a[2], b[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = sA[st][(wr * 64 + i * 32 + l32) * SPA + k2 + lk];
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                b[j] = bt ? sB[st][(wc * 64 + j * 32 + l32) * SPA + k2 + lk]
-                          : sB[st][(k2 + lk) * SPB + wc * 64 + j * 32 + l32];
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) lstore(st ^ 1);
-        __syncthreads();
-        st ^= 1;
-    }
-
-    // accumulator register r of lane l: row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its 32 x 32 tile
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wr * 64 + i * 32 + (r / 4) * 8 + lk * 4 + (r % 4);
-                const int col = n0 + wc * 64 + j * 32 + l32;
-                if (row >= g.m || col >= g.n) continue;
-                if (g.C) {
-                    g.C[int64_t(row) * g.ldc + col] = acc[i][j][r];
-                } else {
-                    const int oc = g.colmap ? g.colmap[col] : col;
-                    g.out[int64_t(row) * g.ldout + oc] = g.base[int64_t(row) * g.ldbase + col] + g.alpha * acc[i][j][r];
-                }
-            }
-}
-
-}  // namespace
-
-onecomp_status sgemm(const SgemmArgs& g, hipStream_t stream) {
-    if (g.m <= 0 || g.n <= 0) return ONECOMP_OK;
-    dim3 grid(unsigned(ceil_div(g.n, ST)), unsigned(ceil_div(g.m, ST)));
-    if (g.flags & S_BTRANS) hipLaunchKernelGGL(sgemm_kernel<true>, grid, dim3(256), 0, stream, g);
-    else hipLaunchKernelGGL(sgemm_kernel<false>, grid, dim3(256), 0, stream, g);
-    ONECOMP_CHECK_LAUNCH();
-    return ONECOMP_OK;
-}
-
 namespace {
 
 // Cp[a][b] = G[p(a)][p(b)] - H[p(a)][p(b)]   (p = perm, or the identity)
@@ -171,6 +38,8 @@ __device__ __forceinline__ void block_max_to_bits(uint32_t* dst, float v, uint32
     if (threadIdx.x == 0 && *s_max != 0u) atomicMax(dst, *s_max);
 }
 
+__global__ void qep_copy_max_kernel(const Scalars* from, Scalars* to) { to->max_u_bits = from->max_u_bits; }
+
 __global__ void qep_scalars_init_kernel(Scalars* sc, int n) {
     for (int i = threadIdx.x; i < n; i += blockDim.x) {
         sc[i].max_w_bits = 0u; sc[i].max_u_bits = 0u;
@@ -192,19 +61,22 @@ __global__ __launch_bounds__(256) void qep_diag_kernel(const float* __restrict__
 
 // Wp[r][a] = float(W[r][p(a)]); max |Wp d| into sc->max_w_bits
 template <typename T>
-__global__ __launch_bounds__(256) void wp_kernel(const T* __restrict__ W, int64_t d_in, const int32_t* __restrict__ perm,
-                                                const float* __restrict__ d, float* __restrict__ Wp, Scalars* sc) {
+__global__ __launch_bounds__(256) void wp_kernel(const T* __restrict__ W, int64_t d_out, int64_t d_in,
+                                                const int32_t* __restrict__ perm, const float* __restrict__ d,
+                                                float* __restrict__ Wp, Scalars* sc) {
     __shared__ uint32_t s_max;
-    const int64_t r = blockIdx.y;
     const int a = blockIdx.x * 256 + threadIdx.x;
     float mx = 0.f;
     if (a < d_in) {
         const int c = perm ? perm[a] : a;
-        float v;
-        if constexpr (sizeof(T) == 2) v = __uint_as_float(uint32_t(W[r * d_in + c]) << 16);
-        else v = W[r * d_in + c];
-        Wp[r * d_in + a] = v;
-        mx = fabsf(v) * d[a];
+        const float da = d[a];
+        for (int64_t r = blockIdx.y; r < d_out; r += gridDim.y) {   // few workgroups: one atomic each at the end
+            float v;
+            if constexpr (sizeof(T) == 2) v = __uint_as_float(uint32_t(W[r * d_in + c]) << 16);
+            else v = W[r * d_in + c];
+            Wp[r * d_in + a] = v;
+            mx = fmaxf(mx, fabsf(v) * da);
+        }
     }
     block_max_to_bits(&sc->max_w_bits, mx, &s_max);
 }
@@ -354,31 +226,32 @@ onecomp_status qep_target_run(const void* W, onecomp_dtype w_dtype, int64_t d_ou
                        w.Cp);
     ONECOMP_CHECK_LAUNCH();
     dim3 wgrid(unsigned(ceil_div(n, 256)), unsigned(d_out));
+    dim3 pgrid(unsigned(ceil_div(n, 256)), unsigned(d_out < 64 ? d_out : 64));
     if (w_dtype == ONECOMP_BF16)
-        hipLaunchKernelGGL(wp_kernel<uint16_t>, wgrid, dim3(256), 0, stream, static_cast<const uint16_t*>(W), d_in, perm,
-                           w.d, w.Wp, w.sc);
+        hipLaunchKernelGGL(wp_kernel<uint16_t>, pgrid, dim3(256), 0, stream, static_cast<const uint16_t*>(W), d_out, d_in,
+                           perm, w.d, w.Wp, w.sc);
     else
-        hipLaunchKernelGGL(wp_kernel<float>, wgrid, dim3(256), 0, stream, static_cast<const float*>(W), d_in, perm, w.d,
-                           w.Wp, w.sc);
+        hipLaunchKernelGGL(wp_kernel<float>, pgrid, dim3(256), 0, stream, static_cast<const float*>(W), d_out, d_in, perm,
+                           w.d, w.Wp, w.sc);
     ONECOMP_CHECK_LAUNCH();
 
     const dim3 bgrid(unsigned(ceil_div(n, 64)), unsigned(ceil_div(n + 32, 64)));
     const dim3 fgrid{2048};
-    // right operand of product i from S (both passes), then the left operand from `left` (its maximum is in sc[i])
-    auto operands = [&](int i, const float* S, bool trans, int upper, const float* rs, const float* cs, const float* left,
+    // right operand of product i from S (products 0 and 1: transposed, maximum pass first; product 2: as stored), then
+    // the left operand from `left` (its maximum is in sc[i])
+    auto operands = [&](int i, const float* S, int upper, const float* rs, const float* cs, const float* left,
                         const float* dl) -> onecomp_status {
         Scalars* sc = w.sc + i;
-        if (trans) {
+        if (i == 2) {   // the entries of U~ are those of U~^T: the maximum of product 1 serves
+            hipLaunchKernelGGL(qep_copy_max_kernel, dim3(1), dim3(1), 0, stream, w.sc + 1, sc);
+            ONECOMP_CHECK_LAUNCH();
+            hipLaunchKernelGGL((qep_right_kernel<true, false>), bgrid, dim3(256), 0, stream, S, n, n + 32, upper, rs, cs, sc,
+                               w.Bh, w.Bl);
+        } else {
             hipLaunchKernelGGL((qep_right_kernel<false, true>), bgrid, dim3(256), 0, stream, S, n, n + 32, upper, rs, cs, sc,
                                w.Bh, w.Bl);
             ONECOMP_CHECK_LAUNCH();
             hipLaunchKernelGGL((qep_right_kernel<true, true>), bgrid, dim3(256), 0, stream, S, n, n + 32, upper, rs, cs, sc,
-                               w.Bh, w.Bl);
-        } else {
-            hipLaunchKernelGGL((qep_right_kernel<false, false>), bgrid, dim3(256), 0, stream, S, n, n + 32, upper, rs, cs, sc,
-                               w.Bh, w.Bl);
-            ONECOMP_CHECK_LAUNCH();
-            hipLaunchKernelGGL((qep_right_kernel<true, false>), bgrid, dim3(256), 0, stream, S, n, n + 32, upper, rs, cs, sc,
                                w.Bh, w.Bl);
         }
         ONECOMP_CHECK_LAUNCH();
@@ -395,13 +268,13 @@ onecomp_status qep_target_run(const void* W, onecomp_dtype w_dtype, int64_t d_ou
         return ONECOMP_OK;
     };
     // M1 = (Wp D) C~^T:  B[k][n] = Cp[n][k] / (d_n d_k)
-    if ((st = operands(0, w.Cp, true, 0, w.rd, w.rd, w.Wp, w.d)) != ONECOMP_OK) return st;
+    if ((st = operands(0, w.Cp, 0, w.rd, w.rd, w.Wp, w.d)) != ONECOMP_OK) return st;
     if ((st = zero(w.M1)) != ONECOMP_OK) return st;
     if ((st = split_update(w.M1, d_out, d_in, w.Dh, w.Dl, ldD, w.Bh, w.Bl, w.sc, 0, kp, 0, 0, n, stream)) != ONECOMP_OK)
         return st;
     // M2 = M1 U~^T:  B[k][n] = U[n][k] d_k, zero for k < n
     if ((st = matmax(w.M1, w.sc + 1)) != ONECOMP_OK) return st;
-    if ((st = operands(1, U, true, 1, w.d, nullptr, w.M1, nullptr)) != ONECOMP_OK) return st;
+    if ((st = operands(1, U, 1, w.d, nullptr, w.M1, nullptr)) != ONECOMP_OK) return st;
     if ((st = zero(w.M2)) != ONECOMP_OK) return st;
     constexpr int CH = 1024;
     for (int c0 = 0; c0 < n; c0 += CH) {
@@ -413,7 +286,7 @@ onecomp_status qep_target_run(const void* W, onecomp_dtype w_dtype, int64_t d_ou
     }
     // M3 = M2 U~ (into M1's place):  B[k][n] = U[k][n] d_n, zero for k > n
     if ((st = matmax(w.M2, w.sc + 2)) != ONECOMP_OK) return st;
-    if ((st = operands(2, U, false, 1, nullptr, w.d, w.M2, nullptr)) != ONECOMP_OK) return st;
+    if ((st = operands(2, U, 1, nullptr, w.d, w.M2, nullptr)) != ONECOMP_OK) return st;
     if ((st = zero(w.M1)) != ONECOMP_OK) return st;
     for (int c0 = 0; c0 < n; c0 += CH) {
         const int c1 = c0 + CH < n ? c0 + CH : n;
