@@ -135,6 +135,19 @@ def test_jointq_after_activation_ordering(bits, G, d_out, d_in, dtype, grid, n_p
     _run(W, Wd, H32, Q0, S0, Z0, bits, G, grid=grid, n_pass=n_pass, max_scans=scans, perm=perm)
 
 
+@pytest.mark.parametrize("bits,G,d_out,d_in,act,lam", [
+    (4, 128, 1, 128, False, 0.0),       # one row, one group, one block
+    (3, 256, 3, 256, False, 0.0),       # one group per row of two blocks, fewer rows than a workgroup holds
+    (4, 16, 5, 48, False, 0.0),         # d_in below one MFMA tile of the products
+    (4, 64, 17, 320, True, 5.0),        # regularizer together with a column order
+])
+def test_jointq_smallest_shapes(bits, G, d_out, d_in, act, lam):
+    _announce(f"jointq small b{bits} g{G} {d_out}x{d_in} act={act} lam={lam}")
+    r = _start(d_out, d_in, bits, G, seed=500 + G + d_out, start="gptq", act=act)
+    perm = r[6] if act else None
+    _run(*r[:6], bits, G, lam=lam, n_pass=2, max_scans=3, perm=perm)
+
+
 def test_jointq_degenerate_rows_and_zero_passes():
     _announce("jointq: all-zero group, codes at the zero-point; n_pass = 0 returns the start")
     W, Wd, H32, Q0, S0, Z0 = _start(8, 256, 4, 64, seed=77)
