@@ -62,7 +62,7 @@ typedef enum {
  * fixed, its range [lo, hi] is shrunk to p_i [lo, hi], p_i = 1 - i / 100 for i = 0 .. 79, (s, z) follow from the
  * shrunk range by the grid's own rule, and the candidate with the least sum over the group of (w - s (q - z))^2
  * (q rounded and clamped as in the sweep) is kept, the lowest i on equal sums; i = 0 is the plain grid.  The search
- * runs in fp32 on the compensated values, for group sizes of at least 32. */
+ * runs in fp32 on the compensated values. */
 typedef enum {
     ONECOMP_GRID_MINMAX = 0,
     ONECOMP_GRID_SYMMETRIC = 1,

@@ -90,8 +90,6 @@ ONECOMP_API onecomp_status onecomp_quantize_layer_form(const void* W, onecomp_dt
     if (group_size % 16 != 0) return ONECOMP_ERR_UNSUPPORTED;
     if (block_size % group_size != 0 && group_size % block_size != 0) return ONECOMP_ERR_INVALID_ARG;
     if (form == ONECOMP_FACTOR_BLOCK && group_size > block_size && group_size != d_in) return ONECOMP_ERR_UNSUPPORTED;
-    if ((grid == ONECOMP_GRID_MINMAX_MSE || grid == ONECOMP_GRID_SYMMETRIC_MSE) && group_size < 32)
-        return ONECOMP_ERR_UNSUPPORTED;
     if (!aligned(W, 16) || !aligned(U, 16) || !aligned(Q_codes, 4) || (W_hat && !aligned(W_hat, 16)))
         return ONECOMP_ERR_INVALID_ARG;
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < sweep_workspace_bytes(d_out, d_in, block_size))

@@ -502,6 +502,24 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                                                    },
                                                    s, z);
                                     }
+                                } else {
+                                    if (a.mse) {   // uniform; the group's 16 values sit in two lanes of the quad
+                                        mse_search(mn, mx, qmax, a.qs,
+                                                   [&](float zi, float rsi) __attribute__((always_inline)) {
+                                                       float e0 = 0.f, e1 = 0.f;
+#pragma unroll
+                                                       for (int k = 0; k < 8; k += 2) {
+                                                           e0 += mse_term(w[k], zi, rsi, qmax);
+                                                           e1 += mse_term(w[k + 1], zi, rsi, qmax);
+                                                       }
+                                                       return e0 + e1;
+                                                   },
+                                                   [&](float x) __attribute__((always_inline)) {
+                                                       x += dpp_quad<QUAD_SWAP1>(x);
+                                                       return dpp_quad<quad_bcast(j / 8)>(x);
+                                                   },
+                                                   s, z);
+                                    }
                                 }
                                 rs = 1.0f / s;
                                 if (sl == 0) {
@@ -1192,8 +1210,6 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
             if (group_size % c == 0) { sbw = c; break; }
     const int sb_pairs = (sbw / SB) * (sbw / SB - 1) / 2;   // block pairs (b' < b) inside a super-block
     if (direct && group_size > SB && group_size != d_in) return ONECOMP_ERR_UNSUPPORTED;
-    if ((grid == ONECOMP_GRID_MINMAX_MSE || grid == ONECOMP_GRID_SYMMETRIC_MSE) && group_size < 32)
-        return ONECOMP_ERR_UNSUPPORTED;
     SweepWs w = carve(workspace, d_out, d_in);
     hipLaunchKernelGGL(init_scalars_kernel, dim3(1), dim3(1), 0, stream, w.sc);
     ONECOMP_CHECK_LAUNCH();

@@ -176,8 +176,6 @@ def test_quantize_grid_argument_checks(lib):
     f.restype = ctypes.c_int
     big = ctypes.c_size_t(1 << 40)
     assert f(P, 1, 64, 256, P, NULL, 4, 128, 128, 4, P, P, P, P, P, P, big, NULL) == UNSUPPORTED    # unknown grid
-    assert f(P, 1, 64, 256, P, NULL, 4, 16, 128, 2, P, P, P, P, P, P, big, NULL) == UNSUPPORTED     # scale search, G < 32
-    assert f(P, 1, 64, 256, P, NULL, 4, 16, 128, 3, P, P, P, P, P, P, big, NULL) == UNSUPPORTED
     assert f(P, 1, 64, 256, P, NULL, 4, 128, 128, 3, P, P, P, P, P, NULL, big, NULL) == WORKSPACE
     assert f(P, 1, 64, 256, P, NULL, 4, 128, 128, -1, P, P, P, P, P, P, big, NULL) == UNSUPPORTED
     assert f(NULL, 1, 64, 256, P, NULL, 4, 128, 128, 1, P, P, P, P, P, P, big, NULL) == INVALID
@@ -213,7 +211,6 @@ def test_quantize_form_argument_checks(lib):
     assert call(form=-1) == UNSUPPORTED
     assert call(d_in=512, G=256) == UNSUPPORTED  # block form: groups no wider than a block, or one group per row
     assert call(grid=4) == UNSUPPORTED
-    assert call(grid=2, G=16) == UNSUPPORTED     # scale search needs groups of at least 32
     assert call(dt=3) == UNSUPPORTED
     assert call(bits=5) == UNSUPPORTED
     assert call(W=NULL) == INVALID

@@ -484,6 +484,8 @@ def test_sweep_symmetric_all_zero_group():
     (4, 128, 256, 512, torch.float32, False, "minmax_mse", False),
     (3, 64, 100, 384, torch.bfloat16, True, "minmax_mse", False),
     (4, 32, 65, 256, torch.float32, False, "minmax_mse", False),
+    (4, 16, 33, 256, torch.bfloat16, True, "minmax_mse", False),       # two groups per quad of lanes
+    (3, 16, 64, 640, torch.float32, False, "symmetric_mse", True),
     (2, 128, 64, 1664, torch.bfloat16, True, "minmax_mse", False),     # several super-blocks, the last one partial
     (4, 128, 100, 1024, torch.bfloat16, False, "symmetric_mse", False),
     (3, 64, 33, 640, torch.float32, True, "symmetric_mse", False),
@@ -512,7 +514,7 @@ def test_sweep_scale_search(bits, G, d_out, d_in, dtype, act, grid, block):
 
 
 def test_sweep_scale_search_degenerate_groups():
-    _announce("sweep with scale search: all-zero, constant and one-signed groups; group size 16 refused")
+    _announce("sweep with scale search: all-zero, constant and one-signed groups")
     W, U32, _ = _layer(8, 256, 700, seed=34)
     W = W.clone()
     W[0, :] = 0.0
@@ -521,8 +523,7 @@ def test_sweep_scale_search_degenerate_groups():
     out, _ = _check_sweep(W, U32, 4, 64, grid="minmax_mse")
     assert torch.all(out["W_hat"][0] == 0) and torch.all(out["scales"][0] == 1)
     _check_sweep(W, U32, 3, 64, grid="symmetric_mse")
-    with pytest.raises(og.OnecompError):
-        og.onecomp_quantize_layer(W, U32, 4, 16, grid="minmax_mse")
+    _check_sweep(W, U32, 4, 16, grid="minmax_mse")
 
 
 def test_sweep_degenerate_and_one_signed_groups():
