@@ -273,6 +273,7 @@ template <int NC, bool WIDE>
 __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     extern __shared__ float sA[];   // G x G: A_tt + lam I
     __shared__ uint32_t s_max;
+    __shared__ int s_moves;
     const int G = v.G;
     const int c0 = v.col0;
     for (int e = threadIdx.x * 4; e < G * G; e += 64 * JQ_ROWS * 4) {
@@ -292,6 +293,7 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * JQ_ROWS + (threadIdx.x >> 6);
     float dr_max = 0.f;
+    int wave_moves = 0;
     bool run = row < v.d_out;
     if (WIDE && run && v.flags[2 * row] == 0) {   // the row's visit is over: no change from this block
         run = false;
@@ -327,12 +329,18 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
 #pragma unroll
     for (int cu = 0; cu < (WIDE ? 0 : NC); ++cu) {
         const int kn = G - 64 * cu < 64 ? G - 64 * cu : 64;
-        for (int k = 0; k < kn; ++k) {
-            const float uk = readlane_f(u[cu], k);
-            const float* rowk = sA + (64 * cu + k) * G + lane;
+        for (int k = 0; k < kn; k += 8) {   // kn is a multiple of 16; eight rows' LDS reads in flight at a time
+            float x[8][NC];
 #pragma unroll
-            for (int c = 0; c < NC; ++c)
-                if (has[c]) a[c] += rowk[64 * c] * uk;
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int c = 0; c < NC; ++c) x[i][c] = has[c] ? sA[(64 * cu + k + i) * G + lane + 64 * c] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float uk = readlane_f(u[cu], k + i);
+#pragma unroll
+                for (int c = 0; c < NC; ++c) a[c] = fmaf(x[i][c], uk, a[c]);
+            }
         }
     }
     float b = 0.f, cc = 0.f;
@@ -363,7 +371,7 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         bool took = false;
         for (;;) {
             // N = 2 d b g + (p^2 - s*^2 c A_jj): the bracket is the expanded form's g^2 + 2 s* g a - s*^2 (c A_jj - a^2)
-            const float twob = 2.0f * b, bss = b * ss;
+            const float twob = 2.0f * b, bss = b * ss, hcc = 0.5f * cc, qtop1 = v.qtop - 1.0f;
             uint64_t m[NC];
             float dd[NC];
 #pragma unroll
@@ -371,9 +379,9 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
                 const float gs = fmaf(-ss, a[c], p[c]);
                 const float base = fmaf(p[c], p[c], -bss * ad[c]);
                 const float t1 = twob * gs;
-                const float cad = cc + ad[c], a2 = 2.0f * a[c];
-                const bool up = q[c] + 1.0f <= v.qtop && base + t1 > 0.f && cad + a2 > 0.f;
-                const bool dn = q[c] - 1.0f >= 0.f && base - t1 > 0.f && cad - a2 > 0.f;
+                const float hc = fmaf(0.5f, ad[c], hcc);    // (c + A_jj) / 2: c' > 0  <=>  hc + d a > 0
+                const bool up = q[c] <= qtop1 && base > -t1 && hc > -a[c];
+                const bool dn = q[c] >= 1.0f && base > t1 && hc > a[c];
                 dd[c] = up ? 1.0f : -1.0f;
                 m[c] = __ballot(has[c] && (up || dn));
                 const int lo = j0 - 64 * c;          // columns up to lo (local numbering) are behind
@@ -431,17 +439,24 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         } else {
             v.scales[int64_t(row) * v.n_g + v.t] = s_new;
         }
-        if (n_moves > 0) atomicAdd(v.moves, n_moves);
     }
+    wave_moves = n_moves;
     }
-    if (threadIdx.x == 0) s_max = 0u;
+    // one atomic per workgroup and target: atomics on one address are serialized
+    if (threadIdx.x == 0) { s_max = 0u; s_moves = 0; }
     __syncthreads();
     dr_max = wave_max(dr_max);
-    if (lane == 0) atomicMax(&s_max, __float_as_uint(dr_max));
+    if (lane == 0) {
+        atomicMax(&s_max, __float_as_uint(dr_max));
+        if (wave_moves > 0) atomicAdd(&s_moves, wave_moves);
+    }
     __syncthreads();
-    if (threadIdx.x == 0 && s_max != 0u) {
-        atomicMax(&v.sc_near->max_w_bits, s_max);
-        atomicMax(&v.sc_far->max_w_bits, s_max);
+    if (threadIdx.x == 0) {
+        if (s_max != 0u) {
+            atomicMax(&v.sc_near->max_w_bits, s_max);
+            atomicMax(&v.sc_far->max_w_bits, s_max);
+        }
+        if (s_moves > 0) atomicAdd(v.moves, s_moves);
     }
 }
 
