@@ -72,7 +72,9 @@ __device__ __forceinline__ void block_max_bits(uint32_t* dst, float v, uint32_t*
     v = wave_max(v);
     if ((threadIdx.x & 63) == 0) atomicMax(s_max, __float_as_uint(v));
     __syncthreads();
-    if (threadIdx.x == 0 && *s_max != 0u) atomicMax(dst, *s_max);
+    // the maximum only grows: a workgroup that does not exceed what is already there (even a stale copy of it)
+    // has nothing to add, which spares most of the serialized atomics
+    if (threadIdx.x == 0 && *s_max > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, *s_max);
 }
 
 __global__ void jq_scalars_init_kernel(Scalars* sc, int n) {
@@ -452,10 +454,10 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        if (s_max != 0u) {
+        if (s_max > __hip_atomic_load(&v.sc_near->max_w_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
             atomicMax(&v.sc_near->max_w_bits, s_max);
+        if (s_max > __hip_atomic_load(&v.sc_far->max_w_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
             atomicMax(&v.sc_far->max_w_bits, s_max);
-        }
         if (s_moves > 0) atomicAdd(v.moves, s_moves);
     }
 }

@@ -35,7 +35,9 @@ __device__ __forceinline__ void block_max_to_bits(uint32_t* dst, float v, uint32
     v = wave_max_f(v);
     if ((threadIdx.x & 63) == 0) atomicMax(s_max, __float_as_uint(v));
     __syncthreads();
-    if (threadIdx.x == 0 && *s_max != 0u) atomicMax(dst, *s_max);
+    // the maximum only grows: a workgroup that does not exceed what is already there (even a stale copy of it)
+    // has nothing to add, which spares most of the serialized atomics
+    if (threadIdx.x == 0 && *s_max > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, *s_max);
 }
 
 __global__ void qep_copy_max_kernel(const Scalars* from, Scalars* to) { to->max_u_bits = from->max_u_bits; }
