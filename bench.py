@@ -401,23 +401,30 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     weights = d_out * d_in
 
-    # Gram kernel: one launch per accumulate call.  Algorithmic flops = symmetric half, T d (d + 1).
+    # Gram kernel.  Algorithmic flops = symmetric half, T d (d + 1).  An accumulate call on a wide layer launches the
+    # kernel once per round of 256 x 256 tiles (one tile per CU) and once more for the tiles cut along the tokens.
     gram_ms = acc_ms / n_calls
+    n256 = (d_in + 255) // 256
+    t256 = n256 * (n256 + 1) // 2
+    gram_launches = (t256 // 256 + (1 if t256 % 256 else 0)) if (cfg.dtype == torch.bfloat16 and t256 > 512) else 1
     algo_flops = float(tpc) * d_in * (d_in + 1)
     gram_tflops = algo_flops / (gram_ms * 1e-3) / 1e12
     # counter-backed traffic of the Gram launch: known for the default workload in one call (see profiles/)
-    gram_traffic = 175.0e9 if (cfg.name == "c3b" and n_calls == 1) else None
+    gram_traffic = 121.0e9 if (cfg.name == "c3b" and n_calls == 1) else None
     roofline = {
         "kernel": gram_kernel_name(d_in, cfg.dtype == torch.bfloat16),
         "bound": "mfma", "achieved": gram_tflops, "peak": PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3,
         "unit": "TFLOP/s", "frac": gram_tflops / (PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3),
         "traffic": gram_traffic,
-        "traffic_note": "L2 <-> fabric bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by a 4 GiB copy "
-                        "(profiles/c3b_hbm_traffic_pmc.md); measured for the default workload only, else null",
+        "traffic_note": "L2 <-> fabric bytes per accumulate call (all its launches) from rocprofv3 FETCH_SIZE / "
+                        "WRITE_SIZE, scaled by a 4 GiB copy (profiles/c3b_hbm_traffic_pmc.md); measured for the default "
+                        "workload only, else null",
         "algorithmic_bytes": 2.0 * tpc * d_in + 8.0 * d_in * d_in,
         "note": "algorithmic flops = T*d_in*(d_in+1) (upper triangle incl. diagonal, 2 flops per MAC); "
                 "dense-equivalent rate is 2x this",
-        "avg_launch_ms": gram_ms,
+        "call_ms": gram_ms, "launches_per_call": gram_launches, "avg_launch_ms": gram_ms / gram_launches,
+        "launch_note": "achieved = flops of one accumulate call / its time; the call is launches_per_call launches of "
+                       "the kernel back to back, so rocprofv3's average duration of the kernel is call_ms / launches_per_call",
     }
     w_bytes = 2 if cfg.dtype == torch.bfloat16 else 4
     sweep_bytes = sweep_model_bytes(d_out, d_in, cfg.group_size, w_bytes)
