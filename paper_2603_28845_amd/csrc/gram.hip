@@ -13,7 +13,8 @@
 //   * The workgroup -> tile map is XCD-aware: hardware deals consecutive workgroups round-robin to
 //     the 8 XCDs, so workgroup b is given the tile with rank (b % 8) * chunk + b / 8 in an
 //     order that walks bands of 4 tile rows column by column.  The 32 workgroups that share an
-//     XCD's L2 at any time then cover a compact 4 x 8 patch of tiles (12 X panels, not 64).
+//     XCD's L2 at any time then cover a compact 4 x 8 patch of tiles (12 X panels, not 64).  A wide layer is
+//     launched one round of tiles (one per CU) at a time, so that those 32 also stay together along the tokens.
 //   * fp32 path (small layers): 128-wide tiles on v_mfma_f32_32x32x2_f32, products in fp32.
 #include "common.hpp"
 
