@@ -806,7 +806,7 @@ onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens,
     // drift apart (L2 hit rate 59 % against 78 % for a round on its own; 46.2 -> 44.7 ms at d_in 14336, 262144 tokens).
     const int total = chunk * 8 + 8 * sp.n_piece * int(ceil_div(n_split, 8));
     const int n_cus_r = device_cus();
-    const int per_launch = (C::TM == 256 && C::TN == 256 && n_cus_r > 0 && n_cus_r % 8 == 0 && chunk * 8 > 2 * n_cus_r)
+    const int per_launch = (C::TM == 256 && C::TN == 256 && n_cus_r > 0 && n_cus_r % 8 == 0 && chunk * 8 >= 2 * n_cus_r)
                                ? n_cus_r : total;
     for (int b0 = 0; b0 < total;) {
         int nb = total - b0;
