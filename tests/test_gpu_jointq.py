@@ -88,6 +88,7 @@ def _run(W, Wd, H32, Q0, S0, Z0, bits, G, grid="asym", lam=0.0, n_pass=1, max_sc
     (3, 64, 32, 256, torch.float32, "asym", "rtn", 1, 4, 25.0),       # proximity regularizer (Eq. (jointq_reg))
     (4, 48, 16, 192, torch.float32, "asym", "rtn", 1, 4, 0.0),        # group size not a power of two
     (3, 128, 64, 768, torch.bfloat16, "asym", "rtn", 1, 1, 0.0),      # one scan: decisions replayed exactly
+    (4, 128, 520, 2048, torch.bfloat16, "asym", "gptq", 1, 4, 0.0),   # many workgroups, four super-blocks, every row compared
 ])
 def test_jointq_matches_oracle(bits, G, d_out, d_in, dtype, grid, start, n_pass, scans, lam):
     _announce(f"jointq b{bits} g{G} {d_out}x{d_in} {dtype} {grid} start={start} passes={n_pass} scans={scans} lam={lam}")
