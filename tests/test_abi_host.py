@@ -301,3 +301,29 @@ def test_jointq_argument_checks(lib):
     assert g(64, 256, 128) >= 2 * 64 * 256 * 4
     assert g(64, 384, 192) == 0 and g(0, 256, 128) == 0 and g(64, 250, 50) == 0
     assert g(64, 256, 256) > g(64, 256, 128)         # wider groups carry two more matrices
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """The boundary is a C header: it must compile as C99 on its own, and a C program must link against the library."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_onecomp.c"
+    src.write_text('#include "onecomp.h"\n'
+                   '#include <stdio.h>\n'
+                   'int main(void) {\n'
+                   '    printf("%d %s\\n", onecomp_version(), onecomp_status_string(ONECOMP_OK));\n'
+                   '    /* host-side argument check: no GPU is touched */\n'
+                   '    return onecomp_hessian_accumulate(0, ONECOMP_BF16, 1, 128, 128, 0, 0) == ONECOMP_ERR_INVALID_ARG ? 0 : 1;\n'
+                   '}\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(src)],
+                   check=True)
+    lib_dir = os.path.dirname(oc_gpu.LIB_PATH)
+    exe = tmp_path / "use_onecomp"
+    subprocess.run([gcc, "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", lib_dir, "-lonecomp",
+                    f"-Wl,-rpath,{lib_dir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) == oc_gpu.onecomp_version() and out[1] == "ok"
