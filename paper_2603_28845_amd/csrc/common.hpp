@@ -96,6 +96,29 @@ int64_t split_update_ld(int64_t d_out);
 onecomp_status split_left_operand(const float* src, int64_t ld_src, int64_t d_out, int k_count, const float* d,
                                   Scalars* sc, Scalars* other, uint16_t* Dh, uint16_t* Dl, hipStream_t stream);
 
+// ---- small device helpers shared by the kernel files -------------------------------------------
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+    return x;
+}
+
+// Workgroup maximum of non-negative values into *dst (bit patterns of non-negative floats order like the values);
+// s_max is one word of LDS.  One atomic per workgroup at most: atomics on one address are serialized, and the
+// maximum only grows, so a workgroup that does not exceed what is already there (even a stale copy of it) has
+// nothing to add.  Every thread of the workgroup must call it.
+__device__ __forceinline__ void block_max_bits(uint32_t* dst, float v, uint32_t* s_max) {
+    if (threadIdx.x == 0) *s_max = 0u;
+    __syncthreads();
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) atomicMax(s_max, __float_as_uint(v));
+    __syncthreads();
+    if (threadIdx.x == 0 && *s_max > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, *s_max);
+}
+
+// p[0 .. 4 n4) = 0 with a kernel (callers may be under graph capture, where memset nodes are avoided)
+onecomp_status fill_zero(float* p, int64_t n4, hipStream_t stream);
+
 // ---- entry points implemented in the kernel files -------------------------------------------
 size_t gram_workspace_bytes(int64_t d_in);
 onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx,

@@ -59,24 +59,6 @@ __device__ __forceinline__ float load_w(const void* W, int bf16, int64_t i) {
 
 constexpr float JQ_FU = 16384.f;   // scale of A~ (|A~| <= 1) in fp16
 
-__device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
-    return x;
-}
-
-// workgroup maximum of non-negative values into *dst (bit patterns order like the values); one atomic per workgroup
-__device__ __forceinline__ void block_max_bits(uint32_t* dst, float v, uint32_t* s_max) {
-    if (threadIdx.x == 0) *s_max = 0u;
-    __syncthreads();
-    v = wave_max(v);
-    if ((threadIdx.x & 63) == 0) atomicMax(s_max, __float_as_uint(v));
-    __syncthreads();
-    // the maximum only grows: a workgroup that does not exceed what is already there (even a stale copy of it)
-    // has nothing to add, which spares most of the serialized atomics
-    if (threadIdx.x == 0 && *s_max > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, *s_max);
-}
-
 __global__ void jq_scalars_init_kernel(Scalars* sc, int n) {
     for (int i = threadIdx.x; i < n; i += blockDim.x) {
         sc[i].max_w_bits = 0u; sc[i].max_u_bits = 0u;
@@ -599,6 +581,13 @@ JqWs carve(void* ws, int64_t d_out, int64_t d_in, bool wide) {
 
 }  // namespace
 
+onecomp_status fill_zero(float* p, int64_t n4, hipStream_t stream) {
+    if (n4 <= 0) return ONECOMP_OK;
+    hipLaunchKernelGGL(jq_fill0_kernel, dim3(2048), dim3(256), 0, stream, p, n4);
+    ONECOMP_CHECK_LAUNCH();
+    return ONECOMP_OK;
+}
+
 onecomp_status split_left_operand(const float* src, int64_t ld_src, int64_t d_out, int k_count, const float* d,
                                   Scalars* sc, Scalars* other, uint16_t* Dh, uint16_t* Dl, hipStream_t stream) {
     const int64_t ldD = split_update_ld(d_out);
@@ -666,8 +655,7 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
         return update_to(w.Gm, row0, k_count, u0, c_lo, c_hi, sc);
     };
     if ((st = dsplit(w.R, d_in, int(d_in), 0, 0, w.sc, nullptr)) != ONECOMP_OK) return st;
-    hipLaunchKernelGGL(jq_fill0_kernel, dim3(2048), dim3(256), 0, stream, w.Gm, d_out * d_in / 4);
-    ONECOMP_CHECK_LAUNCH();
+    if ((st = fill_zero(w.Gm, d_out * d_in / 4, stream)) != ONECOMP_OK) return st;
     if ((st = update(0, int(d_in), 0, 0, int(d_in), w.sc)) != ONECOMP_OK) return st;
     hipLaunchKernelGGL(jq_objective_kernel, rgrid, dim3(256), 0, stream, W, bf16, int(d_out), int(d_in), Q, scales, zeros,
                        G, n_g, perm, w.Gm, w.d, w.rowf, static_cast<float*>(nullptr));
@@ -730,7 +718,6 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
         // Am brought up to date between the launches (the super-block's columns at once, the group's other columns
         // once per super-block); at the end the scale, and the gradient of all columns from the group's dR.
         const int n_b = G / 128;
-        const dim3 fgrid{2048};
         for (int ps = 0; ps < n_pass; ++ps)
             for (int g = 0; g < n_g; ++g) {
                 const int g0 = g * G;
@@ -739,8 +726,7 @@ onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, i
                                    G, perm, w.d, w.R, w.sc + 5);
                 ONECOMP_CHECK_LAUNCH();
                 if ((st = dsplit(w.R + g0, d_in, G, g0, 0, w.sc + 5, w.sc + 6)) != ONECOMP_OK) return st;
-                hipLaunchKernelGGL(jq_fill0_kernel, fgrid, dim3(256), 0, stream, w.Am, d_out * d_in / 4);
-                ONECOMP_CHECK_LAUNCH();
+                if ((st = fill_zero(w.Am, d_out * d_in / 4, stream)) != ONECOMP_OK) return st;
                 if ((st = update_to(w.Am, 0, G, g0, g0, g0 + G, w.sc + 5)) != ONECOMP_OK) return st;
                 hipLaunchKernelGGL(jq_wide_p_kernel, rgrid, dim3(256), 0, stream, int(d_out), int(d_in), scales, n_g, g, G,
                                    w.d, w.R, w.Gm, w.Am, w.P, w.bc, w.flags);

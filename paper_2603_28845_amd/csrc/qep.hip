@@ -22,24 +22,6 @@ __global__ __launch_bounds__(256) void cp_kernel(const float* __restrict__ G, co
     Cp[int64_t(a) * n + b] = G[src] - H[src];
 }
 
-__device__ __forceinline__ float wave_max_f(float x) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
-    return x;
-}
-
-// workgroup maximum of non-negative values into *dst (bit patterns order like the values); one atomic per workgroup
-__device__ __forceinline__ void block_max_to_bits(uint32_t* dst, float v, uint32_t* s_max) {
-    if (threadIdx.x == 0) *s_max = 0u;
-    __syncthreads();
-    v = wave_max_f(v);
-    if ((threadIdx.x & 63) == 0) atomicMax(s_max, __float_as_uint(v));
-    __syncthreads();
-    // the maximum only grows: a workgroup that does not exceed what is already there (even a stale copy of it)
-    // has nothing to add, which spares most of the serialized atomics
-    if (threadIdx.x == 0 && *s_max > __hip_atomic_load(dst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(dst, *s_max);
-}
-
 __global__ void qep_copy_max_kernel(const Scalars* from, Scalars* to) { to->max_u_bits = from->max_u_bits; }
 
 __global__ void qep_scalars_init_kernel(Scalars* sc, int n) {
@@ -80,7 +62,7 @@ __global__ __launch_bounds__(256) void wp_kernel(const T* __restrict__ W, int64_
             mx = fmaxf(mx, fabsf(v) * da);
         }
     }
-    block_max_to_bits(&sc->max_w_bits, mx, &s_max);
+    block_max_bits(&sc->max_w_bits, mx, &s_max);
 }
 
 // max |M| of a row-major matrix into sc->max_w_bits
@@ -91,13 +73,7 @@ __global__ __launch_bounds__(256) void qep_max_kernel(const float* __restrict__ 
         const float4v v = reinterpret_cast<const float4v*>(M)[i];
         mx = fmaxf(fmaxf(fmaxf(mx, fabsf(v[0])), fmaxf(fabsf(v[1]), fabsf(v[2]))), fabsf(v[3]));
     }
-    block_max_to_bits(&sc->max_w_bits, mx, &s_max);
-}
-
-__global__ __launch_bounds__(256) void qep_fill0_kernel(float* __restrict__ p, int64_t n4) {
-    const float4v z = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t i = int64_t(blockIdx.x) * 256 + threadIdx.x; i < n4; i += int64_t(gridDim.x) * 256)
-        reinterpret_cast<float4v*>(p)[i] = z;
+    block_max_bits(&sc->max_w_bits, mx, &s_max);
 }
 
 // Right operand of a split product, B[k][n] (n contiguous, n_rows rows of which those behind n - 1 are zero), from a
@@ -151,7 +127,7 @@ __global__ __launch_bounds__(256) void qep_right_kernel(const float* __restrict_
             mx = fmaxf(mx, fabsf(v));
         }
     }
-    if (!WRITE) block_max_to_bits(&sc->max_u_bits, mx, &s_max);
+    if (!WRITE) block_max_bits(&sc->max_u_bits, mx, &s_max);
 }
 
 // W*[r][p(c)] = Wp[r][c] + alpha M[r][c] rd[c]
@@ -264,11 +240,7 @@ onecomp_status qep_target_run(const void* W, onecomp_dtype w_dtype, int64_t d_ou
         ONECOMP_CHECK_LAUNCH();
         return ONECOMP_OK;
     };
-    auto zero = [&](float* M) -> onecomp_status {
-        hipLaunchKernelGGL(qep_fill0_kernel, fgrid, dim3(256), 0, stream, M, d_out * d_in / 4);
-        ONECOMP_CHECK_LAUNCH();
-        return ONECOMP_OK;
-    };
+    auto zero = [&](float* M) -> onecomp_status { return fill_zero(M, d_out * d_in / 4, stream); };
     // M1 = (Wp D) C~^T:  B[k][n] = Cp[n][k] / (d_n d_k)
     if ((st = operands(0, w.Cp, 0, w.rd, w.rd, w.Wp, w.d)) != ONECOMP_OK) return st;
     if ((st = zero(w.M1)) != ONECOMP_OK) return st;
