@@ -12,14 +12,25 @@
 namespace onecomp {
 namespace {
 
-// Cp[a][b] = G[p(a)][p(b)] - H[p(a)][p(b)]   (p = perm, or the identity)
+// Cp[a][b] = G[p(a)][p(b)] - H[p(a)][p(b)]   (p = perm, or the identity); max |Cp[a][b] rd[a] rd[b]| into
+// sc->max_u_bits (the scale of the first product's right operand)
 __global__ __launch_bounds__(256) void cp_kernel(const float* __restrict__ G, const float* __restrict__ H, int n,
-                                                const int32_t* __restrict__ perm, float* __restrict__ Cp) {
-    const int a = blockIdx.y;
+                                                const int32_t* __restrict__ perm, const float* __restrict__ rd,
+                                                float* __restrict__ Cp, Scalars* sc) {
+    __shared__ uint32_t s_max;
     const int b = blockIdx.x * 256 + threadIdx.x;
-    if (b >= n) return;
-    const int64_t src = int64_t(perm ? perm[a] : a) * n + (perm ? perm[b] : b);
-    Cp[int64_t(a) * n + b] = G[src] - H[src];
+    float mx = 0.f;
+    if (b < n) {
+        const int ob = perm ? perm[b] : b;
+        const float rb = rd[b];
+        for (int a = blockIdx.y; a < n; a += gridDim.y) {
+            const int64_t src = int64_t(perm ? perm[a] : a) * n + ob;
+            const float c = G[src] - H[src];
+            Cp[int64_t(a) * n + b] = c;
+            mx = fmaxf(mx, fabsf(c) * rd[a] * rb);
+        }
+    }
+    block_max_bits(&sc->max_u_bits, mx, &s_max);
 }
 
 __global__ void qep_copy_max_kernel(const Scalars* from, Scalars* to) { to->max_u_bits = from->max_u_bits; }
@@ -200,8 +211,8 @@ onecomp_status qep_target_run(const void* W, onecomp_dtype w_dtype, int64_t d_ou
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(qep_diag_kernel, dim3(unsigned(ceil_div(n, 256))), dim3(256), 0, stream, H, n, perm, w.d, w.rd);
     ONECOMP_CHECK_LAUNCH();
-    hipLaunchKernelGGL(cp_kernel, dim3(unsigned(ceil_div(n, 256)), unsigned(n)), dim3(256), 0, stream, G, H, n, perm,
-                       w.Cp);
+    hipLaunchKernelGGL(cp_kernel, dim3(unsigned(ceil_div(n, 256)), unsigned(n < 128 ? n : 128)), dim3(256), 0, stream, G,
+                       H, n, perm, w.rd, w.Cp, w.sc);
     ONECOMP_CHECK_LAUNCH();
     dim3 wgrid(unsigned(ceil_div(n, 256)), unsigned(d_out));
     dim3 pgrid(unsigned(ceil_div(n, 256)), unsigned(d_out < 64 ? d_out : 64));
@@ -215,8 +226,9 @@ onecomp_status qep_target_run(const void* W, onecomp_dtype w_dtype, int64_t d_ou
 
     const dim3 bgrid(unsigned(ceil_div(n, 64)), unsigned(ceil_div(n + 32, 64)));
     const dim3 fgrid{2048};
-    // right operand of product i from S (products 0 and 1: transposed, maximum pass first; product 2: as stored), then
-    // the left operand from `left` (its maximum is in sc[i])
+    // right operand of product i from S (products 0 and 1: transposed; product 2: as stored; the maximum that sets
+    // its scale comes from cp_kernel, from a pass of its own, from product 1), then the left operand from `left` (its
+    // maximum is in sc[i])
     auto operands = [&](int i, const float* S, int upper, const float* rs, const float* cs, const float* left,
                         const float* dl) -> onecomp_status {
         Scalars* sc = w.sc + i;
@@ -224,6 +236,9 @@ onecomp_status qep_target_run(const void* W, onecomp_dtype w_dtype, int64_t d_ou
             hipLaunchKernelGGL(qep_copy_max_kernel, dim3(1), dim3(1), 0, stream, w.sc + 1, sc);
             ONECOMP_CHECK_LAUNCH();
             hipLaunchKernelGGL((qep_right_kernel<true, false>), bgrid, dim3(256), 0, stream, S, n, n + 32, upper, rs, cs, sc,
+                               w.Bh, w.Bl);
+        } else if (i == 0) {   // cp_kernel has left the maximum of C~ in sc[0]
+            hipLaunchKernelGGL((qep_right_kernel<true, true>), bgrid, dim3(256), 0, stream, S, n, n + 32, upper, rs, cs, sc,
                                w.Bh, w.Bl);
         } else {
             hipLaunchKernelGGL((qep_right_kernel<false, true>), bgrid, dim3(256), 0, stream, S, n, n + 32, upper, rs, cs, sc,
