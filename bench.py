@@ -112,7 +112,7 @@ def cpu_baseline(cfg, synth, seconds_hint=20.0):
 
 
 def bench_jointq(args, cfg, og, W, H, out, perm):
-    """JointQ refinement (Sec. 4.2.2) of the sweep's result: args.jointq passes over the groups, four scans per
+    """JointQ refinement (Sec. 4.3.2) of the sweep's result: args.jointq passes over the groups, four scans per
     visit, on the H of the timed steps.  The refinement works on copies; two timed calls after one warm-up."""
     import torch
     d_out, d_in, G = cfg.d_out, cfg.d_in, cfg.group_size
@@ -225,14 +225,14 @@ def main():
     ap.add_argument("--phase", default="all", choices=["all", "gram", "factor", "sweep"],
                     help="profiling aid: run only one call in the timed loop (the others run once to prepare its inputs)")
     ap.add_argument("--jointq", type=int, default=1,
-                    help="passes of the JointQ refinement (Sec. 4.2.2) timed on the result of the last step and "
+                    help="passes of the JointQ refinement (Sec. 4.3.2) timed on the result of the last step and "
                          "reported under 'jointq' (0 = skip); the headline value is unchanged")
     ap.add_argument("--qep", action="store_true",
-                    help="also time the layer with error propagation (Sec. 4.2.1): Gram of the perturbed activations, "
+                    help="also time the layer with error propagation (Sec. 4.3.1): Gram of the perturbed activations, "
                          "cross-Gram, factor, corrected target, sweep of the corrected target; reported under 'qep', "
                          "the headline value is unchanged")
     ap.add_argument("--factor-form", default="inverse", choices=["inverse", "block"],
-                    help="inverse: the factor call returns U with U^T U = (H + lambda I)^-1 (Sec. 4.2.1) and the sweep "
+                    help="inverse: the factor call returns U with U^T U = (H + lambda I)^-1 (Sec. 4.3.1) and the sweep "
                          "propagates through it; block: one Cholesky only, the sweep runs on the block form (same codes "
                          "up to ties; groups up to 128 columns)")
     ap.add_argument("--group-size", type=int, default=0,
@@ -240,7 +240,7 @@ def main():
                          "paper's Table 3); 0 = as configured")
     ap.add_argument("--grid", default="minmax", choices=["minmax", "symmetric", "minmax_mse", "symmetric_mse"],
                     help="grid of the sweep: min-max (Eq. (2), the configured workloads) or symmetric (Eq. (3)); "
-                         "_mse adds the scale search of Sec. 4.2")
+                         "_mse adds the scale search of Sec. 4.3")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (accumulate, factor, quantize) in a HIP graph after the warm-up and time "
                          "replays of it; per-phase times are then not available (reported as the eager warm-up's)")

@@ -2,20 +2,20 @@
  * onecomp.h -- C ABI of the MI355X (gfx950) layer-wise Hessian-aware quantizer.
  *
  * One linear layer is quantized in three calls that follow the paper's problem
- * statement for layer-wise PTQ (Sec. 4.2):
+ * statement for layer-wise PTQ (Sec. 4.3):
  *
- *   1. onecomp_hessian_accumulate  H += 2 X^T X          (Gram matrix, Sec. 2.5 / 4.2)
+ *   1. onecomp_hessian_accumulate  H += 2 X^T X          (Gram matrix, Sec. 2.5 / 4.3)
  *   2. onecomp_hessian_factor      U^T U = (H + lambda I)^-1, lambda = damp * mean(diag H)
- *                                                         (Sec. 4.2.1, text after Eq. (qep));
- *                                  optional activation ordering (Sec. 4.2, "actorder")
+ *                                                         (Sec. 4.3.1, text after Eq. (qep));
+ *                                  optional activation ordering (Sec. 4.3, "actorder")
  *   3. onecomp_quantize_layer      column-by-column sweep: each column is rounded to the
  *                                  per-group asymmetric min-max grid (Eq. (1), (2), (4))
  *                                  and its residual is propagated through U to the
- *                                  columns not yet quantized (Sec. 4.2)
+ *                                  columns not yet quantized (Sec. 4.3)
  *
  * Variants: onecomp_quantize_layer_grid (symmetric grid of Eq. (3)); onecomp_hessian_factor_form and
  * onecomp_quantize_layer_form (the same sweep on one Cholesky factor, without the triangular inverse);
- * onecomp_crossgram_accumulate and onecomp_qep_target (error propagation, Sec. 4.2.1);
+ * onecomp_crossgram_accumulate and onecomp_qep_target (error propagation, Sec. 4.3.1);
  * onecomp_rtn_sensitivity (error metric of the bit allocation, Sec. 4.1).
  *
  * Storage convention: W is d_out x d_in row-major (rows = output channels); this
@@ -58,7 +58,7 @@ typedef enum {
 } onecomp_dtype;
 
 /* Grid of the column sweep: per-group asymmetric min-max grid of Eq. (2), or the symmetric grid of Eq. (3).
- * The _MSE variants add the scale search of Sec. 4.2 (the sweep's "mse" option): when a group's parameters are
+ * The _MSE variants add the scale search of Sec. 4.3 (the sweep's "mse" option): when a group's parameters are
  * fixed, its range [lo, hi] is shrunk to p_i [lo, hi], p_i = 1 - i / 100 for i = 0 .. 79, (s, z) follow from the
  * shrunk range by the grid's own rule, and the candidate with the least sum over the group of (w - s (q - z))^2
  * (q rounded and clamped as in the sweep) is kept, the lowest i on equal sums; i = 0 is the plain grid.  The search
@@ -71,7 +71,7 @@ typedef enum {
 } onecomp_grid;
 
 /* What the factor call hands to the sweep.
- *   ONECOMP_FACTOR_INVERSE  the inverse factor U of Sec. 4.2.1, U^T U = (H + lambda I)^-1 (one Cholesky plus one
+ *   ONECOMP_FACTOR_INVERSE  the inverse factor U of Sec. 4.3.1, U^T U = (H + lambda I)^-1 (one Cholesky plus one
  *                           triangular inverse, 2 d_in^3 / 3 flops).
  *   ONECOMP_FACTOR_BLOCK    one Cholesky only (d_in^3 / 3 flops).  With R = U^-1 (upper, R R^T = H + lambda I) the
  *                           matrix written is F = U on the 128 x 128 diagonal blocks and
@@ -85,7 +85,7 @@ typedef enum {
 } onecomp_factor_form;
 
 /*
- * H += 2 * X^T X  over the n_tokens rows of X (Gram matrix of Sec. 2.5 / Sec. 4.2; the
+ * H += 2 * X^T X  over the n_tokens rows of X (Gram matrix of Sec. 2.5 / Sec. 4.3; the
  * factor 2 makes it the Hessian of ||X (W^ - W)||^2, cf. Sec. 2.4).
  *
  *   X        [n_tokens x d_in], row-major, row stride `ldx` elements (ldx >= d_in), dtype x_dtype.
@@ -122,7 +122,7 @@ size_t onecomp_accumulate_workspace_bytes(onecomp_dtype x_dtype, int64_t d_in);
 
 /*
  * Damping, optional activation ordering, and the Cholesky-based inverse factor
- * (Sec. 4.2.1: lambda = damp * mean(diag H), Cholesky of H + lambda I; Sec. 4.2 "actorder").
+ * (Sec. 4.3.1: lambda = damp * mean(diag H), Cholesky of H + lambda I; Sec. 4.3 "actorder").
  *
  *   H         [d_in x d_in] fp32 symmetric, read only (only diagonal and one triangle need be valid;
  *             the upper triangle is read).
@@ -159,7 +159,7 @@ onecomp_status onecomp_hessian_factor_form(const float* H, int64_t d_in, float d
                                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
- * The column sweep (Sec. 4.2) on the per-group asymmetric grid (Eq. (1), (2), (4)).
+ * The column sweep (Sec. 4.3) on the per-group asymmetric grid (Eq. (1), (2), (4)).
  * For every output row independently, for columns j in sweep order:
  *   at the first column of a group: s = (max - min) / (2^bits - 1) over the CURRENT
  *     (already compensated) values of the group (s = 1 if max == min),
@@ -192,6 +192,7 @@ onecomp_status onecomp_hessian_factor_form(const float* H, int64_t d_in, float d
  *              (about 9 d_out d_in + 4 d_in^2 bytes: two fp32 copies of W, codes staged in sweep order, two fp16
  *              halves of the scaled U).
  *   d_in       at most 65535, d_out at most 2^24.
+ *   W, U and W_hat must be 16-byte aligned, Q_codes 4-byte aligned (ONECOMP_ERR_INVALID_ARG otherwise).
  */
 onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
                                       const float* U, const int32_t* perm,
@@ -202,7 +203,7 @@ onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w_dtype, int6
 
 /*
  * onecomp_quantize_layer with the grid chosen by the caller (onecomp_quantize_layer is this call with
- * ONECOMP_GRID_MINMAX).  ONECOMP_GRID_SYMMETRIC is the symmetric grid of Sec. 2.2.2, Eq. (3): at the first column
+ * ONECOMP_GRID_MINMAX).  ONECOMP_GRID_SYMMETRIC is the symmetric grid of Sec. 2.3.2, Eq. (3): at the first column
  * of a group  s = max(|min|, |max|) / (2^(bits-1) - 1)  over the current values of the group (s = 1 if all are
  * zero), signed codes q in {-(2^(bits-1) - 1), ..., 2^(bits-1) - 1}, w^ = s q.  Outputs keep the format of the
  * min-max grid: Q_codes holds the unsigned code q + (2^(bits-1) - 1), zeros holds the constant 2^(bits-1) - 1, so
@@ -240,7 +241,7 @@ size_t onecomp_factor_workspace_bytes(int64_t d_in);
 size_t onecomp_quantize_workspace_bytes(int64_t d_out, int64_t d_in, int block_size);
 
 /*
- * Error propagation (QEP, Sec. 4.2.1): cross-Gram of the activations X_hat that reach this layer in the partly
+ * Error propagation (QEP, Sec. 4.3.1): cross-Gram of the activations X_hat that reach this layer in the partly
  * quantized model and the activations X of the full-precision model,
  *     G += 2 X_hat^T X        (the factor 2 of onecomp_hessian_accumulate),
  * so that with H = 2 X_hat^T X_hat (onecomp_hessian_accumulate on X_hat) the error-propagation matrix of the
@@ -256,7 +257,7 @@ onecomp_status onecomp_crossgram_accumulate(const void* X_hat, const void* X, on
                                             float* G, void* hip_stream);
 
 /*
- * Corrected quantization target of Eq. (qep), Sec. 4.2.1 (paper: W* = (I + alpha (H^ + lambda I)^-1 C) W for
+ * Corrected quantization target of Eq. (qep), Sec. 4.3.1 (paper: W* = (I + alpha (H^ + lambda I)^-1 C) W for
  * the d_in x d_out weight).  In this library's d_out x d_in storage and scaling:
  *     W* = W + alpha W (G - H)^T (H + lambda I)^-1,   lambda = damp * mean(diag H),
  * where the regularized inverse is taken from the factor of onecomp_hessian_factor(H, damp, ...):
@@ -289,8 +290,8 @@ size_t onecomp_qep_workspace_bytes(int64_t d_out, int64_t d_in);
  * where W^ rounds every group of group_size consecutive input channels of a row to its own grid (min-max grid of
  * Eq. (2) or symmetric grid of Eq. (3), no error feedback).  With a = b = 1 this is half the squared Frobenius
  * norm of the perturbation.
- *   W        [d_out x d_in] row-major, dtype w_dtype; read only.
- *   a_diag   fp32 [d_in]: diagonal of the input Gram matrix A (e.g. diag H of onecomp_hessian_accumulate, which
+ *   W        [d_out x d_in] row-major, dtype w_dtype, 16-byte aligned; read only.
+ *   a_diag   fp32 [d_in], 16-byte aligned: diagonal of the input Gram matrix A (e.g. diag H of onecomp_hessian_accumulate, which
  *            carries that call's factor 2); read only.
  *   b_diag   fp32 [d_out]: diagonal of the output curvature B, or NULL for all ones; read only.
  *   bits, group_size, grid: the candidate; group_size a multiple of 16 that divides d_in (no block restriction).
@@ -304,7 +305,7 @@ onecomp_status onecomp_rtn_sensitivity(const void* W, onecomp_dtype w_dtype, int
 size_t onecomp_sensitivity_workspace_bytes(void);
 
 /*
- * JointQ refinement of a quantized layer (Sec. 4.2.2, Eq. (jointq); with lam > 0 Eq. (jointq_reg)): local search over
+ * JointQ refinement of a quantized layer (Sec. 4.3.2, Eq. (jointq); with lam > 0 Eq. (jointq_reg)): local search over
  * the integer codes, the scale of the touched group refit in the same move, started from a solution in the format
  * onecomp_quantize_layer returns.  Per output row the objective is
  * f = (w - w^) (H + lam I) (w - w^)^T, w^ = s_g (q - z_g).
@@ -319,6 +320,7 @@ size_t onecomp_sensitivity_workspace_bytes(void);
  *
  *   W         device, d_out x d_in, row-major, fp32 or bf16: the weights the objective measures against.
  *   H         device fp32, d_in x d_in, symmetric (as onecomp_hessian_accumulate leaves it), read only.
+ *             W, H and W_hat must be 16-byte aligned, Q_codes 4-byte aligned (ONECOMP_ERR_INVALID_ARG otherwise).
  *   perm      device int32[d_in] or NULL: the column order the start was quantized in (perm_out of
  *             onecomp_hessian_factor).  As in onecomp_quantize_layer, groups are group_size consecutive columns of
  *             that order, scales / zeros are indexed by group in that order, W, H, Q_codes and W_hat stay in the

@@ -7,28 +7,28 @@ HIP library and must never be used as a fallback for it.
 What it computes (paper sections given in brackets):
 
   * the calibration Gram / Hessian  H = 2 * X^T X  over token rows of X
-    [Sec. 2.5 "Gram matrix H_l = X_l^T X_l"; Sec. 4.2 text after Eq. (layerwise);
+    [Sec. 2.5 "Gram matrix H_l = X_l^T X_l"; Sec. 4.3 text after Eq. (layerwise);
      the factor 2 is the constant that makes it the Hessian of ||X(W^-W)||^2,
      cf. Sec. 2.4 "proportional, up to a constant factor, to the local Hessian"]
   * Tikhonov damping  lambda = eta * mean(diag H)  and a Cholesky-based factor
-    of (H + lambda I)^-1  [Sec. 4.2.1, text after Eq. (qep)]
+    of (H + lambda I)^-1  [Sec. 4.3.1, text after Eq. (qep)]
   * optional activation ordering: columns sorted by decreasing diag(H)
-    [Sec. 4.2, "actorder"]
+    [Sec. 4.3, "actorder"]
   * the column-by-column sweep: quantize one column to the per-group
     asymmetric min-max grid (or the symmetric grid of Eq. (3)), propagate its
-    residual to the columns not yet quantized  [Sec. 4.2; grid: Eq. (1) scalar
+    residual to the columns not yet quantized  [Sec. 4.3; grid: Eq. (1) scalar
     quantizer, Eq. (2) min-max scale / zero-point, Eq. (4) per-group layout]
   * the layer objective tr((W-W^) H (W-W^)^T)  [Eq. (layerwise), Eq. (activation-aware)]
   * the same sweep without the off-diagonal part of the inverse factor (direct_factor, block_feedback_factor,
     quantize_layer_direct): with R = U^-1, R R^T = H + lambda I, the propagated errors are e = (w - w^) R, so a
     blocked sweep can run on one Cholesky factor of the damped matrix itself and the inverses of its diagonal
-    blocks  [a restatement of Sec. 4.2, derived in quantize_layer_direct]
+    blocks  [a restatement of Sec. 4.3, derived in quantize_layer_direct]
   * the scale search of the sweep ("mse": per group, candidate ranges shrunk from the observed one, the smallest
-    squared reconstruction error wins)  [Sec. 4.2; the candidate set is this build's reading, see mse_search]
+    squared reconstruction error wins)  [Sec. 4.3; the candidate set is this build's reading, see mse_search]
   * JointQ's local search over codes with the group scale refit in the same move (jointq_refine)
-    [Sec. 4.2.2, Eq. (jointq); order of moves and stopping are this build's reading, see the function]
+    [Sec. 4.3.2, Eq. (jointq); order of moves and stopping are this build's reading, see the function]
   * the corrected quantization target of error propagation (QEP),
-    W* = (I + alpha (H^ + lambda I)^-1 C) W  with  C = X^^T (X - X^)  [Sec. 4.2.1, Eq. (qep)]
+    W* = (I + alpha (H^ + lambda I)^-1 C) W  with  C = X^^T (X - X^)  [Sec. 4.3.1, Eq. (qep)]
 
 Storage convention: W is d_out x d_in (rows = output channels), i.e. the
 transpose of the paper's N x M matrix; "column j" is input channel j and a group
@@ -52,7 +52,7 @@ from scipy.linalg import solve_triangular
 # Gram / Hessian
 # --------------------------------------------------------------------------
 def hessian_accumulate(X, H=None):
-    """H + 2 * X^T X in float64 (Gram matrix of Sec. 2.5 / Sec. 4.2, times 2).
+    """H + 2 * X^T X in float64 (Gram matrix of Sec. 2.5 / Sec. 4.3, times 2).
 
     X: [n_tokens, d_in] (any float dtype; widened exactly to float64).
     H: optional running sum [d_in, d_in]; a new array is returned either way.
@@ -74,7 +74,7 @@ def hessian_tile(X, idx_i, idx_k):
 # Damping, ordering, inverse factor
 # --------------------------------------------------------------------------
 def damp_hessian(H, damp):
-    """H_d = H + lambda I with lambda = damp * mean(diag H)  [Sec. 4.2.1].
+    """H_d = H + lambda I with lambda = damp * mean(diag H)  [Sec. 4.3.1].
 
     Reading for a dead input channel (H_jj == 0, on which the paper is silent):
     its diagonal entry is set to 1 before lambda is computed, which keeps H_d
@@ -93,7 +93,7 @@ def damp_hessian(H, damp):
 
 def act_order_perm(H):
     """Column order by decreasing diag(H); equal keys keep the lower index first
-    [Sec. 4.2 "actorder"; the tie rule is this build's choice]."""
+    [Sec. 4.3 "actorder"; the tie rule is this build's choice]."""
     d = np.diag(np.asarray(H, dtype=np.float64))
     return np.argsort(-d, kind="stable").astype(np.int64)
 
@@ -148,7 +148,7 @@ def hessian_factor(H, damp, act_order=False):
 
 def direct_factor(Hd):
     """Upper-triangular R with positive diagonal and R R^T = Hd, so that R = U^-1 for the inverse factor U of
-    Sec. 4.2.1 (U^T U = Hd^-1  <=>  Hd = U^-1 U^-T).  One Cholesky of the index-reversed matrix:
+    Sec. 4.3.1 (U^T U = Hd^-1  <=>  Hd = U^-1 U^-T).  One Cholesky of the index-reversed matrix:
     J Hd J = L L^T  =>  Hd = (J L J)(J L J)^T  with J L J upper.  Returns (R, info) like inverse_factor."""
     Hd = np.asarray(Hd, dtype=np.float64)
     try:
@@ -220,7 +220,7 @@ MSE_STEP = 0.01         # i = 0 .. 79 (down to 21 % of the range); the paper nam
 
 
 def mse_search(vals, bits, grid="asym", n_cand=MSE_CANDIDATES, step=MSE_STEP):
-    """Scale search per group [Sec. 4.2: "MSE-based grid tuning (mse), which searches over candidate scales to
+    """Scale search per group [Sec. 4.3: "MSE-based grid tuning (mse), which searches over candidate scales to
     minimize the mean squared reconstruction error per-group"; the candidate set is this build's reading].
 
     vals: [rows, G] current values of one group per row.  Candidate i shrinks both ends of the observed range by
@@ -291,7 +291,7 @@ def rtn_quantize(W, bits, group_size, grid="asym", scale_search=None):
 
 
 # --------------------------------------------------------------------------
-# Column sweep (Sec. 4.2: one column at a time, residual propagated)
+# Column sweep (Sec. 4.3: one column at a time, residual propagated)
 # --------------------------------------------------------------------------
 def quantize_layer(W, U, bits, group_size, perm=None, rows=None,
                    forced_codes=None, forced_zeros=None, grid="asym", scale_search=None, forced_cand=None):
@@ -412,7 +412,7 @@ def layer_loss(W, W_hat, Hd):
 
 
 def quantize_layer_direct(W, R, bits, group_size, block, perm=None, grid="asym"):
-    """The sweep of Sec. 4.2 arranged so that only ONE Cholesky factor of the damped matrix is needed.
+    """The sweep of Sec. 4.3 arranged so that only ONE Cholesky factor of the damped matrix is needed.
 
     For one row let w be the original weights, w^ the quantized ones, e the propagated errors of
     quantize_layer and R = U^-1 (upper, R R^T = Hd, direct_factor).  Column j receives sum_{i<j} e_i U_ij and
@@ -487,13 +487,13 @@ def dequantize(Q, scales, zeros, group_size, perm=None):
 
 
 # --------------------------------------------------------------------------
-# Error propagation (QEP): corrected quantization target  [Sec. 4.2.1, Eq. (qep_obj), Eq. (qep)]
+# Error propagation (QEP): corrected quantization target  [Sec. 4.3.1, Eq. (qep_obj), Eq. (qep)]
 # --------------------------------------------------------------------------
 def crossgram_accumulate(X_hat, X, G=None):
     """G + 2 * X_hat^T X in float64.
 
     X_hat: activations seen by the partly quantized model, X: full-precision activations, both
-    [n_tokens, d_in].  With H = 2 X_hat^T X_hat the error-propagation matrix of Sec. 4.2.1 is
+    [n_tokens, d_in].  With H = 2 X_hat^T X_hat the error-propagation matrix of Sec. 4.3.1 is
     C = X_hat^T (X - X_hat) = (G - H) / 2; the factor 2 is the one of hessian_accumulate.
     """
     X_hat = np.asarray(X_hat, dtype=np.float64)
@@ -511,7 +511,7 @@ def qep_target(W, G, H, damp, alpha):
     (H^_p + lambda_p I)^-1 C = (H + lambda I)^-1 (G - H).  Transposed:
         W* = W + alpha * W (G - H)^T (H + lambda I)^-1.
     The damped matrix is the one damp_hessian builds (a dead channel's diagonal entry becomes 1 first).
-    The inverse is applied with a symmetric positive definite solve (Cholesky based, as Sec. 4.2.1 says).
+    The inverse is applied with a symmetric positive definite solve (Cholesky based, as Sec. 4.3.1 says).
     """
     from scipy.linalg import cho_factor, cho_solve
     W = np.asarray(W, dtype=np.float64)
@@ -526,7 +526,7 @@ def qep_target(W, G, H, damp, alpha):
 
 
 # --------------------------------------------------------------------------
-# JointQ: local search over integer codes with the group scale refit in the same move  [Sec. 4.2.2, Eq. (jointq)]
+# JointQ: local search over integer codes with the group scale refit in the same move  [Sec. 4.3.2, Eq. (jointq)]
 # --------------------------------------------------------------------------
 def row_objective(W, W_hat, A):
     """Per row (w - w^) A (w - w^)^T: the objective of Eq. (jointq) for one output row when A = X^T X up to the
@@ -537,7 +537,7 @@ def row_objective(W, W_hat, A):
 
 def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=1, max_scans=4, rows=None,
                   forced=None, tie_tol=0.0, g_tol=0.0, a_tol=0.0, perm=None):
-    """Local search of Sec. 4.2.2 on a solution in the per-group format of Eq. (4), rows independent.
+    """Local search of Sec. 4.3.2 on a solution in the per-group format of Eq. (4), rows independent.
 
     What the paper fixes: one move changes one integer code by a small amount inside the codebook, the scale of
     that code's group is refit in the same step to the codes, a move is kept iff the objective of Eq. (jointq)

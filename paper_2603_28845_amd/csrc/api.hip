@@ -178,7 +178,8 @@ ONECOMP_API onecomp_status onecomp_jointq_refine(const void* W, onecomp_dtype w_
     if (!(lam >= 0.0f) || n_pass < 0 || max_scans < 1) return ONECOMP_ERR_INVALID_ARG;
     if (group_size <= 0 || d_in % 16 != 0 || d_in % group_size != 0) return ONECOMP_ERR_INVALID_ARG;
     if (group_size % 16 != 0 || (group_size > 128 && group_size % 128 != 0)) return ONECOMP_ERR_UNSUPPORTED;
-    if (!aligned(W, 16) || !aligned(H, 16) || (W_hat && !aligned(W_hat, 16))) return ONECOMP_ERR_INVALID_ARG;
+    if (!aligned(W, 16) || !aligned(H, 16) || !aligned(Q_codes, 4) || (W_hat && !aligned(W_hat, 16)))
+        return ONECOMP_ERR_INVALID_ARG;
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < jointq_workspace_bytes(d_out, d_in, group_size))
         return ONECOMP_ERR_WORKSPACE;
     return jointq_run(W, w_dtype, d_out, d_in, H, perm, lam, bits, group_size, int(grid), n_pass, max_scans, Q_codes, scales,
@@ -198,6 +199,7 @@ ONECOMP_API onecomp_status onecomp_rtn_sensitivity(const void* W, onecomp_dtype 
     if (d_out <= 0 || d_in <= 0 || d_out > (1 << 24) || d_in > (1 << 24)) return ONECOMP_ERR_INVALID_ARG;
     if (group_size <= 0 || d_in % group_size != 0) return ONECOMP_ERR_INVALID_ARG;
     if (group_size % 16 != 0) return ONECOMP_ERR_UNSUPPORTED;
+    if (!aligned(W, 16) || !aligned(a_diag, 16)) return ONECOMP_ERR_INVALID_ARG;   // 16-byte vector loads
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < sensitivity_workspace_bytes())
         return ONECOMP_ERR_WORKSPACE;
     return sensitivity_run(W, w_dtype, d_out, d_in, a_diag, b_diag, bits, group_size, int(grid), err, workspace,

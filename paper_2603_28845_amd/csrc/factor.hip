@@ -1,5 +1,5 @@
-// Damping, activation ordering and the Cholesky-based inverse factor (Sec. 4.2.1 of the paper:
-// lambda = eta * mean(diag H), Cholesky of H + lambda I; Sec. 4.2: optional "actorder").
+// Damping, activation ordering and the Cholesky-based inverse factor (Sec. 4.3.1 of the paper:
+// lambda = eta * mean(diag H), Cholesky of H + lambda I; Sec. 4.3: optional "actorder").
 //
 // Wanted: upper-triangular U, positive diagonal, U^T U = Hd^-1 for the damped (permuted) matrix Hd.
 // Route: let R be Hd with both index orders reversed, R = L L^T its lower Cholesky factor and

@@ -1,4 +1,4 @@
-// Gram / Hessian accumulation  H += 2 X^T X  (Sec. 2.5 and Sec. 4.2 of the paper: H_l = X_l^T X_l,
+// Gram / Hessian accumulation  H += 2 X^T X  (Sec. 2.5 and Sec. 4.3 of the paper: H_l = X_l^T X_l,
 // rows of X are token activations; the factor 2 makes it the Hessian of the layer objective).
 //
 // gfx950 design

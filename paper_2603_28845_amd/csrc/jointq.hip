@@ -1,4 +1,4 @@
-// JointQ (Sec. 4.2.2 of the paper, Eq. (jointq)): local search over the integer codes of a solution in the per-group
+// JointQ (Sec. 4.3.2 of the paper, Eq. (jointq)): local search over the integer codes of a solution in the per-group
 // format of Eq. (4), the scale of the touched group refit in the same move.  Per output row the objective is
 // f = r A r^T with r = w - w^ and A = H + lam I (Eq. (jointq_reg): the regularizer is an augmented input).
 //

@@ -1,4 +1,4 @@
-// Corrected quantization target of error propagation (QEP, Sec. 4.2.1 of the paper, Eq. (qep)):
+// Corrected quantization target of error propagation (QEP, Sec. 4.3.1 of the paper, Eq. (qep)):
 //     W* = (I + alpha (H^ + lambda I)^-1 C) W        (paper: W is d_in x d_out, C = X^^T (X - X^))
 // In this library's d_out x d_in storage, with H = 2 X^^T X^ and G = 2 X^^T X (so 2 C = G - H) and the factor
 // U of onecomp_hessian_factor, U^T U = (H + lambda I)^-1 in sweep order:

@@ -1,4 +1,4 @@
-// Column sweep of the layer-wise quantizer (Sec. 4.2 of the paper: quantize one column, propagate its
+// Column sweep of the layer-wise quantizer (Sec. 4.3 of the paper: quantize one column, propagate its
 // residual to the columns not yet quantized) on the per-group asymmetric min-max grid (Eq. (1), (2), (4)).
 //
 // Per output row, for sweep positions j = 0 .. d_in-1:
@@ -161,7 +161,7 @@ struct PanelArgs {
     int mse;                // scale search: the group's range is shrunk by 1 - i / 100, i < 80; least squared error wins
 };
 
-// Scale search of one group ("mse" option of Sec. 4.2).  partial(z, 1 / s) returns the sum of ((w - w^) / s)^2 over
+// Scale search of one group ("mse" option of Sec. 4.3).  partial(z, 1 / s) returns the sum of ((w - w^) / s)^2 over
 // this lane's values of the group on the grid (s, z) (mse_term per value); reduce(x) sums x over the lanes that share
 // the group.  Candidate i takes (s, z) by the grid's rule from the range shrunk by p_i = 1 - i / 100; the first
 // smallest error wins, candidate 0 is the plain rule.  All lanes of the group end with the same (s, z).

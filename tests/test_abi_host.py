@@ -120,6 +120,10 @@ def test_quantize_argument_checks(lib):
     assert call(ws=NULL) == WORKSPACE
     assert call(wsb=ctypes.c_size_t(16)) == WORKSPACE
     assert call(d_in=65536 + 128) == INVALID    # beyond the 16-bit column limit of the sweep
+    assert call(W=ctypes.c_void_p(0x10004)) == INVALID      # misaligned W / U (16 bytes), Q_codes (4), W_hat (16)
+    assert call(U=ctypes.c_void_p(0x10008)) == INVALID
+    assert call(Q=ctypes.c_void_p(0x10002)) == INVALID
+    assert call(wh=ctypes.c_void_p(0x10004)) == INVALID
 
 
 def test_crossgram_argument_checks(lib):
@@ -241,6 +245,8 @@ def test_sensitivity_argument_checks(lib):
     assert call(W=NULL) == INVALID
     assert call(a=NULL) == INVALID
     assert call(err=NULL) == INVALID
+    assert call(W=ctypes.c_void_p(0x10004)) == INVALID     # W and a_diag are read with 16-byte loads
+    assert call(a=ctypes.c_void_p(0x10008)) == INVALID
     assert call(ws=NULL) == WORKSPACE
     assert call(wsb=ctypes.c_size_t(8)) == WORKSPACE
     assert lib.onecomp_sensitivity_workspace_bytes() >= 4
@@ -295,6 +301,10 @@ def test_jointq_argument_checks(lib):
     assert call(n_pass=-1) == INVALID
     assert call(scans=0) == INVALID
     assert call(G=96) == INVALID                     # does not divide d_in
+    assert call(W=ctypes.c_void_p(0x10004)) == INVALID      # misaligned W (16 bytes), H (16), Q_codes (4), W_hat (16)
+    assert call(H=ctypes.c_void_p(0x10008)) == INVALID
+    assert call(Q=ctypes.c_void_p(0x10002)) == INVALID
+    assert call(wh=ctypes.c_void_p(0x10004)) == INVALID
     assert call(ws=NULL) == WORKSPACE
     assert call(wsb=ctypes.c_size_t(1024)) == WORKSPACE
     g = lib.onecomp_jointq_workspace_bytes

@@ -1,4 +1,4 @@
-"""GPU parity of onecomp_jointq_refine (Sec. 4.2.2) against the oracle's local search from the same start."""
+"""GPU parity of onecomp_jointq_refine (Sec. 4.3.2) against the oracle's local search from the same start."""
 import numpy as np
 import pytest
 import torch

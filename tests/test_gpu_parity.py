@@ -496,7 +496,7 @@ def test_sweep_symmetric_all_zero_group():
     (4, 1152, 33, 1152, torch.float32, False, "symmetric_mse", True),
 ])
 def test_sweep_scale_search(bits, G, d_out, d_in, dtype, act, grid, block):
-    """Grid with the scale search (Sec. 4.2, "mse") against the oracle's sweep with the same search."""
+    """Grid with the scale search (Sec. 4.3, "mse") against the oracle's sweep with the same search."""
     _announce(f"sweep with scale search b{bits} g{G} {d_out}x{d_in} {dtype} act={act} {grid} block={block}")
     if block:
         W, U32, F32, perm = _layer_block(d_out, d_in, 2 * d_in + 13, seed=120 + bits + G % 5, dtype=dtype, act=act)

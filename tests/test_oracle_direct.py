@@ -1,7 +1,7 @@
 """Pins for the form of the sweep that needs one Cholesky factor only (oracle.direct_factor /
 block_feedback_factor / quantize_layer_direct).
 
-The paper's sweep (Sec. 4.2) propagates e_j U_jk with U^T U = (H + lambda I)^-1.  The direct form uses
+The paper's sweep (Sec. 4.3) propagates e_j U_jk with U^T U = (H + lambda I)^-1.  The direct form uses
 R = U^-1 instead; it must reproduce the sweep's codes, grid parameters and loss.  The pins below fix R by what
 defines it (triangular, positive diagonal, R R^T = Hd, R U = I with U from the independent two-Cholesky route),
 the closed form of the 2 x 2 case, and the sweep identity on random layers, act-order and both grids included.

@@ -1,4 +1,4 @@
-"""Pins of the oracle's JointQ local search (Sec. 4.2.2, Eq. (jointq)): hand-worked moves, the gain formula against
+"""Pins of the oracle's JointQ local search (Sec. 4.3.2, Eq. (jointq)): hand-worked moves, the gain formula against
 least squares on the data matrix itself, monotone descent, scale optimality, local optimality at convergence,
 brute force over every code assignment of a tiny group, and the regularizer as an augmented input (Eq. (jointq_reg))."""
 import itertools

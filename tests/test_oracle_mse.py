@@ -1,6 +1,6 @@
 """Pins for the scale search of the sweep (oracle.mse_search and the scale_search="mse" option).
 
-The paper names the option (Sec. 4.2, "MSE-based grid tuning (mse), which searches over candidate scales to minimize
+The paper names the option (Sec. 4.3, "MSE-based grid tuning (mse), which searches over candidate scales to minimize
 the mean squared reconstruction error per-group") without a candidate set; this build's reading shrinks the observed
 range by p_i = 1 - i / 100, i = 0 .. 79.  Pinned by hand-worked cases (tests/golden/mse_hand_worked.json), by the
 special cases that reduce to the plain rule, by invariants, and against the independent whole-array routine."""

@@ -1,4 +1,4 @@
-"""Pins for the oracle's error-propagation (QEP) functions, Sec. 4.2.1 of the paper: the corrected target is
+"""Pins for the oracle's error-propagation (QEP) functions, Sec. 4.3.1 of the paper: the corrected target is
 checked against what Eq. (qep_obj) and Eq. (qep) fix independently of the oracle's own formula."""
 import numpy as np
 

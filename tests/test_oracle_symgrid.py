@@ -1,4 +1,4 @@
-"""Pins for the oracle's symmetric grid (Sec. 2.2.2, Eq. (3)): z fixed, signed codes, s = max|w| / (2^(b-1) - 1)."""
+"""Pins for the oracle's symmetric grid (Sec. 2.3.2, Eq. (3)): z fixed, signed codes, s = max|w| / (2^(b-1) - 1)."""
 import numpy as np
 import pytest
 
