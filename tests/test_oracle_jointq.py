@@ -169,3 +169,102 @@ def test_symmetric_grid_zero_group_rows_subset_and_forced_decisions():
     assert not (np.array_equal(f["Q"], g["Q"]) and np.array_equal(f["scales"], g["scales"]))
     same = f if taken else g                      # forcing a decision the way it fell changes nothing
     assert np.array_equal(same["Q"][0], o["Q"][row]) and np.allclose(same["scales"][0], o["scales"][row], rtol=1e-12)
+
+
+def test_column_order_is_the_search_on_permuted_inputs():
+    """jointq_refine(perm=p) is the search run on W[:, p], A[p][:, p], Q[:, p] in natural order, un-permuted: groups,
+    scan order, scales and zeros follow the sweep's column order, W, A, Q and W_hat stay in the original one."""
+    X, W, H, _, _, _ = _problem(11, 5, 48, 16, 3)
+    rng = np.random.default_rng(12)
+    p = rng.permutation(48)
+    # a start in the format the sweep returns under a column order: groups are runs of the permuted order
+    Qp, s, z, _ = oc.rtn_quantize(W[:, p], 3, 16)
+    Q = np.empty_like(Qp)
+    Q[:, p] = Qp
+    a = oc.jointq_refine(W, H, Q, s, z, 3, 16, n_pass=2, max_scans=3, perm=p, tie_tol=1e-3)
+    b = oc.jointq_refine(W[:, p], H[np.ix_(p, p)], Qp, s, z, 3, 16, n_pass=2, max_scans=3, tie_tol=1e-3)
+    assert a["moves"].sum() > 0
+    assert np.array_equal(a["Q"][:, p], b["Q"]) and np.array_equal(a["scales"], b["scales"])
+    assert np.array_equal(a["W_hat"][:, p], b["W_hat"])
+    assert np.array_equal(a["moves"], b["moves"]) and a["ties"] == b["ties"]
+    assert np.allclose(a["f0"], b["f0"], rtol=1e-13) and np.allclose(a["f1"], b["f1"], rtol=1e-13)
+    # the returned arrays mean what they say in the ORIGINAL order, independently of how perm is implemented
+    assert np.array_equal(a["W_hat"], oc.dequantize(a["Q"], a["scales"], z, 16, perm=p))
+    assert np.allclose(a["f1"], 2.0 * ((X @ (W - a["W_hat"]).T) ** 2).sum(axis=0), rtol=1e-10)
+    # and a different order gives a different search (the order matters)
+    c = oc.jointq_refine(W, H, Q, s, z, 3, 16, n_pass=2, max_scans=3)
+    assert not np.array_equal(a["Q"], c["Q"])
+
+
+def _first_decision_terms(X, W, H, Q, s, z, G, i):
+    """Row i, first decision of the search (pass 0, group 0, scan 0, column 0, +1), from the definitions: the gain
+    N = c' (f_before - f_after) with both objectives by least squares on the data, and the two sums the listing
+    rule weighs (sum_k |r_k| |A_k0| and |s*| sum_k |u_k| |A_k0| over the group)."""
+    q = Q[i].astype(np.float64)
+    f_before, st = _lstsq_objective(X, W[i], q, s[i], z[i], G, 0)
+    q2 = q.copy()
+    q2[0] += 1.0
+    f_after, _ = _lstsq_objective(X, W[i], q2, s[i], z[i], G, 0)
+    u2 = q2[:G] - z[i, 0]
+    c_new = float(u2 @ H[:G, :G] @ u2)
+    r = W[i] - np.repeat(s[i], G) * (q - np.repeat(z[i], G))
+    u = q[:G] - z[i, 0]
+    b = float(u @ (H[:G] @ r + s[i, 0] * (H[:G, :G] @ u)))
+    g_sum = float(np.abs(r) @ np.abs(H[:, 0]))
+    a_sum = abs(st) * float(np.abs(u) @ np.abs(H[:G, 0]))
+    return c_new * (f_before - f_after), b, g_sum, a_sum
+
+
+def test_listing_tolerances_only_list_and_forcing_a_listed_decision_changes_only_it():
+    """tie_tol / g_tol / a_tol decide which decisions are LISTED as toss-ups, never the result; the list grows with
+    each tolerance; a decision that only g_tol (or a_tol) lists can be forced the other way, and then every decision
+    before it is the same and that one is not; for the first decision of a row the listing rule is evaluated from
+    the definitions (least squares on the data)."""
+    X, W, H, Q, s, z = _problem(13, 8, 32, 16, 3)
+    kw = dict(bits=3, group_size=16, n_pass=1, max_scans=2)
+    plain = oc.jointq_refine(W, H, Q, s, z, **kw)
+    runs = {}
+    for name, tol in (("t", dict(tie_tol=1e-9)), ("tg", dict(tie_tol=1e-9, g_tol=3e-3)),
+                      ("ta", dict(tie_tol=1e-9, a_tol=3e-3)), ("tga", dict(tie_tol=1e-9, g_tol=3e-3, a_tol=3e-3)),
+                      ("big", dict(tie_tol=1e-9, g_tol=1e9))):
+        o = oc.jointq_refine(W, H, Q, s, z, **kw, **tol)
+        assert np.array_equal(o["Q"], plain["Q"]) and np.array_equal(o["scales"], plain["scales"])
+        runs[name] = [set(t[:5] for t in row) for row in o["ties"]]
+        assert all(len(set(t[:5] for t in row)) == len(row) for row in o["ties"])      # a decision is listed once
+    for i in range(8):
+        assert runs["t"][i] <= runs["tg"][i] <= runs["tga"][i] and runs["t"][i] <= runs["ta"][i] <= runs["tga"][i]
+        assert runs["tga"][i] <= runs["big"][i]
+    assert sum(len(r) for r in runs["tg"]) > sum(len(r) for r in runs["t"])
+    assert sum(len(r) for r in runs["ta"]) > sum(len(r) for r in runs["t"])
+    # an unbounded tolerance lists every decision that was evaluated: at least one per column and scan entered
+    assert all(len(r) >= 32 for r in runs["big"])
+    # the rule itself, on the first decision of every row, from the definitions
+    for i in range(8):
+        if not np.any(Q[i, :16] - z[i, 0]) or Q[i, 0] + 1 > 7:
+            continue
+        N, b, g_sum, a_sum = _first_decision_terms(X, W, H, Q, s, z, 16, i)
+        key = (0, 0, 0, 0, 1)
+        for g_tol, a_tol in ((3e-3, 0.0), (0.0, 3e-3), (1e-5, 1e-5), (0.3, 0.0)):
+            o = oc.jointq_refine(W, H, Q, s, z, rows=[i], tie_tol=1e-300, g_tol=g_tol, a_tol=a_tol, **kw)
+            bound = 2.0 * abs(b) * (g_tol * g_sum + a_tol * a_sum)
+            if abs(abs(N) - bound) > 1e-6 * bound:                      # away from the edge of the rule
+                assert (key in set(t[:5] for t in o["ties"][0])) == (abs(N) <= bound), (i, N, bound)
+    # forcing a decision that only g_tol (resp. a_tol) lists; one scan, so that no later scan can undo the move and
+    # the code of that column shows the decision
+    kw1 = dict(bits=3, group_size=16, n_pass=1, max_scans=1)
+    for name in ("tg", "ta"):
+        tol = dict(tie_tol=1e-9, g_tol=5e-2) if name == "tg" else dict(tie_tol=1e-9, a_tol=5e-2)
+        listed = [set(t[:5] for t in row) for row in oc.jointq_refine(W, H, Q, s, z, **kw1, **tol)["ties"]]
+        strict = [set(t[:5] for t in row) for row in oc.jointq_refine(W, H, Q, s, z, **kw1, tie_tol=1e-9)["ties"]]
+        i = next(r for r in range(8) if listed[r] - strict[r])
+        key = sorted(listed[i] - strict[i])[0]
+        base = oc.jointq_refine(W, H, Q, s, z, rows=[i], **kw1, **tol)
+        taken = {t[:5]: t[5] for t in base["ties"][0]}[key]
+        flip = oc.jointq_refine(W, H, Q, s, z, rows=[i], forced={(0,) + key: not taken}, **kw1, **tol)
+        before = [t for t in base["ties"][0] if t[:5] < key]
+        assert [t for t in flip["ties"][0] if t[:5] < key] == before     # nothing before it changes
+        col = key[1] * 16 + key[3]
+        assert np.array_equal(flip["Q"][0, :col], base["Q"][0, :col])
+        assert flip["Q"][0, col] != base["Q"][0, col]                    # and that decision does
+        same = oc.jointq_refine(W, H, Q, s, z, rows=[i], forced={(0,) + key: taken}, **kw1, **tol)
+        assert np.array_equal(same["Q"], base["Q"]) and np.array_equal(same["scales"], base["scales"])

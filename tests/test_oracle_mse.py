@@ -117,3 +117,30 @@ def test_sweep_records_and_replays_candidates():
     other = oc.quantize_layer(W, f["U"], 3, 16, scale_search="mse", forced_cand=fc2)
     assert other["scales"][2, 1] != out["scales"][2, 1] and np.array_equal(other["scales"][2, 0], out["scales"][2, 0])
     assert np.array_equal(np.delete(other["Q"], 2, axis=0), np.delete(out["Q"], 2, axis=0))
+
+
+@pytest.mark.parametrize("case", json.load(open(GOLDEN))["alt_cases"], ids=lambda c: c["name"][:40])
+def test_other_neighbour_of_the_zero_point_hand_worked(case):
+    """z_alt / err_alt (what the parity protocol may charge a candidate whose zero-point sits at a rounding tie)."""
+    m = oc.mse_search(np.array([case["w"]], dtype=np.float64), case["bits"], case["grid"], n_cand=case["n_cand"],
+                      step=case["step"])
+    assert np.allclose(m["tz_all"][0], case["tz_all"], rtol=1e-12)
+    assert m["z_all"][0].tolist() == case["z_all"] and m["z_alt"][0].tolist() == case["z_alt"]
+    assert np.allclose(m["err"][0], case["err"], rtol=1e-12) and np.allclose(m["err_alt"][0], case["err_alt"], rtol=1e-12)
+    assert int(m["cand"][0]) == case["cand"]
+
+
+def test_other_neighbour_is_the_other_integer_next_to_tz():
+    rng = np.random.default_rng(9)
+    v = rng.standard_normal((200, 16)) + 0.3
+    m = oc.mse_search(v, 3, "asym")
+    tz, z, za = m["tz_all"], m["z_all"], m["z_alt"]
+    inside = (tz > 0.0) & (tz < 7.0) & (np.abs(tz - np.rint(tz)) > 1e-9)
+    assert inside.any()
+    lo, hi = np.floor(tz), np.ceil(tz)
+    assert np.all(((z == lo) & (za == hi) | (z == hi) & (za == lo))[inside])
+    assert np.all(np.abs(tz - z)[inside] <= np.abs(tz - za)[inside])          # z is the nearer one
+    # its error is the error of Eq. (1) on the grid (s, z_alt), recomputed here without the search
+    for i, c in ((0, 0), (5, 17), (11, 79)):
+        q = np.clip(np.rint(v[i] / m["s_all"][i, c]) + za[i, c], 0, 7)
+        assert np.isclose(m["err_alt"][i, c], ((v[i] - m["s_all"][i, c] * (q - za[i, c])) ** 2).sum(), rtol=1e-12)
