@@ -61,8 +61,8 @@ typedef enum {
  * The _MSE variants add the scale search of Sec. 4.3 (the sweep's "mse" option): when a group's parameters are
  * fixed, its range [lo, hi] is shrunk to p_i [lo, hi], p_i = 1 - i / 100 for i = 0 .. 79, (s, z) follow from the
  * shrunk range by the grid's own rule, and the candidate with the least sum over the group of (w - s (q - z))^2
- * (q rounded and clamped as in the sweep) is kept, the lowest i on equal sums; i = 0 is the plain grid.  The search
- * runs in fp32 on the compensated values. */
+ * (q rounded and clamped as in the sweep) is kept, the lowest i on equal sums; i = 0 is the plain grid.  The
+ * candidates are compared in fp32 on the compensated values; the winner's scale is then taken in fp64. */
 typedef enum {
     ONECOMP_GRID_MINMAX = 0,
     ONECOMP_GRID_SYMMETRIC = 1,
@@ -166,11 +166,16 @@ onecomp_status onecomp_hessian_factor_form(const float* H, int64_t d_in, float d
  *     z = clamp(rne(-min / s), 0, 2^bits - 1)
  *   q_j = clamp(rne(w_j / s) + z, 0, 2^bits - 1),  w^_j = s (q_j - z)
  *   e_j = (w_j - w^_j) / U_jj,   w_k -= e_j U_jk  for all later columns k
- * rne = round half to even.  Arithmetic: fp32.  w_j / s and the division by U_jj are multiplications by
- * correctly rounded reciprocals.  Feedback that crosses a 128-column block is accumulated as
- * (w_j - w^_j) * (U_jk / U_jj) with both factors rounded to 22 significant bits (two fp16 halves after an
- * exact power-of-two scaling taken from max |W| and max |U_jk / U_jj|) and the sum kept in fp32; a residual
- * above 8 max|W|, which no sweep of a sane layer produces, would saturate.
+ * rne = round half to even.  Arithmetic: the value that is rounded has to match exact arithmetic to a small
+ * fraction of a grid step over thousands of columns (one wrong rounding at a near-tie changes the rest of its row),
+ * so the compensated weight is never held in fp32: the original weight (exact) and the feedback sum
+ * c_j = -sum_{i<j} e_i U_ij (a fraction of a grid step) are kept apart, c in fp32; inside a 32-column inner block
+ * w = w0 + c, the scale (fp64 division; returned rounded to fp32), the decision rne(w * fl64(1 / s)) and the feedback
+ * run in fp64.  Feedback that crosses an inner block is accumulated from zero (fp32 MFMA inside a 128-column block;
+ * across blocks as (w_j - w^_j) * (U_jk / U_jj) with both factors rounded to 22 significant bits: two fp16 halves
+ * after an exact power-of-two scaling taken from max |W| and max |U_jk / U_jj|, fp32 accumulation) and added to c
+ * once.  A residual above 8 max|W|, which no sweep of a sane layer produces, would saturate on its way into the fp16
+ * halves: `loss` then comes back as +infinity.
  *
  *   W          [d_out x d_in] row-major (dense, stride d_in), dtype w_dtype, ORIGINAL column order. Read only.
  *   U          [d_in x d_in] fp32, as written by onecomp_hessian_factor. Read only.
@@ -189,8 +194,8 @@ onecomp_status onecomp_hessian_factor_form(const float* H, int64_t d_in, float d
  *              tr((W - W^) H_d (W - W^)^T) for the damped (permuted) matrix behind U (Eq. (layerwise)).
  *              Reduced in a fixed order (bit-wise reproducible).
  *   workspace  device scratch, >= onecomp_quantize_workspace_bytes(d_out, d_in, block_size), 256-byte aligned
- *              (about 9 d_out d_in + 4 d_in^2 bytes: two fp32 copies of W, codes staged in sweep order, two fp16
- *              halves of the scaled U).
+ *              (about 9 d_out d_in + 4 d_in^2 bytes: the fp32 feedback sums, an fp32 copy of W gathered into sweep
+ *              order, codes staged in sweep order, two fp16 halves of the scaled U).
  *   d_in       at most 65535, d_out at most 2^24.
  *   W, U and W_hat must be 16-byte aligned, Q_codes 4-byte aligned (ONECOMP_ERR_INVALID_ARG otherwise).
  */
@@ -224,7 +229,7 @@ onecomp_status onecomp_quantize_layer_grid(const void* W, onecomp_dtype w_dtype,
  * form: inside a 128-column block the steps are those of onecomp_quantize_layer (F holds U there); between blocks
  * the workspace accumulates c_k = sum_i (w_i - w^_i) R_ik / R_kk over the finished columns i of earlier blocks
  * (deviations from the ORIGINAL weights; 22-bit operands, fp32 sum, as described at onecomp_quantize_layer) and a
- * block starts from  w_b + c (U_bb rows divided by their diagonal)  in fp32.  Outputs and their meaning are
+ * block starts from  w_b + c (U_bb rows divided by their diagonal), the product in fp32 from zero, the sum in fp64.  Outputs and their meaning are
  * unchanged; results agree with the inverse form up to rounding.  ONECOMP_FACTOR_BLOCK needs group_size <= 128 or
  * group_size == d_in (one group per row, whose grid comes from the original weights); other wide groups take their
  * grid from columns of later blocks, whose compensated values this form does not hold: ONECOMP_ERR_UNSUPPORTED.

@@ -17,38 +17,17 @@
 //     launched one round of tiles (one per CU) at a time, so that those 32 also stay together along the tokens.
 //   * fp32 path (small layers): 128-wide tiles on v_mfma_f32_32x32x2_f32, products in fp32.
 #include "common.hpp"
+#include "planner.hpp"
 
 namespace onecomp {
 namespace {
 
 constexpr int GRAM_THREADS = 256;
-constexpr int BAND = 4;  // tile rows per band in the workgroup -> tile order
-
-// rank v in the banded order -> (ti, tk), ti <= tk < n_t
-__device__ inline void tile_from_rank(int v, int n_t, int& ti, int& tk) {
-    int a = 0;
-    while (true) {
-        int rows = min(BAND, n_t - a * BAND);
-        int cols = n_t - a * BAND;
-        int cnt = rows * cols - rows * (rows - 1) / 2;
-        if (v < cnt) {
-            int tri = rows * (rows + 1) / 2;
-            if (v < tri) {
-                int c = 0;
-                while ((c + 1) * (c + 2) / 2 <= v) ++c;
-                tk = a * BAND + c;
-                ti = a * BAND + (v - c * (c + 1) / 2);
-            } else {
-                int w = v - tri;
-                tk = a * BAND + rows + w / rows;
-                ti = a * BAND + w % rows;
-            }
-            return;
-        }
-        v -= cnt;
-        ++a;
-    }
-}
+using plan::tile_from_rank;       // workgroup -> tile maps: planner.hpp
+using plan::tile128_from_rank;
+using plan::SplitPlan;
+using plan::plan_split;
+constexpr int BAND = plan::GRAM_BAND;
 
 // -------------------------------------------------------------------------------------------
 // Epilogue shared by the bf16 kernels: H[i][k] += 2 acc for this wave's MT x NT tiles of 32 x 32 and the
@@ -359,20 +338,6 @@ struct Ring {
     static_assert((NL_A + NL_B) % WAVES == 0 && NL_A % WAVES == 0, "whole loads per wave, A loads first");
     static_assert(MT * NT == 8 && MT + NT == 6, "schedule below is written for 8 MFMAs and 6 fragments per step");
 };
-constexpr int RBAND = 8;   // 128-wide tile rows per band of the RingMid tile order
-
-// rank v -> RingMid tile (ti, tk): bands of RBAND tile rows, inside a band column by column, rows fastest
-__device__ inline void tile128_from_rank(int v, int n_rt, int n_ct, int& ti, int& tk) {
-    for (int a = 0;; ++a) {
-        const int r0 = a * RBAND, rows = min(RBAND, n_rt - r0);
-        for (int k = r0 / 2; k < n_ct; ++k) {
-            const int valid = min(rows, 2 * k + 2 - r0);   // rows r0 .. r0+valid-1 satisfy i / 2 <= k
-            if (v < valid) { ti = r0 + v; tk = k; return; }
-            v -= valid;
-        }
-    }
-}
-
 // CROSS = false: H += 2 X^T X, tiles on or above the diagonal, mirrored.  CROSS = true: H += 2 X^T Xb for two
 // different matrices (A panels from X, B panels from Xb), every tile, no mirror.
 template <typename C, bool CROSS>
@@ -391,38 +356,20 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
     // partial sum (gram_store_half); with one, every piece stores its sum there and gram_reduce_kernel adds them.
     // bid: rank of this workgroup in the whole schedule; a launch covers a run of ranks starting at bid0
     const int bid = int(blockIdx.x) + bid0;
-    int v, piece = -1, m_split = 0;
-    if (bid < 8 * chunk) {
-        v = (bid & 7) * chunk + (bid >> 3);
-        if (v >= n_tiles - n_split) return;
-        if (v >= split0) v += n_split;
-    } else {
-        // on an XCD the pieces run tile after tile for one range of tokens, then for the next: workgroups that are
-        // resident together then read the same tokens and share their column panels through the L2
-        const int b = bid - 8 * chunk, per_xcd = (n_split + 7) >> 3, j = b >> 3;
-        m_split = (b & 7) * per_xcd + j % per_xcd;
-        if (m_split >= n_split) return;
-        v = split0 + m_split;
-        piece = j / per_xcd;
-    }
+    plan::RingWork rw;
+    if (!plan::ring_work(bid, chunk, n_tiles, split0, n_split, rw)) return;
+    const int v = rw.v, piece = rw.piece, m_split = rw.m_split;
     if (piece >= 0) {   // this workgroup's share of the tokens: whole steps of KT
-        const int64_t n_st_all = (n_tokens + KT - 1) / KT;
-        const int64_t t_piece = (n_st_all + n_piece - 1) / n_piece * KT, t_begin = piece * t_piece;
+        int64_t t_begin, count;
+        plan::piece_tokens(n_tokens, n_piece, piece, KT, t_begin, count);
         X += t_begin * ldx;
         Xb += t_begin * ldxb;
-        n_tokens = n_tokens - t_begin < t_piece ? n_tokens - t_begin : t_piece;   // <= 0: nothing left, the sum is 0
+        n_tokens = count;   // <= 0: nothing left, the sum is 0
     }
     int ti, tk;
-    if constexpr (CROSS) {   // all tiles: bands of 4 tile rows, column by column inside a band
-        const int band = min(v / (BAND * n_ct), (n_rt - 1) / BAND);
-        const int w = v - band * BAND * n_ct, rows = min(BAND, n_rt - band * BAND);
-        tk = w / rows;
-        ti = band * BAND + w % rows;
-    } else if constexpr (C::TM == C::TN) {
-        tile_from_rank(v, n_ct, ti, tk);
-    } else {
-        tile128_from_rank(v, n_rt, n_ct, ti, tk);
-    }
+    if constexpr (CROSS) plan::cross_tile_from_rank(v, n_rt, n_ct, ti, tk);
+    else if constexpr (C::TM == C::TN) tile_from_rank(v, n_ct, ti, tk);
+    else tile128_from_rank(v, n_rt, n_ct, ti, tk);
     const int i0 = ti * C::TM, k0 = tk * C::TN;
     const bool diag = !CROSS && k0 < i0 + C::TM;   // some entry of the tile lies on or below the diagonal
     const int tid = threadIdx.x, lane = tid & 63;
@@ -736,47 +683,7 @@ onecomp_status launch_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_
 
 
 
-// Which 256 x 256 tiles of the symmetric Gram are computed in pieces of the token axis, and the estimated
-// duration of the launch in units of one whole tile on one CU.
 constexpr size_t GRAM_SLOT_BYTES = size_t(256) * 256 * sizeof(float);   // one partial sum of a 256 x 256 tile
-struct SplitPlan {
-    int split0 = 0, n_split = 0, n_piece = 1;
-    bool use_ws = false;
-    double rounds = 0.0;
-};
-
-// Without a workspace only two pieces per tile are possible (the second partial sum is parked in the tile's mirror
-// position), for tiles strictly above the diagonal and inside the matrix: the short last round is taken from the
-// rectangular part of the first band.  With a workspace any tile can be cut into 2 .. 16 pieces: either the tiles
-// left over after whole rounds, or all of them when there are fewer than two rounds.  A piece costs its share of
-// the tile plus about half a percent of a tile for filling the pipeline and storing the partial sum, and it must
-// keep at least 2048 tokens.
-// ws_slots: how many 256 x 256 partial sums the workspace holds (0: none).
-SplitPlan plan_split(int64_t n_tiles, int64_t n_ct, int64_t d_in, int64_t n_tokens, int n_cus, int64_t ws_slots) {
-    SplitPlan best;
-    best.rounds = double(ceil_div(n_tiles, n_cus));
-    const int64_t r = n_tiles % n_cus;
-    if (r > 0 && r <= n_cus / 2 && n_tokens >= 1024 && n_ct >= BAND + ceil_div(r, BAND) &&
-        (BAND + ceil_div(r, BAND)) * 256 <= d_in) {
-        best.split0 = BAND * (BAND + 1) / 2;
-        best.n_split = int(r);
-        best.n_piece = 2;
-        best.rounds = double(n_tiles / n_cus) + 0.5 * 1.06;
-    }
-    for (int pc = 2; pc <= 16; ++pc) {
-        if (n_tokens / pc < 2048) break;
-        const double piece_cost = 1.0 / pc + 0.005;
-        if (r > 0 && n_tiles > n_cus && r * pc <= ws_slots) {   // the leftover tiles, from the end of the rank order
-            const double rounds = double(n_tiles / n_cus) + double(ceil_div(r * pc, n_cus)) * piece_cost;
-            if (rounds < best.rounds) best = SplitPlan{int(n_tiles - r), int(r), pc, true, rounds};
-        }
-        if (n_tiles < 2 * n_cus && n_tiles * pc <= ws_slots) {   // every tile
-            const double rounds = double(ceil_div(n_tiles * pc, n_cus)) * piece_cost;
-            if (rounds < best.rounds) best = SplitPlan{0, int(n_tiles), pc, true, rounds};
-        }
-    }
-    return best;
-}
 
 template <typename C, bool CROSS>
 onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens, int64_t d_in, int64_t ldx,
@@ -786,7 +693,7 @@ onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens,
     int n_tiles = 0;
     if (CROSS) n_tiles = n_rt * n_ct;
     else if (C::TM == C::TN) n_tiles = n_ct * (n_ct + 1) / 2;
-    else for (int i = 0; i < n_rt; ++i) n_tiles += n_ct - i / 2;
+    else n_tiles = plan::n_tiles128(n_rt, n_ct);
     // tiles computed in pieces of the token axis, dispatched after the whole tiles (see plan_split)
     SplitPlan sp;
     if (!CROSS && C::TM == 256 && C::TN == 256) {
@@ -804,7 +711,7 @@ onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens,
     // together, so the tiles an XCD works on walk through the tokens side by side and share their column panels in
     // its L2; in a single launch of many rounds the workgroups of later rounds start whenever a CU falls free and
     // drift apart (L2 hit rate 59 % against 78 % for a round on its own; 46.2 -> 44.7 ms at d_in 14336, 262144 tokens).
-    const int total = chunk * 8 + 8 * sp.n_piece * int(ceil_div(n_split, 8));
+    const int total = plan::ring_total_blocks(chunk, n_split, sp.n_piece);
     const int n_cus_r = device_cus();
     const int per_launch = (C::TM == 256 && C::TN == 256 && n_cus_r > 0 && n_cus_r % 8 == 0 && chunk * 8 >= 2 * n_cus_r)
                                ? n_cus_r : total;

@@ -5,8 +5,16 @@
 //   group start:  s = (max - min) / (2^b - 1) of the current values of the group (1 if max == min),
 //                 z = clamp(rne(-min / s), 0, 2^b - 1)
 //   q = clamp(rne(w_j / s) + z, 0, 2^b - 1),  w^ = s (q - z),  e = (w_j - w^) / U_jj
-//   (w_j / s and the division by U_jj are multiplications by correctly rounded reciprocals),
+//   (w_j / s and the division by U_jj are multiplications by correctly rounded fp64 reciprocals),
 //   w_k -= e U_jk for k > j.
+//
+// Precision.  A code is rne(w_j / s); one wrong rounding at a near-tie changes the rest of its row, so the value
+// that is rounded has to agree with exact arithmetic to about 1e-7 of a grid step over thousands of columns.  The
+// library therefore never stores the compensated weight w_j itself in fp32.  It keeps the ORIGINAL weight (exact)
+// and, apart from it, the feedback sum  c_j = -sum_{i<j} e_i U_ij  (a fraction of a grid step, so its fp32 rounding
+// is ~1e-8 of a step): the working copy in memory holds c, every MFMA accumulation starts from zero and is added
+// to c once, and inside a 32-column inner block the values w = w0 + c, the scale, the decision and the feedback
+// run in fp64 registers.
 //
 // gfx950 schedule (lazy batch of B = 128 columns inside super-blocks of up to 512 columns):
 //   panel kernel    64 rows per workgroup carried through the blocks of a super-block: the feedback between the
@@ -23,6 +31,7 @@
 //   The loss is the sum of e^2 (equal to tr((W-W^) Hd (W-W^)^T) because U Hd U^T = I), kept per row and
 //   reduced in a fixed order.
 #include "common.hpp"
+#include "planner.hpp"
 #include <type_traits>
 
 #pragma clang fp contract(off)
@@ -53,9 +62,14 @@ __device__ inline float to_f32<float>(float v) { return v; }
 template <>
 __device__ inline float to_f32<uint16_t>(uint16_t v) { return __uint_as_float(uint32_t(v) << 16); }
 
+// the sweep's scalars live in a 256-byte slot: the Scalars of its split products, then (offset 64) the flag that
+// a residual was saturated
+__device__ __host__ inline uint32_t* sat_flag(Scalars* sc) { return reinterpret_cast<uint32_t*>(sc) + 16; }
+
 __global__ void init_scalars_kernel(Scalars* sc) {
     sc->max_w_bits = 0u;
     sc->max_u_bits = 0u;
+    *sat_flag(sc) = 0u;
 }
 
 __device__ inline void block_max_to(uint32_t* dst, float v) {
@@ -77,16 +91,16 @@ template <typename T>
 __global__ __launch_bounds__(256) void load_kernel(const T* __restrict__ W, int64_t d_out, int64_t d_in,
                                                   const int32_t* __restrict__ perm, float* __restrict__ Wf,
                                                   float* __restrict__ rowloss, Scalars* __restrict__ sc,
-                                                  const int zero_fill, float* __restrict__ W0p) {
-    // zero_fill: the working copy starts as zeros (it then holds only the feedback, the weights are read from W, or,
-    // under a column order, from the gathered copy W0p written here)
+                                                  float* __restrict__ W0p) {
+    // The working copy Wf starts as zeros: it holds only the accumulated feedback; the weights themselves are read
+    // from W or, under a column order, from the gathered copy W0p written here.  Also max |W|.
     float m = 0.f;
     for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {   // a workgroup per row, rows strided over the grid
     if (threadIdx.x == 0) rowloss[r] = 0.f;
     if (perm) {
         for (int p = threadIdx.x; p < d_in; p += 256) {
             const float v = to_f32<T>(W[r * d_in + perm[p]]);
-            Wf[r * d_in + p] = zero_fill ? 0.f : v;
+            Wf[r * d_in + p] = 0.f;
             if (W0p) W0p[r * d_in + p] = v;
             m = fmaxf(m, fabsf(v));
         }
@@ -107,9 +121,7 @@ __global__ __launch_bounds__(256) void load_kernel(const T* __restrict__ W, int6
             }
 #pragma unroll
             for (int e = 0; e < V; e += 4) {
-                float4v o = {v[e], v[e + 1], v[e + 2], v[e + 3]};
-                if (zero_fill) o = float4v{0.f, 0.f, 0.f, 0.f};
-                *reinterpret_cast<float4v*>(Wf + r * d_in + p + e) = o;
+                *reinterpret_cast<float4v*>(Wf + r * d_in + p + e) = float4v{0.f, 0.f, 0.f, 0.f};
             }
 #pragma unroll
             for (int e = 0; e < V; ++e) m = fmaxf(m, fabsf(v[e]));
@@ -138,11 +150,13 @@ constexpr int IB = 32;          // columns swept in registers at a time
 // LDS tile sW holds current values; a finished column holds its code (as a float).
 // ------------------------------------------------------------------------------------------
 struct PanelArgs {
-    const float* Wf;            // [d_out x d_in] working copy (columns beyond the super-block are current up to the
-                                // previous super-block); block form: only the accumulated feedback c
-    const void* W0;             // block form: the layer's weights in sweep order (the caller's matrix, or the gathered
-                                // fp32 copy under a column order)
+    const float* Wf;            // [d_out x d_in] accumulated feedback c of the earlier super-blocks (block form: the
+                                // sums c_k = sum_i (w_i - w^_i) R_ik / R_kk)
+    const void* W0;             // the layer's weights in sweep order (the caller's matrix, or the gathered fp32 copy
+                                // under a column order)
     int w0_bf16;
+    const double* s64;          // [d_out] wide groups: the current group's scale in fp64 (group_params_kernel)
+    uint32_t* sat;              // set to 1 if a residual had to be saturated when it was split into fp16 halves
     const float* U;
     uint8_t* Q;                 // sweep order (the caller's array, or the staging copy under a column order)
     float* scales;
@@ -164,7 +178,10 @@ struct PanelArgs {
 // Scale search of one group ("mse" option of Sec. 4.3).  partial(z, 1 / s) returns the sum of ((w - w^) / s)^2 over
 // this lane's values of the group on the grid (s, z) (mse_term per value); reduce(x) sums x over the lanes that share
 // the group.  Candidate i takes (s, z) by the grid's rule from the range shrunk by p_i = 1 - i / 100; the first
-// smallest error wins, candidate 0 is the plain rule.  All lanes of the group end with the same (s, z).
+// smallest error wins, candidate 0 is the plain rule.  The candidates are compared in fp32; all lanes of the group
+// return the same index, from which the caller takes the scale in fp64 (grid_params), and the zero-point the
+// winner was evaluated with (at a rounding tie of -lo / s the fp64 rule might pick the other neighbour, whose
+// error was not the one compared).
 constexpr int MSE_CANDIDATES = 80;
 // one value's squared error in units of the scale: t = v / s + z, ((t - clamp(rne(t), 0, qmax)))^2; the caller
 // multiplies the sum by s^2.  (rne(v / s) + z and rne(v / s + z) agree except at exact ties, where both choices give
@@ -175,9 +192,11 @@ __device__ __forceinline__ float mse_term(float v, float zi, float rsi, float qm
     return d * d;
 }
 template <typename P, typename R>
-__device__ __forceinline__ void mse_search(const float mn, const float mx, const float qmax, const float qs,
-                                           P&& partial, R&& reduce, float& s, float& z) {
+__device__ __forceinline__ int mse_search(const float mn, const float mx, const float qmax, const float qs,
+                                          P&& partial, R&& reduce, float& zbest) {
     float best = 3.0e38f;
+    int ibest = 0;
+    zbest = 0.f;
 #pragma unroll 1
     for (int i = 0; i < MSE_CANDIDATES; ++i) {
         const float p = 1.0f - float(i) * 0.01f;
@@ -193,20 +212,56 @@ __device__ __forceinline__ void mse_search(const float mn, const float mx, const
             zi = fminf(fmaxf(rintf(-lo / si), 0.f), qmax);
         }
         const float err = si * si * reduce(partial(zi, 1.0f / si));
-        if (err < best) { best = err; s = si; z = zi; }
+        if (err < best) { best = err; ibest = i; zbest = zi; }
+    }
+    return ibest;
+}
+
+// Scale and zero-point of a group from the smallest and largest of its current values, in fp64: Eq. (2), or Eq. (3)
+// when qs > 0 (symmetric grid, zero-point qs); cand > 0: from the range shrunk by 1 - cand / 100 (scale search).
+__device__ __forceinline__ void grid_params(double mn, double mx, const int cand, const double qmax, const double qs,
+                                            double& s, double& z) {
+    if (cand > 0) {
+        const double p = 1.0 - double(cand) * 0.01;
+        mn *= p; mx *= p;
+    }
+    if (qs > 0.0) {
+        s = fmax(fabs(mn), fabs(mx)) / qs;
+        if (s == 0.0) s = 1.0;
+        z = qs;
+    } else {
+        s = (mx - mn) / qmax;
+        if (s == 0.0) s = 1.0;
+        z = fmin(fmax(rint(-mn / s), 0.0), qmax);
     }
 }
 
-constexpr int PANEL_LDS = (SB * SB + 2 * ROWS * SP + SB + 2 * ROWS * 8) * 4;
+constexpr int PANEL_LDS = (SB * SB + 2 * ROWS * SP + 2 * SB + 3 * ROWS * 8) * 4;
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_quad(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
+template <int CTRL>
+__device__ __forceinline__ double dpp_quad(double v) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = uint32_t(__builtin_amdgcn_update_dpp(0, int(uint32_t(u)), CTRL, 0xF, 0xF, true));
+    const uint32_t hi = uint32_t(__builtin_amdgcn_update_dpp(0, int(uint32_t(u >> 32)), CTRL, 0xF, 0xF, true));
+    return __builtin_bit_cast(double, (uint64_t(hi) << 32) | lo);
+}
 constexpr int quad_bcast(int o) { return o | (o << 2) | (o << 4) | (o << 6); }
 constexpr int QUAD_SWAP1 = 1 | (0 << 2) | (3 << 4) | (2 << 6);   // lanes 0<->1, 2<->3
 constexpr int QUAD_SWAP2 = 2 | (3 << 2) | (0 << 4) | (1 << 6);   // lanes 0<->2, 1<->3
 
+// What a block of 128 columns starts from.  The feedback of all earlier columns is kept apart from the weights:
+//   sC   (LDS, fp32)  c = -sum_i e_i U_i,col over the finished columns i: the part from earlier super-blocks comes
+//                     from the working copy (a.Wf), the part from the earlier blocks of this super-block from the
+//                     near update (split-fp16 MFMAs accumulated from zero), the part from the earlier inner blocks
+//                     of this block from fp32 MFMAs accumulated from zero; each part is added once in fp32;
+//   sE   (LDS, fp32)  an unfinished column holds its ORIGINAL weight w0 (exact: the input is bf16 or fp32); once the
+//                     column is finished the slot receives its error e (sC's slot its code).
+// The value that is quantized is w0 + c formed in fp64.
+//
 // DIRECT (block form of the factor): a.U holds U only on its 128 x 128 diagonal blocks and -U_jj R_jk / R_kk
 // elsewhere (R = U^-1).  The working copy then accumulates c_k = sum_i (w_i - w^_i) R_ik / R_kk over the finished
 // columns i of earlier blocks, where w are the ORIGINAL weights; a block starts from
@@ -217,11 +272,11 @@ constexpr int QUAD_SWAP2 = 2 | (3 << 2) | (0 << 4) | (1 << 6);   // lanes 0<->2,
 template <int GB, bool DIRECT>  // GB: group width seen inside an inner block: 16 (G == 16) or 32 (G = 32, 64, 128)
 __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, char* psm) {
     float* sU = reinterpret_cast<float*>(psm);   // SB x SB: U[j0 + j][j0 .. j0 + 127], filled by direct loads
-    float* sW = sU + SB * SB;                    // ROWS x SP
-    float* sE = sW + ROWS * SP;                  // ROWS x SP errors e
-    float* sRd = sE + ROWS * SP;                 // SB reciprocals of the diagonal
-    float* sS = sRd + SB;                        // ROWS x 8 scales of the block's groups
-    float* sZ = sS + ROWS * 8;                   // ROWS x 8 zero points
+    float* sC = sU + SB * SB;                    // ROWS x SP feedback sums / codes (see above)
+    float* sE = sC + ROWS * SP;                  // ROWS x SP original weights / errors e
+    double* sRd = reinterpret_cast<double*>(sE + ROWS * SP);   // SB reciprocals of the diagonal
+    double* sS = sRd + SB;                       // ROWS x 8 scales of the block's groups (fp64; returned rounded to fp32)
+    float* sZ = reinterpret_cast<float*>(sS + ROWS * 8);       // ROWS x 8 zero points
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -234,14 +289,16 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
     const bool row_ok = (r0 + qrow) < a.d_out;
     // MFMA accumulator layout: register r of lane l = row (r/4)*8 + (l/32)*4 + r%4, column l%32
     const int lr = (lane >> 5) * 4, lc = lane & 31;
-    const float qmax = a.qmax;
-    const float f_d = a.sc->f_d, f_all = a.sc->f_all, f_inv = a.sc->f_inv;
+    const double qmax = double(a.qmax), qsd = double(a.qs);
+    const float f_d = a.sc->f_d, f_inv = a.sc->f_inv;
     const uint32_t ldsU = uint32_t(uintptr_t((ONECOMP_LDS char*)psm));
-    float s = 1.f, rs = 1.f, z = 0.f, lossacc = 0.f;
+    double s = 1.0, rs = 1.0, z = 0.0;
+    float lossacc = 0.f;
+    bool saturated = false;
     if (a.wide_g >= 0) {
-        s = a.scales[int64_t(grow) * a.n_g + a.wide_g];
-        z = a.zeros[int64_t(grow) * a.n_g + a.wide_g];
-        rs = 1.0f / s;
+        s = a.s64[grow];
+        z = double(a.zeros[int64_t(grow) * a.n_g + a.wide_g]);
+        rs = 1.0 / s;
     }
 
 #pragma unroll 1
@@ -250,7 +307,7 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
         __syncthreads();   // everybody is done with the previous block's tiles
         if (a.wide_g >= 0 && sl == 0) {   // published by the barriers below, long before the first use
             sS[qrow * 8] = s;
-            sZ[qrow * 8] = z;
+            sZ[qrow * 8] = float(z);
         }
         // ---- U diagonal block -> sU, two rows (1 KB) per wave load, no registers involved
         {
@@ -263,51 +320,53 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                 lds_load16(ldsU + (16 * wave + q) * 1024, uint32_t((int64_t(row) * d_in + (lane & 31) * 4) * 4), rsrc);
             }
         }
-        // DIRECT: the original weights of this wave's two 32 x 32 tiles (row tile 0, column tile wave) and
-        // (1, 3 - wave), in accumulator layout; requested here so that they arrive behind the near update, kept in
-        // registers until the block is done
+        // The original weights of two of the block's eight 32 x 32 tiles, in accumulator layout: row tile 0 / 1 of
+        // column tile `wave` (DIRECT: (0, wave) and (1, 3 - wave), the tiles this wave transforms).  Requested here
+        // so that they arrive behind the near update; DIRECT keeps them in registers until the block is done.
         float16v w0r[2];
-        if constexpr (DIRECT) {
-            // 32 independent loads in straight-line code (one uniform branch on the element type around them)
-            int64_t off[2][16];
+        auto load_w0 = [&](float16v(&dst)[2]) __attribute__((always_inline)) {
+            // 32 independent loads in straight-line code (one uniform branch on the element type around them); the
+            // workgroup's rows span less than 2^31 elements, so a uniform base and 32-bit lane offsets address them
+            int off[2][16];
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
-                const int p = j0 + (mt == 0 ? wave : 3 - wave) * 32 + lc;
-                const int oc = p;
+                const int p = j0 + ((!DIRECT || mt == 0) ? wave : 3 - wave) * 32 + lc;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    off[mt][r] = int64_t(min(r0 + mt * 32 + (r / 4) * 8 + lr + (r % 4), a.d_out - 1)) * d_in + oc;
+                    off[mt][r] = (min(r0 + mt * 32 + (r / 4) * 8 + lr + (r % 4), a.d_out - 1) - r0) * int(d_in) + p;
             }
             if (a.w0_bf16) {
-                const uint16_t* wp = static_cast<const uint16_t*>(a.W0);
+                const uint16_t* wp = static_cast<const uint16_t*>(a.W0) + int64_t(r0) * d_in;
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) w0r[mt][r] = __uint_as_float(uint32_t(wp[off[mt][r]]) << 16);
+                    for (int r = 0; r < 16; ++r) dst[mt][r] = __uint_as_float(uint32_t(wp[off[mt][r]]) << 16);
             } else {
-                const float* wp = static_cast<const float*>(a.W0);
+                const float* wp = static_cast<const float*>(a.W0) + int64_t(r0) * d_in;
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) w0r[mt][r] = wp[off[mt][r]];
+                    for (int r = 0; r < 16; ++r) dst[mt][r] = wp[off[mt][r]];
             }
-        }
-        // ---- near update of this block's columns, wave = column tile
+        };
+        load_w0(w0r);
+        // ---- feedback sums of this block's columns, wave = column tile: what earlier super-blocks left in the
+        // working copy plus the near update from the earlier blocks of this super-block, accumulated from zero
         {
-            float16v acc[2];
+            float16v cf[2], acc[2];
+            {
+                const float* cbase = a.Wf + int64_t(r0) * d_in;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+                for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int rr = min(r0 + mt * 32 + (r / 4) * 8 + lr + (r % 4), a.d_out - 1);
-                    acc[mt][r] = a.Wf[int64_t(rr) * d_in + j0 + 32 * wave + lc];
-                }
+                    for (int r = 0; r < 16; ++r) {
+                        const int rr = min(r0 + mt * 32 + (r / 4) * 8 + lr + (r % 4), a.d_out - 1) - r0;
+                        cf[mt][r] = cbase[rr * int(d_in) + j0 + 32 * wave + lc];
+                        acc[mt][r] = 0.f;
+                    }
+            }
             if (b > 0)
             {
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[mt][r] *= f_all;
                 // rolling window of WIN k-steps of operand fragments (a source block has 8 k-steps)
                 constexpr int WIN = 4;
                 uint4v win[WIN][6];
@@ -343,26 +402,31 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                         else if (more) issue(bp + 1, ks + WIN - 8, cur);
                     }
                 }
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[mt][r] *= f_inv;
             }
+            // c = (near update) / (f_d f_u) + (earlier super-blocks): one fp32 rounding
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mt][r] = __builtin_fmaf(acc[mt][r], f_inv, cf[mt][r]);
             if constexpr (!DIRECT) {
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        sW[(mt * 32 + (r / 4) * 8 + lr + (r % 4)) * SP + 32 * wave + lc] = acc[mt][r];
+                    for (int r = 0; r < 16; ++r) {
+                        const int o = (mt * 32 + (r / 4) * 8 + lr + (r % 4)) * SP + 32 * wave + lc;
+                        sC[o] = acc[mt][r];
+                        sE[o] = w0r[mt][r];
+                    }
             }
             __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // the direct loads into sU have landed
             __syncthreads();
-            if (tid < SB) sRd[tid] = 1.0f / sU[tid * SB + tid];
+            if (tid < SB) sRd[tid] = 1.0 / double(sU[tid * SB + tid]);
             __syncthreads();
             if constexpr (DIRECT) {
-                // c_k / U_kk -> sE (free until the sweep writes its errors), as the A operand of c Un_bb = (c / diag) U_bb
+                // c_k / U_kk -> sE (free until the original weights go there), as the A operand of
+                // c Un_bb = (c / diag) U_bb
                 if (j0 > 0) {
-                    const float rd = sRd[32 * wave + lc];
+                    const float rd = float(sRd[32 * wave + lc]);
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -370,11 +434,13 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                             sE[(mt * 32 + (r / 4) * 8 + lr + (r % 4)) * SP + 32 * wave + lc] = acc[mt][r] * rd;
                     __syncthreads();
                 }
-                // eight 32 x 32 tiles of w_b + (c / diag) U_bb; column tile nt needs k < 32 (nt + 1) (U_bb is upper
-                // triangular), so wave w takes (row tile 0, column tile w) and (1, 3 - w): five chunks of 32 k, 16
-                // MFMAs each.  A chunk's 32 operand values are read before its first MFMA, and the two tiles'
-                // chunks alternate so that one tile's LDS reads fall behind the other's MFMAs.
-                float16v c0 = w0r[0], c1 = w0r[1];
+                // eight 32 x 32 tiles of (c / diag) U_bb, accumulated from zero; column tile nt needs k < 32 (nt + 1)
+                // (U_bb is upper triangular), so wave w takes (row tile 0, column tile w) and (1, 3 - w): five chunks
+                // of 32 k, 16 MFMAs each.  A chunk's 32 operand values are read before its first MFMA, and the two
+                // tiles' chunks alternate so that one tile's LDS reads fall behind the other's MFMAs.
+                float16v c0, c1;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { c0[r] = 0.f; c1[r] = 0.f; }
                 if (j0 > 0) {
                     const int nt0 = wave, nt1 = 3 - wave;
                     const float* ap0 = sE + lc * SP + (lane >> 5);
@@ -396,11 +462,14 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                         if (ch <= nt0) chunk(c0, ap0, bp0, ch);
                         if (ch <= nt1) chunk(c1, ap1, bp1, ch);
                     }
+                    __syncthreads();   // every wave is done reading sE as an operand
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    sW[((r / 4) * 8 + lr + (r % 4)) * SP + wave * 32 + lc] = c0[r];
-                    sW[(32 + (r / 4) * 8 + lr + (r % 4)) * SP + (3 - wave) * 32 + lc] = c1[r];
+                    const int o0 = ((r / 4) * 8 + lr + (r % 4)) * SP + wave * 32 + lc;
+                    const int o1 = (32 + (r / 4) * 8 + lr + (r % 4)) * SP + (3 - wave) * 32 + lc;
+                    sC[o0] = c0[r]; sE[o0] = w0r[0][r];
+                    sC[o1] = c1[r]; sE[o1] = w0r[1][r];
                 }
                 __syncthreads();
             }
@@ -409,15 +478,16 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
 #pragma unroll 1
         for (int jb = 0; jb < SB; jb += IB) {
             {
-                float w[8];
+                double w[8];
                 {
-                    const float* wp = sW + qrow * SP + jb + 8 * sl;
+                    const float* cp = sC + qrow * SP + jb + 8 * sl;
+                    const float* wp = sE + qrow * SP + jb + 8 * sl;
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) w[i] = wp[i];
+                    for (int i = 0; i < 8; ++i) w[i] = double(wp[i]) + double(cp[i]);
                 }
                 // row j of the inner block's U triangle (this lane's 8 columns) and 1 / U_jj, one step ahead
                 float4v ua[2], ub[2];
-                float rdc = sRd[jb], rdn = 0.f;
+                double rdc = sRd[jb], rdn = 0.0;
                 const float* up = sU + jb * SB + jb + 8 * sl;
                 ua[0] = *reinterpret_cast<const float4v*>(up);
                 ua[1] = *reinterpret_cast<const float4v*>(up + 4);
@@ -432,66 +502,68 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                         if constexpr (j % GB == 0) {
                             const int col = j0 + jb + j;
                             bool fresh;
-                            float mn, mx;
+                            double mn, mx;
                             if constexpr (GB == 16) {
                                 // group = the 16 columns held by lanes 2 (j / 16) and 2 (j / 16) + 1 of the quad
                                 fresh = true;
                                 mn = w[0]; mx = w[0];
 #pragma unroll
-                                for (int i = 1; i < 8; ++i) { mn = fminf(mn, w[i]); mx = fmaxf(mx, w[i]); }
-                                mn = fminf(mn, dpp_quad<QUAD_SWAP1>(mn));
-                                mx = fmaxf(mx, dpp_quad<QUAD_SWAP1>(mx));
+                                for (int i = 1; i < 8; ++i) { mn = fmin(mn, w[i]); mx = fmax(mx, w[i]); }
+                                mn = fmin(mn, dpp_quad<QUAD_SWAP1>(mn));
+                                mx = fmax(mx, dpp_quad<QUAD_SWAP1>(mx));
                                 mn = dpp_quad<quad_bcast(j / 8)>(mn);
                                 mx = dpp_quad<quad_bcast(j / 8)>(mx);
                             } else {
                                 fresh = a.wide_g < 0 && (col & (G - 1)) == 0;
-                                if (fresh) {   // uniform: the group's G <= 128 columns are current in sW
-                                    const float* gp = sW + qrow * SP + jb + sl;
-                                    mn = gp[0]; mx = gp[0];
-                                    for (int c = 4; c < G; c += 4) { const float v = gp[c]; mn = fminf(mn, v); mx = fmaxf(mx, v); }
-                                    mn = fminf(mn, dpp_quad<QUAD_SWAP1>(mn));
-                                    mx = fmaxf(mx, dpp_quad<QUAD_SWAP1>(mx));
-                                    mn = fminf(mn, dpp_quad<QUAD_SWAP2>(mn));
-                                    mx = fmaxf(mx, dpp_quad<QUAD_SWAP2>(mx));
+                                if (fresh) {   // uniform: the group's G <= 128 columns are unfinished, w0 in sE, c in sC
+                                    const float* gc = sC + qrow * SP + jb + sl;
+                                    const float* gw = sE + qrow * SP + jb + sl;
+                                    mn = double(gw[0]) + double(gc[0]); mx = mn;
+                                    for (int c = 4; c < G; c += 4) {
+                                        const double v = double(gw[c]) + double(gc[c]);
+                                        mn = fmin(mn, v); mx = fmax(mx, v);
+                                    }
+                                    mn = fmin(mn, dpp_quad<QUAD_SWAP1>(mn));
+                                    mx = fmax(mx, dpp_quad<QUAD_SWAP1>(mx));
+                                    mn = fmin(mn, dpp_quad<QUAD_SWAP2>(mn));
+                                    mx = fmax(mx, dpp_quad<QUAD_SWAP2>(mx));
                                 }
                             }
                             if (fresh) {
-                                if (a.qs > 0.f) {
-                                    s = fmaxf(fabsf(mn), fabsf(mx)) / a.qs;
-                                    if (s == 0.f) s = 1.f;
-                                    z = a.qs;
-                                } else {
-                                    s = (mx - mn) / qmax;
-                                    if (s == 0.f) s = 1.f;
-                                    z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
-                                }
+                                int cand = 0;
+                                float zsearch = 0.f;
                                 if constexpr (GB != 16) {
                                     if (a.mse) {   // uniform; this lane's quarter of the group, held in registers
-                                        const float* gp = sW + qrow * SP + jb + sl;
+                                        const float* gc = sC + qrow * SP + jb + sl;
+                                        const float* gw = sE + qrow * SP + jb + sl;
                                         float gv[32];
 #pragma unroll
-                                        for (int k = 0; k < 32; ++k) gv[k] = gp[(4 * k) & (G - 1)];
+                                        for (int k = 0; k < 32; ++k) {
+                                            const int c = (4 * k) & (G - 1);
+                                            gv[k] = float(double(gw[c]) + double(gc[c]));
+                                        }
                                         const int n8 = G >> 5;   // batches of 8 values: 1, 2 or 4
-                                        mse_search(mn, mx, qmax, a.qs,
+                                        const float qmf = a.qmax;
+                                        cand = mse_search(float(mn), float(mx), qmf, a.qs,
                                                    [&](float zi, float rsi) __attribute__((always_inline)) {
                                                        float e0 = 0.f, e1 = 0.f;
 #pragma unroll
                                                        for (int k = 0; k < 8; k += 2) {
-                                                           e0 += mse_term(gv[k], zi, rsi, qmax);
-                                                           e1 += mse_term(gv[k + 1], zi, rsi, qmax);
+                                                           e0 += mse_term(gv[k], zi, rsi, qmf);
+                                                           e1 += mse_term(gv[k + 1], zi, rsi, qmf);
                                                        }
                                                        if (n8 > 1) {
 #pragma unroll
                                                            for (int k = 8; k < 16; k += 2) {
-                                                               e0 += mse_term(gv[k], zi, rsi, qmax);
-                                                               e1 += mse_term(gv[k + 1], zi, rsi, qmax);
+                                                               e0 += mse_term(gv[k], zi, rsi, qmf);
+                                                               e1 += mse_term(gv[k + 1], zi, rsi, qmf);
                                                            }
                                                        }
                                                        if (n8 > 2) {
 #pragma unroll
                                                            for (int k = 16; k < 32; k += 2) {
-                                                               e0 += mse_term(gv[k], zi, rsi, qmax);
-                                                               e1 += mse_term(gv[k + 1], zi, rsi, qmax);
+                                                               e0 += mse_term(gv[k], zi, rsi, qmf);
+                                                               e1 += mse_term(gv[k + 1], zi, rsi, qmf);
                                                            }
                                                        }
                                                        return e0 + e1;
@@ -499,51 +571,54 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                                                    [&](float x) __attribute__((always_inline)) {
                                                        x += dpp_quad<QUAD_SWAP1>(x);
                                                        return x + dpp_quad<QUAD_SWAP2>(x);
-                                                   },
-                                                   s, z);
+                                                   }, zsearch);
                                     }
                                 } else {
                                     if (a.mse) {   // uniform; the group's 16 values sit in two lanes of the quad
-                                        mse_search(mn, mx, qmax, a.qs,
+                                        float gv[8];
+#pragma unroll
+                                        for (int k = 0; k < 8; ++k) gv[k] = float(w[k]);
+                                        const float qmf = a.qmax;
+                                        cand = mse_search(float(mn), float(mx), qmf, a.qs,
                                                    [&](float zi, float rsi) __attribute__((always_inline)) {
                                                        float e0 = 0.f, e1 = 0.f;
 #pragma unroll
                                                        for (int k = 0; k < 8; k += 2) {
-                                                           e0 += mse_term(w[k], zi, rsi, qmax);
-                                                           e1 += mse_term(w[k + 1], zi, rsi, qmax);
+                                                           e0 += mse_term(gv[k], zi, rsi, qmf);
+                                                           e1 += mse_term(gv[k + 1], zi, rsi, qmf);
                                                        }
                                                        return e0 + e1;
                                                    },
                                                    [&](float x) __attribute__((always_inline)) {
                                                        x += dpp_quad<QUAD_SWAP1>(x);
                                                        return dpp_quad<quad_bcast(j / 8)>(x);
-                                                   },
-                                                   s, z);
+                                                   }, zsearch);
                                     }
                                 }
-                                rs = 1.0f / s;
+                                grid_params(mn, mx, cand, qmax, qsd, s, z);
+                                if (a.mse) z = double(zsearch);
+                                rs = 1.0 / s;
                                 if (sl == 0) {
                                     const int gi = (jb + j) >> a.lgG;
                                     sS[qrow * 8 + gi] = s;
-                                    sZ[qrow * 8 + gi] = z;
+                                    sZ[qrow * 8 + gi] = float(z);
                                     if (row_ok) {
-                                        a.scales[int64_t(grow) * a.n_g + (col >> a.lgG)] = s;
-                                        a.zeros[int64_t(grow) * a.n_g + (col >> a.lgG)] = z;
+                                        a.scales[int64_t(grow) * a.n_g + (col >> a.lgG)] = float(s);
+                                        a.zeros[int64_t(grow) * a.n_g + (col >> a.lgG)] = float(z);
                                     }
                                 }
                             }
                         }
-                        const float wj = dpp_quad<quad_bcast(j / 8)>(w[j % 8]);
-                        const float q = fminf(fmaxf(rintf(wj * rs) + z, 0.f), qmax);   // w / s as w * fl(1 / s)
-                        const float wh = s * (q - z);
-                        const float e = (wj - wh) * rdc;
+                        const double wj = dpp_quad<quad_bcast(j / 8)>(w[j % 8]);
+                        const double q = fmin(fmax(rint(wj * rs) + z, 0.0), qmax);   // w / s as w * fl64(1 / s)
+                        const double e = __builtin_fma(-s, q - z, wj) * rdc;         // (w - s (q - z)) / U_jj
                         // feedback inside the inner block: w_k -= e U_jk.  Columns up to j are finished, updating
                         // them is harmless; in the last slice the finished registers are skipped.
 #pragma unroll
                         for (int i = 0; i < 8; ++i)
-                            if (j < 24 || i > j % 8) w[i] = __builtin_fmaf(-e, cur[i / 4][i % 4], w[i]);
-                        sE[qrow * SP + jb + j] = e;
-                        sW[qrow * SP + jb + j] = q;
+                            if (j < 24 || i > j % 8) w[i] = __builtin_fma(-e, double(cur[i / 4][i % 4]), w[i]);
+                        sE[qrow * SP + jb + j] = float(e);
+                        sC[qrow * SP + jb + j] = float(q);
                         rdc = rdn;
                     };
                     if constexpr (j % 2 == 0) step(ua, ub);
@@ -551,24 +626,25 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                 });
             }
             __syncthreads();
-            // remaining columns of the block: w_c -= sum_i e_i U[jb+i][c], c >= jb + 32, on 32 x 32 tiles
+            // remaining columns of the block: c_col -= sum_i e_i U[jb+i][col], col >= jb + 32, on 32 x 32 tiles
+            // accumulated from zero and then added to the tile in LDS
             const int cs = jb + IB;
             if (cs < SB)
             {
                 const int n_tiles = 2 * ((SB - cs) / 32);
                 for (int t = wave; t < n_tiles; t += 4) {
                     const int mt = t & 1, nt = t >> 1;
-                    float* cp = sW + (mt * 32 + lr) * SP + cs + nt * 32 + lc;
+                    float* cp = sC + (mt * 32 + lr) * SP + cs + nt * 32 + lc;
                     float16v c;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) c[r] = cp[((r / 4) * 8 + (r % 4)) * SP];
+                    for (int r = 0; r < 16; ++r) c[r] = 0.f;
                     const float* ap = sE + (mt * 32 + lc) * SP + jb + (lane >> 5);
                     const float* bp = sU + (jb + (lane >> 5)) * SB + cs + nt * 32 + lc;
 #pragma unroll
                     for (int kk = 0; kk < IB / 2; ++kk)
                         c = __builtin_amdgcn_mfma_f32_32x32x2f32(-ap[2 * kk], bp[2 * kk * SB], c, 0, 0, 0);
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) cp[((r / 4) * 8 + (r % 4)) * SP] = c[r];
+                    for (int r = 0; r < 16; ++r) cp[((r / 4) * 8 + (r % 4)) * SP] += c[r];
                 }
             }
             __syncthreads();
@@ -585,11 +661,13 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
             lossacc += acc;
         }
         // residual w - w^ = e U_jj, negated, scaled by a power of two and split into fp16 hi + lo
-        // (hi = rne(x), lo = rne(x - hi): 22 significant bits); saturated far above anything a sweep produces.
+        // (hi = rne(x), lo = rne(x - hi): 22 significant bits); saturated far above anything a sweep of a sane layer
+        // produces, and the saturation is reported (the loss then comes back as +infinity).
         auto split8 = [&](auto&& value, short8v& dh, short8v& dl) __attribute__((always_inline)) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 float x = value(e);
+                saturated |= !(fabsf(x) <= 60000.f);
                 x = fminf(fmaxf(x, -60000.f), 60000.f);
                 const _Float16 h = (_Float16)x;
                 const _Float16 lo = (_Float16)(x - (float)h);
@@ -605,8 +683,9 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int rr = mt * 32 + (r / 4) * 8 + lr + (r % 4);
-                    const float wh = sS[rr * 8 + gi] * (sW[rr * SP + col] - sZ[rr * 8 + gi]);
-                    sO[rr * SP + col] = w0r[mt][r] - wh;
+                    // w0 - s (q - z) with the fp64 scale the sweep used
+                    sO[rr * SP + col] = float(__builtin_fma(-sS[rr * 8 + gi], double(sC[rr * SP + col] - sZ[rr * 8 + gi]),
+                                                            double(w0r[mt][r])));
                 }
             }
             __syncthreads();
@@ -645,8 +724,8 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int gi = (c4 + e) >> a.lgG;
-                qv[e] = sW[rr * SP + c4 + e];
-                hv[e] = sS[rr * 8 + gi] * (qv[e] - sZ[rr * 8 + gi]);
+                qv[e] = sC[rr * SP + c4 + e];
+                hv[e] = float(sS[rr * 8 + gi]) * (qv[e] - sZ[rr * 8 + gi]);
             }
             if (a.W_hat) {
                 const float4v h = {hv[0], hv[1], hv[2], hv[3]};
@@ -660,6 +739,7 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     }
     if (sl == 0 && row_ok) a.rowloss[grow] += lossacc;
+    if (saturated) *a.sat = 1u;
 }
 
 // Fragments of the normalized U blocks the panel kernel's near updates multiply with: for super-block S (sbw
@@ -782,7 +862,6 @@ constexpr int A_PANELB = KT * A_ROWB, B_PANELB = KT * B_ROWB;       // 4 KB, 8 K
 constexpr int OFF_AH = 0, OFF_AL = A_PANELB, OFF_BH = 2 * A_PANELB, OFF_BL = 2 * A_PANELB + B_PANELB;
 constexpr int STAGEB = 2 * A_PANELB + 2 * B_PANELB;                 // 24 KB
 constexpr size_t LDS_BYTES = size_t(3) * STAGEB;                    // 72 KB with 3 slots: two workgroups per CU
-constexpr int BAND = 8;                                             // row tiles per band of the tile order
 }  // namespace tg
 
 struct TrailArgs {
@@ -795,17 +874,16 @@ struct TrailArgs {
     int n_mt, n_nt, chunk;
 };
 
-template <int NBUF>   // slots of the LDS ring
+// FROM_ZERO: the accumulators start at zero and the product is added to the tile of C once, at the end, with one
+// fp32 rounding (the sweep: every rounding inside the MFMA chain then happens at the size of the increment, not of
+// the sum it joins).  Otherwise the tile of C is loaded, scaled, into the accumulators before the loop.
+template <int NBUF, bool FROM_ZERO>   // NBUF: slots of the LDS ring
 __device__ __forceinline__ void trailing_tile(const TrailArgs& a, const int bid, char* tl) {
     using namespace tg;
-    const int n_tiles = a.n_mt * a.n_nt;
-    const int v = (bid & 7) * a.chunk + (bid >> 3);
-    if (v >= n_tiles) return;
-    const int band = min(v / (BAND * a.n_nt), (a.n_mt - 1) / BAND);
-    const int rem = v - band * BAND * a.n_nt;
-    const int mb = min(BAND, a.n_mt - BAND * band);
-    const int m0 = (band * BAND + rem % mb) * TM;
-    const int n0 = a.c0 + (rem / mb) * TN;
+    int mt_, nt_;
+    if (!plan::trail_tile(bid, a.chunk, a.n_mt, a.n_nt, mt_, nt_)) return;
+    const int m0 = mt_ * TM;
+    const int n0 = a.c0 + nt_ * TN;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -900,9 +978,13 @@ __device__ __forceinline__ void trailing_tile(const TrailArgs& a, const int bid,
         for (int n = 0; n < 4; ++n)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int rr = min(m0 + wr * 64 + m * 32 + (r / 4) * 8 + lr + (r % 4), d_out - 1);
-                const int cc = min(n0 + wc * 128 + n * 32 + lc, c1 - 1);
-                acc[m][n][r] = a.Wf[int64_t(rr) * d_in + cc] * f_all;
+                if constexpr (FROM_ZERO) {
+                    acc[m][n][r] = 0.f;
+                } else {
+                    const int rr = min(m0 + wr * 64 + m * 32 + (r / 4) * 8 + lr + (r % 4), d_out - 1);
+                    const int cc = min(n0 + wc * 128 + n * 32 + lc, c1 - 1);
+                    acc[m][n][r] = a.Wf[int64_t(rr) * d_in + cc] * f_all;
+                }
             }
     __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));
     __syncthreads();
@@ -960,12 +1042,32 @@ __device__ __forceinline__ void trailing_tile(const TrailArgs& a, const int bid,
     if ((m0 + TM <= d_out) && (n0 + TN <= c1)) {
         float* wp = a.Wf + int64_t(m0 + wr * 64 + lr) * d_in + n0 + wc * 128 + lc;
 #pragma unroll
-        for (int m = 0; m < 2; ++m)
+        for (int m = 0; m < 2; ++m) {
+            if constexpr (FROM_ZERO) {
+                // the tile's current values: 32 independent loads at a time (the operand registers are free now)
 #pragma unroll
-            for (int n = 0; n < 4; ++n)
+                for (int n2 = 0; n2 < 4; n2 += 2) {
+                    float16v old[2];
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    wp[int64_t(m * 32 + (r / 4) * 8 + (r % 4)) * d_in + n * 32] = acc[m][n][r] * f_inv;
+                    for (int n = 0; n < 2; ++n)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            old[n][r] = wp[int64_t(m * 32 + (r / 4) * 8 + (r % 4)) * d_in + (n2 + n) * 32];
+#pragma unroll
+                    for (int n = 0; n < 2; ++n)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            wp[int64_t(m * 32 + (r / 4) * 8 + (r % 4)) * d_in + (n2 + n) * 32] =
+                                __builtin_fmaf(acc[m][n2 + n][r], f_inv, old[n][r]);
+                }
+            } else {
+#pragma unroll
+                for (int n = 0; n < 4; ++n)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        wp[int64_t(m * 32 + (r / 4) * 8 + (r % 4)) * d_in + n * 32] = acc[m][n][r] * f_inv;
+            }
+        }
     } else {
 #pragma unroll
         for (int m = 0; m < 2; ++m)
@@ -975,14 +1077,19 @@ __device__ __forceinline__ void trailing_tile(const TrailArgs& a, const int bid,
                 for (int r = 0; r < 16; ++r) {
                     const int rr = m0 + wr * 64 + m * 32 + (r / 4) * 8 + lr + (r % 4);
                     const int cc = n0 + wc * 128 + n * 32 + lc;
-                    if (rr < d_out && cc < c1) a.Wf[int64_t(rr) * d_in + cc] = acc[m][n][r] * f_inv;
+                    if (rr < d_out && cc < c1) {
+                        float* q = a.Wf + int64_t(rr) * d_in + cc;
+                        if constexpr (FROM_ZERO) *q = __builtin_fmaf(acc[m][n][r], f_inv, *q);
+                        else *q = acc[m][n][r] * f_inv;
+                    }
                 }
     }
 }
 
+template <bool FROM_ZERO>
 __global__ __launch_bounds__(256, 2) void trailing_kernel(TrailArgs a) {
     extern __shared__ __attribute__((aligned(1024))) char dyn_lds[];
-    trailing_tile<3>(a, blockIdx.x, dyn_lds);
+    trailing_tile<3, FROM_ZERO>(a, blockIdx.x, dyn_lds);
 }
 
 // One launch = the panel sweep of a super-block next to the far update of the previous super-block on the
@@ -994,67 +1101,69 @@ template <int GB, bool DIRECT>
 __global__ __launch_bounds__(256) void panel_far_kernel(PanelArgs pa, TrailArgs ta, int n_panel) {
     extern __shared__ __attribute__((aligned(1024))) char dyn_lds[];
     if (int(blockIdx.x) < n_panel) panel_body<GB, DIRECT>(pa, blockIdx.x, dyn_lds);
-    else trailing_tile<3>(ta, blockIdx.x - n_panel, dyn_lds);
+    else trailing_tile<3, true>(ta, blockIdx.x - n_panel, dyn_lds);
 }
 
-// Scale and zero-point of one wide group (columns g0 .. g0 + G - 1 of every row) from the values in Wsrc, which the
-// caller guarantees to be current: the original weights for the first group of a row, the working copy after the
-// feedback of all earlier columns has been applied for a later one.  One workgroup per row.
+// Scale and zero-point of one wide group (columns g0 .. g0 + G - 1 of every row) from its current values
+// w0 + c in fp64: W0 the weights in sweep order, C the working copy (accumulated feedback; nullptr = none, the
+// first group of a row or one group per row), which the caller guarantees to be complete for these columns: the far
+// updates of all earlier super-blocks have run.  One workgroup per row; the fp64 scale goes to s64[row].
 template <typename T>
-__global__ __launch_bounds__(256) void group_params_kernel(const T* __restrict__ Wsrc, int d_out, int d_in, int g0, int G,
-                                                          float qmax, float qs, int mse, int n_g, int g_idx,
-                                                          float* __restrict__ scales, float* __restrict__ zeros) {
-    __shared__ float smn[256], smx[256];
+__global__ __launch_bounds__(256) void group_params_kernel(const T* __restrict__ W0, const float* __restrict__ C, int d_out,
+                                                          int d_in, int g0, int G, float qmax, float qs, int mse, int n_g,
+                                                          int g_idx, float* __restrict__ scales, float* __restrict__ zeros,
+                                                          double* __restrict__ s64) {
+    __shared__ double smn[256], smx[256];
+    __shared__ float sred[256];
     for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {
-        const T* row = Wsrc + r * d_in + g0;
-        float mn = to_f32<T>(row[0]), mx = mn;
+        const T* row = W0 + r * d_in + g0;
+        const float* crow = C ? C + r * d_in + g0 : nullptr;
+        auto value = [&](int c) __attribute__((always_inline)) {
+            return double(to_f32<T>(row[c])) + (crow ? double(crow[c]) : 0.0);
+        };
+        double mn = value(0), mx = mn;
         for (int c = threadIdx.x; c < G; c += 256) {
-            const float v = to_f32<T>(row[c]);
-            mn = fminf(mn, v); mx = fmaxf(mx, v);
+            const double v = value(c);
+            mn = fmin(mn, v); mx = fmax(mx, v);
         }
         smn[threadIdx.x] = mn; smx[threadIdx.x] = mx;
         __syncthreads();
         for (int w = 128; w > 0; w >>= 1) {
             if (int(threadIdx.x) < w) {
-                smn[threadIdx.x] = fminf(smn[threadIdx.x], smn[threadIdx.x + w]);
-                smx[threadIdx.x] = fmaxf(smx[threadIdx.x], smx[threadIdx.x + w]);
+                smn[threadIdx.x] = fmin(smn[threadIdx.x], smn[threadIdx.x + w]);
+                smx[threadIdx.x] = fmax(smx[threadIdx.x], smx[threadIdx.x + w]);
             }
             __syncthreads();
         }
         mn = smn[0]; mx = smx[0];
         __syncthreads();
-        float s, z;
-        if (qs > 0.f) {
-            s = fmaxf(fabsf(mn), fabsf(mx)) / qs;
-            if (s == 0.f) s = 1.f;
-            z = qs;
-        } else {
-            s = (mx - mn) / qmax;
-            if (s == 0.f) s = 1.f;
-            z = fminf(fmaxf(rintf(-mn / s), 0.f), qmax);
-        }
+        int cand = 0;
+        float zsearch = 0.f;
         if (mse) {   // uniform; the row's values are re-read from cache for every candidate
-            mse_search(mn, mx, qmax, qs,
+            cand = mse_search(float(mn), float(mx), qmax, qs,
                        [&](float zi, float rsi) __attribute__((always_inline)) {
                            float e = 0.f;
-                           for (int c = threadIdx.x; c < G; c += 256) e += mse_term(to_f32<T>(row[c]), zi, rsi, qmax);
+                           for (int c = threadIdx.x; c < G; c += 256) e += mse_term(float(value(c)), zi, rsi, qmax);
                            return e;
                        },
                        [&](float x) __attribute__((always_inline)) {   // workgroup sum, the same value in every thread
                            x += dpp_quad<QUAD_SWAP1>(x);
                            x += dpp_quad<QUAD_SWAP2>(x);
-                           smn[threadIdx.x] = x;
+                           sred[threadIdx.x] = x;
                            __syncthreads();
                            float t = 0.f;
-                           for (int w = 0; w < 256; w += 4) t += smn[w];
+                           for (int w = 0; w < 256; w += 4) t += sred[w];
                            __syncthreads();
                            return t;
-                       },
-                       s, z);
+                       }, zsearch);
         }
+        double s, z;
+        grid_params(mn, mx, cand, double(qmax), double(qs), s, z);
+        if (mse) z = double(zsearch);
         if (threadIdx.x == 0) {
-            scales[r * n_g + g_idx] = s;
-            zeros[r * n_g + g_idx] = z;
+            scales[r * n_g + g_idx] = float(s);
+            zeros[r * n_g + g_idx] = float(z);
+            s64[r] = s;
         }
     }
 }
@@ -1090,9 +1199,10 @@ __global__ __launch_bounds__(256) void unpermute_kernel(const uint8_t* __restric
     }
 }
 
-// loss = sum of the per-row sums, fixed order.  One workgroup.
+// loss = sum of the per-row sums, fixed order; +infinity if a residual was saturated on its way into the fp16
+// operands of the feedback products (the codes of later columns are then not those of the sweep).  One workgroup.
 __global__ __launch_bounds__(1024) void loss_kernel(const float* __restrict__ rowloss, int d_out,
-                                                   float* __restrict__ loss) {
+                                                   const uint32_t* __restrict__ sat, float* __restrict__ loss) {
     __shared__ double part[1024];
     double s = 0.0;
     for (int i = threadIdx.x; i < d_out; i += 1024) s += double(rowloss[i]);
@@ -1102,7 +1212,7 @@ __global__ __launch_bounds__(1024) void loss_kernel(const float* __restrict__ ro
         if (threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
         __syncthreads();
     }
-    if (threadIdx.x == 0) *loss = float(part[0]);
+    if (threadIdx.x == 0) *loss = *sat ? __builtin_inff() : float(part[0]);
 }
 
 struct SweepWs {
@@ -1117,7 +1227,8 @@ struct SweepWs {
     Scalars* sc;
     uint8_t* Qs;         // [d_out x d_in] codes in sweep order (used under a column order)
     int32_t* inv;        // [d_in] inverse of the column order
-    float* W0p;          // [d_out x d_in] the weights gathered into sweep order (block form under a column order)
+    float* W0p;          // [d_out x d_in] the weights gathered into sweep order (used under a column order)
+    double* s64;         // [d_out] fp64 scale of the wide group being swept
 };
 
 constexpr size_t F_PER_WG = size_t(3) * 8 * 2 * 64 * 8 * 2;    // bytes of Fh (or Fl) per workgroup of the panel kernel
@@ -1129,7 +1240,7 @@ inline int64_t ld_d(int64_t d_out) { return ceil_div(d_out, ROWS) * ROWS; }
 SweepWs carve(void* ws, int64_t d_out, int64_t d_in) {
     char* p = static_cast<char*>(ws);
     SweepWs w;
-    w.Wf = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * d_in * sizeof(float), 256);
+    w.Wf = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * d_in * sizeof(float), 256);   // feedback sums c
     w.Dh = reinterpret_cast<uint16_t*>(p); p += 2 * size_t(SBIG) * ld_d(d_out) * 2;
     w.Dl = reinterpret_cast<uint16_t*>(p); p += 2 * size_t(SBIG) * ld_d(d_out) * 2;
     w.Uh = reinterpret_cast<uint16_t*>(p); p += align_up(size_t(d_in) * d_in * 2, 256);
@@ -1143,7 +1254,8 @@ SweepWs carve(void* ws, int64_t d_out, int64_t d_in) {
     w.sc = reinterpret_cast<Scalars*>(p); p += 256;
     w.Qs = reinterpret_cast<uint8_t*>(p); p += align_up(size_t(d_out) * d_in, 256);
     w.inv = reinterpret_cast<int32_t*>(p); p += align_up(size_t(d_in) * sizeof(int32_t), 256);
-    w.W0p = reinterpret_cast<float*>(p);
+    w.W0p = reinterpret_cast<float*>(p); p += align_up(size_t(d_out) * d_in * sizeof(float), 256);
+    w.s64 = reinterpret_cast<double*>(p);
     return w;
 }
 
@@ -1167,7 +1279,7 @@ size_t sweep_workspace_bytes(int64_t d_out, int64_t d_in, int block) {
            2 * align_up(size_t(d_in) * d_in * 2, 256) + align_up(size_t(d_out) * sizeof(float), 256) +
            2 * size_t(ceil_div(d_out, ROWS)) * F_PER_WG + 2 * size_t(ceil_div(d_in, SBIG)) * B_PER_SB + 256 +
            align_up(size_t(d_out) * d_in, 256) + align_up(size_t(d_in) * sizeof(int32_t), 256) +
-           align_up(size_t(d_out) * d_in * sizeof(float), 256);
+           align_up(size_t(d_out) * d_in * sizeof(float), 256) + align_up(size_t(d_out) * sizeof(double), 256);
 }
 
 // C[:, c0 .. c1) += f_inv * (D[ek .. ek + K, :])^T * B[u0 .. u0 + K, c0 .. c1): the split-fp16 product of the sweep's
@@ -1177,7 +1289,7 @@ onecomp_status split_update(float* C, int64_t d_out, int64_t d_in, const uint16_
                             int c1, hipStream_t stream) {
     if (c1 <= c0 || K <= 0) return ONECOMP_OK;
     static std::atomic<uint64_t> lds_ok{0};
-    if (allow_dynamic_lds(reinterpret_cast<const void*>(&trailing_kernel), int(tg::LDS_BYTES), lds_ok) != ONECOMP_OK)
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(&trailing_kernel<false>), int(tg::LDS_BYTES), lds_ok) != ONECOMP_OK)
         return ONECOMP_ERR_HIP;
     TrailArgs t;
     t.Wf = C; t.Dh = Dh; t.Dl = Dl; t.Uh = Bh; t.Ul = Bl; t.sc = sc;
@@ -1186,7 +1298,7 @@ onecomp_status split_update(float* C, int64_t d_out, int64_t d_in, const uint16_
     t.n_mt = int(ceil_div(d_out, tg::TM));
     t.n_nt = int(ceil_div(c1 - c0, tg::TN));
     t.chunk = int(ceil_div(int64_t(t.n_mt) * t.n_nt, 8));
-    hipLaunchKernelGGL(trailing_kernel, dim3(unsigned(t.chunk * 8)), dim3(256), tg::LDS_BYTES, stream, t);
+    hipLaunchKernelGGL(trailing_kernel<false>, dim3(unsigned(t.chunk * 8)), dim3(256), tg::LDS_BYTES, stream, t);
     ONECOMP_CHECK_LAUNCH();
     return ONECOMP_OK;
 }
@@ -1204,10 +1316,7 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
     const bool wide_static = group_size > SB;
     // super-block width: 512 columns, or for wide groups the largest of 512 / 384 / 256 / 128 that divides the group,
     // so that a group is a run of whole super-blocks
-    int sbw = SBIG;
-    if (wide_static && group_size != d_in)
-        for (int c = SBIG; c >= SB; c -= SB)
-            if (group_size % c == 0) { sbw = c; break; }
+    const int sbw = plan::sweep_superblock_width(group_size, d_in);
     const int sb_pairs = (sbw / SB) * (sbw / SB - 1) / 2;   // block pairs (b' < b) inside a super-block
     if (direct && group_size > SB && group_size != d_in) return ONECOMP_ERR_UNSUPPORTED;
     SweepWs w = carve(workspace, d_out, d_in);
@@ -1216,10 +1325,10 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
     dim3 lgrid{unsigned(d_out < 1024 ? d_out : 1024)};
     if (w_dtype == ONECOMP_BF16)
         hipLaunchKernelGGL(load_kernel<uint16_t>, lgrid, dim3(256), 0, stream, static_cast<const uint16_t*>(W), d_out,
-                           d_in, perm, w.Wf, w.rowloss, w.sc, int(direct), (direct && perm) ? w.W0p : nullptr);
+                           d_in, perm, w.Wf, w.rowloss, w.sc, perm ? w.W0p : nullptr);
     else
         hipLaunchKernelGGL(load_kernel<float>, lgrid, dim3(256), 0, stream, static_cast<const float*>(W), d_out, d_in,
-                           perm, w.Wf, w.rowloss, w.sc, int(direct), (direct && perm) ? w.W0p : nullptr);
+                           perm, w.Wf, w.rowloss, w.sc, perm ? w.W0p : nullptr);
     ONECOMP_CHECK_LAUNCH();
     hipLaunchKernelGGL(umax_kernel, dim3(unsigned(d_in < 1024 ? d_in : 1024)), dim3(256), 0, stream, U,
                        int(d_in), w.sc);
@@ -1231,7 +1340,7 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
     ONECOMP_CHECK_LAUNCH();
 
     static std::atomic<uint64_t> lds_ok{0};
-    if (allow_dynamic_lds(reinterpret_cast<const void*>(&trailing_kernel), int(tg::LDS_BYTES), lds_ok) != ONECOMP_OK)
+    if (allow_dynamic_lds(reinterpret_cast<const void*>(&trailing_kernel<true>), int(tg::LDS_BYTES), lds_ok) != ONECOMP_OK)
         return ONECOMP_ERR_HIP;
     TrailArgs t;
     t.Wf = w.Wf; t.Dh = w.Dh; t.Dl = w.Dl; t.Uh = w.Uh; t.Ul = w.Ul; t.sc = w.sc;
@@ -1252,7 +1361,7 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
     auto trailing = [&](int buf, int ek, int K, int u0, int c0, int c1) -> onecomp_status {
         const int wgs = set_trailing(buf, ek, K, u0, c0, c1);
         if (wgs == 0) return ONECOMP_OK;
-        hipLaunchKernelGGL(trailing_kernel, dim3(unsigned(wgs)), dim3(256), tg::LDS_BYTES, stream, t);
+        hipLaunchKernelGGL(trailing_kernel<true>, dim3(unsigned(wgs)), dim3(256), tg::LDS_BYTES, stream, t);
         ONECOMP_CHECK_LAUNCH();
         return ONECOMP_OK;
     };
@@ -1270,9 +1379,10 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
         }
         PanelArgs pa;
         pa.Wf = w.Wf; pa.U = U;
-        // block form: where the panel finds the original weights; under a column order, the gathered fp32 copy
-        pa.W0 = (direct && perm) ? static_cast<const void*>(w.W0p) : W;
-        pa.w0_bf16 = !(direct && perm) && w_dtype == ONECOMP_BF16;
+        // where the panel finds the original weights in sweep order: under a column order, the gathered fp32 copy
+        pa.W0 = perm ? static_cast<const void*>(w.W0p) : W;
+        pa.w0_bf16 = !perm && w_dtype == ONECOMP_BF16;
+        pa.s64 = w.s64; pa.sat = sat_flag(w.sc);
         pa.Q = perm ? w.Qs : Q; pa.scales = scales; pa.zeros = zeros; pa.W_hat = perm ? nullptr : W_hat;
         pa.Fh = w.Fh; pa.Fl = w.Fl; pa.sc = w.sc; pa.rowloss = w.rowloss;
         pa.d_out = int(d_out); pa.d_in = int(d_in); pa.n_g = int(d_in / group_size); pa.ldD = int(ld_d(d_out));
@@ -1298,17 +1408,17 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
             if (group_start) {
                 const dim3 pgrid{unsigned(d_out < 2048 ? d_out : 2048)};
                 const int g_idx = s0 / group_size;
-                if (!direct)
-                    hipLaunchKernelGGL(group_params_kernel<float>, pgrid, dim3(256), 0, stream, w.Wf, int(d_out), int(d_in),
-                                       s0, group_size, pa.qmax, pa.qs, pa.mse, pa.n_g, g_idx, scales, zeros);
-                else if (pa.w0_bf16)
+                // the feedback of the earlier columns (none before the first group; the block form only takes one
+                // group per row, whose grid comes from the original weights)
+                const float* cur = (direct || s0 == 0) ? nullptr : w.Wf;
+                if (pa.w0_bf16)
                     hipLaunchKernelGGL(group_params_kernel<uint16_t>, pgrid, dim3(256), 0, stream,
-                                       static_cast<const uint16_t*>(pa.W0), int(d_out), int(d_in), s0, group_size, pa.qmax,
-                                       pa.qs, pa.mse, pa.n_g, g_idx, scales, zeros);
+                                       static_cast<const uint16_t*>(pa.W0), cur, int(d_out), int(d_in), s0, group_size,
+                                       pa.qmax, pa.qs, pa.mse, pa.n_g, g_idx, scales, zeros, w.s64);
                 else
                     hipLaunchKernelGGL(group_params_kernel<float>, pgrid, dim3(256), 0, stream,
-                                       static_cast<const float*>(pa.W0), int(d_out), int(d_in), s0, group_size, pa.qmax,
-                                       pa.qs, pa.mse, pa.n_g, g_idx, scales, zeros);
+                                       static_cast<const float*>(pa.W0), cur, int(d_out), int(d_in), s0, group_size,
+                                       pa.qmax, pa.qs, pa.mse, pa.n_g, g_idx, scales, zeros, w.s64);
                 ONECOMP_CHECK_LAUNCH();
             }
             if (wide_static) pa.wide_g = s0 / group_size;
@@ -1333,7 +1443,7 @@ onecomp_status sweep_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, in
                            int(d_in / group_size), Q, W_hat);
         ONECOMP_CHECK_LAUNCH();
     }
-    hipLaunchKernelGGL(loss_kernel, dim3(1), dim3(1024), 0, stream, w.rowloss, int(d_out), loss);
+    hipLaunchKernelGGL(loss_kernel, dim3(1), dim3(1024), 0, stream, w.rowloss, int(d_out), sat_flag(w.sc), loss);
     ONECOMP_CHECK_LAUNCH();
     return ONECOMP_OK;
 }

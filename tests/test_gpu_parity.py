@@ -73,14 +73,18 @@ def _check_sweep(W, U32, bits, G, perm=None, rows=None, min_agree=0.999, grid="m
               f"real {len(st['real_mismatches'])}")
     assert st["real_mismatches"] == []
     assert st["final_agree"] == 1.0
-    # Raw agreement: 99.9 % of the entries.  A flip at a tie can change every later code of its row, so on a layer
-    # of few rows one legitimate flip alone may cost more than 0.1 %: there the bar is what the counted flips can
-    # account for (at most one row's worth of entries each), with the number of flips itself bounded.
-    # With the scale search, two candidates whose error sums agree to 1e-4 are either one a valid choice; such a
-    # flip changes its group and the rest of the row like a rounding tie does and is counted the same way.
+    # Raw agreement: 99.9 % of the entries, before any replay.  A flip at a tie can change every later code of its
+    # row, so where fewer than 100 rows are compared one legitimate flip alone may cost more than 0.1 %: only there
+    # the bar is what the counted flips can account for (at most one row's worth of entries each).  The number of
+    # flips is bounded everywhere.  With the scale search, two candidates whose error sums agree to 1e-4 are either
+    # one a valid choice; such a flip changes its group and the rest of the row like a rounding tie does and is
+    # counted the same way.
     n_cmp = len(sel)
     flips = st["tie_flips"] + st["cand_flips"]
-    assert st["raw_agree"] >= min(min_agree, 1.0 - flips / n_cmp)
+    if n_cmp >= 100:
+        assert st["raw_agree"] >= min_agree
+    else:
+        assert st["raw_agree"] >= min(min_agree, 1.0 - flips / n_cmp)
     assert st["tie_flips"] <= max(2, n_cmp // 50)
     assert st["cand_flips"] <= max(2, n_cmp // 20)
     if mse:
@@ -565,15 +569,20 @@ def test_end_to_end_c1():
 
 
 # ------------------------------------------------------------- full size, sampled oracle ---
-def _full_size_sampled(name, n_rows, act, search=False):
+def _sample_rows(d_out, n, seed=7):
+    return np.sort(np.random.default_rng(seed).choice(d_out, size=n, replace=False))
+
+
+def _full_size_sampled(name, act, sweeps):
     """One full-size layer of the benchmark configurations (bf16, d_in 14336): Gram against the oracle, both forms
-    of the factor against the oracle's for the same H, sweep on sampled rows with tie replay, both forms.  The
-    calibration set is cut to 32768 tokens (still more than 2 d_in, so H has full rank as in the real workload)
-    so that the float64 oracle finishes in about half a minute."""
+    of the factor against the oracle's for the same H, sweeps on sampled rows with tie replay.  The calibration set
+    is cut to 32768 tokens (still more than 2 d_in, so H has full rank as in the real workload) so that the float64
+    oracle finishes in about a minute.  sweeps: list of (bits, n_rows, grid, form); the bar on raw agreement is
+    99.9 % of the compared entries everywhere."""
     cfg = synth.scaled(synth.CONFIGS[name], n_tokens=32768)
     d_out, d_in = cfg.d_out, cfg.d_in
     assert cfg.act_order == act
-    _announce(f"full size {name} {d_out}x{d_in} b{cfg.bits} g{cfg.group_size} act={act}: gram ({cfg.n_tokens} tokens)")
+    _announce(f"full size {name} {d_out}x{d_in} g{cfg.group_size} act={act}: gram ({cfg.n_tokens} tokens)")
     X = synth.make_activations(cfg, DEV)
     W = synth.make_weight(cfg, DEV)
     H = _gpu_gram(X)
@@ -598,49 +607,42 @@ def _full_size_sampled(name, n_rows, act, search=False):
     _announce(f"   U rel. Frobenius error {err:.3e}")
     assert err <= 1e-6
     del U
-    _announce(f"full size: sweep, {n_rows} sampled rows")
+    F = None
+    if any(form == "block" for _, _, _, form in sweeps):
+        _announce("full size: factor in block form")
+        F, _, info = og.onecomp_hessian_factor(torch.from_numpy(H32).to(DEV), cfg.damp, act_order=act, form="block")
+        torch.cuda.synchronize()
+        assert int(info.item()) == 0
+        Fo = _oracle_block_factor(f)
+        err = rel_fro(F.cpu().numpy().astype(np.float64), Fo)
+        _announce(f"   F rel. Frobenius error {err:.3e}")
+        assert err <= 1e-6
+        del Fo
     U32 = torch.from_numpy(f["U"].astype(np.float32)).to(DEV)
-    rows = np.sort(np.random.default_rng(7).choice(d_out, size=n_rows, replace=False))
-    # A flip at a tie changes later codes of its row (the feedback differs by a whole grid step), so in a sample
-    # of a few dozen rows one flipped row alone costs a few tenths of a percent of raw agreement: the raw bar is
-    # 99 % here, the flips themselves are bounded, and agreement after replaying the flips must still be exact.
-    _, st = _check_sweep(W, U32, cfg.bits, cfg.group_size, perm=perm if act else None, rows=rows, min_agree=0.99)
-    assert st["tie_flips"] <= 4
-    if search:
-        _announce("full size: sweep with the scale search, same rows")
-        _, st = _check_sweep(W, U32, cfg.bits, cfg.group_size, perm=perm if act else None, rows=rows, min_agree=0.99,
-                             grid="minmax_mse")
-        assert st["tie_flips"] <= 4
-    del U32
-    _announce("full size: factor in block form")
-    F, _, info = og.onecomp_hessian_factor(torch.from_numpy(H32).to(DEV), cfg.damp, act_order=act, form="block")
-    torch.cuda.synchronize()
-    assert int(info.item()) == 0
-    Fo = _oracle_block_factor(f)
-    err = rel_fro(F.cpu().numpy().astype(np.float64), Fo)
-    _announce(f"   F rel. Frobenius error {err:.3e}")
-    assert err <= 1e-6
-    del Fo
-    _announce("full size: sweep with the block form, same rows")
-    U32 = torch.from_numpy(f["U"].astype(np.float32)).to(DEV)
-    _, st = _check_sweep(W, U32, cfg.bits, cfg.group_size, perm=perm if act else None, rows=rows, min_agree=0.99,
-                         F32=F)
-    assert st["tie_flips"] <= 4
+    for bits, n_rows, grid, form in sweeps:
+        _announce(f"full size: sweep b{bits} {grid}, {form} form, {n_rows} sampled rows")
+        _, st = _check_sweep(W, U32, bits, cfg.group_size, perm=perm if act else None, rows=_sample_rows(d_out, n_rows),
+                             min_agree=0.999, grid=grid, F32=F if form == "block" else None)
+        assert st["tie_flips"] <= max(2, n_rows // 50)
 
 
 def test_full_size_down_projection_sampled():
-    """The 4096 x 14336 layer in the launch configuration bench.py times (4-bit, group 128, natural order)."""
-    _full_size_sampled("c3b", 48, act=False, search=True)
+    """The 4096 x 14336 layer in the launch configuration bench.py times (4-bit, group 128, natural order): 512
+    sampled rows with the inverse factor, fewer with the block form and with the scale search."""
+    _full_size_sampled("c3b", False, [(4, 512, "minmax", "inverse"), (4, 128, "minmax", "block"),
+                                      (4, 96, "minmax_mse", "inverse")])
 
 
-def test_full_size_act_order_3bit_sampled():
-    """The same layer at 3 bits, group 64, with activation ordering."""
-    _full_size_sampled("c4_3bit", 32, act=True)
+def test_full_size_act_order_low_bit_sampled():
+    """The same layer at 3 bits and at 2 bits, group 64, with activation ordering, either form of the factor."""
+    _full_size_sampled("c4_3bit", True, [(3, 128, "minmax", "inverse"), (3, 128, "minmax", "block"),
+                                         (2, 128, "minmax", "inverse"), (2, 128, "minmax", "block")])
 
 
 def test_largest_layer_properties():
-    """The widest benchmark layer (8192 x 28672, bf16, 4-bit, group 128) is out of the float64 oracle's reach, so it
-    is checked through properties that hold at any size: H symmetric and equal to library-computed sampled entries,
+    """The widest benchmark layer (8192 x 28672, bf16, 3-bit, group 128): the float64 factorization of a 28672-wide
+    matrix is out of the host's reach inside a test, so Gram and factor are
+    checked through properties that hold at any size: H symmetric and equal to library-computed sampled entries,
     U^T U (H + lambda I) = I on sampled columns, W_hat = scales (Q - zeros) bit for bit, and the returned loss equal
     to tr((W - W_hat) Hd (W - W_hat)^T), an identity that only holds if every residual was propagated through U
     exactly as the sweep prescribes.  Both forms of the factor; their codes must agree but for tie flips."""
@@ -680,6 +682,20 @@ def test_largest_layer_properties():
             del Ud, V, E
         out = og.onecomp_quantize_layer(W, U, cfg.bits, G, form=form)
         torch.cuda.synchronize()
+        if form == "inverse":
+            # the sweep itself against the oracle's at this width, on sampled rows, both fed the GPU's factor
+            rows = _sample_rows(d_out, 24, seed=5)
+            _announce(f"largest layer: oracle sweep of {len(rows)} rows with the GPU's U")
+            Ud = U.cpu().numpy().astype(np.float64)
+            st = compare_codes(out["Q_codes"][torch.from_numpy(rows).to(DEV)].cpu().numpy(),
+                               out["zeros"][torch.from_numpy(rows).to(DEV)].cpu().numpy(), to_f64(W), Ud, cfg.bits, G,
+                               rows=rows)
+            del Ud
+            _announce(f"   raw agreement {st['raw_agree']:.6f}, tie flips {st['tie_flips']}, real {len(st['real_mismatches'])}")
+            assert st["real_mismatches"] == [] and st["final_agree"] == 1.0
+            assert st["raw_agree"] >= min(0.999, 1.0 - st["tie_flips"] / len(rows)) and st["tie_flips"] <= 2
+            np.testing.assert_allclose(out["scales"][torch.from_numpy(rows).to(DEV)].cpu().numpy(), st["oracle"]["scales"],
+                                       rtol=1e-5)
         del U
         Q, S, Z, WH = out["Q_codes"], out["scales"], out["zeros"], out["W_hat"]
         assert int(Q.max().item()) <= 2 ** cfg.bits - 1
