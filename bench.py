@@ -24,6 +24,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# L2 <-> fabric bytes per call from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a plain 4 GiB copy), taken with
+# `python bench.py --phase gram|sweep` under rocprofv3 --pmc; see profiles/c3b_hbm_traffic_pmc.md for the commands
+GRAM_TRAFFIC_C3B = 121.0e9
+SWEEP_TRAFFIC_C3B = 13.5e9
 
 
 def sweep_model_bytes_b128(d_out, d_in, B, G, w_bytes):
@@ -43,8 +47,9 @@ def sweep_model_bytes(d_out, d_in, G, w_bytes, SBW=512):
     """HBM bytes of the schedule onecomp_quantize_layer runs for G <= 128 (super-blocks of SBW = 512 columns):
       preparation   W in, fp32 working copy out; the strict upper block triangle of U read twice (maximum, then
                     split) and written once as two fp16 halves
-      per super-block  its columns of the working copy in, codes / W^ / scales / zeros out, its residuals out as
-                    two fp16 halves (transposed panel), the 128 x 128 diagonal blocks of U in
+      per super-block  its columns of the working copy (the fp32 feedback sums) and of W in, codes / W^ / scales /
+                    zeros out, its residuals out as two fp16 halves (transposed panel), the 128 x 128 diagonal blocks
+                    of U in
       far update    the columns beyond the super-block read and written once (8 B / element), the residual panel
                     and the super-block's rows of the split U read once
     Operands that the panel kernel writes and reads back itself (residual fragments) and re-reads of the same
@@ -55,10 +60,16 @@ def sweep_model_bytes(d_out, d_in, G, w_bytes, SBW=512):
     for s0 in range(0, d_in, SBW):
         s1 = min(d_in, s0 + SBW)
         wdt = s1 - s0
-        total += d_out * wdt * (4 + 1 + 4) + 8 * d_out * wdt // G + d_out * wdt * 4 + (wdt // 128) * 128 * 128 * 4
+        total += d_out * wdt * (4 + w_bytes + 1 + 4) + 8 * d_out * wdt // G + d_out * wdt * 4 + (wdt // 128) * 128 * 128 * 4
         rest = d_in - s1
         total += 8 * d_out * rest + 4 * d_out * wdt + 4 * wdt * rest
     return total
+
+
+def _median(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
 
 
 def gram_kernel_name(d_in, bf16):
@@ -89,7 +100,10 @@ def cpu_baseline(cfg, synth, seconds_hint=20.0):
     Hs = np.ascontiguousarray(H[:d_s, :d_s])
     del H
     t0 = time.perf_counter()
-    f = oc.hessian_factor(Hs, max(cfg.damp, 0.01) * 10.0, act_order=cfg.act_order)   # rank-deficient sample: heavier damping keeps it PD
+    # the sample has full rank when it holds at least as many tokens as columns; a shorter one (the widest layers)
+    # is held positive definite by heavier damping, which does not change the work
+    damp = cfg.damp if n_s >= 2 * d_s else max(cfg.damp, 0.01) * 10.0
+    f = oc.hessian_factor(Hs, damp, act_order=cfg.act_order)
     t_factor = time.perf_counter() - t0
     Wc = synth.scaled(cfg, d_out=r_s, d_in=d_s)
     W = synth.make_weight(Wc, "cpu").to(dtype=__import__("torch").float64).numpy()
@@ -129,7 +143,7 @@ def bench_jointq(args, cfg, og, W, H, out, perm):
         torch.cuda.synchronize()
         if it > 0:
             ms.append(e[0].elapsed_time(e[1]))
-    t = sum(ms) / len(ms)
+    t = _median(ms)
     obj = r["objective"].tolist()
     # products per call: the gradient once; per pass one update per group (groups up to 128 columns) or, for wider
     # groups, a = A_gg u once, one update per scan and the gradient update, each over the group's own columns only
@@ -199,7 +213,7 @@ def bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out):
     torch.cuda.synchronize()
     sens_ms = e_s[0].elapsed_time(e_s[1]) / 10
     names = ["hessian_accumulate", "crossgram_accumulate", "hessian_factor", "qep_target", "quantize_layer"]
-    ph = {n: sum(e[i].elapsed_time(e[i + 1]) for e in rec) / len(rec) for i, n in enumerate(names)}
+    ph = {n: _median([e[i].elapsed_time(e[i + 1]) for e in rec]) for i, n in enumerate(names)}
     total = sum(ph.values())
     return {
         "phases_ms": ph, "ms_per_step": total, "weights_per_sec": d_out * d_in / (total * 1e-3),
@@ -214,12 +228,109 @@ def bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out):
     }
 
 
+def bench_c5(args, og, synth):
+    """The 70B-class configuration as stated: six layer instances (three of 28672 x 8192, three of 8192 x 28672) whose
+    bit-widths are a seeded shuffle of [2, 3, 4, 2, 3, 4].  One step = the whole hot path (accumulate over all
+    calibration tokens, factor, quantize) for each of the six layers in turn, every input resident in HBM; the value
+    is allocation-weighted: all six layers' weights over the step's time.  Layers of one shape share H, U, the
+    outputs and the workspaces (a layer-wise quantizer holds one layer at a time)."""
+    import torch
+    dev = "cuda:0"
+    layers = synth.c5_allocation(0)
+    shapes = {}
+    data = []
+    for cfg in layers:
+        key = (cfg.d_out, cfg.d_in)
+        if key not in shapes:
+            d_out, d_in = key
+            ws_a_bytes = og.onecomp_accumulate_workspace_bytes(cfg.dtype, d_in)
+            shapes[key] = {
+                "H": torch.zeros((d_in, d_in), dtype=torch.float32, device=dev),
+                "U": torch.empty((d_in, d_in), dtype=torch.float32, device=dev),
+                "info": torch.zeros(1, dtype=torch.int32, device=dev),
+                "ws_a": torch.empty(ws_a_bytes, dtype=torch.uint8, device=dev) if ws_a_bytes > 0 else None,
+                "ws_f": torch.empty(og.onecomp_factor_workspace_bytes(d_in), dtype=torch.uint8, device=dev),
+                "ws_q": torch.empty(og.onecomp_quantize_workspace_bytes(d_out, d_in, 128), dtype=torch.uint8, device=dev),
+                "out": {"Q_codes": torch.empty((d_out, d_in), dtype=torch.uint8, device=dev),
+                        "scales": torch.empty((d_out, d_in // cfg.group_size), dtype=torch.float32, device=dev),
+                        "zeros": torch.empty((d_out, d_in // cfg.group_size), dtype=torch.float32, device=dev),
+                        "W_hat": torch.empty((d_out, d_in), dtype=torch.float32, device=dev),
+                        "loss": torch.zeros(1, dtype=torch.float32, device=dev)},
+            }
+        data.append((cfg, synth.make_weight(cfg, dev), synth.make_activations(cfg, dev)))
+
+    def step(rec=None):
+        for i, (cfg, W, X) in enumerate(data):
+            b = shapes[(cfg.d_out, cfg.d_in)]
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            b["H"].zero_()
+            e[0].record()
+            og.onecomp_hessian_accumulate(X, b["H"], workspace=b["ws_a"])
+            e[1].record()
+            og.onecomp_hessian_factor(b["H"], cfg.damp, cfg.act_order, U=b["U"], info=b["info"], workspace=b["ws_f"],
+                                      form=args.factor_form)
+            e[2].record()
+            og.onecomp_quantize_layer(W, b["U"], cfg.bits, cfg.group_size, workspace=b["ws_q"], out=b["out"],
+                                      form=args.factor_form, grid=args.grid)
+            e[3].record()
+            if rec is not None:
+                rec[i].append(e)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    rec = [[] for _ in data]
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(rec)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for b in shapes.values():
+        assert int(b["info"].item()) == 0, "Hessian not positive definite"
+    ms_per_step = wall * 1e3 / args.steps
+    per_layer, weights = [], 0
+    for (cfg, W, X), r in zip(data, rec):
+        ph = [_median([e[i].elapsed_time(e[i + 1]) for e in r]) for i in range(3)]
+        n = cfg.d_out * cfg.d_in
+        weights += n
+        per_layer.append({"layer": cfg.name, "shape": [cfg.d_out, cfg.d_in], "bits": cfg.bits, "tokens": cfg.n_tokens,
+                          "phases_ms": {"hessian_accumulate": ph[0], "hessian_factor": ph[1], "quantize_layer": ph[2]},
+                          "ms": sum(ph), "weights_per_sec": n / (sum(ph) * 1e-3),
+                          "weights_per_sec_factor_plus_sweep": n / ((ph[1] + ph[2]) * 1e-3)})
+    # dominant kernel: the Gram launch of the 28672-wide layers
+    wide = [(cfg, p) for (cfg, _, _), p in zip(data, per_layer) if cfg.d_in == 28672]
+    cfgw, pw = wide[0]
+    gram_ms = _median([p["phases_ms"]["hessian_accumulate"] for _, p in wide])
+    flops = float(cfgw.n_tokens) * cfgw.d_in * (cfgw.d_in + 1)
+    tfl = flops / (gram_ms * 1e-3) / 1e12
+    return {
+        "metric": "weights_quantized_per_sec", "value": weights / (ms_per_step * 1e-3), "unit": "weights/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 inputs, f32 accumulate, f64 factor and sweep decisions", "data": "synthetic",
+        "config": {"workload": "c5: 70B-class shapes, 3 x (28672x8192) + 3 x (8192x28672) bf16, 131072 tokens each, group 128, "
+                               "bit-widths " + ", ".join(f"{c.name.split('_')[0]}={c.bits}" for c, _, _ in data)
+                               + f" (seeded shuffle of 2,3,4,2,3,4; mean 3), {args.grid} grid, damp 0.01, factor form {args.factor_form}; "
+                               "one step = all six layers"},
+        "allocation_weighted_weights_per_sec": weights / (sum(p["ms"] for p in per_layer) * 1e-3),
+        "layers": per_layer,
+        "roofline": {"kernel": "gram_bf16_ring_kernel", "bound": "mfma", "achieved": tfl, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tfl / PEAK_BF16_TFLOPS, "traffic": None,
+                     "note": "Gram call of the 8192x28672 layers (median of the three): T*d_in*(d_in+1) flops / call time",
+                     "call_ms": gram_ms},
+        "cpu_baseline": None,
+        "cpu_baseline_note": "the oracle is timed for the default workload only (python bench.py)",
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c3b", help="synthetic layer config (see paper_2603_28845_amd/synth.py)")
+    ap.add_argument("--workload", default="c3b",
+                    help="synthetic layer config (see paper_2603_28845_amd/synth.py); 'c5' = the six-layer mixed 2/3/4-bit "
+                         "allocation of the 70B-class shapes")
     ap.add_argument("--tokens-per-call", type=int, default=0, help="0 = all calibration tokens in one accumulate call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--phase", default="all", choices=["all", "gram", "factor", "sweep"],
@@ -267,6 +378,9 @@ def main():
     og.load_library()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.workload == "c5":
+        print(json.dumps(bench_c5(args, og, synth)))
+        return
     cfg = synth.CONFIGS[args.workload]
     if args.group_size > 0:
         cfg = synth.scaled(cfg, group_size=args.group_size)
@@ -388,16 +502,16 @@ def main():
             "what": "same step through onecomp_hessian_factor_form / onecomp_quantize_layer_form with "
                     "ONECOMP_FACTOR_BLOCK: one Cholesky instead of Cholesky + triangular inverse; same codes up to ties",
             "ms_per_step": ms_b, "value": d_out * d_in / (ms_b * 1e-3),
-            "phases_ms": {"hessian_accumulate": sum(e[0].elapsed_time(e[1]) for e in rec_b) / len(rec_b),
-                          "hessian_factor": sum(e[1].elapsed_time(e[2]) for e in rec_b) / len(rec_b),
-                          "quantize_layer": sum(e[2].elapsed_time(e[3]) for e in rec_b) / len(rec_b)},
+            "phases_ms": {"hessian_accumulate": _median([e[0].elapsed_time(e[1]) for e in rec_b]),
+                          "hessian_factor": _median([e[1].elapsed_time(e[2]) for e in rec_b]),
+                          "quantize_layer": _median([e[2].elapsed_time(e[3]) for e in rec_b])},
             "loss": float(out["loss"].item()),
         }
 
     tiny = 1e-6   # phases skipped by --phase read as ~0; keep the ratios finite
-    acc_ms = max(tiny, sum(e[0].elapsed_time(e[1]) for e in rec) / len(rec))
-    fac_ms = max(tiny, sum(e[1].elapsed_time(e[2]) for e in rec) / len(rec))
-    swp_ms = max(tiny, sum(e[2].elapsed_time(e[3]) for e in rec) / len(rec))
+    acc_ms = max(tiny, _median([e[0].elapsed_time(e[1]) for e in rec]))   # per-phase times: medians over the steps
+    fac_ms = max(tiny, _median([e[1].elapsed_time(e[2]) for e in rec]))
+    swp_ms = max(tiny, _median([e[2].elapsed_time(e[3]) for e in rec]))
     ms_per_step = wall * 1e3 / args.steps
     weights = d_out * d_in
 
@@ -409,8 +523,10 @@ def main():
     gram_launches = (t256 // 256 + (1 if t256 % 256 else 0)) if (cfg.dtype == torch.bfloat16 and t256 > 512) else 1
     algo_flops = float(tpc) * d_in * (d_in + 1)
     gram_tflops = algo_flops / (gram_ms * 1e-3) / 1e12
-    # counter-backed traffic of the Gram launch: known for the default workload in one call (see profiles/)
-    gram_traffic = 121.0e9 if (cfg.name == "c3b" and n_calls == 1) else None
+    # Counter-backed traffic of the Gram call.  Counters cannot be read from inside this process: the figure is the one
+    # of profiles/c3b_hbm_traffic_pmc.md (rocprofv3 --pmc runs of this file's --phase gram loop), valid for the default
+    # workload in one accumulate call with the workspace; null for anything else.
+    gram_traffic = GRAM_TRAFFIC_C3B if (cfg.name == "c3b" and n_calls == 1) else None
     roofline = {
         "kernel": gram_kernel_name(d_in, cfg.dtype == torch.bfloat16),
         "bound": "mfma", "achieved": gram_tflops, "peak": PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3,
@@ -433,7 +549,11 @@ def main():
     roofline_sweep = {
         "kernel": "onecomp_quantize_layer (panel_far_kernel + trailing_kernel launches)", "bound": "hbm",
         "achieved": sweep_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": sweep_gbs / PEAK_HBM_GBS,
-        "traffic": 13.5e9 if (cfg.name == "c3b") else None, "model_bytes": sweep_bytes,
+        "traffic": SWEEP_TRAFFIC_C3B if (cfg.name == "c3b" and args.grid == "minmax" and args.group_size == 0
+                                          and args.factor_form == "inverse") else None,
+        "traffic_note": "FETCH_SIZE + WRITE_SIZE of all the call's launches, profiles/c3b_hbm_traffic_pmc.md; null for "
+                        "any other configuration",
+        "model_bytes": sweep_bytes,
         "note": "modelled HBM bytes of the two-level schedule actually run (512-column super-blocks) / whole-call "
                 "time; the trailing updates are split-fp16 MFMA GEMMs fed from L2, so the call is not HBM bound",
         "b128_model_bytes": b128_bytes,

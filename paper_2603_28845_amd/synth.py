@@ -52,6 +52,24 @@ CONFIGS = {
 }
 
 
+def c5_allocation(seed: int = 0):
+    """The mixed-precision stand-in of the 70B-class configuration: six layer instances, three of each shape
+    (28672 x 8192 and 8192 x 28672), whose bit-widths are a seeded shuffle of [2, 3, 4, 2, 3, 4] (3 bits on
+    average).  The paper plans bit-widths with an integer program over real models (Sec. 4.1); this seeded
+    allocation only reproduces the mix of widths such a plan hands to the layer-wise quantizer.
+    Returns a list of LayerConfig, each instance with its own seed (distinct weights and activations)."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed * 1000003 + 55)
+    bits = [2, 3, 4, 2, 3, 4]
+    order = torch.randperm(6, generator=g).tolist()
+    shapes = ["c5a", "c5a", "c5a", "c5b", "c5b", "c5b"]
+    out = []
+    for i, name in enumerate(shapes):
+        b = bits[order[i]]
+        out.append(scaled(CONFIGS[name], name=f"{name}#{i % 3}_b{b}", bits=b, seed=seed + i))
+    return out
+
+
 def scaled(cfg: LayerConfig, d_out=None, d_in=None, n_tokens=None, **kw) -> LayerConfig:
     """A copy of cfg at other sizes (outlier count follows d_in unless given)."""
     d_in_new = d_in if d_in is not None else cfg.d_in

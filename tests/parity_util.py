@@ -224,3 +224,61 @@ def compare_jointq(gpu_Q, gpu_S, W, A, Q0, S0, Z, bits, G, grid="asym", n_pass=1
         else:
             real.append(int(rows[i]))
     return {"clean_rows": clean, "flipped_rows": flipped, "flips": flips, "real_mismatches": real, "oracle": res}
+
+
+def compare_jointq_by_scan(gpu_Q_by_scan, gpu_S, W, A, Q0, S0, Z, bits, G, grid="asym", rows=None, perm=None):
+    """One group per row, one pass, several scans: exact replay of onecomp_jointq_refine against the oracle.
+
+    gpu_Q_by_scan[k - 1]: the GPU's codes after a call with max_scans = k (k = 1 .. S), all from the same start; the
+    visit of a row's single group after k scans is the first k scans of the visit with more, so the GPU's decision at
+    column j in scan k is the difference of the codes after k and after k - 1 scans.  Scan by scan, the oracle (run
+    with max_scans = k and the decisions forced so far) must reproduce the GPU's codes; where it first differs, the
+    decision at that column must be one the oracle itself lists as a toss-up (JQ_TIE_TOL, JQ_G_TOL, JQ_A_TOL), which
+    is then forced to the GPU's, and the scan is compared again.  gpu_S: the GPU's scales after the last call.
+    Returns dict(clean_rows, flipped_rows, flips, real_mismatches [(row, scan, column)], oracle)."""
+    W = np.asarray(W, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    rows = np.arange(W.shape[0]) if rows is None else np.asarray(rows)
+    d_in = W.shape[1]
+    assert G == d_in, "one group per row"
+    S = len(gpu_Q_by_scan)
+    gq = [np.asarray(q, dtype=np.int64) for q in gpu_Q_by_scan]
+    Q0 = np.asarray(Q0)
+    pv = np.arange(d_in) if perm is None else np.asarray(perm, dtype=np.int64)
+    kw = dict(bits=bits, group_size=G, grid=grid, n_pass=1, tie_tol=JQ_TIE_TOL, g_tol=JQ_G_TOL, a_tol=JQ_A_TOL, perm=perm)
+    clean, flipped, flips, real = 0, 0, 0, []
+    final = []
+    for i in range(len(rows)):
+        forced, bad = {}, None
+        for k in range(1, S + 1):
+            prev = Q0[rows[i]].astype(np.int64) if k == 1 else gq[k - 2][i]
+            for _ in range(64):
+                cur = oc.jointq_refine(W, A, Q0, S0, Z, rows=rows[i:i + 1], forced=forced, max_scans=k, **kw)
+                j = _jq_first_column(cur, 0, gq[k - 1][i], pv)
+                if j < 0:
+                    break
+                want = int(gq[k - 1][i][pv[j]] - prev[pv[j]])          # the GPU's decision at this position in scan k
+                listed = {t[:5]: t[5] for t in cur["ties"][0]}
+                f2 = dict(forced)
+                for d in (1, -1):
+                    key = (0, 0, k - 1, j, d)
+                    if key in listed and listed[key] != (want == d):
+                        f2[(0,) + key] = (want == d)
+                if f2 == forced:
+                    bad = (int(rows[i]), k - 1, int(j))                  # not a listed toss-up
+                    break
+                forced = f2
+                flips += 1
+            else:
+                bad = (int(rows[i]), k - 1, -1)
+            if bad is not None:
+                break
+        if bad is not None:
+            real.append(bad)
+        elif forced:
+            flipped += 1
+        else:
+            clean += 1
+        final.append(cur)
+    res = {"Q": np.concatenate([c["Q"] for c in final]), "scales": np.concatenate([c["scales"] for c in final])}
+    return {"clean_rows": clean, "flipped_rows": flipped, "flips": flips, "real_mismatches": real, "oracle": res}

@@ -6,7 +6,7 @@ import torch
 import paper_2603_28845_amd as og
 from paper_2603_28845_amd import synth
 from oracle import onecomp_oracle as oc
-from parity_util import compare_jointq, to_f64
+from parity_util import compare_jointq, compare_jointq_by_scan, to_f64
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -187,34 +187,44 @@ def test_jointq_full_size_sampled():
     Wd = to_f64(W)
     H = torch.from_numpy(H32).to(DEV)
     U32 = torch.from_numpy(f["U"].astype(np.float32)).to(DEV)
-    # one group per row: a single scan, so that every decision can be read off the codes and replayed exactly
-    for G, grid, n_rows, scans in ((cfg.group_size, "asym", 12, 4), (d_in, "sym", 6, 1)):
+    # group 128: four scans per visit, compared through the oracle's listed toss-ups.  One group per row (the setting
+    # of the paper's JointQ table, and what bench.py times): four scans as well, replayed exactly scan by scan from
+    # GPU calls with max_scans = 1, 2, 3, 4 (the first k scans of a row's only visit do not depend on max_scans).
+    for G, grid, n_rows, scans in ((cfg.group_size, "asym", 12, 4), (d_in, "sym", 6, 4)):
         ggrid = "symmetric" if grid == "sym" else "minmax"
         rows = np.sort(np.random.default_rng(11).choice(d_out, size=n_rows, replace=False))
         _announce(f"jointq full size g{G} {grid}: oracle sweep of {n_rows} sampled rows, GPU sweep of the layer")
         o0 = oc.quantize_layer(Wd, f["U"], bits, G, rows=rows, grid=grid)
         g0 = og.onecomp_quantize_layer(W, U32, bits, G, want_w_hat=False, grid=ggrid)
-        Q, S, Z = g0["Q_codes"], g0["scales"], g0["zeros"]
         ridx = torch.from_numpy(rows).to(DEV)
-        Q[ridx] = torch.from_numpy(o0["Q"].astype(np.uint8)).to(DEV)
-        S[ridx] = torch.from_numpy(o0["scales"].astype(np.float32)).to(DEV)
-        Z[ridx] = torch.from_numpy(o0["zeros"].astype(np.float32)).to(DEV)
-        _announce("jointq full size: GPU refinement, one pass")
-        out = og.onecomp_jointq_refine(W, H, Q, S, Z, bits, G, grid=ggrid, n_pass=1, max_scans=scans, want_w_hat=False)
-        torch.cuda.synchronize()
-        obj = out["objective"].cpu().numpy()
-        _announce(f"   objective {obj[0]:.4e} -> {obj[1]:.4e}, moves {int(out['n_moves'].item())}")
+        g0["Q_codes"][ridx] = torch.from_numpy(o0["Q"].astype(np.uint8)).to(DEV)
+        g0["scales"][ridx] = torch.from_numpy(o0["scales"].astype(np.float32)).to(DEV)
+        g0["zeros"][ridx] = torch.from_numpy(o0["zeros"].astype(np.float32)).to(DEV)
+        by_scan = []
+        for k in (range(1, scans + 1) if G == d_in else (scans,)):
+            _announce(f"jointq full size: GPU refinement, one pass, up to {k} scan(s) per visit")
+            Q, S = g0["Q_codes"].clone(), g0["scales"].clone()
+            out = og.onecomp_jointq_refine(W, H, Q, S, g0["zeros"], bits, G, grid=ggrid, n_pass=1, max_scans=k,
+                                           want_w_hat=False)
+            torch.cuda.synchronize()
+            obj = out["objective"].cpu().numpy()
+            _announce(f"   objective {obj[0]:.4e} -> {obj[1]:.4e}, moves {int(out['n_moves'].item())}")
+            by_scan.append(out["Q_codes"][ridx].cpu().numpy())
+            gs = out["scales"][ridx].cpu().numpy()
+            del out, Q, S
         assert obj[1] < 0.9 * obj[0]
-        gq = out["Q_codes"][ridx].cpu().numpy()
-        gs = out["scales"][ridx].cpu().numpy()
-        del out, g0, Q, S, Z
+        gq = by_scan[-1]
+        del g0
         torch.cuda.empty_cache()
         _announce("jointq full size: oracle refinement of the sampled rows")
         S0f = o0["scales"].astype(np.float32).astype(np.float64)
-        st = compare_jointq(gq, gs, Wd[rows], A, o0["Q"], S0f, o0["zeros"], bits, G, grid=grid, n_pass=1,
-                            max_scans=scans, wide=G > 128)
+        if G == d_in:
+            st = compare_jointq_by_scan(by_scan, gs, Wd[rows], A, o0["Q"], S0f, o0["zeros"], bits, G, grid=grid)
+        else:
+            st = compare_jointq(gq, gs, Wd[rows], A, o0["Q"], S0f, o0["zeros"], bits, G, grid=grid, n_pass=1,
+                                max_scans=scans, wide=G > 128)
         _announce(f"   clean rows {st['clean_rows']}/{len(rows)}, rows equal after {st['flips']} forced toss-ups: "
-                  f"{st['flipped_rows']}, real mismatches {len(st['real_mismatches'])}")
+                  f"{st['flipped_rows']}, real mismatches {st['real_mismatches']}")
         assert st["real_mismatches"] == []
         assert np.array_equal(st["oracle"]["Q"], gq)
         np.testing.assert_allclose(gs, st["oracle"]["scales"], rtol=1e-4)
