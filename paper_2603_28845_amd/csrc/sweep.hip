@@ -175,50 +175,9 @@ struct PanelArgs {
     int mse;                // scale search: the group's range is shrunk by 1 - i / 100, i < 80; least squared error wins
 };
 
-// Scale search of one group ("mse" option of Sec. 4.3).  partial(z, 1 / s) returns the sum of ((w - w^) / s)^2 over
-// this lane's values of the group on the grid (s, z) (mse_term per value); reduce(x) sums x over the lanes that share
-// the group.  Candidate i takes (s, z) by the grid's rule from the range shrunk by p_i = 1 - i / 100; the first
-// smallest error wins, candidate 0 is the plain rule.  The candidates are compared in fp32; all lanes of the group
-// return the same index, from which the caller takes the scale in fp64 (grid_params), and the zero-point the
-// winner was evaluated with (at a rounding tie of -lo / s the fp64 rule might pick the other neighbour, whose
-// error was not the one compared).
-constexpr int MSE_CANDIDATES = 80;
-// one value's squared error in units of the scale: t = v / s + z, ((t - clamp(rne(t), 0, qmax)))^2; the caller
-// multiplies the sum by s^2.  (rne(v / s) + z and rne(v / s + z) agree except at exact ties, where both choices give
-// the same error.)
-__device__ __forceinline__ float mse_term(float v, float zi, float rsi, float qmax) {
-    const float t = fmaf(v, rsi, zi);
-    const float d = t - __builtin_amdgcn_fmed3f(rintf(t), 0.f, qmax);
-    return d * d;
-}
-template <typename P, typename R>
-__device__ __forceinline__ int mse_search(const float mn, const float mx, const float qmax, const float qs,
-                                          P&& partial, R&& reduce, float& zbest) {
-    float best = 3.0e38f;
-    int ibest = 0;
-    zbest = 0.f;
-#pragma unroll 1
-    for (int i = 0; i < MSE_CANDIDATES; ++i) {
-        const float p = 1.0f - float(i) * 0.01f;
-        const float lo = p * mn, hi = p * mx;
-        float si, zi;
-        if (qs > 0.f) {
-            si = fmaxf(fabsf(lo), fabsf(hi)) / qs;
-            if (si == 0.f) si = 1.f;
-            zi = qs;
-        } else {
-            si = (hi - lo) / qmax;
-            if (si == 0.f) si = 1.f;
-            zi = fminf(fmaxf(rintf(-lo / si), 0.f), qmax);
-        }
-        const float err = si * si * reduce(partial(zi, 1.0f / si));
-        if (err < best) { best = err; ibest = i; zbest = zi; }
-    }
-    return ibest;
-}
-
-// Scale and zero-point of a group from the smallest and largest of its current values, in fp64: Eq. (2), or Eq. (3)
-// when qs > 0 (symmetric grid, zero-point qs); cand > 0: from the range shrunk by 1 - cand / 100 (scale search).
+// Scale and zero-point of a group from the smallest and largest of its current values, in fp64, operation by
+// operation as the definition reads: Eq. (2), or Eq. (3) when qs > 0 (symmetric grid, zero-point qs); cand > 0: from
+// the range shrunk by 1 - cand / 100 (scale search).
 __device__ __forceinline__ void grid_params(double mn, double mx, const int cand, const double qmax, const double qs,
                                             double& s, double& z) {
     if (cand > 0) {
@@ -234,6 +193,37 @@ __device__ __forceinline__ void grid_params(double mn, double mx, const int cand
         if (s == 0.0) s = 1.0;
         z = fmin(fmax(rint(-mn / s), 0.0), qmax);
     }
+}
+
+// Scale search of one group ("mse" option of Sec. 4.3).  partial(z, 1 / s) returns the sum of ((w - w^) / s)^2 over
+// this lane's values of the group on the grid (s, z) (mse_term per value); reduce(x) sums x over the lanes that share
+// the group.  Candidate i takes (s, z) by the grid's rule from the range shrunk by p_i = 1 - i / 100 (grid_params,
+// fp64: a zero-point at an exact rounding tie, e.g. a group with min = -max, then falls the same way for every
+// candidate and for the final parameters); the errors are summed and compared in fp32; the first smallest error
+// wins, candidate 0 is the plain rule.  All lanes of the group return the same index.
+constexpr int MSE_CANDIDATES = 80;
+// one value's squared error in units of the scale: t = v / s + z, ((t - clamp(rne(t), 0, qmax)))^2; the caller
+// multiplies the sum by s^2.  (rne(v / s) + z and rne(v / s + z) agree except at exact ties, where both choices give
+// the same error.)
+__device__ __forceinline__ float mse_term(float v, float zi, float rsi, float qmax) {
+    const float t = fmaf(v, rsi, zi);
+    const float d = t - __builtin_amdgcn_fmed3f(rintf(t), 0.f, qmax);
+    return d * d;
+}
+template <typename P, typename R>
+__device__ __forceinline__ int mse_search(const double mn, const double mx, const double qmax, const double qs,
+                                          P&& partial, R&& reduce) {
+    float best = 3.0e38f;
+    int ibest = 0;
+#pragma unroll 1
+    for (int i = 0; i < MSE_CANDIDATES; ++i) {
+        double sd, zd;
+        grid_params(mn, mx, i, qmax, qs, sd, zd);
+        const float si = float(sd);
+        const float err = si * si * reduce(partial(float(zd), 1.0f / si));
+        if (err < best) { best = err; ibest = i; }
+    }
+    return ibest;
 }
 
 constexpr int PANEL_LDS = (SB * SB + 2 * ROWS * SP + 2 * SB + 3 * ROWS * 8) * 4;
@@ -531,7 +521,6 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                             }
                             if (fresh) {
                                 int cand = 0;
-                                float zsearch = 0.f;
                                 if constexpr (GB != 16) {
                                     if (a.mse) {   // uniform; this lane's quarter of the group, held in registers
                                         const float* gc = sC + qrow * SP + jb + sl;
@@ -544,7 +533,7 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                                         }
                                         const int n8 = G >> 5;   // batches of 8 values: 1, 2 or 4
                                         const float qmf = a.qmax;
-                                        cand = mse_search(float(mn), float(mx), qmf, a.qs,
+                                        cand = mse_search(mn, mx, qmax, qsd,
                                                    [&](float zi, float rsi) __attribute__((always_inline)) {
                                                        float e0 = 0.f, e1 = 0.f;
 #pragma unroll
@@ -571,7 +560,7 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                                                    [&](float x) __attribute__((always_inline)) {
                                                        x += dpp_quad<QUAD_SWAP1>(x);
                                                        return x + dpp_quad<QUAD_SWAP2>(x);
-                                                   }, zsearch);
+                                                   });
                                     }
                                 } else {
                                     if (a.mse) {   // uniform; the group's 16 values sit in two lanes of the quad
@@ -579,7 +568,7 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
 #pragma unroll
                                         for (int k = 0; k < 8; ++k) gv[k] = float(w[k]);
                                         const float qmf = a.qmax;
-                                        cand = mse_search(float(mn), float(mx), qmf, a.qs,
+                                        cand = mse_search(mn, mx, qmax, qsd,
                                                    [&](float zi, float rsi) __attribute__((always_inline)) {
                                                        float e0 = 0.f, e1 = 0.f;
 #pragma unroll
@@ -592,11 +581,10 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                                                    [&](float x) __attribute__((always_inline)) {
                                                        x += dpp_quad<QUAD_SWAP1>(x);
                                                        return dpp_quad<quad_bcast(j / 8)>(x);
-                                                   }, zsearch);
+                                                   });
                                     }
                                 }
                                 grid_params(mn, mx, cand, qmax, qsd, s, z);
-                                if (a.mse) z = double(zsearch);
                                 rs = 1.0 / s;
                                 if (sl == 0) {
                                     const int gi = (jb + j) >> a.lgG;
@@ -610,7 +598,12 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                             }
                         }
                         const double wj = dpp_quad<quad_bcast(j / 8)>(w[j % 8]);
-                        const double q = fmin(fmax(rint(wj * rs) + z, 0.0), qmax);   // w / s as w * fl64(1 / s)
+                        // w / s as w * fl64(1 / s); within rounding of a tie the quotient itself decides, so that an
+                        // exact tie (weights and scale are short binary numbers in a row's first group) falls as the
+                        // definition's division does
+                        double t = wj * rs;
+                        if (fabs(fabs(t - rint(t)) - 0.5) < 1e-9) t = wj / s;
+                        const double q = fmin(fmax(rint(t) + z, 0.0), qmax);
                         const double e = __builtin_fma(-s, q - z, wj) * rdc;         // (w - s (q - z)) / U_jj
                         // feedback inside the inner block: w_k -= e U_jk.  Columns up to j are finished, updating
                         // them is harmless; in the last slice the finished registers are skipped.
@@ -1138,9 +1131,8 @@ __global__ __launch_bounds__(256) void group_params_kernel(const T* __restrict__
         mn = smn[0]; mx = smx[0];
         __syncthreads();
         int cand = 0;
-        float zsearch = 0.f;
         if (mse) {   // uniform; the row's values are re-read from cache for every candidate
-            cand = mse_search(float(mn), float(mx), qmax, qs,
+            cand = mse_search(mn, mx, double(qmax), double(qs),
                        [&](float zi, float rsi) __attribute__((always_inline)) {
                            float e = 0.f;
                            for (int c = threadIdx.x; c < G; c += 256) e += mse_term(float(value(c)), zi, rsi, qmax);
@@ -1155,11 +1147,10 @@ __global__ __launch_bounds__(256) void group_params_kernel(const T* __restrict__
                            for (int w = 0; w < 256; w += 4) t += sred[w];
                            __syncthreads();
                            return t;
-                       }, zsearch);
+                       });
         }
         double s, z;
         grid_params(mn, mx, cand, double(qmax), double(qs), s, z);
-        if (mse) z = double(zsearch);
         if (threadIdx.x == 0) {
             scales[r * n_g + g_idx] = float(s);
             zeros[r * n_g + g_idx] = float(z);
