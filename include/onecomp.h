@@ -310,6 +310,24 @@ onecomp_status onecomp_rtn_sensitivity(const void* W, onecomp_dtype w_dtype, int
 size_t onecomp_sensitivity_workspace_bytes(void);
 
 /*
+ * onecomp_rtn_sensitivity for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight planning loops over many (bits, group size) candidates, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels, result (bit for bit) and errors as onecomp_rtn_sensitivity, without the workspace: the
+ * per-workgroup partial sums (2048 floats, 8 KB) go to a fixed array in the library's device data segment, one per
+ * GPU, held until the process ends.  The call allocates and frees nothing and never synchronizes; its first use on
+ * a device looks the array's address up (no allocation, no stream operation).
+ *   - Limits: d_out and d_in up to 2^24 as for onecomp_rtn_sensitivity (the scratch is sized for the largest launch,
+ *     so no smaller limit applies); beyond them ONECOMP_ERR_INVALID_ARG, nothing is launched.
+ *   - Every call on a GPU uses that GPU's one array, which keeps the last call's contents; each call overwrites the
+ *     part it reads, so nothing has to be cleared.  Calls that overlap on one GPU (different streams or host
+ *     threads) race on it: serialize them, or use onecomp_rtn_sensitivity with separate workspaces.
+ */
+onecomp_status onecomp_rtn_sensitivity_static(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                              const float* a_diag, const float* b_diag,
+                                              int bits, int group_size, onecomp_grid grid, float* err,
+                                              void* hip_stream);
+
+/*
  * JointQ refinement of a quantized layer (Sec. 4.3.2, Eq. (jointq); with lam > 0 Eq. (jointq_reg)): local search over
  * the integer codes, the scale of the touched group refit in the same move, started from a solution in the format
  * onecomp_quantize_layer returns.  Per output row the objective is

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     onecomp_quantize_layer,
     onecomp_quantize_workspace_bytes,
     onecomp_rtn_sensitivity,
+    onecomp_rtn_sensitivity_static,
     onecomp_version,
     status_string,
 )

@@ -44,6 +44,7 @@ EXPORTED_SYMBOLS = (
     "onecomp_qep_workspace_bytes",
     "onecomp_rtn_sensitivity",
     "onecomp_sensitivity_workspace_bytes",
+    "onecomp_rtn_sensitivity_static",
     "onecomp_jointq_refine",
     "onecomp_jointq_workspace_bytes",
     "onecomp_status_string",
@@ -100,6 +101,8 @@ def load_library() -> ctypes.CDLL:
     lib.onecomp_qep_workspace_bytes.restype = sz
     lib.onecomp_rtn_sensitivity.argtypes = [vp, i32, i64, i64, vp, vp, i32, i32, i32, vp, vp, sz, vp]
     lib.onecomp_rtn_sensitivity.restype = i32
+    lib.onecomp_rtn_sensitivity_static.argtypes = [vp, i32, i64, i64, vp, vp, i32, i32, i32, vp, vp]
+    lib.onecomp_rtn_sensitivity_static.restype = i32
     lib.onecomp_sensitivity_workspace_bytes.argtypes = []
     lib.onecomp_sensitivity_workspace_bytes.restype = sz
     lib.onecomp_jointq_refine.argtypes = [vp, i32, i64, i64, vp, vp, f32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
@@ -326,6 +329,26 @@ def onecomp_rtn_sensitivity(W: torch.Tensor, a_diag: torch.Tensor, bits: int, gr
                                      workspace.numel(), _stream())
     if rc != ONECOMP_OK:
         raise OnecompError(rc, "onecomp_rtn_sensitivity")
+    return err
+
+
+def onecomp_rtn_sensitivity_static(W: torch.Tensor, a_diag: torch.Tensor, bits: int, group_size: int,
+                                   b_diag: Optional[torch.Tensor] = None, grid: str = "minmax",
+                                   err: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """onecomp_rtn_sensitivity without a workspace (the library's built-in scratch).  Pass `err` (device fp32[1]) to keep
+    this wrapper from allocating as well."""
+    lib = load_library()
+    d_out, d_in = W.shape
+    if err is None:
+        err = torch.zeros(1, dtype=torch.float32, device=W.device)
+    if grid not in ("minmax", "symmetric"):
+        raise ValueError("grid must be 'minmax' or 'symmetric'")
+    rc = lib.onecomp_rtn_sensitivity_static(_dev(W, "W"), _dtype_code(W), d_out, d_in,
+                                            _dev(a_diag, "a_diag", torch.float32), _ptr(b_diag), int(bits), int(group_size),
+                                            ONECOMP_GRID_SYMMETRIC if grid == "symmetric" else ONECOMP_GRID_MINMAX,
+                                            _dev(err, "err", torch.float32), _stream())
+    if rc != ONECOMP_OK:
+        raise OnecompError(rc, "onecomp_rtn_sensitivity_static")
     return err
 
 

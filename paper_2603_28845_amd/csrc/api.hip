@@ -206,6 +206,24 @@ ONECOMP_API onecomp_status onecomp_rtn_sensitivity(const void* W, onecomp_dtype 
                            static_cast<hipStream_t>(hip_stream));
 }
 
+ONECOMP_API onecomp_status onecomp_rtn_sensitivity_static(const void* W, onecomp_dtype w_dtype, int64_t d_out,
+                                                          int64_t d_in, const float* a_diag, const float* b_diag,
+                                                          int bits, int group_size, onecomp_grid grid, float* err,
+                                                          void* hip_stream) {
+    if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
+    if (grid != ONECOMP_GRID_MINMAX && grid != ONECOMP_GRID_SYMMETRIC) return ONECOMP_ERR_UNSUPPORTED;
+    if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return ONECOMP_ERR_UNSUPPORTED;
+    if (!W || !a_diag || !err) return ONECOMP_ERR_INVALID_ARG;
+    // the built-in scratch holds one partial sum per workgroup of a grid capped at 2048 workgroups, which covers every
+    // size up to the limits below; anything beyond them is rejected here, before any launch
+    if (d_out <= 0 || d_in <= 0 || d_out > (1 << 24) || d_in > (1 << 24)) return ONECOMP_ERR_INVALID_ARG;
+    if (group_size <= 0 || d_in % group_size != 0) return ONECOMP_ERR_INVALID_ARG;
+    if (group_size % 16 != 0) return ONECOMP_ERR_UNSUPPORTED;
+    if (!aligned(W, 16) || !aligned(a_diag, 16)) return ONECOMP_ERR_INVALID_ARG;
+    return sensitivity_run_static(W, w_dtype, d_out, d_in, a_diag, b_diag, bits, group_size, int(grid), err,
+                                  static_cast<hipStream_t>(hip_stream));
+}
+
 ONECOMP_API const char* onecomp_status_string(onecomp_status status) {
     switch (status) {
         case ONECOMP_OK: return "ok";

@@ -149,6 +149,10 @@ onecomp_status sensitivity_run(const void* W, onecomp_dtype w_dtype, int64_t d_o
                                const float* b_diag, int bits, int group_size, int grid, float* err, void* workspace,
                                hipStream_t stream);
 
+onecomp_status sensitivity_run_static(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                      const float* a_diag, const float* b_diag, int bits, int group_size, int grid,
+                                      float* err, hipStream_t stream);
+
 size_t jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size);
 onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* A,
                           const int32_t* perm, float lam, int bits, int group_size, int grid, int n_pass, int max_scans, uint8_t* Q, float* scales,

@@ -127,9 +127,35 @@ __global__ __launch_bounds__(256) void sens_final_kernel(const float* __restrict
 
 constexpr int SENS_WGS = 2048;
 
+// Scratch of the entry point that takes no workspace: the per-workgroup partial sums, SENS_WGS floats (8 KB), in
+// device memory that belongs to the loaded code object (one copy per GPU, held until the process ends).  In host
+// code the array's name is only a handle: the device address is looked up once per device and used from then on.
+static __device__ __align__(256) float scratch[SENS_WGS];
+
+// device address of `scratch` on the current device (nullptr on failure); looked up on the first call per device
+float* scratch_address() {
+    static std::atomic<float*> cache[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    const bool cached = dev >= 0 && dev < 64;
+    float* p = cached ? cache[dev].load(std::memory_order_acquire) : nullptr;
+    if (p) return p;
+    if (hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    if (cached) cache[dev].store(p, std::memory_order_release);
+    return p;
+}
+
 }  // namespace
 
 size_t sensitivity_workspace_bytes() { return size_t(SENS_WGS) * sizeof(float); }
+
+onecomp_status sensitivity_run_static(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in,
+                                      const float* a_diag, const float* b_diag, int bits, int group_size, int grid,
+                                      float* err, hipStream_t stream) {
+    float* ws = scratch_address();
+    if (!ws) return ONECOMP_ERR_HIP;
+    return sensitivity_run(W, w_dtype, d_out, d_in, a_diag, b_diag, bits, group_size, grid, err, ws, stream);
+}
 
 onecomp_status sensitivity_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* a_diag,
                                const float* b_diag, int bits, int group_size, int grid, float* err, void* workspace,
