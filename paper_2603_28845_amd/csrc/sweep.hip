@@ -598,18 +598,26 @@ __device__ __forceinline__ void panel_body(const PanelArgs& a, const int wg, cha
                             }
                         }
                         const double wj = dpp_quad<quad_bcast(j / 8)>(w[j % 8]);
-                        // w / s as w * fl64(1 / s); within rounding of a tie the quotient itself decides, so that an
-                        // exact tie (weights and scale are short binary numbers in a row's first group) falls as the
-                        // definition's division does
-                        double t = wj * rs;
-                        if (fabs(fabs(t - rint(t)) - 0.5) < 1e-9) t = wj / s;
+                        // w / s correctly rounded, as the definition's division gives it (an exact tie, possible in a
+                        // row's first group where weights and scale are short binary numbers, then falls the same way):
+                        // t0 = w * fl(1 / s), residual by FMA, one correction step; no division, no branch
+                        const double t0 = wj * rs;
+                        const double t = __builtin_fma(__builtin_fma(-t0, s, wj), rs, t0);
                         const double q = fmin(fmax(rint(t) + z, 0.0), qmax);
                         const double e = __builtin_fma(-s, q - z, wj) * rdc;         // (w - s (q - z)) / U_jj
                         // feedback inside the inner block: w_k -= e U_jk.  Columns up to j are finished, updating
                         // them is harmless; in the last slice the finished registers are skipped.
+                        // The register the next step broadcasts comes first, and every update is pinned to this step:
+                        // left alone, the compiler sinks each register's updates to its next use, a dependent chain
+                        // of up to 32 FMAs in front of a decision (and recomputed for each of the four lanes' turns).
 #pragma unroll
-                        for (int i = 0; i < 8; ++i)
-                            if (j < 24 || i > j % 8) w[i] = __builtin_fma(-e, double(cur[i / 4][i % 4]), w[i]);
+                        for (int ii = 0; ii < 8; ++ii) {
+                            const int i = (j + 1 + ii) % 8;
+                            if (j < 24 || i > j % 8) {
+                                w[i] = __builtin_fma(-e, double(cur[i / 4][i % 4]), w[i]);
+                                asm volatile("" : "+v"(w[i]));
+                            }
+                        }
                         sE[qrow * SP + jb + j] = float(e);
                         sC[qrow * SP + jb + j] = float(q);
                         rdc = rdn;

@@ -628,9 +628,9 @@ def _full_size_sampled(name, act, sweeps):
 
 def test_full_size_down_projection_sampled():
     """The 4096 x 14336 layer in the launch configuration bench.py times (4-bit, group 128, natural order): 512
-    sampled rows with the inverse factor, fewer with the block form and with the scale search."""
+    sampled rows with the inverse factor, 128 with the block form and with the scale search."""
     _full_size_sampled("c3b", False, [(4, 512, "minmax", "inverse"), (4, 128, "minmax", "block"),
-                                      (4, 96, "minmax_mse", "inverse")])
+                                      (4, 128, "minmax_mse", "inverse")])
 
 
 def test_full_size_act_order_low_bit_sampled():
