@@ -26,8 +26,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # L2 <-> fabric bytes per call from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a plain 4 GiB copy), taken with
 # `python bench.py --phase gram|sweep` under rocprofv3 --pmc; see profiles/c3b_hbm_traffic_pmc.md for the commands
-GRAM_TRAFFIC_C3B = 121.0e9
-SWEEP_TRAFFIC_C3B = 13.5e9
+GRAM_TRAFFIC_C3B = 128.0e9    # 127.2 GB fetched + 0.86 GB written per accumulate call
+SWEEP_TRAFFIC_C3B = 13.6e9
 
 
 def sweep_model_bytes_b128(d_out, d_in, B, G, w_bytes):

@@ -3,9 +3,10 @@
 Bars:
   G        relative Frobenius error <= 1e-4 (bf16 products exact in fp32, fp32 accumulation), as for H
   W*       against the oracle's target for the SAME fp32 G, H (isolates the call): relative Frobenius error of
-           W* <= 2e-6, and of the correction W* - W <= 1e-4.  The correction is W (G - H)^T (H + lambda I)^-1 in
-           fp32 (G - H itself is exact here: both are given in fp32 and agree in their leading digits); three fp32
-           GEMMs with K up to d_in and a factor U rounded to fp32 give ~1e-6 (measured 1e-6 .. 4e-6).
+           W* <= 2e-6, and of the correction W* - W <= 1e-4.  The correction is W (G - H)^T (H + lambda I)^-1
+           (G - H itself is exact here: both are given in fp32 and agree in their leading digits); three products
+           with K up to d_in, each from operands split into two fp16 halves (22 significant bits, fp32
+           accumulation), and a factor U rounded to fp32 give ~1e-6 (measured 1e-6 .. 4e-6).
 """
 import numpy as np
 import pytest
