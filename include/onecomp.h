@@ -170,8 +170,8 @@ onecomp_status onecomp_hessian_factor_form(const float* H, int64_t d_in, float d
  * fraction of a grid step over thousands of columns (one wrong rounding at a near-tie changes the rest of its row),
  * so the compensated weight is never held in fp32: the original weight (exact) and the feedback sum
  * c_j = -sum_{i<j} e_i U_ij (a fraction of a grid step) are kept apart, c in fp32; inside a 32-column inner block
- * w = w0 + c, the scale (fp64 division; returned rounded to fp32), the decision rne(w * fl64(1 / s)) and the feedback
- * run in fp64.  Feedback that crosses an inner block is accumulated from zero (fp32 MFMA inside a 128-column block;
+ * w = w0 + c, the scale (fp64 division; returned rounded to fp32), the decision rne(w / s) (the correctly rounded
+ * quotient, from the reciprocal and one correction by the FMA residual) and the feedback run in fp64.  Feedback that crosses an inner block is accumulated from zero (fp32 MFMA inside a 128-column block;
  * across blocks as (w_j - w^_j) * (U_jk / U_jj) with both factors rounded to 22 significant bits: two fp16 halves
  * after an exact power-of-two scaling taken from max |W| and max |U_jk / U_jj|, fp32 accumulation) and added to c
  * once.  A residual above 8 max|W|, which no sweep of a sane layer produces, would saturate on its way into the fp16
