@@ -32,6 +32,9 @@
  *     launched; a numerical failure (matrix not positive definite) is reported
  *     through the device scalar `info`.
  *   - The binary contains gfx950 code only.
+ *   - Profiling: with ONECOMP_ROCTX=1 in the environment at the first call, every launching entry point pushes a
+ *     ROCTx range named after itself (the ROCTx library is looked up at run time; `rocprofv3 --marker-trace` shows
+ *     the ranges).  A range covers the argument checks and the enqueueing of the launches, not the kernels' run time.
  */
 #ifndef ONECOMP_H
 #define ONECOMP_H

@@ -1,10 +1,45 @@
 // extern "C" boundary: argument checks, then dispatch to the kernel launchers.  See include/onecomp.h.
 #include "common.hpp"
+#include <dlfcn.h>
+#include <cstdlib>
 
 using namespace onecomp;
 
 namespace {
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Named host ranges around the entry points for a profiler's marker trace (rocprofv3 --marker-trace), off unless the
+// environment holds ONECOMP_ROCTX=1 when the first entry point is called: then the ROCTx library is looked up at run
+// time (the library does not link against it) and every call pushes a range with its own name.  The launches are
+// asynchronous, so a range covers the argument checks and the enqueueing, not the kernels' run time.
+struct Roctx {
+    int (*push)(const char*) = nullptr;
+    int (*pop)() = nullptr;
+};
+const Roctx& roctx() {
+    static const Roctx r = [] {
+        Roctx x;
+        const char* e = std::getenv("ONECOMP_ROCTX");
+        if (!e || e[0] != '1' || e[1] != 0) return x;
+        for (const char* lib : {"librocprofiler-sdk-roctx.so.1", "librocprofiler-sdk-roctx.so", "libroctx64.so.4", "libroctx64.so"}) {
+            void* h = dlopen(lib, RTLD_NOW | RTLD_LOCAL);
+            if (!h) continue;
+            x.push = reinterpret_cast<int (*)(const char*)>(dlsym(h, "roctxRangePushA"));
+            x.pop = reinterpret_cast<int (*)()>(dlsym(h, "roctxRangePop"));
+            if (x.push && x.pop) return x;
+            x = Roctx();
+        }
+        return x;
+    }();
+    return r;
+}
+struct ApiRange {
+    const Roctx& r;
+    explicit ApiRange(const char* name) : r(roctx()) { if (r.push) r.push(name); }
+    ~ApiRange() { if (r.push) r.pop(); }
+    ApiRange(const ApiRange&) = delete;
+    ApiRange& operator=(const ApiRange&) = delete;
+};
 }  // namespace
 
 #define ONECOMP_API __attribute__((visibility("default")))
@@ -18,6 +53,7 @@ ONECOMP_API size_t onecomp_accumulate_workspace_bytes(onecomp_dtype x_dtype, int
 ONECOMP_API onecomp_status onecomp_hessian_accumulate_ws(const void* X, onecomp_dtype x_dtype, int64_t n_tokens,
                                                          int64_t d_in, int64_t ldx, float* H, void* workspace,
                                                          size_t workspace_bytes, void* hip_stream) {
+    const ApiRange range("onecomp_hessian_accumulate_ws");
     if (x_dtype != ONECOMP_F32 && x_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
     if (!H || d_in <= 0 || n_tokens < 0 || ldx < d_in) return ONECOMP_ERR_INVALID_ARG;
     if (d_in % 16 != 0 || d_in > (1 << 20)) return ONECOMP_ERR_INVALID_ARG;
@@ -46,6 +82,7 @@ ONECOMP_API onecomp_status onecomp_hessian_factor_form(const float* H, int64_t d
                                                        onecomp_factor_form form, int32_t* perm_out, float* F_out,
                                                        int32_t* info, void* workspace, size_t workspace_bytes,
                                                        void* hip_stream) {
+    const ApiRange range("onecomp_hessian_factor_form");
     if (form != ONECOMP_FACTOR_INVERSE && form != ONECOMP_FACTOR_BLOCK) return ONECOMP_ERR_UNSUPPORTED;
     if (!H || !F_out || !info || d_in <= 0) return ONECOMP_ERR_INVALID_ARG;
     if (d_in % 16 != 0 || d_in > 46336) return ONECOMP_ERR_INVALID_ARG;
@@ -76,6 +113,7 @@ ONECOMP_API onecomp_status onecomp_quantize_layer_form(const void* W, onecomp_dt
                                                        onecomp_grid grid, uint8_t* Q_codes, float* scales,
                                                        float* zeros, float* W_hat, float* loss, void* workspace,
                                                        size_t workspace_bytes, void* hip_stream) {
+    const ApiRange range("onecomp_quantize_layer_form");
     const float* U = F;
     if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
     if (grid != ONECOMP_GRID_MINMAX && grid != ONECOMP_GRID_SYMMETRIC && grid != ONECOMP_GRID_MINMAX_MSE &&
@@ -121,6 +159,7 @@ ONECOMP_API onecomp_status onecomp_quantize_layer(const void* W, onecomp_dtype w
 ONECOMP_API onecomp_status onecomp_crossgram_accumulate(const void* X_hat, const void* X, onecomp_dtype x_dtype,
                                                         int64_t n_tokens, int64_t d_in, int64_t ldxh, int64_t ldx,
                                                         float* G, void* hip_stream) {
+    const ApiRange range("onecomp_crossgram_accumulate");
     if (x_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
     if (!G || d_in <= 0 || n_tokens < 0 || ldxh < d_in || ldx < d_in) return ONECOMP_ERR_INVALID_ARG;
     if (d_in % 16 != 0 || d_in > (1 << 20)) return ONECOMP_ERR_INVALID_ARG;
@@ -142,6 +181,7 @@ ONECOMP_API onecomp_status onecomp_qep_target(const void* W, onecomp_dtype w_dty
                                               const float* G, const float* H, const float* U, const int32_t* perm,
                                               float alpha, float* W_star, void* workspace, size_t workspace_bytes,
                                               void* hip_stream) {
+    const ApiRange range("onecomp_qep_target");
     if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
     if (!W || !G || !H || !U || !W_star) return ONECOMP_ERR_INVALID_ARG;
     if (d_out <= 0 || d_in <= 0 || d_in % 16 != 0 || d_in > 65535 || d_out > (1 << 24)) return ONECOMP_ERR_INVALID_ARG;
@@ -168,6 +208,7 @@ ONECOMP_API onecomp_status onecomp_jointq_refine(const void* W, onecomp_dtype w_
                                                  float* scales, const float* zeros, float* W_hat, float* objective,
                                                  int32_t* n_moves, void* workspace, size_t workspace_bytes,
                                                  void* hip_stream) {
+    const ApiRange range("onecomp_jointq_refine");
     if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
     if (grid != ONECOMP_GRID_MINMAX && grid != ONECOMP_GRID_SYMMETRIC && grid != ONECOMP_GRID_MINMAX_MSE &&
         grid != ONECOMP_GRID_SYMMETRIC_MSE)
@@ -192,6 +233,7 @@ ONECOMP_API onecomp_status onecomp_rtn_sensitivity(const void* W, onecomp_dtype 
                                                    const float* a_diag, const float* b_diag, int bits, int group_size,
                                                    onecomp_grid grid, float* err, void* workspace,
                                                    size_t workspace_bytes, void* hip_stream) {
+    const ApiRange range("onecomp_rtn_sensitivity");
     if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
     if (grid != ONECOMP_GRID_MINMAX && grid != ONECOMP_GRID_SYMMETRIC) return ONECOMP_ERR_UNSUPPORTED;
     if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return ONECOMP_ERR_UNSUPPORTED;
@@ -210,6 +252,7 @@ ONECOMP_API onecomp_status onecomp_rtn_sensitivity_static(const void* W, onecomp
                                                           int64_t d_in, const float* a_diag, const float* b_diag,
                                                           int bits, int group_size, onecomp_grid grid, float* err,
                                                           void* hip_stream) {
+    const ApiRange range("onecomp_rtn_sensitivity_static");
     if (w_dtype != ONECOMP_F32 && w_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
     if (grid != ONECOMP_GRID_MINMAX && grid != ONECOMP_GRID_SYMMETRIC) return ONECOMP_ERR_UNSUPPORTED;
     if (bits != 2 && bits != 3 && bits != 4 && bits != 8) return ONECOMP_ERR_UNSUPPORTED;

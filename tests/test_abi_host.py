@@ -337,3 +337,27 @@ def test_header_is_plain_c_and_links(tmp_path):
                     f"-Wl,-rpath,{lib_dir}"], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
     assert int(out[0]) == oc_gpu.onecomp_version() and out[1] == "ok"
+
+
+def test_marker_ranges_are_opt_in(tmp_path):
+    """ONECOMP_ROCTX=1 makes the entry points look the ROCTx library up at run time and push a named range per call;
+    without it the library loads nothing of the kind.  Checked in child processes through an argument-check path
+    (no GPU is touched); skipped where no ROCTx library is installed."""
+    import subprocess
+    import sys
+    if not any(os.path.exists(os.path.join("/opt/rocm/lib", n)) for n in ("librocprofiler-sdk-roctx.so.1", "libroctx64.so.4")):
+        pytest.skip("no ROCTx library in this image")
+    prog = tmp_path / "probe.py"
+    prog.write_text(
+        "import ctypes\n"
+        f"lib = ctypes.CDLL({oc_gpu.LIB_PATH!r})\n"
+        "lib.onecomp_rtn_sensitivity_static.restype = ctypes.c_int\n"
+        "rc = lib.onecomp_rtn_sensitivity_static(None, 0, ctypes.c_int64(4), ctypes.c_int64(16), None, None, 4, 16, 0, None, None)\n"
+        "print(rc, 'roctx' in open('/proc/self/maps').read())\n")
+    for value, expect in (("1", "True"), ("0", "False"), (None, "False")):
+        env = dict(os.environ)
+        env.pop("ONECOMP_ROCTX", None)
+        if value is not None:
+            env["ONECOMP_ROCTX"] = value
+        out = subprocess.run([sys.executable, str(prog)], env=env, check=True, capture_output=True, text=True).stdout.split()
+        assert out == [str(INVALID), expect], (value, out)
