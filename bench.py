@@ -72,14 +72,16 @@ def _median(xs):
     return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
 
 
-def gram_kernel_name(d_in, bf16):
-    """Kernel onecomp_hessian_accumulate launches for this width; the ring kernel's tile shape (256 x 256 or 128 x 256)
-    and how it cuts tiles along the token axis are the library's own choice (estimated rounds over the CUs)."""
+def gram_kernel_name(d_in, bf16, plan=None):
+    """Kernel onecomp_hessian_accumulate launches for this width; the ring kernel's tile shape (384 x 256, 256 x 256 or
+    128 x 256) and how it cuts tiles along the token axis are the library's own choice (estimated rounds over the
+    CUs), reported by onecomp_accumulate_describe."""
     if not bf16:
         return "gram_f32_kernel"
     if d_in < 1024:
         return "gram_bf16_kernel<2>"
-    return "gram_bf16_ring_kernel"
+    shape = {384: "RingWide", 256: "RingBig", 128: "RingMid"}.get(plan["tile_rows"], "?") if plan else "?"
+    return f"gram_bf16_ring_kernel<{shape}, false>"
 
 
 def cpu_baseline(cfg, synth, seconds_hint=20.0):
@@ -516,11 +518,11 @@ def main():
     weights = d_out * d_in
 
     # Gram kernel.  Algorithmic flops = symmetric half, T d (d + 1).  An accumulate call on a wide layer launches the
-    # kernel once per round of 256 x 256 tiles (one tile per CU) and once more for the tiles cut along the tokens.
+    # kernel once per round of tiles (one tile per CU) and once more for the tiles cut along the tokens; the library
+    # reports the tile shape it chose and the number of launches.
     gram_ms = acc_ms / n_calls
-    n256 = (d_in + 255) // 256
-    t256 = n256 * (n256 + 1) // 2
-    gram_launches = (t256 // 256 + (1 if t256 % 256 else 0)) if (cfg.dtype == torch.bfloat16 and t256 > 512) else 1
+    gram_plan = og.onecomp_accumulate_describe(cfg.dtype, tpc, d_in, ws_a.numel() if ws_a is not None else 0)
+    gram_launches = gram_plan["launches"]
     algo_flops = float(tpc) * d_in * (d_in + 1)
     gram_tflops = algo_flops / (gram_ms * 1e-3) / 1e12
     # Counter-backed traffic of the Gram call.  Counters cannot be read from inside this process: the figure is the one
@@ -528,7 +530,8 @@ def main():
     # workload in one accumulate call with the workspace; null for anything else.
     gram_traffic = GRAM_TRAFFIC_C3B if (cfg.name == "c3b" and n_calls == 1) else None
     roofline = {
-        "kernel": gram_kernel_name(d_in, cfg.dtype == torch.bfloat16),
+        "kernel": gram_kernel_name(d_in, cfg.dtype == torch.bfloat16, gram_plan),
+        "tile": [gram_plan["tile_rows"], gram_plan["tile_cols"]],
         "bound": "mfma", "achieved": gram_tflops, "peak": PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3,
         "unit": "TFLOP/s", "frac": gram_tflops / (PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3),
         "traffic": gram_traffic,

@@ -122,6 +122,15 @@ onecomp_status onecomp_hessian_accumulate_ws(const void* X, onecomp_dtype x_dtyp
                                              int64_t n_tokens, int64_t d_in, int64_t ldx,
                                              float* H, void* workspace, size_t workspace_bytes, void* hip_stream);
 size_t onecomp_accumulate_workspace_bytes(onecomp_dtype x_dtype, int64_t d_in);
+/*
+ * Profiling aid: how onecomp_hessian_accumulate_ws would run a call of this size on the current device (Sec. 2.5 /
+ * 4.3, the same Gram accumulation; nothing is launched).  out3 is a HOST pointer to three int32: rows and columns of
+ * the output tile one workgroup of the call's main kernel owns, and the number of launches of that kernel in the
+ * call (a wide layer is launched one round of tiles at a time).  workspace_bytes: size of the workspace the call
+ * would be given (0: none).  Errors as for the call itself.
+ */
+onecomp_status onecomp_accumulate_describe(onecomp_dtype x_dtype, int64_t n_tokens, int64_t d_in, int64_t ldx,
+                                           size_t workspace_bytes, int32_t* out3);
 
 /*
  * Damping, optional activation ordering, and the Cholesky-based inverse factor

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     LIB_PATH,
     OnecompError,
     load_library,
+    onecomp_accumulate_describe,
     onecomp_accumulate_workspace_bytes,
     onecomp_crossgram_accumulate,
     onecomp_factor_workspace_bytes,

@@ -36,6 +36,7 @@ EXPORTED_SYMBOLS = (
     "onecomp_hessian_factor_form",
     "onecomp_hessian_accumulate_ws",
     "onecomp_accumulate_workspace_bytes",
+    "onecomp_accumulate_describe",
     "onecomp_quantize_layer_form",
     "onecomp_factor_workspace_bytes",
     "onecomp_quantize_workspace_bytes",
@@ -79,6 +80,8 @@ def load_library() -> ctypes.CDLL:
     lib.onecomp_hessian_accumulate_ws.restype = i32
     lib.onecomp_accumulate_workspace_bytes.argtypes = [i32, i64]
     lib.onecomp_accumulate_workspace_bytes.restype = sz
+    lib.onecomp_accumulate_describe.argtypes = [i32, i64, i64, i64, sz, vp]
+    lib.onecomp_accumulate_describe.restype = i32
     lib.onecomp_hessian_factor_form.argtypes = [vp, i64, f32, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.onecomp_hessian_factor_form.restype = i32
     lib.onecomp_quantize_layer_form.argtypes = [vp, i32, i64, i64, vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp,
@@ -163,6 +166,18 @@ def onecomp_quantize_workspace_bytes(d_out: int, d_in: int, block_size: int = 12
 def onecomp_accumulate_workspace_bytes(dtype: torch.dtype, d_in: int) -> int:
     code = ONECOMP_BF16 if dtype == torch.bfloat16 else ONECOMP_F32
     return int(load_library().onecomp_accumulate_workspace_bytes(code, int(d_in)))
+
+
+def onecomp_accumulate_describe(dtype: torch.dtype, n_tokens: int, d_in: int, workspace_bytes: int = 0,
+                                ldx: Optional[int] = None) -> dict:
+    """How an accumulate call of this size would run: tile shape of its main kernel and launches of it per call."""
+    code = ONECOMP_BF16 if dtype == torch.bfloat16 else ONECOMP_F32
+    out = (ctypes.c_int32 * 3)()
+    rc = load_library().onecomp_accumulate_describe(code, int(n_tokens), int(d_in), int(d_in if ldx is None else ldx),
+                                                    int(workspace_bytes), ctypes.cast(out, ctypes.c_void_p))
+    if rc != 0:
+        raise OnecompError(rc, "onecomp_accumulate_describe")
+    return {"tile_rows": int(out[0]), "tile_cols": int(out[1]), "launches": int(out[2])}
 
 
 def onecomp_hessian_accumulate(X: torch.Tensor, H: torch.Tensor, workspace: Optional[torch.Tensor] = None) -> None:

@@ -68,6 +68,23 @@ ONECOMP_API onecomp_status onecomp_hessian_accumulate_ws(const void* X, onecomp_
     return gram_accumulate_f32(X, n_tokens, d_in, ldx, H, s);
 }
 
+ONECOMP_API onecomp_status onecomp_accumulate_describe(onecomp_dtype x_dtype, int64_t n_tokens, int64_t d_in, int64_t ldx,
+                                                       size_t workspace_bytes, int32_t* out3) {
+    if (x_dtype != ONECOMP_F32 && x_dtype != ONECOMP_BF16) return ONECOMP_ERR_UNSUPPORTED;
+    if (!out3 || d_in <= 0 || n_tokens < 0 || ldx < d_in) return ONECOMP_ERR_INVALID_ARG;
+    if (d_in % 16 != 0 || d_in > (1 << 20)) return ONECOMP_ERR_INVALID_ARG;
+    GramPlanInfo info{128, 128, 1};
+    if (x_dtype == ONECOMP_BF16) {
+        const onecomp_status st = gram_accumulate_bf16(nullptr, n_tokens, d_in, ldx, nullptr, nullptr, workspace_bytes,
+                                                       nullptr, &info);
+        if (st != ONECOMP_OK) return st;
+    }
+    out3[0] = info.tile_rows;
+    out3[1] = info.tile_cols;
+    out3[2] = info.launches;
+    return ONECOMP_OK;
+}
+
 ONECOMP_API onecomp_status onecomp_hessian_accumulate(const void* X, onecomp_dtype x_dtype, int64_t n_tokens, int64_t d_in,
                                           int64_t ldx, float* H, void* hip_stream) {
     return onecomp_hessian_accumulate_ws(X, x_dtype, n_tokens, d_in, ldx, H, nullptr, 0, hip_stream);

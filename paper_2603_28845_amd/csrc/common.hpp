@@ -121,8 +121,14 @@ onecomp_status fill_zero(float* p, int64_t n4, hipStream_t stream);
 
 // ---- entry points implemented in the kernel files -------------------------------------------
 size_t gram_workspace_bytes(int64_t d_in);
+// schedule of an accumulate call: tile shape of its main kernel and how many times that kernel is launched
+struct GramPlanInfo {
+    int tile_rows, tile_cols, launches;
+};
+// info != nullptr: describe the call (ws_bytes is the size a workspace would have), launch nothing
 onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx,
-                                    float* H, void* ws, size_t ws_bytes, hipStream_t stream);
+                                    float* H, void* ws, size_t ws_bytes, hipStream_t stream,
+                                    GramPlanInfo* info = nullptr);
 onecomp_status gram_accumulate_f32(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx,
                                    float* H, hipStream_t stream);
 

@@ -18,6 +18,8 @@
 //   * fp32 path (small layers): 128-wide tiles on v_mfma_f32_32x32x2_f32, products in fp32.
 #include "common.hpp"
 #include "planner.hpp"
+#include <stdlib.h>
+#include <string.h>
 
 namespace onecomp {
 namespace {
@@ -325,6 +327,9 @@ struct RingMid {
 struct RingBig {
     static constexpr int TM = 256, TN = 256, WM = 2, WN = 4, NBUF = 8, MIN_WAVES = 2;
 };
+struct RingWide {
+    static constexpr int TM = 384, TN = 256, WM = 2, WN = 2, NBUF = 7, MIN_WAVES = 1;
+};
 template <typename C>
 struct Ring {
     static constexpr int KT = 16;
@@ -336,7 +341,8 @@ struct Ring {
     static constexpr int LPW = (NL_A + NL_B) / WAVES;                            // loads per wave and step
     static constexpr size_t LDS_BYTES = size_t(C::NBUF) * STAGEB;
     static_assert((NL_A + NL_B) % WAVES == 0 && NL_A % WAVES == 0, "whole loads per wave, A loads first");
-    static_assert(MT * NT == 8 && MT + NT == 6, "schedule below is written for 8 MFMAs and 6 fragments per step");
+    static_assert(MT + NT <= MT * NT && LPW <= MT * NT, "fragment reads and loads are placed one behind each MFMA");
+    static_assert((A_ROWB / 16) % 16 == 0 && (B_ROWB / 16) % 16 == 0, "the chunk swizzle stays inside groups of 16 chunks");
 };
 // CROSS = false: H += 2 X^T X, tiles on or above the diagonal, mirrored.  CROSS = true: H += 2 X^T Xb for two
 // different matrices (A panels from X, B panels from Xb), every tile, no mirror.
@@ -369,6 +375,7 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
     int ti, tk;
     if constexpr (CROSS) plan::cross_tile_from_rank(v, n_rt, n_ct, ti, tk);
     else if constexpr (C::TM == C::TN) tile_from_rank(v, n_ct, ti, tk);
+    else if constexpr (C::TM == 384) plan::tile_wide_from_rank(v, n_rt, n_ct, ti, tk);
     else tile128_from_rank(v, n_rt, n_ct, ti, tk);
     const int i0 = ti * C::TM, k0 = tk * C::TN;
     const bool diag = !CROSS && k0 < i0 + C::TM;   // some entry of the tile lies on or below the diagonal
@@ -385,9 +392,10 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
         const bool is_a = j < R::NL_A;
         const int jj = is_a ? j : j - R::NL_A;
         const int rowb = is_a ? A_ROWB : B_ROWB;
-        const int lpr = rowb / 16;                         // lanes (16-byte chunks) per token row
-        const int row = jj * (64 / lpr) + lane / lpr;
-        const int c = (lane % lpr) ^ ((row & 3) << 2);
+        const int cpr = rowb / 16;                         // 16-byte chunks per token row
+        const int lin = jj * 64 + lane;                    // this lane's chunk of the panel as it lies in LDS
+        const int row = lin / cpr;
+        const int c = (lin % cpr) ^ ((row & 3) << 2);
         const int col = (is_a ? i0 : k0) + c * 8;
         voff[q] = (col < d_in) ? uint32_t((int64_t(row) * (is_a ? ldx : ldxb) + col) * 2) : LDS_DMA_OOB;
         ldst[q] = (is_a ? 0 : A_PANELB) + jj * 1024;
@@ -468,11 +476,24 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
     for (int r = 0; r < MT + NT; ++r) rd(Fc, r, 0);
     __syncthreads();   // slot 0 is overwritten by the loads of the first half-iteration
 
+    // More than 256 accumulator registers per lane: the first 16 tiles are pinned to the AGPR half of the register
+    // file and the rest to the VGPR half by the operand constraints of the instruction itself (left to choose, the
+    // compiler copies tiles between the halves).
+    constexpr int N_AGPR_TILES = (MT * NT > 16) ? 16 : MT * NT;
     auto mma = [&](const Frags& f, auto&& between) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < MT * NT; ++i) {
-            acc[i / NT][i % NT] =
-                __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i / NT], f.b[i % NT], acc[i / NT][i % NT], 0, 0, 0);
+            if constexpr (MT * NT > 16) {
+                if (i < N_AGPR_TILES)
+                    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
+                                 : "+a"(acc[i / NT][i % NT]) : "v"(f.a[i / NT]), "v"(f.b[i % NT]));
+                else
+                    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
+                                 : "+v"(acc[i / NT][i % NT]) : "v"(f.a[i / NT]), "v"(f.b[i % NT]));
+            } else {
+                acc[i / NT][i % NT] =
+                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i / NT], f.b[i % NT], acc[i / NT][i % NT], 0, 0, 0);
+            }
             between(i);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -509,6 +530,11 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
         s0 = s2;
     }
     __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // no LDS write may be in flight when the workgroup ends
+    if constexpr (MT * NT > 16) {
+        // the MFMAs above are opaque to the compiler's hazard handling: let the last of them retire before the
+        // epilogue reads the accumulators
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    }
     if (piece >= 0 && ws) {   // partial sum of the tile, in accumulator order: consecutive lanes, consecutive addresses
         float* slot = ws + (int64_t(m_split) * n_piece + piece) * (C::TM * C::TN) + wave * (MT * NT * 16 * 64) + lane;
 #pragma unroll
@@ -525,39 +551,50 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
 }
 
 // Sum of the n_piece partial sums of each split tile (fixed order), then the usual epilogue: H += 2 sum, mirrored.
-// One workgroup of the main kernel's shape per tile.
+// One single-wave workgroup per part of a tile: the share of one wave of the main kernel, cut into RS parts along its
+// rows and NS along its columns when that share is more than 128 registers per lane.
 template <typename C>
-__global__ __launch_bounds__(Ring<C>::THREADS) void gram_reduce_kernel(const float* __restrict__ ws, float* __restrict__ H,
-                                                                      int d_in, int n_ct, int split0, int n_split,
-                                                                      int n_piece) {
+struct ReduceCfg {
+    static constexpr int RS = (Ring<C>::MT * Ring<C>::NT > 8) ? 2 : 1;
+    static constexpr int NS = RS;
+    static constexpr int PARTS = Ring<C>::WAVES * RS * NS;   // workgroups per tile
+    static_assert(Ring<C>::MT % RS == 0 && Ring<C>::NT % NS == 0, "whole 32 x 32 tiles per part");
+};
+template <typename C>
+__global__ __launch_bounds__(64) void gram_reduce_kernel(const float* __restrict__ ws, float* __restrict__ H, int d_in,
+                                                         int n_rt, int n_ct, int split0, int n_split, int n_piece) {
     using R = Ring<C>;
-    constexpr int MT = R::MT, NT = R::NT;
-    const int m_split = blockIdx.x;
+    using RC = ReduceCfg<C>;
+    constexpr int MT = R::MT, NT = R::NT, MTS = MT / RC::RS, NTS = NT / RC::NS;
+    const int m_split = blockIdx.x / RC::PARTS, sub = blockIdx.x % RC::PARTS;
     if (m_split >= n_split) return;
     int ti, tk;
-    tile_from_rank(split0 + m_split, n_ct, ti, tk);
+    if constexpr (C::TM == C::TN) tile_from_rank(split0 + m_split, n_ct, ti, tk);
+    else plan::tile_wide_from_rank(split0 + m_split, n_rt, n_ct, ti, tk);
     const int i0 = ti * C::TM, k0 = tk * C::TN;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x;
+    const int wave = sub / (RC::RS * RC::NS), part = (sub / RC::NS) % RC::RS, nh = sub % RC::NS;
     const int wr = wave / C::WN, wc = wave % C::WN;
-    float16v acc[MT][NT];
+    float16v acc[MTS][NTS];
 #pragma unroll
-    for (int m = 0; m < MT; ++m)
+    for (int m = 0; m < MTS; ++m)
 #pragma unroll
-        for (int n = 0; n < NT; ++n)
+        for (int n = 0; n < NTS; ++n)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
     for (int p = 0; p < n_piece; ++p) {
         const float* slot = ws + (int64_t(m_split) * n_piece + p) * (C::TM * C::TN) + wave * (MT * NT * 16 * 64) + lane;
 #pragma unroll
-        for (int m = 0; m < MT; ++m)
+        for (int m = 0; m < MTS; ++m)
 #pragma unroll
-            for (int n = 0; n < NT; ++n)
+            for (int n = 0; n < NTS; ++n)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[m][n][r] += slot[((m * NT + n) * 16 + r) * 64];
+                for (int r = 0; r < 16; ++r)
+                    acc[m][n][r] += slot[(((part * MTS + m) * NT + nh * NTS + n) * 16 + r) * 64];
     }
-    gram_store<MT, NT, true>(acc, H, d_in, i0 + wr * (32 * MT), k0 + wc * (32 * NT), k0 < i0 + C::TM, lane);
+    gram_store<MTS, NTS, true>(acc, H, d_in, i0 + wr * (32 * MT) + part * (32 * MTS),
+                               k0 + wc * (32 * NT) + nh * (32 * NTS), k0 < i0 + C::TM, lane);
 }
-
 
 // -------------------------------------------------------------------------------------------
 // fp32 kernel: 128 x 128 tile, 4 waves in 2x2, each 2x2 tiles of v_mfma_f32_32x32x2_f32
@@ -687,25 +724,28 @@ constexpr size_t GRAM_SLOT_BYTES = size_t(256) * 256 * sizeof(float);   // one p
 
 template <typename C, bool CROSS>
 onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens, int64_t d_in, int64_t ldx,
-                                int64_t ldxb, float* H, float* ws, size_t ws_bytes, hipStream_t stream) {
+                                int64_t ldxb, float* H, float* ws, size_t ws_bytes, hipStream_t stream,
+                                GramPlanInfo* info = nullptr) {
     using R = Ring<C>;
     const int n_rt = int(ceil_div(d_in, C::TM)), n_ct = int(ceil_div(d_in, C::TN));
     int n_tiles = 0;
     if (CROSS) n_tiles = n_rt * n_ct;
     else if (C::TM == C::TN) n_tiles = n_ct * (n_ct + 1) / 2;
+    else if (C::TM == 384) n_tiles = plan::n_tiles_wide(n_rt, n_ct);
     else n_tiles = plan::n_tiles128(n_rt, n_ct);
     // tiles computed in pieces of the token axis, dispatched after the whole tiles (see plan_split)
     SplitPlan sp;
-    if (!CROSS && C::TM == 256 && C::TN == 256) {
+    if (!CROSS && C::TM >= 256 && C::TN == 256) {
         const int n_cus = device_cus();
         if (n_cus <= 0) return ONECOMP_ERR_HIP;
-        sp = plan_split(n_tiles, n_ct, d_in, n_tokens, n_cus, ws ? int64_t(ws_bytes / GRAM_SLOT_BYTES) : 0);
+        constexpr size_t slot_bytes = size_t(C::TM) * C::TN * sizeof(float);
+        sp = plan_split(n_tiles, n_ct, d_in, n_tokens, n_cus, ws ? int64_t(ws_bytes / slot_bytes) : 0, C::TM == 256);
     }
     const int n_split = sp.n_split, split0 = sp.split0;
     const int chunk = int(ceil_div(n_tiles - n_split, 8));
     static std::atomic<uint64_t> lds_ok{0};
-    if (allow_dynamic_lds(reinterpret_cast<const void*>(&gram_bf16_ring_kernel<C, CROSS>), int(R::LDS_BYTES),
-                          lds_ok) != ONECOMP_OK)
+    if (!info && allow_dynamic_lds(reinterpret_cast<const void*>(&gram_bf16_ring_kernel<C, CROSS>), int(R::LDS_BYTES),
+                                   lds_ok) != ONECOMP_OK)
         return ONECOMP_ERR_HIP;
     // One launch per round of whole tiles (one tile per CU), then one for the pieces.  Workgroups of one launch start
     // together, so the tiles an XCD works on walk through the tokens side by side and share their column panels in
@@ -713,62 +753,113 @@ onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens,
     // drift apart (L2 hit rate 59 % against 78 % for a round on its own; 46.2 -> 44.7 ms at d_in 14336, 262144 tokens).
     const int total = plan::ring_total_blocks(chunk, n_split, sp.n_piece);
     const int n_cus_r = device_cus();
-    const int per_launch = (C::TM == 256 && C::TN == 256 && n_cus_r > 0 && n_cus_r % 8 == 0 && chunk * 8 >= 2 * n_cus_r)
+    const int per_launch = (C::TM >= 256 && C::TN == 256 && n_cus_r > 0 && n_cus_r % 8 == 0 && chunk * 8 >= 2 * n_cus_r)
                                ? n_cus_r : total;
     for (int b0 = 0; b0 < total;) {
         int nb = total - b0;
         if (per_launch < total && b0 < chunk * 8) nb = (chunk * 8 - b0 < per_launch) ? chunk * 8 - b0 : per_launch;
+        if (info) {   // describe the schedule, launch nothing
+            ++info->launches;
+            b0 += nb;
+            continue;
+        }
         hipLaunchKernelGGL((gram_bf16_ring_kernel<C, CROSS>), dim3(unsigned(nb)), dim3(R::THREADS), R::LDS_BYTES, stream,
                            static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(Xb), n_tokens, int(d_in), ldx,
                            ldxb, H, n_rt, n_ct, n_tiles, chunk, split0, n_split, sp.n_piece, sp.use_ws ? ws : nullptr, b0);
         ONECOMP_CHECK_LAUNCH();
         b0 += nb;
     }
+    if (info) {
+        info->tile_rows = C::TM;
+        info->tile_cols = C::TN;
+        return ONECOMP_OK;
+    }
     if (n_split > 0 && sp.use_ws) {
-        if constexpr (!CROSS && C::TM == 256 && C::TN == 256) {
-            hipLaunchKernelGGL(gram_reduce_kernel<C>, dim3(unsigned(n_split)), dim3(R::THREADS), 0, stream, ws, H,
-                               int(d_in), n_ct, split0, n_split, sp.n_piece);
+        if constexpr (!CROSS && C::TM >= 256 && C::TN == 256) {
+            hipLaunchKernelGGL(gram_reduce_kernel<C>, dim3(unsigned(n_split) * ReduceCfg<C>::PARTS), dim3(64), 0, stream,
+                               ws, H, int(d_in), n_rt, n_ct, split0, n_split, sp.n_piece);
             ONECOMP_CHECK_LAUNCH();
         }
-    } else if (n_split > 0) {
+    } else if (n_split > 0) {   // 256 x 256 tiles only (plan_split: other shapes split with a workspace or not at all)
         hipLaunchKernelGGL(gram_merge_kernel, dim3(64, unsigned(n_split)), dim3(256), 0, stream, H, int(d_in), n_split);
         ONECOMP_CHECK_LAUNCH();
     }
     return ONECOMP_OK;
 }
 
+// Which ring kernel a symmetric call takes.  The estimated number of rounds decides: a 256 x 256 tile runs one per CU
+// and costs two units; a 128 x 256 tile runs two per CU (a CU with two of them takes twice as long) and costs one unit
+// plus 15 % for its higher L2 traffic per flop; a 384 x 256 tile runs one per CU, is 1.5 times the work and moves 17 %
+// fewer L2 and LDS bytes per flop, which makes a round of them about 10 % shorter than its work (2.7 units).  The
+// 384-row shape needs the workspace for a last round that is not full.
+// ONECOMP_GRAM_SHAPE=big|mid|wide in the environment forces a shape (testing and tuning).
+enum class GramShape { Big, Mid, Wide };
+constexpr double WIDE_UNITS = 2.7;
+constexpr size_t GRAM_WIDE_SLOT_BYTES = size_t(384) * 256 * sizeof(float);
+int forced_shape() {
+    const char* e = getenv("ONECOMP_GRAM_SHAPE");
+    if (!e) return -1;
+    if (!strcmp(e, "big")) return int(GramShape::Big);
+    if (!strcmp(e, "mid")) return int(GramShape::Mid);
+    if (!strcmp(e, "wide")) return int(GramShape::Wide);
+    return -1;
+}
+GramShape choose_shape(int64_t d_in, int64_t n_tokens, int n_cus, size_t ws_bytes) {
+    const int64_t n256 = ceil_div(d_in, 256), n128 = ceil_div(d_in, 128), n384 = ceil_div(d_in, 384);
+    const int64_t big = n256 * (n256 + 1) / 2;
+    const int64_t mid = plan::n_tiles128(int(n128), int(n256)), wide = plan::n_tiles_wide(int(n384), int(n256));
+    const double cost_big = 2.0 * plan_split(big, n256, d_in, n_tokens, n_cus, int64_t(ws_bytes / GRAM_SLOT_BYTES)).rounds;
+    const double cost_mid = 1.15 * double(ceil_div(mid, n_cus));
+    const double cost_wide =
+        WIDE_UNITS * plan_split(wide, n256, d_in, n_tokens, n_cus, int64_t(ws_bytes / GRAM_WIDE_SLOT_BYTES), false).rounds;
+    const int f = forced_shape();
+    if (f >= 0) return GramShape(f);
+    if (cost_wide < cost_big && cost_wide < cost_mid) return GramShape::Wide;
+    return cost_big <= cost_mid ? GramShape::Big : GramShape::Mid;
+}
+
 }  // namespace
 
-// bytes of workspace that let gram_accumulate_bf16 cut tiles into pieces (0: this width never does)
+// bytes of workspace that let gram_accumulate_bf16 cut tiles into pieces (0: this width never does): the larger of
+// what the 256 x 256 and the 384 x 256 schedule can use
 size_t gram_workspace_bytes(int64_t d_in) {
     if (d_in < 1024) return 0;
     const int n_cus = device_cus();
     if (n_cus <= 0) return 0;
     const int64_t n256 = ceil_div(d_in, 256), big = n256 * (n256 + 1) / 2;
+    const int64_t wide = plan::n_tiles_wide(int(ceil_div(d_in, 384)), int(n256));
     const SplitPlan sp = plan_split(big, n256, d_in, int64_t(1) << 40, n_cus, int64_t(1) << 40);
-    return sp.use_ws ? size_t(sp.n_split) * sp.n_piece * GRAM_SLOT_BYTES : 0;
+    const SplitPlan sw = plan_split(wide, n256, d_in, int64_t(1) << 40, n_cus, int64_t(1) << 40, false);
+    const size_t b = sp.use_ws ? size_t(sp.n_split) * sp.n_piece * GRAM_SLOT_BYTES : 0;
+    const size_t w = sw.use_ws ? size_t(sw.n_split) * sw.n_piece * GRAM_WIDE_SLOT_BYTES : 0;
+    return b > w ? b : w;
 }
 
 onecomp_status gram_accumulate_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_t ldx, float* H, void* wsv,
-                                    size_t ws_bytes, hipStream_t stream) {
+                                    size_t ws_bytes, hipStream_t stream, GramPlanInfo* info) {
     float* ws = static_cast<float*>(wsv);
+    if (info) *info = GramPlanInfo{128, 128, 0};
     // The direct-to-LDS kernels need 32-bit byte offsets inside a step of tokens; narrow layers take the
-    // register-staged 128 x 128 kernel.  Between the two direct-to-LDS kernels the estimated number of rounds
-    // decides: 256 x 256 tiles run one per CU and cost two units each, 128 x 256 tiles run two per CU (a CU with
-    // two of them takes twice as long) and cost one unit plus 15 % for their higher L2 traffic per flop.
-    if (ldx * 64 >= (int64_t(1) << 31) || d_in < 1024) return launch_bf16<2>(X, n_tokens, d_in, ldx, H, stream);
+    // register-staged 128 x 128 kernel.
+    if (ldx * 64 >= (int64_t(1) << 31) || d_in < 1024) {
+        if (info) {
+            info->launches = 1;
+            return ONECOMP_OK;
+        }
+        return launch_bf16<2>(X, n_tokens, d_in, ldx, H, stream);
+    }
     const int n_cus = device_cus();
     if (n_cus <= 0) return ONECOMP_ERR_HIP;
-    const int64_t n256 = ceil_div(d_in, 256), n128 = ceil_div(d_in, 128);
-    const int64_t big = n256 * (n256 + 1) / 2;
-    int64_t mid = 0;
-    for (int64_t i = 0; i < n128; ++i) mid += n256 - i / 2;
-    const double rounds_big =
-        plan_split(big, n256, d_in, n_tokens, n_cus, ws ? int64_t(ws_bytes / GRAM_SLOT_BYTES) : 0).rounds;
-    const double cost_big = 2.0 * rounds_big, cost_mid = 1.15 * double(ceil_div(mid, n_cus));
-    if (cost_big <= cost_mid)
-        return launch_bf16_ring<RingBig, false>(X, X, n_tokens, d_in, ldx, ldx, H, ws, ws_bytes, stream);
-    return launch_bf16_ring<RingMid, false>(X, X, n_tokens, d_in, ldx, ldx, H, nullptr, 0, stream);
+    // describing a call: the workspace is only a size
+    float* wsp = info ? reinterpret_cast<float*>(uintptr_t(ws_bytes ? 256 : 0)) : ws;
+    switch (choose_shape(d_in, n_tokens, n_cus, wsp ? ws_bytes : 0)) {
+        case GramShape::Wide:
+            return launch_bf16_ring<RingWide, false>(X, X, n_tokens, d_in, ldx, ldx, H, wsp, ws_bytes, stream, info);
+        case GramShape::Big:
+            return launch_bf16_ring<RingBig, false>(X, X, n_tokens, d_in, ldx, ldx, H, wsp, ws_bytes, stream, info);
+        default:
+            return launch_bf16_ring<RingMid, false>(X, X, n_tokens, d_in, ldx, ldx, H, nullptr, 0, stream, info);
+    }
 }
 
 // G += 2 Xh^T X for two bf16 matrices of the same shape (every tile, no symmetry to use)
@@ -776,9 +867,17 @@ onecomp_status gram_cross_accumulate_bf16(const void* Xh, const void* X, int64_t
                                           int64_t ldx, float* G, hipStream_t stream) {
     const int n_cus = device_cus();
     if (n_cus <= 0) return ONECOMP_ERR_HIP;
-    const int64_t n256 = ceil_div(d_in, 256), n128 = ceil_div(d_in, 128);
+    const int64_t n256 = ceil_div(d_in, 256), n128 = ceil_div(d_in, 128), n384 = ceil_div(d_in, 384);
     const double cost_big = 2.0 * double(ceil_div(n256 * n256, n_cus)), cost_mid = 1.15 * double(ceil_div(n128 * n256, n_cus));
-    if (cost_big <= cost_mid)
+    const double cost_wide = WIDE_UNITS * double(ceil_div(n384 * n256, n_cus));
+    int shape = forced_shape();
+    if (shape < 0)
+        shape = int((cost_wide < cost_big && cost_wide < cost_mid) ? GramShape::Wide
+                    : cost_big <= cost_mid                         ? GramShape::Big
+                                                                   : GramShape::Mid);
+    if (shape == int(GramShape::Wide))
+        return launch_bf16_ring<RingWide, true>(Xh, X, n_tokens, d_in, ldxh, ldx, G, nullptr, 0, stream);
+    if (shape == int(GramShape::Big))
         return launch_bf16_ring<RingBig, true>(Xh, X, n_tokens, d_in, ldxh, ldx, G, nullptr, 0, stream);
     return launch_bf16_ring<RingMid, true>(Xh, X, n_tokens, d_in, ldxh, ldx, G, nullptr, 0, stream);
 }

@@ -66,6 +66,25 @@ ONECOMP_HD int n_tiles128(int n_rt, int n_ct) {
     return n;
 }
 
+// ---- symmetric Gram, 384 x 256 tiles: tile (i, k) = rows [384 i, +384) x columns [256 k, +256) is computed when it
+// reaches above the diagonal (256 (k + 1) > 384 i, i.e. k >= floor(3 i / 2)).  Bands of GRAM_BAND tile rows, inside a
+// band column by column, rows fastest.
+ONECOMP_HD void tile_wide_from_rank(int v, int n_rt, int n_ct, int& ti, int& tk) {
+    for (int a = 0;; ++a) {
+        const int r0 = a * GRAM_BAND, rows = imin(GRAM_BAND, n_rt - r0);
+        for (int k = 3 * r0 / 2; k < n_ct; ++k) {
+            const int valid = imin(rows, (2 * k + 1) / 3 - r0 + 1);   // rows r0 .. r0+valid-1 satisfy 3 i / 2 <= k
+            if (v < valid) { ti = r0 + v; tk = k; return; }
+            v -= valid;
+        }
+    }
+}
+ONECOMP_HD int n_tiles_wide(int n_rt, int n_ct) {
+    int n = 0;
+    for (int i = 0; i < n_rt; ++i) n += n_ct - 3 * i / 2;
+    return n;
+}
+
 // ---- cross-Gram (every tile): bands of GRAM_BAND tile rows, column by column inside a band
 ONECOMP_HD void cross_tile_from_rank(int v, int n_rt, int n_ct, int& ti, int& tk) {
     const int band = imin(v / (GRAM_BAND * n_ct), (n_rt - 1) / GRAM_BAND);
@@ -125,18 +144,22 @@ struct SplitPlan {
     bool use_ws = false;
     double rounds = 0.0;
 };
-inline SplitPlan plan_split(int64_t n_tiles, int64_t n_ct, int64_t d_in, int64_t n_tokens, int n_cus, int64_t ws_slots) {
+// mirror_ok: the tiles are 256 x 256, so the workspace-free form exists (other tile shapes split only with a workspace,
+// whose slots are then partial sums of that shape).
+inline SplitPlan plan_split(int64_t n_tiles, int64_t n_ct, int64_t d_in, int64_t n_tokens, int n_cus, int64_t ws_slots,
+                            bool mirror_ok = true) {
     SplitPlan best;
     best.rounds = double(cdiv(n_tiles, n_cus));
     const int64_t r = n_tiles % n_cus;
-    if (r > 0 && r <= n_cus / 2 && n_tokens >= 1024 && n_ct >= GRAM_BAND + cdiv(r, GRAM_BAND) &&
+    if (mirror_ok && r > 0 && r <= n_cus / 2 && n_tokens >= 1024 && n_ct >= GRAM_BAND + cdiv(r, GRAM_BAND) &&
         (GRAM_BAND + cdiv(r, GRAM_BAND)) * 256 <= d_in) {
         best.split0 = GRAM_BAND * (GRAM_BAND + 1) / 2;
         best.n_split = int(r);
         best.n_piece = 2;
         best.rounds = double(n_tiles / n_cus) + 0.5 * 1.06;
     }
-    for (int pc = 2; pc <= 16; ++pc) {
+    const int max_pc = mirror_ok ? 16 : 8;   // the larger slots of the other shapes: fewer of them
+    for (int pc = 2; pc <= max_pc; ++pc) {
         if (n_tokens / pc < 2048) break;
         const double piece_cost = 1.0 / pc + 0.005;
         if (r > 0 && n_tiles > n_cus && r * pc <= ws_slots) {   // the leftover tiles, from the end of the rank order

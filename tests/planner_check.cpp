@@ -38,13 +38,47 @@ static void check_simple_upper(int d_in, int ts) {
     REQUIRE(int(seen.size()) == n_tiles, "d_in %d ts %d: %zu of %d tiles owned", d_in, ts, seen.size(), n_tiles);
 }
 
-// ring kernel, symmetric: 256 x 256 tiles with the split plan, or 128 x 256 tiles
-static void check_ring(int d_in, int64_t n_tokens, int n_cus, int64_t ws_slots, bool big) {
-    const int tm = big ? 256 : 128;
+// ring kernel, symmetric: 256 x 256 tiles with the split plan, 128 x 256 tiles, or 384 x 256 tiles with the
+// workspace-only split plan
+enum Shape { BIG, MID, WIDE };
+static void tile_of(Shape shape, int v, int n_rt, int n_ct, int& ti, int& tk) {
+    if (shape == BIG) tile_from_rank(v, n_ct, ti, tk);
+    else if (shape == MID) tile128_from_rank(v, n_rt, n_ct, ti, tk);
+    else tile_wide_from_rank(v, n_rt, n_ct, ti, tk);
+}
+// the ranks of a shape's tile map are a bijection onto the tiles that reach the diagonal or lie above it
+static void check_tile_set(int d_in, Shape shape) {
+    const int tm = shape == BIG ? 256 : shape == MID ? 128 : 384;
     const int n_rt = int(cdiv(d_in, tm)), n_ct = int(cdiv(d_in, 256));
-    const int n_tiles = big ? n_upper_tiles(n_ct) : n_tiles128(n_rt, n_ct);
+    const int n_tiles = shape == BIG ? n_upper_tiles(n_ct) : shape == MID ? n_tiles128(n_rt, n_ct) : n_tiles_wide(n_rt, n_ct);
+    std::set<std::pair<int, int>> seen;
+    for (int v = 0; v < n_tiles; ++v) {
+        int ti, tk;
+        tile_of(shape, v, n_rt, n_ct, ti, tk);
+        REQUIRE(seen.insert({ti, tk}).second, "d_in %d tile (%d, %d) has two ranks", d_in, ti, tk);
+    }
+    // ... and the tile set is everything that reaches the diagonal or lies above it
+    int needed = 0;
+    for (int i = 0; i < n_rt; ++i)
+        for (int k = 0; k < n_ct; ++k)
+            if (int64_t(k + 1) * 256 > int64_t(i) * tm) {
+                ++needed;
+                REQUIRE(seen.count({i, k}) == 1, "d_in %d tile (%d, %d) has no rank", d_in, i, k);
+            }
+    REQUIRE(needed == n_tiles, "d_in %d: %d tiles needed, %d ranked", d_in, needed, n_tiles);
+}
+
+static void check_ring(int d_in, int64_t n_tokens, int n_cus, int64_t ws_slots, Shape shape) {
+    const bool big = shape == BIG;
+    const int tm = shape == BIG ? 256 : shape == MID ? 128 : 384;
+    const int n_rt = int(cdiv(d_in, tm)), n_ct = int(cdiv(d_in, 256));
+    const int n_tiles = shape == BIG ? n_upper_tiles(n_ct) : shape == MID ? n_tiles128(n_rt, n_ct) : n_tiles_wide(n_rt, n_ct);
     SplitPlan sp;
     if (big) sp = plan_split(n_tiles, n_ct, d_in, n_tokens, n_cus, ws_slots);
+    if (shape == WIDE) {
+        sp = plan_split(n_tiles, n_ct, d_in, n_tokens, n_cus, ws_slots, false);
+        REQUIRE(sp.n_split == 0 || sp.use_ws, "d_in %d: a 384-row tile split without the workspace", d_in);
+    }
     REQUIRE(sp.n_split >= 0 && sp.n_split <= n_tiles && sp.split0 >= 0 && sp.split0 + sp.n_split <= n_tiles,
             "d_in %d plan split0 %d n_split %d of %d", d_in, sp.split0, sp.n_split, n_tiles);
     REQUIRE(sp.n_piece >= 1 && sp.n_piece <= 16, "d_in %d n_piece %d", d_in, sp.n_piece);
@@ -69,10 +103,10 @@ static void check_ring(int d_in, int64_t n_tokens, int n_cus, int64_t ws_slots, 
         if (!ring_work(bid, chunk, n_tiles, sp.split0, sp.n_split, w)) continue;
         REQUIRE(w.v >= 0 && w.v < n_tiles, "d_in %d block %d -> rank %d of %d", d_in, bid, w.v, n_tiles);
         int ti, tk;
-        if (big) tile_from_rank(w.v, n_ct, ti, tk); else tile128_from_rank(w.v, n_rt, n_ct, ti, tk);
+        tile_of(shape, w.v, n_rt, n_ct, ti, tk);
         REQUIRE(ti >= 0 && ti < n_rt && tk >= 0 && tk < n_ct, "d_in %d rank %d -> (%d, %d)", d_in, w.v, ti, tk);
-        if (big) REQUIRE(ti <= tk, "d_in %d rank %d below the diagonal", d_in, w.v);
-        else REQUIRE(tk >= ti / 2, "d_in %d rank %d below the diagonal", d_in, w.v);
+        // the tile reaches the diagonal or lies above it: its last column is not left of its first row
+        REQUIRE(int64_t(tk + 1) * 256 > int64_t(ti) * tm, "d_in %d rank %d below the diagonal", d_in, w.v);
         if (w.piece < 0) {
             REQUIRE(w.v < sp.split0 || w.v >= sp.split0 + sp.n_split, "d_in %d split tile %d taken whole", d_in, w.v);
             ++whole[w.v];
@@ -91,13 +125,6 @@ static void check_ring(int d_in, int64_t n_tokens, int n_cus, int64_t ws_slots, 
             REQUIRE(int(pieces[v].size()) == sp.n_piece && int(s.size()) == sp.n_piece,
                     "d_in %d tile %d has %zu pieces of %d", d_in, v, pieces[v].size(), sp.n_piece);
         }
-    }
-    // the ranks are a bijection onto the tile set
-    std::set<std::pair<int, int>> seen;
-    for (int v = 0; v < n_tiles; ++v) {
-        int ti, tk;
-        if (big) tile_from_rank(v, n_ct, ti, tk); else tile128_from_rank(v, n_rt, n_ct, ti, tk);
-        REQUIRE(seen.insert({ti, tk}).second, "d_in %d tile (%d, %d) has two ranks", d_in, ti, tk);
     }
     // token ranges of the pieces: whole steps of 16, in bounds, tiling the token axis
     if (sp.n_split > 0) {
@@ -120,8 +147,8 @@ static void check_ring(int d_in, int64_t n_tokens, int n_cus, int64_t ws_slots, 
     }
 }
 
-static void check_cross(int d_in, bool big) {
-    const int n_rt = int(cdiv(d_in, big ? 256 : 128)), n_ct = int(cdiv(d_in, 256));
+static void check_cross(int d_in, Shape shape) {
+    const int n_rt = int(cdiv(d_in, shape == BIG ? 256 : shape == MID ? 128 : 384)), n_ct = int(cdiv(d_in, 256));
     const int n_tiles = n_rt * n_ct, chunk = int(cdiv(n_tiles, 8));
     std::set<std::pair<int, int>> seen;
     for (int bid = 0; bid < ring_total_blocks(chunk, 0, 1); ++bid) {
@@ -167,10 +194,13 @@ int main() {
             for (int64_t t : toks)
                 for (int64_t s : slots) {
                     if (!dense && !(t == 262144 || t == 9001)) continue;
-                    check_ring(d_in, t, n_cus, s, true);
+                    check_ring(d_in, t, n_cus, s, BIG);
+                    // slots of the 384 x 256 shape are 1.5 times as large: the same workspace holds two thirds as many
+                    check_ring(d_in, t, n_cus, s / 3 * 2, WIDE);
                 }
-            check_ring(d_in, 262144, n_cus, 0, false);
-            if (d_in % 256 == 0 || d_in <= 4096) { check_cross(d_in, true); check_cross(d_in, false); }
+            check_ring(d_in, 262144, n_cus, 0, MID);
+            for (Shape sh : {BIG, MID, WIDE}) check_tile_set(d_in, sh);
+            if (d_in % 256 == 0 || d_in <= 4096) { check_cross(d_in, BIG); check_cross(d_in, MID); check_cross(d_in, WIDE); }
         }
     }
     for (int d_out : {1, 7, 64, 128, 129, 1000, 4096, 8192, 14336, 28672})

@@ -80,6 +80,22 @@ def test_accumulate_ws_argument_checks(lib):
     assert g(1, 0) == 0 and g(1, 100) == 0
 
 
+def test_accumulate_describe_argument_checks(lib):
+    out = (ctypes.c_int32 * 3)(-1, -1, -1)
+    fn = lib.onecomp_accumulate_describe
+    fn.restype = ctypes.c_int
+    i64, sz = ctypes.c_int64, ctypes.c_size_t
+    assert fn(1, i64(100), i64(512), i64(512), sz(0), None) == INVALID          # no output pointer
+    assert fn(7, i64(100), i64(512), i64(512), sz(0), out) == UNSUPPORTED       # dtype
+    assert fn(1, i64(100), i64(520), i64(520), sz(0), out) == INVALID           # d_in not a multiple of 16
+    assert fn(1, i64(-1), i64(512), i64(512), sz(0), out) == INVALID
+    assert fn(1, i64(100), i64(512), i64(256), sz(0), out) == INVALID           # row stride below d_in
+    assert list(out) == [-1, -1, -1]
+    # narrow layers and fp32 inputs: one launch of a 128 x 128 kernel, known without asking the device
+    assert fn(1, i64(100), i64(512), i64(512), sz(0), out) == OK and list(out) == [128, 128, 1]
+    assert fn(0, i64(100), i64(4096), i64(4096), sz(0), out) == OK and list(out) == [128, 128, 1]
+
+
 def test_factor_argument_checks(lib):
     f = lib.onecomp_hessian_factor
     big = ctypes.c_size_t(1 << 40)

@@ -171,7 +171,7 @@ def test_gram_with_workspace(d_in, n_tok, ws_frac):
     """onecomp_hessian_accumulate_ws: partial sums of token pieces parked in a workspace and added in a fixed order."""
     _announce(f"gram with workspace d_in={d_in} n_tok={n_tok} workspace fraction {ws_frac}")
     need = og.onecomp_accumulate_workspace_bytes(torch.bfloat16, d_in)
-    assert need > 0 and need % (256 * 256 * 4) == 0
+    assert need > 0 and need % (128 * 256 * 4) == 0    # whole partial sums of a 256 x 256 or a 384 x 256 tile
     ws = torch.empty(max(256, int(need * ws_frac) // 256 * 256), dtype=torch.uint8, device=DEV)
     ws.fill_(0xFF)          # the contents on entry must not matter (0xFFFFFFFF is a NaN)
     cfg = synth.scaled(synth.CONFIGS["c2"], d_out=16, d_in=d_in, n_tokens=n_tok, seed=9)
@@ -198,6 +198,65 @@ def test_gram_with_workspace(d_in, n_tok, ws_frac):
     H2 = _gpu_gram(torch.cat([X, X]), chunks=2, ws=ws)
     assert torch.equal(H2, H2.T)
     assert rel_fro(H2.cpu().numpy().astype(np.float64), 2.0 * Hn.astype(np.float64)) <= 5e-6
+
+
+@pytest.mark.parametrize("shape", ["wide", "big", "mid"])
+@pytest.mark.parametrize("d_in,n_tok,with_ws", [
+    (1040, 333, False),     # one ragged tile row and column
+    (2304, 1000, True),     # 6 x 9 tiles of 384 x 256, every one in pieces when a workspace is there
+    (4096, 9000, True),     # 10 2/3 tile rows of 384: the last one a third full
+    (8192, 2063, False),    # more tiles than CUs, whole tiles only, ragged token tail
+    (8192, 9001, True),     # whole rounds plus leftover tiles in pieces
+])
+def test_gram_tile_shapes(monkeypatch, shape, d_in, n_tok, with_ws):
+    """Every tile shape of the direct-to-LDS Gram kernel on the same inputs (the library picks one by estimated
+    cost; ONECOMP_GRAM_SHAPE forces it): 384 x 256 tiles with pinned accumulator registers, 256 x 256, 128 x 256."""
+    _announce(f"gram tile shape {shape}: d_in={d_in} n_tok={n_tok} workspace={with_ws}")
+    monkeypatch.setenv("ONECOMP_GRAM_SHAPE", shape)
+    ws = None
+    if with_ws:
+        ws = torch.empty(og.onecomp_accumulate_workspace_bytes(torch.bfloat16, d_in), dtype=torch.uint8, device=DEV)
+        ws.fill_(0xFF)
+    plan = og.onecomp_accumulate_describe(torch.bfloat16, n_tok, d_in, ws.numel() if with_ws else 0)
+    assert plan["tile_rows"] == {"wide": 384, "big": 256, "mid": 128}[shape] and plan["tile_cols"] == 256
+    assert plan["launches"] >= 1
+    cfg = synth.scaled(synth.CONFIGS["c2"], d_out=16, d_in=d_in, n_tokens=n_tok, seed=21)
+    X = synth.make_activations(cfg, DEV)
+    H = _gpu_gram(X, ws=ws)
+    assert torch.equal(H, H.T)
+    assert torch.equal(H, _gpu_gram(X, ws=ws))          # reproducible bit for bit
+    Hn = H.cpu().numpy()
+    Xd = to_f64(X)
+    if d_in <= 2304:
+        assert rel_fro(Hn.astype(np.float64), oc.hessian_accumulate(Xd)) <= 1e-4
+    else:
+        r = np.random.default_rng(2)
+        for _ in range(4):
+            i = np.sort(r.choice(d_in, size=200, replace=False))
+            k = np.sort(r.choice(d_in, size=200, replace=False))
+            assert rel_fro(Hn[np.ix_(i, k)].astype(np.float64), oc.hessian_tile(Xd, i, k)) <= 1e-4
+        # the band along the diagonal, where tiles are cut by it: every entry of a 700-wide window and the far corner
+        for lo in (0, 1300, d_in - 700):
+            i = np.arange(lo, lo + 700)
+            assert rel_fro(Hn[np.ix_(i, i)].astype(np.float64), oc.hessian_tile(Xd, i, i)) <= 1e-4
+        d = np.arange(d_in)
+        np.testing.assert_allclose(Hn[d, d], 2.0 * (Xd * Xd).sum(0), rtol=1e-4)
+    # additive on a non-zero H, two calls of different length
+    H2 = _gpu_gram(torch.cat([X, X[: n_tok // 2]]), chunks=2, ws=ws)
+    assert torch.equal(H2, H2.T)
+    ref2 = Hn.astype(np.float64) + _gpu_gram(X[: n_tok // 2], ws=ws).cpu().numpy().astype(np.float64)
+    assert rel_fro(H2.cpu().numpy().astype(np.float64), ref2) <= 1e-5
+
+
+def test_gram_schedule_of_the_benchmark_layer():
+    """What the library reports for the call bench.py times: with the workspace the 384 x 256 shape in four whole rounds
+    plus one launch of pieces, without it 256 x 256 tiles in six rounds plus the split last round."""
+    _announce("gram schedule at d_in=14336, 262144 tokens")
+    d_in, T = 14336, 262144
+    need = og.onecomp_accumulate_workspace_bytes(torch.bfloat16, d_in)
+    assert og.onecomp_accumulate_describe(torch.bfloat16, T, d_in, need) == {"tile_rows": 384, "tile_cols": 256, "launches": 5}
+    assert og.onecomp_accumulate_describe(torch.bfloat16, T, d_in, 0) == {"tile_rows": 256, "tile_cols": 256, "launches": 7}
+    assert og.onecomp_accumulate_describe(torch.float32, T, d_in, 0)["launches"] == 1
 
 
 def test_gram_full_calibration_set_sampled():

@@ -63,6 +63,21 @@ def test_crossgram_shapes(d_in, n_tok):
     assert rel_fro(Gxx.cpu().numpy().astype(np.float64), H.cpu().numpy().astype(np.float64)) <= 1e-6
 
 
+@pytest.mark.parametrize("shape", ["wide", "big", "mid"])
+@pytest.mark.parametrize("d_in,n_tok", [(1040, 515), (2304, 1000), (4096, 300)])
+def test_crossgram_tile_shapes(monkeypatch, shape, d_in, n_tok):
+    """Each tile shape of the cross-Gram kernel (384 x 256, 256 x 256, 128 x 256) on the same inputs."""
+    _announce(f"cross-Gram tile shape {shape}: d_in={d_in} n_tok={n_tok}")
+    monkeypatch.setenv("ONECOMP_GRAM_SHAPE", shape)
+    _, X, Xh = _pair(d_in, n_tok, seed=60 + d_in % 7)
+    G = _gpu_cross(Xh, X)
+    Go = oc.crossgram_accumulate(to_f64(Xh), to_f64(X))
+    assert rel_fro(G.cpu().numpy().astype(np.float64), Go) <= 1e-4
+    assert torch.equal(G, _gpu_cross(Xh, X))
+    G3 = _gpu_cross(Xh, X, chunks=3)
+    assert rel_fro(G3.cpu().numpy().astype(np.float64), Go) <= 1e-4
+
+
 def test_crossgram_strided_rows_and_zero_tokens():
     _announce("cross-Gram strided rows / zero tokens")
     _, X, Xh = _pair(256, 300, seed=3)
