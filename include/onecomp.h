@@ -107,12 +107,16 @@ onecomp_status onecomp_hessian_accumulate(const void* X, onecomp_dtype x_dtype,
 
 /*
  * onecomp_hessian_accumulate with an optional scratch buffer (onecomp_hessian_accumulate is this call with
- * workspace = NULL).  The kernel computes H in 256 x 256 tiles, one per compute unit at a time; when the number of
- * tiles does not fill the last round of compute units (or there are fewer tiles than units), a workspace lets it
- * cut tiles into 2 to 16 pieces along the token axis, park the partial sums there and add them in a fixed order:
- * same result up to fp32 rounding order, still bit-wise symmetric and reproducible, and faster for such widths
- * (d_in 4096, 262144 tokens: 6.0 -> 4.5 ms; d_in 8192, 131072 tokens: 9.1 -> 8.0 ms).  Without a workspace only
- * the mirror positions of H can hold a second partial sum, which covers a short last round of wide matrices.
+ * workspace = NULL).  The kernel computes H in tiles (256 x 256 without a workspace), one per compute unit at a
+ * time; when the number of tiles does not fill the last round of compute units (or there are fewer tiles than
+ * units), a workspace lets it cut tiles into 2 to 16 pieces along the token axis, park the partial sums there and
+ * add them in a fixed order: same result up to fp32 rounding order, still bit-wise symmetric and reproducible, and
+ * faster for such widths (d_in 4096, 262144 tokens: 6.0 -> 3.9 ms; d_in 8192, 131072 tokens: 9.1 -> 8.0 ms).  With
+ * a workspace the call may also take 384 x 256 tiles (fewer cache and LDS bytes per flop; their last round always
+ * needs the workspace): d_in 14336, 262144 tokens: 46-49 -> 43-46 ms.  Without a workspace only the mirror positions
+ * of H can hold a second partial sum, which covers a short last round of wide matrices.  The tile shape is chosen by
+ * estimated cost; ONECOMP_GRAM_SHAPE=wide|big|mid in the environment forces 384 x 256, 256 x 256 or 128 x 256 tiles
+ * for d_in >= 1024 (testing and tuning; onecomp_accumulate_describe reports the choice).
  *   workspace        device scratch or NULL, 256-byte aligned; any size is accepted, the kernel uses what fits
  *                    (onecomp_accumulate_workspace_bytes(x_dtype, d_in) is what it can use at most; 0 for fp32
  *                    inputs and for widths that gain nothing).  Contents on entry and exit are meaningless.

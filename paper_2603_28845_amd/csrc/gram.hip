@@ -7,9 +7,10 @@
 //     (no floating-point atomics, reproducible).
 //   * bf16 path: X is token-major while the MFMA operands (v_mfma_f32_32x32x16_bf16) need 8 consecutive
 //     TOKENS per lane, so the token-major LDS tile is read with ds_read_b64_tr_b16 (LDS transpose read) and no
-//     register shuffles are needed.  Wide layers: ring kernel, tiles go global -> LDS directly (256 x 256 tile,
-//     8 waves; 128 x 256 tile, two workgroups per CU, when that fills the CUs better).  Narrow layers
-//     (d_in < 1024): register-staged 128 x 128 kernel, double-buffered LDS.
+//     register shuffles are needed.  Wide layers: ring kernel, tiles go global -> LDS directly (384 x 256 tile on
+//     four waves with three quarters of the register file as accumulators; 256 x 256 tile, 8 waves; 128 x 256 tile,
+//     two workgroups per CU; whichever the estimated cost favours).  Narrow layers (d_in < 1024): register-staged
+//     128 x 128 kernel, double-buffered LDS.
 //   * The workgroup -> tile map is XCD-aware: hardware deals consecutive workgroups round-robin to
 //     the 8 XCDs, so workgroup b is given the tile with rank (b % 8) * chunk + b / 8 in an
 //     order that walks bands of 4 tile rows column by column.  The 32 workgroups that share an
@@ -301,7 +302,15 @@ __global__ __launch_bounds__(256) void gram_merge_kernel(float* __restrict__ H, 
 
 // -------------------------------------------------------------------------------------------
 // bf16 ring kernel: global -> LDS without passing through registers (buffer_load_dwordx4 ... lds), in steps of
-// 16 tokens through a ring of NBUF LDS slots.  Two shapes:
+// 16 tokens through a ring of NBUF LDS slots.  Three shapes:
+//   RingWide 384 x 256 tile, 4 waves (2 x 2, 192 x 128 each = 24 MFMA tiles = 384 accumulator registers per lane),
+//            one wave per SIMD with the whole register file.  The fewest L2 and LDS bytes per flop (17 % less than
+//            256 x 256, 10 fragments for 24 MFMAs per step instead of 6 for 8).  The compiler cannot place 384
+//            accumulators by itself (it copies tiles between the VGPR and AGPR halves and spills), so for this shape
+//            the MFMA is inline assembly whose operand constraints pin 16 tiles to AGPRs and 8 to VGPRs; being opaque
+//            to the compiler's hazard handling, the last MFMAs are followed by explicit wait states before the
+//            epilogue reads the accumulators.  Tile (i, k) = rows [384 i, +384) x columns [256 k, +256) is computed
+//            when it reaches above the diagonal (k >= floor(3 i / 2)).
 //   RingBig  256 x 256 tile, 8 waves (2 x 4, 128 x 64 each), i.e. two waves per SIMD: one wave's waits are covered
 //            by the other's MFMAs.  Only tiles on or above the diagonal (banded, XCD-aware order of tile_from_rank).
 //   RingMid  128 x 256 tile, 4 waves (2 x 2, 64 x 128 each), two workgroups per CU: for mid-size d_in, where
