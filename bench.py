@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # L2 <-> fabric bytes per call from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a plain 4 GiB copy), taken with
 # `python bench.py --phase gram|sweep` under rocprofv3 --pmc; see profiles/c3b_hbm_traffic_pmc.md for the commands
-GRAM_TRAFFIC_C3B = 128.0e9    # 127.2 GB fetched + 0.86 GB written per accumulate call
+GRAM_TRAFFIC_C3B = 185.0e9    # 183.7 GB fetched + 1.2 GB written per accumulate call (384 x 256 tiles; 100-187 GB from run to run)
 SWEEP_TRAFFIC_C3B = 13.6e9
 
 
@@ -528,7 +528,7 @@ def main():
     # Counter-backed traffic of the Gram call.  Counters cannot be read from inside this process: the figure is the one
     # of profiles/c3b_hbm_traffic_pmc.md (rocprofv3 --pmc runs of this file's --phase gram loop), valid for the default
     # workload in one accumulate call with the workspace; null for anything else.
-    gram_traffic = GRAM_TRAFFIC_C3B if (cfg.name == "c3b" and n_calls == 1) else None
+    gram_traffic = GRAM_TRAFFIC_C3B if (cfg.name == "c3b" and n_calls == 1 and gram_plan["tile_rows"] == 384) else None
     roofline = {
         "kernel": gram_kernel_name(d_in, cfg.dtype == torch.bfloat16, gram_plan),
         "tile": [gram_plan["tile_rows"], gram_plan["tile_cols"]],
