@@ -84,6 +84,31 @@ def gram_kernel_name(d_in, bf16, plan=None):
     return f"gram_bf16_ring_kernel<{shape}, false>"
 
 
+def achievable_mfma(og, torch):
+    """What the matrix pipes of this box sustain on a register-only loop of independent MFMAs (no LDS, no memory
+    traffic), timed with HIP events: the ceiling under which the Gram kernel (bf16) and the factor (fp64) run.  The
+    published peaks assume the 2.4 GHz boost clock, which the chip does not hold under MFMA load."""
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    out = {}
+    for kind, iters in (("bf16", 40000), ("f64", 16000)):
+        for w, rnd in ((1, True), (2, True), (2, False)):
+            og.onecomp_mfma_rate_probe(kind, w, 2000, sink, random_operands=rnd)                 # warm-up
+            ts = []
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                flops = og.onecomp_mfma_rate_probe(kind, w, iters, sink, random_operands=rnd)
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            key = f"{kind}_tflops_{w}_wave_per_simd" + ("" if rnd else "_constant_operands")
+            out[key] = flops / (_median(ts) * 1e-3) / 1e12
+    out["note"] = ("register-only loops of 8 independent MFMAs per trip (v_mfma_f32_32x32x16_bf16, v_mfma_f64_16x16x4_f64) "
+                   "on every CU, 5-15 ms each, operands pseudo-random per lane and MFMA unless marked constant (the pipes "
+                   "draw more power on toggling data and the clock follows); published peaks 2500 / 78.6")
+    return out
+
+
 def cpu_baseline(cfg, synth, seconds_hint=20.0):
     """Oracle (float64, numpy) timed per phase on bounded samples of the same workload and extrapolated by
     work: Gram over n_s tokens (linear in tokens), factor at d_s = d_in / 2 (cubic), sweep of r_s rows at
@@ -602,6 +627,19 @@ def main():
             "dense_tflops": 2.0 * T * d_in * d_in / (v_ms * 1e-3) / 1e12,
             "frac_of_bf16_peak": 2.0 * T * d_in * d_in / (v_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
             "gram_kernel_ms_for_the_same_tokens": acc_ms,
+        }
+    if phase == "all":
+        ach = achievable_mfma(og, torch)
+        res["achievable_mfma"] = ach
+        if cfg.dtype == torch.bfloat16:
+            res["roofline"]["frac_of_achievable"] = gram_tflops / max(ach["bf16_tflops_1_wave_per_simd"],
+                                                                      ach["bf16_tflops_2_wave_per_simd"])
+        res["factor_fp64"] = {
+            "tflops": 2.0 * d_in ** 3 / 3.0 / (fac_ms * 1e-3) / 1e12 * (1.0 if args.factor_form == "inverse" else 0.5),
+            "frac_of_peak": 2.0 * d_in ** 3 / 3.0 / (fac_ms * 1e-3) / 1e12 * (1.0 if args.factor_form == "inverse" else 0.5) / 78.6,
+            "frac_of_achievable": 2.0 * d_in ** 3 / 3.0 / (fac_ms * 1e-3) / 1e12 * (1.0 if args.factor_form == "inverse" else 0.5)
+                                  / max(ach["f64_tflops_1_wave_per_simd"], ach["f64_tflops_2_wave_per_simd"]),
+            "note": "2 d^3 / 3 flops (Cholesky + triangular inverse; d^3 / 3 in block form) over the factor call's time",
         }
     if args.jointq > 0 and phase == "all" and (cfg.group_size <= 128 or cfg.group_size % 128 == 0):
         res["jointq"] = bench_jointq(args, cfg, og, W, H, out, perm if cfg.act_order else None)

@@ -389,6 +389,23 @@ onecomp_status onecomp_jointq_refine(const void* W, onecomp_dtype w_dtype, int64
 size_t onecomp_jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size);
 
 /* Static, NUL-terminated description of a status code. */
+/*
+ * Measurement aid, no part of the method: launches a register-only loop of independent MFMAs (no LDS, no memory
+ * traffic) on every compute unit, so that a caller can time what the matrix pipes of this device sustain and quote
+ * the Gram accumulation (Sec. 2.5 / 4.3) and the factor (Sec. 4.3.1) against that rate as well as against the
+ * published peak, which assumes the boost clock.
+ *   kind            0: v_mfma_f32_32x32x16_bf16 (the Gram kernel's instruction), 1: v_mfma_f64_16x16x4_f64 (the factor's)
+ *   waves_per_simd  1 or 2 (workgroups of four waves per compute unit)
+ *   random_operands 0: the same small constant in every lane; 1: pseudo-random values per lane and per MFMA (the
+ *                   pipes draw more power on data that toggles, and the sustained clock follows)
+ *   iters           loop trips per wave, 1 .. 2^24; each trip issues 8 MFMAs
+ *   sink            device float, at least one element; never written in practice (it keeps the loop alive)
+ *   flops_out       HOST double, out: floating-point operations of the launch (2 M N K per MFMA)
+ * Asynchronous on hip_stream like every other call; the caller times it with events.
+ */
+onecomp_status onecomp_mfma_rate_probe(int kind, int waves_per_simd, int random_operands, int64_t iters, float* sink,
+                                       double* flops_out, void* hip_stream);
+
 const char* onecomp_status_string(onecomp_status status);
 
 /* Library version as major * 10000 + minor * 100 + patch. */

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     onecomp_hessian_factor,
     onecomp_jointq_refine,
     onecomp_jointq_workspace_bytes,
+    onecomp_mfma_rate_probe,
     onecomp_qep_target,
     onecomp_qep_workspace_bytes,
     onecomp_quantize_layer,

@@ -37,6 +37,7 @@ EXPORTED_SYMBOLS = (
     "onecomp_hessian_accumulate_ws",
     "onecomp_accumulate_workspace_bytes",
     "onecomp_accumulate_describe",
+    "onecomp_mfma_rate_probe",
     "onecomp_quantize_layer_form",
     "onecomp_factor_workspace_bytes",
     "onecomp_quantize_workspace_bytes",
@@ -82,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     lib.onecomp_accumulate_workspace_bytes.restype = sz
     lib.onecomp_accumulate_describe.argtypes = [i32, i64, i64, i64, sz, vp]
     lib.onecomp_accumulate_describe.restype = i32
+    lib.onecomp_mfma_rate_probe.argtypes = [i32, i32, i32, i64, vp, vp, vp]
+    lib.onecomp_mfma_rate_probe.restype = i32
     lib.onecomp_hessian_factor_form.argtypes = [vp, i64, f32, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.onecomp_hessian_factor_form.restype = i32
     lib.onecomp_quantize_layer_form.argtypes = [vp, i32, i64, i64, vp, i32, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp,
@@ -178,6 +181,19 @@ def onecomp_accumulate_describe(dtype: torch.dtype, n_tokens: int, d_in: int, wo
     if rc != 0:
         raise OnecompError(rc, "onecomp_accumulate_describe")
     return {"tile_rows": int(out[0]), "tile_cols": int(out[1]), "launches": int(out[2])}
+
+
+def onecomp_mfma_rate_probe(kind: str, waves_per_simd: int, iters: int, sink: torch.Tensor,
+                            random_operands: bool = True) -> float:
+    """Enqueues the register-only MFMA loop (kind "bf16" or "f64") on the current stream; returns its flop count."""
+    flops = ctypes.c_double(0.0)
+    rc = load_library().onecomp_mfma_rate_probe({"bf16": 0, "f64": 1}[kind], int(waves_per_simd),
+                                                int(bool(random_operands)), int(iters),
+                                                _ptr(sink), ctypes.cast(ctypes.byref(flops), ctypes.c_void_p),
+                                                _stream())
+    if rc != 0:
+        raise OnecompError(rc, "onecomp_mfma_rate_probe")
+    return float(flops.value)
 
 
 def onecomp_hessian_accumulate(X: torch.Tensor, H: torch.Tensor, workspace: Optional[torch.Tensor] = None) -> None:

@@ -10,7 +10,7 @@ from concurrent.futures import ThreadPoolExecutor
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libonecomp.so")
-SOURCES = ["api.hip", "gram.hip", "factor.hip", "sweep.hip", "qep.hip", "sensitivity.hip", "jointq.hip"]
+SOURCES = ["api.hip", "gram.hip", "factor.hip", "sweep.hip", "qep.hip", "sensitivity.hip", "jointq.hip", "probe.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -284,6 +284,17 @@ ONECOMP_API onecomp_status onecomp_rtn_sensitivity_static(const void* W, onecomp
                                   static_cast<hipStream_t>(hip_stream));
 }
 
+ONECOMP_API onecomp_status onecomp_mfma_rate_probe(int kind, int waves_per_simd, int random_operands, int64_t iters,
+                                                   float* sink, double* flops_out, void* hip_stream) {
+    if (kind != 0 && kind != 1) return ONECOMP_ERR_UNSUPPORTED;
+    if (waves_per_simd != 1 && waves_per_simd != 2) return ONECOMP_ERR_UNSUPPORTED;
+    if (random_operands != 0 && random_operands != 1) return ONECOMP_ERR_INVALID_ARG;
+    if (!sink || !flops_out || iters <= 0 || iters > (int64_t(1) << 24)) return ONECOMP_ERR_INVALID_ARG;
+    const ApiRange range("onecomp_mfma_rate_probe");
+    return mfma_rate_probe(kind, waves_per_simd, random_operands, iters, sink, flops_out,
+                           static_cast<hipStream_t>(hip_stream));
+}
+
 ONECOMP_API const char* onecomp_status_string(onecomp_status status) {
     switch (status) {
         case ONECOMP_OK: return "ok";

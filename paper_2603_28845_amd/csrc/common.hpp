@@ -159,6 +159,11 @@ onecomp_status sensitivity_run_static(const void* W, onecomp_dtype w_dtype, int6
                                       const float* a_diag, const float* b_diag, int bits, int group_size, int grid,
                                       float* err, hipStream_t stream);
 
+// register-only MFMA loop (kind 0: bf16 32x32x16, 1: fp64 16x16x4) on every CU with waves_per_simd waves per SIMD,
+// operands constant (random == 0) or pseudo-random; *flops (host) receives the flop count of the launch
+onecomp_status mfma_rate_probe(int kind, int waves_per_simd, int random, int64_t iters, float* sink, double* flops,
+                               hipStream_t stream);
+
 size_t jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size);
 onecomp_status jointq_run(const void* W, onecomp_dtype w_dtype, int64_t d_out, int64_t d_in, const float* A,
                           const int32_t* perm, float lam, int bits, int group_size, int grid, int n_pass, int max_scans, uint8_t* Q, float* scales,

@@ -614,9 +614,21 @@ __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, cons
     }
 }
 
+// Workgroups are dispatched x fastest.  With a triangular operand the tiles differ in length (B lower: the inner
+// range starts at the tile's column, so tile columns get shorter to the right; A lower: it ends at the tile's row, so
+// tile rows get longer downwards); the longest tiles are dispatched first, so that no long tile starts when the
+// rest of the launch is nearly done: B lower: tile column = blockIdx.y (the grid is launched transposed), A lower:
+// tile rows from the bottom.
 template <bool bt>
 __global__ __launch_bounds__(256, 2) void dgemm_kernel(GemmArgs g) {
-    dgemm_tile<bt>(g, blockIdx.x, blockIdx.y, blockIdx.z, false);
+    int tn = blockIdx.x, tm = blockIdx.y;
+    if (g.flags & G_BLOWER) {
+        tn = blockIdx.y;
+        tm = blockIdx.x;
+    } else if (g.flags & G_ALOWER) {
+        tm = gridDim.y - 1 - blockIdx.y;
+    }
+    dgemm_tile<bt>(g, tn, tm, blockIdx.z, false);
 }
 
 __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A, double* __restrict__ V, int n,
@@ -699,6 +711,7 @@ __global__ __launch_bounds__(256) void trsm_kernel(double* __restrict__ P, int64
 onecomp_status dgemm(const GemmArgs& g, hipStream_t stream) {
     if (g.m <= 0 || g.n <= 0 || g.batch <= 0) return ONECOMP_OK;
     dim3 grid(unsigned(ceil_div(g.n, GT)), unsigned(ceil_div(g.m, GT)), unsigned(g.batch));
+    if (g.flags & G_BLOWER) grid = dim3(grid.y, grid.x, grid.z);   // see dgemm_kernel
     if (g.flags & G_BTRANS) hipLaunchKernelGGL(dgemm_kernel<true>, grid, dim3(256), 0, stream, g);
     else hipLaunchKernelGGL(dgemm_kernel<false>, grid, dim3(256), 0, stream, g);
     ONECOMP_CHECK_LAUNCH();

@@ -96,6 +96,23 @@ def test_accumulate_describe_argument_checks(lib):
     assert fn(0, i64(100), i64(4096), i64(4096), sz(0), out) == OK and list(out) == [128, 128, 1]
 
 
+def test_mfma_rate_probe_argument_checks(lib):
+    fn = lib.onecomp_mfma_rate_probe
+    fn.restype = ctypes.c_int
+    i64 = ctypes.c_int64
+    flops = ctypes.c_double(-1.0)
+    fp = ctypes.byref(flops)
+    sink = ctypes.c_void_p(256)      # never dereferenced: every case below is rejected on the host
+    assert fn(2, 1, 1, i64(10), sink, fp, None) == UNSUPPORTED            # kind
+    assert fn(0, 3, 1, i64(10), sink, fp, None) == UNSUPPORTED            # waves per SIMD
+    assert fn(0, 1, 2, i64(10), sink, fp, None) == INVALID                # operand pattern
+    assert fn(0, 1, 1, i64(0), sink, fp, None) == INVALID                 # no trips
+    assert fn(1, 2, 0, i64(1 << 25), sink, fp, None) == INVALID           # too many trips
+    assert fn(0, 1, 1, i64(10), None, fp, None) == INVALID                # no sink
+    assert fn(0, 1, 1, i64(10), sink, None, None) == INVALID              # no flop count
+    assert flops.value == -1.0
+
+
 def test_factor_argument_checks(lib):
     f = lib.onecomp_hessian_factor
     big = ctypes.c_size_t(1 << 40)

@@ -259,6 +259,26 @@ def test_gram_schedule_of_the_benchmark_layer():
     assert og.onecomp_accumulate_describe(torch.float32, T, d_in, 0)["launches"] == 1
 
 
+def test_mfma_rate_probe_runs():
+    """The measurement aid: flop count as documented, and a rate between a tenth of the published peak and the peak."""
+    _announce("register-only MFMA loops")
+    sink = torch.zeros(64, dtype=torch.float32, device=DEV)
+    n_cus = torch.cuda.get_device_properties(0).multi_processor_count
+    for kind, per_mfma, peak in (("bf16", 2 * 32 * 32 * 16, 2500e12), ("f64", 2 * 16 * 16 * 4, 78.6e12)):
+        for w, rnd in ((1, True), (2, True), (2, False)):
+            og.onecomp_mfma_rate_probe(kind, w, 500, sink, random_operands=rnd)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = og.onecomp_mfma_rate_probe(kind, w, 4000, sink, random_operands=rnd)
+            e1.record()
+            torch.cuda.synchronize()
+            assert flops == n_cus * w * 4 * 4000 * 8 * per_mfma
+            rate = flops / (e0.elapsed_time(e1) * 1e-3)
+            _announce(f"   {kind}, {w} wave(s) per SIMD, {'random' if rnd else 'constant'} operands: {rate / 1e12:.1f} TFLOP/s")
+            assert 0.1 * peak < rate < 1.02 * peak
+    assert float(sink.abs().sum().item()) == 0.0
+
+
 def test_gram_full_calibration_set_sampled():
     """The Gram launch exactly as bench.py times it: 262144 tokens x 14336 channels (bf16) in ONE call.  The full
     float64 product is out of reach of the host, so the oracle computes sampled index blocks (over all tokens)
