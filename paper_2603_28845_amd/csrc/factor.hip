@@ -447,9 +447,13 @@ __device__ __forceinline__ double* wg_lds() {
 // One 128 x 128 tile (tm, tn) of batch entry z.  tri_out: the finished tile is also left in LDS (from its start,
 // over the dead operand tiles) in the layout of potrf_body (lower sub-blocks, identity beyond the matrix edge),
 // for a diagonal tile that the same workgroup factors next.
-template <bool bt>   // B is given transposed (n x k, k contiguous)
+// NW waves per workgroup: 4 (2 x 2 waves of 64 x 64) or 8 (2 x 4 waves of 64 x 32: half the accumulators per lane, so
+// that twice as many waves share a SIMD and cover each other's waits).
+template <bool bt, int NW = 4>   // bt: B is given transposed (n x k, k contiguous)
 __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, const int tm, const int z,
                                            const bool tri_out) {
+    constexpr int NJ = 16 / NW;          // 16-column MFMA tiles per wave
+    constexpr int EP = 2048 / (64 * NW); // elements of each operand tile per thread and stage
     double* lds = wg_lds();
     double(*sA)[GT * GPA] = reinterpret_cast<double(*)[GT * GPA]>(lds);
     double(*sB)[GSB] = reinterpret_cast<double(*)[GSB]>(lds + 2 * GT * GPA);
@@ -466,21 +470,22 @@ __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, cons
     if (g.flags & G_ALOWER) k_hi = min(kdim, (tm + 1) * GT);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wr = wave >> 1, wc = wave & 1;
+    const int wr = wave / (NW / 2), wc = wave % (NW / 2);
     const int m0 = tm * GT, n0 = tn * GT;
+    const int cw = wc * (NJ * 16);   // first column of this wave inside the tile
 
-    // loaders: A-form tile (rows x GK, k contiguous): row = tid/2, 8 doubles at k = (tid%2)*8
-    //          NN B tile (GK x cols): krow = tid/16, 8 doubles at col (tid%16)*8
-    const int a_row = tid >> 1, a_k = (tid & 1) * 8;
-    const int b_kr = tid >> 4, b_c = (tid & 15) * 8;
-    double ra[8], rb[8];
+    // loaders: A-form tile (rows x GK, k contiguous): EP doubles of one row per thread
+    //          NN B tile (GK x cols): EP doubles of one k row per thread
+    const int a_row = tid / (GK / EP), a_k = (tid % (GK / EP)) * EP;
+    const int b_kr = tid / (GT / EP), b_c = (tid % (GT / EP)) * EP;
+    double ra[EP], rb[EP];
     auto gload = [&](int k0) {
         {
             const int r = m0 + a_row, kk = k0 + a_k;
             const bool ok = (r < m) && (kk < k_hi);
             const double2* p = reinterpret_cast<const double2*>(A + int64_t(r) * g.lda + kk);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < EP / 2; ++e) {
                 double2 v = ok ? p[e] : make_double2(0.0, 0.0);
                 ra[2 * e] = v.x; ra[2 * e + 1] = v.y;
             }
@@ -490,7 +495,7 @@ __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, cons
             const bool ok = (r < g.n) && (kk < k_hi);
             const double2* p = reinterpret_cast<const double2*>(B + int64_t(r) * g.ldb + kk);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < EP / 2; ++e) {
                 double2 v = ok ? p[e] : make_double2(0.0, 0.0);
                 rb[2 * e] = v.x; rb[2 * e + 1] = v.y;
             }
@@ -499,7 +504,7 @@ __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, cons
             const bool ok = (kk < k_hi) && (c < g.n);
             const double2* p = reinterpret_cast<const double2*>(B + int64_t(kk) * g.ldb + c);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < EP / 2; ++e) {
                 double2 v = ok ? p[e] : make_double2(0.0, 0.0);
                 rb[2 * e] = v.x; rb[2 * e + 1] = v.y;
             }
@@ -507,13 +512,13 @@ __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, cons
     };
     auto lstore = [&](int st) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) sA[st][a_row * GPA + a_k + e] = g.alpha * ra[e];   // alpha folded into A
+        for (int e = 0; e < EP; ++e) sA[st][a_row * GPA + a_k + e] = g.alpha * ra[e];   // alpha folded into A
         if (bt) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sB[st][a_row * GPA + a_k + e] = rb[e];
+            for (int e = 0; e < EP; ++e) sB[st][a_row * GPA + a_k + e] = rb[e];
         } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sB[st][b_kr * GPB + b_c + e] = rb[e];
+            for (int e = 0; e < EP; ++e) sB[st][b_kr * GPB + b_c + e] = rb[e];
         }
     };
 
@@ -521,32 +526,32 @@ __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, cons
     if (k_lo < k_hi) gload(k_lo);
     // accumulators start as beta * C (register r of lane l: row 4 r + l / 16, column l % 16 of its 16 x 16 tile),
     // so the C tile is in flight together with the first operand tiles
-    double4v acc[4][4];
+    double4v acc[4][NJ];
     const bool full = (m0 + GT <= m) && (n0 + GT <= g.n);   // uniform: interior tiles need no per-element masks
-    double* __restrict__ ct = C + int64_t(m0 + wr * 64 + lk) * g.ldc + n0 + wc * 64 + l16;
+    double* __restrict__ ct = C + int64_t(m0 + wr * 64 + lk) * g.ldc + n0 + cw + l16;
     if (g.beta == 0.0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0;
     } else if (full) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[i][j][r] = g.beta * ct[int64_t(i * 16 + 4 * r) * g.ldc + j * 16];
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
-                    const int col = n0 + wc * 64 + j * 16 + l16;
+                    const int col = n0 + cw + j * 16 + l16;
                     double c = 0.0;
                     if (row < m && col < g.n) c = g.beta * C[int64_t(row) * g.ldc + col];
                     acc[i][j][r] = c;
@@ -561,17 +566,17 @@ __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, cons
         if (more) gload(k0 + GK);
 #pragma unroll
         for (int k4 = 0; k4 < GK; k4 += 4) {
-            double a[4], b[4];
+            double a[4], b[NJ];
 #pragma unroll
             for (int i = 0; i < 4; ++i) a[i] = sA[st][(wr * 64 + i * 16 + l16) * GPA + k4 + lk];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                b[j] = bt ? sB[st][(wc * 64 + j * 16 + l16) * GPA + k4 + lk]
-                          : sB[st][(k4 + lk) * GPB + wc * 64 + j * 16 + l16];
+            for (int j = 0; j < NJ; ++j)
+                b[j] = bt ? sB[st][(cw + j * 16 + l16) * GPA + k4 + lk]
+                          : sB[st][(k4 + lk) * GPB + cw + j * 16 + l16];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < NJ; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
         }
         if (more) lstore(st ^ 1);
@@ -584,18 +589,18 @@ __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, cons
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) ct[int64_t(i * 16 + 4 * r) * g.ldc + j * 16] = acc[i][j][r];
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
-                    const int col = n0 + wc * 64 + j * 16 + l16;
+                    const int col = n0 + cw + j * 16 + l16;
                     if (row < m && col < g.n) C[int64_t(row) * g.ldc + col] = acc[i][j][r];
                 }
     }
@@ -603,10 +608,10 @@ __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, cons
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int lrow = wr * 64 + i * 16 + 4 * r + lk, lcol = wc * 64 + j * 16 + l16;
+                    const int lrow = wr * 64 + i * 16 + 4 * r + lk, lcol = cw + j * 16 + l16;
                     if ((lcol >> 4) > (lrow >> 4)) continue;
                     const bool inside = (m0 + lrow < m) && (n0 + lcol < g.n);
                     lds[tri(lrow, lcol)] = inside ? acc[i][j][r] : (lrow == lcol ? 1.0 : 0.0);
@@ -614,21 +619,75 @@ __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, cons
     }
 }
 
-// Workgroups are dispatched x fastest.  With a triangular operand the tiles differ in length (B lower: the inner
-// range starts at the tile's column, so tile columns get shorter to the right; A lower: it ends at the tile's row, so
-// tile rows get longer downwards); the longest tiles are dispatched first, so that no long tile starts when the
-// rest of the launch is nearly done: B lower: tile column = blockIdx.y (the grid is launched transposed), A lower:
-// tile rows from the bottom.
-template <bool bt>
-__global__ __launch_bounds__(256, 2) void dgemm_kernel(GemmArgs g) {
-    int tn = blockIdx.x, tm = blockIdx.y;
-    if (g.flags & G_BLOWER) {
-        tn = blockIdx.y;
-        tm = blockIdx.x;
-    } else if (g.flags & G_ALOWER) {
-        tm = gridDim.y - 1 - blockIdx.y;
+// Tile (tm, tn), tn <= tm, of rank v in the row-major enumeration of a lower triangle of tiles.
+__device__ __forceinline__ void lower_tile_from_rank(int v, int& tm, int& tn) {
+    int r = int((__fsqrt_rn(8.0f * float(v) + 1.0f) - 1.0f) * 0.5f);
+    while (r * (r + 1) / 2 > v) --r;
+    while ((r + 1) * (r + 2) / 2 <= v) ++r;
+    tm = r;
+    tn = v - r * (r + 1) / 2;
+}
+
+// Work map of a GEMM launch: one workgroup per tile that has work, in a one-dimensional grid (workgroups that return
+// at once are not free: each still waits for its turn at a CU, and a quarter of such workgroups in a launch cost a
+// quarter of its time).  Workgroups are dispatched in rank order; with a triangular operand the tiles differ in
+// length (B lower: the inner range starts at the tile's column, so tile columns get shorter to the right; A lower: it
+// ends at the tile's row, so tile rows get longer downwards) and the longest tiles come first, so that no long tile
+// starts when the rest of the launch is nearly done.  Order: the last batch entry (the only one that can be
+// shorter), then the other entries interleaved tile by tile.
+struct GemmGrid {
+    int tn_cnt, tm_full, tm_last, per_full, per_last, total;
+};
+__host__ __device__ inline GemmGrid gemm_grid(const GemmArgs& g) {
+    GemmGrid q;
+    q.tn_cnt = (g.n + GT - 1) / GT;
+    q.tm_full = (g.m + GT - 1) / GT;
+    q.tm_last = (g.m_last + GT - 1) / GT;
+    if (g.flags & G_CLOWER) {   // square C, lower tiles only
+        q.per_full = q.tm_full * (q.tm_full + 1) / 2;
+        q.per_last = q.tm_last * (q.tm_last + 1) / 2;
+    } else {
+        q.per_full = q.tm_full * q.tn_cnt;
+        q.per_last = q.tm_last * q.tn_cnt;
     }
-    dgemm_tile<bt>(g, tn, tm, blockIdx.z, false);
+    q.total = q.per_last + (g.batch - 1) * q.per_full;
+    return q;
+}
+__device__ __forceinline__ void gemm_tile_from_rank(const GemmArgs& g, int v, int& tm, int& tn, int& z) {
+    const GemmGrid q = gemm_grid(g);
+    int rem, tm_cnt;
+    if (v < q.per_last) {
+        z = g.batch - 1;
+        rem = v;
+        tm_cnt = q.tm_last;
+    } else {
+        v -= q.per_last;
+        z = v % (g.batch - 1);
+        rem = v / (g.batch - 1);
+        tm_cnt = q.tm_full;
+    }
+    if (g.flags & G_CLOWER) {
+        lower_tile_from_rank(rem, tm, tn);
+    } else if (g.flags & G_BLOWER) {   // tile columns left to right, rows fastest
+        tn = rem / tm_cnt;
+        tm = rem % tm_cnt;
+    } else if (g.flags & G_ALOWER) {   // tile rows from the bottom
+        tm = tm_cnt - 1 - rem / q.tn_cnt;
+        tn = rem % q.tn_cnt;
+    } else {
+        tm = rem / q.tn_cnt;
+        tn = rem % q.tn_cnt;
+    }
+}
+
+// Stand-alone GEMM launches run eight waves per workgroup (64 x 32 per wave, under 128 registers): four waves share a
+// SIMD and cover each other's waits (k = 128 updates: 46 -> 51 TFLOP/s; large GEMMs 64 -> 66).
+constexpr int GEMM_WAVES = 8;
+template <bool bt>
+__global__ __launch_bounds__(64 * GEMM_WAVES, 2) void dgemm_kernel(GemmArgs g) {
+    int tm, tn, z;
+    gemm_tile_from_rank(g, blockIdx.x, tm, tn, z);
+    dgemm_tile<bt, GEMM_WAVES>(g, tn, tm, z, false);
 }
 
 __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A, double* __restrict__ V, int n,
@@ -642,8 +701,10 @@ __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A,
 // matrix.  Takes the single-workgroup factorization off the critical path of every step whose update is longer.
 __global__ __launch_bounds__(256, 2) void syrk_potrf_kernel(GemmArgs g, double* __restrict__ A, double* __restrict__ V,
                                                            int n, int off, int bs, int32_t* __restrict__ info) {
-    const bool first = (blockIdx.x == 0 && blockIdx.y == 0);
-    dgemm_tile<true>(g, blockIdx.x, blockIdx.y, 0, first);
+    const bool first = blockIdx.x == 0;
+    int tm, tn;
+    lower_tile_from_rank(blockIdx.x, tm, tn);
+    dgemm_tile<true>(g, tn, tm, 0, first);
     if (first) {
         __syncthreads();
         potrf_body(A, V, n, off, bs, info, wg_lds(), true);
@@ -709,11 +770,10 @@ __global__ __launch_bounds__(256) void trsm_kernel(double* __restrict__ P, int64
 }
 
 onecomp_status dgemm(const GemmArgs& g, hipStream_t stream) {
-    if (g.m <= 0 || g.n <= 0 || g.batch <= 0) return ONECOMP_OK;
-    dim3 grid(unsigned(ceil_div(g.n, GT)), unsigned(ceil_div(g.m, GT)), unsigned(g.batch));
-    if (g.flags & G_BLOWER) grid = dim3(grid.y, grid.x, grid.z);   // see dgemm_kernel
-    if (g.flags & G_BTRANS) hipLaunchKernelGGL(dgemm_kernel<true>, grid, dim3(256), 0, stream, g);
-    else hipLaunchKernelGGL(dgemm_kernel<false>, grid, dim3(256), 0, stream, g);
+    if (g.m <= 0 || g.n <= 0 || g.batch <= 0 || g.m_last <= 0) return ONECOMP_OK;
+    const dim3 grid(unsigned(gemm_grid(g).total), 1, 1);
+    if (g.flags & G_BTRANS) hipLaunchKernelGGL(dgemm_kernel<true>, grid, dim3(64 * GEMM_WAVES), 0, stream, g);
+    else hipLaunchKernelGGL(dgemm_kernel<false>, grid, dim3(64 * GEMM_WAVES), 0, stream, g);
     ONECOMP_CHECK_LAUNCH();
     return ONECOMP_OK;
 }
@@ -791,7 +851,8 @@ onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_orde
         s.alpha = -1.0; s.beta = 1.0; s.flags = G_BTRANS | G_CLOWER;
         {
             const int off1 = off + bs;
-            dim3 grid(unsigned(ceil_div(rest, GT)), unsigned(ceil_div(rest, GT)), 1);
+            const unsigned nt = unsigned(ceil_div(rest, GT));
+            dim3 grid(nt * (nt + 1) / 2, 1, 1);   // the lower tiles, (0, 0) first
             hipLaunchKernelGGL(syrk_potrf_kernel, grid, dim3(256), 0, stream, s, w.A, w.V, n, off1, min(NB, n - off1),
                                info);
             ONECOMP_CHECK_LAUNCH();
