@@ -619,6 +619,197 @@ __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, cons
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// The same tile with the operands streamed global -> LDS directly (buffer_load ... lds) through a ring of RNS slots
+// of RK inner steps each, three stages ahead of the MFMAs: no staging registers, no LDS stores, no multiplication by
+// alpha on the way (alpha = +-1 is folded into the accumulators: they start as (beta / alpha) C and the result is
+// alpha acc, both exact), one barrier per stage.  A direct load deposits lane l at slot + 16 l, so rows cannot be
+// padded; the 16-byte chunks (two doubles) are permuted instead, which costs nothing on the global side because
+// every lane supplies its own address:
+//   A-form part (128 rows x RK k, a row is 64 B = 4 chunks): chunk c of row r sits at position c ^ ((r >> 2) & 3);
+//     the 16 rows x 2 k that one half-wave reads for an MFMA operand then fall into 64 different banks.
+//   NN B part (RK k-rows x 128 columns, a k-row is 1 KB = 64 chunks): chunk c of k-row kr sits at c ^ ((kr & 1) << 3).
+// ------------------------------------------------------------------------------------------
+constexpr int RK = 8, RNS = 4;
+constexpr int R_PART_BYTES = GT * RK * 8;           // 8 KB: the A part or the B part of a stage
+constexpr int R_STAGE_BYTES = 2 * R_PART_BYTES;
+static_assert(RNS * R_STAGE_BYTES <= LDS_DOUBLES * 8, "the ring fits the workgroup's LDS");
+
+template <bool bt, int NW>
+__device__ __forceinline__ void dgemm_tile_ring(const GemmArgs& g, const int tn, const int tm, const int z,
+                                                const bool tri_out) {
+    constexpr int NJ = 16 / NW;    // 16-column MFMA tiles per wave
+    constexpr int LPW = 16 / NW;   // 1 KB loads per wave and stage: 8 for the A part, 8 for the B part
+    double* lds = wg_lds();
+    const bool last = (z == g.batch - 1);
+    const int m = last ? g.m_last : g.m;
+    const int kdim = last ? g.k_last : g.k;
+    if (tm * GT >= m) return;
+    if ((g.flags & G_CLOWER) && tn > tm) return;
+    const double* __restrict__ A = g.A + z * g.sa;
+    const double* __restrict__ B = g.B + z * g.sb;
+    double* __restrict__ C = g.C + z * g.sc;
+    int k_lo = 0, k_hi = kdim;
+    if (g.flags & G_BLOWER) k_lo = tn * GT;
+    if (g.flags & G_ALOWER) k_hi = min(kdim, (tm + 1) * GT);
+    const int n_st = k_hi > k_lo ? (k_hi - k_lo) / RK : 0;   // inner ranges are multiples of 16
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave / (NW / 2), wc = wave % (NW / 2);
+    const int m0 = tm * GT, n0 = tn * GT;
+    const int cw = wc * (NJ * 16);
+    const int l16 = lane & 15, lk = lane >> 4;
+    const uint32_t lds0 = uint32_t(uintptr_t((ONECOMP_LDS char*)lds));
+
+    // descriptor bases: the tile's first operand row / column at the start of the inner range; a stage's descriptor
+    // starts RK inner steps further on (64-bit scalar arithmetic), so that the 32-bit offsets of the lanes stay
+    // below 128 rows x ld
+    const double* const abase = A + int64_t(m0) * g.lda + k_lo;
+    const double* const bbase = bt ? B + int64_t(n0) * g.ldb + k_lo : B + int64_t(k_lo) * g.ldb + n0;
+    const int64_t step_b = bt ? int64_t(RK) : int64_t(RK) * g.ldb;   // doubles along k per stage
+    uint32_t voff[LPW], ldst[LPW];
+#pragma unroll
+    for (int q = 0; q < LPW; ++q) {
+        const int j = wave + NW * q;            // load of the stage: 0 .. 7 A part, 8 .. 15 B part (uniform per q)
+        const bool is_a = q * NW < 8;
+        const int jj = is_a ? j : j - 8;
+        if (is_a || bt) {
+            const int row = 16 * jj + (lane >> 2);
+            const int c = (lane & 3) ^ ((row >> 2) & 3);
+            const bool ok = is_a ? (m0 + row < m) : (n0 + row < g.n);
+            voff[q] = ok ? uint32_t((int64_t(row) * (is_a ? g.lda : g.ldb) + 2 * c) * 8) : LDS_DMA_OOB;
+        } else {
+            const int kr = jj;
+            const int c = lane ^ ((kr & 1) << 3);
+            voff[q] = (n0 + 2 * c < g.n) ? uint32_t((int64_t(kr) * g.ldb + 2 * c) * 8) : LDS_DMA_OOB;
+        }
+        ldst[q] = (is_a ? 0 : R_PART_BYTES) + jj * 1024;
+    }
+    auto issue = [&](int st) __attribute__((always_inline)) {   // loads of stage st into its slot; past the end: zeros
+        const uint32_t slot = lds0 + uint32_t(st % RNS) * R_STAGE_BYTES;
+        const bool live = st < n_st;
+        const int64_t sk = live ? int64_t(st) : 0;
+        const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<double*>(abase + sk * RK), 0, 0x7FFFFFFF, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<double*>(bbase + sk * step_b), 0, 0x7FFFFFFF, 0x00020000);
+#pragma unroll
+        for (int q = 0; q < LPW; ++q)
+            lds_load16(slot + ldst[q], live ? voff[q] : LDS_DMA_OOB, (q * NW < 8) ? ra : rb);
+    };
+    for (int st = 0; st < RNS - 1; ++st) issue(st);
+
+    // accumulators start as (beta / alpha) C (alpha = +-1: exact); register r of lane l: row 4 r + l / 16,
+    // column l % 16 of its 16 x 16 tile
+    const double binit = g.beta * g.alpha;   // beta / alpha for alpha = +-1
+    double4v acc[4][NJ];
+    const bool full = (m0 + GT <= m) && (n0 + GT <= g.n);
+    double* __restrict__ ct = C + int64_t(m0 + wr * 64 + lk) * g.ldc + n0 + cw + l16;
+    if (g.beta == 0.0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0;
+    } else if (full) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[i][j][r] = binit * ct[int64_t(i * 16 + 4 * r) * g.ldc + j * 16];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
+                    const int col = n0 + cw + j * 16 + l16;
+                    double c = 0.0;
+                    if (row < m && col < g.n) c = binit * C[int64_t(row) * g.ldc + col];
+                    acc[i][j][r] = c;
+                }
+    }
+
+    // fragment addresses inside a stage (bytes), inner steps 0 .. 3; steps 4 .. 7: A-form ^ 32, NN + 4 KB
+    int fa[4], fb[NJ];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = wr * 64 + i * 16 + l16;
+        fa[i] = row * 64 + (((lk >> 1) ^ ((row >> 2) & 3)) << 4) + (lk & 1) * 8;
+    }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int col = cw + j * 16 + l16;
+        if (bt) fb[j] = R_PART_BYTES + col * 64 + (((lk >> 1) ^ ((col >> 2) & 3)) << 4) + (lk & 1) * 8;
+        else fb[j] = R_PART_BYTES + lk * 1024 + (((col >> 1) ^ ((lk & 1) << 3)) << 4) + (col & 1) * 8;
+    }
+    const char* ldsc = reinterpret_cast<const char*>(lds);
+
+    for (int st = 0; st < n_st; ++st) {
+        // the loads of stages st + 1 and st + 2 may still be in flight: wait for those of stage st, publish them,
+        // and refill the slot every wave has finished reading (stage st - 1)
+        __builtin_amdgcn_s_waitcnt(wait_vmcnt(LPW * (RNS - 2)));
+        __syncthreads();
+        issue(st + RNS - 1);
+        const char* sp = ldsc + (st % RNS) * R_STAGE_BYTES;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            double a[4], b[NJ];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const double*>(sp + (h ? fa[i] ^ 32 : fa[i]));
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                b[j] = *reinterpret_cast<const double*>(sp + (bt ? (h ? fb[j] ^ 32 : fb[j]) : fb[j] + h * 4096));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // no LDS write may be in flight when the slots are reused or the workgroup ends
+
+    const double aout = g.alpha;
+    if (full) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) ct[int64_t(i * 16 + 4 * r) * g.ldc + j * 16] = aout * acc[i][j][r];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
+                    const int col = n0 + cw + j * 16 + l16;
+                    if (row < m && col < g.n) C[int64_t(row) * g.ldc + col] = aout * acc[i][j][r];
+                }
+    }
+    if (tri_out) {   // uniform; every wave must be done with the last stage before the operand slots are overwritten
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int lrow = wr * 64 + i * 16 + 4 * r + lk, lcol = cw + j * 16 + l16;
+                    if ((lcol >> 4) > (lrow >> 4)) continue;
+                    const bool inside = (m0 + lrow < m) && (n0 + lcol < g.n);
+                    lds[tri(lrow, lcol)] = inside ? aout * acc[i][j][r] : (lrow == lcol ? 1.0 : 0.0);
+                }
+    }
+}
+
 // Tile (tm, tn), tn <= tm, of rank v in the row-major enumeration of a lower triangle of tiles.
 __device__ __forceinline__ void lower_tile_from_rank(int v, int& tm, int& tn) {
     int r = int((__fsqrt_rn(8.0f * float(v) + 1.0f) - 1.0f) * 0.5f);
@@ -687,7 +878,7 @@ template <bool bt>
 __global__ __launch_bounds__(64 * GEMM_WAVES, 2) void dgemm_kernel(GemmArgs g) {
     int tm, tn, z;
     gemm_tile_from_rank(g, blockIdx.x, tm, tn, z);
-    dgemm_tile<bt, GEMM_WAVES>(g, tn, tm, z, false);
+    dgemm_tile_ring<bt, GEMM_WAVES>(g, tn, tm, z, false);
 }
 
 __global__ __launch_bounds__(256) void potrf_diag_kernel(double* __restrict__ A, double* __restrict__ V, int n,
@@ -704,7 +895,7 @@ __global__ __launch_bounds__(256, 2) void syrk_potrf_kernel(GemmArgs g, double* 
     const bool first = blockIdx.x == 0;
     int tm, tn;
     lower_tile_from_rank(blockIdx.x, tm, tn);
-    dgemm_tile<true>(g, tn, tm, 0, first);
+    dgemm_tile_ring<true, 4>(g, tn, tm, 0, first);
     if (first) {
         __syncthreads();
         potrf_body(A, V, n, off, bs, info, wg_lds(), true);
