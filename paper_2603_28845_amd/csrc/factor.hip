@@ -10,7 +10,8 @@
 // gfx950 design
 //   * blocked right-looking Cholesky, block 128: diagonal block factored (and inverted) inside one
 //     workgroup's LDS; panel solve and trailing update are fp64 MFMA GEMMs (v_mfma_f64_16x16x4_f64),
-//     128 x 128 tile per workgroup, LDS double-buffered.
+//     128 x 128 tile per workgroup, operands streamed global -> LDS directly through a four-slot ring; a launch
+//     has one workgroup per tile that has work, the longest tiles first.
 //   * triangular inverse by recursive doubling over aligned block pairs: for block size s = 128 * 2^l,
 //     V[C,A] = -V[C,C] (L[C,A] V[A,A]); every level is two batched GEMMs, so the whole inverse is
 //     ~2 log2(n/128) large launches instead of n/128 skinny ones.
@@ -416,10 +417,6 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
 // fp64 MFMA GEMM:  C = alpha * A * op(B) + beta * C   (batched, optional triangular structure)
 // ------------------------------------------------------------------------------------------
 constexpr int GT = 128;  // tile side
-constexpr int GK = 16;   // K per LDS stage
-constexpr int GPA = GK + 1;
-constexpr int GPB = GT + 4;
-constexpr int GSB = GT * GPA;  // >= GK * GPB
 
 enum : int { G_BTRANS = 1, G_ALOWER = 2, G_BLOWER = 4, G_CLOWER = 8 };
 
@@ -435,7 +432,10 @@ struct GemmArgs {
     int flags;
 };
 
-constexpr int GEMM_LDS_DOUBLES = 2 * GT * GPA + 2 * GSB;
+constexpr int RK = 8, RNS = 4;                      // inner steps per ring slot, ring slots of the GEMM tile
+constexpr int R_PART_BYTES = GT * RK * 8;           // 8 KB: the A part or the B part of a stage
+constexpr int R_STAGE_BYTES = 2 * R_PART_BYTES;
+constexpr int GEMM_LDS_DOUBLES = RNS * R_STAGE_BYTES / 8;
 constexpr int LDS_DOUBLES = GEMM_LDS_DOUBLES > POTRF_LDS_DOUBLES ? GEMM_LDS_DOUBLES : POTRF_LDS_DOUBLES;
 
 // The workgroup's LDS: one static array per kernel, shared by the GEMM tile code and the factorization code.
@@ -444,183 +444,13 @@ __device__ __forceinline__ double* wg_lds() {
     return lds;
 }
 
-// One 128 x 128 tile (tm, tn) of batch entry z.  tri_out: the finished tile is also left in LDS (from its start,
-// over the dead operand tiles) in the layout of potrf_body (lower sub-blocks, identity beyond the matrix edge),
-// for a diagonal tile that the same workgroup factors next.
-// NW waves per workgroup: 4 (2 x 2 waves of 64 x 64) or 8 (2 x 4 waves of 64 x 32: half the accumulators per lane, so
-// that twice as many waves share a SIMD and cover each other's waits).
-template <bool bt, int NW = 4>   // bt: B is given transposed (n x k, k contiguous)
-__device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, const int tm, const int z,
-                                           const bool tri_out) {
-    constexpr int NJ = 16 / NW;          // 16-column MFMA tiles per wave
-    constexpr int EP = 2048 / (64 * NW); // elements of each operand tile per thread and stage
-    double* lds = wg_lds();
-    double(*sA)[GT * GPA] = reinterpret_cast<double(*)[GT * GPA]>(lds);
-    double(*sB)[GSB] = reinterpret_cast<double(*)[GSB]>(lds + 2 * GT * GPA);
-    const bool last = (z == g.batch - 1);
-    const int m = last ? g.m_last : g.m;
-    const int kdim = last ? g.k_last : g.k;
-    if (tm * GT >= m) return;
-    if ((g.flags & G_CLOWER) && tn > tm) return;
-    const double* __restrict__ A = g.A + z * g.sa;
-    const double* __restrict__ B = g.B + z * g.sb;
-    double* __restrict__ C = g.C + z * g.sc;
-    int k_lo = 0, k_hi = kdim;
-    if (g.flags & G_BLOWER) k_lo = tn * GT;
-    if (g.flags & G_ALOWER) k_hi = min(kdim, (tm + 1) * GT);
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wr = wave / (NW / 2), wc = wave % (NW / 2);
-    const int m0 = tm * GT, n0 = tn * GT;
-    const int cw = wc * (NJ * 16);   // first column of this wave inside the tile
-
-    // loaders: A-form tile (rows x GK, k contiguous): EP doubles of one row per thread
-    //          NN B tile (GK x cols): EP doubles of one k row per thread
-    const int a_row = tid / (GK / EP), a_k = (tid % (GK / EP)) * EP;
-    const int b_kr = tid / (GT / EP), b_c = (tid % (GT / EP)) * EP;
-    double ra[EP], rb[EP];
-    auto gload = [&](int k0) {
-        {
-            const int r = m0 + a_row, kk = k0 + a_k;
-            const bool ok = (r < m) && (kk < k_hi);
-            const double2* p = reinterpret_cast<const double2*>(A + int64_t(r) * g.lda + kk);
-#pragma unroll
-            for (int e = 0; e < EP / 2; ++e) {
-                double2 v = ok ? p[e] : make_double2(0.0, 0.0);
-                ra[2 * e] = v.x; ra[2 * e + 1] = v.y;
-            }
-        }
-        if (bt) {
-            const int r = n0 + a_row, kk = k0 + a_k;
-            const bool ok = (r < g.n) && (kk < k_hi);
-            const double2* p = reinterpret_cast<const double2*>(B + int64_t(r) * g.ldb + kk);
-#pragma unroll
-            for (int e = 0; e < EP / 2; ++e) {
-                double2 v = ok ? p[e] : make_double2(0.0, 0.0);
-                rb[2 * e] = v.x; rb[2 * e + 1] = v.y;
-            }
-        } else {
-            const int kk = k0 + b_kr, c = n0 + b_c;
-            const bool ok = (kk < k_hi) && (c < g.n);
-            const double2* p = reinterpret_cast<const double2*>(B + int64_t(kk) * g.ldb + c);
-#pragma unroll
-            for (int e = 0; e < EP / 2; ++e) {
-                double2 v = ok ? p[e] : make_double2(0.0, 0.0);
-                rb[2 * e] = v.x; rb[2 * e + 1] = v.y;
-            }
-        }
-    };
-    auto lstore = [&](int st) {
-#pragma unroll
-        for (int e = 0; e < EP; ++e) sA[st][a_row * GPA + a_k + e] = g.alpha * ra[e];   // alpha folded into A
-        if (bt) {
-#pragma unroll
-            for (int e = 0; e < EP; ++e) sB[st][a_row * GPA + a_k + e] = rb[e];
-        } else {
-#pragma unroll
-            for (int e = 0; e < EP; ++e) sB[st][b_kr * GPB + b_c + e] = rb[e];
-        }
-    };
-
-    const int l16 = lane & 15, lk = lane >> 4;
-    if (k_lo < k_hi) gload(k_lo);
-    // accumulators start as beta * C (register r of lane l: row 4 r + l / 16, column l % 16 of its 16 x 16 tile),
-    // so the C tile is in flight together with the first operand tiles
-    double4v acc[4][NJ];
-    const bool full = (m0 + GT <= m) && (n0 + GT <= g.n);   // uniform: interior tiles need no per-element masks
-    double* __restrict__ ct = C + int64_t(m0 + wr * 64 + lk) * g.ldc + n0 + cw + l16;
-    if (g.beta == 0.0) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0;
-    } else if (full) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc[i][j][r] = g.beta * ct[int64_t(i * 16 + 4 * r) * g.ldc + j * 16];
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
-                    const int col = n0 + cw + j * 16 + l16;
-                    double c = 0.0;
-                    if (row < m && col < g.n) c = g.beta * C[int64_t(row) * g.ldc + col];
-                    acc[i][j][r] = c;
-                }
-    }
-
-    if (k_lo < k_hi) lstore(0);
-    __syncthreads();
-    int st = 0;
-    for (int k0 = k_lo; k0 < k_hi; k0 += GK) {
-        const bool more = (k0 + GK < k_hi);
-        if (more) gload(k0 + GK);
-#pragma unroll
-        for (int k4 = 0; k4 < GK; k4 += 4) {
-            double a[4], b[NJ];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = sA[st][(wr * 64 + i * 16 + l16) * GPA + k4 + lk];
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                b[j] = bt ? sB[st][(cw + j * 16 + l16) * GPA + k4 + lk]
-                          : sB[st][(k4 + lk) * GPB + cw + j * 16 + l16];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < NJ; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) lstore(st ^ 1);
-        __syncthreads();
-        st ^= 1;
-    }
-
-    // accumulator register r of lane l: row 4 r + l / 16, column l % 16 of its 16 x 16 tile
-    if (full) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) ct[int64_t(i * 16 + 4 * r) * g.ldc + j * 16] = acc[i][j][r];
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = m0 + wr * 64 + i * 16 + 4 * r + lk;
-                    const int col = n0 + cw + j * 16 + l16;
-                    if (row < m && col < g.n) C[int64_t(row) * g.ldc + col] = acc[i][j][r];
-                }
-    }
-    if (tri_out) {   // uniform; the K loop ended with a barrier, so the operand tiles are dead
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int lrow = wr * 64 + i * 16 + 4 * r + lk, lcol = cw + j * 16 + l16;
-                    if ((lcol >> 4) > (lrow >> 4)) continue;
-                    const bool inside = (m0 + lrow < m) && (n0 + lcol < g.n);
-                    lds[tri(lrow, lcol)] = inside ? acc[i][j][r] : (lrow == lcol ? 1.0 : 0.0);
-                }
-    }
-}
-
 // ------------------------------------------------------------------------------------------
-// The same tile with the operands streamed global -> LDS directly (buffer_load ... lds) through a ring of RNS slots
+// One 128 x 128 tile (tm, tn) of batch entry z with NW waves: 4 (2 x 2 waves of 64 x 64) or 8 (2 x 4 waves of
+// 64 x 32: half the accumulators per lane, so that four waves share a SIMD and cover each other's waits).
+// tri_out: the finished tile is also left in LDS (from its start, over the dead operand slots) in the layout of
+// potrf_body (lower sub-blocks, identity beyond the matrix edge), for a diagonal tile that the same workgroup
+// factors next.
+// The operands are streamed global -> LDS directly (buffer_load ... lds) through a ring of RNS slots
 // of RK inner steps each, three stages ahead of the MFMAs: no staging registers, no LDS stores, no multiplication by
 // alpha on the way (alpha = +-1 is folded into the accumulators: they start as (beta / alpha) C and the result is
 // alpha acc, both exact), one barrier per stage.  A direct load deposits lane l at slot + 16 l, so rows cannot be
@@ -630,10 +460,6 @@ __device__ __forceinline__ void dgemm_tile(const GemmArgs& g, const int tn, cons
 //     the 16 rows x 2 k that one half-wave reads for an MFMA operand then fall into 64 different banks.
 //   NN B part (RK k-rows x 128 columns, a k-row is 1 KB = 64 chunks): chunk c of k-row kr sits at c ^ ((kr & 1) << 3).
 // ------------------------------------------------------------------------------------------
-constexpr int RK = 8, RNS = 4;
-constexpr int R_PART_BYTES = GT * RK * 8;           // 8 KB: the A part or the B part of a stage
-constexpr int R_STAGE_BYTES = 2 * R_PART_BYTES;
-static_assert(RNS * R_STAGE_BYTES <= LDS_DOUBLES * 8, "the ring fits the workgroup's LDS");
 
 template <bool bt, int NW>
 __device__ __forceinline__ void dgemm_tile_ring(const GemmArgs& g, const int tn, const int tm, const int z,
