@@ -194,7 +194,7 @@ def bench_jointq(args, cfg, og, W, H, out, perm):
     }
 
 
-def bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out):
+def bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out, ws_a=None):
     """The layer with error propagation: X_hat = X perturbed by 5 % stands in for the activations of the partly
     quantized model.  One step = H from X_hat, G from (X_hat, X), factor, corrected target W*, sweep of W*."""
     import torch
@@ -208,7 +208,7 @@ def bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out):
         e = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
         H.zero_(); G.zero_()
         e[0].record()
-        og.onecomp_hessian_accumulate(Xh, H)
+        og.onecomp_hessian_accumulate(Xh, H, workspace=ws_a)
         e[1].record()
         og.onecomp_crossgram_accumulate(Xh, X, G)
         e[2].record()
@@ -644,7 +644,7 @@ def main():
     if args.jointq > 0 and phase == "all" and (cfg.group_size <= 128 or cfg.group_size % 128 == 0):
         res["jointq"] = bench_jointq(args, cfg, og, W, H, out, perm if cfg.act_order else None)
     if args.qep:
-        res["qep"] = bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out)
+        res["qep"] = bench_qep(args, cfg, og, synth, W, X, H, U, info, perm, ws_f, ws_q, out, ws_a)
     if not args.no_cpu_baseline:
         del X
         torch.cuda.empty_cache()
