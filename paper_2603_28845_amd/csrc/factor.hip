@@ -720,7 +720,12 @@ __global__ __launch_bounds__(256, 2) void syrk_potrf_kernel(GemmArgs g, double* 
                                                            int n, int off, int bs, int32_t* __restrict__ info) {
     const bool first = blockIdx.x == 0;
     int tm, tn;
-    lower_tile_from_rank(blockIdx.x, tm, tn);
+    if (g.flags & G_CLOWER) {
+        lower_tile_from_rank(blockIdx.x, tm, tn);
+    } else {   // one block column whose first tile lies on the diagonal: one workgroup per tile row
+        tm = blockIdx.x;
+        tn = 0;
+    }
     dgemm_tile_ring<true, 4>(g, tn, tm, 0, first);
     if (first) {
         __syncthreads();
@@ -847,32 +852,52 @@ onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_orde
     const int nblk = int(ceil_div(n, NB));
     hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), 0, stream, w.A, w.V, n, 0, min(NB, n), info);
     ONECOMP_CHECK_LAUNCH();
-    for (int kb = 0; kb < nblk; ++kb) {
-        const int off = kb * NB;
-        const int bs = min(NB, n - off);
-        const int rest = n - off - bs;
-        if (rest <= 0) break;
-        // panel: A[off+bs:, off:off+bs] <- A[off+bs:, off:off+bs] * Linv_kk^T   (in place; bs = NB: only the last
-        // block can be shorter and it has no panel below it)
-        GemmArgs p{};
-        p.C = w.A + int64_t(off + bs) * n + off;
-        hipLaunchKernelGGL(trsm_kernel, dim3(unsigned(ceil_div(rest, TR))), dim3(256), 0, stream, p.C, int64_t(n), rest,
-                           w.V + int64_t(off) * n + off, int64_t(n));
+    // One step: panel solve below diagonal block kb, then the trailing update fused with the factorization of the
+    // next diagonal block.  While the trailing matrix is large the steps go in pairs: the first block's update is
+    // applied to the next block column only (enough to factor and solve that one), and both blocks update everything
+    // behind the pair in one pass with k = 256: the rank-128 update is bound by reading and writing the trailing
+    // matrix (52 TFLOP/s at best, 60 with k = 256), and the additions happen in the same order, so the factor is
+    // bit-equal.  The price is the second block's factorization, which now has only a short launch to hide behind
+    // (about 70 us per pair): below PAIR_MIN_BLOCKS tile rows the saving no longer covers it.
+    auto panel_solve = [&](int off, int rest) -> onecomp_status {
+        // A[off+NB:, off:off+NB] <- A[off+NB:, off:off+NB] * Linv_kk^T   (in place)
+        hipLaunchKernelGGL(trsm_kernel, dim3(unsigned(ceil_div(rest, TR))), dim3(256), 0, stream,
+                           w.A + int64_t(off + NB) * n + off, int64_t(n), rest, w.V + int64_t(off) * n + off, int64_t(n));
         ONECOMP_CHECK_LAUNCH();
-        // trailing: A[i][j] -= P[i] P[j]^T on the lower tiles
+        return ONECOMP_OK;
+    };
+    // C[c_off:, c_off : c_off + cols) -= P P^T with P = A[c_off:, k_off : k_off + k), lower tiles when cols covers the
+    // whole remainder; the first tile is the next diagonal block, factored by the same workgroup
+    auto update = [&](int c_off, int cols, int k_off, int k, bool lower) -> onecomp_status {
+        const int rows = n - c_off;
         GemmArgs s{};
-        s.A = p.C; s.lda = n; s.sa = 0;
-        s.B = p.C; s.ldb = n; s.sb = 0;
-        s.C = w.A + int64_t(off + bs) * n + (off + bs); s.ldc = n; s.sc = 0;
-        s.m = rest; s.m_last = rest; s.n = rest; s.k = bs; s.k_last = bs; s.batch = 1;
-        s.alpha = -1.0; s.beta = 1.0; s.flags = G_BTRANS | G_CLOWER;
-        {
-            const int off1 = off + bs;
-            const unsigned nt = unsigned(ceil_div(rest, GT));
-            dim3 grid(nt * (nt + 1) / 2, 1, 1);   // the lower tiles, (0, 0) first
-            hipLaunchKernelGGL(syrk_potrf_kernel, grid, dim3(256), 0, stream, s, w.A, w.V, n, off1, min(NB, n - off1),
-                               info);
-            ONECOMP_CHECK_LAUNCH();
+        s.A = w.A + int64_t(c_off) * n + k_off; s.lda = n; s.sa = 0;
+        s.B = s.A; s.ldb = n; s.sb = 0;
+        s.C = w.A + int64_t(c_off) * n + c_off; s.ldc = n; s.sc = 0;
+        s.m = rows; s.m_last = rows; s.n = cols; s.k = k; s.k_last = k; s.batch = 1;
+        s.alpha = -1.0; s.beta = 1.0; s.flags = G_BTRANS | (lower ? G_CLOWER : 0);
+        const unsigned nt = unsigned(ceil_div(rows, GT));
+        const dim3 grid(lower ? nt * (nt + 1) / 2 : nt, 1, 1);   // tile (0, 0) first
+        hipLaunchKernelGGL(syrk_potrf_kernel, grid, dim3(256), 0, stream, s, w.A, w.V, n, c_off, min(NB, n - c_off),
+                           info);
+        ONECOMP_CHECK_LAUNCH();
+        return ONECOMP_OK;
+    };
+    constexpr int PAIR_MIN_BLOCKS = 60;
+    for (int kb = 0; kb < nblk;) {
+        const int off = kb * NB;
+        const int rest = n - off - NB;     // rows below this block (only the last block can be shorter than NB,
+        if (rest <= 0) break;              // and it has nothing below it)
+        if ((st = panel_solve(off, rest)) != ONECOMP_OK) return st;
+        const int rest2 = rest - NB;       // rows below the next block
+        if (rest2 >= PAIR_MIN_BLOCKS * NB) {
+            if ((st = update(off + NB, NB, off, NB, false)) != ONECOMP_OK) return st;       // next block column only
+            if ((st = panel_solve(off + NB, rest2)) != ONECOMP_OK) return st;
+            if ((st = update(off + 2 * NB, rest2, off, 2 * NB, true)) != ONECOMP_OK) return st;   // both blocks, k = 256
+            kb += 2;
+        } else {
+            if ((st = update(off + NB, rest, off, NB, true)) != ONECOMP_OK) return st;
+            kb += 1;
         }
     }
 
