@@ -21,6 +21,7 @@
 #include "planner.hpp"
 #include <stdlib.h>
 #include <string.h>
+#include <type_traits>
 
 namespace onecomp {
 namespace {
@@ -489,11 +490,18 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
     // file and the rest to the VGPR half by the operand constraints of the instruction itself (left to choose, the
     // compiler copies tiles between the halves).
     constexpr int N_AGPR_TILES = (MT * NT > 16) ? 16 : MT * NT;
-    auto mma = [&](const Frags& f, auto&& between) __attribute__((always_inline)) {
+    // These MFMAs are opaque to the compiler's hazard handling, which therefore puts no wait states between the last
+    // of them and whatever reads an accumulator at the loop's exit (the epilogue, or a spill or a copy between the
+    // register halves that the compiler places there).  The last MFMA of a loop iteration carries the wait states
+    // itself; they pass while that MFMA executes, and the instructions that follow wait for the other waves anyway.
+    auto mma = [&](const Frags& f, auto&& between, auto closes_iteration) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < MT * NT; ++i) {
             if constexpr (MT * NT > 16) {
-                if (i < N_AGPR_TILES)
+                if (decltype(closes_iteration)::value && i == MT * NT - 1)
+                    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15\n\ts_nop 15"
+                                 : "+v"(acc[i / NT][i % NT]) : "v"(f.a[i / NT]), "v"(f.b[i % NT]));
+                else if (i < N_AGPR_TILES)
                     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
                                  : "+a"(acc[i / NT][i % NT]) : "v"(f.a[i / NT]), "v"(f.b[i % NT]));
                 else
@@ -521,7 +529,7 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
             mma(Fc, [&](int i) __attribute__((always_inline)) {
                 if (i < MT + NT) rd(FH, i, sb);
                 if (i < LPW) gload(d, dst, i);
-            });
+            }, std::false_type{});
             __builtin_amdgcn_s_waitcnt(wait_vmcnt(LPW * (NBUF - 2)));   // step st+2 has landed
             __syncthreads();
         }
@@ -532,18 +540,13 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
             mma(FH, [&](int i) __attribute__((always_inline)) {
                 if (i < MT + NT) rd(Fc, i, sb);
                 if (i < LPW) gload(d, dst, i);
-            });
+            }, std::true_type{});
             __builtin_amdgcn_s_waitcnt(wait_vmcnt(LPW * (NBUF - 2)));   // step st+3 has landed
             __syncthreads();
         }
         s0 = s2;
     }
     __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // no LDS write may be in flight when the workgroup ends
-    if constexpr (MT * NT > 16) {
-        // the MFMAs above are opaque to the compiler's hazard handling: let the last of them retire before the
-        // epilogue reads the accumulators
-        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-    }
     if (piece >= 0 && ws) {   // partial sum of the tile, in accumulator order: consecutive lanes, consecutive addresses
         float* slot = ws + (int64_t(m_split) * n_piece + piece) * (C::TM * C::TN) + wave * (MT * NT * 16 * 64) + lane;
 #pragma unroll
