@@ -546,7 +546,10 @@ def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=
     in order, n_pass times; inside a visit the columns of the group are scanned in order, for each column +1 is
     tried before -1 and the first improving one is taken at once (at most one per column and scan); the visit ends
     with the first scan that takes no move, or after max_scans scans; on entering a visit the group's scale is
-    first refit to its current codes; a group whose codes all equal its zero-point is left alone.
+    first refit to its current codes; a group whose codes all equal its zero-point is left alone, and no move may
+    bring a group there (the refit scale b / c is undefined at u = 0: c' = 0 and N = -c' b^2 / c reaches 0 from
+    below, so by "N > 0 and c' > 0" the move is never taken; deciding it on the integer codes keeps rounding noise
+    in a carried c from deciding it).
 
     One visit, one row, group t with codes q, u = q - z, residual r = w - w^ over the whole row:
         p = (A r)_t + s_old A_tt u     (= (A r0)_t with r0 the residual with group t taken out; fixed in the visit)
@@ -602,6 +605,7 @@ def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=
             c = (u * a).sum(axis=1)
             live = c > 0.0
             active = live.copy()
+            nz = (u != 0.0).sum(axis=1)          # codes of the group away from its zero-point
             for scan in range(int(max_scans)):
                 took = np.zeros(n, dtype=bool)
                 aabs = np.abs(u) @ np.abs(Att) if a_tol > 0.0 else None
@@ -609,7 +613,7 @@ def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=
                     done = np.zeros(n, dtype=bool)
                     for d in (1.0, -1.0):
                         qn = Q[:, t * G + j] + d
-                        ok = active & ~done & (qn >= 0.0) & (qn <= qtop)
+                        ok = active & ~done & (qn >= 0.0) & (qn <= qtop) & ~((nz == 1) & (u[:, j] == -d))
                         if not ok.any():
                             continue
                         aj, pj, Ajj = a[:, j], p[:, j], Att[j, j]
@@ -633,6 +637,7 @@ def jointq_refine(W, A, Q, scales, zeros, bits, group_size, grid="asym", n_pass=
                             if key in forced:
                                 acc[i] = bool(forced[key]) and cn[i] > 0.0
                         if acc.any():
+                            nz = nz + np.where(acc, (u[:, j] == 0.0).astype(np.int64) - (u[:, j] + d == 0.0), 0)
                             Q[acc, t * G + j] += d
                             u[acc, j] += d
                             b = np.where(acc, b + d * pj, b)

@@ -11,8 +11,10 @@
 // One visit of group t for one row (u = q - z, a = A_tt u, p = (A r)_t + s_old a, b = u.p, c = u.a, s* = b / c):
 // the move u + d e_j changes b^2 / c by N / c' with
 //     g = p_j - s* a_j,   N = 2 d b g + g^2 + 2 s* g a_j - s*^2 (c A_jj - a_j^2),   c' = c + 2 d a_j + A_jj,
-// and is taken iff N > 0 and c' > 0.  (The last three terms of N equal p_j^2 - s*^2 c A_jj, which is how the kernel
-// forms them; what matters for fp32 is that the small g is computed first and multiplied by the large b.)
+// and is taken iff N > 0 and c' > 0; a move that would leave every code of the group at its zero-point (c' = 0, the
+// scale undefined) is no candidate, which the kernel decides on the codes.  (The last three terms of N equal
+// p_j^2 - s*^2 c A_jj, which is how the kernel forms them; what matters for fp32 is that the small g is computed
+// first and multiplied by the large b.)
 //
 // gfx950 mapping.  The rows are independent and a visit only needs the row's gradient restricted to the group,
 // (A r)_t, so the whole layer moves through the groups together:
@@ -238,7 +240,8 @@ struct VisitArgs {
     const float* Am;           // column-normalized a = (A_gg + lam I) u of the group, kept current
     const float* P;            // p of the group's columns, fixed during the visit
     float* bc;                 // per row b, c of the visited group
-    int32_t* flags;            // per row: [0] still scanning this visit, [1] took a move in this scan
+    int32_t* flags;            // per row (4 slots): [0] still scanning this visit, [1] took a move in this scan,
+                               // [2] codes of the visited group that differ from its zero-point
     int max_scans;
     int32_t* moves;
 };
@@ -279,7 +282,7 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     float dr_max = 0.f;
     int wave_moves = 0;
     bool run = row < v.d_out;
-    if (WIDE && run && v.flags[2 * row] == 0) {   // the row's visit is over: no change from this block
+    if (WIDE && run && v.flags[4 * row] == 0) {   // the row's visit is over: no change from this block
         run = false;
 #pragma unroll
         for (int c = 0; c < NC; ++c)
@@ -342,6 +345,19 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         cc = wave_sum(cc);
     }
     const bool live = cc > 0.f;
+    // Codes of the group that differ from its zero-point.  The move that would take the last of them there has
+    // c' = 0 exactly and N = 0 from below, so it is never taken; in fp32, with c carried through earlier moves, both
+    // come out as rounding noise of either sign, and once taken the scale b / c is noise over noise.  The count
+    // settles it on the integers.
+    int nnz;
+    if (WIDE) {
+        nnz = v.flags[4 * row + 2];
+    } else {
+        float cnt = 0.f;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) cnt += (has[c] && u[c] != 0.f) ? 1.f : 0.f;
+        nnz = int(wave_sum(cnt));
+    }
     int n_moves = 0;
     if (live) {
         // b / cc to within rounding, in fewer dependent steps than the correctly rounded division
@@ -364,8 +380,9 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
                 const float base = fmaf(p[c], p[c], -bss * ad[c]);
                 const float t1 = twob * gs;
                 const float hc = fmaf(0.5f, ad[c], hcc);    // (c + A_jj) / 2: c' > 0  <=>  hc + d a > 0
-                const bool up = q[c] <= qtop1 && base > -t1 && hc > -a[c];
-                const bool dn = q[c] >= 1.0f && base > t1 && hc > a[c];
+                const bool last = nnz == 1;
+                const bool up = q[c] <= qtop1 && base > -t1 && hc > -a[c] && !(last && u[c] == -1.0f);
+                const bool dn = q[c] >= 1.0f && base > t1 && hc > a[c] && !(last && u[c] == 1.0f);
                 dd[c] = up ? 1.0f : -1.0f;
                 m[c] = __ballot(has[c] && (up || dn));
                 const int lo = j0 - 64 * c;          // columns up to lo (local numbering) are behind
@@ -385,15 +402,18 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
             float arow[NC];
 #pragma unroll
             for (int c = 0; c < NC; ++c) arow[c] = has[c] ? rowj[64 * c] : 0.f;
-            float d, pj, aj, adj;
+            float d, pj, aj, adj, uj;
             if (NC == 1 || j < 64) {
                 d = readlane_f(dd[0], j); pj = readlane_f(p[0], j); aj = readlane_f(a[0], j); adj = readlane_f(ad[0], j);
+                uj = readlane_f(u[0], j);
                 if (lane == j) { u[0] += d; q[0] += d; }
             } else {
                 d = readlane_f(dd[NC - 1], j - 64); pj = readlane_f(p[NC - 1], j - 64);
                 aj = readlane_f(a[NC - 1], j - 64); adj = readlane_f(ad[NC - 1], j - 64);
+                uj = readlane_f(u[NC - 1], j - 64);
                 if (lane == j - 64) { u[NC - 1] += d; q[NC - 1] += d; }
             }
+            nnz += (uj == 0.f ? 1 : 0) - (uj + d == 0.f ? 1 : 0);
             b = fmaf(d, pj, b);
             cc += fmaf(2.0f * d, aj, adj);
             ss = ratio(b, cc);
@@ -419,7 +439,8 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         if (WIDE) {
             v.bc[2 * row] = b;
             v.bc[2 * row + 1] = cc;
-            if (n_moves > 0) v.flags[2 * row + 1] = 1;
+            v.flags[4 * row + 2] = nnz;
+            if (n_moves > 0) v.flags[4 * row + 1] = 1;
         } else {
             v.scales[int64_t(row) * v.n_g + v.t] = s_new;
         }
@@ -473,10 +494,12 @@ __global__ __launch_bounds__(256) void jq_wide_p_kernel(int d_out, int d_in, con
                                                         const float* __restrict__ Am, float* __restrict__ P,
                                                         float* __restrict__ bc, int32_t* __restrict__ flags) {
     __shared__ float rb[256], rc[256];
+    __shared__ int rn[256];
     const int g0 = g * G;
     for (int64_t r = blockIdx.x; r < d_out; r += gridDim.x) {
         const float s_old = scales[r * n_g + g];
         float b = 0.f, c = 0.f;
+        int nz = 0;
         for (int k = threadIdx.x; k < G; k += 256) {
             const int64_t i = r * d_in + g0 + k;
             const float dj = d[g0 + k], a = Am[i] * dj, u = U[i];
@@ -484,17 +507,22 @@ __global__ __launch_bounds__(256) void jq_wide_p_kernel(int d_out, int d_in, con
             P[i] = p;
             b += u * p;
             c += u * a;
+            nz += u != 0.f ? 1 : 0;
         }
-        rb[threadIdx.x] = b; rc[threadIdx.x] = c;
+        rb[threadIdx.x] = b; rc[threadIdx.x] = c; rn[threadIdx.x] = nz;
         __syncthreads();
         for (int w = 128; w > 0; w >>= 1) {
-            if (int(threadIdx.x) < w) { rb[threadIdx.x] += rb[threadIdx.x + w]; rc[threadIdx.x] += rc[threadIdx.x + w]; }
+            if (int(threadIdx.x) < w) {
+                rb[threadIdx.x] += rb[threadIdx.x + w]; rc[threadIdx.x] += rc[threadIdx.x + w];
+                rn[threadIdx.x] += rn[threadIdx.x + w];
+            }
             __syncthreads();
         }
         if (threadIdx.x == 0) {
             bc[2 * r] = rb[0]; bc[2 * r + 1] = rc[0];
-            flags[2 * r] = rc[0] > 0.f ? 1 : 0;
-            flags[2 * r + 1] = 0;
+            flags[4 * r] = rc[0] > 0.f ? 1 : 0;
+            flags[4 * r + 1] = 0;
+            flags[4 * r + 2] = rn[0];
         }
         __syncthreads();
     }
@@ -504,8 +532,8 @@ __global__ __launch_bounds__(256) void jq_wide_p_kernel(int d_out, int d_in, con
 __global__ __launch_bounds__(256) void jq_scan_end_kernel(int d_out, int32_t* __restrict__ flags) {
     const int r = blockIdx.x * 256 + threadIdx.x;
     if (r >= d_out) return;
-    if (flags[2 * r + 1] == 0) flags[2 * r] = 0;
-    flags[2 * r + 1] = 0;
+    if (flags[4 * r + 1] == 0) flags[4 * r] = 0;
+    flags[4 * r + 1] = 0;
 }
 
 // end of a visit: s = b / c; U <- change of the residual s_old u_old - s_new u_new; max |dR d|
@@ -550,7 +578,7 @@ struct JqWs {
     float* Am;        // d_out x d_in: column-normalized a of the visited group
     float* P;         // d_out x d_in: p of the visited group
     float* bc;        // d_out x 2
-    int32_t* flags;   // d_out x 2
+    int32_t* flags;   // d_out x 4
 };
 
 int64_t rows_d(int64_t d_in) { return d_in + 32 > JQ_NEAR0 + 160 ? d_in + 32 : JQ_NEAR0 + 160; }
@@ -600,7 +628,8 @@ onecomp_status split_left_operand(const float* src, int64_t ld_src, int64_t d_ou
 
 size_t jointq_workspace_bytes(int64_t d_out, int64_t d_in, int group_size) {
     const int64_t ldD = split_update_ld(d_out);
-    const size_t wide = group_size > 128 ? 2 * align_up(size_t(d_out) * d_in * 4, 256) + 2 * align_up(size_t(d_out) * 8, 256)
+    const size_t wide = group_size > 128 ? 2 * align_up(size_t(d_out) * d_in * 4, 256) + align_up(size_t(d_out) * 8, 256) +
+                                               align_up(size_t(d_out) * 16, 256)
                                          : 0;
     return 2 * align_up(size_t(d_out) * d_in * 4, 256) + 2 * align_up(size_t(d_in + 32) * d_in * 2, 256) +
            2 * align_up(size_t(rows_d(d_in)) * ldD * 2, 256) + align_up(size_t(d_out) * JQ_SBW * 4, 256) +

@@ -149,6 +149,18 @@ def test_jointq_smallest_shapes(bits, G, d_out, d_in, act, lam):
     _run(*r[:6], bits, G, lam=lam, n_pass=2, max_scans=3, perm=perm)
 
 
+def test_jointq_group_with_one_code_left_is_not_emptied():
+    """2-bit symmetric grid, groups of 16: one row reaches a group with a single code away from the zero-point.  The
+    move that would empty it has c' = 0 and N = 0 in exact arithmetic and rounding noise in fp32; it is no candidate
+    (decided on the codes), so codes AND the number of moves equal the oracle's (the kernel once took the move and
+    took it back in the next scan: same codes, two moves more)."""
+    bits, G, d_out, d_in = 2, 16, 64, 768
+    _announce(f"jointq b{bits} g{G} {d_out}x{d_in}: a group with one code left")
+    W, Wd, H32, Q0, S0, Z0 = _start(d_out, d_in, bits, G, seed=339, dtype=torch.bfloat16, grid="sym", start="rtn")
+    out, st = _run(W, Wd, H32, Q0, S0, Z0, bits, G, grid="sym", n_pass=2, max_scans=2)
+    assert st["flips"] == 0 and int(out["n_moves"].item()) == int(st["oracle"]["moves"].sum())
+
+
 def test_jointq_degenerate_rows_and_zero_passes():
     _announce("jointq: all-zero group, codes at the zero-point; n_pass = 0 returns the start")
     W, Wd, H32, Q0, S0, Z0 = _start(8, 256, 4, 64, seed=77)

@@ -268,3 +268,35 @@ def test_listing_tolerances_only_list_and_forcing_a_listed_decision_changes_only
         assert flip["Q"][0, col] != base["Q"][0, col]                    # and that decision does
         same = oc.jointq_refine(W, H, Q, s, z, rows=[i], forced={(0,) + key: taken}, **kw1, **tol)
         assert np.array_equal(same["Q"], base["Q"]) and np.array_equal(same["scales"], base["scales"])
+
+
+def test_no_move_empties_a_group():
+    """A group may not be brought to 'every code at its zero-point' (c' = 0: the refit scale is undefined there and the
+    gain reaches 0 from below).  Checked where floating point alone would not settle it: a group with a single code
+    away from the zero-point, reached after other moves so that c is a carried sum.  The emptying move is no candidate
+    (not even a listed toss-up, and it cannot be forced), the group stays alive, and by the definition the objective
+    with the group emptied is indeed no better than what the search returns."""
+    rng = np.random.default_rng(3)
+    d_in, G, bits = 8, 4, 2
+    X = rng.standard_normal((40, d_in))
+    X[:, 1:] += 0.7 * X[:, :-1]
+    H = oc.hessian_accumulate(X)
+    z = np.ones((1, 2))                                   # symmetric 2-bit grid: codes 0..2 around the zero-point 1
+    s = np.full((1, 2), 0.05)
+    # group 0 wants a single small weight on column 2; it starts with two codes away from the zero-point, so the
+    # search first takes one of them back (c becomes a carried sum), and is then one move from emptying the group
+    W = np.array([[0.0, 0.0, 0.004, 0.0, 0.05, -0.05, 0.05, 0.0]])
+    Q = np.array([[1, 2, 2, 1, 2, 0, 2, 1]])
+    o = oc.jointq_refine(W, H, Q, s, z, bits, G, grid="sym", n_pass=1, max_scans=6, tie_tol=1e-3, g_tol=1e-3)
+    u0 = o["Q"][0, :G] - 1
+    assert np.count_nonzero(u0) == 1                      # the search did reach the single-code state
+    j = int(np.nonzero(u0)[0][0])
+    d_empty = -int(u0[j])
+    assert not any(t[1] == 0 and t[3] == j and t[4] == d_empty for t in o["ties"][0])
+    forced = {(0, 0, 0, sc, j, d_empty): True for sc in range(6)}
+    o2 = oc.jointq_refine(W, H, Q, s, z, bits, G, grid="sym", n_pass=1, max_scans=6, forced=forced)
+    assert np.array_equal(o2["Q"], o["Q"]) and np.array_equal(o2["moves"], o["moves"])
+    # by the definition: emptying the group does not lower the objective
+    w_hat_empty = o["W_hat"].copy()
+    w_hat_empty[0, :G] = 0.0
+    assert oc.row_objective(W, w_hat_empty, H)[0] >= o["f1"][0]
