@@ -154,7 +154,9 @@ def compare_jointq(gpu_Q, gpu_S, W, A, Q0, S0, Z, bits, G, grid="asym", n_pass=1
     first column that differs names the decision, which must be a listed toss-up and is then forced to the GPU's
     (the replay of the sweep's protocol).  Otherwise the decisions are not observable: the oracle is rerun with one
     listed toss-up flipped at a time, and a flip is kept when the rows then agree over more leading groups or, with
-    that unchanged, in more codes; up to max_flips flips.
+    that unchanged, in more codes; up to max_flips flips.  Where no single flip helps, a depth-first search over the
+    listed toss-ups of the first differing group follows (a flipped toss-up tends to return as a toss-up of the same
+    column in the next scan, so the right replay can be a chain of flips none of which helps alone).
     Returns dict(clean_rows, flipped_rows, flips, real_mismatches, oracle)."""
     W = np.asarray(W, dtype=np.float64)
     A = np.asarray(A, dtype=np.float64)
@@ -202,20 +204,53 @@ def compare_jointq(gpu_Q, gpu_S, W, A, Q0, S0, Z, bits, G, grid="asym", n_pass=1
                 forced, cur = f2, run1(i, f2)
                 flips += 1
                 continue
+            # greedy: one listed toss-up flipped at a time, kept when the rows then agree over more leading groups
+            # or, with that unchanged, in more codes
             ham = int((cur["Q"][0] != gq[i]).sum())
-            cands = [k for k in listed if (0,) + k not in forced and (n_pass > 1 or k[1] == pre)]
             best = None
-            for k in cands[:max_tries]:
+            for k in [k for k in listed if (0,) + k not in forced and (n_pass > 1 or k[1] == pre)][:max_tries]:
                 f2 = dict(forced)
                 f2[(0,) + k] = not listed[k]
                 trial = run1(i, f2)
                 score = (_jq_prefix(trial, 0, gq[i], gs[i], G, n_g, pv), -int((trial["Q"][0] != gq[i]).sum()))
                 if score > (pre, -ham) and (best is None or score > best[0]):
                     best = (score, f2, trial)
-            if best is None:
-                break
-            _, forced, cur = best
-            flips += 1
+            if best is not None:
+                _, forced, cur = best
+                flips += 1
+                continue
+            # No single flip helps.  A toss-up flipped in one scan usually comes back as a new toss-up of the same
+            # column in the next scan, so the right replay can be a chain of flips none of which helps alone:
+            # depth-first over the listed toss-ups of the first differing group (of any pass), a branch followed
+            # while that group does not move backwards, up to max_flips flips deep and 4 max_tries oracle runs.
+            budget = [max_tries * 4]
+
+            def dfs(f, c, depth):
+                pre_c = _jq_prefix(c, 0, gq[i], gs[i], G, n_g, pv)
+                if pre_c == n_g:
+                    return f, c, depth
+                if depth >= max_flips:
+                    return None
+                now = {t[:5]: t[5] for t in c["ties"][0]}
+                for k in [k for k in now if k[1] == pre_c and (0,) + k not in f]:
+                    if budget[0] <= 0:
+                        return None
+                    budget[0] -= 1
+                    f2 = dict(f)
+                    f2[(0,) + k] = not now[k]
+                    trial = run1(i, f2)
+                    if _jq_prefix(trial, 0, gq[i], gs[i], G, n_g, pv) < pre_c:
+                        continue
+                    got = dfs(f2, trial, depth + 1)
+                    if got is not None:
+                        return got
+                return None
+
+            got = dfs(forced, cur, 0)
+            if got is not None:
+                forced, cur, n = got
+                flips += n
+            break
         ok = ok or _jq_prefix(cur, 0, gq[i], gs[i], G, n_g, pv) == n_g
         if ok:
             flipped += 1

@@ -70,8 +70,14 @@ def _run(W, Wd, H32, Q0, S0, Z0, bits, G, grid="asym", lam=0.0, n_pass=1, max_sc
     assert obj[1] <= obj[0]
     f_gpu = oc.row_objective(Wd, wh.astype(np.float64), A)     # the objective of the GPU's result, by definition
     assert abs(f_gpu.sum() - obj[1]) <= 1e-3 * obj[1]
-    if st["flips"] == 0:
-        assert int(out["n_moves"].item()) == int(orc["moves"].sum())
+    # Moves: equal to the oracle's, except that a listed toss-up taken the other way is often undone in the next
+    # scan, which leaves the codes alone and changes the count by two.  With equal codes the difference is even, and
+    # it is bounded by what the listed toss-ups (of the run before any replay) can account for.
+    n_listed = sum(len(t) for t in orc["ties"])
+    d_moves = int(out["n_moves"].item()) - int(orc["moves"].sum())
+    assert d_moves % 2 == 0 and abs(d_moves) <= 2 * (n_listed + st["flips"])
+    if n_listed == 0:
+        assert d_moves == 0
     limit = max(2, d_out // 10) if max_bad_rows is None else max_bad_rows
     assert st["flipped_rows"] <= limit
     return out, st
