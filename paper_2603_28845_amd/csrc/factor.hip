@@ -144,8 +144,7 @@ constexpr int SBW = 16;      // sub-block width
 constexpr int SBP = SBW + 1;
 constexpr int SBS = SBW * SBP;
 constexpr int NSB = NB / SBW;
-// sub-blocks + one 16 x 16 buffer for the leaf inverse + NB reciprocal diagonal entries
-constexpr int POTRF_LDS_DOUBLES = NSB * (NSB + 1) / 2 * SBS + SBS + NB;
+constexpr int POTRF_LDS_DOUBLES = NSB * (NSB + 1) / 2 * SBS;   // the lower sub-blocks
 __device__ __forceinline__ int tri(int r, int c) {   // element (r, c), c / 16 <= r / 16
     const int rb = r >> 4, cb = c >> 4;
     return ((rb * (rb + 1)) / 2 + cb) * SBS + (r & 15) * SBP + (c & 15);
@@ -214,8 +213,6 @@ __device__ __forceinline__ void tri_inverse16(const double (&r)[SBW], const doub
 // already in S and a barrier has been passed.
 __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __restrict__ V, int n, int off, int bs,
                                            int32_t* __restrict__ info, double* S, bool preloaded) {
-    double* Tb = S + NSB * (NSB + 1) / 2 * SBS;   // leaf inverse of the current block column
-    double* dinv = Tb + SBS;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, lk = lane >> 4;
@@ -248,52 +245,69 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
     };
 
     // ---------------- Cholesky, 8 block columns of 16 ----------------
-#pragma unroll 1
-    for (int J = 0; J < NSB; ++J) {
+    // Leaf of block column J: wave 0 factors the diagonal sub-block in registers (lane i (mod 16) = row i; lanes
+    // 16..63 shadow lanes 0..15) and leaves its INVERSE in the sub-block's place: the panel solves below and the
+    // inversion of the whole block need T = L_JJ^-1, nothing reads L_JJ itself.
+    auto leaf = [&](int J) __attribute__((always_inline)) {
         double* DJ = S + sub(J, J);
-        // leaf: wave 0, lane i (mod 16) = row i of the sub-block, held in registers; lanes 16..63 shadow
-        // lanes 0..15 and store nothing.
-        if (wave == 0) {
-            const int i = l16;
-            // Entries above the diagonal (c > i) are carried along unmasked: they never reach a valid entry (a
-            // broadcast of column j takes lane c >= j) and are zeroed when the sub-block is stored.  The first bad
-            // pivot is remembered in a register, so the 16 steps form one straight-line block.
-            double r[SBW];
-            double my_dinv = 1.0;
-            int bad_at = -1;
+        const int i = l16;
+        // Entries above the diagonal (c > i) are carried along unmasked: they never reach a valid entry (a
+        // broadcast of column j takes lane c >= j).  The first bad pivot is remembered in a register, so the 16
+        // steps form one straight-line block.
+        double r[SBW];
+        double my_dinv = 1.0;
+        int bad_at = -1;
 #pragma unroll
-            for (int c = 0; c < SBW; ++c) r[c] = DJ[i * SBP + c];
-            static_for<0, SBW>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                double p = bcast16<j>(r[j]);           // pivot, the same in every lane
-                const bool bad = !(p > 0.0);
-                if (bad) p = 1.0;
-                bad_at = (bad && bad_at < 0) ? j : bad_at;
-                const double ri = rsqrt_refined(p);
-                double sq = p * ri;
-                sq = __builtin_fma(0.5 * ri, __builtin_fma(-sq, sq, p), sq);
-                const double lij = (i == j) ? sq : r[j] * ri;   // column j on and below the pivot
-                r[j] = lij;
-                if (i == j) my_dinv = ri;
-                static_for<j + 1, SBW>([&](auto cc) {
-                    constexpr int c = decltype(cc)::value;
-                    const double lcj = bcast16<c>(lij);
-                    r[c] = __builtin_fma(-lij, lcj, r[c]);
-                });
+        for (int c = 0; c < SBW; ++c) r[c] = DJ[i * SBP + c];
+        static_for<0, SBW>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            double p = bcast16<j>(r[j]);           // pivot, the same in every lane
+            const bool bad = !(p > 0.0);
+            if (bad) p = 1.0;
+            bad_at = (bad && bad_at < 0) ? j : bad_at;
+            const double ri = rsqrt_refined(p);
+            double sq = p * ri;
+            sq = __builtin_fma(0.5 * ri, __builtin_fma(-sq, sq, p), sq);
+            const double lij = (i == j) ? sq : r[j] * ri;   // column j on and below the pivot
+            r[j] = lij;
+            if (i == j) my_dinv = ri;
+            static_for<j + 1, SBW>([&](auto cc) {
+                constexpr int c = decltype(cc)::value;
+                const double lcj = bcast16<c>(lij);
+                r[c] = __builtin_fma(-lij, lcj, r[c]);
             });
-            if (bad_at >= 0 && tid == 0 && *info == 0) *info = off + J * SBW + bad_at + 1;
-            // T = L_JJ^-1 from the rows still in registers (all four 16-lane rows hold them)
-            double x[4];
-            tri_inverse16(r, my_dinv, i, lk, x);
+        });
+        if (bad_at >= 0 && tid == 0 && *info == 0) *info = off + J * SBW + bad_at + 1;
+        // T = L_JJ^-1 from the rows still in registers (all four 16-lane rows hold them); every lane has read its
+        // row before any lane overwrites the sub-block (one wave: program order); zeros above the diagonal
+        double x[4];
+        tri_inverse16(r, my_dinv, i, lk, x);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) Tb[i * SBP + 4 * k + lk] = x[k];
-            if (tid < SBW) {
-                dinv[J * SBW + i] = my_dinv;
+        for (int k = 0; k < 4; ++k) DJ[i * SBP + 4 * k + lk] = x[k];
+    };
+    // A_IK -= L_IJ L_KJ^T for the pair p of the sub-blocks below J (row-major over the triangle, kk <= ii)
+    auto update_pair = [&](int J, int p) __attribute__((always_inline)) {
+        int ii = 0;
+        while ((ii + 1) * (ii + 2) / 2 <= p) ++ii;
+        const int kk = p - ii * (ii + 1) / 2;
+        const int I = J + 1 + ii, K = J + 1 + kk;
+        double* M = S + sub(I, K);
+        const double* LI = S + sub(I, J);
+        const double* LK = S + sub(K, J);
+        double4v c = load_c(M);
 #pragma unroll
-                for (int c = 0; c < SBW; ++c) DJ[i * SBP + c] = (c <= i) ? r[c] : 0.0;   // zeros above the diagonal
-            }
-        }
-        __syncthreads();
+        for (int q = 0; q < 4; ++q)
+            c = __builtin_amdgcn_mfma_f64_16x16x4f64(-frag_rowk(LI, q), frag_rowk(LK, q), c, 0, 0, 0);
+        store_c(M, c);
+    };
+    // The leaves are a chain of latencies on one wave (16 dependent pivots each, then the 16 x 16 inverse), so the
+    // next leaf runs beside the update it does not depend on: after the panel solve of column J, wave 0 updates the
+    // next diagonal sub-block alone and factors it at once, while the other three waves update the rest.
+    if (wave == 0) leaf(0);
+    __syncthreads();
+#pragma unroll 1
+    for (int J = 0; J < NSB - 1; ++J) {
+        const double* TJ = S + sub(J, J);
         // L_IJ = A_IJ T^T for I > J (in place: the wave holds A_IJ's fragments before it writes)
         for (int I = J + 1 + wave; I < NSB; I += 4) {
             double* M = S + sub(I, J);
@@ -302,29 +316,17 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
             for (int q = 0; q < 4; ++q) a[q] = frag_rowk(M, q);
             double4v c = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-            for (int q = 0; q < 4; ++q) c = __builtin_amdgcn_mfma_f64_16x16x4f64(a[q], frag_rowk(Tb, q), c, 0, 0, 0);
+            for (int q = 0; q < 4; ++q) c = __builtin_amdgcn_mfma_f64_16x16x4f64(a[q], frag_rowk(TJ, q), c, 0, 0, 0);
             store_c(M, c);
         }
         __syncthreads();
-        // A_IK -= L_IJ L_KJ^T for J < K <= I
-        {
-            const int nr = NSB - 1 - J;                 // sub-block rows below J
-            const int np = nr * (nr + 1) / 2;
-            for (int p = wave; p < np; p += 4) {
-                // p -> (ii, kk), kk <= ii < nr, row-major over the triangle
-                int ii = 0;
-                while ((ii + 1) * (ii + 2) / 2 <= p) ++ii;
-                const int kk = p - ii * (ii + 1) / 2;
-                const int I = J + 1 + ii, K = J + 1 + kk;
-                double* M = S + sub(I, K);
-                const double* LI = S + sub(I, J);
-                const double* LK = S + sub(K, J);
-                double4v c = load_c(M);
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    c = __builtin_amdgcn_mfma_f64_16x16x4f64(-frag_rowk(LI, q), frag_rowk(LK, q), c, 0, 0, 0);
-                store_c(M, c);
-            }
+        const int nr = NSB - 1 - J;                 // sub-block rows below J
+        const int np = nr * (nr + 1) / 2;
+        if (wave == 0) {
+            update_pair(J, 0);                      // the next diagonal sub-block
+            leaf(J + 1);
+        } else {
+            for (int p = wave; p < np; p += 3) update_pair(J, p);
         }
         __syncthreads();
     }
@@ -334,22 +336,7 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
     (void)A;
 
     // ---------------- X = L^-1 in place ----------------
-    // leaf inverses of the diagonal sub-blocks: thread t < 128 solves column t % 16 of sub-block t / 16
-    // (two sub-blocks per wave, in registers: every lane reads row l % 16 and writes back its four columns)
-    __syncthreads();   // the write-out above has read every sub-block
-#pragma unroll 1
-    for (int h = 0; h < 2; ++h) {
-        const int Jb = 2 * wave + h, i = l16;
-        double* DJ = S + sub(Jb, Jb);
-        double r[SBW], x[4];
-#pragma unroll
-        for (int c = 0; c < SBW; ++c) r[c] = DJ[i * SBP + c];
-        tri_inverse16(r, dinv[Jb * SBW + i], i, lk, x);
-        // all lanes of the wave have read the sub-block before any of them overwrites it (one wave: program order)
-#pragma unroll
-        for (int k = 0; k < 4; ++k) DJ[i * SBP + 4 * k + lk] = x[k];   // zeros above the diagonal
-    }
-    __syncthreads();
+    // the diagonal sub-blocks hold their inverses already
     // recursive doubling: ns = sub-blocks per side of a pair
     static_for<0, 3>([&](auto lc) {
         constexpr int ns = 1 << decltype(lc)::value;     // 1, 2, 4
