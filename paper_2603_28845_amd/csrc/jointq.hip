@@ -348,16 +348,17 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
     // Codes of the group that differ from its zero-point.  The move that would take the last of them there has
     // c' = 0 exactly and N = 0 from below, so it is never taken; in fp32, with c carried through earlier moves, both
     // come out as rounding noise of either sign, and once taken the scale b / c is noise over noise.  The count
-    // settles it on the integers.
-    int nnz;
-    if (WIDE) {
-        nnz = v.flags[4 * row + 2];
-    } else {
-        float cnt = 0.f;
+    // settles it on the integers: ballots of u != 0 plus, for a group wider than a block, the count in its other
+    // blocks.  A move changes the count by at most one, so after a count of n the next n - 2 moves cannot meet the
+    // case and run without the check (the kernel is bound by its instruction count, and groups with one or two such
+    // codes are rare).
+    auto count_here = [&]() __attribute__((always_inline)) {
+        int n = 0;
 #pragma unroll
-        for (int c = 0; c < NC; ++c) cnt += (has[c] && u[c] != 0.f) ? 1.f : 0.f;
-        nnz = int(wave_sum(cnt));
-    }
+        for (int c = 0; c < NC; ++c) n += __builtin_popcountll(__ballot(has[c] && u[c] != 0.f));
+        return n;
+    };
+    const int nnz_other = WIDE ? v.flags[4 * row + 2] - count_here() : 0;
     int n_moves = 0;
     if (live) {
         // b / cc to within rounding, in fewer dependent steps than the correctly rounded division
@@ -368,10 +369,24 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         };
         float ss = ratio(b, cc);
         int scan = 0, j0 = -1;   // j0: the column of the last move taken in this scan
+        int unchecked = 0;       // moves that may still be taken before the codes are counted again
+        float qup[NC], qdn[NC];  // a lane may go up from codes <= qup, down from codes >= qdn
         bool took = false;
         for (;;) {
             // N = 2 d b g + (p^2 - s*^2 c A_jj): the bracket is the expanded form's g^2 + 2 s* g a - s*^2 (c A_jj - a^2)
             const float twob = 2.0f * b, bss = b * ss, hcc = 0.5f * cc, qtop1 = v.qtop - 1.0f;
+            if (unchecked <= 0) {
+                // the guard lives in the per-lane code bounds of the two directions, which the step compares
+                // anyway: with one code left, its lane may not move towards the zero-point
+                const int n = nnz_other + count_here();
+                const bool last = n == 1;
+                unchecked = n - 2;
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    qup[c] = (last && u[c] == -1.0f) ? -1.0f : qtop1;
+                    qdn[c] = (last && u[c] == 1.0f) ? 3.0e38f : 1.0f;
+                }
+            }
             uint64_t m[NC];
             float dd[NC];
 #pragma unroll
@@ -380,9 +395,8 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
                 const float base = fmaf(p[c], p[c], -bss * ad[c]);
                 const float t1 = twob * gs;
                 const float hc = fmaf(0.5f, ad[c], hcc);    // (c + A_jj) / 2: c' > 0  <=>  hc + d a > 0
-                const bool last = nnz == 1;
-                const bool up = q[c] <= qtop1 && base > -t1 && hc > -a[c] && !(last && u[c] == -1.0f);
-                const bool dn = q[c] >= 1.0f && base > t1 && hc > a[c] && !(last && u[c] == 1.0f);
+                const bool up = q[c] <= qup[c] && base > -t1 && hc > -a[c];
+                const bool dn = q[c] >= qdn[c] && base > t1 && hc > a[c];
                 dd[c] = up ? 1.0f : -1.0f;
                 m[c] = __ballot(has[c] && (up || dn));
                 const int lo = j0 - 64 * c;          // columns up to lo (local numbering) are behind
@@ -402,18 +416,15 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
             float arow[NC];
 #pragma unroll
             for (int c = 0; c < NC; ++c) arow[c] = has[c] ? rowj[64 * c] : 0.f;
-            float d, pj, aj, adj, uj;
+            float d, pj, aj, adj;
             if (NC == 1 || j < 64) {
                 d = readlane_f(dd[0], j); pj = readlane_f(p[0], j); aj = readlane_f(a[0], j); adj = readlane_f(ad[0], j);
-                uj = readlane_f(u[0], j);
                 if (lane == j) { u[0] += d; q[0] += d; }
             } else {
                 d = readlane_f(dd[NC - 1], j - 64); pj = readlane_f(p[NC - 1], j - 64);
                 aj = readlane_f(a[NC - 1], j - 64); adj = readlane_f(ad[NC - 1], j - 64);
-                uj = readlane_f(u[NC - 1], j - 64);
                 if (lane == j - 64) { u[NC - 1] += d; q[NC - 1] += d; }
             }
-            nnz += (uj == 0.f ? 1 : 0) - (uj + d == 0.f ? 1 : 0);
             b = fmaf(d, pj, b);
             cc += fmaf(2.0f * d, aj, adj);
             ss = ratio(b, cc);
@@ -422,9 +433,11 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
             took = true;
             j0 = j;
             ++n_moves;
+            --unchecked;
         }
     }
     const float s_new = live ? b / cc : s_old;
+    const int nnz_here = WIDE ? count_here() : 0;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         if (!has[c]) continue;
@@ -439,7 +452,7 @@ __global__ __launch_bounds__(64 * JQ_ROWS) void jq_visit_kernel(VisitArgs v) {
         if (WIDE) {
             v.bc[2 * row] = b;
             v.bc[2 * row + 1] = cc;
-            v.flags[4 * row + 2] = nnz;
+            v.flags[4 * row + 2] = nnz_other + nnz_here;
             if (n_moves > 0) v.flags[4 * row + 1] = 1;
         } else {
             v.scales[int64_t(row) * v.n_g + v.t] = s_new;
