@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # L2 <-> fabric bytes per call from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a plain 4 GiB copy), taken with
 # `python bench.py --phase gram|sweep` under rocprofv3 --pmc; see profiles/c3b_hbm_traffic_pmc.md for the commands
-GRAM_TRAFFIC_C3B = 185.0e9    # 183.7 GB fetched + 1.2 GB written per accumulate call (384 x 256 tiles; 100-187 GB from run to run)
+GRAM_TRAFFIC_C3B = 185.0e9    # 183.7 GB fetched + 1.2 GB written per accumulate call (384 x 256 tiles; 100-191 GB from run to run)
 SWEEP_TRAFFIC_C3B = 13.6e9
 
 
