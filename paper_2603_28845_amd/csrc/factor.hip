@@ -128,12 +128,13 @@ __global__ __launch_bounds__(256) void output_block_kernel(const double* __restr
 // factor L_kk of the block itself stays in LDS (nothing downstream reads it).  A non-positive pivot sets *info (first one wins) and is replaced by 1.
 //
 // The block lives in LDS as 16 x 16 sub-blocks (only those on and below the diagonal, 36 of them, row pitch 17
-// doubles, 78 KB: small enough for two workgroups per CU, so the factorization can share a launch with GEMM
+// doubles, 76.5 KB: small enough for two workgroups per CU, so the factorization can share a launch with GEMM
 // tiles).  Everything but the 16 x 16 leaves runs on v_mfma_f64_16x16x4_f64 with sub-blocks as operands:
-//   Cholesky, block column J:  leaf factorization of (J,J) by one wave in registers (pivot and column
-//     broadcasts by DPP row_newbcast, square roots from v_rsq_f64 + two Newton steps);  T = L_JJ^-1 (one thread
-//     per column);  L_IJ = A_IJ T^T for the sub-blocks below;  A_IK -= L_IJ L_KJ^T for J < K <= I.
-//   Inverse:  leaf inverses of the 8 diagonal sub-blocks, then recursive doubling over aligned pairs of
+//   Cholesky, block column J:  leaf factorization of (J,J) by wave 0 in registers (pivot and column broadcasts
+//     by DPP row_newbcast, reciprocal square roots from v_rsq_f64 + a Newton step), which leaves T = L_JJ^-1 in the
+//     sub-block's place;  L_IJ = A_IJ T^T for the sub-blocks below;  A_IK -= L_IJ L_KJ^T for J < K <= I, of which
+//     wave 0 takes (J+1, J+1) alone and goes straight on to the next leaf while the other waves do the rest.
+//   Inverse:  the diagonal sub-blocks hold their inverses already; recursive doubling over aligned pairs of
 //     s = 16, 32, 64:  X[C,A] = -X[C,C] (L[C,A] X[A,A]), both products in place: the first by sub-block rows
 //     (a wave holds its row of L[C,A] in registers while it overwrites it), the second by sub-block columns.
 //     Every level has exactly four row / column tasks: one per wave.
