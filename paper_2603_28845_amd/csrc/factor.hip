@@ -624,6 +624,135 @@ __device__ __forceinline__ void dgemm_tile_ring(const GemmArgs& g, const int tn,
     }
 }
 
+// Tile (0, 0) of a trailing update C -= P P^T whose first tile lies on the diagonal: the tile the next diagonal block
+// is waiting for.  Its workgroup is the first of the launch and what counts is how soon it is done, not throughput.
+// A 128 x 128 x 128 tile is 512 fp64 MFMAs per wave, 64 cycles each: 17 us on a CU to itself, twice that next to a
+// second workgroup.  Only the 36 sub-blocks of 16 x 16 on and below the diagonal are needed (potrf_body takes
+// nothing else), so wave w computes the sub-block rows w and 7 - w: (w + 1) + (8 - w) = 9 sub-blocks each instead
+// of 16.  Both operands are the same 128 rows, so a stage holds that one 8 KB part only and the same LDS takes a
+// ring of eight slots.  Every sub-block sees the MFMAs of dgemm_tile_ring<true, 4> in the same order: bit-equal
+// results.  The updated tile goes, as lower 16 x 16 sub-blocks (identity beyond the matrix edge), to the LDS layout
+// of potrf_body and nowhere else: the block column it heads is finished with this step and nothing reads the tile
+// from C again.
+constexpr int DNS = 2 * RNS;   // slots of the diagonal tile's ring
+static_assert(DNS * R_PART_BYTES <= LDS_DOUBLES * 8, "the diagonal tile's ring fits into the workgroup's LDS");
+template <int W>
+__device__ __forceinline__ void dgemm_diag_tile_wave(const GemmArgs& g, double* lds) {
+    constexpr int NW = 4, LPW = 2;           // waves; 1 KB loads per wave and stage
+    constexpr int RA = W, RB = 7 - W;        // this wave's sub-block rows; row R needs the sub-block columns 0 .. R
+    constexpr int NB_COLS = RB + 1;          // operand fragments of the second kind: sub-block columns 0 .. RB
+    const int m = g.m_last, nc = g.n;        // rows and columns of C that exist (the last block may be short)
+    const int n_st = g.k_last / RK;
+    const double* __restrict__ A = g.A;
+    const double* __restrict__ C = g.C;
+    const int lane = threadIdx.x & 63;
+    const int l16 = lane & 15, lk = lane >> 4;
+    const uint32_t lds0 = uint32_t(uintptr_t((ONECOMP_LDS char*)lds));
+    uint32_t voff[LPW], ldst[LPW];
+#pragma unroll
+    for (int q = 0; q < LPW; ++q) {
+        const int j = W + NW * q;               // load 0 .. 7 of the stage: rows 16 j .. 16 j + 15
+        const int row = 16 * j + (lane >> 2);
+        const int c = (lane & 3) ^ ((row >> 2) & 3);
+        voff[q] = (row < m) ? uint32_t((int64_t(row) * g.lda + 2 * c) * 8) : LDS_DMA_OOB;
+        ldst[q] = j * 1024;
+    }
+    auto issue = [&](int st) __attribute__((always_inline)) {   // loads of stage st into its slot; past the end: zeros
+        const uint32_t slot = lds0 + uint32_t(st % DNS) * R_PART_BYTES;
+        const bool live = st < n_st;
+        const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<double*>(A + (live ? int64_t(st) : 0) * RK), 0, 0x7FFFFFFF, 0x00020000);
+#pragma unroll
+        for (int q = 0; q < LPW; ++q) lds_load16(slot + ldst[q], live ? voff[q] : LDS_DMA_OOB, ra);
+    };
+    for (int st = 0; st < DNS - 1; ++st) issue(st);
+
+    // accumulators start as (beta / alpha) C (alpha = +-1: exact); register r of lane l: row 4 r + l / 16,
+    // column l % 16 of its sub-block
+    const double binit = g.beta * g.alpha;
+    double4v accA[RA + 1], accB[RB + 1];
+    const bool full = m >= GT && nc >= GT;
+    auto init = [&](double4v& acc, int R, int c, auto whole) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = R * 16 + 4 * r + lk, col = c * 16 + l16;
+            if constexpr (decltype(whole)::value) {   // unconditional loads: all in flight together
+                acc[r] = binit * C[int64_t(row) * g.ldc + col];
+            } else {
+                double v = 0.0;
+                if (row < m && col < nc) v = binit * C[int64_t(row) * g.ldc + col];
+                acc[r] = v;
+            }
+        }
+    };
+    if (full) {
+#pragma unroll
+        for (int c = 0; c <= RA; ++c) init(accA[c], RA, c, std::true_type{});
+#pragma unroll
+        for (int c = 0; c <= RB; ++c) init(accB[c], RB, c, std::true_type{});
+    } else {
+#pragma unroll
+        for (int c = 0; c <= RA; ++c) init(accA[c], RA, c, std::false_type{});
+#pragma unroll
+        for (int c = 0; c <= RB; ++c) init(accB[c], RB, c, std::false_type{});
+    }
+
+    // fragment addresses inside a stage (bytes), inner steps 0 .. 3; steps 4 .. 7: ^ 32
+    auto frag = [&](int sb) __attribute__((always_inline)) {
+        const int row = sb * 16 + l16;
+        return row * 64 + (((lk >> 1) ^ ((row >> 2) & 3)) << 4) + (lk & 1) * 8;
+    };
+    int fr[NB_COLS];
+#pragma unroll
+    for (int c = 0; c < NB_COLS; ++c) fr[c] = frag(c);
+    const int faA = frag(RA), faB = frag(RB);
+    const char* ldsc = reinterpret_cast<const char*>(lds);
+    for (int st = 0; st < n_st; ++st) {
+        __builtin_amdgcn_s_waitcnt(wait_vmcnt(LPW * (DNS - 2)));   // stage st has landed
+        __syncthreads();
+        issue(st + DNS - 1);                                        // into the slot every wave has finished reading
+        const char* sp = ldsc + (st % DNS) * R_PART_BYTES;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            double b[NB_COLS];
+#pragma unroll
+            for (int c = 0; c < NB_COLS; ++c) b[c] = *reinterpret_cast<const double*>(sp + (h ? fr[c] ^ 32 : fr[c]));
+            const double aA = *reinterpret_cast<const double*>(sp + (h ? faA ^ 32 : faA));
+            const double aB = *reinterpret_cast<const double*>(sp + (h ? faB ^ 32 : faB));
+#pragma unroll
+            for (int c = 0; c <= RB; ++c) {
+                accB[c] = __builtin_amdgcn_mfma_f64_16x16x4f64(aB, b[c], accB[c], 0, 0, 0);
+                if (c <= RA) accA[c] = __builtin_amdgcn_mfma_f64_16x16x4f64(aA, b[c], accA[c], 0, 0, 0);
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(wait_vmcnt(0));   // no LDS write may be in flight when the slots are reused
+    __syncthreads();   // every wave is done with the last stage before the operand slots are overwritten
+    const double aout = g.alpha;
+    auto put = [&](const double4v& acc, int R, int c) __attribute__((always_inline)) {
+        double* M = lds + sub(R, c);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int lrow = R * 16 + 4 * r + lk, lcol = c * 16 + l16;
+            const bool inside = full || ((lrow < m) && (lcol < nc));
+            M[(4 * r + lk) * SBP + l16] = inside ? aout * acc[r] : (lrow == lcol ? 1.0 : 0.0);
+        }
+    };
+#pragma unroll
+    for (int c = 0; c <= RA; ++c) put(accA[c], RA, c);
+#pragma unroll
+    for (int c = 0; c <= RB; ++c) put(accB[c], RB, c);
+}
+__device__ __forceinline__ void dgemm_diag_tile(const GemmArgs& g) {
+    double* lds = wg_lds();
+    switch (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) {
+        case 0: dgemm_diag_tile_wave<0>(g, lds); break;
+        case 1: dgemm_diag_tile_wave<1>(g, lds); break;
+        case 2: dgemm_diag_tile_wave<2>(g, lds); break;
+        default: dgemm_diag_tile_wave<3>(g, lds); break;
+    }
+}
+
 // Tile (tm, tn), tn <= tm, of rank v in the row-major enumeration of a lower triangle of tiles.
 __device__ __forceinline__ void lower_tile_from_rank(int v, int& tm, int& tn) {
     int r = int((__fsqrt_rn(8.0f * float(v) + 1.0f) - 1.0f) * 0.5f);
@@ -714,10 +843,12 @@ __global__ __launch_bounds__(256, 2) void syrk_potrf_kernel(GemmArgs g, double* 
         tm = blockIdx.x;
         tn = 0;
     }
-    dgemm_tile_ring<true, 4>(g, tn, tm, 0, first);
     if (first) {
+        dgemm_diag_tile(g);
         __syncthreads();
         potrf_body(A, V, n, off, bs, info, wg_lds(), true);
+    } else {
+        dgemm_tile_ring<true, 4>(g, tn, tm, 0, false);
     }
 }
 
