@@ -881,16 +881,23 @@ __global__ __launch_bounds__(256) void trsm_kernel(double* __restrict__ P, int64
             sA[r * TRP + c0 + 2 * e + 1] = v.y;
         }
     }
-    __syncthreads();
     const int li = lane & 15, lk = lane >> 4;
-#pragma unroll 1
+    // the Linv operands of both passes are requested before the rows arrive: one memory latency instead of three
+    double bvs[2][32];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        const int c = pass == 0 ? NB / 16 - 1 - wave : wave;
+        const int nk = 4 * (c + 1);
+        const double* bp = Linv + int64_t(c * 16 + li) * ldl + lk;
+#pragma unroll
+        for (int ks = 0; ks < 32; ++ks) bvs[pass][ks] = ks < nk ? bp[4 * ks] : 0.0;
+    }
+    __syncthreads();
+#pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
         const int c = pass == 0 ? NB / 16 - 1 - wave : wave;   // column tile
         const int nk = 4 * (c + 1);                             // MFMA steps of 4 k
-        const double* bp = Linv + int64_t(c * 16 + li) * ldl + lk;
-        double bv[32];
-#pragma unroll
-        for (int ks = 0; ks < 32; ++ks) bv[ks] = ks < nk ? bp[4 * ks] : 0.0;
+        const double (&bv)[32] = bvs[pass];
         const double* ap0 = sA + li * TRP + lk;
         const double* ap1 = sA + (16 + li) * TRP + lk;
         double4v acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
