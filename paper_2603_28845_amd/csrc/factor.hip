@@ -384,19 +384,28 @@ __device__ __forceinline__ void potrf_body(double* __restrict__ A, double* __res
         }
         __syncthreads();
     });
-    // L_kk^-1 to V (zeros above the diagonal): 8 LDS reads per thread in flight before the stores that need them
-#pragma unroll 1
-    for (int e0 = tid; e0 < NB * NB; e0 += 256 * 8) {
-        double v[8];
+    // L_kk^-1 to V (zeros above the diagonal), sub-block by sub-block: wave w takes the sub-block rows w and 7 - w
+    // (eight sub-blocks each), a lane four rows of one column, so that addresses step by constants and a store
+    // instruction writes four 128-byte row segments
+    {
+        const int rows2[2] = {wave, NSB - 1 - wave};
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int e = e0 + 256 * u, r = e / NB, c = e % NB;
-            v[u] = S[tri(r, min(c, r))];
-        }
+        for (int h = 0; h < 2; ++h) {
+            const int I = rows2[h];
+#pragma unroll 2
+            for (int J = 0; J < NSB; ++J) {
+                double v[4] = {0.0, 0.0, 0.0, 0.0};
+                if (J <= I) {   // uniform
+                    const double* M = S + sub(I, J);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int e = e0 + 256 * u, r = e / NB, c = e % NB;
-            if (r < bs && c < bs) V[int64_t(off + r) * n + off + c] = (c <= r) ? v[u] : 0.0;
+                    for (int r = 0; r < 4; ++r) v[r] = M[(4 * r + lk) * SBP + l16];
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = I * SBW + 4 * r + lk, col = J * SBW + l16;
+                    if (row < bs && col < bs) V[int64_t(off + row) * n + off + col] = v[r];
+                }
+            }
         }
     }
 }
