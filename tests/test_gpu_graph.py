@@ -11,13 +11,18 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.mark.parametrize("form,act", [("inverse", False), ("block", True)])
-def test_layer_step_in_a_hip_graph(form, act):
-    print(f"[case] graph capture of a layer step, factor form {form}, act_order {act}", flush=True)
-    cfg = synth.scaled(synth.CONFIGS["c2"], d_out=130, d_in=640, n_tokens=2100, seed=3)
+# the wide case takes the paths of the benchmark layers: 384 x 256 Gram tiles with token pieces parked in the
+# accumulate workspace and added by the reduce kernel, Cholesky steps in pairs, the triangular diagonal tile
+@pytest.mark.parametrize("form,act,d_out,d_in", [("inverse", False, 130, 640), ("block", True, 130, 640),
+                                                 ("inverse", True, 64, 8192)])
+def test_layer_step_in_a_hip_graph(form, act, d_out, d_in):
+    print(f"[case] graph capture of a layer step {d_out}x{d_in}, factor form {form}, act_order {act}", flush=True)
+    cfg = synth.scaled(synth.CONFIGS["c2"], d_out=d_out, d_in=d_in, n_tokens=2100, seed=3)
     W = synth.make_weight(cfg, DEV)
     X = synth.make_activations(cfg, DEV)
     d = cfg.d_in
+    need = og.onecomp_accumulate_workspace_bytes(X.dtype, d)
+    ws_a = torch.empty(need, dtype=torch.uint8, device=DEV) if need else None
     H = torch.zeros((d, d), dtype=torch.float32, device=DEV)
     U = torch.empty((d, d), dtype=torch.float32, device=DEV)
     info = torch.zeros(1, dtype=torch.int32, device=DEV)
@@ -36,8 +41,8 @@ def test_layer_step_in_a_hip_graph(form, act):
 
     def step(out):
         H.zero_()                     # a fill kernel, not a memset node
-        og.onecomp_hessian_accumulate(X[:1000], H)
-        og.onecomp_hessian_accumulate(X[1000:], H)
+        og.onecomp_hessian_accumulate(X[:1000], H, workspace=ws_a)
+        og.onecomp_hessian_accumulate(X[1000:], H, workspace=ws_a)
         og.onecomp_hessian_factor(H, cfg.damp, act, U=U, perm_out=perm, info=info, workspace=ws_f, form=form)
         og.onecomp_quantize_layer(W, U, cfg.bits, cfg.group_size, perm=perm if act else None, workspace=ws_q,
                                   out=out, form=form)
