@@ -355,7 +355,8 @@ onecomp_status onecomp_rtn_sensitivity_static(const void* W, onecomp_dtype w_dty
  * group's scale is refit to its codes (s = u.p / u.A_tt u with u = q - z, p the gradient of the row's residual with
  * the group taken out); the group's columns are then scanned in order, +1 is tried before -1, the first of the two
  * that lowers f is taken at once; a visit ends with the first scan that takes nothing, or after max_scans scans.  A
- * group whose codes all equal its zero-point is left alone.
+ * group whose codes all equal its zero-point is left alone, and no move brings a group there (the refit scale is
+ * undefined at u = 0 and the objective cannot fall by such a move; it is excluded on the codes, not by rounding).
  *
  *   W         device, d_out x d_in, row-major, fp32 or bf16: the weights the objective measures against.
  *   H         device fp32, d_in x d_in, symmetric (as onecomp_hessian_accumulate leaves it), read only.
