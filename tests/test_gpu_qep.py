@@ -128,6 +128,52 @@ def test_qep_target(d_out, d_in, n_tok, dtype, act, alpha):
     assert torch.equal(W0, W.to(torch.float32))
 
 
+def test_qep_full_size_sampled():
+    """The error-propagation calls at the 4096 x 14336 layer, in the launch configuration bench.py --qep times
+    (bf16, natural order, alpha = 1, accumulate workspace, 384 x 256 cross-Gram tiles): sampled blocks of G against
+    the oracle's cross-Gram of the same column subsets, and sampled rows of W* against the oracle's target for the
+    SAME fp32 G and H (rows of W are independent in Eq. (qep)).  The calibration set is cut to 32768 tokens, still
+    more than 2 d_in, so that the float64 side finishes in about a minute."""
+    cfg = synth.scaled(synth.CONFIGS["c3b"], n_tokens=32768)
+    d_out, d_in = cfg.d_out, cfg.d_in
+    _announce(f"QEP full size {d_out}x{d_in}: activations, Gram and cross-Gram ({cfg.n_tokens} tokens)")
+    X = synth.make_activations(cfg, DEV)
+    Xh = synth.make_perturbed_activations(cfg, X, 0.05)
+    W = synth.make_weight(cfg, DEV)
+    ws = torch.empty(og.onecomp_accumulate_workspace_bytes(torch.bfloat16, d_in), dtype=torch.uint8, device=DEV)
+    H = torch.zeros((d_in, d_in), dtype=torch.float32, device=DEV)
+    og.onecomp_hessian_accumulate(Xh, H, workspace=ws)
+    G = torch.zeros((d_in, d_in), dtype=torch.float32, device=DEV)
+    og.onecomp_crossgram_accumulate(Xh, X, G)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(31)
+    for _ in range(6):   # blocks of 64 x 64 entries anywhere in G (it is not symmetric: both triangles)
+        i = np.sort(rng.choice(d_in, size=64, replace=False))
+        k = np.sort(rng.choice(d_in, size=64, replace=False))
+        ref = oc.crossgram_accumulate(to_f64(Xh[:, torch.from_numpy(i).to(DEV)]), to_f64(X[:, torch.from_numpy(k).to(DEV)]))
+        got = G[torch.from_numpy(i).to(DEV)][:, torch.from_numpy(k).to(DEV)].cpu().numpy().astype(np.float64)
+        assert rel_fro(got, ref) <= 1e-4
+    del X, Xh, ws
+    _announce("QEP full size: factor and corrected target on the GPU")
+    U, perm, info = og.onecomp_hessian_factor(H, cfg.damp, False)
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0
+    Ws = og.onecomp_qep_target(W, G, H, U, 1.0, perm=None)
+    torch.cuda.synchronize()
+    del U
+    rows = np.sort(rng.choice(d_out, size=64, replace=False))
+    _announce("QEP full size: oracle target on 64 sampled rows")
+    Wd = to_f64(W)[rows]
+    ref = oc.qep_target(Wd, G.cpu().numpy(), H.cpu().numpy(), cfg.damp, 1.0)
+    got = Ws.cpu().numpy()[rows].astype(np.float64)
+    e_all = rel_fro(got, ref)
+    e_corr = rel_fro(got - Wd, ref - Wd)
+    _announce(f"   W* rel. error {e_all:.2e}, correction rel. error {e_corr:.2e}, "
+              f"|correction| / |W| = {np.linalg.norm(ref - Wd) / np.linalg.norm(Wd):.3f}")
+    assert e_all <= 2e-6
+    assert e_corr <= 1e-4
+
+
 def test_qep_reduces_the_output_error_of_the_quantized_layer():
     """The point of the corrected target (Eq. (qep_obj)): quantizing W* reproduces the full-precision output X W^T
     from the perturbed input X_hat better than quantizing W does."""
