@@ -206,6 +206,8 @@ def test_qep_reduces_the_output_error_of_the_quantized_layer():
     (8, 32, 7, 384, torch.float32, "minmax"),
     (4, 1280, 40, 1280, torch.bfloat16, "symmetric"),     # per-channel
     (4, 128, 4096, 4096, torch.bfloat16, "minmax"),       # a full-size attention projection
+    (3, 128, 4096, 14336, torch.bfloat16, "minmax"),      # the layer bench.py times it on
+    (2, 128, 28672, 8192, torch.bfloat16, "symmetric"),   # a 70B-class layer
 ])
 def test_rtn_sensitivity(bits, G, d_out, d_in, dtype, grid):
     """Bit-allocation proxy 1/2 sum b_r a_c dW_rc^2 (Sec. 4.1).  Bar: relative error <= 1e-3 against the float64
