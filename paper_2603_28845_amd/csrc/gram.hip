@@ -734,6 +734,15 @@ onecomp_status launch_bf16(const void* X, int64_t n_tokens, int64_t d_in, int64_
 
 constexpr size_t GRAM_SLOT_BYTES = size_t(256) * 256 * sizeof(float);   // one partial sum of a 256 x 256 tile
 
+// Whether a call of n_tokens launches its rounds of whole tiles one by one (see launch_bf16_ring).
+// ONECOMP_GRAM_ROUND_LAUNCHES=0|1 in the environment forces the answer (tuning).
+constexpr int64_t ROUND_LAUNCH_MIN_TOKENS = 49152;
+bool launch_by_rounds(int64_t n_tokens) {
+    const char* e = getenv("ONECOMP_GRAM_ROUND_LAUNCHES");
+    if (e && (e[0] == '0' || e[0] == '1') && e[1] == 0) return e[0] == '1';
+    return n_tokens >= ROUND_LAUNCH_MIN_TOKENS;
+}
+
 template <typename C, bool CROSS>
 onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens, int64_t d_in, int64_t ldx,
                                 int64_t ldxb, float* H, float* ws, size_t ws_bytes, hipStream_t stream,
@@ -763,9 +772,14 @@ onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens,
     // together, so the tiles an XCD works on walk through the tokens side by side and share their column panels in
     // its L2; in a single launch of many rounds the workgroups of later rounds start whenever a CU falls free and
     // drift apart (L2 hit rate 59 % against 78 % for a round on its own; 46.2 -> 44.7 ms at d_in 14336, 262144 tokens).
+    // A call of few tokens is one launch instead: its time is the read-modify-write of H as much as the products, and
+    // in one launch the epilogue of one tile runs beside the products of the tiles on other CUs (262144 tokens at
+    // d_in 14336 in calls of 2048 / 8192 / 32768 tokens: 121 -> 80, 75 -> 60 (52 with 256 x 256 tiles), 48 -> 47 ms;
+    // from 65536 tokens per call on, the launches by rounds win).
     const int total = plan::ring_total_blocks(chunk, n_split, sp.n_piece);
     const int n_cus_r = device_cus();
-    const int per_launch = (C::TM >= 256 && C::TN == 256 && n_cus_r > 0 && n_cus_r % 8 == 0 && chunk * 8 >= 2 * n_cus_r)
+    const int per_launch = (C::TM >= 256 && C::TN == 256 && n_cus_r > 0 && n_cus_r % 8 == 0 && chunk * 8 >= 2 * n_cus_r &&
+                            launch_by_rounds(n_tokens))
                                ? n_cus_r : total;
     for (int b0 = 0; b0 < total;) {
         int nb = total - b0;
@@ -807,6 +821,11 @@ onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens,
 // ONECOMP_GRAM_SHAPE=big|mid|wide in the environment forces a shape (testing and tuning).
 enum class GramShape { Big, Mid, Wide };
 constexpr double WIDE_UNITS = 2.7;
+// The 384-row shape pays for its size when a call has few tokens: its four waves read, add and write 1.2 MB of H per
+// tile, a latency chain of 0.66 ms per call at d_in 14336 against 0.28 ms with 256 x 256 tiles on eight waves (close to
+// what reading half of H and writing all of it costs).  Measured over 262144 tokens in calls of 4096 / 16384 / 32768
+// tokens: 82 / 50.8 / 46.9 ms with 384 x 256 tiles, 60.5 / 48.9 / 47.9 ms with 256 x 256.
+constexpr int64_t WIDE_MIN_TOKENS = 24576;
 constexpr size_t GRAM_WIDE_SLOT_BYTES = size_t(384) * 256 * sizeof(float);
 int forced_shape() {
     const char* e = getenv("ONECOMP_GRAM_SHAPE");
@@ -826,7 +845,7 @@ GramShape choose_shape(int64_t d_in, int64_t n_tokens, int n_cus, size_t ws_byte
         WIDE_UNITS * plan_split(wide, n256, d_in, n_tokens, n_cus, int64_t(ws_bytes / GRAM_WIDE_SLOT_BYTES), false).rounds;
     const int f = forced_shape();
     if (f >= 0) return GramShape(f);
-    if (cost_wide < cost_big && cost_wide < cost_mid) return GramShape::Wide;
+    if (n_tokens >= WIDE_MIN_TOKENS && cost_wide < cost_big && cost_wide < cost_mid) return GramShape::Wide;
     return cost_big <= cost_mid ? GramShape::Big : GramShape::Mid;
 }
 
@@ -884,7 +903,7 @@ onecomp_status gram_cross_accumulate_bf16(const void* Xh, const void* X, int64_t
     const double cost_wide = WIDE_UNITS * double(ceil_div(n384 * n256, n_cus));
     int shape = forced_shape();
     if (shape < 0)
-        shape = int((cost_wide < cost_big && cost_wide < cost_mid) ? GramShape::Wide
+        shape = int((n_tokens >= WIDE_MIN_TOKENS && cost_wide < cost_big && cost_wide < cost_mid) ? GramShape::Wide
                     : cost_big <= cost_mid                         ? GramShape::Big
                                                                    : GramShape::Mid);
     if (shape == int(GramShape::Wide))

@@ -258,6 +258,12 @@ def test_gram_schedule_of_the_benchmark_layer(monkeypatch):
     assert og.onecomp_accumulate_describe(torch.bfloat16, T, d_in, need) == {"tile_rows": 384, "tile_cols": 256, "launches": 5}
     assert og.onecomp_accumulate_describe(torch.bfloat16, T, d_in, 0) == {"tile_rows": 256, "tile_cols": 256, "launches": 7}
     assert og.onecomp_accumulate_describe(torch.float32, T, d_in, 0)["launches"] == 1
+    # a call of few tokens (the calibration set handed over sequence by sequence): 256 x 256 tiles in one launch
+    monkeypatch.delenv("ONECOMP_GRAM_ROUND_LAUNCHES", raising=False)
+    for t in (2048, 16384):
+        assert og.onecomp_accumulate_describe(torch.bfloat16, t, d_in, need) == {"tile_rows": 256, "tile_cols": 256, "launches": 1}
+    assert og.onecomp_accumulate_describe(torch.bfloat16, 32768, d_in, need) == {"tile_rows": 384, "tile_cols": 256, "launches": 1}
+    assert og.onecomp_accumulate_describe(torch.bfloat16, 65536, d_in, need) == {"tile_rows": 384, "tile_cols": 256, "launches": 5}
 
 
 def test_mfma_rate_probe_runs():
