@@ -491,7 +491,8 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
     // compiler copies tiles between the halves).
     constexpr int N_AGPR_TILES = (MT * NT > 16) ? 16 : MT * NT;
     // the tile of the last MFMA of an iteration (its statement carries the wait states) is one of the VGPR tiles
-    static_assert(MT * NT <= 16 || (MT - 1) * NT + (((MT - 1) & 1) ? 0 : NT - 1) >= N_AGPR_TILES, "last tile in VGPRs");
+    constexpr bool BY_COLUMNS = MT * NT > 16;
+    static_assert(!BY_COLUMNS || ((NT - 1) & 1), "the last column runs downwards and ends in tile (MT - 1, NT - 1), a VGPR tile");
     // These MFMAs are opaque to the compiler's hazard handling, which therefore puts no wait states between the last
     // of them and whatever reads an accumulator at the loop's exit (the epilogue, or a spill or a copy between the
     // register halves that the compiler places there).  The last MFMA of a loop iteration carries the wait states
@@ -499,10 +500,14 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
     auto mma = [&](const Frags& f, auto&& between, auto closes_iteration) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < MT * NT; ++i) {
-            // Tile rows in turn, the columns of every second row backwards: from one MFMA to the next only one of the
-            // two operands changes (the pipes draw less on operands that stay: 44.3 -> 44.1 ms per call at d_in 14336,
-            // alternating in one process).
-            const int tm = i / NT, tn = (tm & 1) ? NT - 1 - i % NT : i % NT;
+            // Serpentine order over the wave's tiles: from one MFMA to the next only one of the two operands changes
+            // (the pipes draw less on operands that stay, and the clock follows: 44.3 -> 44.1 ms per call at d_in
+            // 14336, alternating in one process).  By rows, the columns of every second row backwards; the 6 x 4 tiles
+            // of the 384 x 256 shape by columns instead (the B operand stays for six MFMAs: another 44.0 -> 43.8 ms),
+            // odd columns downwards so that the last tile of a step is one of the VGPR tiles.
+            const int tn_c = i / MT, tm_c = (tn_c & 1) ? i % MT : MT - 1 - i % MT;
+            const int tm_r = i / NT, tn_r = (tm_r & 1) ? NT - 1 - i % NT : i % NT;
+            const int tm = BY_COLUMNS ? tm_c : tm_r, tn = BY_COLUMNS ? tn_c : tn_r;
             if constexpr (MT * NT > 16) {
                 if (decltype(closes_iteration)::value && i == MT * NT - 1)
                     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\ts_nop 15\n\ts_nop 15"
