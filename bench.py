@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # L2 <-> fabric bytes per call from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a plain 4 GiB copy), taken with
 # `python bench.py --phase gram|sweep` under rocprofv3 --pmc; see profiles/c3b_hbm_traffic_pmc.md for the commands
-GRAM_TRAFFIC_C3B = 185.0e9    # 183.7 GB fetched + 1.2 GB written per accumulate call (384 x 256 tiles; 100-191 GB from run to run)
+GRAM_TRAFFIC_C3B = 69.3e9     # 68.1 GB fetched + 1.2 GB written per accumulate call (384 x 256 tiles, paced launches)
 SWEEP_TRAFFIC_C3B = 13.6e9
 
 
@@ -72,7 +72,10 @@ def _median(xs):
     return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
 
 
-def gram_kernel_name(d_in, bf16, plan=None):
+PACED_MIN_TOKENS = 196608   # the library's own constant (gram.hip): long calls of the 384 x 256 shape run its paced form
+
+
+def gram_kernel_name(d_in, bf16, plan=None, tokens_per_call=0):
     """Kernel onecomp_hessian_accumulate launches for this width; the ring kernel's tile shape (384 x 256, 256 x 256 or
     128 x 256) and how it cuts tiles along the token axis are the library's own choice (estimated rounds over the
     CUs), reported by onecomp_accumulate_describe."""
@@ -81,7 +84,9 @@ def gram_kernel_name(d_in, bf16, plan=None):
     if d_in < 1024:
         return "gram_bf16_kernel<2>"
     shape = {384: "RingWide", 256: "RingBig", 128: "RingMid"}.get(plan["tile_rows"], "?") if plan else "?"
-    return f"gram_bf16_ring_kernel<{shape}, false>"
+    if shape == "RingWide" and plan["launches"] > 1 and tokens_per_call >= PACED_MIN_TOKENS:
+        return "gram_bf16_ring_kernel<RingWide, false, true>"   # third argument: every wave pauses 64 cycles per step
+    return f"gram_bf16_ring_kernel<{shape}, false, false>"
 
 
 def achievable_mfma(og, torch):
@@ -555,7 +560,7 @@ def main():
     # workload in one accumulate call with the workspace; null for anything else.
     gram_traffic = GRAM_TRAFFIC_C3B if (cfg.name == "c3b" and n_calls == 1 and gram_plan["tile_rows"] == 384) else None
     roofline = {
-        "kernel": gram_kernel_name(d_in, cfg.dtype == torch.bfloat16, gram_plan),
+        "kernel": gram_kernel_name(d_in, cfg.dtype == torch.bfloat16, gram_plan, tpc),
         "tile": [gram_plan["tile_rows"], gram_plan["tile_cols"]],
         "bound": "mfma", "achieved": gram_tflops, "peak": PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3,
         "unit": "TFLOP/s", "frac": gram_tflops / (PEAK_BF16_TFLOPS if cfg.dtype == torch.bfloat16 else 157.3),

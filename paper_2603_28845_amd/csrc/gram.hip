@@ -356,7 +356,14 @@ struct Ring {
 };
 // CROSS = false: H += 2 X^T X, tiles on or above the diagonal, mirrored.  CROSS = true: H += 2 X^T Xb for two
 // different matrices (A panels from X, B panels from Xb), every tile, no mirror.
-template <typename C, bool CROSS>
+// PACED: every wave sleeps 64 cycles at the start of each step.  In a launch of many thousand steps the workgroups of
+// an XCD otherwise drift apart along the tokens until the panels they share no longer meet in its L2 (hit rate 55 %
+// after 16384 steps against 79 % after 4096); with the pause they stay together (81 %, the ideal of the 4 x 8 patch is
+// 82 %), 162 -> 69 GB come over the fabric per call at d_in 14336, and the clock the chip holds under this load rises
+// from 1.65 to 1.76 GHz: 45.4 -> 44.6 ms per call.  The pause itself costs 0.5 - 2 % where there is no drift to cure
+// (shorter launches), so the host asks for it only in long ones, and only for the symmetric product (the cross-Gram's
+// launches gained 0.5 ms on one box and lost 1.3 on another).
+template <typename C, bool CROSS, bool PACED = false>
 __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring_kernel(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ Xb, int64_t n_tokens, int d_in, int64_t ldx,
     int64_t ldxb, float* __restrict__ H, int n_rt, int n_ct, int n_tiles, int chunk, int split0, int n_split,
@@ -533,6 +540,7 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
         // loads past the last step get an empty descriptor (zeros into a slot nobody reads again); fragment reads
         // past it fetch stale data nobody uses
         {
+            if constexpr (PACED) __builtin_amdgcn_s_sleep(1);
             const Desc d = make_desc(st + NBUF);
             const uint32_t dst = lds0 + s0 * STAGEB;
             const int sb = s1 * STAGEB;
@@ -544,6 +552,7 @@ __global__ __launch_bounds__(Ring<C>::THREADS, C::MIN_WAVES) void gram_bf16_ring
             __syncthreads();
         }
         {
+            if constexpr (PACED) __builtin_amdgcn_s_sleep(1);
             const Desc d = make_desc(st + 1 + NBUF);
             const uint32_t dst = lds0 + s1 * STAGEB;
             const int sb = s2 * STAGEB;
@@ -747,6 +756,9 @@ constexpr size_t GRAM_SLOT_BYTES = size_t(256) * 256 * sizeof(float);   // one p
 // Whether a call of n_tokens launches its rounds of whole tiles one by one (see launch_bf16_ring).
 // ONECOMP_GRAM_ROUND_LAUNCHES=0|1 in the environment forces the answer (tuning).
 constexpr int64_t ROUND_LAUNCH_MIN_TOKENS = 49152;
+// From this many tokens per call on, the launches of the 384 x 256 shape are paced (measured: a gain at 262144 tokens
+// per launch, a small loss at 131072).
+constexpr int64_t PACED_MIN_TOKENS = 196608;
 bool launch_by_rounds(int64_t n_tokens) {
     const char* e = getenv("ONECOMP_GRAM_ROUND_LAUNCHES");
     if (e && (e[0] == '0' || e[0] == '1') && e[1] == 0) return e[0] == '1';
@@ -791,6 +803,15 @@ onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens,
     const int per_launch = (C::TM >= 256 && C::TN == 256 && n_cus_r > 0 && n_cus_r % 8 == 0 && chunk * 8 >= 2 * n_cus_r &&
                             launch_by_rounds(n_tokens))
                                ? n_cus_r : total;
+    // long launches of the 384 x 256 shape run paced (see the kernel)
+    const bool paced = C::TM == 384 && !CROSS && per_launch < total && n_tokens >= PACED_MIN_TOKENS;
+    if constexpr (C::TM == 384 && !CROSS) {
+        static std::atomic<uint64_t> lds_ok_paced{0};
+        if (!info && paced &&
+            allow_dynamic_lds(reinterpret_cast<const void*>(&gram_bf16_ring_kernel<C, CROSS, true>), int(R::LDS_BYTES),
+                              lds_ok_paced) != ONECOMP_OK)
+            return ONECOMP_ERR_HIP;
+    }
     for (int b0 = 0; b0 < total;) {
         int nb = total - b0;
         if (per_launch < total && b0 < chunk * 8) nb = (chunk * 8 - b0 < per_launch) ? chunk * 8 - b0 : per_launch;
@@ -799,9 +820,18 @@ onecomp_status launch_bf16_ring(const void* X, const void* Xb, int64_t n_tokens,
             b0 += nb;
             continue;
         }
-        hipLaunchKernelGGL((gram_bf16_ring_kernel<C, CROSS>), dim3(unsigned(nb)), dim3(R::THREADS), R::LDS_BYTES, stream,
-                           static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(Xb), n_tokens, int(d_in), ldx,
-                           ldxb, H, n_rt, n_ct, n_tiles, chunk, split0, n_split, sp.n_piece, sp.use_ws ? ws : nullptr, b0);
+        if (paced) {
+            if constexpr (C::TM == 384 && !CROSS)
+                hipLaunchKernelGGL((gram_bf16_ring_kernel<C, CROSS, true>), dim3(unsigned(nb)), dim3(R::THREADS),
+                                   R::LDS_BYTES, stream, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(Xb),
+                                   n_tokens, int(d_in), ldx, ldxb, H, n_rt, n_ct, n_tiles, chunk, split0, n_split,
+                                   sp.n_piece, sp.use_ws ? ws : nullptr, b0);
+        } else {
+            hipLaunchKernelGGL((gram_bf16_ring_kernel<C, CROSS>), dim3(unsigned(nb)), dim3(R::THREADS), R::LDS_BYTES,
+                               stream, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(Xb), n_tokens,
+                               int(d_in), ldx, ldxb, H, n_rt, n_ct, n_tiles, chunk, split0, n_split, sp.n_piece,
+                               sp.use_ws ? ws : nullptr, b0);
+        }
         ONECOMP_CHECK_LAUNCH();
         b0 += nb;
     }

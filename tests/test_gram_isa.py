@@ -42,4 +42,4 @@ def test_wide_gram_loop_is_straight_line(tmp_path):
         assert [l.strip() for l in body[mf[-1] + 1:mf[-1] + 4]] == ["s_nop 15", "s_nop 15", ";;#ASMEND"], \
             "no wait states after the last MFMA of the loop"
         found += 1
-    assert found == 2        # the symmetric and the cross kernel
+    assert found == 3        # the symmetric kernel, its paced form and the cross kernel
