@@ -117,6 +117,8 @@ onecomp_status onecomp_hessian_accumulate(const void* X, onecomp_dtype x_dtype,
  * of H can hold a second partial sum, which covers a short last round of wide matrices.  The tile shape is chosen by
  * estimated cost; ONECOMP_GRAM_SHAPE=wide|big|mid in the environment forces 384 x 256, 256 x 256 or 128 x 256 tiles
  * for d_in >= 1024 (testing and tuning; onecomp_accumulate_describe reports the choice).
+ * A call of fewer than 49152 tokens is one launch, a longer one a launch per round of tiles (one tile per compute unit);
+ * ONECOMP_GRAM_ROUND_LAUNCHES=0|1 forces either (tuning).  None of these choices changes what the call computes.
  *   workspace        device scratch or NULL, 256-byte aligned; any size is accepted, the kernel uses what fits
  *                    (onecomp_accumulate_workspace_bytes(x_dtype, d_in) is what it can use at most; 0 for fp32
  *                    inputs and for widths that gain nothing).  Contents on entry and exit are meaningless.
