@@ -17,6 +17,7 @@
 //     ~2 log2(n/128) large launches instead of n/128 skinny ones.
 //   * ordering by rank counting (stable, deterministic), no floating-point atomics anywhere.
 #include "common.hpp"
+#include "planner.hpp"
 #include <type_traits>
 
 namespace onecomp {
@@ -847,7 +848,15 @@ __global__ __launch_bounds__(256, 2) void syrk_potrf_kernel(GemmArgs g, double* 
     const bool first = blockIdx.x == 0;
     int tm, tn;
     if (g.flags & G_CLOWER) {
-        lower_tile_from_rank(blockIdx.x, tm, tn);
+        // Workgroup b runs on XCD b % 8; each XCD takes a run of consecutive ranks of the banded order (bands of eight
+        // tile columns walked row by row), so that the 64 tiles resident on an XCD at one time form a patch of about
+        // 8 x 8 and find the 16 operand panels they share in its L2 (in row-major order of the ranks the tiles of an XCD
+        // were every eighth of five tile rows; 38.4 -> 38.0 ms at d_in 14336, 265 -> 261.5 at 28672).  Rank 0 is
+        // tile (0, 0).
+        const int nt = (g.m + GT - 1) / GT, total = nt * (nt + 1) / 2, chunk = (total + 7) >> 3;
+        const int v = (int(blockIdx.x) & 7) * chunk + (int(blockIdx.x) >> 3);
+        if (v >= total) return;
+        plan::tile_from_rank_band<plan::SYRK_BAND>(v, nt, tn, tm);
     } else {   // one block column whose first tile lies on the diagonal: one workgroup per tile row
         tm = blockIdx.x;
         tn = 0;
@@ -1012,7 +1021,7 @@ onecomp_status factor_run(const float* H, int64_t d_in, float damp, int act_orde
         s.m = rows; s.m_last = rows; s.n = cols; s.k = k; s.k_last = k; s.batch = 1;
         s.alpha = -1.0; s.beta = 1.0; s.flags = G_BTRANS | (lower ? G_CLOWER : 0);
         const unsigned nt = unsigned(ceil_div(rows, GT));
-        const dim3 grid(lower ? nt * (nt + 1) / 2 : nt, 1, 1);   // tile (0, 0) first
+        const dim3 grid(lower ? 8 * ((nt * (nt + 1) / 2 + 7) / 8) : nt, 1, 1);   // tile (0, 0) first
         hipLaunchKernelGGL(syrk_potrf_kernel, grid, dim3(256), 0, stream, s, w.A, w.V, n, c_off, min(NB, n - c_off),
                            info);
         ONECOMP_CHECK_LAUNCH();

@@ -21,23 +21,24 @@ ONECOMP_HD int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // rows; inside a band first the triangle on the diagonal (column by column), then the rectangle right of it column
 // by column, rows fastest.
 constexpr int GRAM_BAND = 4;
-ONECOMP_HD void tile_from_rank(int v, int n_t, int& ti, int& tk) {
+template <int BAND>
+ONECOMP_HD void tile_from_rank_band(int v, int n_t, int& ti, int& tk) {
     int a = 0;
     while (true) {
-        int rows = imin(GRAM_BAND, n_t - a * GRAM_BAND);
-        int cols = n_t - a * GRAM_BAND;
+        int rows = imin(BAND, n_t - a * BAND);
+        int cols = n_t - a * BAND;
         int cnt = rows * cols - rows * (rows - 1) / 2;
         if (v < cnt) {
             int tri = rows * (rows + 1) / 2;
             if (v < tri) {
                 int c = 0;
                 while ((c + 1) * (c + 2) / 2 <= v) ++c;
-                tk = a * GRAM_BAND + c;
-                ti = a * GRAM_BAND + (v - c * (c + 1) / 2);
+                tk = a * BAND + c;
+                ti = a * BAND + (v - c * (c + 1) / 2);
             } else {
                 int w = v - tri;
-                tk = a * GRAM_BAND + rows + w / rows;
-                ti = a * GRAM_BAND + w % rows;
+                tk = a * BAND + rows + w / rows;
+                ti = a * BAND + w % rows;
             }
             return;
         }
@@ -45,6 +46,11 @@ ONECOMP_HD void tile_from_rank(int v, int n_t, int& ti, int& tk) {
         ++a;
     }
 }
+ONECOMP_HD void tile_from_rank(int v, int n_t, int& ti, int& tk) { tile_from_rank_band<GRAM_BAND>(v, n_t, ti, tk); }
+// ---- factor: the lower tiles of a trailing update go through the same banded order with bands of SYRK_BAND tile
+// columns ((tn, tm) = tile_from_rank_band<SYRK_BAND>): two workgroups per CU, 64 tiles of an XCD in flight, an 8 x 8
+// patch of them shares 16 operand panels.
+constexpr int SYRK_BAND = 8;
 ONECOMP_HD int n_upper_tiles(int n_t) { return n_t * (n_t + 1) / 2; }
 
 // ---- symmetric Gram, 128 x 256 tiles: tile (i, k) = rows [128 i, +128) x columns [256 k, +256) is computed when it

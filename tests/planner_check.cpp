@@ -38,6 +38,23 @@ static void check_simple_upper(int d_in, int ts) {
     REQUIRE(int(seen.size()) == n_tiles, "d_in %d ts %d: %zu of %d tiles owned", d_in, ts, seen.size(), n_tiles);
 }
 
+// trailing update of the blocked Cholesky: the lower tiles of a matrix of n_t tile rows through the banded order with
+// bands of SYRK_BAND, (tn, tm) = tile_from_rank_band(v), rank 0 = tile (0, 0), grid rounded up to a multiple of 8
+static void check_syrk_lower(int n_t) {
+    const int n_tiles = n_upper_tiles(n_t), chunk = int(cdiv(n_tiles, 8));
+    std::set<std::pair<int, int>> seen;
+    for (int b = 0; b < chunk * 8; ++b) {
+        const int v = (b & 7) * chunk + (b >> 3);
+        if (v >= n_tiles) continue;
+        int tn, tm;
+        tile_from_rank_band<SYRK_BAND>(v, n_t, tn, tm);
+        REQUIRE(0 <= tn && tn <= tm && tm < n_t, "syrk n_t %d rank %d -> (%d, %d)", n_t, v, tm, tn);
+        REQUIRE(b != 0 || (tm == 0 && tn == 0), "syrk n_t %d: workgroup 0 owns (%d, %d), not the diagonal tile", n_t, tm, tn);
+        REQUIRE(seen.insert({tm, tn}).second, "syrk n_t %d tile (%d, %d) owned twice", n_t, tm, tn);
+    }
+    REQUIRE(int(seen.size()) == n_tiles, "syrk n_t %d: %zu of %d tiles owned", n_t, seen.size(), n_tiles);
+}
+
 // ring kernel, symmetric: 256 x 256 tiles with the split plan, 128 x 256 tiles, or 384 x 256 tiles with the
 // workspace-only split plan
 enum Shape { BIG, MID, WIDE };
@@ -182,6 +199,7 @@ int main() {
 #else
     const int step = 16;
 #endif
+    for (int n_t = 1; n_t <= 512; ++n_t) check_syrk_lower(n_t);   // every trailing matrix up to d_in 65536
     for (int d_in = 16; d_in <= 32768; d_in += step) {
         if (d_in <= 4096 || d_in % 256 == 0) {            // every width up to 4096, then every multiple of 256 (set-based checks)
             check_simple_upper(d_in, 128);
